@@ -1,0 +1,312 @@
+"""Pins of the fp64 oracle against what the definitions and mathematics fix.
+
+None of these re-type the oracle's own formula: they use Kronecker products,
+SVD round trips, per-entry matrix products and traces from numpy, nested-loop
+summation, gauge and rotation invariances, and closed-form statistics.
+"""
+from math import prod
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import tn_oracle as O
+import workloads as wl
+
+TT, TR, TUCKER, DENSE = O.FORMAT_TT, O.FORMAT_TR, O.FORMAT_TUCKER, O.FORMAT_DENSE
+
+
+def _cores(rng, ms, ns, rs):
+    return [rng.standard_normal((rs[k], ms[k], ns[k], rs[k + 1])) for k in range(len(ms))]
+
+
+# ---- 1. rank-1 TT is the Kronecker product of its cores (pins C-order digits,
+#         the [r, m, n, r] axis order and the [out, in] orientation) ------------
+def test_rank1_tt_is_kronecker():
+    rng = np.random.default_rng(1)
+    ms, ns = (3, 4, 2), (2, 5, 3)        # non-square modes: a transposed core cannot pass
+    cores = _cores(rng, ms, ns, (1, 1, 1, 1))
+    w = O.tt_dense(cores)
+    k = cores[0][0, :, :, 0]
+    for g in cores[1:]:
+        k = np.kron(k, g[0, :, :, 0])
+    assert w.shape == (24, 30)
+    np.testing.assert_allclose(w, k, rtol=0, atol=1e-13)
+
+
+def test_rank1_tr_is_kronecker():
+    rng = np.random.default_rng(2)
+    cores = _cores(rng, (2, 3), (3, 2), (1, 1, 1))
+    k = np.kron(cores[0][0, :, :, 0], cores[1][0, :, :, 0])
+    np.testing.assert_allclose(O.tr_dense(cores), k, atol=1e-13)
+
+
+# ---- 2. TR with boundary rank 1 is TT (pins the trace closure) ---------------
+@pytest.mark.parametrize("d", [2, 3, 4, 5])
+def test_tr_boundary_rank1_equals_tt(d):
+    rng = np.random.default_rng(10 + d)
+    ms = [2, 3, 2, 2, 3][:d]
+    ns = [3, 2, 2, 3, 2][:d]
+    rs = [1] + [3, 2, 4, 3][: d - 1] + [1]
+    cores = _cores(rng, ms, ns, rs)
+    np.testing.assert_allclose(O.tr_dense(cores), O.tt_dense(cores), atol=1e-13)
+
+
+# ---- 2b. TR entry = trace of the product of core slices, entry by entry ------
+def test_tr_entries_are_traces_of_matrix_products():
+    rng = np.random.default_rng(3)
+    ms, ns, rs = (2, 3, 2), (3, 2, 2), (3, 2, 4, 3)
+    cores = _cores(rng, ms, ns, rs)
+    w = O.tr_dense(cores)
+    for i in [(0, 0, 0), (1, 2, 1), (0, 1, 1), (1, 0, 0)]:
+        for j in [(0, 0, 0), (2, 1, 1), (1, 0, 1)]:
+            mat = np.eye(rs[0])
+            for k in range(3):
+                mat = mat @ cores[k][:, i[k], j[k], :]
+            fi = np.ravel_multi_index(i, ms)
+            fj = np.ravel_multi_index(j, ns)
+            assert abs(w[fi, fj] - np.trace(mat)) < 1e-12
+
+
+def test_tt_entries_are_matrix_products():
+    rng = np.random.default_rng(4)
+    ms, ns, rs = (2, 3, 2, 2), (3, 2, 2, 3), (1, 3, 2, 4, 1)
+    cores = _cores(rng, ms, ns, rs)
+    w = O.tt_dense(cores)
+    for i in [(0, 0, 0, 0), (1, 2, 1, 1), (0, 1, 1, 0)]:
+        for j in [(0, 0, 0, 0), (2, 1, 1, 2), (1, 0, 1, 1)]:
+            mat = np.eye(1)
+            for k in range(4):
+                mat = mat @ cores[k][:, i[k], j[k], :]
+            assert abs(w[np.ravel_multi_index(i, ms), np.ravel_multi_index(j, ns)] - mat[0, 0]) < 1e-12
+
+
+def test_tr_single_core_is_partial_trace():
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal((3, 4, 5, 3))
+    w = O.tr_dense([g])
+    ref = sum(g[a, :, :, a] for a in range(3))
+    np.testing.assert_allclose(w, ref, atol=1e-14)
+
+
+# ---- 3. Tucker special cases ---------------------------------------------------
+def test_tucker_identity_factors_return_core():
+    rng = np.random.default_rng(6)
+    core = rng.standard_normal((3, 4, 2, 5))
+    us = [np.eye(3), np.eye(4)]
+    vs = [np.eye(2), np.eye(5)]
+    w = O.tucker_dense(core, us, vs)
+    np.testing.assert_array_equal(w, core.reshape(12, 10))
+
+
+def test_tucker_one_mode_per_side_is_u_c_vt():
+    rng = np.random.default_rng(7)
+    c = rng.standard_normal((3, 4))
+    u = rng.standard_normal((6, 3))
+    v = rng.standard_normal((5, 4))
+    np.testing.assert_allclose(O.tucker_dense(c, [u], [v]), u @ c @ v.T, atol=1e-13)
+
+
+def test_tucker_is_kron_factor_sandwich():
+    # W = (U1 kron U2) C_mat (V1 kron V2)^T for C-order flattening
+    rng = np.random.default_rng(8)
+    core = rng.standard_normal((2, 3, 2, 2))
+    u1, u2 = rng.standard_normal((4, 2)), rng.standard_normal((3, 3))
+    v1, v2 = rng.standard_normal((3, 2)), rng.standard_normal((5, 2))
+    ref = np.kron(u1, u2) @ core.reshape(6, 4) @ np.kron(v1, v2).T
+    np.testing.assert_allclose(O.tucker_dense(core, [u1, u2], [v1, v2]), ref, atol=1e-12)
+
+
+def test_tucker_orthonormal_factors_preserve_frobenius_norm():
+    rng = np.random.default_rng(9)
+    core = rng.standard_normal((3, 2, 2, 3))
+    fs = [np.linalg.qr(rng.standard_normal(s))[0] for s in [(5, 3), (4, 2), (3, 2), (6, 3)]]
+    w = O.tucker_dense(core, fs[:2], fs[2:])
+    assert abs(np.linalg.norm(w) - np.linalg.norm(core)) < 1e-12
+
+
+# ---- 4. untruncated TT-SVD round trip ------------------------------------------
+@pytest.mark.parametrize("ms,ns", [((2, 3, 2), (3, 2, 2)), ((4, 2), (3, 5)), ((2, 2, 3, 2), (3, 2, 2, 2))])
+def test_tt_svd_round_trip(ms, ns):
+    rng = np.random.default_rng(11)
+    w = rng.standard_normal((prod(ms), prod(ns)))
+    cores = O.tt_svd(w, ms, ns)
+    for k, g in enumerate(cores):
+        assert g.shape[1] == ms[k] and g.shape[2] == ns[k]
+    assert cores[0].shape[0] == 1 and cores[-1].shape[3] == 1
+    assert np.max(np.abs(O.tt_dense(cores) - w)) < 1e-12
+
+
+# ---- 5. nested-loop summation on tiny shapes ------------------------------------
+def test_brute_force_tt():
+    rng = np.random.default_rng(12)
+    cores = _cores(rng, (2, 3, 2), (3, 2, 2), (1, 2, 3, 1))
+    np.testing.assert_allclose(O.tt_dense(cores), O.brute_force_weight(TT, cores), atol=1e-13)
+
+
+def test_brute_force_tr():
+    rng = np.random.default_rng(13)
+    cores = _cores(rng, (2, 3, 2), (3, 2, 2), (2, 2, 3, 2))
+    np.testing.assert_allclose(O.tr_dense(cores), O.brute_force_weight(TR, cores), atol=1e-13)
+    cores4 = _cores(rng, (2, 2, 2, 2), (2, 3, 2, 2), (2, 2, 2, 3, 2))
+    np.testing.assert_allclose(O.tr_dense(cores4), O.brute_force_weight(TR, cores4), atol=1e-13)
+
+
+def test_brute_force_tucker():
+    rng = np.random.default_rng(14)
+    core = rng.standard_normal((2, 3, 2, 2))
+    ts = [core, rng.standard_normal((3, 2)), rng.standard_normal((4, 3)),
+          rng.standard_normal((3, 2)), rng.standard_normal((2, 2))]
+    np.testing.assert_allclose(O.dense_weight(TUCKER, ts, 2), O.brute_force_weight(TUCKER, ts, 2), atol=1e-13)
+    # three out modes, one in mode (the paper's "3-way reshaping" flavour)
+    core = rng.standard_normal((2, 2, 2, 3))
+    ts = [core, rng.standard_normal((3, 2)), rng.standard_normal((2, 2)), rng.standard_normal((2, 2)),
+          rng.standard_normal((4, 3))]
+    np.testing.assert_allclose(O.dense_weight(TUCKER, ts, 3), O.brute_force_weight(TUCKER, ts, 3), atol=1e-13)
+
+
+# ---- 6. gauge invariance on every bond, ring bond included ------------------------
+@pytest.mark.parametrize("fmt", [TT, TR])
+def test_gauge_invariance(fmt):
+    rng = np.random.default_rng(15)
+    rs = (1, 3, 2, 1) if fmt == TT else (3, 3, 2, 3)
+    cores = _cores(rng, (2, 3, 2), (3, 2, 2), rs)
+    w0 = O.dense_weight(fmt, cores)
+    d = len(cores)
+    bonds = range(1, d) if fmt == TT else range(0, d)
+    for b in bonds:
+        r = rs[b]
+        a = rng.standard_normal((r, r)) + 3 * np.eye(r)
+        ainv = np.linalg.inv(a)
+        mod = [g.copy() for g in cores]
+        left = (b - 1) % d
+        right = b % d
+        mod[left] = np.einsum("amnb,bc->amnc", mod[left], a)
+        mod[right] = np.einsum("ab,bmnc->amnc", ainv, mod[right])
+        np.testing.assert_allclose(O.dense_weight(fmt, mod), w0, atol=1e-10)
+
+
+# ---- 6b. rotating a ring by one core permutes the digits of W accordingly ------
+def test_tr_cyclic_rotation():
+    rng = np.random.default_rng(16)
+    ms, ns, rs = (2, 3, 2), (3, 2, 2), (2, 3, 2, 2)
+    cores = _cores(rng, ms, ns, rs)
+    w = O.tr_dense(cores).reshape(*ms, *ns)
+    rot = cores[1:] + cores[:1]
+    w_rot = O.tr_dense(rot).reshape(ms[1], ms[2], ms[0], ns[1], ns[2], ns[0])
+    np.testing.assert_allclose(w_rot, w.transpose(1, 2, 0, 4, 5, 3), atol=1e-12)
+
+
+# ---- 7. closed-form statistics of the synthetic workloads ---------------------------
+def test_tt_qproj_statistics():
+    spec, _ = wl.baseline_spec(1)
+    cores = wl.make_tensors(spec, 1)
+    w = O.dense_weight(spec.format, cores)
+    assert w.shape == (8192, 5120)
+    # Var(W_ij) = prod_{k<d} r_k * prod_k sigma_k^2 = 1/N, so ||W||_F^2 ~ M
+    assert abs(np.sum(w * w) / spec.M - 1.0) < 0.1
+    x = wl.make_x(spec, 8, 1)
+    y = O.apply_linear(w, x)
+    assert abs(y.var() - 1.0) < 0.1
+
+
+def test_tucker_upproj_statistics():
+    spec, _ = wl.baseline_spec(2)
+    ts = wl.make_tensors(spec, 2)
+    for f in ts[1:]:
+        assert np.max(np.abs(f.T @ f - np.eye(f.shape[1]))) < 2e-2      # bf16-rounded orthonormal
+    w = O.dense_weight(spec.format, ts, 2)
+    assert w.shape == (25600, 5120)
+    # orthonormal factors keep ||W||_F = ||C||_F and every core row has unit norm
+    assert abs(np.sum(w * w) / (96 * 96) - 1.0) < 2e-2
+
+
+def test_tr_downproj_statistics():
+    spec, _ = wl.baseline_spec(3)
+    cores = wl.make_tensors(spec, 3)
+    w = O.dense_weight(spec.format, cores)
+    assert w.shape == (5120, 25600)
+    assert abs(np.sum(w * w) / spec.M - 1.0) < 0.1
+    x = wl.make_x(spec, 4, 3)
+    assert abs(O.apply_linear(w, x).var() - 1.0) < 0.15
+
+
+# ---- 8. contracting the activations core by core equals rebuild-then-multiply ------
+def _tt_chain_left_to_right(cores, x):
+    """z[t, out digits so far, bond, remaining in digits] absorbed one core at a time."""
+    t = x.shape[0]
+    ns = [g.shape[2] for g in cores]
+    z = x.reshape(t, 1, 1, *ns)                       # [t, I, a, n_1..n_d]
+    for g in cores:
+        # contract bond a and the leading remaining in-digit
+        z = np.tensordot(z, g, axes=([2, 3], [0, 2]))  # [t, I, rest..., m_k, b]
+        nd = z.ndim
+        z = np.moveaxis(z, [nd - 2, nd - 1], [2, 3])   # [t, I, m_k, b, rest...]
+        z = z.reshape(t, z.shape[1] * z.shape[2], z.shape[3], *z.shape[4:])
+    return z.reshape(t, -1)
+
+
+def _tt_chain_right_to_left(cores, x):
+    t = x.shape[0]
+    ns = [g.shape[2] for g in cores]
+    z = x.reshape(t, *ns, 1, 1)                        # [t, n_1..n_k, b, Itail]
+    for g in reversed(cores):
+        k = z.ndim - 3                                  # axis of the last remaining in-digit
+        z = np.tensordot(z, g, axes=([k, k + 1], [2, 3]))   # [t, rest..., Itail, a, m_k]
+        nd = z.ndim
+        z = np.moveaxis(z, [nd - 2, nd - 1], [nd - 3, nd - 2])   # [t, rest..., a, m_k, Itail]
+        z = z.reshape(*z.shape[: nd - 2], z.shape[nd - 2] * z.shape[nd - 1])
+    return z.reshape(t, -1)
+
+
+def test_chain_equals_rebuild():
+    rng = np.random.default_rng(17)
+    ms, ns, rs = (2, 3, 2, 3), (3, 2, 4, 2), (1, 3, 4, 2, 1)
+    cores = _cores(rng, ms, ns, rs)
+    x = rng.standard_normal((5, prod(ns)))
+    y = O.forward(TT, cores, x)
+    np.testing.assert_allclose(_tt_chain_left_to_right(cores, x), y, atol=1e-12)
+    np.testing.assert_allclose(_tt_chain_right_to_left(cores, x), y, atol=1e-12)
+
+
+# ---- 9. d = 1 TT is a dense layer; linearity; token independence --------------------
+def test_single_core_tt_is_dense():
+    rng = np.random.default_rng(18)
+    w = rng.standard_normal((7, 5))
+    x = rng.standard_normal((3, 5))
+    np.testing.assert_allclose(O.forward(TT, [w.reshape(1, 7, 5, 1)], x), x @ w.T, atol=1e-14)
+    np.testing.assert_allclose(O.forward(DENSE, [w], x), x @ w.T, atol=1e-14)
+
+
+def test_token_independence():
+    spec, _ = wl.baseline_spec(0)
+    cores = wl.make_tensors(spec, 0)
+    x = wl.make_x(spec, 16, 0)
+    y = O.forward(spec.format, cores, x)
+    y3 = O.forward(spec.format, cores, x[3:4])
+    np.testing.assert_allclose(y[3:4], y3, atol=1e-13)
+
+
+# ---- 10. parameter counts of the four single-layer workloads ----------------------
+def test_parameter_counts():
+    expect = {0: 4736, 1: 925696, 2: 21271296, 3: 458752}
+    for i, n in expect.items():
+        spec, _ = wl.baseline_spec(i)
+        assert spec.n_params == n
+
+
+# ---- a planted mistake must be caught: little-endian digits fail the Kronecker pin ---
+def test_planted_digit_order_mistake_is_detected():
+    rng = np.random.default_rng(19)
+    ms, ns = (3, 4), (2, 5)
+    cores = _cores(rng, ms, ns, (1, 1, 1))
+    wrong = O.tt_dense(cores[::-1])          # digits in the wrong significance order
+    k = np.kron(cores[0][0, :, :, 0], cores[1][0, :, :, 0])
+    assert np.max(np.abs(wrong - k)) > 1e-3
+
+
+def test_rel_max_err():
+    a = np.array([[1.0, -2.0], [0.5, 4.0]])
+    b = a + np.array([[0.0, 0.0], [0.0, 0.04]])
+    assert abs(O.rel_max_err(b, a) - 0.01) < 1e-15
+    assert O.rel_max_err(np.zeros((0, 3)), np.zeros((0, 3))) == 0.0
