@@ -1,0 +1,175 @@
+/*
+ * tn_linear: forward pass of tensor-network-structured linear layers on one
+ * MI355X (gfx950).
+ *
+ * y = W x with W [M, N] held as dense, tensor-train (TT), tensor-ring (TR) or
+ * Tucker factors (the formats of the paper's Stage 2, Section 3.3) and applied
+ * to a batch of token activations by sequential contraction of the factors
+ * (the kernels of Stage 4, Section 3.5). The paper names the formats without
+ * formulas; the standard definitions are used:
+ *
+ *   TT     W[i, j] = G_1[:, i_1, j_1, :] G_2[:, i_2, j_2, :] ... G_d[:, i_d, j_d, :]   (r_0 = r_d = 1)
+ *   TR     W[i, j] = trace of the same matrix product                                  (r_0 = r_d = r)
+ *   Tucker W[(i_1..i_p), (j_1..j_q)] = sum_{a, c} C[a_1..a_p, c_1..c_q]
+ *                                      prod_a U_a[i_a, a_a]  prod_b V_b[j_b, c_b]
+ *   dense  W given directly
+ *
+ * M = prod m_k, N = prod n_k. Flat index <-> mode digits is C order, first
+ * mode most significant: i = ((i_1 m_2 + i_2) m_3 + i_3)... All tensors are
+ * contiguous row-major. X is [tokens, N], Y is [tokens, M],
+ * Y[t, i] = sum_j W[i, j] X[t, j]; no bias.
+ *
+ * Every pointer named "device" is GPU memory of the current HIP device; every
+ * other pointer is host memory. No function throws; all return an int status
+ * (TN_OK = 0, errors negative). The library keeps no global state besides the
+ * handles it returns.
+ */
+#ifndef TN_LINEAR_H
+#define TN_LINEAR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define TN_OK                 0
+#define TN_ERR_INVALID_ARG   (-1)   /* NULL pointer, bad extent, inconsistent ranks ... */
+#define TN_ERR_UNSUPPORTED   (-2)   /* valid request this build cannot run (e.g. too many modes) */
+#define TN_ERR_ALLOC         (-3)   /* host or device allocation failed */
+#define TN_ERR_HIP           (-4)   /* a HIP runtime call or kernel launch failed */
+
+/* desc.format */
+#define TN_FORMAT_DENSE   0
+#define TN_FORMAT_TT      1
+#define TN_FORMAT_TR      2
+#define TN_FORMAT_TUCKER  3
+
+/* desc.dtype: storage type of tensors, X and Y. Accumulation is always fp32. */
+#define TN_DTYPE_F32   0    /* fp32 storage, fp32 FMA arithmetic, fp32 intermediates */
+#define TN_DTYPE_BF16  1    /* bf16 storage, bf16 MFMA with fp32 accumulate, bf16 intermediates */
+
+/* desc.flags */
+#define TN_FLAG_SCALAR_KERNELS  1   /* run every contraction step on the plain FMA kernel (debug aid) */
+
+/* tn_linear_query / tn_linear_plan_query: what */
+#define TN_QUERY_PARAM_COUNT        0   /* number of parameters in the caller's tensors */
+#define TN_QUERY_PACKED_BYTES       1   /* bytes of the library's packed copy (padding included) */
+#define TN_QUERY_FLOPS_PER_TOKEN    2   /* 2 * multiply-adds of the chosen contraction order, per token */
+#define TN_QUERY_WORKSPACE_BYTES    3   /* device workspace held by the handle (0 from plan_query) */
+#define TN_QUERY_NUM_STEPS          4   /* contraction steps = kernel launches per token chunk */
+#define TN_QUERY_CHUNK_TOKENS       5   /* tokens processed per pass over the chain (0 from plan_query) */
+#define TN_QUERY_MAX_INTERMEDIATE   6   /* largest per-token intermediate, in elements */
+#define TN_QUERY_OUT_FEATURES       7   /* M */
+#define TN_QUERY_IN_FEATURES        8   /* N */
+#define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
+                                           f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
+                                           4 id of the absorbed tensor (index into desc.tensors),
+                                           5 kernel variant chosen (0 scalar; >0 MFMA tile id) */
+
+typedef struct tn_linear_s* tn_linear_t;
+
+/*
+ * Layer description.
+ *
+ *  format, dtype      see above.
+ *  out_modes[n_out_modes], in_modes[n_in_modes]
+ *                     m_1..m_p and n_1..n_q, all >= 1. TT/TR need p == q = d.
+ *                     dense: any factorisation is accepted, only M and N matter.
+ *  ranks[n_ranks]     TT/TR: d+1 bond sizes r_0..r_d (TT: r_0 = r_d = 1; TR: r_0 = r_d);
+ *                     Tucker: p+q ranks R_1..R_p, S_1..S_q; dense: ignored (n_ranks may be 0).
+ *  tensors[n_tensors] DEVICE pointers to contiguous row-major arrays of `dtype`:
+ *                     dense : 1 tensor  W[M, N]
+ *                     TT/TR : d cores   G_k[r_{k-1}, m_k, n_k, r_k]
+ *                     Tucker: core C[R_1..R_p, S_1..S_q], then U_1..U_p as [m_a, R_a],
+ *                             then V_1..V_q as [n_b, S_b]
+ *                     The array of pointers itself is host memory.
+ *  max_tokens         largest token count a single pass will be sized for (>= 1); larger
+ *                     forward calls are processed in several passes.
+ *  workspace_limit_bytes
+ *                     upper bound for the handle's device workspace; 0 = library default,
+ *                     which keeps a pass's intermediates about the size of the last-level cache.
+ *  flags              TN_FLAG_* bits.
+ *  stream             hipStream_t on which create enqueues its repacking work.
+ */
+typedef struct tn_linear_desc {
+    int32_t format;
+    int32_t dtype;
+    int32_t n_out_modes;
+    const int32_t* out_modes;
+    int32_t n_in_modes;
+    const int32_t* in_modes;
+    int32_t n_ranks;
+    const int32_t* ranks;
+    int32_t n_tensors;
+    const void* const* tensors;
+    int64_t max_tokens;
+    int64_t workspace_limit_bytes;
+    int32_t flags;
+    void* stream;
+} tn_linear_desc;
+
+/*
+ * Build a layer (Section 3.5: contiguous, kernel-friendly parameter storage).
+ * Validates the description, chooses the contraction order with the fewest
+ * FLOPs, copies the caller's tensors into library-owned packed device buffers
+ * (one per contraction step, K-contiguous, zero-padded to the MFMA tile) by
+ * kernels enqueued on desc->stream, and allocates the workspace. The caller
+ * keeps ownership of its tensors and may free them once desc->stream has
+ * drained. On success *out receives the handle; on failure *out is untouched.
+ * May wait for desc->stream while uploading its tables; allocates device memory
+ * (not capturable).
+ */
+int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc);
+
+/*
+ * Y = X W^T for `tokens` rows (Section 3.5, the TN matmul).
+ *  x  DEVICE [tokens, N] of the handle's dtype, read only
+ *  y  DEVICE [tokens, M] of the handle's dtype, fully overwritten
+ *  x and y must not overlap each other. Enqueues kernels on `stream`
+ *  (hipStream_t) and returns without synchronising or allocating. tokens == 0
+ *  is a no-op. One forward per handle may be in flight at a time (the
+ *  workspace is shared); different handles are independent. Results are
+ *  bit-identical from call to call for the same handle, inputs and token count.
+ */
+int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream);
+
+/* Free packed tensors and workspace. No forward may be in flight. NULL is accepted. */
+int tn_linear_destroy(tn_linear_t h);
+
+/* Read a property of a built layer (TN_QUERY_*). */
+int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value);
+
+/*
+ * Host-only planning: the same validation and contraction-order search as
+ * create, with no GPU call and no tensor access (desc->tensors may be NULL).
+ */
+int tn_linear_plan_query(const tn_linear_desc* desc, int32_t what, int64_t* value);
+
+/*
+ * Per-step timing for measurement (Section 3.5 gives no kernel-level numbers; these are
+ * ours). While enabled, every kernel launch of tn_linear_forward on this handle is
+ * bracketed by a pair of HIP events on the caller's stream (events are created as needed,
+ * so an enabled handle allocates and must not be used under graph capture). Enabling
+ * clears earlier records; disabling keeps them readable.
+ */
+int tn_linear_profile(tn_linear_t h, int32_t enable);
+
+/*
+ * Sum of the recorded kernel durations of contraction step `step` in milliseconds and the
+ * number of launches recorded. Waits for the recorded events (host-blocking). total_ms and
+ * launches are host pointers.
+ */
+int tn_linear_profile_read(tn_linear_t h, int32_t step, double* total_ms, int64_t* launches);
+
+/* Static, NUL-terminated description of a status code. */
+const char* tn_linear_strerror(int status);
+
+/* Library ABI version (incremented when a signature or struct changes). */
+int tn_linear_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TN_LINEAR_H */

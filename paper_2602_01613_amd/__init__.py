@@ -1,0 +1,30 @@
+"""MI355X-native forward pass of tensor-network linear layers.
+
+The work is done by hand-written HIP kernels behind a C-ABI shared library
+(include/tn_linear.h); this package is the thin ctypes binding over it. PyTorch
+is used only for device memory and streams. There is no CPU fallback: if the
+library is missing or no GPU is present, calls raise.
+"""
+from .binding import (  # noqa: F401
+    TNLinear,
+    TNLinearError,
+    library_path,
+    load_library,
+    plan_query,
+    tn_linear_create,
+    tn_linear_destroy,
+    tn_linear_forward,
+    tn_linear_plan_query,
+    tn_linear_profile,
+    tn_linear_profile_read,
+    tn_linear_query,
+    tn_linear_strerror,
+    tn_linear_version,
+    EXPORTED_SYMBOLS,
+    TN_FORMAT_DENSE, TN_FORMAT_TT, TN_FORMAT_TR, TN_FORMAT_TUCKER,
+    TN_DTYPE_F32, TN_DTYPE_BF16,
+    TN_FLAG_SCALAR_KERNELS,
+    TN_QUERY_PARAM_COUNT, TN_QUERY_PACKED_BYTES, TN_QUERY_FLOPS_PER_TOKEN, TN_QUERY_WORKSPACE_BYTES,
+    TN_QUERY_NUM_STEPS, TN_QUERY_CHUNK_TOKENS, TN_QUERY_MAX_INTERMEDIATE, TN_QUERY_OUT_FEATURES,
+    TN_QUERY_IN_FEATURES, TN_QUERY_STEP_BASE,
+)

@@ -1,0 +1,268 @@
+"""ctypes binding of libtn_linear.so: argument marshalling only.
+
+Function names mirror the C ABI (include/tn_linear.h). Tensors are torch CUDA
+(ROCm) tensors; the binding passes their data pointers and the current HIP
+stream. Nothing here computes.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch  # imported before the library so both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libtn_linear.so"
+
+TN_FORMAT_DENSE, TN_FORMAT_TT, TN_FORMAT_TR, TN_FORMAT_TUCKER = 0, 1, 2, 3
+TN_DTYPE_F32, TN_DTYPE_BF16 = 0, 1
+TN_FLAG_SCALAR_KERNELS = 1
+TN_QUERY_PARAM_COUNT = 0
+TN_QUERY_PACKED_BYTES = 1
+TN_QUERY_FLOPS_PER_TOKEN = 2
+TN_QUERY_WORKSPACE_BYTES = 3
+TN_QUERY_NUM_STEPS = 4
+TN_QUERY_CHUNK_TOKENS = 5
+TN_QUERY_MAX_INTERMEDIATE = 6
+TN_QUERY_OUT_FEATURES = 7
+TN_QUERY_IN_FEATURES = 8
+TN_QUERY_STEP_BASE = 100
+
+EXPORTED_SYMBOLS = (
+    "tn_linear_create",
+    "tn_linear_forward",
+    "tn_linear_destroy",
+    "tn_linear_query",
+    "tn_linear_plan_query",
+    "tn_linear_profile",
+    "tn_linear_profile_read",
+    "tn_linear_strerror",
+    "tn_linear_version",
+)
+
+
+class TNLinearError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {tn_linear_strerror(status)} (status {status})")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [
+        ("format", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("n_out_modes", ctypes.c_int32),
+        ("out_modes", ctypes.POINTER(ctypes.c_int32)),
+        ("n_in_modes", ctypes.c_int32),
+        ("in_modes", ctypes.POINTER(ctypes.c_int32)),
+        ("n_ranks", ctypes.c_int32),
+        ("ranks", ctypes.POINTER(ctypes.c_int32)),
+        ("n_tensors", ctypes.c_int32),
+        ("tensors", ctypes.POINTER(ctypes.c_void_p)),
+        ("max_tokens", ctypes.c_int64),
+        ("workspace_limit_bytes", ctypes.c_int64),
+        ("flags", ctypes.c_int32),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(
+            f"{path} is missing: build it with `python -m paper_2602_01613_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    lib.tn_linear_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(_Desc)]
+    lib.tn_linear_create.restype = ctypes.c_int
+    lib.tn_linear_forward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                      ctypes.c_void_p]
+    lib.tn_linear_forward.restype = ctypes.c_int
+    lib.tn_linear_destroy.argtypes = [ctypes.c_void_p]
+    lib.tn_linear_destroy.restype = ctypes.c_int
+    lib.tn_linear_query.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
+    lib.tn_linear_query.restype = ctypes.c_int
+    lib.tn_linear_plan_query.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
+    lib.tn_linear_plan_query.restype = ctypes.c_int
+    lib.tn_linear_profile.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+    lib.tn_linear_profile.restype = ctypes.c_int
+    lib.tn_linear_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_int64)]
+    lib.tn_linear_profile_read.restype = ctypes.c_int
+    lib.tn_linear_strerror.argtypes = [ctypes.c_int]
+    lib.tn_linear_strerror.restype = ctypes.c_char_p
+    lib.tn_linear_version.argtypes = []
+    lib.tn_linear_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _int_array(values: Sequence[int]):
+    arr = (ctypes.c_int32 * max(1, len(values)))(*[int(v) for v in values])
+    return arr
+
+
+def _make_desc(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens, workspace_limit_bytes, flags,
+               stream):
+    keep = []
+    d = _Desc()
+    d.format, d.dtype = int(fmt), int(dtype)
+    om, im, rk = _int_array(out_modes), _int_array(in_modes), _int_array(ranks)
+    keep += [om, im, rk]
+    d.n_out_modes, d.out_modes = len(out_modes), om
+    d.n_in_modes, d.in_modes = len(in_modes), im
+    d.n_ranks, d.ranks = len(ranks), rk
+    if tensor_ptrs is not None:
+        tp = (ctypes.c_void_p * max(1, len(tensor_ptrs)))(*tensor_ptrs)
+        keep.append(tp)
+        d.n_tensors, d.tensors = len(tensor_ptrs), tp
+    else:
+        d.n_tensors, d.tensors = 0, None
+    d.max_tokens = int(max_tokens)
+    d.workspace_limit_bytes = int(workspace_limit_bytes)
+    d.flags = int(flags)
+    d.stream = stream
+    return d, keep
+
+
+def tn_linear_version() -> int:
+    return int(load_library().tn_linear_version())
+
+
+def tn_linear_strerror(status: int) -> str:
+    return load_library().tn_linear_strerror(int(status)).decode()
+
+
+def tn_linear_plan_query(fmt, dtype, out_modes, in_modes, ranks, what, max_tokens=1) -> int:
+    """Host-only plan property; needs no GPU."""
+    d, keep = _make_desc(fmt, dtype, out_modes, in_modes, ranks, None, max_tokens, 0, 0, None)
+    val = ctypes.c_int64(0)
+    rc = load_library().tn_linear_plan_query(ctypes.byref(d), int(what), ctypes.byref(val))
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_plan_query")
+    return int(val.value)
+
+
+plan_query = tn_linear_plan_query
+
+
+def tn_linear_create(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens,
+                     workspace_limit_bytes=0, flags=0, stream=None) -> int:
+    """Returns the opaque handle (an integer address)."""
+    d, keep = _make_desc(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens,
+                         workspace_limit_bytes, flags, stream)
+    h = ctypes.c_void_p(0)
+    rc = load_library().tn_linear_create(ctypes.byref(h), ctypes.byref(d))
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_create")
+    return int(h.value)
+
+
+def tn_linear_forward(handle: int, x_ptr: int, y_ptr: int, tokens: int, stream) -> None:
+    rc = load_library().tn_linear_forward(handle, x_ptr, y_ptr, int(tokens), stream)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_forward")
+
+
+def tn_linear_destroy(handle: Optional[int]) -> None:
+    rc = load_library().tn_linear_destroy(handle)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_destroy")
+
+
+def tn_linear_query(handle: int, what: int) -> int:
+    val = ctypes.c_int64(0)
+    rc = load_library().tn_linear_query(handle, int(what), ctypes.byref(val))
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_query")
+    return int(val.value)
+
+
+def tn_linear_profile(handle: int, enable: bool) -> None:
+    rc = load_library().tn_linear_profile(handle, 1 if enable else 0)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_profile")
+
+
+def tn_linear_profile_read(handle: int, step: int):
+    """(total milliseconds, launches) recorded for one contraction step."""
+    ms = ctypes.c_double(0)
+    n = ctypes.c_int64(0)
+    rc = load_library().tn_linear_profile_read(handle, int(step), ctypes.byref(ms), ctypes.byref(n))
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_profile_read")
+    return float(ms.value), int(n.value)
+
+
+_TORCH_DTYPE = {TN_DTYPE_F32: torch.float32, TN_DTYPE_BF16: torch.bfloat16}
+
+
+class TNLinear:
+    """One tensor-network linear layer living on the current GPU."""
+
+    def __init__(self, fmt: int, dtype: int, out_modes: Sequence[int], in_modes: Sequence[int],
+                 ranks: Sequence[int], tensors: List[torch.Tensor], max_tokens: int,
+                 workspace_limit_bytes: int = 0, flags: int = 0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("TNLinear needs a GPU: there is no CPU path")
+        self.dtype = int(dtype)
+        self.torch_dtype = _TORCH_DTYPE[self.dtype]
+        for t in tensors:
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == self.torch_dtype):
+                raise ValueError("tensors must be contiguous CUDA tensors of the layer dtype")
+        stream = torch.cuda.current_stream().cuda_stream
+        self._handle = tn_linear_create(fmt, dtype, out_modes, in_modes, ranks,
+                                        [t.data_ptr() for t in tensors], max_tokens,
+                                        workspace_limit_bytes, flags, stream)
+        self.M = tn_linear_query(self._handle, TN_QUERY_OUT_FEATURES)
+        self.N = tn_linear_query(self._handle, TN_QUERY_IN_FEATURES)
+
+    def forward(self, x: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if self._handle is None:
+            raise RuntimeError("layer was closed")
+        if not (x.is_cuda and x.is_contiguous() and x.dtype == self.torch_dtype and x.dim() == 2
+                and x.shape[1] == self.N):
+            raise ValueError(f"x must be a contiguous CUDA [tokens, {self.N}] tensor of the layer dtype")
+        tokens = x.shape[0]
+        if out is None:
+            out = torch.empty((tokens, self.M), dtype=self.torch_dtype, device=x.device)
+        elif not (out.is_cuda and out.is_contiguous() and out.dtype == self.torch_dtype
+                  and tuple(out.shape) == (tokens, self.M)):
+            raise ValueError("out has the wrong shape, dtype or layout")
+        tn_linear_forward(self._handle, x.data_ptr(), out.data_ptr(), tokens,
+                          torch.cuda.current_stream().cuda_stream)
+        return out
+
+    __call__ = forward
+
+    def query(self, what: int) -> int:
+        return tn_linear_query(self._handle, what)
+
+    def profile(self, enable: bool) -> None:
+        tn_linear_profile(self._handle, enable)
+
+    def profile_read(self, step: int):
+        return tn_linear_profile_read(self._handle, step)
+
+    def close(self) -> None:
+        if self._handle is not None:
+            tn_linear_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

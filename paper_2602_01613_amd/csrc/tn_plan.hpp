@@ -1,0 +1,484 @@
+// Host-side planner for tensor-network linear layers (no GPU calls).
+//
+// A layer is a small tensor network: the activation tensor x[n_1..n_q] and a
+// set of parameter tensors (TT/TR cores, Tucker core and factors, or one dense
+// matrix; formats of Section 3.3). The forward pass absorbs one parameter
+// tensor per step into a running intermediate Z (Section 3.5: sequential core
+// contractions). Absorbing tensor P contracts every index of P that is live in
+// Z and introduces every other index of P, which as a matrix product reads
+//     rows = all other live indices of Z   (times tokens)
+//     K    = indices shared by Z and P
+//     cols = indices of P not in Z
+// The planner picks the absorption order with the fewest multiply-adds by a
+// dynamic programme over subsets of absorbed tensors, then assigns a memory
+// layout to every intermediate such that each step reads a plain row-major
+// [rows, K] matrix, and the index permutation between steps happens in the
+// store of the previous step through two small offset tables.
+#pragma once
+
+#include <algorithm>
+#include <cstdint>
+#include <limits>
+#include <string>
+#include <vector>
+
+#include "../../include/tn_linear.h"
+
+namespace tn {
+
+constexpr int kMaxTensors = 16;
+constexpr int kMaxGatherDims = 8;
+
+struct GatherDim {
+    int64_t extent;
+    int64_t stride;   // in elements of the caller's tensor
+};
+
+struct NetTensor {
+    int slot;                       // index into desc.tensors
+    std::vector<int> idx;           // index ids, outer -> inner, canonical layout (trace pair removed)
+    std::vector<int64_t> stride;    // element stride of each idx entry
+    int64_t trace_extent = 1;       // >1: sum over a repeated index (single-core ring)
+    int64_t trace_stride = 0;
+    int64_t n_elems = 0;
+};
+
+struct Step {
+    int tensor = -1;                // network tensor absorbed
+    int slot = -1;                  // desc.tensors slot of that tensor
+    int64_t R = 1, K = 1, C = 1;    // rows per token, contraction length, columns
+    std::vector<GatherDim> kdims, cdims;   // decomposition of k and c into source strides
+    int64_t trace_extent = 1, trace_stride = 0;
+    bool a_plain = true;            // A is row-major [tokens*R, K] with leading dimension K
+    std::vector<int32_t> arow, acol;       // gather tables when !a_plain
+    int64_t a_tok_stride = 0;       // elements per token of the step's input
+    std::vector<int32_t> crow, ccol;       // scatter tables of the output
+    int64_t c_tok_stride = 0;       // elements per token of the step's output
+    int c_vec = 1;                  // columns come in aligned contiguous runs of this many (1, 4 or 8)
+    int r_vec = 1;                  // rows come in aligned contiguous runs of this many (1 or 8)
+    int64_t flops = 0;              // 2*R*K*C
+};
+
+struct Plan {
+    int format = 0, dtype = 0;
+    int64_t M = 1, N = 1;
+    int64_t params = 0;
+    int64_t flops = 0;
+    int64_t max_intermediate = 0;   // elements per token, over all step inputs and outputs except x and y
+    std::vector<int64_t> extent;    // per index id
+    std::vector<NetTensor> tensors;
+    std::vector<int> x_idx, y_idx;  // index ids of x and y, outer -> inner
+    std::vector<Step> steps;
+};
+
+namespace detail {
+
+inline bool mul_overflow(int64_t a, int64_t b, int64_t* out) {
+    return __builtin_mul_overflow(a, b, out);
+}
+
+inline int64_t prod_extents(const std::vector<int>& ids, const std::vector<int64_t>& ext) {
+    int64_t p = 1;
+    for (int i : ids) p *= ext[i];
+    return p;
+}
+
+inline bool contains(const std::vector<int>& v, int x) {
+    return std::find(v.begin(), v.end(), x) != v.end();
+}
+
+}  // namespace detail
+
+// Validate the description and build the index network. Returns TN_OK or an error.
+inline int build_network(const tn_linear_desc* d, Plan* p) {
+    using detail::mul_overflow;
+    if (!d) return TN_ERR_INVALID_ARG;
+    if (d->format < TN_FORMAT_DENSE || d->format > TN_FORMAT_TUCKER) return TN_ERR_INVALID_ARG;
+    if (d->dtype != TN_DTYPE_F32 && d->dtype != TN_DTYPE_BF16) return TN_ERR_INVALID_ARG;
+    if (d->n_out_modes < 1 || d->n_in_modes < 1 || !d->out_modes || !d->in_modes) return TN_ERR_INVALID_ARG;
+    if (d->n_out_modes > kMaxTensors || d->n_in_modes > kMaxTensors) return TN_ERR_UNSUPPORTED;
+    if (d->max_tokens < 1) return TN_ERR_INVALID_ARG;
+    if (d->workspace_limit_bytes < 0) return TN_ERR_INVALID_ARG;
+    p->format = d->format;
+    p->dtype = d->dtype;
+    int64_t M = 1, N = 1;
+    for (int i = 0; i < d->n_out_modes; ++i) {
+        if (d->out_modes[i] < 1) return TN_ERR_INVALID_ARG;
+        if (mul_overflow(M, d->out_modes[i], &M)) return TN_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < d->n_in_modes; ++i) {
+        if (d->in_modes[i] < 1) return TN_ERR_INVALID_ARG;
+        if (mul_overflow(N, d->in_modes[i], &N)) return TN_ERR_INVALID_ARG;
+    }
+    // int32 offset tables address positions inside one token's tensors.
+    if (M > (int64_t(1) << 30) || N > (int64_t(1) << 30)) return TN_ERR_UNSUPPORTED;
+    p->M = M;
+    p->N = N;
+    auto new_index = [&](int64_t e) {
+        p->extent.push_back(e);
+        return int(p->extent.size()) - 1;
+    };
+    auto add_tensor = [&](int slot, const std::vector<int>& idx) -> int {
+        NetTensor t;
+        t.slot = slot;
+        int n = int(idx.size());
+        std::vector<int64_t> st(n, 1);
+        int64_t total = 1;
+        for (int i = n - 1; i >= 0; --i) {
+            st[i] = total;
+            if (mul_overflow(total, p->extent[idx[i]], &total)) return TN_ERR_INVALID_ARG;
+        }
+        if (total > (int64_t(1) << 40)) return TN_ERR_UNSUPPORTED;
+        t.n_elems = total;
+        // a repeated index inside one tensor (ring of one core) becomes a partial trace
+        std::vector<bool> drop(n, false);
+        for (int i = 0; i < n; ++i)
+            for (int j = i + 1; j < n; ++j)
+                if (idx[i] == idx[j] && !drop[i] && !drop[j]) {
+                    if (t.trace_extent != 1) return TN_ERR_UNSUPPORTED;
+                    t.trace_extent = p->extent[idx[i]];
+                    t.trace_stride = st[i] + st[j];
+                    drop[i] = drop[j] = true;
+                }
+        for (int i = 0; i < n; ++i)
+            if (!drop[i]) {
+                t.idx.push_back(idx[i]);
+                t.stride.push_back(st[i]);
+            }
+        p->params += total;
+        p->tensors.push_back(t);
+        return TN_OK;
+    };
+
+    if (d->format == TN_FORMAT_DENSE) {
+        // one index per side: only M and N matter for a dense matrix
+        int mi = new_index(M), ni = new_index(N);
+        p->y_idx = {mi};
+        p->x_idx = {ni};
+        if (d->tensors && d->n_tensors != 1) return TN_ERR_INVALID_ARG;
+        return add_tensor(0, {mi, ni});
+    }
+    if (d->format == TN_FORMAT_TT || d->format == TN_FORMAT_TR) {
+        int dd = d->n_out_modes;
+        if (d->n_in_modes != dd) return TN_ERR_INVALID_ARG;
+        if (d->n_ranks != dd + 1 || !d->ranks) return TN_ERR_INVALID_ARG;
+        for (int i = 0; i <= dd; ++i)
+            if (d->ranks[i] < 1) return TN_ERR_INVALID_ARG;
+        if (d->format == TN_FORMAT_TT && (d->ranks[0] != 1 || d->ranks[dd] != 1)) return TN_ERR_INVALID_ARG;
+        if (d->format == TN_FORMAT_TR && d->ranks[0] != d->ranks[dd]) return TN_ERR_INVALID_ARG;
+        if (d->tensors && d->n_tensors != dd) return TN_ERR_INVALID_ARG;
+        std::vector<int> mi(dd), ni(dd), bi(dd + 1);
+        for (int k = 0; k < dd; ++k) mi[k] = new_index(d->out_modes[k]);
+        for (int k = 0; k < dd; ++k) ni[k] = new_index(d->in_modes[k]);
+        for (int k = 0; k <= dd; ++k) bi[k] = new_index(d->ranks[k]);
+        if (d->format == TN_FORMAT_TR) bi[dd] = bi[0];   // the ring bond is one index with two owners
+        p->y_idx = mi;
+        p->x_idx = ni;
+        for (int k = 0; k < dd; ++k) {
+            // the two boundary bonds of a train have extent 1 and no second owner: leave them
+            // out (strides are unchanged by an extent-1 axis)
+            std::vector<int> idx;
+            if (!(d->format == TN_FORMAT_TT && k == 0)) idx.push_back(bi[k]);
+            idx.push_back(mi[k]);
+            idx.push_back(ni[k]);
+            if (!(d->format == TN_FORMAT_TT && k == dd - 1)) idx.push_back(bi[k + 1]);
+            int rc = add_tensor(k, idx);
+            if (rc != TN_OK) return rc;
+        }
+        return TN_OK;
+    }
+    // Tucker
+    int pp = d->n_out_modes, qq = d->n_in_modes;
+    if (pp + qq + 1 > kMaxTensors) return TN_ERR_UNSUPPORTED;
+    if (d->n_ranks != pp + qq || !d->ranks) return TN_ERR_INVALID_ARG;
+    for (int i = 0; i < pp + qq; ++i)
+        if (d->ranks[i] < 1) return TN_ERR_INVALID_ARG;
+    if (d->tensors && d->n_tensors != pp + qq + 1) return TN_ERR_INVALID_ARG;
+    std::vector<int> mi(pp), ni(qq), ri(pp), si(qq);
+    for (int a = 0; a < pp; ++a) mi[a] = new_index(d->out_modes[a]);
+    for (int b = 0; b < qq; ++b) ni[b] = new_index(d->in_modes[b]);
+    for (int a = 0; a < pp; ++a) ri[a] = new_index(d->ranks[a]);
+    for (int b = 0; b < qq; ++b) si[b] = new_index(d->ranks[pp + b]);
+    p->y_idx = mi;
+    p->x_idx = ni;
+    std::vector<int> core_idx = ri;
+    core_idx.insert(core_idx.end(), si.begin(), si.end());
+    int rc = add_tensor(0, core_idx);
+    if (rc != TN_OK) return rc;
+    for (int a = 0; a < pp; ++a) {
+        rc = add_tensor(1 + a, {mi[a], ri[a]});
+        if (rc != TN_OK) return rc;
+    }
+    for (int b = 0; b < qq; ++b) {
+        rc = add_tensor(1 + pp + b, {ni[b], si[b]});
+        if (rc != TN_OK) return rc;
+    }
+    return TN_OK;
+}
+
+// Live indices after absorbing the tensors in `mask`: an index is live when it is
+// carried by x or an absorbed tensor, and also by y or a tensor not yet absorbed.
+inline std::vector<int> live_after(const Plan& p, uint32_t mask) {
+    int ni = int(p.extent.size());
+    std::vector<int> in_done(ni, 0), in_todo(ni, 0);
+    for (int i : p.x_idx) in_done[i] = 1;
+    for (int i : p.y_idx) in_todo[i] = 1;
+    for (size_t t = 0; t < p.tensors.size(); ++t)
+        for (int i : p.tensors[t].idx) {
+            if (mask & (1u << t)) in_done[i] = 1;
+            else in_todo[i] = 1;
+        }
+    std::vector<int> live;
+    for (int i = 0; i < ni; ++i)
+        if (in_done[i] && in_todo[i]) live.push_back(i);
+    return live;
+}
+
+// Fewest-FLOP absorption order by dynamic programming over subsets.
+inline int choose_order(const Plan& p, std::vector<int>* order) {
+    int n = int(p.tensors.size());
+    if (n > kMaxTensors) return TN_ERR_UNSUPPORTED;
+    uint32_t full = (n == 32) ? 0xffffffffu : ((1u << n) - 1);
+    struct Cost {
+        double flops = std::numeric_limits<double>::infinity();
+        double penalty = 0;      // first step cannot read x as a plain matrix
+        double peak = 0;         // largest intermediate
+        int prev = -1;
+        bool better(const Cost& o) const {
+            if (flops != o.flops) return flops < o.flops;
+            if (penalty != o.penalty) return penalty < o.penalty;
+            return peak < o.peak;
+        }
+    };
+    std::vector<Cost> best(size_t(full) + 1);
+    best[0].flops = 0;
+    for (uint32_t mask = 0; mask <= full; ++mask) {
+        if (best[mask].flops == std::numeric_limits<double>::infinity()) {
+            if (mask == full) break;
+            continue;
+        }
+        if (mask == full) break;
+        std::vector<int> live = live_after(p, mask);
+        double live_sz = 1;
+        for (int i : live) live_sz *= double(p.extent[i]);
+        for (int t = 0; t < n; ++t) {
+            if (mask & (1u << t)) continue;
+            const NetTensor& T = p.tensors[t];
+            double ksz = 1, csz = 1;
+            int nk = 0;
+            for (int i : T.idx) {
+                if (detail::contains(live, i)) { ksz *= double(p.extent[i]); ++nk; }
+                else csz *= double(p.extent[i]);
+            }
+            if (nk == 0) continue;    // an outer product is never a useful step here
+            Cost c;
+            c.flops = best[mask].flops + 2.0 * live_sz * csz;   // rows*K = live_sz
+            double out_sz = live_sz / ksz * csz;
+            c.peak = std::max(best[mask].peak, (mask | (1u << t)) == full ? 0.0 : out_sz);
+            c.penalty = best[mask].penalty;
+            if (mask == 0) {
+                // plain first step: the contracted in-modes are the innermost of x
+                size_t q = p.x_idx.size();
+                bool suffix = true;
+                for (int j = 0; j < nk; ++j)
+                    if (!detail::contains(T.idx, p.x_idx[q - 1 - j])) suffix = false;
+                c.penalty = suffix ? 0 : 1;
+            }
+            c.prev = t;
+            uint32_t nm = mask | (1u << t);
+            if (c.better(best[nm])) best[nm] = c;
+        }
+    }
+    if (best[full].prev < 0 && n > 0) return TN_ERR_INVALID_ARG;
+    order->clear();
+    uint32_t mask = full;
+    while (mask) {
+        int t = best[mask].prev;
+        order->push_back(t);
+        mask &= ~(1u << t);
+    }
+    std::reverse(order->begin(), order->end());
+    return TN_OK;
+}
+
+// Offsets of every multi-index over `ids` (outer -> inner) inside a layout.
+inline std::vector<int32_t> offset_table(const std::vector<int>& ids, const std::vector<int64_t>& ext,
+                                         const std::vector<int>& layout) {
+    // stride of each layout index
+    std::vector<int64_t> lst(layout.size(), 1);
+    int64_t s = 1;
+    for (int i = int(layout.size()) - 1; i >= 0; --i) {
+        lst[i] = s;
+        s *= ext[layout[i]];
+    }
+    std::vector<int64_t> st(ids.size(), 0);
+    for (size_t j = 0; j < ids.size(); ++j)
+        for (size_t i = 0; i < layout.size(); ++i)
+            if (layout[i] == ids[j]) st[j] = lst[i];
+    int64_t total = detail::prod_extents(ids, ext);
+    std::vector<int32_t> tab(static_cast<size_t>(total), 0);
+    std::vector<int64_t> digit(ids.size(), 0);
+    int64_t off = 0;
+    for (int64_t f = 0; f < total; ++f) {
+        tab[size_t(f)] = int32_t(off);
+        for (int j = int(ids.size()) - 1; j >= 0; --j) {
+            off += st[j];
+            if (++digit[j] < ext[ids[j]]) break;
+            off -= st[j] * ext[ids[j]];
+            digit[j] = 0;
+        }
+    }
+    return tab;
+}
+
+inline int run_length(const std::vector<int32_t>& tab, int want) {
+    // largest v in {want, 4, 1} such that the table is made of aligned runs of v consecutive offsets
+    for (int v : {want, 4}) {
+        if (v > want) continue;
+        if (tab.size() % size_t(v)) continue;
+        bool ok = true;
+        for (size_t i = 0; i < tab.size() && ok; i += size_t(v)) {
+            if (tab[i] % v) ok = false;
+            for (int j = 1; j < v && ok; ++j)
+                if (tab[i + j] != tab[i] + j) ok = false;
+        }
+        if (ok) return v;
+    }
+    return 1;
+}
+
+inline bool all_multiple_of(const std::vector<int32_t>& tab, int v) {
+    for (int32_t x : tab)
+        if (x % v) return false;
+    return true;
+}
+
+// Build the steps (layouts, tables, packing recipes) for the chosen order.
+inline int build_steps(Plan* p, const std::vector<int>& order) {
+    using detail::contains;
+    const auto& ext = p->extent;
+    int n = int(order.size());
+    // time at which each index is contracted (n = never, i.e. an output mode)
+    std::vector<int> when(ext.size(), n);
+    {
+        uint32_t mask = 0;
+        for (int s = 0; s < n; ++s) {
+            std::vector<int> live = live_after(*p, mask);
+            for (int i : p->tensors[order[s]].idx)
+                if (contains(live, i)) when[i] = s;
+            mask |= 1u << order[s];
+        }
+    }
+    std::vector<int> layout = p->x_idx;
+    uint32_t mask = 0;
+    p->steps.clear();
+    p->flops = 0;
+    p->max_intermediate = 0;
+    for (int s = 0; s < n; ++s) {
+        const NetTensor& T = p->tensors[order[s]];
+        Step st;
+        st.tensor = order[s];
+        st.slot = T.slot;
+        st.trace_extent = T.trace_extent;
+        st.trace_stride = T.trace_stride;
+        std::vector<int> kset, rows, cset;
+        for (int i : layout) (contains(T.idx, i) ? kset : rows).push_back(i);
+        for (int i : T.idx)
+            if (!contains(layout, i)) cset.push_back(i);
+        if (kset.empty()) return TN_ERR_INVALID_ARG;
+        // plain when the contracted indices are the innermost of the layout
+        bool plain = true;
+        for (size_t j = 0; j < kset.size(); ++j)
+            if (layout[layout.size() - kset.size() + j] != kset[j]) plain = false;
+        st.a_plain = plain;
+        st.R = detail::prod_extents(rows, ext);
+        st.K = detail::prod_extents(kset, ext);
+        st.a_tok_stride = detail::prod_extents(layout, ext);
+        if (!plain) {
+            st.arow = offset_table(rows, ext, layout);
+            st.acol = offset_table(kset, ext, layout);
+        }
+        // next layout
+        std::vector<int> next;
+        uint32_t nmask = mask | (1u << order[s]);
+        bool last = (s == n - 1);
+        if (last) {
+            next = p->y_idx;
+            // everything else must be gone
+            std::vector<int> live = rows;
+            live.insert(live.end(), cset.begin(), cset.end());
+            if (live.size() != next.size()) return TN_ERR_INVALID_ARG;
+            for (int i : live)
+                if (!contains(next, i)) return TN_ERR_INVALID_ARG;
+        } else {
+            const NetTensor& Tn = p->tensors[order[s + 1]];
+            std::vector<int> live = rows;
+            live.insert(live.end(), cset.begin(), cset.end());
+            std::vector<int> nk_rows, nk_cols, nrows;
+            for (int i : live) {
+                if (contains(Tn.idx, i)) (contains(cset, i) ? nk_cols : nk_rows).push_back(i);
+                else nrows.push_back(i);
+            }
+            // rows of the next step: later-contracted indices outermost, output modes first and
+            // in output order, so that consecutive rows of a tile land close together when stored
+            std::stable_sort(nrows.begin(), nrows.end(), [&](int a, int b) {
+                if (when[a] != when[b]) return when[a] > when[b];
+                return a < b;
+            });
+            next = nrows;
+            next.insert(next.end(), nk_rows.begin(), nk_rows.end());
+            next.insert(next.end(), nk_cols.begin(), nk_cols.end());
+        }
+        // column order follows the position of the new indices in the next layout
+        std::stable_sort(cset.begin(), cset.end(), [&](int a, int b) {
+            auto pa = std::find(next.begin(), next.end(), a) - next.begin();
+            auto pb = std::find(next.begin(), next.end(), b) - next.begin();
+            return pa < pb;
+        });
+        st.C = detail::prod_extents(cset, ext);
+        st.c_tok_stride = detail::prod_extents(next, ext);
+        st.crow = offset_table(rows, ext, next);
+        st.ccol = offset_table(cset, ext, next);
+        st.c_vec = run_length(st.ccol, 8);
+        if (st.c_vec > 1 && (!all_multiple_of(st.crow, st.c_vec) || st.c_tok_stride % st.c_vec)) st.c_vec = 1;
+        st.r_vec = run_length(st.crow, 8) == 8 ? 8 : 1;
+        if (st.r_vec > 1 && (!all_multiple_of(st.ccol, 8) || st.c_tok_stride % 8)) st.r_vec = 1;
+        // packing recipe: B[c][k] = tensor[sum of digit*stride]
+        auto dims_of = [&](const std::vector<int>& ids, std::vector<GatherDim>* out) {
+            for (int i : ids) {
+                int64_t stride = 0;
+                for (size_t j = 0; j < T.idx.size(); ++j)
+                    if (T.idx[j] == i) stride = T.stride[j];
+                out->push_back({ext[i], stride});
+            }
+        };
+        dims_of(kset, &st.kdims);
+        dims_of(cset, &st.cdims);
+        if (int(st.kdims.size()) > kMaxGatherDims || int(st.cdims.size()) > kMaxGatherDims) return TN_ERR_UNSUPPORTED;
+        int64_t f;
+        if (detail::mul_overflow(st.R, st.K, &f) || detail::mul_overflow(f, st.C, &f) ||
+            detail::mul_overflow(f, 2, &f))
+            return TN_ERR_UNSUPPORTED;
+        st.flops = f;
+        p->flops += f;
+        if (st.a_tok_stride > (int64_t(1) << 31) - 1 || st.c_tok_stride > (int64_t(1) << 31) - 1)
+            return TN_ERR_UNSUPPORTED;
+        if (s > 0) p->max_intermediate = std::max(p->max_intermediate, st.a_tok_stride);
+        if (!last) p->max_intermediate = std::max(p->max_intermediate, st.c_tok_stride);
+        p->steps.push_back(std::move(st));
+        layout = next;
+        mask = nmask;
+    }
+    return TN_OK;
+}
+
+inline int make_plan(const tn_linear_desc* d, Plan* p) {
+    int rc = build_network(d, p);
+    if (rc != TN_OK) return rc;
+    std::vector<int> order;
+    rc = choose_order(*p, &order);
+    if (rc != TN_OK) return rc;
+    return build_steps(p, order);
+}
+
+}  // namespace tn

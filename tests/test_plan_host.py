@@ -1,0 +1,206 @@
+"""Host logic of the library: planner order, FLOP totals, layouts, scatter
+tables and packing recipes, executed on the CPU in double precision by a
+test-only C++ walker of the plan and compared with the oracle."""
+import ctypes
+import os
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as wl
+import paper_2602_01613_amd as tn
+from paper_2602_01613_amd.binding import _Desc, _make_desc
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.fixture(scope="module")
+def host_exec():
+    out = os.path.join(tempfile.mkdtemp(prefix="tn_plan_host_"), "libplan_host_exec.so")
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC",
+                           os.path.join(HERE, "plan_host_exec.cpp"), "-o", out])
+    lib = ctypes.CDLL(out)
+    lib.plan_host_forward.restype = ctypes.c_int
+    lib.plan_host_forward.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(ctypes.c_void_p),
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+    lib.plan_host_step_hint.restype = ctypes.c_int
+    lib.plan_host_step_hint.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_int64)]
+    return lib
+
+
+def _run(lib, fmt, out_modes, in_modes, ranks, tensors, x):
+    d, keep = _make_desc(fmt, tn.TN_DTYPE_F32, out_modes, in_modes, ranks, None, 1, 0, 0, None)
+    ts = [np.ascontiguousarray(t, dtype=np.float64) for t in tensors]
+    ptrs = (ctypes.c_void_p * len(ts))(*[t.ctypes.data for t in ts])
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    m = int(np.prod(out_modes))
+    y = np.zeros((x.shape[0], m))
+    rc = lib.plan_host_forward(ctypes.byref(d), ptrs, x.ctypes.data, y.ctypes.data, x.shape[0])
+    assert rc == 0, f"plan_host_forward failed with {rc}"
+    return y
+
+
+def _rand_tensors(rng, fmt, out_modes, in_modes, ranks):
+    spec = wl.TNSpec(fmt, "f32", tuple(out_modes), tuple(in_modes), tuple(ranks))
+    return [rng.standard_normal(s) for s in spec.tensor_shapes()]
+
+
+CASES = [
+    (tn.TN_FORMAT_TT, (4, 8, 8), (4, 8, 8), (1, 8, 8, 1)),
+    (tn.TN_FORMAT_TT, (3, 4, 2), (2, 5, 3), (1, 3, 4, 1)),
+    (tn.TN_FORMAT_TT, (2, 3, 2, 2), (5, 2, 3, 2), (1, 2, 5, 3, 1)),       # best order is not right-to-left
+    (tn.TN_FORMAT_TT, (7,), (5,), (1, 1)),
+    (tn.TN_FORMAT_TT, (1, 3, 1), (2, 1, 3), (1, 1, 2, 1)),                 # size-1 modes and bonds
+    (tn.TN_FORMAT_TR, (2, 3, 2), (3, 2, 2), (3, 2, 4, 3)),
+    (tn.TN_FORMAT_TR, (2, 3, 2, 2), (3, 2, 2, 3), (2, 3, 2, 3, 2)),
+    (tn.TN_FORMAT_TR, (4, 3), (3, 5), (2, 3, 2)),
+    (tn.TN_FORMAT_TR, (5,), (7,), (3, 3)),                                  # ring of one core: partial trace
+    (tn.TN_FORMAT_TR, (3, 2), (2, 4), (1, 3, 1)),
+    (tn.TN_FORMAT_TUCKER, (4, 5), (3, 6), (2, 3, 2, 4)),
+    (tn.TN_FORMAT_TUCKER, (6,), (5,), (3, 4)),
+    (tn.TN_FORMAT_TUCKER, (3, 2, 4), (5,), (2, 2, 3, 4)),
+    (tn.TN_FORMAT_TUCKER, (4,), (2, 3, 2), (3, 2, 2, 2)),
+    (tn.TN_FORMAT_DENSE, (9,), (11,), ()),
+    (tn.TN_FORMAT_DENSE, (3, 3), (2, 5), ()),
+]
+
+
+@pytest.mark.parametrize("fmt,om,im,rk", CASES)
+def test_plan_executes_to_oracle(host_exec, fmt, om, im, rk):
+    rng = np.random.default_rng(hash((fmt, om, im, rk)) % (2 ** 32))
+    if fmt == tn.TN_FORMAT_DENSE:
+        tensors = [rng.standard_normal((int(np.prod(om)), int(np.prod(im))))]
+    else:
+        tensors = _rand_tensors(rng, fmt, om, im, rk)
+    x = rng.standard_normal((3, int(np.prod(im))))
+    y = _run(host_exec, fmt, om, im, rk, tensors, x)
+    ref = O.forward(fmt, tensors, x, n_out_modes=len(om))
+    assert O.rel_max_err(y, ref) < 1e-12
+
+
+def test_plan_small_baseline_config(host_exec):
+    spec, toks = wl.baseline_spec(0)
+    tensors = wl.make_tensors(spec, 0)
+    x = wl.make_x(spec, toks[0], 0)
+    y = _run(host_exec, spec.format, spec.out_modes, spec.in_modes, spec.ranks, tensors, x)
+    assert O.rel_max_err(y, O.forward(spec.format, tensors, x)) < 1e-12
+
+
+def _q(spec, what):
+    dt = tn.TN_DTYPE_BF16 if spec.dtype == "bf16" else tn.TN_DTYPE_F32
+    return tn.plan_query(spec.format, dt, spec.out_modes, spec.in_modes, spec.ranks, what)
+
+
+def test_flop_totals_and_orders():
+    # fewest-FLOP orders of the four single-layer workloads (2 * multiply-adds per token)
+    expect = {0: 311296, 1: 1020264448, 2: 51118080, 3: 12666798080}
+    for i, f in expect.items():
+        spec, _ = wl.baseline_spec(i)
+        assert _q(spec, tn.TN_QUERY_FLOPS_PER_TOKEN) == f
+        assert _q(spec, tn.TN_QUERY_PARAM_COUNT) == spec.n_params
+        assert _q(spec, tn.TN_QUERY_OUT_FEATURES) == spec.M
+        assert _q(spec, tn.TN_QUERY_IN_FEATURES) == spec.N
+    # TT q_proj: right-to-left, steps (rows, K, cols)
+    spec, _ = wl.baseline_spec(1)
+    steps = [[_q(spec, 100 + 10 * s + f) for f in range(5)] for s in range(4)]
+    assert [s[4] for s in steps] == [3, 2, 1, 0]
+    assert [tuple(s[:3]) for s in steps] == [(640, 8, 512), (640, 512, 512), (512, 640, 1024), (1024, 512, 8)]
+    # TR down_proj: core 4, then across the ring bond to core 1, then 3, and core 2 closes two bonds
+    spec, _ = wl.baseline_spec(3)
+    steps = [[_q(spec, 100 + 10 * s + f) for f in range(5)] for s in range(4)]
+    assert [s[4] for s in steps] == [3, 0, 2, 1]
+    assert tuple(steps[3][:3]) == (512, 16384, 10)
+    # Tucker up_proj: in-factors, core, out-factors
+    spec, _ = wl.baseline_spec(2)
+    assert _q(spec, tn.TN_QUERY_NUM_STEPS) == 5
+    assert [_q(spec, 100 + 10 * s + 4) for s in range(3)] == [4, 3, 0]
+    assert tuple(_q(spec, 120 + f) for f in range(3)) == (1, 2304, 9216)
+
+
+def test_planned_flops_equal_brute_force_minimum():
+    # exhaustive search over all absorption orders of a TT and a TR, in Python
+    from itertools import permutations
+
+    def cost(order, ms, ns, rs, ring):
+        d = len(ms)
+        live = {("n", k): ns[k] for k in range(d)}
+        total = 0
+        for k in order:
+            bonds = [("b", k % d if ring else k), ("b", (k + 1) % d if ring else k + 1)]
+            ext = {bonds[0]: rs[k], bonds[1]: rs[k + 1]}
+            if not ring:
+                ext = {b: e for b, e in ext.items() if b[1] not in (0, d)}
+            size = int(np.prod(list(live.values()))) if live else 1
+            new = ms[k]
+            for b, e in ext.items():
+                if b not in live:
+                    new *= e
+            total += 2 * size * new
+            del live[("n", k)]
+            live[("m", k)] = ms[k]
+            for b, e in ext.items():
+                if b in live:
+                    del live[b]
+                else:
+                    live[b] = e
+        return total
+
+    for fmt, ms, ns, rs in [(tn.TN_FORMAT_TT, (8, 16, 8, 8), (8, 10, 8, 8), (1, 64, 64, 64, 1)),
+                            (tn.TN_FORMAT_TR, (8, 10, 8, 8), (10, 16, 10, 16), (32,) * 5),
+                            (tn.TN_FORMAT_TT, (2, 3, 2, 2), (5, 2, 3, 2), (1, 2, 5, 3, 1)),
+                            (tn.TN_FORMAT_TR, (2, 3, 2), (3, 2, 2), (3, 2, 4, 3))]:
+        best = min(cost(o, ms, ns, rs, fmt == tn.TN_FORMAT_TR) for o in permutations(range(len(ms))))
+        assert tn.plan_query(fmt, 1, ms, ns, rs, tn.TN_QUERY_FLOPS_PER_TOKEN) == best
+
+
+def test_vector_store_hints(host_exec):
+    # TT q_proj: intermediate steps store runs of 64 contiguous bond entries, the last step
+    # stores contiguous rows; every step after the first reads a plain matrix.
+    spec, _ = wl.baseline_spec(1)
+    d, keep = _make_desc(spec.format, 1, spec.out_modes, spec.in_modes, spec.ranks, None, 1, 0, 0, None)
+    v = ctypes.c_int64(0)
+    hints = []
+    for s in range(4):
+        row = []
+        for f in range(3):
+            assert host_exec.plan_host_step_hint(ctypes.byref(d), s, f, ctypes.byref(v)) == 0
+            row.append(v.value)
+        hints.append(row)
+    assert [h[2] for h in hints] == [1, 1, 1, 1]
+    assert [h[0] for h in hints[:3]] == [8, 8, 8]
+    assert hints[3][1] == 8
+
+
+def test_invalid_descriptions_are_rejected():
+    bad = [
+        (tn.TN_FORMAT_TT, (4, 4), (4,), (1, 2, 1)),          # mode count mismatch
+        (tn.TN_FORMAT_TT, (4, 4), (4, 4), (2, 2, 1)),        # r_0 != 1
+        (tn.TN_FORMAT_TR, (4, 4), (4, 4), (2, 2, 3)),        # ring bond mismatch
+        (tn.TN_FORMAT_TT, (4, 0), (4, 4), (1, 2, 1)),        # zero extent
+        (tn.TN_FORMAT_TUCKER, (4, 4), (4, 4), (2, 2, 2)),    # wrong number of ranks
+        (7, (4,), (4,), ()),                                  # unknown format
+    ]
+    for fmt, om, im, rk in bad:
+        with pytest.raises(tn.TNLinearError) as e:
+            tn.plan_query(fmt, 1, om, im, rk, tn.TN_QUERY_FLOPS_PER_TOKEN)
+        assert e.value.status == -1
+    with pytest.raises(tn.TNLinearError):
+        tn.plan_query(tn.TN_FORMAT_TT, 5, (4,), (4,), (1, 1), tn.TN_QUERY_FLOPS_PER_TOKEN)
+
+
+def test_library_exports_every_declared_symbol():
+    import re
+    hdr = open(os.path.join(os.path.dirname(HERE), "include", "tn_linear.h")).read()
+    declared = set(re.findall(r"\b(tn_linear_[a-z_]+)\s*\(", hdr))
+    declared -= {"tn_linear_s"}
+    assert declared == set(tn.EXPORTED_SYMBOLS)
+    lib = tn.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert tn.tn_linear_version() == 1
+    assert tn.tn_linear_strerror(0) == "success"
+    assert "invalid" in tn.tn_linear_strerror(-1)
