@@ -60,6 +60,9 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--workload", type=int, default=1, help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR)")
     ap.add_argument("--workspace-mb", type=int, default=0, help="workspace limit in MiB (0 = library default)")
+    ap.add_argument("--variant", type=int, default=0, help="tuning override: kernel variant id of the wide steps")
+    ap.add_argument("--no-merge", action="store_true",
+                    help="keep the chain as given (no create-time merging of parameter tensors)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -84,7 +87,7 @@ def main() -> int:
     x = torch.from_numpy(x64).to(torch.float32).to(torch.bfloat16).cuda()
     del x64
     layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
-                        tokens, args.workspace_mb << 20)
+                        tokens, args.workspace_mb << 20, flags=(args.variant << 8) | (2 if args.no_merge else 0))
     y = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 

@@ -52,6 +52,10 @@ extern "C" {
 
 /* desc.flags */
 #define TN_FLAG_SCALAR_KERNELS  1   /* run every contraction step on the plain FMA kernel (debug aid) */
+#define TN_FLAG_NO_MERGE        2   /* keep every parameter tensor separate: do not contract adjacent
+                                       tensors into one at create time even where that is free */
+#define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
+                                       bf16 steps (0 = library's choice; see TN_QUERY_STEP_BASE f=5) */
 
 /* tn_linear_query / tn_linear_plan_query: what */
 #define TN_QUERY_PARAM_COUNT        0   /* number of parameters in the caller's tensors */
@@ -63,9 +67,11 @@ extern "C" {
 #define TN_QUERY_MAX_INTERMEDIATE   6   /* largest per-token intermediate, in elements */
 #define TN_QUERY_OUT_FEATURES       7   /* M */
 #define TN_QUERY_IN_FEATURES        8   /* N */
+#define TN_QUERY_NUM_MERGES         9   /* parameter-tensor pairs contracted into one at create time */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
-                                           4 id of the absorbed tensor (index into desc.tensors),
+                                           4 id of the absorbed tensor (index into desc.tensors; ids >=
+                                             n_tensors name tensors merged at create time),
                                            5 kernel variant chosen (0 scalar; >0 MFMA tile id) */
 
 typedef struct tn_linear_s* tn_linear_t;

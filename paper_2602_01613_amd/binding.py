@@ -18,6 +18,7 @@ _LIB_NAME = "libtn_linear.so"
 TN_FORMAT_DENSE, TN_FORMAT_TT, TN_FORMAT_TR, TN_FORMAT_TUCKER = 0, 1, 2, 3
 TN_DTYPE_F32, TN_DTYPE_BF16 = 0, 1
 TN_FLAG_SCALAR_KERNELS = 1
+TN_FLAG_NO_MERGE = 2
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -27,6 +28,7 @@ TN_QUERY_CHUNK_TOKENS = 5
 TN_QUERY_MAX_INTERMEDIATE = 6
 TN_QUERY_OUT_FEATURES = 7
 TN_QUERY_IN_FEATURES = 8
+TN_QUERY_NUM_MERGES = 9
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (
@@ -145,9 +147,9 @@ def tn_linear_strerror(status: int) -> str:
     return load_library().tn_linear_strerror(int(status)).decode()
 
 
-def tn_linear_plan_query(fmt, dtype, out_modes, in_modes, ranks, what, max_tokens=1) -> int:
+def tn_linear_plan_query(fmt, dtype, out_modes, in_modes, ranks, what, max_tokens=1, flags=0) -> int:
     """Host-only plan property; needs no GPU."""
-    d, keep = _make_desc(fmt, dtype, out_modes, in_modes, ranks, None, max_tokens, 0, 0, None)
+    d, keep = _make_desc(fmt, dtype, out_modes, in_modes, ranks, None, max_tokens, 0, flags, None)
     val = ctypes.c_int64(0)
     rc = load_library().tn_linear_plan_query(ctypes.byref(d), int(what), ctypes.byref(val))
     if rc != 0:

@@ -334,12 +334,213 @@ __global__ void __launch_bounds__(256) step_mfma_kernel(StepArgs a, int cmode) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Pipelined bf16 MFMA step kernel for the FLOP-heavy steps (wide C, plain A with K % 8 == 0 or
+// gathered A). Differences from the kernel above:
+//   * the next K tile is fetched from global memory into registers while the current one is
+//     multiplied (and, with STAGES == 2, written to the other LDS buffer: one barrier per tile);
+//   * the MFMA operands are swapped (packed tensor first), so a lane ends up with 4 consecutive
+//     columns of one row and the epilogue writes 8-byte pieces to LDS;
+//   * tiles are numbered so that the column tiles of one row tile run back to back on the same
+//     XCD (workgroup i goes to XCD i % 8): the second read of an A tile hits that XCD's L2;
+//   * per-row output offsets are computed once per tile and kept in LDS.
+// ---------------------------------------------------------------------------------------------
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+template <int WM, int WN, int TM, int TN, int AMODE, int STAGES, int MINB>
+__global__ void __launch_bounds__(WM * WN * 64, MINB)
+step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
+    constexpr int LDK = BK + 8;
+    constexpr int A_ELEMS = BM * LDK, B_ELEMS = BN * LDK, STAGE_ELEMS = A_ELEMS + B_ELEMS;
+    constexpr int LDC = BN + 8;
+    constexpr int NT = WM * WN * 64;                 // threads per workgroup
+    constexpr int RPP = NT / 8;                       // tile rows covered by one pass of 16-byte loads
+    constexpr int A_CHUNKS = BM / RPP, B_CHUNKS = BN / RPP;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    bf16_t* smem = reinterpret_cast<bf16_t*>(dyn_smem);
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int row_tile = (slot / ncol_tiles) * 8 + xcd;
+    const int col_tile = slot % ncol_tiles;
+    if (row_tile >= nrow_tiles) return;
+    const uint32_t row0 = uint32_t(row_tile) * BM;
+    const int col0 = col_tile * BN;
+
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = tid >> 3, lkc = (tid & 7) * 8;      // this thread's row (mod 32) and k offset in a tile
+
+    // A addressing: AMODE 0 -> one pointer, rows 32*j apart; AMODE 1 -> per-row element offsets
+    const bf16_t* a_ptr = A + int64_t(row0 + lrow) * a.K + lkc;
+    int64_t a_base[AMODE == 1 ? A_CHUNKS : 1];
+    if (AMODE == 1) {
+#pragma unroll
+        for (int j = 0; j < A_CHUNKS; ++j) {
+            uint32_t g = row0 + lrow + RPP * j;
+            a_base[j] = -1;
+            if (g < a.total_rows) {
+                uint32_t t = g / a.R;
+                uint32_t r = g - t * a.R;
+                a_base[j] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+            }
+        }
+    }
+    const bf16_t* b_ptr = B + int64_t(col0 + lrow) * a.Kp + lkc;
+
+    bf16x8 ra[A_CHUNKS], rb[B_CHUNKS];
+    auto load_tile = [&](int k0) {
+#pragma unroll
+        for (int j = 0; j < A_CHUNKS; ++j) {
+            bf16x8 v;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
+            int k = k0 + lkc;
+            if (AMODE == 0) {
+                if (row0 + lrow + RPP * j < a.total_rows && k < a.K)
+                    v = *reinterpret_cast<const bf16x8*>(a_ptr + int64_t(RPP * j) * a.K + k0);
+            } else if (a_base[j] >= 0) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (k + q < a.K) v[q] = A[a_base[j] + (a.acol ? a.acol[k + q] : k + q)];
+            }
+            ra[j] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < B_CHUNKS; ++j)
+            rb[j] = *reinterpret_cast<const bf16x8*>(b_ptr + int64_t(RPP * j) * a.Kp + k0);
+    };
+    auto store_tile = [&](int stage) {
+        bf16_t* sA = smem + stage * STAGE_ELEMS;
+        bf16_t* sB = sA + A_ELEMS;
+#pragma unroll
+        for (int j = 0; j < A_CHUNKS; ++j)
+            *reinterpret_cast<bf16x8*>(sA + (lrow + RPP * j) * LDK + lkc) = ra[j];
+#pragma unroll
+        for (int j = 0; j < B_CHUNKS; ++j)
+            *reinterpret_cast<bf16x8*>(sB + (lrow + RPP * j) * LDK + lkc) = rb[j];
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = a.Kp / BK;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = (STAGES == 2) ? (kt & 1) : 0;
+        if (kt + 1 < nk) load_tile((kt + 1) * BK);
+        const bf16_t* sA = smem + cur * STAGE_ELEMS + ((wm * TM) * 32 + (lane & 31)) * LDK + 8 * (lane >> 5);
+        const bf16_t* sB = smem + cur * STAGE_ELEMS + A_ELEMS + ((wn * TN) * 32 + (lane & 31)) * LDK + 8 * (lane >> 5);
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += 16) {
+            bf16x8 af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * LDK + ks);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * LDK + ks);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        }
+        if (STAGES == 1) __syncthreads();
+        if (kt + 1 < nk) store_tile((STAGES == 2) ? (cur ^ 1) : 0);
+        __syncthreads();
+    }
+
+    // ---- epilogue. With the operands swapped: lane l, register v of a tile holds
+    //      row = l%32, col = 8*(v/4) + 4*(l/32) + v%4.
+    bf16_t* sC = smem;
+    int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + size_t(BM) * LDC * sizeof(bf16_t));
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4 pk;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
+                int rr = (wm * TM + i) * 32 + (lane & 31);
+                int cc = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
+                *reinterpret_cast<bf16x4*>(sC + rr * LDC + cc) = pk;
+            }
+    for (int rr = tid; rr < BM; rr += NT) {
+        uint32_t g = row0 + rr;
+        int64_t base = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            base = int64_t(t) * a.c_tok_stride + a.crow[r];
+        }
+        sBase[rr] = base;
+    }
+    __syncthreads();
+
+    constexpr int GROUPS = BM * BN / 8;
+    if (cmode == 1) {
+#pragma unroll 4
+        for (int e = tid; e < GROUPS; e += NT) {
+            int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
+            int c = col0 + cg;
+            int64_t base = sBase[rr];
+            if (base < 0 || c >= a.C) continue;
+            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
+        }
+    } else if (cmode == 2) {
+        for (int e = tid; e < GROUPS; e += NT) {
+            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
+            int c = col0 + cc;
+            int64_t base = sBase[rg];
+            if (base < 0 || c >= a.C) continue;
+            bf16x8 v;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = sC[(rg + q) * LDC + cc];
+            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = v;
+        }
+    } else {
+        for (int e = tid; e < BM * BN; e += NT) {
+            int rr = e / BN, cc = e % BN;
+            int c = col0 + cc;
+            int64_t base = sBase[rr];
+            if (base < 0 || c >= a.C) continue;
+            Out[base + a.ccol[c]] = sC[rr * LDC + cc];
+        }
+    }
+}
+
+template <int WM, int WN, int TM, int TN, int STAGES>
+constexpr size_t pipe_smem_bytes() {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t stage = size_t(BM + BN) * (64 + 8) * 2 * STAGES;
+    constexpr size_t epi = size_t(BM) * (BN + 8) * 2 + size_t(BM) * 8;
+    return stage > epi ? stage : epi;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 enum Variant : int {
     VAR_SCALAR = 0,
     VAR_MFMA_128x128 = 1,
     VAR_MFMA_256x32 = 2,
+    VAR_PIPE_128x256 = 3,     // 2 workgroups per CU, one LDS stage
+    VAR_PIPE_256x256 = 4,     // 1 workgroup per CU, two LDS stages
+    VAR_PIPE_128x128 = 5,     // 2 workgroups per CU, two LDS stages
+    VAR_PIPE8_256x256 = 6,    // 8 waves (2 per SIMD), 1 workgroup per CU, two LDS stages
+    VAR_PIPE8_256x256_S1 = 7, // same, one LDS stage
 };
 
 struct DevStep {
@@ -405,9 +606,15 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
         s->bm = 256;
         s->bn = 32;
     } else {
-        s->variant = VAR_MFMA_128x128;
-        s->bm = 128;
-        s->bn = 128;
+        int forced = (flags >> TN_FLAG_VARIANT_SHIFT) & 0xff;
+        s->variant = forced ? forced : VAR_MFMA_128x128;
+        switch (s->variant) {
+            case VAR_PIPE_128x256: s->bm = 128; s->bn = 256; break;
+            case VAR_PIPE_256x256: s->bm = 256; s->bn = 256; break;
+            case VAR_PIPE_128x128: s->bm = 128; s->bn = 128; break;
+            case VAR_PIPE8_256x256: case VAR_PIPE8_256x256_S1: s->bm = 256; s->bn = 256; break;
+            default: s->variant = VAR_MFMA_128x128; s->bm = 128; s->bn = 128; break;
+        }
     }
     s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : 1;
     s->cmode = p.c_vec == 8 ? 1 : (p.r_vec == 8 ? 2 : 0);
@@ -421,6 +628,31 @@ void launch_mfma(const DevStep& s, const StepArgs& a, dim3 grid, hipStream_t st)
         hipLaunchKernelGGL((step_mfma_kernel<WM, WN, TM, TN, 0>), grid, dim3(256), 0, st, a, s.cmode);
     else
         hipLaunchKernelGGL((step_mfma_kernel<WM, WN, TM, TN, 1>), grid, dim3(256), 0, st, a, s.cmode);
+}
+
+template <int WM, int WN, int TM, int TN, int STAGES, int MINB>
+int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t st) {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t smem = pipe_smem_bytes<WM, WN, TM, TN, STAGES>();
+    int nrow = int((rows + BM - 1) / BM), ncol = s.Cp / BN;
+    int nrow_pad = (nrow + 7) / 8 * 8;
+    dim3 grid(uint32_t(nrow_pad) * uint32_t(ncol));
+    auto k0 = step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB>;
+    auto k1 = step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB>;
+    static bool configured = false;   // per instantiation
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(smem)) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(smem)) != hipSuccess)
+            return TN_ERR_HIP;
+        configured = true;
+    }
+    if (s.amode == 0)
+        hipLaunchKernelGGL(k0, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
+    else
+        hipLaunchKernelGGL(k1, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
+    return TN_OK;
 }
 
 int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out, int64_t tokens,
@@ -456,6 +688,31 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
         case VAR_MFMA_256x32:
             launch_mfma<4, 1, 2, 1>(s, a, grid, st);
             break;
+        case VAR_PIPE_128x256: {
+            int rc = launch_pipe<2, 2, 2, 4, 1, 2>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_PIPE_256x256: {
+            int rc = launch_pipe<2, 2, 4, 4, 2, 1>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_PIPE8_256x256: {
+            int rc = launch_pipe<4, 2, 2, 4, 2, 1>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_PIPE8_256x256_S1: {
+            int rc = launch_pipe<4, 2, 2, 4, 1, 1>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_PIPE_128x128: {
+            int rc = launch_pipe<2, 2, 2, 2, 2, 2>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
         default:
             return TN_ERR_UNSUPPORTED;
     }
@@ -470,6 +727,7 @@ int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
         case TN_QUERY_MAX_INTERMEDIATE: *value = p.max_intermediate; return TN_OK;
         case TN_QUERY_OUT_FEATURES: *value = p.M; return TN_OK;
         case TN_QUERY_IN_FEATURES: *value = p.N; return TN_OK;
+        case TN_QUERY_NUM_MERGES: *value = int64_t(p.merges.size()); return TN_OK;
         default: break;
     }
     if (what >= TN_QUERY_STEP_BASE) {
@@ -486,6 +744,107 @@ int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
         }
     }
     return TN_ERR_INVALID_ARG;
+}
+
+// Offsets of every flat index over `dims` (outer -> inner) as an int32 table.
+std::vector<int32_t> gather_table(const std::vector<tn::GatherDim>& dims, int64_t total) {
+    std::vector<int32_t> tab(static_cast<size_t>(total));
+    for (int64_t f = 0; f < total; ++f) {
+        int64_t off = 0, rem = f;
+        for (int j = int(dims.size()) - 1; j >= 0; --j) {
+            off += (rem % dims[size_t(j)].extent) * dims[size_t(j)].stride;
+            rem /= dims[size_t(j)].extent;
+        }
+        tab[size_t(f)] = int32_t(off);
+    }
+    return tab;
+}
+
+void fill_pack_dims(PackArgs* pa, const std::vector<tn::GatherDim>& kd, const std::vector<tn::GatherDim>& cd) {
+    pa->nk = int32_t(kd.size());
+    pa->nc = int32_t(cd.size());
+    for (int j = 0; j < pa->nk; ++j) {
+        pa->kext[j] = kd[size_t(j)].extent;
+        pa->kstr[j] = kd[size_t(j)].stride;
+    }
+    for (int j = 0; j < pa->nc; ++j) {
+        pa->cext[j] = cd[size_t(j)].extent;
+        pa->cstr[j] = cd[size_t(j)].stride;
+    }
+}
+
+void launch_pack(const PackArgs& pa, int elt, hipStream_t st) {
+    int64_t total = int64_t(pa.Cp) * pa.Kp;
+    uint32_t blocks = uint32_t(std::min<int64_t>((total + 255) / 256, 65535));
+    if (elt == 2)
+        hipLaunchKernelGGL(pack_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, pa);
+    else
+        hipLaunchKernelGGL(pack_kernel<float>, dim3(blocks), dim3(256), 0, st, pa);
+}
+
+// Contract pairs of parameter tensors at create time (tn::MergeOp) with the plain FMA kernel
+// (fp32 accumulate, one rounding to the storage type). `virt` receives one device buffer per merge;
+// `temps` receives scratch buffers the caller frees once the stream has drained.
+int materialise_merges(const tn::Plan& plan, const tn_linear_desc* desc, int elt, hipStream_t st,
+                       std::vector<void*>* virt, std::vector<void*>* temps) {
+    auto source = [&](int slot) -> const void* {
+        return slot < plan.n_caller_tensors ? desc->tensors[slot] : (*virt)[size_t(slot - plan.n_caller_tensors)];
+    };
+    for (const tn::MergeOp& m : plan.merges) {
+        void* out = nullptr;
+        if (hipMalloc(&out, size_t(m.R * m.C) * elt) != hipSuccess) return TN_ERR_ALLOC;
+        virt->push_back(out);
+        int Kp = round_up(int(m.K), 64), Cp = round_up(int(m.C), 64);
+        void* packed = nullptr;
+        if (hipMalloc(&packed, size_t(Kp) * Cp * elt) != hipSuccess) return TN_ERR_ALLOC;
+        temps->push_back(packed);
+        PackArgs pa;
+        memset(&pa, 0, sizeof(pa));
+        pa.src = source(m.q_slot);
+        pa.dst = packed;
+        pa.K = int32_t(m.K);
+        pa.Kp = Kp;
+        pa.C = int32_t(m.C);
+        pa.Cp = Cp;
+        fill_pack_dims(&pa, m.kq, m.cdims);
+        pa.trace_extent = 1;
+        launch_pack(pa, elt, st);
+        // tables: arow | acol | crow | ccol
+        std::vector<int32_t> tab = gather_table(m.rdims, m.R);
+        std::vector<int32_t> acol = gather_table(m.kp, m.K);
+        tab.insert(tab.end(), acol.begin(), acol.end());
+        for (int64_t r = 0; r < m.R; ++r) tab.push_back(int32_t(r * m.C));
+        for (int64_t c = 0; c < m.C; ++c) tab.push_back(int32_t(c));
+        int32_t* dtab = nullptr;
+        if (hipMalloc(reinterpret_cast<void**>(&dtab), tab.size() * sizeof(int32_t)) != hipSuccess) return TN_ERR_ALLOC;
+        temps->push_back(dtab);
+        if (hipMemcpyAsync(dtab, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            return TN_ERR_HIP;
+        StepArgs a;
+        a.A = source(m.p_slot);
+        a.B = packed;
+        a.Out = out;
+        a.arow = dtab;
+        a.acol = dtab + m.R;
+        a.crow = dtab + m.R + m.K;
+        a.ccol = dtab + m.R + m.K + m.R;
+        a.a_tok_stride = 0;
+        a.c_tok_stride = 0;
+        a.total_rows = uint32_t(m.R);
+        a.R = uint32_t(m.R);
+        a.K = int32_t(m.K);
+        a.Kp = Kp;
+        a.C = int32_t(m.C);
+        a.Cp = Cp;
+        dim3 grid(uint32_t((m.R + 63) / 64), uint32_t(Cp / 64));
+        if (elt == 2)
+            hipLaunchKernelGGL(step_scalar_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(step_scalar_kernel<float>, grid, dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    }
+    return TN_OK;
 }
 
 }  // namespace
@@ -561,6 +920,18 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     h->elt = desc->dtype == TN_DTYPE_BF16 ? 2 : 4;
     h->max_tokens = desc->max_tokens;
     h->steps.resize(h->plan.steps.size());
+    std::vector<void*> virt, temps;     // merged tensors and scratch: freed before create returns
+    auto release_temps = [&]() {
+        for (void* v : virt) (void)hipFree(v);
+        for (void* v : temps) (void)hipFree(v);
+    };
+    rc = materialise_merges(h->plan, desc, h->elt, st, &virt, &temps);
+    if (rc != TN_OK) {
+        (void)hipStreamSynchronize(st);
+        release_temps();
+        free_handle(h);
+        return rc;
+    }
     for (size_t i = 0; i < h->steps.size(); ++i) {
         DevStep& s = h->steps[i];
         s.plan = h->plan.steps[i];
@@ -575,16 +946,22 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         host_tab.insert(host_tab.end(), p.crow.begin(), p.crow.end());
         host_tab.insert(host_tab.end(), p.ccol.begin(), p.ccol.end());
         if (hipMalloc(reinterpret_cast<void**>(&s.tables), n_tab * sizeof(int32_t)) != hipSuccess) {
+            (void)hipStreamSynchronize(st);
+            release_temps();
             free_handle(h);
             return TN_ERR_ALLOC;
         }
         // pageable source: the copy is staged before the call returns, so host_tab may go away
         if (hipMemcpyAsync(s.tables, host_tab.data(), n_tab * sizeof(int32_t), hipMemcpyHostToDevice, st) !=
             hipSuccess) {
+            (void)hipStreamSynchronize(st);
+            release_temps();
             free_handle(h);
             return TN_ERR_HIP;
         }
         if (hipStreamSynchronize(st) != hipSuccess) {
+            (void)hipStreamSynchronize(st);
+            release_temps();
             free_handle(h);
             return TN_ERR_HIP;
         }
@@ -598,40 +975,40 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         // packed parameter tensor
         int64_t bytes = int64_t(s.Cp) * s.Kp * h->elt;
         if (hipMalloc(&s.packed, size_t(bytes)) != hipSuccess) {
+            (void)hipStreamSynchronize(st);
+            release_temps();
             free_handle(h);
             return TN_ERR_ALLOC;
         }
         h->packed_bytes += bytes;
         PackArgs pa;
         memset(&pa, 0, sizeof(pa));
-        pa.src = desc->tensors[p.slot];
+        pa.src = p.slot < h->plan.n_caller_tensors ? desc->tensors[p.slot]
+                                                    : virt[size_t(p.slot - h->plan.n_caller_tensors)];
         pa.dst = s.packed;
         pa.K = int32_t(p.K);
         pa.Kp = s.Kp;
         pa.C = int32_t(p.C);
         pa.Cp = s.Cp;
-        pa.nk = int32_t(p.kdims.size());
-        pa.nc = int32_t(p.cdims.size());
-        for (int j = 0; j < pa.nk; ++j) {
-            pa.kext[j] = p.kdims[size_t(j)].extent;
-            pa.kstr[j] = p.kdims[size_t(j)].stride;
-        }
-        for (int j = 0; j < pa.nc; ++j) {
-            pa.cext[j] = p.cdims[size_t(j)].extent;
-            pa.cstr[j] = p.cdims[size_t(j)].stride;
-        }
+        fill_pack_dims(&pa, p.kdims, p.cdims);
         pa.trace_extent = p.trace_extent;
         pa.trace_stride = p.trace_stride;
-        int64_t total = int64_t(s.Cp) * s.Kp;
-        uint32_t blocks = uint32_t(std::min<int64_t>((total + 255) / 256, 65535));
-        if (h->elt == 2)
-            hipLaunchKernelGGL(pack_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, pa);
-        else
-            hipLaunchKernelGGL(pack_kernel<float>, dim3(blocks), dim3(256), 0, st, pa);
+        launch_pack(pa, h->elt, st);
         if (hipGetLastError() != hipSuccess) {
+            (void)hipStreamSynchronize(st);
+            release_temps();
             free_handle(h);
             return TN_ERR_HIP;
         }
+    }
+    if (!virt.empty() || !temps.empty()) {
+        // the pack kernels read the merged tensors: wait for them before the buffers go away
+        if (hipStreamSynchronize(st) != hipSuccess) {
+            release_temps();
+            free_handle(h);
+            return TN_ERR_HIP;
+        }
+        release_temps();
     }
     // workspace: two ping-pong buffers, each chunk_tokens * max_intermediate elements
     int64_t per_token = h->plan.max_intermediate * h->elt;

@@ -59,8 +59,23 @@ struct Step {
     int64_t flops = 0;              // 2*R*K*C
 };
 
+// Create-time contraction of two parameter tensors into one (a "virtual" tensor):
+//   out[p_free..., q_free...] = sum_shared P[...] * Q[...]
+// taken when the result is no larger than the two tensors together, e.g. a TT boundary core whose
+// bond already has the full rank m*n of that core carries no compression and is absorbed into its
+// neighbour (Section 3.5: "fuse core contractions ... where possible").
+struct MergeOp {
+    int p_slot = -1, q_slot = -1;           // sources: caller slots, or n_caller + index of an earlier merge
+    std::vector<GatherDim> rdims;           // free indices of P: extent, stride in P
+    std::vector<GatherDim> kp, kq;          // shared indices: extent and stride in P / in Q
+    std::vector<GatherDim> cdims;           // free indices of Q: extent, stride in Q
+    int64_t R = 1, K = 1, C = 1;            // out is row-major [R, C]
+};
+
 struct Plan {
     int format = 0, dtype = 0;
+    int n_caller_tensors = 0;
+    std::vector<MergeOp> merges;
     int64_t M = 1, N = 1;
     int64_t params = 0;
     int64_t flops = 0;
@@ -147,6 +162,7 @@ inline int build_network(const tn_linear_desc* d, Plan* p) {
             }
         p->params += total;
         p->tensors.push_back(t);
+        p->n_caller_tensors = int(p->tensors.size());
         return TN_OK;
     };
 
@@ -472,13 +488,112 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
     return TN_OK;
 }
 
+// Merge pairs of parameter tensors whose contraction is no larger than the pair. Returns the
+// number of merges made. Only indices owned by exactly these two tensors are summed.
+inline int merge_pass(Plan* p) {
+    int made = 0;
+    for (;;) {
+        int best_a = -1, best_b = -1;
+        double best_ratio = 2.0;
+        int n = int(p->tensors.size());
+        for (int a = 0; a < n; ++a)
+            for (int b = 0; b < n; ++b) {
+                if (a == b) continue;
+                const NetTensor& P = p->tensors[size_t(a)];
+                const NetTensor& Q = p->tensors[size_t(b)];
+                if (P.trace_extent != 1 || Q.trace_extent != 1) continue;
+                std::vector<int> shared;
+                for (int i : P.idx)
+                    if (detail::contains(Q.idx, i)) shared.push_back(i);
+                if (shared.empty()) continue;
+                bool ok = true;
+                for (int i : shared) {
+                    if (detail::contains(p->x_idx, i) || detail::contains(p->y_idx, i)) ok = false;
+                    for (int c = 0; c < n && ok; ++c)
+                        if (c != a && c != b && detail::contains(p->tensors[size_t(c)].idx, i)) ok = false;
+                }
+                if (!ok) continue;
+                double merged = 1;
+                for (int i : P.idx)
+                    if (!detail::contains(shared, i)) merged *= double(p->extent[size_t(i)]);
+                for (int i : Q.idx)
+                    if (!detail::contains(shared, i)) merged *= double(p->extent[size_t(i)]);
+                double ratio = merged / double(P.n_elems + Q.n_elems);
+                // a < b keeps P's free indices (the earlier tensor's) outermost in the result
+                if (ratio <= 1.0 && a < b && ratio < best_ratio) {
+                    best_ratio = ratio;
+                    best_a = a;
+                    best_b = b;
+                }
+            }
+        if (best_a < 0) break;
+        const NetTensor P = p->tensors[size_t(best_a)];
+        const NetTensor Q = p->tensors[size_t(best_b)];
+        MergeOp m;
+        m.p_slot = P.slot;
+        m.q_slot = Q.slot;
+        NetTensor out;
+        out.slot = p->n_caller_tensors + int(p->merges.size());
+        for (size_t j = 0; j < P.idx.size(); ++j) {
+            int i = P.idx[j];
+            if (detail::contains(Q.idx, i)) {
+                m.kp.push_back({p->extent[size_t(i)], P.stride[j]});
+                int64_t qs = 0;
+                for (size_t l = 0; l < Q.idx.size(); ++l)
+                    if (Q.idx[l] == i) qs = Q.stride[l];
+                m.kq.push_back({p->extent[size_t(i)], qs});
+                m.K *= p->extent[size_t(i)];
+            } else {
+                m.rdims.push_back({p->extent[size_t(i)], P.stride[j]});
+                m.R *= p->extent[size_t(i)];
+                out.idx.push_back(i);
+            }
+        }
+        for (size_t j = 0; j < Q.idx.size(); ++j) {
+            int i = Q.idx[j];
+            if (detail::contains(P.idx, i)) continue;
+            m.cdims.push_back({p->extent[size_t(i)], Q.stride[j]});
+            m.C *= p->extent[size_t(i)];
+            out.idx.push_back(i);
+        }
+        if (int(m.rdims.size()) > kMaxGatherDims || int(m.cdims.size()) > kMaxGatherDims ||
+            int(m.kp.size()) > kMaxGatherDims || m.R * m.C > (int64_t(1) << 31) - 1 ||
+            P.n_elems > (int64_t(1) << 31) - 1 || Q.n_elems > (int64_t(1) << 31) - 1)
+            break;
+        out.n_elems = m.R * m.C;
+        out.stride.assign(out.idx.size(), 1);
+        int64_t s = 1;
+        for (int j = int(out.idx.size()) - 1; j >= 0; --j) {
+            out.stride[size_t(j)] = s;
+            s *= p->extent[size_t(out.idx[size_t(j)])];
+        }
+        p->merges.push_back(m);
+        // replace P by the merged tensor, drop Q
+        p->tensors[size_t(best_a)] = out;
+        p->tensors.erase(p->tensors.begin() + best_b);
+        ++made;
+    }
+    return made;
+}
+
 inline int make_plan(const tn_linear_desc* d, Plan* p) {
     int rc = build_network(d, p);
     if (rc != TN_OK) return rc;
     std::vector<int> order;
     rc = choose_order(*p, &order);
     if (rc != TN_OK) return rc;
-    return build_steps(p, order);
+    rc = build_steps(p, order);
+    if (rc != TN_OK) return rc;
+    if (!(d->flags & TN_FLAG_NO_MERGE)) {
+        Plan q = *p;
+        q.steps.clear();
+        if (merge_pass(&q) > 0) {
+            std::vector<int> qorder;
+            if (choose_order(q, &qorder) == TN_OK && build_steps(&q, qorder) == TN_OK && q.flops < p->flops)
+                *p = q;
+        }
+    }
+    return TN_OK;
 }
 
 }  // namespace tn

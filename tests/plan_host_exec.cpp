@@ -15,6 +15,32 @@ extern "C" int plan_host_forward(const tn_linear_desc* d, const double* const* t
     tn::Plan p;
     int rc = tn::make_plan(d, &p);
     if (rc != TN_OK) return rc;
+    // tensors merged at create time, in double
+    std::vector<std::vector<double>> virt;
+    auto source = [&](int slot) -> const double* {
+        return slot < p.n_caller_tensors ? tensors[slot] : virt[size_t(slot - p.n_caller_tensors)].data();
+    };
+    auto offset_of = [](int64_t flat, const std::vector<tn::GatherDim>& dims) {
+        int64_t off = 0;
+        for (int j = int(dims.size()) - 1; j >= 0; --j) {
+            off += (flat % dims[size_t(j)].extent) * dims[size_t(j)].stride;
+            flat /= dims[size_t(j)].extent;
+        }
+        return off;
+    };
+    for (const tn::MergeOp& m : p.merges) {
+        const double* P = source(m.p_slot);
+        const double* Q = source(m.q_slot);
+        std::vector<double> out(size_t(m.R * m.C), 0.0);
+        for (int64_t r = 0; r < m.R; ++r)
+            for (int64_t c = 0; c < m.C; ++c) {
+                double acc = 0;
+                for (int64_t k = 0; k < m.K; ++k)
+                    acc += P[offset_of(r, m.rdims) + offset_of(k, m.kp)] * Q[offset_of(c, m.cdims) + offset_of(k, m.kq)];
+                out[size_t(r * m.C + c)] = acc;
+            }
+        virt.push_back(std::move(out));
+    }
     std::vector<double> cur(x, x + tokens * p.N), nxt;
     for (size_t s = 0; s < p.steps.size(); ++s) {
         const tn::Step& st = p.steps[s];
@@ -32,7 +58,7 @@ extern "C" int plan_host_forward(const tn_linear_desc* d, const double* const* t
                     rem /= st.cdims[j].extent;
                 }
                 double v = 0;
-                for (int64_t a = 0; a < st.trace_extent; ++a) v += tensors[st.slot][off + a * st.trace_stride];
+                for (int64_t a = 0; a < st.trace_extent; ++a) v += source(st.slot)[off + a * st.trace_stride];
                 B[size_t(c * st.K + k)] = v;
             }
         nxt.assign(size_t(tokens * st.c_tok_stride), 0.0);
@@ -60,13 +86,13 @@ extern "C" int plan_host_forward(const tn_linear_desc* d, const double* const* t
     return 0;
 }
 
-// vectorisation hints of a step, for the tests: field 0 c_vec, 1 r_vec, 2 a_plain
+// vectorisation hints of a step, for the tests: field 0 c_vec, 1 r_vec, 2 a_plain, 3 merges in the plan
 extern "C" int plan_host_step_hint(const tn_linear_desc* d, int step, int field, int64_t* value) {
     tn::Plan p;
     int rc = tn::make_plan(d, &p);
     if (rc != TN_OK) return rc;
     if (step < 0 || step >= int(p.steps.size())) return TN_ERR_INVALID_ARG;
     const tn::Step& st = p.steps[size_t(step)];
-    *value = field == 0 ? st.c_vec : field == 1 ? st.r_vec : st.a_plain;
+    *value = field == 0 ? st.c_vec : field == 1 ? st.r_vec : field == 2 ? int64_t(st.a_plain) : int64_t(p.merges.size());
     return 0;
 }

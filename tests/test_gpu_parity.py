@@ -26,6 +26,8 @@ def _rand_layer(spec, seed):
 
 
 SMALL = [
+    (tn.TN_FORMAT_TT, (2, 3, 2, 2), (2, 2, 3, 2), (1, 4, 2, 4, 1)),      # end cores merge at create time
+    (tn.TN_FORMAT_TT, (8, 16, 8), (8, 10, 8), (1, 64, 64, 1)),           # both merges, MFMA-sized
     (tn.TN_FORMAT_TT, (4, 8, 8), (4, 8, 8), (1, 8, 8, 1)),
     (tn.TN_FORMAT_TT, (3, 4, 2), (2, 5, 3), (1, 3, 4, 1)),               # odd extents, K not multiple of 8
     (tn.TN_FORMAT_TT, (2, 3, 2, 2), (5, 2, 3, 2), (1, 2, 5, 3, 1)),      # first step gathers from x
@@ -80,10 +82,16 @@ def dense_w():
     return get
 
 
-@pytest.mark.parametrize("i", [1, 2, 3])
-def test_baseline_configs_decode_sizes(i, dense_w):
+# workload 1 is run both ways: with its end cores merged at create time (the default) and as
+# the four-core chain exactly as given
+CONFIG_RUNS = [(1, 0), (1, tn.TN_FLAG_NO_MERGE), (2, 0), (3, 0)]
+
+
+@pytest.mark.parametrize("i,flags", CONFIG_RUNS)
+def test_baseline_configs_decode_sizes(i, flags, dense_w):
     spec, ts, w = dense_w(i)
-    layer = make_layer(spec, ts, 64)
+    layer = make_layer(spec, ts, 64, flags=flags)
+    assert layer.query(tn.TN_QUERY_NUM_STEPS) == {(1, 0): 2, (1, 2): 4, (2, 0): 5, (3, 0): 4}[(i, flags)]
     for tokens in (1, 64):
         x = wl.make_x(spec, tokens, i)
         y = to_host(layer(to_dev(x, spec.dtype)))
@@ -93,15 +101,15 @@ def test_baseline_configs_decode_sizes(i, dense_w):
     layer.close()
 
 
-@pytest.mark.parametrize("i", [1, 2, 3])
-def test_baseline_configs_prefill_8192(i, dense_w):
+@pytest.mark.parametrize("i,flags", CONFIG_RUNS)
+def test_baseline_configs_prefill_8192(i, flags, dense_w):
     """Full size, in the launch configuration the benchmark times; the oracle checks a
     seeded sample of token rows in full (every output column of those rows)."""
     spec, ts, w = dense_w(i)
     tokens = 8192
     print(f"[gen] x for workload {i}", flush=True)
     x = wl.make_x(spec, tokens, i)
-    layer = make_layer(spec, ts, tokens)
+    layer = make_layer(spec, ts, tokens, flags=flags)
     xd = to_dev(x, spec.dtype)
     yd = layer(xd)
     torch.cuda.synchronize()
@@ -201,3 +209,23 @@ def test_stack_sample_matrices():
         y = run_layer(spec, ts, x)
         err = O.rel_max_err(y, O.forward(fmt, ts, x, n_out_modes=len(spec.out_modes)))
         assert err <= TOL["bf16"], (fmt, n_in, n_out, r, err)
+
+
+@pytest.mark.parametrize("variant", [1, 3, 4, 5, 6, 7])
+def test_wide_step_kernel_variants(variant):
+    """Every tile variant of the wide bf16 steps (tuning override) on shapes with ragged row
+    and column tiles, a K that is not a multiple of the K tile, and a gathered first step."""
+    cases = [
+        _spec(tn.TN_FORMAT_TT, "bf16", (8, 16, 8), (8, 10, 8), (1, 32, 24, 1)),
+        _spec(tn.TN_FORMAT_TT, "bf16", (2, 3, 2, 2), (5, 2, 3, 2), (1, 2, 5, 3, 1)),
+        _spec(tn.TN_FORMAT_TR, "bf16", (4, 6, 4), (6, 4, 8), (8, 16, 8, 8)),
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (200,), (136,), ()),
+        _spec(tn.TN_FORMAT_TUCKER, "bf16", (16, 24), (8, 40), (8, 16, 8, 16)),
+    ]
+    for n, spec in enumerate(cases):
+        ts = _rand_layer(spec, 300 + n)
+        for tokens in (3, 67, 300):
+            x = wl.round_to_dtype(np.random.default_rng(n + tokens).standard_normal((tokens, spec.N)), "bf16")
+            y = run_layer(spec, ts, x, flags=variant << 8)
+            err = O.rel_max_err(y, O.forward(spec.format, ts, x, n_out_modes=len(spec.out_modes)))
+            assert err <= TOL["bf16"], (variant, n, tokens, err)

@@ -32,8 +32,8 @@ def host_exec():
     return lib
 
 
-def _run(lib, fmt, out_modes, in_modes, ranks, tensors, x):
-    d, keep = _make_desc(fmt, tn.TN_DTYPE_F32, out_modes, in_modes, ranks, None, 1, 0, 0, None)
+def _run(lib, fmt, out_modes, in_modes, ranks, tensors, x, flags=0):
+    d, keep = _make_desc(fmt, tn.TN_DTYPE_F32, out_modes, in_modes, ranks, None, 1, 0, flags, None)
     ts = [np.ascontiguousarray(t, dtype=np.float64) for t in tensors]
     ptrs = (ctypes.c_void_p * len(ts))(*[t.ctypes.data for t in ts])
     x = np.ascontiguousarray(x, dtype=np.float64)
@@ -66,18 +66,23 @@ CASES = [
     (tn.TN_FORMAT_TUCKER, (4,), (2, 3, 2), (3, 2, 2, 2)),
     (tn.TN_FORMAT_DENSE, (9,), (11,), ()),
     (tn.TN_FORMAT_DENSE, (3, 3), (2, 5), ()),
+    # boundary bonds at full rank: the end cores are contracted into their neighbours at create time
+    (tn.TN_FORMAT_TT, (2, 3, 2, 2), (2, 2, 3, 2), (1, 4, 2, 4, 1)),
+    (tn.TN_FORMAT_TT, (2, 3, 2), (2, 2, 2), (1, 4, 4, 1)),
+    (tn.TN_FORMAT_TT, (2, 4, 2), (3, 4, 2), (1, 6, 5, 1)),
 ]
 
 
+@pytest.mark.parametrize("flags", [0, tn.TN_FLAG_NO_MERGE])
 @pytest.mark.parametrize("fmt,om,im,rk", CASES)
-def test_plan_executes_to_oracle(host_exec, fmt, om, im, rk):
+def test_plan_executes_to_oracle(host_exec, fmt, om, im, rk, flags):
     rng = np.random.default_rng(hash((fmt, om, im, rk)) % (2 ** 32))
     if fmt == tn.TN_FORMAT_DENSE:
         tensors = [rng.standard_normal((int(np.prod(om)), int(np.prod(im))))]
     else:
         tensors = _rand_tensors(rng, fmt, om, im, rk)
     x = rng.standard_normal((3, int(np.prod(im))))
-    y = _run(host_exec, fmt, om, im, rk, tensors, x)
+    y = _run(host_exec, fmt, om, im, rk, tensors, x, flags)
     ref = O.forward(fmt, tensors, x, n_out_modes=len(om))
     assert O.rel_max_err(y, ref) < 1e-12
 
@@ -90,9 +95,9 @@ def test_plan_small_baseline_config(host_exec):
     assert O.rel_max_err(y, O.forward(spec.format, tensors, x)) < 1e-12
 
 
-def _q(spec, what):
+def _q(spec, what, flags=tn.TN_FLAG_NO_MERGE):
     dt = tn.TN_DTYPE_BF16 if spec.dtype == "bf16" else tn.TN_DTYPE_F32
-    return tn.plan_query(spec.format, dt, spec.out_modes, spec.in_modes, spec.ranks, what)
+    return tn.plan_query(spec.format, dt, spec.out_modes, spec.in_modes, spec.ranks, what, flags=flags)
 
 
 def test_flop_totals_and_orders():
@@ -119,6 +124,33 @@ def test_flop_totals_and_orders():
     assert _q(spec, tn.TN_QUERY_NUM_STEPS) == 5
     assert [_q(spec, 100 + 10 * s + 4) for s in range(3)] == [4, 3, 0]
     assert tuple(_q(spec, 120 + f) for f in range(3)) == (1, 2304, 9216)
+
+
+def test_create_time_merging():
+    # TT q_proj: r_1 = m_1 n_1 = 64 and r_3 = m_4 n_4 = 64, so both end cores merge into their
+    # neighbours without adding parameters; two steps remain:
+    #   rows n_1 n_2 = 80, K = n_3 n_4 = 64, cols m_3 m_4 r_2 = 4096   (41 943 040 FLOP)
+    #   rows m_3 m_4 = 64, K = n_1 n_2 r_2 = 5120, cols m_1 m_2 = 128   (83 886 080 FLOP)
+    spec, _ = wl.baseline_spec(1)
+    assert _q(spec, tn.TN_QUERY_NUM_MERGES, 0) == 2
+    assert _q(spec, tn.TN_QUERY_NUM_STEPS, 0) == 2
+    assert _q(spec, tn.TN_QUERY_FLOPS_PER_TOKEN, 0) == 41943040 + 83886080
+    steps = [tuple(_q(spec, 100 + 10 * s + f, 0) for f in range(3)) for s in range(2)]
+    assert steps == [(80, 64, 4096), (64, 5120, 128)]
+    assert _q(spec, tn.TN_QUERY_PARAM_COUNT, 0) == spec.n_params
+    # nothing to merge where a merge would add parameters
+    for i in (0, 2, 3):
+        spec, _ = wl.baseline_spec(i)
+        assert _q(spec, tn.TN_QUERY_NUM_MERGES, 0) == 0
+        assert _q(spec, tn.TN_QUERY_FLOPS_PER_TOKEN, 0) == _q(spec, tn.TN_QUERY_FLOPS_PER_TOKEN)
+    # the flag keeps the chain as given
+    spec, _ = wl.baseline_spec(1)
+    assert _q(spec, tn.TN_QUERY_NUM_MERGES) == 0 and _q(spec, tn.TN_QUERY_NUM_STEPS) == 4
+    # rank above what the end cores can carry (96 > 8*8): merging shrinks the parameters
+    big = wl.stack_spec(wl.FORMAT_TT, 5120, 8192, 96)
+    assert _q(big, tn.TN_QUERY_NUM_MERGES, 0) == 2
+    small = wl.stack_spec(wl.FORMAT_TT, 5120, 8192, 32)
+    assert _q(small, tn.TN_QUERY_NUM_MERGES, 0) == 0
 
 
 def test_planned_flops_equal_brute_force_minimum():
@@ -154,14 +186,15 @@ def test_planned_flops_equal_brute_force_minimum():
                             (tn.TN_FORMAT_TT, (2, 3, 2, 2), (5, 2, 3, 2), (1, 2, 5, 3, 1)),
                             (tn.TN_FORMAT_TR, (2, 3, 2), (3, 2, 2), (3, 2, 4, 3))]:
         best = min(cost(o, ms, ns, rs, fmt == tn.TN_FORMAT_TR) for o in permutations(range(len(ms))))
-        assert tn.plan_query(fmt, 1, ms, ns, rs, tn.TN_QUERY_FLOPS_PER_TOKEN) == best
+        assert tn.plan_query(fmt, 1, ms, ns, rs, tn.TN_QUERY_FLOPS_PER_TOKEN, flags=tn.TN_FLAG_NO_MERGE) == best
 
 
 def test_vector_store_hints(host_exec):
     # TT q_proj: intermediate steps store runs of 64 contiguous bond entries, the last step
     # stores contiguous rows; every step after the first reads a plain matrix.
     spec, _ = wl.baseline_spec(1)
-    d, keep = _make_desc(spec.format, 1, spec.out_modes, spec.in_modes, spec.ranks, None, 1, 0, 0, None)
+    d, keep = _make_desc(spec.format, 1, spec.out_modes, spec.in_modes, spec.ranks, None, 1, 0,
+                         tn.TN_FLAG_NO_MERGE, None)
     v = ctypes.c_int64(0)
     hints = []
     for s in range(4):
