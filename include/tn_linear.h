@@ -94,8 +94,9 @@ typedef struct tn_linear_s* tn_linear_t;
  *  max_tokens         largest token count a single pass will be sized for (>= 1); larger
  *                     forward calls are processed in several passes.
  *  workspace_limit_bytes
- *                     upper bound for the handle's device workspace; 0 = library default,
- *                     which keeps a pass's intermediates about the size of the last-level cache.
+ *                     upper bound for the handle's device workspace; 0 = library default
+ *                     (16 GiB): a pass then covers as many tokens as fit, which keeps every
+ *                     launch large enough to fill the chip.
  *  flags              TN_FLAG_* bits.
  *  stream             hipStream_t on which create enqueues its repacking work.
  */

@@ -541,6 +541,7 @@ enum Variant : int {
     VAR_PIPE_128x128 = 5,     // 2 workgroups per CU, two LDS stages
     VAR_PIPE8_256x256 = 6,    // 8 waves (2 per SIMD), 1 workgroup per CU, two LDS stages
     VAR_PIPE8_256x256_S1 = 7, // same, one LDS stage
+    VAR_PIPE_256x128 = 8,     // 4 waves stacked along rows, 2 workgroups per CU, one LDS stage
 };
 
 struct DevStep {
@@ -571,7 +572,7 @@ struct tn_linear_s {
 
 namespace {
 
-constexpr int64_t kDefaultWorkspaceBytes = int64_t(192) << 20;
+constexpr int64_t kDefaultWorkspaceBytes = int64_t(16) << 30;
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
@@ -607,13 +608,18 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
         s->bn = 32;
     } else {
         int forced = (flags >> TN_FLAG_VARIANT_SHIFT) & 0xff;
-        s->variant = forced ? forced : VAR_MFMA_128x128;
+        // default: the tile width that wastes the fewest padded columns; 256 on a tie
+        int auto_variant = round_up(int(p.C), 128) < round_up(int(p.C), 256) ? VAR_PIPE_256x128 : VAR_PIPE_128x256;
+        s->variant = forced ? forced : auto_variant;
         switch (s->variant) {
+            case VAR_MFMA_128x128: s->bm = 128; s->bn = 128; break;
             case VAR_PIPE_128x256: s->bm = 128; s->bn = 256; break;
             case VAR_PIPE_256x256: s->bm = 256; s->bn = 256; break;
             case VAR_PIPE_128x128: s->bm = 128; s->bn = 128; break;
             case VAR_PIPE8_256x256: case VAR_PIPE8_256x256_S1: s->bm = 256; s->bn = 256; break;
-            default: s->variant = VAR_MFMA_128x128; s->bm = 128; s->bn = 128; break;
+            case VAR_PIPE_256x128: s->bm = 256; s->bn = 128; break;
+            default: s->variant = auto_variant; s->bm = auto_variant == VAR_PIPE_256x128 ? 256 : 128;
+                     s->bn = auto_variant == VAR_PIPE_256x128 ? 128 : 256; break;
         }
     }
     s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : 1;
@@ -705,6 +711,11 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
         }
         case VAR_PIPE8_256x256_S1: {
             int rc = launch_pipe<4, 2, 2, 4, 1, 1>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_PIPE_256x128: {
+            int rc = launch_pipe<4, 1, 2, 4, 1, 2>(s, a, rows, st);
             if (rc != TN_OK) return rc;
             break;
         }
