@@ -94,7 +94,12 @@ def main() -> int:
     flops_tok = layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
     n_steps = layer.query(tn.TN_QUERY_NUM_STEPS)
     chunk = layer.query(tn.TN_QUERY_CHUNK_TOKENS)
-    step_flops = [layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + 3) for s in range(n_steps)]
+    q = lambda s, f: layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + f)
+    step_flops = [q(s, 3) for s in range(n_steps)]
+    # algorithmic bytes of a step per token: read its [rows, K] input, write its [rows, cols]
+    # output (bf16), plus its packed parameter tensor once per launch
+    step_io_bytes = [2 * q(s, 0) * (q(s, 1) + q(s, 2)) for s in range(n_steps)]
+    step_param_bytes = [2 * q(s, 1) * q(s, 2) for s in range(n_steps)]
 
     for _ in range(args.warmup):
         layer.forward(x, out=y)
@@ -110,7 +115,8 @@ def main() -> int:
     ms_per_step = e0.elapsed_time(e1) / args.steps
     tokens_per_s = tokens * args.steps / wall
 
-    # per-kernel durations: the same steps again with an event pair around every launch
+    # per-kernel durations: the same steps again with a HIP event pair around every launch,
+    # recorded by the library on the stream the kernels run on
     layer.profile(True)
     for _ in range(args.steps):
         layer.forward(x, out=y)
@@ -119,11 +125,28 @@ def main() -> int:
     per_step = []
     for s in range(n_steps):
         ms, launches = layer.profile_read(s)
-        per_step.append({"step": s, "ms_per_forward": ms / args.steps, "launches_per_forward": launches // args.steps,
-                         "avg_launch_us": 1e3 * ms / max(1, launches),
-                         "tflops": step_flops[s] * tokens * args.steps / (ms * 1e-3) / 1e12 if ms > 0 else 0.0})
+        sec = ms * 1e-3
+        nbytes = (step_io_bytes[s] * tokens + step_param_bytes[s] * (launches // args.steps)) * args.steps
+        per_step.append({
+            "step": s, "rows_per_token": q(s, 0), "K": q(s, 1), "cols": q(s, 2), "kernel_variant": q(s, 5),
+            "ms_per_forward": ms / args.steps, "launches_per_forward": launches // args.steps,
+            "avg_launch_us": 1e3 * ms / max(1, launches),
+            "tflops": step_flops[s] * tokens * args.steps / sec / 1e12 if sec > 0 else 0.0,
+            "algorithmic_GBps": nbytes / sec / 1e9 if sec > 0 else 0.0,
+            "flop_per_byte": step_flops[s] / step_io_bytes[s]})
     dom = max(range(n_steps), key=lambda s: per_step[s]["ms_per_forward"])
-    dom_tflops = per_step[dom]["tflops"]
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if per_step[dom]["flop_per_byte"] >= ridge:
+        roof = {"bound": "mfma", "achieved": per_step[dom]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": per_step[dom]["algorithmic_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = (f"contraction step {dom}: rows {q(dom, 0)} x K {q(dom, 1)} x cols {q(dom, 2)} per token, "
+                      f"{per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge of {ridge:.0f}")
+    roof["avg_launch_us"] = per_step[dom]["avg_launch_us"]
+    roof["also_tflops"] = per_step[dom]["tflops"]
+    roof["also_GBps"] = per_step[dom]["algorithmic_GBps"]
 
     # 1-token decode latency of the same layer (back-to-back calls on one stream)
     x1 = x[:1].contiguous()
@@ -154,14 +177,12 @@ def main() -> int:
         "config": {"workload": f"{spec.name}: {wl.FORMAT_NAMES[spec.format]} in {spec.N}={'x'.join(map(str, spec.in_modes))} "
                                f"out {spec.M}={'x'.join(map(str, spec.out_modes))} ranks {list(spec.ranks)}, "
                                f"{tokens}-token prefill, bf16 storage, fp32 accumulate",
-                   "tokens": tokens, "chunk_tokens": chunk},
+                   "tokens": tokens, "chunk_tokens": chunk,
+                   "create_time_merges": layer.query(tn.TN_QUERY_NUM_MERGES)},
+        "flops_per_token": flops_tok,
         "tflops_factorised": flops_tok * tokens_per_s / 1e12,
         "gpu_ms_per_step_events": ms_per_step,
-        "roofline": {"bound": "mfma", "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": f"contraction step {dom} (scatter-GEMM, rows {layer.query(100 + 10 * dom)} x K "
-                               f"{layer.query(101 + 10 * dom)} x cols {layer.query(102 + 10 * dom)} per token)",
-                     "avg_launch_us": per_step[dom]["avg_launch_us"]},
+        "roofline": roof,
         "whole_chain_frac_of_mfma_peak": flops_tok * tokens_per_s / 1e12 / PEAK_BF16_TFLOPS,
         "per_step": per_step,
         "decode_1tok": {"us_per_token": decode_us, "tokens_per_s": 1e6 / decode_us,
