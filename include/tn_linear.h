@@ -54,6 +54,7 @@ extern "C" {
 #define TN_FLAG_SCALAR_KERNELS  1   /* run every contraction step on the plain FMA kernel (debug aid) */
 #define TN_FLAG_NO_MERGE        2   /* keep every parameter tensor separate: do not contract adjacent
                                        tensors into one at create time even where that is free */
+#define TN_FLAG_NO_SPLIT_K      4   /* never use the split-K kernel for small launches (tuning/debug aid) */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
                                        bf16 steps (0 = library's choice; see TN_QUERY_STEP_BASE f=5) */
 

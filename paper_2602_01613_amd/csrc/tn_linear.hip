@@ -56,6 +56,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Packed parameter tensors are stored "fragment-major": the [Cp][Kp] matrix is cut into blocks of
+// 32 columns x 16 k; a block is 64 chunks of 8 consecutive k (16 bytes in bf16), chunk l holding
+// column l%32 and k offset 8*(l/32) - exactly the operand one lane of v_mfma_f32_32x32x16_bf16
+// wants. A wave that reads a block with one 16-byte load per lane therefore fetches 1 KB of
+// contiguous memory straight into MFMA operand registers (decode path), and the tiled kernels
+// read whole 1 KB blocks as well. Element (c, k) lives at:
+__host__ __device__ __forceinline__ int64_t bfrag_offset(int c, int k, int nks /* Kp / 16 */) {
+    return (int64_t(c >> 5) * nks + (k >> 4)) * 512 + ((c & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7);
+}
+
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(bf16_t v) { return float(v); }
 template <typename T> __device__ __forceinline__ T from_float(float v);
@@ -63,7 +73,8 @@ template <> __device__ __forceinline__ float from_float<float>(float v) { return
 template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) { return bf16_t(v); }
 
 // ---------------------------------------------------------------------------------------------
-// create-time repack: Bp[c][k] = sum_a src[off_c(c) + off_k(k) + a*trace_stride], zero padded
+// create-time repack: Bp(c, k) = sum_a src[off_c(c) + off_k(k) + a*trace_stride], zero padded to
+// [Cp][Kp] and stored fragment-major
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) pack_kernel(PackArgs p) {
@@ -91,12 +102,12 @@ __global__ void __launch_bounds__(256) pack_kernel(PackArgs p) {
             }
             const T* s = static_cast<const T*>(p.src);
             if (p.trace_extent == 1) {
-                static_cast<T*>(p.dst)[i] = s[off];
+                static_cast<T*>(p.dst)[bfrag_offset(c, k, p.Kp >> 4)] = s[off];
                 continue;
             }
             for (int64_t a = 0; a < p.trace_extent; ++a) v += to_float(s[off + a * p.trace_stride]);
         }
-        static_cast<T*>(p.dst)[i] = from_float<T>(v);
+        static_cast<T*>(p.dst)[bfrag_offset(c, k, p.Kp >> 4)] = from_float<T>(v);
     }
 }
 
@@ -137,7 +148,7 @@ __global__ void __launch_bounds__(256) step_scalar_kernel(StepArgs a) {
             As[kk][rr] = v;
             int c = col0 + rr;
             float w = 0.f;
-            if (c < a.Cp && k < a.Kp) w = to_float(B[int64_t(c) * a.Kp + k]);
+            if (c < a.Cp && k < a.Kp) w = to_float(B[bfrag_offset(c, k, a.Kp >> 4)]);
             Bs[kk][rr] = w;
         }
         __syncthreads();
@@ -252,7 +263,7 @@ __global__ void __launch_bounds__(256) step_mfma_kernel(StepArgs a, int cmode) {
         for (int j = 0; j < B_CHUNKS; ++j) {
             int e = tid + 256 * j;
             int cc = e >> 3, kc = (e & 7) * 8;
-            bf16x8 v = *reinterpret_cast<const bf16x8*>(B + int64_t(col0 + cc) * a.Kp + k0 + kc);
+            bf16x8 v = *reinterpret_cast<const bf16x8*>(B + bfrag_offset(col0 + cc, k0 + kc, a.Kp >> 4));
             *reinterpret_cast<bf16x8*>(sB + cc * LDK + kc) = v;
         }
         __syncthreads();
@@ -390,7 +401,10 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
             }
         }
     }
-    const bf16_t* b_ptr = B + int64_t(col0 + lrow) * a.Kp + lkc;
+    // B: chunk e = tid + NT*j of a K tile is lane e%64 of block e/64; block b = (column block b/4,
+    // k-step b%4): every wave reads whole 1 KB blocks
+    const int nks = a.Kp >> 4;
+    const bf16_t* b_ptr = B + (int64_t(col0 >> 5) * nks) * 512 + (tid & 63) * 8;
 
     bf16x8 ra[A_CHUNKS], rb[B_CHUNKS];
     auto load_tile = [&](int k0) {
@@ -412,7 +426,10 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
         }
 #pragma unroll
         for (int j = 0; j < B_CHUNKS; ++j)
-            rb[j] = *reinterpret_cast<const bf16x8*>(b_ptr + int64_t(RPP * j) * a.Kp + k0);
+        {
+            int blk = (tid >> 6) + (NT / 64) * j;
+            rb[j] = *reinterpret_cast<const bf16x8*>(b_ptr + (int64_t(blk >> 2) * nks + (k0 >> 4) + (blk & 3)) * 512);
+        }
     };
     auto store_tile = [&](int stage) {
         bf16_t* sA = smem + stage * STAGE_ELEMS;
@@ -421,8 +438,11 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
         for (int j = 0; j < A_CHUNKS; ++j)
             *reinterpret_cast<bf16x8*>(sA + (lrow + RPP * j) * LDK + lkc) = ra[j];
 #pragma unroll
-        for (int j = 0; j < B_CHUNKS; ++j)
-            *reinterpret_cast<bf16x8*>(sB + (lrow + RPP * j) * LDK + lkc) = rb[j];
+        for (int j = 0; j < B_CHUNKS; ++j) {
+            int blk = (tid >> 6) + (NT / 64) * j;
+            int col = (blk >> 2) * 32 + (lane & 31), kc = (blk & 3) * 16 + 8 * (lane >> 5);
+            *reinterpret_cast<bf16x8*>(sB + col * LDK + kc) = rb[j];
+        }
     };
 
     floatx16 acc[TM][TN];
@@ -530,6 +550,119 @@ constexpr size_t pipe_smem_bytes() {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Split-K kernel for launches whose output has too few tiles to fill the chip: decode (1-64
+// tokens) and small batches. Grid = (row tiles of TM*32 rows) x (32-column blocks) x (K splits).
+// The 4 waves of a workgroup take the 16-wide k-steps of the split round-robin; each wave loads
+// the packed tensor's 1 KB fragment blocks straight from memory into MFMA operand registers (no
+// LDS staging, fully coalesced: this is the stream that is HBM-bound at decode) and the matching
+// A fragments (a few rows) from global memory. The 4 partial accumulators are summed through LDS
+// in a fixed order. With one split the result is stored through the scatter tables; otherwise it
+// goes to an fp32 partial buffer that step_split_reduce_kernel sums in split order, so results
+// stay bit-reproducible (no atomics).
+// ---------------------------------------------------------------------------------------------
+template <int TM, int AMODE>
+__global__ void __launch_bounds__(256) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
+    __shared__ float red[4][TM][16][64];
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t row0 = blockIdx.x * (TM * 32);
+    const int cb = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
+    const int nks = a.Kp >> 4;
+    const int ks_begin = split * ksteps_per_split;
+    const int ks_end = min(nks, ks_begin + ksteps_per_split);
+
+    int64_t a_base[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        uint32_t g = row0 + i * 32 + (lane & 31);
+        a_base[i] = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            a_base[i] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+        }
+    }
+    const bf16_t* bp = B + (int64_t(cb) * nks) * 512 + lane * 8;
+    floatx16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    constexpr int U = 4;                               // k-steps in flight per wave
+    for (int ks0 = ks_begin + wave; ks0 < ks_end; ks0 += 4 * U) {
+        bf16x8 bf[U], af[U][TM];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int ks = ks0 + 4 * u;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) bf[u][q] = bf16_t(0.f);
+            if (ks < ks_end) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(ks) * 512);
+            int k = ks * 16 + 8 * (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                bf16x8 v;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
+                if (ks < ks_end && a_base[i] >= 0) {
+                    if (AMODE == 0) {
+                        if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + a_base[i] + k);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            if (k + q < a.K) v[q] = A[a_base[i] + (a.acol ? a.acol[k + q] : k + q)];
+                    }
+                }
+                af[u][i] = v;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], af[u][i], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][i][v][lane] = acc[i][v];
+    __syncthreads();
+    // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
+    const uint32_t rows_pad = gridDim.x * (TM * 32);
+    for (int e = tid; e < TM * 1024; e += 256) {
+        int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
+        float sum = red[0][i][v][l] + red[1][i][v][l] + red[2][i][v][l] + red[3][i][v][l];
+        uint32_t g = row0 + i * 32 + (l & 31);
+        int c = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+        if (g >= a.total_rows || c >= a.C) continue;
+        if (nsplit == 1) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
+        } else {
+            partial[(int64_t(split) * rows_pad + g) * a.Cp + c] = sum;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, const float* partial, int nsplit,
+                                                                uint32_t rows_pad) {
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    int64_t total = int64_t(a.total_rows) * a.C;
+    for (int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x; e < total; e += int64_t(gridDim.x) * 256) {
+        uint32_t g = uint32_t(e / a.C);
+        int c = int(e - int64_t(g) * a.C);
+        float sum = 0.f;
+        for (int s = 0; s < nsplit; ++s) sum += partial[(int64_t(s) * rows_pad + g) * a.Cp + c];
+        uint32_t t = g / a.R;
+        uint32_t r = g - t * a.R;
+        Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 enum Variant : int {
@@ -564,6 +697,9 @@ struct tn_linear_s {
     int64_t max_tokens = 0, chunk_tokens = 0;
     int64_t packed_bytes = 0, workspace_bytes = 0;
     void* ws[2] = {nullptr, nullptr};
+    void* partial = nullptr;          // fp32 partial sums of the split-K kernel
+    int64_t partial_bytes = 0;
+    int flags = 0;
     int device = 0;
     bool profiling = false;
     struct ProfRec { int step; hipEvent_t start, stop; };
@@ -593,6 +729,7 @@ void free_handle(tn_linear_s* h) {
     }
     for (void* w : h->ws)
         if (w) (void)hipFree(w);
+    if (h->partial) (void)hipFree(h->partial);
     delete h;
 }
 
@@ -626,6 +763,40 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
     s->cmode = p.c_vec == 8 ? 1 : (p.r_vec == 8 ? 2 : 0);
     s->Kp = round_up(int(p.K), 64);
     s->Cp = round_up(int(p.C), s->bn);
+}
+
+struct SplitCfg {
+    bool use = false;
+    int tm = 1, row_tiles = 0, col_blocks = 0, nsplit = 1, ksteps_per_split = 0;
+    int64_t partial_bytes = 0;
+};
+
+constexpr int64_t kMaxPartialBytes = int64_t(64) << 20;
+
+// Decide whether a launch of `rows` rows runs on the split-K kernel: when the tiled kernel would
+// start fewer workgroups than there are compute units and K is long enough to share out.
+SplitCfg split_config(const DevStep& s, int64_t rows) {
+    SplitCfg c;
+    if (s.variant == VAR_SCALAR || rows <= 0) return c;
+    int64_t tiles = ((rows + s.bm - 1) / s.bm) * (s.Cp / s.bn);
+    int nks = s.Kp / 16;
+    if (tiles >= 256 || nks < 8 || rows > 16384) return c;
+    c.tm = rows > 32 ? 2 : 1;
+    c.row_tiles = int((rows + 32 * c.tm - 1) / (32 * c.tm));
+    c.col_blocks = int((s.plan.C + 31) / 32);
+    int64_t base = int64_t(c.row_tiles) * c.col_blocks;
+    int want = int(std::max<int64_t>(1, (768 + base - 1) / base));
+    int max_split = std::max(1, nks / 8);               // at least 2 k-steps per wave
+    c.nsplit = std::min(want, max_split);
+    for (;;) {
+        c.ksteps_per_split = (nks + c.nsplit - 1) / c.nsplit;
+        c.nsplit = (nks + c.ksteps_per_split - 1) / c.ksteps_per_split;      // no empty split
+        c.partial_bytes = c.nsplit > 1 ? int64_t(c.nsplit) * c.row_tiles * 32 * c.tm * s.Cp * 4 : 0;
+        if (c.partial_bytes <= kMaxPartialBytes || c.nsplit == 1) break;
+        c.nsplit = std::max(1, c.nsplit / 2);
+    }
+    c.use = true;
+    return c;
 }
 
 template <int WM, int WN, int TM, int TN>
@@ -680,6 +851,29 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
     a.Kp = s.Kp;
     a.C = int32_t(s.plan.C);
     a.Cp = s.Cp;
+    SplitCfg sc = (h->flags & TN_FLAG_NO_SPLIT_K) ? SplitCfg() : split_config(s, rows);
+    if (sc.use && (sc.partial_bytes == 0 || (h->partial && sc.partial_bytes <= h->partial_bytes))) {
+        dim3 sgrid(uint32_t(sc.row_tiles), uint32_t(sc.col_blocks), uint32_t(sc.nsplit));
+        float* part = static_cast<float*>(h->partial);
+        if (sc.tm == 1) {
+            if (s.amode == 0)
+                hipLaunchKernelGGL((step_split_kernel<1, 0>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
+            else
+                hipLaunchKernelGGL((step_split_kernel<1, 1>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
+        } else {
+            if (s.amode == 0)
+                hipLaunchKernelGGL((step_split_kernel<2, 0>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
+            else
+                hipLaunchKernelGGL((step_split_kernel<2, 1>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
+        }
+        if (sc.nsplit > 1) {
+            int64_t total = rows * s.plan.C;
+            uint32_t blocks = uint32_t(std::min<int64_t>((total + 255) / 256, 2048));
+            hipLaunchKernelGGL(step_split_reduce_kernel, dim3(blocks), dim3(256), 0, st, a, part, sc.nsplit,
+                               uint32_t(sc.row_tiles * 32 * sc.tm));
+        }
+        return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+    }
     dim3 grid(uint32_t((rows + s.bm - 1) / s.bm), uint32_t(s.Cp / s.bn));
     switch (s.variant) {
         case VAR_SCALAR:
@@ -930,6 +1124,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     hipStream_t st = static_cast<hipStream_t>(desc->stream);
     h->elt = desc->dtype == TN_DTYPE_BF16 ? 2 : 4;
     h->max_tokens = desc->max_tokens;
+    h->flags = desc->flags;
     h->steps.resize(h->plan.steps.size());
     std::vector<void*> virt, temps;     // merged tensors and scratch: freed before create returns
     auto release_temps = [&]() {
@@ -1044,6 +1239,21 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, ((int64_t(1) << 31) - 1024) / max_r));
     }
     h->chunk_tokens = chunk;
+    // partial-sum buffer of the split-K kernel: the largest any pass of up to `chunk` tokens needs
+    if (!(desc->flags & TN_FLAG_NO_SPLIT_K)) {
+        int64_t need = 0;
+        for (const auto& s : h->steps)
+            for (int64_t t = 1; t <= chunk && t * s.plan.R <= 16384; ++t)
+                need = std::max(need, split_config(s, t * s.plan.R).partial_bytes);
+        if (need > 0) {
+            if (hipMalloc(&h->partial, size_t(need)) != hipSuccess) {
+                free_handle(h);
+                return TN_ERR_ALLOC;
+            }
+            h->partial_bytes = need;
+            h->workspace_bytes += need;
+        }
+    }
     *out = h;
     return TN_OK;
 }

@@ -156,14 +156,18 @@ def test_chunked_passes_match_single_pass(dense_w):
     y_big = layer(to_dev(x, "bf16"))
     torch.cuda.synchronize()
     layer.close()
-    assert torch.equal(y_small, y_big)
-    assert O.rel_max_err(to_host(y_small), O.apply_linear(w, x)) <= TOL["bf16"]
+    # pass size changes which kernel (tiled or split-K) and which split a launch gets, hence the
+    # summation order: the two agree to rounding, not bit for bit
+    ref = O.apply_linear(w, x)
+    assert O.rel_max_err(to_host(y_small), ref) <= TOL["bf16"]
+    assert O.rel_max_err(to_host(y_big), ref) <= TOL["bf16"]
+    assert O.rel_max_err(to_host(y_small), to_host(y_big)) <= 1e-2
     # more tokens than max_tokens: processed in several passes
     layer = make_layer(spec, ts, 10)
     y_cap = layer(to_dev(x, "bf16"))
     torch.cuda.synchronize()
     layer.close()
-    assert torch.equal(y_cap, y_big)
+    assert O.rel_max_err(to_host(y_cap), ref) <= TOL["bf16"]
 
 
 def test_linearity_on_gpu(dense_w):
@@ -230,3 +234,28 @@ def test_wide_step_kernel_variants(variant):
             y = run_layer(spec, ts, x, flags=variant << 8)
             err = O.rel_max_err(y, O.forward(spec.format, ts, x, n_out_modes=len(spec.out_modes)))
             assert err <= TOL["bf16"], (variant, n, tokens, err)
+
+
+@pytest.mark.parametrize("tokens", [1, 3, 33, 64, 100])
+def test_split_k_small_launches(tokens):
+    """Launches too small to fill the chip run on the split-K kernel (decode regime): long-K
+    dense, Tucker and merged-TT shapes, odd extents, gathered first step; checked against the
+    oracle and against the tiled kernels."""
+    cases = [
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (200,), (1000,), ()),
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (1024,), (2048,), ()),
+        _spec(tn.TN_FORMAT_TUCKER, "bf16", (40, 48), (32, 40), (24, 32, 16, 24)),
+        _spec(tn.TN_FORMAT_TT, "bf16", (8, 16, 8), (8, 10, 8), (1, 64, 64, 1)),
+        _spec(tn.TN_FORMAT_TT, "bf16", (4, 6, 5), (6, 20, 4), (1, 8, 16, 1)),
+        _spec(tn.TN_FORMAT_TR, "bf16", (4, 6, 4), (6, 4, 8), (8, 16, 8, 8)),
+    ]
+    for n, spec in enumerate(cases):
+        ts = _rand_layer(spec, 500 + n)
+        x = wl.round_to_dtype(np.random.default_rng(n + tokens).standard_normal((tokens, spec.N)), "bf16")
+        ref = O.forward(spec.format, ts, x, n_out_modes=len(spec.out_modes))
+        y = run_layer(spec, ts, x)
+        y_tiled = run_layer(spec, ts, x, flags=tn.TN_FLAG_NO_SPLIT_K)
+        assert O.rel_max_err(y, ref) <= TOL["bf16"], (n, tokens)
+        assert O.rel_max_err(y_tiled, ref) <= TOL["bf16"], (n, tokens)
+        # a second run of the split path gives the same bits (fixed-order reduction, no atomics)
+        assert np.array_equal(y, run_layer(spec, ts, x))
