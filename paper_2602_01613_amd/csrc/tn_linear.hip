@@ -780,7 +780,7 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     if (s.variant == VAR_SCALAR || rows <= 0) return c;
     int64_t tiles = ((rows + s.bm - 1) / s.bm) * (s.Cp / s.bn);
     int nks = s.Kp / 16;
-    if (tiles >= 256 || nks < 8 || rows > 16384) return c;
+    if (tiles >= 256 || nks < 8) return c;
     c.tm = rows > 32 ? 2 : 1;
     c.row_tiles = int((rows + 32 * c.tm - 1) / (32 * c.tm));
     c.col_blocks = int((s.plan.C + 31) / 32);
@@ -1243,8 +1243,11 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     if (!(desc->flags & TN_FLAG_NO_SPLIT_K)) {
         int64_t need = 0;
         for (const auto& s : h->steps)
-            for (int64_t t = 1; t <= chunk && t * s.plan.R <= 16384; ++t)
-                need = std::max(need, split_config(s, t * s.plan.R).partial_bytes);
+            for (int64_t t = 1; t <= chunk; ++t) {
+                SplitCfg c = split_config(s, t * s.plan.R);
+                if (!c.use) break;          // larger passes only add tiles
+                need = std::max(need, c.partial_bytes);
+            }
         if (need > 0) {
             if (hipMalloc(&h->partial, size_t(need)) != hipSuccess) {
                 free_handle(h);
