@@ -550,6 +550,133 @@ constexpr size_t pipe_smem_bytes() {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Short-K kernel (K <= 64): steps such as the first contraction of a chain read little and write
+// a lot, so they are bound by the store stream. A workgroup owns 128 rows and walks over all
+// columns, 128 at a time. The A fragments of its rows (the whole K) stay in registers for the whole
+// walk; the packed tensor's fragment blocks are loaded from memory straight into MFMA operand
+// registers (double-buffered across column iterations); each wave turns its 64x64 result into
+// row-contiguous 16-byte pieces through a private LDS patch and stores it. No workgroup barrier
+// is used anywhere, so the stores of one wave overlap the loads and MFMAs of the others.
+// Requires Kp == 64, aligned runs of 8 columns in the output (CMODE 1) and Cp % 128 == 0.
+// ---------------------------------------------------------------------------------------------
+template <int AMODE>
+__global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
+    constexpr int LDP = 64 + 8;                          // padded row of the wave's LDS patch
+    __shared__ __attribute__((aligned(16))) bf16_t patch[4][64 * LDP];
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const uint32_t row0 = blockIdx.x * 128 + wm * 64;
+    bf16_t* sP = patch[wave];
+
+    // A fragments for the wave's 64 rows and all 4 k-steps
+    bf16x8 af[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        uint32_t g = row0 + i * 32 + (lane & 31);
+        int64_t base = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            base = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 v;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
+            int k = ks * 16 + 8 * (lane >> 5);
+            if (base >= 0) {
+                if (AMODE == 0) {
+                    if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + base + k);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (k + q < a.K) v[q] = A[base + (a.acol ? a.acol[k + q] : k + q)];
+                }
+            }
+            af[i][ks] = v;
+        }
+    }
+    // output row bases of the 8 rows this lane stores per iteration: row p*8 + lane/8
+    int64_t obase[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        uint32_t g = row0 + p * 8 + (lane >> 3);
+        obase[p] = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            obase[p] = int64_t(t) * a.c_tok_stride + a.crow[r];
+        }
+    }
+    const int ncol_iters = a.Cp >> 7;
+    const bf16_t* bp = B + lane * 8;                     // Kp == 64: 4 k-step blocks per column block
+    auto load_b = [&](int it, bf16x8 (&bf)[2][4]) {
+        int cb = it * 4 + wn * 2;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                bf[j][ks] = *reinterpret_cast<const bf16x8*>(bp + (int64_t(cb + j) * 4 + ks) * 512);
+    };
+    // column iterations are dealt round-robin over gridDim.y workgroups (1 when there are enough
+    // row tiles to fill the chip)
+    const int it_step = gridDim.y;
+    bf16x8 bcur[2][4], bnext[2][4];
+    if (int(blockIdx.y) < ncol_iters) load_b(blockIdx.y, bcur);
+    for (int it = blockIdx.y; it < ncol_iters; it += it_step) {
+        if (it + it_step < ncol_iters) load_b(it + it_step, bnext);
+        floatx16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bcur[j][ks], af[i][ks], acc[i][j], 0, 0, 0);
+        // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
+                    *reinterpret_cast<bf16x4*>(sP + (i * 32 + (lane & 31)) * LDP + j * 32 + 8 * q + 4 * (lane >> 5)) = pk;
+                }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int c = it * 128 + wn * 64 + (lane & 7) * 8;
+        if (c < a.C) {
+            const int32_t coff = a.ccol[c];
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                bf16x8 v = *reinterpret_cast<const bf16x8*>(sP + (p * 8 + (lane >> 3)) * LDP + (lane & 7) * 8);
+                if (obase[p] >= 0) *reinterpret_cast<bf16x8*>(Out + obase[p] + coff) = v;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bcur[j][ks] = bnext[j][ks];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Split-K kernel for launches whose output has too few tiles to fill the chip: decode (1-64
 // tokens) and small batches. Grid = (row tiles of TM*32 rows) x (32-column blocks) x (K splits).
 // The 4 waves of a workgroup take the 16-wide k-steps of the split round-robin; each wave loads
@@ -675,6 +802,7 @@ enum Variant : int {
     VAR_PIPE8_256x256 = 6,    // 8 waves (2 per SIMD), 1 workgroup per CU, two LDS stages
     VAR_PIPE8_256x256_S1 = 7, // same, one LDS stage
     VAR_PIPE_256x128 = 8,     // 4 waves stacked along rows, 2 workgroups per CU, one LDS stage
+    VAR_SHORTK = 9,           // K <= 64, store-bound: registers-only operands, barrier-free
 };
 
 struct DevStep {
@@ -745,18 +873,20 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
         s->bn = 32;
     } else {
         int forced = (flags >> TN_FLAG_VARIANT_SHIFT) & 0xff;
-        // default: the tile width that wastes the fewest padded columns; 256 on a tie
-        int auto_variant = round_up(int(p.C), 128) < round_up(int(p.C), 256) ? VAR_PIPE_256x128 : VAR_PIPE_128x256;
-        s->variant = forced ? forced : auto_variant;
-        switch (s->variant) {
-            case VAR_MFMA_128x128: s->bm = 128; s->bn = 128; break;
+        // default: the tile width that wastes the fewest padded columns (256 on a tie); the
+        // register-only kernel for short-K, wide steps
+        const bool shortk_ok = p.K <= 64 && p.c_vec == 8;
+        int v = round_up(int(p.C), 128) < round_up(int(p.C), 256) ? VAR_PIPE_256x128 : VAR_PIPE_128x256;
+        if (shortk_ok && p.C >= 256) v = VAR_SHORTK;
+        if (forced >= VAR_MFMA_128x128 && forced <= VAR_SHORTK && forced != VAR_MFMA_256x32 &&
+            (forced != VAR_SHORTK || shortk_ok))
+            v = forced;
+        s->variant = v;
+        switch (v) {
+            case VAR_MFMA_128x128: case VAR_PIPE_128x128: case VAR_SHORTK: s->bm = 128; s->bn = 128; break;
             case VAR_PIPE_128x256: s->bm = 128; s->bn = 256; break;
-            case VAR_PIPE_256x256: s->bm = 256; s->bn = 256; break;
-            case VAR_PIPE_128x128: s->bm = 128; s->bn = 128; break;
-            case VAR_PIPE8_256x256: case VAR_PIPE8_256x256_S1: s->bm = 256; s->bn = 256; break;
             case VAR_PIPE_256x128: s->bm = 256; s->bn = 128; break;
-            default: s->variant = auto_variant; s->bm = auto_variant == VAR_PIPE_256x128 ? 256 : 128;
-                     s->bn = auto_variant == VAR_PIPE_256x128 ? 128 : 256; break;
+            default: s->bm = 256; s->bn = 256; break;      // the 256x256 variants
         }
     }
     s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : 1;
@@ -906,6 +1036,17 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
         case VAR_PIPE8_256x256_S1: {
             int rc = launch_pipe<4, 2, 2, 4, 1, 1>(s, a, rows, st);
             if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_SHORTK: {
+            int64_t row_tiles = (rows + 127) / 128;
+            int col_iters = s.Cp / 128;
+            int groups = int(std::min<int64_t>(col_iters, std::max<int64_t>(1, 1024 / row_tiles)));
+            dim3 g{uint32_t(row_tiles), uint32_t(groups)};
+            if (s.amode == 0)
+                hipLaunchKernelGGL(step_shortk_kernel<0>, g, dim3(256), 0, st, a);
+            else
+                hipLaunchKernelGGL(step_shortk_kernel<1>, g, dim3(256), 0, st, a);
             break;
         }
         case VAR_PIPE_256x128: {

@@ -402,10 +402,27 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
         for (int i : T.idx)
             if (!contains(layout, i)) cset.push_back(i);
         if (kset.empty()) return TN_ERR_INVALID_ARG;
-        // plain when the contracted indices are the innermost of the layout
+        if (s == 0 && n > 1) {
+            // x arrives in a fixed layout, but the order in which the first step walks its rows is
+            // free: put the indices the next step contracts innermost (and later-contracted ones
+            // outermost) so that the rows of one tile store next to each other; A is then gathered
+            // through the tables, which is cheap because x is small
+            const NetTensor& Tn = p->tensors[order[1]];
+            std::vector<int> outer, inner;
+            for (int i : rows) (contains(Tn.idx, i) ? inner : outer).push_back(i);
+            std::stable_sort(outer.begin(), outer.end(), [&](int a, int b) {
+                if (when[a] != when[b]) return when[a] > when[b];
+                return a < b;
+            });
+            rows = outer;
+            rows.insert(rows.end(), inner.begin(), inner.end());
+        }
+        // plain when the layout is exactly [rows..., contracted indices...]
         bool plain = true;
         for (size_t j = 0; j < kset.size(); ++j)
             if (layout[layout.size() - kset.size() + j] != kset[j]) plain = false;
+        for (size_t j = 0; j < rows.size() && plain; ++j)
+            if (layout[j] != rows[j]) plain = false;
         st.a_plain = plain;
         st.R = detail::prod_extents(rows, ext);
         st.K = detail::prod_extents(kset, ext);
