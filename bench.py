@@ -148,18 +148,40 @@ def main() -> int:
     roof["also_tflops"] = per_step[dom]["tflops"]
     roof["also_GBps"] = per_step[dom]["algorithmic_GBps"]
 
-    # 1-token decode latency of the same layer (back-to-back calls on one stream)
-    x1 = x[:1].contiguous()
-    y1 = torch.empty((1, spec.M), dtype=torch.bfloat16, device="cuda")
-    for _ in range(20):
-        layer.forward(x1, out=y1)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    reps = 200
-    for _ in range(reps):
-        layer.forward(x1, out=y1)
-    torch.cuda.synchronize()
-    decode_us = (time.perf_counter() - t0) / reps * 1e6
+    # decode: 1-token (and 64-token) latency of the same layer, back-to-back calls on one stream,
+    # then the per-kernel durations of the same calls from the library's HIP events
+    def decode_stats(t):
+        xt = x[:t].contiguous()
+        yt = torch.empty((t, spec.M), dtype=torch.bfloat16, device="cuda")
+        for _ in range(20):
+            layer.forward(xt, out=yt)
+        torch.cuda.synchronize()
+        reps = 200
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            layer.forward(xt, out=yt)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / reps * 1e6
+        layer.profile(True)
+        for _ in range(50):
+            layer.forward(xt, out=yt)
+        torch.cuda.synchronize()
+        layer.profile(False)
+        steps = []
+        for s in range(n_steps):
+            ms, launches = layer.profile_read(s)
+            k_us = 1e3 * ms / max(1, launches)
+            nbytes = step_io_bytes[s] * t + step_param_bytes[s]
+            steps.append({"step": s, "kernel_us": k_us, "GBps": nbytes / k_us / 1e3,
+                          "param_GBps": step_param_bytes[s] / k_us / 1e3,
+                          "tflops": step_flops[s] * t / k_us / 1e6})
+        return {"tokens": t, "us_per_call": us, "tokens_per_s": t * 1e6 / us,
+                "tflops": flops_tok * t / us / 1e6,
+                "sum_kernel_us": sum(p["kernel_us"] for p in steps), "per_step": steps}
+
+    dec1 = decode_stats(1)
+    dec64 = decode_stats(64)
+    decode_us = dec1["us_per_call"]
 
     result = {
         "metric": METRIC,
@@ -185,9 +207,9 @@ def main() -> int:
         "roofline": roof,
         "whole_chain_frac_of_mfma_peak": flops_tok * tokens_per_s / 1e12 / PEAK_BF16_TFLOPS,
         "per_step": per_step,
-        "decode_1tok": {"us_per_token": decode_us, "tokens_per_s": 1e6 / decode_us,
-                        "tflops": flops_tok / decode_us / 1e6,
-                        "param_GBps": layer.query(tn.TN_QUERY_PACKED_BYTES) / decode_us / 1e3},
+        "decode_1tok": dict(dec1, us_per_token=decode_us,
+                            param_GBps=layer.query(tn.TN_QUERY_PACKED_BYTES) / decode_us / 1e3),
+        "decode_64tok": dec64,
         "paper_context": "paper reports ~40 -> ~50 -> ~75 tokens/s end-to-end decode on Qwen3-32B, 8K context, "
                          "1x A100 80GB (whole model with healing and speculative decoding; not this kernel)",
     }

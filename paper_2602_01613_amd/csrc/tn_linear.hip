@@ -353,11 +353,14 @@ __global__ void __launch_bounds__(256) step_mfma_kernel(StepArgs a, int cmode) {
 //     columns of one row and the epilogue writes 8-byte pieces to LDS;
 //   * tiles are numbered so that the column tiles of one row tile run back to back on the same
 //     XCD (workgroup i goes to XCD i % 8): the second read of an A tile hits that XCD's L2;
-//   * per-row output offsets are computed once per tile and kept in LDS.
+//   * per-row output offsets are computed once per tile and kept in LDS;
+//   * TRANS = 1 serves outputs whose contiguous direction is along rows (CMODE 2): the operands
+//     are not swapped, a lane holds 4 consecutive rows of one column, and the tile is staged in LDS
+//     column-major so that the stores again move 16 contiguous bytes per lane.
 // ---------------------------------------------------------------------------------------------
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-template <int WM, int WN, int TM, int TN, int AMODE, int STAGES, int MINB>
+template <int WM, int WN, int TM, int TN, int AMODE, int STAGES, int MINB, int TRANS>
 __global__ void __launch_bounds__(WM * WN * 64, MINB)
 step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
@@ -473,17 +476,22 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = TRANS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0)
+                                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
         if (STAGES == 1) __syncthreads();
         if (kt + 1 < nk) store_tile((STAGES == 2) ? (cur ^ 1) : 0);
         __syncthreads();
     }
 
-    // ---- epilogue. With the operands swapped: lane l, register v of a tile holds
-    //      row = l%32, col = 8*(v/4) + 4*(l/32) + v%4.
+    // ---- epilogue. Operands swapped (TRANS = 0): lane l, register v of a tile holds
+    //      row = l%32, col = 8*(v/4) + 4*(l/32) + v%4; staged row-major [BM][LDC].
+    //      Not swapped (TRANS = 1): col = l%32, row = 8*(v/4) + 4*(l/32) + v%4; staged
+    //      column-major [BN][LDR].
+    constexpr int LDR = BM + 8;
+    constexpr size_t C_ELEMS = size_t(BM) * LDC > size_t(BN) * LDR ? size_t(BM) * LDC : size_t(BN) * LDR;
     bf16_t* sC = smem;
-    int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + size_t(BM) * LDC * sizeof(bf16_t));
+    int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + C_ELEMS * sizeof(bf16_t));
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -493,9 +501,15 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
                 bf16x4 pk;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
-                int rr = (wm * TM + i) * 32 + (lane & 31);
-                int cc = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
-                *reinterpret_cast<bf16x4*>(sC + rr * LDC + cc) = pk;
+                if (TRANS) {
+                    int cc = (wn * TN + j) * 32 + (lane & 31);
+                    int rr = (wm * TM + i) * 32 + 8 * q + 4 * (lane >> 5);
+                    *reinterpret_cast<bf16x4*>(sC + cc * LDR + rr) = pk;
+                } else {
+                    int rr = (wm * TM + i) * 32 + (lane & 31);
+                    int cc = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
+                    *reinterpret_cast<bf16x4*>(sC + rr * LDC + cc) = pk;
+                }
             }
     for (int rr = tid; rr < BM; rr += NT) {
         uint32_t g = row0 + rr;
@@ -510,7 +524,17 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
     __syncthreads();
 
     constexpr int GROUPS = BM * BN / 8;
-    if (cmode == 1) {
+    if (TRANS) {
+        // rows come in aligned contiguous runs of 8: thread -> (group of 8 rows, column), rows fastest
+#pragma unroll 4
+        for (int e = tid; e < GROUPS; e += NT) {
+            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
+            int c = col0 + cc;
+            int64_t base = sBase[rg];
+            if (base < 0 || c >= a.C) continue;
+            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + cc * LDR + rg);
+        }
+    } else if (cmode == 1) {
 #pragma unroll 4
         for (int e = tid; e < GROUPS; e += NT) {
             int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
@@ -518,17 +542,6 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
             int64_t base = sBase[rr];
             if (base < 0 || c >= a.C) continue;
             *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
-        }
-    } else if (cmode == 2) {
-        for (int e = tid; e < GROUPS; e += NT) {
-            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
-            int c = col0 + cc;
-            int64_t base = sBase[rg];
-            if (base < 0 || c >= a.C) continue;
-            bf16x8 v;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = sC[(rg + q) * LDC + cc];
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = v;
         }
     } else {
         for (int e = tid; e < BM * BN; e += NT) {
@@ -545,7 +558,8 @@ template <int WM, int WN, int TM, int TN, int STAGES>
 constexpr size_t pipe_smem_bytes() {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t stage = size_t(BM + BN) * (64 + 8) * 2 * STAGES;
-    constexpr size_t epi = size_t(BM) * (BN + 8) * 2 + size_t(BM) * 8;
+    constexpr size_t c_elems = size_t(BM) * (BN + 8) > size_t(BN) * (BM + 8) ? size_t(BM) * (BN + 8) : size_t(BN) * (BM + 8);
+    constexpr size_t epi = c_elems * 2 + size_t(BM) * 8;
     return stage > epi ? stage : epi;
 }
 
@@ -679,17 +693,20 @@ __global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
 // ---------------------------------------------------------------------------------------------
 // Split-K kernel for launches whose output has too few tiles to fill the chip: decode (1-64
 // tokens) and small batches. Grid = (row tiles of TM*32 rows) x (32-column blocks) x (K splits).
-// The 4 waves of a workgroup take the 16-wide k-steps of the split round-robin; each wave loads
+// The NW waves of a workgroup (4, 8 or 16: more waves keep more of the weight stream in flight)
+// take the 16-wide k-steps of the split round-robin; each wave loads
 // the packed tensor's 1 KB fragment blocks straight from memory into MFMA operand registers (no
 // LDS staging, fully coalesced: this is the stream that is HBM-bound at decode) and the matching
-// A fragments (a few rows) from global memory. The 4 partial accumulators are summed through LDS
+// A fragments (a few rows) from global memory. The per-wave accumulators are summed through LDS
 // in a fixed order. With one split the result is stored through the scatter tables; otherwise it
 // goes to an fp32 partial buffer that step_split_reduce_kernel sums in split order, so results
-// stay bit-reproducible (no atomics).
+// stay bit-reproducible (no atomics). A single-pass variant in which the last workgroup to arrive
+// at a tile does the sum was measured 8x slower: a device-scope fence on this chip writes back the
+// L2 of the workgroup's XCD.
 // ---------------------------------------------------------------------------------------------
-template <int TM, int AMODE>
-__global__ void __launch_bounds__(256) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
-    __shared__ float red[4][TM][16][64];
+template <int TM, int AMODE, int NW>
+__global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
+    __shared__ float red[NW][TM][16][64];
     const bf16_t* A = static_cast<const bf16_t*>(a.A);
     const bf16_t* B = static_cast<const bf16_t*>(a.B);
     bf16_t* Out = static_cast<bf16_t*>(a.Out);
@@ -719,11 +736,11 @@ __global__ void __launch_bounds__(256) step_split_kernel(StepArgs a, float* part
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
     constexpr int U = 4;                               // k-steps in flight per wave
-    for (int ks0 = ks_begin + wave; ks0 < ks_end; ks0 += 4 * U) {
+    for (int ks0 = ks_begin + wave; ks0 < ks_end; ks0 += NW * U) {
         bf16x8 bf[U], af[U][TM];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int ks = ks0 + 4 * u;
+            int ks = ks0 + NW * u;
 #pragma unroll
             for (int q = 0; q < 8; ++q) bf[u][q] = bf16_t(0.f);
             if (ks < ks_end) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(ks) * 512);
@@ -758,9 +775,12 @@ __global__ void __launch_bounds__(256) step_split_kernel(StepArgs a, float* part
     __syncthreads();
     // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
     const uint32_t rows_pad = gridDim.x * (TM * 32);
-    for (int e = tid; e < TM * 1024; e += 256) {
+    const float* rw = &red[0][0][0][0];
+    for (int e = tid; e < TM * 1024; e += NW * 64) {
         int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
-        float sum = red[0][i][v][l] + red[1][i][v][l] + red[2][i][v][l] + red[3][i][v][l];
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += rw[w * TM * 1024 + e];
         uint32_t g = row0 + i * 32 + (l & 31);
         int c = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
         if (g >= a.total_rows || c >= a.C) continue;
@@ -774,6 +794,7 @@ __global__ void __launch_bounds__(256) step_split_kernel(StepArgs a, float* part
     }
 }
 
+// Sums the partial results of the split-K kernel in split order and stores through the tables.
 __global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, const float* partial, int nsplit,
                                                                 uint32_t rows_pad) {
     bf16_t* Out = static_cast<bf16_t*>(a.Out);
@@ -897,7 +918,7 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
 
 struct SplitCfg {
     bool use = false;
-    int tm = 1, row_tiles = 0, col_blocks = 0, nsplit = 1, ksteps_per_split = 0;
+    int tm = 1, nw = 4, row_tiles = 0, col_blocks = 0, nsplit = 1, ksteps_per_split = 0;
     int64_t partial_bytes = 0;
 };
 
@@ -915,8 +936,12 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     c.row_tiles = int((rows + 32 * c.tm - 1) / (32 * c.tm));
     c.col_blocks = int((s.plan.C + 31) / 32);
     int64_t base = int64_t(c.row_tiles) * c.col_blocks;
-    int want = int(std::max<int64_t>(1, (768 + base - 1) / base));
-    int max_split = std::max(1, nks / 8);               // at least 2 k-steps per wave
+    // long K: wide workgroups (16 waves for up to 32 rows, 8 for up to 64), so that one split per
+    // tile is enough to keep the weight stream busy and no reduction pass is needed
+    c.nw = nks >= 64 ? (c.tm == 1 ? 16 : 8) : 4;
+    int64_t target_wgs = 3072 / c.nw;
+    int want = int(std::max<int64_t>(1, target_wgs / base));
+    int max_split = std::max(1, nks / (2 * c.nw));      // at least 2 k-steps per wave
     c.nsplit = std::min(want, max_split);
     for (;;) {
         c.ksteps_per_split = (nks + c.nsplit - 1) / c.nsplit;
@@ -944,21 +969,20 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
     int nrow = int((rows + BM - 1) / BM), ncol = s.Cp / BN;
     int nrow_pad = (nrow + 7) / 8 * 8;
     dim3 grid(uint32_t(nrow_pad) * uint32_t(ncol));
-    auto k0 = step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB>;
-    auto k1 = step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB>;
+    using kern_t = void (*)(StepArgs, int, int, int);
+    static const kern_t kerns[4] = {
+        step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 0>, step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 0>,
+        step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 1>, step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 1>};
     static bool configured = false;   // per instantiation
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                int(smem)) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                int(smem)) != hipSuccess)
-            return TN_ERR_HIP;
+        for (kern_t k : kerns)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(smem)) != hipSuccess)
+                return TN_ERR_HIP;
         configured = true;
     }
-    if (s.amode == 0)
-        hipLaunchKernelGGL(k0, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
-    else
-        hipLaunchKernelGGL(k1, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
+    kern_t k = kerns[(s.cmode == 2 ? 2 : 0) + (s.amode == 0 ? 0 : 1)];
+    hipLaunchKernelGGL(k, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
     return TN_OK;
 }
 
@@ -985,17 +1009,15 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
     if (sc.use && (sc.partial_bytes == 0 || (h->partial && sc.partial_bytes <= h->partial_bytes))) {
         dim3 sgrid(uint32_t(sc.row_tiles), uint32_t(sc.col_blocks), uint32_t(sc.nsplit));
         float* part = static_cast<float*>(h->partial);
-        if (sc.tm == 1) {
-            if (s.amode == 0)
-                hipLaunchKernelGGL((step_split_kernel<1, 0>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
-            else
-                hipLaunchKernelGGL((step_split_kernel<1, 1>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
-        } else {
-            if (s.amode == 0)
-                hipLaunchKernelGGL((step_split_kernel<2, 0>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
-            else
-                hipLaunchKernelGGL((step_split_kernel<2, 1>), sgrid, dim3(256), 0, st, a, part, sc.ksteps_per_split);
-        }
+        using split_t = void (*)(StepArgs, float*, int);
+        split_t k;
+        if (sc.tm == 1)
+            k = sc.nw == 16 ? (s.amode == 0 ? step_split_kernel<1, 0, 16> : step_split_kernel<1, 1, 16>)
+                            : (s.amode == 0 ? step_split_kernel<1, 0, 4> : step_split_kernel<1, 1, 4>);
+        else
+            k = sc.nw == 8 ? (s.amode == 0 ? step_split_kernel<2, 0, 8> : step_split_kernel<2, 1, 8>)
+                           : (s.amode == 0 ? step_split_kernel<2, 0, 4> : step_split_kernel<2, 1, 4>);
+        hipLaunchKernelGGL(k, sgrid, dim3(uint32_t(sc.nw * 64)), 0, st, a, part, sc.ksteps_per_split);
         if (sc.nsplit > 1) {
             int64_t total = rows * s.plan.C;
             uint32_t blocks = uint32_t(std::min<int64_t>((total + 255) / 256, 2048));
