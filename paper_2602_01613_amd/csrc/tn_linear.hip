@@ -554,6 +554,240 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Direct-to-LDS bf16 MFMA step kernel (the fastest tiled kernel; needs a plain A with K % 32 == 0).
+//   * K tiles of 32 travel from global memory straight into LDS with global_load_lds_dwordx4
+//     (16 bytes per lane, no staging registers, no LDS write instructions) into a ring of NS
+//     stages; a wave waits on its own loads with s_waitcnt vmcnt(n) and a workgroup barrier makes
+//     the other waves' loads visible;
+//   * tile kt+1 is known to have landed before tile kt is multiplied, and the MFMA operand
+//     fragments are double-buffered in registers, so the LDS reads of the next k-step are in
+//     flight while the current MFMAs run, across the barrier as well;
+//   * an LDS tile row is 64 bytes (4 chunks of 16 B); chunk c of row r sits at chunk position
+//     c ^ ((r >> 2) & 3), which makes the fragment reads of 16 consecutive rows conflict-free. The
+//     swizzle costs nothing: each lane simply fetches the global chunk that belongs at its LDS slot.
+// Tile numbering (XCD-aware), epilogue (CMODE 1, TRANS, scalar) and tables are those of the kernel
+// above. Rows past the end are clamped to the last row when loading and masked when storing.
+// ---------------------------------------------------------------------------------------------
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
+    constexpr int imm = (N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14);
+    __builtin_amdgcn_s_waitcnt(imm);
+}
+
+template <int WM, int WN, int TM, int TN, int NS, int MINB, int TRANS>
+__global__ void __launch_bounds__(WM * WN * 64, MINB)
+step_mfma_dlds_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
+    constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 32;
+    constexpr int ROWB = BK * 2;                       // bytes per LDS tile row
+    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    constexpr int A_PER_WAVE = BM / 16 / NWAVE, B_PER_WAVE = BN / 16 / NWAVE;   // 1 KB loads per wave and stage
+    constexpr int L = A_PER_WAVE + B_PER_WAVE;
+    constexpr int LDC = BN + 8, LDR = BM + 8;
+    static_assert((BM / 16) % NWAVE == 0 && (BN / 16) % NWAVE == 0, "16-row blocks per wave");
+    static_assert(NS >= 3 && NS <= 4 && 2 * L <= 63, "ring depth / vmcnt range");
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int row_tile = (slot / ncol_tiles) * 8 + xcd;
+    const int col_tile = slot % ncol_tiles;
+    if (row_tile >= nrow_tiles) return;
+    const uint32_t row0 = uint32_t(row_tile) * BM;
+    const int col0 = col_tile * BN;
+
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int nks = a.Kp >> 4;
+
+    // per-lane sources: lane l of a 1 KB load fills LDS row l/4, chunk position l%4 of its block
+    const int lr = lane >> 2, lpc = lane & 3;
+    const bf16_t* a_src[A_PER_WAVE];
+    const bf16_t* b_src[B_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < A_PER_WAVE; ++j) {
+        int r = (j * NWAVE + wave) * 16 + lr;
+        int c = lpc ^ ((r >> 2) & 3);
+        uint32_t g = row0 + r;
+        if (g >= a.total_rows) g = a.total_rows - 1;
+        a_src[j] = A + int64_t(g) * a.K + c * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < B_PER_WAVE; ++j) {
+        int r = (j * NWAVE + wave) * 16 + lr;              // column within the tile
+        int c = lpc ^ ((r >> 2) & 3);                       // logical chunk: k = kt*32 + c*8
+        int col = col0 + r;
+        // fragment-major: block (col/32, k/16), chunk (col%32) + 32*((k/8)%2)
+        b_src[j] = B + (int64_t(col >> 5) * nks + (c >> 1)) * 512 + ((col & 31) + 32 * (c & 1)) * 8;
+    }
+    auto issue = [&](int kt, int stage) {
+        unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < A_PER_WAVE; ++j)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)(a_src[j] + kt * BK),
+                (void __attribute__((address_space(3)))*)(sbase + (j * NWAVE + wave) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_PER_WAVE; ++j)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)(b_src[j] + int64_t(kt) * 2 * 512),
+                (void __attribute__((address_space(3)))*)(sbase + A_BYTES + (j * NWAVE + wave) * 1024), 16, 0, 0);
+    };
+    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform
+        if (n <= 0) wait_vmcnt<0>();
+        else if (n == 1) wait_vmcnt<L>();
+        else wait_vmcnt<2 * L>();
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // fragment read offsets: lane reads row lane%32, logical chunk ks*2 + lane/32
+    int a_off[TM][2], b_off[TN][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            int r = (wm * TM + i) * 32 + (lane & 31);
+            a_off[i][ks] = r * ROWB + (((ks * 2 + (lane >> 5)) ^ ((r >> 2) & 3)) * 16);
+        }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            int r = (wn * TN + j) * 32 + (lane & 31);
+            b_off[j][ks] = A_BYTES + r * ROWB + (((ks * 2 + (lane >> 5)) ^ ((r >> 2) & 3)) * 16);
+        }
+
+    const int nk = a.Kp / BK;                            // K % 32 == 0, so tiles past K are all padding
+    const int nk_real = a.K / BK;                        // only these hold data; B is zero beyond
+    int issued = 0;
+    for (; issued < NS - 1 && issued < nk_real; ++issued) issue(issued, issued);
+    wait_outstanding_tiles(min(issued - 1, NS - 2));     // tile 0 has landed
+    __syncthreads();
+    bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(dyn_smem + a_off[i][0]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(dyn_smem + b_off[j][0]);
+    (void)nk;
+
+    for (int kt = 0; kt < nk_real; ++kt) {
+        if (kt + 1 < nk_real) wait_outstanding_tiles(issued - (kt + 2));   // tile kt+1 has landed
+        __syncthreads();       // everyone is done with tile kt-1: its stage may be refilled
+        if (issued < nk_real) {
+            issue(issued, issued % NS);
+            ++issued;
+        }
+        const unsigned char* scur = dyn_smem + (kt % NS) * STAGE_BYTES;
+        const unsigned char* snxt = dyn_smem + ((kt + 1) % NS) * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int cb = ks & 1, nb = cb ^ 1;
+            if (ks == 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[nb][i] = *reinterpret_cast<const bf16x8*>(scur + a_off[i][1]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bfr[nb][j] = *reinterpret_cast<const bf16x8*>(scur + b_off[j][1]);
+            } else if (kt + 1 < nk_real) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[nb][i] = *reinterpret_cast<const bf16x8*>(snxt + a_off[i][0]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bfr[nb][j] = *reinterpret_cast<const bf16x8*>(snxt + b_off[j][0]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = TRANS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0)
+                                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][j], af[cb][i], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+
+    // ---- epilogue (see step_mfma_pipe_kernel)
+    constexpr size_t C_ELEMS = size_t(BM) * LDC > size_t(BN) * LDR ? size_t(BM) * LDC : size_t(BN) * LDR;
+    bf16_t* sC = reinterpret_cast<bf16_t*>(dyn_smem);
+    int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + C_ELEMS * sizeof(bf16_t));
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4 pk;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
+                if (TRANS) {
+                    int cc = (wn * TN + j) * 32 + (lane & 31);
+                    int rr = (wm * TM + i) * 32 + 8 * q + 4 * (lane >> 5);
+                    *reinterpret_cast<bf16x4*>(sC + cc * LDR + rr) = pk;
+                } else {
+                    int rr = (wm * TM + i) * 32 + (lane & 31);
+                    int cc = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
+                    *reinterpret_cast<bf16x4*>(sC + rr * LDC + cc) = pk;
+                }
+            }
+    for (int rr = tid; rr < BM; rr += NT) {
+        uint32_t g = row0 + rr;
+        int64_t base = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            base = int64_t(t) * a.c_tok_stride + a.crow[r];
+        }
+        sBase[rr] = base;
+    }
+    __syncthreads();
+    constexpr int GROUPS = BM * BN / 8;
+    if (TRANS) {
+#pragma unroll 4
+        for (int e = tid; e < GROUPS; e += NT) {
+            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
+            int c = col0 + cc;
+            int64_t base = sBase[rg];
+            if (base < 0 || c >= a.C) continue;
+            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + cc * LDR + rg);
+        }
+    } else if (cmode == 1) {
+#pragma unroll 4
+        for (int e = tid; e < GROUPS; e += NT) {
+            int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
+            int c = col0 + cg;
+            int64_t base = sBase[rr];
+            if (base < 0 || c >= a.C) continue;
+            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
+        }
+    } else {
+        for (int e = tid; e < BM * BN; e += NT) {
+            int rr = e / BN, cc = e % BN;
+            int c = col0 + cc;
+            int64_t base = sBase[rr];
+            if (base < 0 || c >= a.C) continue;
+            Out[base + a.ccol[c]] = sC[rr * LDC + cc];
+        }
+    }
+}
+
+template <int WM, int WN, int TM, int TN, int NS>
+constexpr size_t dlds_smem_bytes() {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t stage = size_t(BM + BN) * 64 * NS;
+    constexpr size_t c_elems = size_t(BM) * (BN + 8) > size_t(BN) * (BM + 8) ? size_t(BM) * (BN + 8) : size_t(BN) * (BM + 8);
+    constexpr size_t epi = c_elems * 2 + size_t(BM) * 8;
+    return stage > epi ? stage : epi;
+}
+
 template <int WM, int WN, int TM, int TN, int STAGES>
 constexpr size_t pipe_smem_bytes() {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -824,6 +1058,9 @@ enum Variant : int {
     VAR_PIPE8_256x256_S1 = 7, // same, one LDS stage
     VAR_PIPE_256x128 = 8,     // 4 waves stacked along rows, 2 workgroups per CU, one LDS stage
     VAR_SHORTK = 9,           // K <= 64, store-bound: registers-only operands, barrier-free
+    VAR_DLDS_128x256 = 10,    // direct-to-LDS, 4 waves, 3 stages, 2 workgroups per CU
+    VAR_DLDS_256x128 = 11,    // same, 4 waves stacked along rows
+    VAR_DLDS8_256x256 = 12,   // direct-to-LDS, 8 waves, 4 stages, 1 workgroup per CU (long K)
 };
 
 struct DevStep {
@@ -898,15 +1135,20 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
         // register-only kernel for short-K, wide steps
         const bool shortk_ok = p.K <= 64 && p.c_vec == 8;
         int v = round_up(int(p.C), 128) < round_up(int(p.C), 256) ? VAR_PIPE_256x128 : VAR_PIPE_128x256;
+        // direct-to-LDS tiles where A is a plain matrix whose K is a whole number of 32-wide tiles
+        const bool dlds_ok = p.a_plain && p.K % 32 == 0 && p.K >= 64;
+        // (measured: the 8-wave 256x256 ring beats the register-prefetch tiles on every shape it
+        // fits without extra column padding; the 4-wave direct-to-LDS tiles do not)
+        if (dlds_ok && p.C >= 256 && round_up(int(p.C), 256) == round_up(int(p.C), 128)) v = VAR_DLDS8_256x256;
         if (shortk_ok && p.C >= 256) v = VAR_SHORTK;
-        if (forced >= VAR_MFMA_128x128 && forced <= VAR_SHORTK && forced != VAR_MFMA_256x32 &&
-            (forced != VAR_SHORTK || shortk_ok))
+        if (forced >= VAR_MFMA_128x128 && forced <= VAR_DLDS8_256x256 && forced != VAR_MFMA_256x32 &&
+            (forced != VAR_SHORTK || shortk_ok) && (forced < VAR_DLDS_128x256 || dlds_ok))
             v = forced;
         s->variant = v;
         switch (v) {
             case VAR_MFMA_128x128: case VAR_PIPE_128x128: case VAR_SHORTK: s->bm = 128; s->bn = 128; break;
-            case VAR_PIPE_128x256: s->bm = 128; s->bn = 256; break;
-            case VAR_PIPE_256x128: s->bm = 256; s->bn = 128; break;
+            case VAR_PIPE_128x256: case VAR_DLDS_128x256: s->bm = 128; s->bn = 256; break;
+            case VAR_PIPE_256x128: case VAR_DLDS_256x128: s->bm = 256; s->bn = 128; break;
             default: s->bm = 256; s->bn = 256; break;      // the 256x256 variants
         }
     }
@@ -931,7 +1173,8 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     if (s.variant == VAR_SCALAR || rows <= 0) return c;
     int64_t tiles = ((rows + s.bm - 1) / s.bm) * (s.Cp / s.bn);
     int nks = s.Kp / 16;
-    if (tiles >= 256 || nks < 8) return c;
+    // the narrow tile keeps 4 waves of a CU busy at best: it needs twice as many tiles to fill the chip
+    if (tiles >= (s.variant == VAR_MFMA_256x32 ? 512 : 128) || nks < 8) return c;
     c.tm = rows > 32 ? 2 : 1;
     c.row_tiles = int((rows + 32 * c.tm - 1) / (32 * c.tm));
     c.col_blocks = int((s.plan.C + 31) / 32);
@@ -983,6 +1226,28 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
     }
     kern_t k = kerns[(s.cmode == 2 ? 2 : 0) + (s.amode == 0 ? 0 : 1)];
     hipLaunchKernelGGL(k, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
+    return TN_OK;
+}
+
+template <int WM, int WN, int TM, int TN, int NS, int MINB>
+int launch_dlds(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t st) {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t smem = dlds_smem_bytes<WM, WN, TM, TN, NS>();
+    int nrow = int((rows + BM - 1) / BM), ncol = s.Cp / BN;
+    int nrow_pad = (nrow + 7) / 8 * 8;
+    dim3 grid(uint32_t(nrow_pad) * uint32_t(ncol));
+    using kern_t = void (*)(StepArgs, int, int, int);
+    static const kern_t kerns[2] = {step_mfma_dlds_kernel<WM, WN, TM, TN, NS, MINB, 0>,
+                                    step_mfma_dlds_kernel<WM, WN, TM, TN, NS, MINB, 1>};
+    static bool configured = false;   // per instantiation
+    if (!configured) {
+        for (kern_t k : kerns)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(smem)) != hipSuccess)
+                return TN_ERR_HIP;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kerns[s.cmode == 2 ? 1 : 0], grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
     return TN_OK;
 }
 
@@ -1057,6 +1322,21 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
         }
         case VAR_PIPE8_256x256_S1: {
             int rc = launch_pipe<4, 2, 2, 4, 1, 1>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_DLDS_128x256: {
+            int rc = launch_dlds<2, 2, 2, 4, 3, 2>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_DLDS_256x128: {
+            int rc = launch_dlds<4, 1, 2, 4, 3, 2>(s, a, rows, st);
+            if (rc != TN_OK) return rc;
+            break;
+        }
+        case VAR_DLDS8_256x256: {
+            int rc = launch_dlds<4, 2, 2, 4, 4, 1>(s, a, rows, st);
             if (rc != TN_OK) return rc;
             break;
         }

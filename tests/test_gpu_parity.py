@@ -216,7 +216,7 @@ def test_stack_sample_matrices():
         assert err <= TOL["bf16"], (fmt, n_in, n_out, r, err)
 
 
-@pytest.mark.parametrize("variant", [1, 3, 4, 5, 6, 7, 8, 9])
+@pytest.mark.parametrize("variant", [1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
 def test_wide_step_kernel_variants(variant):
     """Every tile variant of the wide bf16 steps (tuning override) on shapes with ragged row
     and column tiles, a K that is not a multiple of the K tile, and a gathered first step."""
@@ -226,12 +226,16 @@ def test_wide_step_kernel_variants(variant):
         _spec(tn.TN_FORMAT_TR, "bf16", (4, 6, 4), (6, 4, 8), (8, 16, 8, 8)),
         _spec(tn.TN_FORMAT_DENSE, "bf16", (200,), (136,), ()),
         _spec(tn.TN_FORMAT_TUCKER, "bf16", (16, 24), (8, 40), (8, 16, 8, 16)),
+        _spec(tn.TN_FORMAT_TT, "bf16", (8, 16, 8), (8, 12, 8), (1, 32, 16, 1)),     # K = 96, 128, 384: 32-wide tiles
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (328,), (1056,), ()),
     ]
     for n, spec in enumerate(cases):
         ts = _rand_layer(spec, 300 + n)
         for tokens in (3, 67, 300):
             x = wl.round_to_dtype(np.random.default_rng(n + tokens).standard_normal((tokens, spec.N)), "bf16")
-            y = run_layer(spec, ts, x, flags=variant << 8)
+            # the tiled kernels themselves: no split-K, no create-time merging
+            flags = (variant << 8) | tn.TN_FLAG_NO_SPLIT_K | tn.TN_FLAG_NO_MERGE
+            y = run_layer(spec, ts, x, flags=flags)
             err = O.rel_max_err(y, O.forward(spec.format, ts, x, n_out_modes=len(spec.out_modes)))
             assert err <= TOL["bf16"], (variant, n, tokens, err)
 
