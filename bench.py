@@ -52,13 +52,131 @@ def cpu_baseline(spec, tensors, sample_tokens):
     }
 
 
+def run_stack(args) -> int:
+    """The mixed 64-layer projection stack: 448 layers (format and rank drawn per matrix) run
+    back to back on one stream, sharing one workspace block; 1-token decode and a prefill pass.
+    Weights are drawn on the GPU from a seeded generator (there are 60 GB of them)."""
+    import torch
+    import workloads as wl
+    import paper_2602_01613_amd as tn
+
+    torch.cuda.set_device(0)
+    specs = wl.qwen3_32b_stack(args.layers)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.SEED_BASE + 4)
+    ws = torch.empty(args.stack_workspace_gb << 30, dtype=torch.uint8, device="cuda")
+    tokens = args.tokens
+
+    def draw(spec):
+        shapes = spec.tensor_shapes()
+        if spec.format == wl.FORMAT_DENSE:
+            return [(torch.randn(shapes[0], generator=gen, device="cuda") / spec.N ** 0.5).to(torch.bfloat16)]
+        if spec.format in (wl.FORMAT_TT, wl.FORMAT_TR):
+            return [(torch.randn(shp, generator=gen, device="cuda") / (shp[0] * shp[2]) ** 0.5).to(torch.bfloat16)
+                    for shp in shapes]
+        p = len(spec.out_modes)
+        core = torch.randn(shapes[0], generator=gen, device="cuda")
+        flat = core.reshape(int(torch.tensor(shapes[0][:p]).prod()), -1)
+        core = (flat / flat.norm(dim=1, keepdim=True)).reshape(shapes[0])
+        out = [core.to(torch.bfloat16)]
+        for shp in shapes[1:]:
+            q, r = torch.linalg.qr(torch.randn(shp, generator=gen, device="cuda"))
+            out.append((q * torch.sign(torch.diagonal(r))[None, :]).to(torch.bfloat16).contiguous())
+        return out
+
+    t0 = time.perf_counter()
+    layers, flops, params, packed = [], [], [], []
+    for spec in specs:
+        ts = draw(spec)
+        layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, ts,
+                            tokens, flags=(2 if args.no_merge else 0), workspace=ws)
+        layers.append(layer)
+        flops.append(layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN))
+        params.append(spec.n_params)
+        packed.append(layer.query(tn.TN_QUERY_PACKED_BYTES))
+        del ts
+    torch.cuda.synchronize()
+    create_s = time.perf_counter() - t0
+    xs = {n: torch.randn((tokens, n), generator=gen, device="cuda").to(torch.bfloat16) for n in {s.N for s in specs}}
+    ys = {m: torch.empty((tokens, m), dtype=torch.bfloat16, device="cuda") for m in {s.M for s in specs}}
+    stream = torch.cuda.current_stream()
+
+    def one_pass(t, timed_events=False):
+        evs = []
+        for spec, layer in zip(specs, layers):
+            if timed_events:
+                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+            layer.forward(xs[spec.N][:t], out=ys[spec.M][:t])
+            if timed_events:
+                e1.record(stream)
+                evs.append((e0, e1))
+        return evs
+
+    def timed(t, reps):
+        # reps == 0: one pass only, timed as it runs (the prefill pass of the full stack takes
+        # minutes; the decode passes before it have already loaded the kernels)
+        wall = None
+        if reps > 0:
+            one_pass(t)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                one_pass(t)
+            torch.cuda.synchronize()
+            wall = (time.perf_counter() - t0) / reps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        evs = one_pass(t, timed_events=True)
+        torch.cuda.synchronize()
+        if wall is None:
+            wall = time.perf_counter() - t0
+        by_fmt = {}
+        for spec, (e0, e1) in zip(specs, evs):
+            k = wl.FORMAT_NAMES[spec.format]
+            by_fmt[k] = by_fmt.get(k, 0.0) + e0.elapsed_time(e1)
+        return wall, by_fmt
+
+    dec_wall, dec_fmt = timed(1, args.steps)
+    pre_wall, pre_fmt = timed(tokens, 0)
+    counts = {}
+    for spec in specs:
+        k = f"{wl.FORMAT_NAMES[spec.format]}"
+        counts[k] = counts.get(k, 0) + 1
+    total_flops = sum(flops)
+    result = {
+        "metric": METRIC, "value": tokens / pre_wall, "unit": "tokens/s", "n_gpus": 1, "steps": 1, "warmup": 0,
+        "ms_per_step": 1e3 * pre_wall, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"mixed-format projection stack, {len(specs)} matrices ({args.layers} layers x 7), "
+                               f"formats {counts}, ranks drawn from {{32,64,96}}, {tokens}-token prefill pass; one "
+                               f"token passes through every matrix once (a projection stack, not a transformer)",
+                   "tokens": tokens, "matrices": len(specs)},
+        "flops_per_token_all_matrices": total_flops,
+        "tflops_factorised": total_flops * tokens / pre_wall / 1e12,
+        "prefill_ms_by_format": pre_fmt,
+        "decode_1tok": {"ms_per_token_all_matrices": 1e3 * dec_wall, "tokens_per_s": 1.0 / dec_wall,
+                        "ms_by_format": dec_fmt, "packed_GB": sum(packed) / 1e9,
+                        "packed_GBps": sum(packed) / dec_wall / 1e9},
+        "parameters": sum(params), "create_seconds": create_s,
+        "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(result))
+    for layer in layers:
+        layer.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tokens", type=int, default=8192)
-    ap.add_argument("--workload", type=int, default=1, help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR)")
+    ap.add_argument("--workload", type=int, default=1,
+                    help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR); 4 = the mixed 64-layer stack")
+    ap.add_argument("--layers", type=int, default=64, help="layers of the stack (workload 4)")
+    ap.add_argument("--stack-workspace-gb", type=int, default=24, help="shared workspace of the stack in GiB")
     ap.add_argument("--workspace-mb", type=int, default=0, help="workspace limit in MiB (0 = library default)")
     ap.add_argument("--variant", type=int, default=0, help="tuning override: kernel variant id of the wide steps")
     ap.add_argument("--no-merge", action="store_true",
@@ -79,6 +197,8 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.workload == 4:
+        return run_stack(args)
     spec, _ = wl.baseline_spec(args.workload)
     tensors = wl.make_tensors(spec, args.workload)
     tokens = args.tokens

@@ -100,6 +100,13 @@ typedef struct tn_linear_s* tn_linear_t;
  *                     launch large enough to fill the chip.
  *  flags              TN_FLAG_* bits.
  *  stream             hipStream_t on which create enqueues its repacking work.
+ *  workspace, workspace_bytes
+ *                     optional DEVICE block owned by the caller (NULL = the library allocates its
+ *                     own, bounded by workspace_limit_bytes). The handle then keeps its intermediates
+ *                     and split-K partial sums inside this block and allocates no workspace; the block
+ *                     must outlive the handle and be 256-byte aligned. Several handles may share one
+ *                     block as long as their forwards never overlap in time (e.g. all layers of a model
+ *                     run on one stream). Too small for one token's intermediates: TN_ERR_INVALID_ARG.
  */
 typedef struct tn_linear_desc {
     int32_t format;
@@ -116,6 +123,8 @@ typedef struct tn_linear_desc {
     int64_t workspace_limit_bytes;
     int32_t flags;
     void* stream;
+    void* workspace;
+    int64_t workspace_bytes;
 } tn_linear_desc;
 
 /*

@@ -67,6 +67,8 @@ class _Desc(ctypes.Structure):
         ("workspace_limit_bytes", ctypes.c_int64),
         ("flags", ctypes.c_int32),
         ("stream", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_int64),
     ]
 
 
@@ -118,7 +120,7 @@ def _int_array(values: Sequence[int]):
 
 
 def _make_desc(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens, workspace_limit_bytes, flags,
-               stream):
+               stream, workspace_ptr=None, workspace_bytes=0):
     keep = []
     d = _Desc()
     d.format, d.dtype = int(fmt), int(dtype)
@@ -137,6 +139,8 @@ def _make_desc(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens, 
     d.workspace_limit_bytes = int(workspace_limit_bytes)
     d.flags = int(flags)
     d.stream = stream
+    d.workspace = workspace_ptr
+    d.workspace_bytes = int(workspace_bytes)
     return d, keep
 
 
@@ -162,10 +166,10 @@ plan_query = tn_linear_plan_query
 
 
 def tn_linear_create(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens,
-                     workspace_limit_bytes=0, flags=0, stream=None) -> int:
+                     workspace_limit_bytes=0, flags=0, stream=None, workspace_ptr=None, workspace_bytes=0) -> int:
     """Returns the opaque handle (an integer address)."""
     d, keep = _make_desc(fmt, dtype, out_modes, in_modes, ranks, tensor_ptrs, max_tokens,
-                         workspace_limit_bytes, flags, stream)
+                         workspace_limit_bytes, flags, stream, workspace_ptr, workspace_bytes)
     h = ctypes.c_void_p(0)
     rc = load_library().tn_linear_create(ctypes.byref(h), ctypes.byref(d))
     if rc != 0:
@@ -217,7 +221,7 @@ class TNLinear:
 
     def __init__(self, fmt: int, dtype: int, out_modes: Sequence[int], in_modes: Sequence[int],
                  ranks: Sequence[int], tensors: List[torch.Tensor], max_tokens: int,
-                 workspace_limit_bytes: int = 0, flags: int = 0):
+                 workspace_limit_bytes: int = 0, flags: int = 0, workspace: Optional[torch.Tensor] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("TNLinear needs a GPU: there is no CPU path")
         self.dtype = int(dtype)
@@ -226,9 +230,15 @@ class TNLinear:
             if not (t.is_cuda and t.is_contiguous() and t.dtype == self.torch_dtype):
                 raise ValueError("tensors must be contiguous CUDA tensors of the layer dtype")
         stream = torch.cuda.current_stream().cuda_stream
+        self._workspace = workspace          # keep the caller's block alive as long as the handle
+        ws_ptr, ws_bytes = None, 0
+        if workspace is not None:
+            if not (workspace.is_cuda and workspace.is_contiguous()):
+                raise ValueError("workspace must be a contiguous CUDA tensor")
+            ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
         self._handle = tn_linear_create(fmt, dtype, out_modes, in_modes, ranks,
                                         [t.data_ptr() for t in tensors], max_tokens,
-                                        workspace_limit_bytes, flags, stream)
+                                        workspace_limit_bytes, flags, stream, ws_ptr, ws_bytes)
         self.M = tn_linear_query(self._handle, TN_QUERY_OUT_FEATURES)
         self.N = tn_linear_query(self._handle, TN_QUERY_IN_FEATURES)
 

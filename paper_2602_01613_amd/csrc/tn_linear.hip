@@ -1086,6 +1086,7 @@ struct tn_linear_s {
     void* partial = nullptr;          // fp32 partial sums of the split-K kernel
     int64_t partial_bytes = 0;
     int flags = 0;
+    bool owns_workspace = true;
     int device = 0;
     bool profiling = false;
     struct ProfRec { int step; hipEvent_t start, stop; };
@@ -1113,9 +1114,11 @@ void free_handle(tn_linear_s* h) {
         if (s.packed) (void)hipFree(s.packed);
         if (s.tables) (void)hipFree(s.tables);
     }
-    for (void* w : h->ws)
-        if (w) (void)hipFree(w);
-    if (h->partial) (void)hipFree(h->partial);
+    if (h->owns_workspace) {
+        for (void* w : h->ws)
+            if (w) (void)hipFree(w);
+        if (h->partial) (void)hipFree(h->partial);
+    }
     delete h;
 }
 
@@ -1499,7 +1502,7 @@ int materialise_merges(const tn::Plan& plan, const tn_linear_desc* desc, int elt
 
 extern "C" {
 
-int tn_linear_version(void) { return 1; }
+int tn_linear_version(void) { return 2; }
 
 const char* tn_linear_strerror(int status) {
     switch (status) {
@@ -1659,38 +1662,64 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         }
         release_temps();
     }
-    // workspace: two ping-pong buffers, each chunk_tokens * max_intermediate elements
+    // workspace: two ping-pong buffers, each chunk_tokens * max_intermediate elements, and the
+    // partial-sum buffer of the split-K kernel; allocated here, or carved out of the caller's block
     int64_t per_token = h->plan.max_intermediate * h->elt;
-    int64_t limit = desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes;
-    int64_t chunk = h->max_tokens;
-    if (per_token > 0) {
-        chunk = std::max<int64_t>(1, std::min<int64_t>(h->max_tokens, limit / (2 * per_token)));
-        // rows of a pass are indexed with 32 bits
-        int64_t max_r = 1;
-        for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
-        chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, ((int64_t(1) << 31) - 1024) / max_r));
-        for (int b = 0; b < 2; ++b) {
-            if (hipMalloc(&h->ws[b], size_t(chunk * per_token)) != hipSuccess) {
-                free_handle(h);
-                return TN_ERR_ALLOC;
-            }
-        }
-        h->workspace_bytes = 2 * chunk * per_token;
-    } else {
-        int64_t max_r = 1;
-        for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
-        chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, ((int64_t(1) << 31) - 1024) / max_r));
-    }
-    h->chunk_tokens = chunk;
-    // partial-sum buffer of the split-K kernel: the largest any pass of up to `chunk` tokens needs
-    if (!(desc->flags & TN_FLAG_NO_SPLIT_K)) {
+    int64_t max_r = 1;
+    for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
+    const int64_t row_cap = ((int64_t(1) << 31) - 1024) / max_r;      // rows of a pass are indexed with 32 bits
+    const bool split_ok = !(desc->flags & TN_FLAG_NO_SPLIT_K) && h->elt == 2;
+    auto partial_need = [&](int64_t chunk) {
         int64_t need = 0;
+        if (!split_ok) return need;
         for (const auto& s : h->steps)
             for (int64_t t = 1; t <= chunk; ++t) {
                 SplitCfg c = split_config(s, t * s.plan.R);
                 if (!c.use) break;          // larger passes only add tiles
                 need = std::max(need, c.partial_bytes);
             }
+        return need;
+    };
+    int64_t chunk = h->max_tokens;
+    if (desc->workspace) {
+        // caller-owned block: [partial sums | buffer 0 | buffer 1], 256-byte aligned pieces
+        h->owns_workspace = false;
+        char* base = static_cast<char*>(desc->workspace);
+        int64_t avail = desc->workspace_bytes;
+        int64_t part = split_ok ? std::min<int64_t>(kMaxPartialBytes, avail / 4) & ~int64_t(255) : 0;
+        int64_t half = ((avail - part) / 2) & ~int64_t(255);
+        if (per_token > 0) {
+            chunk = std::min<int64_t>(std::min<int64_t>(h->max_tokens, half / per_token), row_cap);
+            if (chunk < 1) {
+                free_handle(h);
+                return TN_ERR_INVALID_ARG;      // the block cannot hold one token's intermediates
+            }
+            h->ws[0] = base + part;
+            h->ws[1] = base + part + half;
+        } else {
+            chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, row_cap));
+        }
+        if (part > 0) {
+            h->partial = base;
+            h->partial_bytes = part;
+        }
+        h->workspace_bytes = 0;
+    } else {
+        int64_t limit = desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes;
+        if (per_token > 0) {
+            chunk = std::max<int64_t>(1, std::min<int64_t>(h->max_tokens, limit / (2 * per_token)));
+            chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, row_cap));
+            for (int b = 0; b < 2; ++b) {
+                if (hipMalloc(&h->ws[b], size_t(chunk * per_token)) != hipSuccess) {
+                    free_handle(h);
+                    return TN_ERR_ALLOC;
+                }
+            }
+            h->workspace_bytes = 2 * chunk * per_token;
+        } else {
+            chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, row_cap));
+        }
+        int64_t need = partial_need(chunk);
         if (need > 0) {
             if (hipMalloc(&h->partial, size_t(need)) != hipSuccess) {
                 free_handle(h);
@@ -1700,6 +1729,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             h->workspace_bytes += need;
         }
     }
+    h->chunk_tokens = chunk;
     *out = h;
     return TN_OK;
 }

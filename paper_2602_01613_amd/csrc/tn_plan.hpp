@@ -114,6 +114,7 @@ inline int build_network(const tn_linear_desc* d, Plan* p) {
     if (d->n_out_modes > kMaxTensors || d->n_in_modes > kMaxTensors) return TN_ERR_UNSUPPORTED;
     if (d->max_tokens < 1) return TN_ERR_INVALID_ARG;
     if (d->workspace_limit_bytes < 0) return TN_ERR_INVALID_ARG;
+    if (d->workspace && d->workspace_bytes < 512) return TN_ERR_INVALID_ARG;
     p->format = d->format;
     p->dtype = d->dtype;
     int64_t M = 1, N = 1;
