@@ -175,6 +175,9 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--workload", type=int, default=1,
                     help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR); 4 = the mixed 64-layer stack")
+    ap.add_argument("--custom", type=str, default="",
+                    help="one matrix of the stack instead of a numbered workload: format,in,out,rank "
+                         "(e.g. tr,25600,5120,96)")
     ap.add_argument("--layers", type=int, default=64, help="layers of the stack (workload 4)")
     ap.add_argument("--stack-workspace-gb", type=int, default=24, help="shared workspace of the stack in GiB")
     ap.add_argument("--workspace-mb", type=int, default=0, help="workspace limit in MiB (0 = library default)")
@@ -199,7 +202,12 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.workload == 4:
         return run_stack(args)
-    spec, _ = wl.baseline_spec(args.workload)
+    if args.custom:
+        f, n_in, n_out, r = args.custom.split(",")
+        fmt = {"dense": wl.FORMAT_DENSE, "tt": wl.FORMAT_TT, "tr": wl.FORMAT_TR, "tucker": wl.FORMAT_TUCKER}[f]
+        spec = wl.stack_spec(fmt, int(n_in), int(n_out), int(r), f"{f}_{n_in}_{n_out}_r{r}")
+    else:
+        spec, _ = wl.baseline_spec(args.workload)
     tensors = wl.make_tensors(spec, args.workload)
     tokens = args.tokens
     x64 = wl.make_x(spec, tokens, args.workload)
