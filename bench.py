@@ -52,6 +52,20 @@ def cpu_baseline(spec, tensors, sample_tokens):
     }
 
 
+def measured_traffic(args, step):
+    """HBM bytes per launch of a step of the default workload, measured in separate rocprofv3
+    counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy) and recorded in profiles/."""
+    if args.workload != 1 or args.custom or args.no_merge or args.tokens != 8192:
+        return None
+    path = os.path.join(ROOT, "profiles", "tt_q_proj_prefill8192_hbm_traffic.txt")
+    try:
+        import re
+        m = re.search(rf"TRAFFIC_BYTES_PER_LAUNCH step{step} = (\d+)", open(path).read())
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def run_stack(args) -> int:
     """The mixed 64-layer projection stack: 448 layers (format and rank drawn per matrix) run
     back to back on one stream, sharing one workspace block; 1-token decode and a prefill pass.
@@ -175,6 +189,9 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--workload", type=int, default=1,
                     help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR); 4 = the mixed 64-layer stack")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to "
+                         "calibrate the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--custom", type=str, default="",
                     help="one matrix of the stack instead of a numbered workload: format,in,out,rank "
                          "(e.g. tr,25600,5120,96)")
@@ -269,7 +286,7 @@ def main() -> int:
     else:
         roof = {"bound": "hbm", "achieved": per_step[dom]["algorithmic_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(args, dom)
     roof["kernel"] = (f"contraction step {dom}: rows {q(dom, 0)} x K {q(dom, 1)} x cols {q(dom, 2)} per token, "
                       f"{per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge of {ridge:.0f}")
     roof["avg_launch_us"] = per_step[dom]["avg_launch_us"]
@@ -341,6 +358,14 @@ def main() -> int:
         "paper_context": "paper reports ~40 -> ~50 -> ~75 tokens/s end-to-end decode on Qwen3-32B, 8K context, "
                          "1x A100 80GB (whole model with healing and speculative decoding; not this kernel)",
     }
+    if args.calib_copy_mb > 0:
+        src = torch.ones(args.calib_copy_mb << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calib_copy_bytes"] = args.calib_copy_mb << 20
+        del src, dst
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(spec, tensors, args.cpu_sample_tokens)
     layer.close()
