@@ -278,7 +278,8 @@ def main() -> int:
             "avg_launch_us": 1e3 * ms / max(1, launches),
             "tflops": step_flops[s] * tokens * args.steps / sec / 1e12 if sec > 0 else 0.0,
             "algorithmic_GBps": nbytes / sec / 1e9 if sec > 0 else 0.0,
-            "flop_per_byte": step_flops[s] / step_io_bytes[s]})
+            "flop_per_byte": step_flops[s] / step_io_bytes[s],
+            "fused_with_next": bool(q(s, 6))})
     dom = max(range(n_steps), key=lambda s: per_step[s]["ms_per_forward"])
     ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if per_step[dom]["flop_per_byte"] >= ridge:
@@ -317,6 +318,10 @@ def main() -> int:
             ms, launches = layer.profile_read(s)
             k_us = 1e3 * ms / max(1, launches)
             nbytes = step_io_bytes[s] * t + step_param_bytes[s]
+            if launches == 0:        # runs inside the previous step's fused launch
+                steps.append({"step": s, "kernel_us": 0.0, "GBps": 0.0, "param_GBps": 0.0, "tflops": 0.0,
+                              "fused_into_previous": True})
+                continue
             steps.append({"step": s, "kernel_us": k_us, "GBps": nbytes / k_us / 1e3,
                           "param_GBps": step_param_bytes[s] / k_us / 1e3,
                           "tflops": step_flops[s] * t / k_us / 1e6})

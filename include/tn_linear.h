@@ -55,6 +55,9 @@ extern "C" {
 #define TN_FLAG_NO_MERGE        2   /* keep every parameter tensor separate: do not contract adjacent
                                        tensors into one at create time even where that is free */
 #define TN_FLAG_NO_SPLIT_K      4   /* never use the split-K kernel for small launches (tuning/debug aid) */
+#define TN_FLAG_FUSE_SMALL_STEPS 8  /* run pairs of small adjacent steps (e.g. Tucker factor products) as one
+                                       launch with the intermediate in LDS; off by default: saves HBM traffic
+                                       but measured slower than two launches on MI355X */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
                                        bf16 steps (0 = library's choice; see TN_QUERY_STEP_BASE f=5) */
 
@@ -73,7 +76,8 @@ extern "C" {
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=
                                              n_tensors name tensors merged at create time),
-                                           5 kernel variant chosen (0 scalar; >0 MFMA tile id) */
+                                           5 kernel variant chosen (0 scalar; >0 MFMA tile id),
+                                           6 1 if this step and the next run as one fused launch */
 
 typedef struct tn_linear_s* tn_linear_t;
 

@@ -1045,6 +1045,190 @@ __global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, cons
 }
 
 // ---------------------------------------------------------------------------------------------
+// Fused pair of small steps (e.g. the two out-factor or the two in-factor products of a Tucker
+// layer): when one token's input of the first step and its intermediate fit in LDS, a workgroup
+// takes tokens one at a time, stages the token's [R1, K1] input in LDS, runs step 1 with MFMA into
+// an LDS copy of the intermediate (written through step 1's scatter tables, i.e. already in the
+// layout step 2 reads), runs step 2 from LDS and stores its result through step 2's tables. Each
+// wave owns up to two 32-column tiles of either packed tensor and keeps their fragment blocks in
+// registers for all the tokens of the workgroup (K <= 96, C <= 256); the next token's input is
+// prefetched into registers while the current one is computed. The intermediate never touches HBM and one launch
+// replaces two. Needs K1 % 16 == 0 and K2 % 16 == 0 (no padded k-steps are ever read).
+// CM2 = 1: step 2's columns come in aligned runs of 8 -> 16-byte stores via a per-wave LDS patch;
+// CM2 = 0: scalar stores.
+// ---------------------------------------------------------------------------------------------
+struct Fused2Args {
+    StepArgs s1, s2;
+    int32_t tokens;
+    int32_t in_elems;     // LDS elements reserved for the staged input: roundup(R1, 32) * (K1 + 8)
+    int32_t mid_elems;    // LDS elements reserved for the intermediate: roundup(R2, 32) * K2
+};
+
+template <int CM2>
+__global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    const StepArgs& a1 = f.s1;
+    const StepArgs& a2 = f.s2;
+    const int R1 = int(a1.R), K1 = a1.K, C1 = a1.C, R2 = int(a2.R), K2 = a2.K, C2 = a2.C;
+    const int LD1 = K1 + 8;
+    bf16_t* sIn = reinterpret_cast<bf16_t*>(dyn_smem);
+    bf16_t* sMid = sIn + f.in_elems;
+    bf16_t* sPatch = sMid + f.mid_elems;                       // 4 waves x 32 x 40
+    int32_t* sTab = reinterpret_cast<int32_t*>(sPatch + 4 * 32 * 40);
+    int32_t* t_crow1 = sTab;
+    int32_t* t_ccol1 = t_crow1 + R1;
+    int32_t* t_crow2 = t_ccol1 + C1;
+    int32_t* t_ccol2 = t_crow2 + R2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < R1; i += 256) t_crow1[i] = a1.crow[i];
+    for (int i = tid; i < C1; i += 256) t_ccol1[i] = a1.ccol[i];
+    for (int i = tid; i < R2; i += 256) t_crow2[i] = a2.crow[i];
+    for (int i = tid; i < C2; i += 256) t_ccol2[i] = a2.ccol[i];
+    // rows past R1 / R2 of the last row tile are read by the MFMAs (their results are dropped):
+    // give them defined contents once
+    for (int i = tid; i < f.in_elems; i += 256) sIn[i] = bf16_t(0.f);
+    for (int i = tid; i < f.mid_elems; i += 256) sMid[i] = bf16_t(0.f);
+    __syncthreads();
+
+    const bf16_t* A = static_cast<const bf16_t*>(a1.A);
+    const bf16_t* B1 = static_cast<const bf16_t*>(a1.B);
+    const bf16_t* B2 = static_cast<const bf16_t*>(a2.B);
+    bf16_t* Out = static_cast<bf16_t*>(a2.Out);
+    const int nks1 = K1 >> 4, nks2 = K2 >> 4;                  // real k-steps (<= 6)
+    const int bks1 = a1.Kp >> 4, bks2 = a2.Kp >> 4;            // k-steps per column block in the packed tensors
+    const int nrt1 = (R1 + 31) >> 5, nct1 = (C1 + 31) >> 5;
+    const int nrt2 = (R2 + 31) >> 5, nct2 = (C2 + 31) >> 5;     // nct <= 8: column tiles j = wave, wave + 4
+    const int chunks_per_row = K1 >> 3;
+    bf16_t* myPatch = sPatch + wave * 32 * 40;
+
+    // the wave's column tiles of both packed tensors stay in registers for all of its tokens
+    bf16x8 bw1[2][6], bw2[2][6];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int ks = 0; ks < 6; ++ks) {
+            bf16x8 z;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
+            int j = wave + 4 * jj;
+            bw1[jj][ks] = (j < nct1 && ks < nks1)
+                              ? *reinterpret_cast<const bf16x8*>(B1 + (int64_t(j) * bks1 + ks) * 512 + lane * 8) : z;
+            bw2[jj][ks] = (j < nct2 && ks < nks2)
+                              ? *reinterpret_cast<const bf16x8*>(B2 + (int64_t(j) * bks2 + ks) * 512 + lane * 8) : z;
+        }
+
+    // the next token's input is fetched into registers while the current token is computed
+    // (at most 6 chunks of 16 bytes per thread: R1 * K1 <= 12288)
+    const int n_chunks = R1 * chunks_per_row;
+    int my_off[6];                                             // LDS element offset of each of my chunks
+#pragma unroll
+    for (int q = 0; q < 6; ++q) {
+        int e = tid + 256 * q;
+        int r = e / chunks_per_row;
+        my_off[q] = e < n_chunks ? r * LD1 + (e - r * chunks_per_row) * 8 : -1;
+    }
+    bf16x8 pre[6];
+    auto fetch_in = [&](int t) {
+        const bf16_t* in = A + int64_t(t) * a1.a_tok_stride + tid * 8;
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+            if (my_off[q] >= 0) pre[q] = *reinterpret_cast<const bf16x8*>(in + 2048 * q);
+    };
+    if (int(blockIdx.x) < f.tokens) fetch_in(blockIdx.x);
+    for (int t = blockIdx.x; t < f.tokens; t += gridDim.x) {
+        // ---- stage the token's input
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+            if (my_off[q] >= 0) *reinterpret_cast<bf16x8*>(sIn + my_off[q]) = pre[q];
+        __syncthreads();
+        if (t + int(gridDim.x) < f.tokens) fetch_in(t + gridDim.x);
+        // ---- step 1
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = wave + 4 * jj;
+            if (j >= nct1) continue;
+            for (int i = 0; i < nrt1; ++i) {
+                floatx16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                const bf16_t* ap = sIn + (i * 32 + (lane & 31)) * LD1 + 8 * (lane >> 5);
+                bf16x8 af[6];                 // all fragment reads first, then the MFMA chain
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks1) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw1[jj][ks], af[ks], acc, 0, 0, 0);
+                // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
+                int r = i * 32 + (lane & 31);
+                if (r < R1) {
+                    int rbase = t_crow1[r];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                        if (c < C1) sMid[rbase + t_ccol1[c]] = bf16_t(acc[v]);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // ---- step 2 from the LDS intermediate
+        bf16_t* out_t = Out + int64_t(t) * a2.c_tok_stride;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = wave + 4 * jj;
+            if (j >= nct2) continue;
+            for (int i = 0; i < nrt2; ++i) {
+                floatx16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                const bf16_t* ap = sMid + (i * 32 + (lane & 31)) * K2 + 8 * (lane >> 5);
+                bf16x8 af[6];
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks2) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw2[jj][ks], af[ks], acc, 0, 0, 0);
+                if (CM2 == 1) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        bf16x4 pk;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[4 * q + u]);
+                        *reinterpret_cast<bf16x4*>(myPatch + (lane & 31) * 40 + 8 * q + 4 * (lane >> 5)) = pk;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    int c = j * 32 + (lane & 3) * 8;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        int rr = h * 16 + (lane >> 2);
+                        int r = i * 32 + rr;
+                        bf16x8 v = *reinterpret_cast<const bf16x8*>(myPatch + rr * 40 + (lane & 3) * 8);
+                        if (r < R2 && c < C2) *reinterpret_cast<bf16x8*>(out_t + t_crow2[r] + t_ccol2[c]) = v;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                } else {
+                    int r = i * 32 + (lane & 31);
+                    if (r < R2) {
+                        int rbase = t_crow2[r];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                            if (c < C2) out_t[rbase + t_ccol2[c]] = bf16_t(acc[v]);
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();   // sIn and sMid are rewritten for the next token
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 enum Variant : int {
@@ -1072,6 +1256,9 @@ struct DevStep {
     int variant = VAR_SCALAR;
     int amode = 0, cmode = 0;
     int bn = 64, bm = 64;
+    bool fuse_next = false;       // this step and the next run as one step_fused2_kernel launch
+    int fused_in_elems = 0, fused_mid_elems = 0;
+    size_t fused_smem = 0;
 };
 
 }  // namespace
@@ -1370,6 +1557,76 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
+// Can steps s and s+1 run as one fused launch? (small per-token tensors, k-steps without padding)
+void plan_fusion(tn_linear_s* h) {
+    // opt-in: measured slower than the two separate launches on MI355X (the per-token work is a
+    // chain of small dependent LDS reads and MFMAs that 8 waves per CU cannot overlap)
+    if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & TN_FLAG_SCALAR_KERNELS) || !(h->flags & TN_FLAG_FUSE_SMALL_STEPS)) return;
+    for (size_t s = 0; s + 1 < h->steps.size(); ++s) {
+        DevStep& a = h->steps[s];
+        DevStep& b = h->steps[s + 1];
+        if (s > 0 && h->steps[s - 1].fuse_next) continue;
+        const tn::Step& p1 = a.plan;
+        const tn::Step& p2 = b.plan;
+        if (!p1.a_plain || !p2.a_plain || p1.K % 16 || p2.K % 16) continue;
+        if (p1.K > 96 || p2.K > 96 || p1.C > 256 || p2.C > 256) continue;      // register-resident packed tensors
+        if (p1.R * p1.K > 12288) continue;                                      // register-prefetched input
+        if (p1.c_tok_stride != p2.R * p2.K) continue;
+        int64_t in_elems = int64_t((p1.R + 31) / 32 * 32) * (p1.K + 8);
+        int64_t mid_elems = int64_t((p2.R + 31) / 32 * 32) * p2.K;
+        int64_t tab = p1.R + p1.C + p2.R + p2.C;
+        int64_t smem = (in_elems + mid_elems + 4 * 32 * 40) * 2 + tab * 4 + 64;
+        if (smem > 72 * 1024) continue;
+        if (int64_t(a.Cp) * a.Kp > 65536 || int64_t(b.Cp) * b.Kp > 65536) continue;
+        a.fuse_next = true;
+        a.fused_in_elems = int(in_elems);
+        a.fused_mid_elems = int((mid_elems + 7) / 8 * 8);
+        a.fused_smem = size_t((a.fused_in_elems + a.fused_mid_elems + 4 * 32 * 40) * 2 + tab * 4 + 64);
+    }
+}
+
+void fill_args(const DevStep& s, const void* A, void* Out, int64_t tokens, StepArgs* a) {
+    a->A = A;
+    a->B = s.packed;
+    a->Out = Out;
+    a->arow = s.arow;
+    a->acol = s.acol;
+    a->crow = s.crow;
+    a->ccol = s.ccol;
+    a->a_tok_stride = s.plan.a_tok_stride;
+    a->c_tok_stride = s.plan.c_tok_stride;
+    a->total_rows = uint32_t(tokens * s.plan.R);
+    a->R = uint32_t(s.plan.R);
+    a->K = int32_t(s.plan.K);
+    a->Kp = s.Kp;
+    a->C = int32_t(s.plan.C);
+    a->Cp = s.Cp;
+}
+
+int launch_fused2(const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens, hipStream_t st) {
+    Fused2Args f;
+    fill_args(s1, A, nullptr, tokens, &f.s1);
+    fill_args(s2, nullptr, Out, tokens, &f.s2);
+    f.tokens = int32_t(tokens);
+    f.in_elems = s1.fused_in_elems;
+    f.mid_elems = s1.fused_mid_elems;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess)
+            return TN_ERR_HIP;
+        configured = true;
+    }
+    dim3 grid(uint32_t(std::min<int64_t>(tokens, 1024)));
+    if (s2.cmode == 1)
+        hipLaunchKernelGGL(step_fused2_kernel<1>, grid, dim3(256), s1.fused_smem, st, f);
+    else
+        hipLaunchKernelGGL(step_fused2_kernel<0>, grid, dim3(256), s1.fused_smem, st, f);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
 int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
     switch (what) {
         case TN_QUERY_PARAM_COUNT: *value = p.params; return TN_OK;
@@ -1531,7 +1788,8 @@ int tn_linear_plan_query(const tn_linear_desc* desc, int32_t what, int64_t* valu
         *value = total;   // lower bound: the tile width used for padding is chosen at create
         return TN_OK;
     }
-    if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 == 5) {
+    if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 >= 5 &&
+        (what - TN_QUERY_STEP_BASE) % 10 <= 6) {
         *value = 0;
         return TN_OK;
     }
@@ -1662,6 +1920,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         }
         release_temps();
     }
+    plan_fusion(h);
     // workspace: two ping-pong buffers, each chunk_tokens * max_intermediate elements, and the
     // partial-sum buffer of the split-K kernel; allocated here, or carved out of the caller's block
     int64_t per_token = h->plan.max_intermediate * h->elt;
@@ -1745,20 +2004,24 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
     for (int64_t t0 = 0; t0 < tokens; t0 += h->chunk_tokens) {
         int64_t nt = std::min(h->chunk_tokens, tokens - t0);
         for (size_t s = 0; s < ns; ++s) {
+            const bool fused = h->steps[s].fuse_next;
+            const size_t so = fused ? s + 1 : s;                 // step whose output this launch writes
             const void* A = (s == 0) ? static_cast<const void*>(xb + t0 * h->plan.N * h->elt) : h->ws[(s - 1) & 1];
-            void* Out = (s == ns - 1) ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : h->ws[s & 1];
+            void* Out = (so == ns - 1) ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : h->ws[so & 1];
             tn_linear_s::ProfRec rec{int(s), nullptr, nullptr};
             if (h->profiling) {
                 if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess)
                     return TN_ERR_HIP;
                 (void)hipEventRecord(rec.start, st);
             }
-            int rc = launch_step(h, h->steps[s], A, Out, nt, st);
+            int rc = fused ? launch_fused2(h->steps[s], h->steps[s + 1], A, Out, nt, st)
+                           : launch_step(h, h->steps[s], A, Out, nt, st);
             if (h->profiling) {
                 (void)hipEventRecord(rec.stop, st);
                 h->prof.push_back(rec);
             }
             if (rc != TN_OK) return rc;
+            if (fused) ++s;
         }
     }
     return TN_OK;
@@ -1805,6 +2068,12 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
         int s = (what - TN_QUERY_STEP_BASE) / 10;
         if (s >= int(h->steps.size())) return TN_ERR_INVALID_ARG;
         *value = h->steps[size_t(s)].variant;
+        return TN_OK;
+    }
+    if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 == 6) {
+        int s = (what - TN_QUERY_STEP_BASE) / 10;
+        if (s >= int(h->steps.size())) return TN_ERR_INVALID_ARG;
+        *value = h->steps[size_t(s)].fuse_next ? 1 : 0;
         return TN_OK;
     }
     return plan_value(h->plan, what, value);
