@@ -201,7 +201,7 @@ def main() -> int:
     ap.add_argument("--variant", type=int, default=0, help="tuning override: kernel variant id of the wide steps")
     ap.add_argument("--no-merge", action="store_true",
                     help="keep the chain as given (no create-time merging of parameter tensors)")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -330,6 +330,7 @@ def main() -> int:
                 "sum_kernel_us": sum(p["kernel_us"] for p in steps), "per_step": steps}
 
     dec1 = decode_stats(1)
+    dec8 = decode_stats(8)          # the size a speculative-decoding verifier sends (paper Section 3.6)
     dec64 = decode_stats(64)
     decode_us = dec1["us_per_call"]
 
@@ -359,6 +360,7 @@ def main() -> int:
         "per_step": per_step,
         "decode_1tok": dict(dec1, us_per_token=decode_us,
                             param_GBps=layer.query(tn.TN_QUERY_PACKED_BYTES) / decode_us / 1e3),
+        "verify_8tok": dec8,
         "decode_64tok": dec64,
         "paper_context": "paper reports ~40 -> ~50 -> ~75 tokens/s end-to-end decode on Qwen3-32B, 8K context, "
                          "1x A100 80GB (whole model with healing and speculative decoding; not this kernel)",

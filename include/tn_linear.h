@@ -59,7 +59,9 @@ extern "C" {
                                        launch with the intermediate in LDS; off by default: saves HBM traffic
                                        but measured slower than two launches on MI355X */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
-                                       bf16 steps (0 = library's choice; see TN_QUERY_STEP_BASE f=5) */
+                                       bf16 steps (0 = library's choice): 3 = 128x256 and 8 = 256x128
+                                       register-prefetch tiles, 9 = short-K store kernel, 12 = 256x256
+                                       direct-to-LDS ring; ignored where the variant cannot run the step */
 
 /* tn_linear_query / tn_linear_plan_query: what */
 #define TN_QUERY_PARAM_COUNT        0   /* number of parameters in the caller's tensors */
@@ -76,7 +78,8 @@ extern "C" {
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=
                                              n_tensors name tensors merged at create time),
-                                           5 kernel variant chosen (0 scalar; >0 MFMA tile id),
+                                           5 kernel variant chosen (0 plain FMA, 2 narrow 256x32 tile, else
+                                             the ids listed at TN_FLAG_VARIANT_SHIFT),
                                            6 1 if this step and the next run as one fused launch */
 
 typedef struct tn_linear_s* tn_linear_t;

@@ -1233,18 +1233,11 @@ __global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
 // ---------------------------------------------------------------------------------------------
 enum Variant : int {
     VAR_SCALAR = 0,
-    VAR_MFMA_128x128 = 1,
-    VAR_MFMA_256x32 = 2,
-    VAR_PIPE_128x256 = 3,     // 2 workgroups per CU, one LDS stage
-    VAR_PIPE_256x256 = 4,     // 1 workgroup per CU, two LDS stages
-    VAR_PIPE_128x128 = 5,     // 2 workgroups per CU, two LDS stages
-    VAR_PIPE8_256x256 = 6,    // 8 waves (2 per SIMD), 1 workgroup per CU, two LDS stages
-    VAR_PIPE8_256x256_S1 = 7, // same, one LDS stage
-    VAR_PIPE_256x128 = 8,     // 4 waves stacked along rows, 2 workgroups per CU, one LDS stage
+    VAR_MFMA_256x32 = 2,      // narrow outputs (<= 32 columns)
+    VAR_PIPE_128x256 = 3,     // register-prefetch tiles, 4 waves, 2 workgroups per CU, one LDS stage
+    VAR_PIPE_256x128 = 8,     // same, 4 waves stacked along rows
     VAR_SHORTK = 9,           // K <= 64, store-bound: registers-only operands, barrier-free
-    VAR_DLDS_128x256 = 10,    // direct-to-LDS, 4 waves, 3 stages, 2 workgroups per CU
-    VAR_DLDS_256x128 = 11,    // same, 4 waves stacked along rows
-    VAR_DLDS8_256x256 = 12,   // direct-to-LDS, 8 waves, 4 stages, 1 workgroup per CU (long K)
+    VAR_DLDS8_256x256 = 12,   // direct-to-LDS ring, 8 waves, 4 stages, 1 workgroup per CU
 };
 
 struct DevStep {
@@ -1331,15 +1324,15 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
         // fits without extra column padding; the 4-wave direct-to-LDS tiles do not)
         if (dlds_ok && p.C >= 256 && round_up(int(p.C), 256) == round_up(int(p.C), 128)) v = VAR_DLDS8_256x256;
         if (shortk_ok && p.C >= 256) v = VAR_SHORTK;
-        if (forced >= VAR_MFMA_128x128 && forced <= VAR_DLDS8_256x256 && forced != VAR_MFMA_256x32 &&
-            (forced != VAR_SHORTK || shortk_ok) && (forced < VAR_DLDS_128x256 || dlds_ok))
+        if (forced == VAR_PIPE_128x256 || forced == VAR_PIPE_256x128 || (forced == VAR_SHORTK && shortk_ok) ||
+            (forced == VAR_DLDS8_256x256 && dlds_ok))
             v = forced;
         s->variant = v;
         switch (v) {
-            case VAR_MFMA_128x128: case VAR_PIPE_128x128: case VAR_SHORTK: s->bm = 128; s->bn = 128; break;
-            case VAR_PIPE_128x256: case VAR_DLDS_128x256: s->bm = 128; s->bn = 256; break;
-            case VAR_PIPE_256x128: case VAR_DLDS_256x128: s->bm = 256; s->bn = 128; break;
-            default: s->bm = 256; s->bn = 256; break;      // the 256x256 variants
+            case VAR_SHORTK: s->bm = 128; s->bn = 128; break;
+            case VAR_PIPE_128x256: s->bm = 128; s->bn = 256; break;
+            case VAR_PIPE_256x128: s->bm = 256; s->bn = 128; break;
+            default: s->bm = 256; s->bn = 256; break;      // VAR_DLDS8_256x256
         }
     }
     s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : 1;
@@ -1489,39 +1482,11 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
             else
                 hipLaunchKernelGGL(step_scalar_kernel<float>, grid, dim3(256), 0, st, a);
             break;
-        case VAR_MFMA_128x128:
-            launch_mfma<2, 2, 2, 2>(s, a, grid, st);
-            break;
         case VAR_MFMA_256x32:
             launch_mfma<4, 1, 2, 1>(s, a, grid, st);
             break;
         case VAR_PIPE_128x256: {
             int rc = launch_pipe<2, 2, 2, 4, 1, 2>(s, a, rows, st);
-            if (rc != TN_OK) return rc;
-            break;
-        }
-        case VAR_PIPE_256x256: {
-            int rc = launch_pipe<2, 2, 4, 4, 2, 1>(s, a, rows, st);
-            if (rc != TN_OK) return rc;
-            break;
-        }
-        case VAR_PIPE8_256x256: {
-            int rc = launch_pipe<4, 2, 2, 4, 2, 1>(s, a, rows, st);
-            if (rc != TN_OK) return rc;
-            break;
-        }
-        case VAR_PIPE8_256x256_S1: {
-            int rc = launch_pipe<4, 2, 2, 4, 1, 1>(s, a, rows, st);
-            if (rc != TN_OK) return rc;
-            break;
-        }
-        case VAR_DLDS_128x256: {
-            int rc = launch_dlds<2, 2, 2, 4, 3, 2>(s, a, rows, st);
-            if (rc != TN_OK) return rc;
-            break;
-        }
-        case VAR_DLDS_256x128: {
-            int rc = launch_dlds<4, 1, 2, 4, 3, 2>(s, a, rows, st);
             if (rc != TN_OK) return rc;
             break;
         }
@@ -1543,11 +1508,6 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
         }
         case VAR_PIPE_256x128: {
             int rc = launch_pipe<4, 1, 2, 4, 1, 2>(s, a, rows, st);
-            if (rc != TN_OK) return rc;
-            break;
-        }
-        case VAR_PIPE_128x128: {
-            int rc = launch_pipe<2, 2, 2, 2, 2, 2>(s, a, rows, st);
             if (rc != TN_OK) return rc;
             break;
         }

@@ -216,7 +216,7 @@ def test_stack_sample_matrices():
         assert err <= TOL["bf16"], (fmt, n_in, n_out, r, err)
 
 
-@pytest.mark.parametrize("variant", [1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
+@pytest.mark.parametrize("variant", [3, 8, 9, 12])
 def test_wide_step_kernel_variants(variant):
     """Every tile variant of the wide bf16 steps (tuning override) on shapes with ragged row
     and column tiles, a K that is not a multiple of the K tile, and a gathered first step."""
