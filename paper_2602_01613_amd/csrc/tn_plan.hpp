@@ -508,12 +508,14 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
 
 // Merge pairs of parameter tensors whose contraction is no larger than the pair. Returns the
 // number of merges made. Only indices owned by exactly these two tensors are summed.
-inline int merge_pass(Plan* p) {
+inline int merge_pass(Plan* p, double budget_elems = 0) {
     int made = 0;
     for (;;) {
         int best_a = -1, best_b = -1;
-        double best_ratio = 2.0;
+        double best_ratio = 1e300;
         int n = int(p->tensors.size());
+        double total_now = 0;
+        for (const NetTensor& T : p->tensors) total_now += double(T.n_elems);
         for (int a = 0; a < n; ++a)
             for (int b = 0; b < n; ++b) {
                 if (a == b) continue;
@@ -537,8 +539,11 @@ inline int merge_pass(Plan* p) {
                 for (int i : Q.idx)
                     if (!detail::contains(shared, i)) merged *= double(p->extent[size_t(i)]);
                 double ratio = merged / double(P.n_elems + Q.n_elems);
+                // free merges always; growing ones only inside the caller's parameter budget
+                bool ok_size = ratio <= 1.0 ||
+                               (budget_elems > 0 && total_now - double(P.n_elems + Q.n_elems) + merged <= budget_elems);
                 // a < b keeps P's free indices (the earlier tensor's) outermost in the result
-                if (ratio <= 1.0 && a < b && ratio < best_ratio) {
+                if (ok_size && a < b && ratio < best_ratio) {
                     best_ratio = ratio;
                     best_a = a;
                     best_b = b;
@@ -605,7 +610,9 @@ inline int make_plan(const tn_linear_desc* d, Plan* p) {
     if (!(d->flags & TN_FLAG_NO_MERGE)) {
         Plan q = *p;
         q.steps.clear();
-        if (merge_pass(&q) > 0) {
+        // TN_FLAG_MERGE_GROW: merges may add parameters up to a quarter of the dense matrix
+        double budget = (d->flags & TN_FLAG_MERGE_GROW) ? double(p->M) * double(p->N) / 4.0 : 0.0;
+        if (merge_pass(&q, budget) > 0) {
             std::vector<int> qorder;
             if (choose_order(q, &qorder) == TN_OK && build_steps(&q, qorder) == TN_OK && q.flops < p->flops)
                 *p = q;

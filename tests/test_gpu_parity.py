@@ -84,14 +84,14 @@ def dense_w():
 
 # workload 1 is run both ways: with its end cores merged at create time (the default) and as
 # the four-core chain exactly as given
-CONFIG_RUNS = [(1, 0), (1, tn.TN_FLAG_NO_MERGE), (2, 0), (3, 0)]
+CONFIG_RUNS = [(1, 0), (1, tn.TN_FLAG_NO_MERGE), (2, 0), (3, 0), (3, tn.TN_FLAG_MERGE_GROW)]
 
 
 @pytest.mark.parametrize("i,flags", CONFIG_RUNS)
 def test_baseline_configs_decode_sizes(i, flags, dense_w):
     spec, ts, w = dense_w(i)
     layer = make_layer(spec, ts, 64, flags=flags)
-    assert layer.query(tn.TN_QUERY_NUM_STEPS) == {(1, 0): 2, (1, 2): 4, (2, 0): 5, (3, 0): 4}[(i, flags)]
+    assert layer.query(tn.TN_QUERY_NUM_STEPS) == {(1, 0): 2, (1, 2): 4, (2, 0): 5, (3, 0): 4, (3, 16): 2}[(i, flags)]
     for tokens in (1, 64):
         x = wl.make_x(spec, tokens, i)
         y = to_host(layer(to_dev(x, spec.dtype)))

@@ -70,10 +70,13 @@ CASES = [
     (tn.TN_FORMAT_TT, (2, 3, 2, 2), (2, 2, 3, 2), (1, 4, 2, 4, 1)),
     (tn.TN_FORMAT_TT, (2, 3, 2), (2, 2, 2), (1, 4, 4, 1)),
     (tn.TN_FORMAT_TT, (2, 4, 2), (3, 4, 2), (1, 6, 5, 1)),
+    # with TN_FLAG_MERGE_GROW these rings become two half-rings
+    (tn.TN_FORMAT_TR, (4, 4, 4, 4), (4, 4, 4, 4), (2, 2, 2, 2, 2)),
+    (tn.TN_FORMAT_TR, (4, 3, 4, 2), (2, 4, 3, 4), (2, 3, 2, 3, 2)),
 ]
 
 
-@pytest.mark.parametrize("flags", [0, tn.TN_FLAG_NO_MERGE])
+@pytest.mark.parametrize("flags", [0, tn.TN_FLAG_NO_MERGE, tn.TN_FLAG_MERGE_GROW])
 @pytest.mark.parametrize("fmt,om,im,rk", CASES)
 def test_plan_executes_to_oracle(host_exec, fmt, om, im, rk, flags):
     rng = np.random.default_rng(hash((fmt, om, im, rk)) % (2 ** 32))
@@ -151,6 +154,20 @@ def test_create_time_merging():
     assert _q(big, tn.TN_QUERY_NUM_MERGES, 0) == 2
     small = wl.stack_spec(wl.FORMAT_TT, 5120, 8192, 32)
     assert _q(small, tn.TN_QUERY_NUM_MERGES, 0) == 0
+
+
+def test_growing_merges_half_ring():
+    # TR down_proj with TN_FLAG_MERGE_GROW: cores (4,1) and (2,3) are contracted at create time
+    # (23.6 M parameters, under a quarter of the dense 131 M) and the chain is two steps,
+    # 5 033 164 800 FLOP per token instead of 12 666 798 080
+    spec, _ = wl.baseline_spec(3)
+    g = tn.TN_FLAG_MERGE_GROW
+    assert _q(spec, tn.TN_QUERY_NUM_MERGES, g) == 2
+    assert _q(spec, tn.TN_QUERY_NUM_STEPS, g) == 2
+    assert _q(spec, tn.TN_QUERY_FLOPS_PER_TOKEN, g) == 5033164800
+    # rank 96: every merge would exceed the budget, the plan is unchanged
+    big = wl.stack_spec(wl.FORMAT_TR, 25600, 5120, 96)
+    assert _q(big, tn.TN_QUERY_NUM_MERGES, g) == 0
 
 
 def test_planned_flops_equal_brute_force_minimum():
