@@ -201,6 +201,7 @@ def main() -> int:
     ap.add_argument("--variant", type=int, default=0, help="tuning override: kernel variant id of the wide steps")
     ap.add_argument("--no-merge", action="store_true",
                     help="keep the chain as given (no create-time merging of parameter tensors)")
+    ap.add_argument("--shortk-mode", type=int, default=0, help="tuning override of the short-K kernel (0 = library choice, 1..3 = form 0..2)")
     ap.add_argument("--merge-grow", action="store_true",
                     help="allow create-time merges that add parameters (up to a quarter of the dense matrix)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
@@ -234,7 +235,8 @@ def main() -> int:
     x = torch.from_numpy(x64).to(torch.float32).to(torch.bfloat16).cuda()
     del x64
     layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
-                        tokens, args.workspace_mb << 20, flags=(args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0))
+                        tokens, args.workspace_mb << 20, flags=(args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
+                        | (args.shortk_mode << 16))
     y = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 

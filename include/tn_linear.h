@@ -61,6 +61,8 @@ extern "C" {
 #define TN_FLAG_MERGE_GROW     16   /* trade memory for speed: also contract parameter tensors at create time
                                        when that ADDS parameters, as long as the layer stays under a quarter
                                        of the dense matrix (e.g. a ring of 4 cores becomes two half-rings) */
+#define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
+                                       choice) */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
                                        bf16 steps (0 = library's choice): 3 = 128x256 and 8 = 256x128
                                        register-prefetch tiles, 9 = short-K store kernel, 12 = 256x256

@@ -807,22 +807,24 @@ constexpr size_t pipe_smem_bytes() {
 // is used anywhere, so the stores of one wave overlap the loads and MFMAs of the others.
 // Requires Kp == 64, aligned runs of 8 columns in the output (CMODE 1) and Cp % 128 == 0.
 // ---------------------------------------------------------------------------------------------
-template <int AMODE>
-__global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
+template <int AMODE, int TMW, int DBUF, int MINB>
+__global__ void __launch_bounds__(256, MINB) step_shortk_kernel(StepArgs a) {
+    // TMW = 32-row tiles per wave (1 or 2): the workgroup covers 4 * TMW * 32 / 2 ... rows, see below
     constexpr int LDP = 64 + 8;                          // padded row of the wave's LDS patch
-    __shared__ __attribute__((aligned(16))) bf16_t patch[4][64 * LDP];
+    constexpr int WROWS = TMW * 32;                      // rows per wave
+    __shared__ __attribute__((aligned(16))) bf16_t patch[4][WROWS * LDP];
     const bf16_t* A = static_cast<const bf16_t*>(a.A);
     const bf16_t* B = static_cast<const bf16_t*>(a.B);
     bf16_t* Out = static_cast<bf16_t*>(a.Out);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const uint32_t row0 = blockIdx.x * 128 + wm * 64;
+    const int wm = wave >> 1, wn = wave & 1;             // 2 x 2 waves: rows wm, 64-column half wn
+    const uint32_t row0 = blockIdx.x * (2 * WROWS) + wm * WROWS;
     bf16_t* sP = patch[wave];
 
-    // A fragments for the wave's 64 rows and all 4 k-steps
-    bf16x8 af[2][4];
+    // A fragments for the wave's rows and all 4 k-steps
+    bf16x8 af[TMW][4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < TMW; ++i) {
         uint32_t g = row0 + i * 32 + (lane & 31);
         int64_t base = -1;
         if (g < a.total_rows) {
@@ -848,16 +850,20 @@ __global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
             af[i][ks] = v;
         }
     }
-    // output row bases of the 8 rows this lane stores per iteration: row p*8 + lane/8
-    int64_t obase[8];
+    // output bases of the rows this lane stores per iteration (row p*8 + lane/8), in units of 8
+    // elements (every run of 8 columns is 16-byte aligned), so that they fit 32 bits
+    constexpr int NP = WROWS / 8;
+    uint32_t obase8[NP];
+    bool ovalid[NP];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
+    for (int p = 0; p < NP; ++p) {
         uint32_t g = row0 + p * 8 + (lane >> 3);
-        obase[p] = -1;
-        if (g < a.total_rows) {
+        ovalid[p] = g < a.total_rows;
+        obase8[p] = 0;
+        if (ovalid[p]) {
             uint32_t t = g / a.R;
             uint32_t r = g - t * a.R;
-            obase[p] = int64_t(t) * a.c_tok_stride + a.crow[r];
+            obase8[p] = uint32_t((int64_t(t) * a.c_tok_stride + a.crow[r]) >> 3);
         }
     }
     const int ncol_iters = a.Cp >> 7;
@@ -874,12 +880,16 @@ __global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
     // row tiles to fill the chip)
     const int it_step = gridDim.y;
     bf16x8 bcur[2][4], bnext[2][4];
-    if (int(blockIdx.y) < ncol_iters) load_b(blockIdx.y, bcur);
+    if (DBUF && int(blockIdx.y) < ncol_iters) load_b(blockIdx.y, bcur);
     for (int it = blockIdx.y; it < ncol_iters; it += it_step) {
-        if (it + it_step < ncol_iters) load_b(it + it_step, bnext);
-        floatx16 acc[2][2];
+        if (DBUF) {
+            if (it + it_step < ncol_iters) load_b(it + it_step, bnext);
+        } else {
+            load_b(it, bcur);
+        }
+        floatx16 acc[TMW][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TMW; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -887,13 +897,13 @@ __global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < TMW; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bcur[j][ks], af[i][ks], acc[i][j], 0, 0, 0);
         // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TMW; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -908,19 +918,21 @@ __global__ void __launch_bounds__(256, 2) step_shortk_kernel(StepArgs a) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int c = it * 128 + wn * 64 + (lane & 7) * 8;
         if (c < a.C) {
-            const int32_t coff = a.ccol[c];
+            const uint32_t coff8 = uint32_t(a.ccol[c]) >> 3;
 #pragma unroll
-            for (int p = 0; p < 8; ++p) {
+            for (int p = 0; p < NP; ++p) {
                 bf16x8 v = *reinterpret_cast<const bf16x8*>(sP + (p * 8 + (lane >> 3)) * LDP + (lane & 7) * 8);
-                if (obase[p] >= 0) *reinterpret_cast<bf16x8*>(Out + obase[p] + coff) = v;
+                if (ovalid[p]) *reinterpret_cast<bf16x8*>(Out + (int64_t(obase8[p] + coff8) << 3)) = v;
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        if (DBUF) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bcur[j][ks] = bnext[j][ks];
+                for (int ks = 0; ks < 4; ++ks) bcur[j][ks] = bnext[j][ks];
+        }
     }
 }
 
@@ -1496,14 +1508,32 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
             break;
         }
         case VAR_SHORTK: {
-            int64_t row_tiles = (rows + 127) / 128;
+            // forms (tuning override in flag bits 16..19, value = form + 1): 0 = 64 rows per wave with
+            // double-buffered packed fragments, 1 = 64 rows single-buffered, 2 = 32 rows single-buffered
+            if (tokens * s.plan.c_tok_stride >= (int64_t(1) << 35)) {
+                // output offsets would not fit the kernel's 32-bit (x8) row bases: use the tiled kernel
+                int rc = launch_pipe<4, 1, 2, 4, 1, 2>(s, a, rows, st);
+                if (rc != TN_OK) return rc;
+                break;
+            }
+            // measured: 32 rows per wave at 4 workgroups per CU streams best when A is a plain matrix
+            // (4.7 TB/s stored); with a gathered A the 64-row double-buffered form is slightly ahead
+            int mode = (h->flags >> 16) & 0xf;
+            mode = mode ? mode - 1 : (s.amode == 0 ? 2 : 0);
+            const int wrows = mode == 2 ? 32 : 64;
+            int64_t row_tiles = (rows + 2 * wrows - 1) / (2 * wrows);
             int col_iters = s.Cp / 128;
             int groups = int(std::min<int64_t>(col_iters, std::max<int64_t>(1, 1024 / row_tiles)));
             dim3 g{uint32_t(row_tiles), uint32_t(groups)};
-            if (s.amode == 0)
-                hipLaunchKernelGGL(step_shortk_kernel<0>, g, dim3(256), 0, st, a);
+            using k_t = void (*)(StepArgs);
+            k_t k;
+            if (mode == 2)
+                k = s.amode == 0 ? step_shortk_kernel<0, 1, 0, 4> : step_shortk_kernel<1, 1, 0, 4>;
+            else if (mode == 1)
+                k = s.amode == 0 ? step_shortk_kernel<0, 2, 0, 3> : step_shortk_kernel<1, 2, 0, 3>;
             else
-                hipLaunchKernelGGL(step_shortk_kernel<1>, g, dim3(256), 0, st, a);
+                k = s.amode == 0 ? step_shortk_kernel<0, 2, 1, 2> : step_shortk_kernel<1, 2, 1, 2>;
+            hipLaunchKernelGGL(k, g, dim3(256), 0, st, a);
             break;
         }
         case VAR_PIPE_256x128: {
