@@ -288,3 +288,34 @@ def test_fused_small_steps(tokens):
         y_unfused = run_layer(spec, ts, x)
         assert O.rel_max_err(y, ref) <= TOL["bf16"], (n, tokens)
         assert O.rel_max_err(y_unfused, ref) <= TOL["bf16"], (n, tokens)
+
+
+def test_shared_caller_workspace(dense_w):
+    """Several handles keep their intermediates in one caller-owned block (run one after the
+    other on one stream); results equal those of handles with their own workspace."""
+    spec1, ts1, w1 = dense_w(1)
+    spec2, ts2, w2 = dense_w(2)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    layers = []
+    for spec, ts in ((spec1, ts1), (spec2, ts2), (spec1, ts1)):
+        dev = [to_dev(t, spec.dtype) for t in ts]
+        layers.append(tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks,
+                                  dev, 200, workspace=ws))
+        assert layers[-1].query(tn.TN_QUERY_WORKSPACE_BYTES) == 0        # nothing allocated by the library
+    for tokens in (1, 150):
+        x = wl.make_x(spec1, tokens, 1)
+        xd = to_dev(x, "bf16")
+        y1 = to_host(layers[0](xd))
+        y2 = to_host(layers[1](xd))
+        y3 = to_host(layers[2](xd))
+        assert O.rel_max_err(y1, O.apply_linear(w1, x)) <= TOL["bf16"]
+        assert O.rel_max_err(y2, O.apply_linear(w2, x)) <= TOL["bf16"]
+        assert np.array_equal(y1, y3)
+    for layer in layers:
+        layer.close()
+    # a block that cannot hold one token's intermediates is refused
+    tiny = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(tn.TNLinearError) as e:
+        tn.TNLinear(spec1.format, tn.TN_DTYPE_BF16, spec1.out_modes, spec1.in_modes, spec1.ranks,
+                    [to_dev(t, "bf16") for t in ts1], 8, workspace=tiny)
+    assert e.value.status == -1
