@@ -204,6 +204,8 @@ def main() -> int:
     ap.add_argument("--shortk-mode", type=int, default=0, help="tuning override of the short-K kernel (0 = library choice, 1..3 = form 0..2)")
     ap.add_argument("--merge-grow", action="store_true",
                     help="allow create-time merges that add parameters (up to a quarter of the dense matrix)")
+    ap.add_argument("--no-pair-chain", action="store_true",
+                    help="run a two-step train as two launches (intermediate in the workspace)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -236,7 +238,7 @@ def main() -> int:
     del x64
     layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
                         tokens, args.workspace_mb << 20, flags=(args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
-                        | (args.shortk_mode << 16))
+                        | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0))
     y = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 
@@ -272,18 +274,29 @@ def main() -> int:
     torch.cuda.synchronize()
     layer.profile(False)
     per_step = []
+    reads = [layer.profile_read(s) for s in range(n_steps)]
     for s in range(n_steps):
-        ms, launches = layer.profile_read(s)
+        ms, launches = reads[s]
+        if launches == 0:            # ran inside the previous step's launch
+            per_step.append({"step": s, "rows_per_token": q(s, 0), "K": q(s, 1), "cols": q(s, 2),
+                             "ms_per_forward": 0.0, "launches_per_forward": 0, "fused_into_previous": True})
+            continue
         sec = ms * 1e-3
-        nbytes = (step_io_bytes[s] * tokens + step_param_bytes[s] * (launches // args.steps)) * args.steps
+        fused = s + 1 < n_steps and reads[s + 1][1] == 0
+        flops_s = step_flops[s] + (step_flops[s + 1] if fused else 0)
+        # one launch for both steps: it reads the first step's input and writes the second step's
+        # output; the intermediate never reaches memory
+        io_s = 2 * (q(s, 0) * q(s, 1) + q(s + 1, 0) * q(s + 1, 2)) if fused else step_io_bytes[s]
+        par_s = step_param_bytes[s] + (step_param_bytes[s + 1] if fused else 0)
+        nbytes = (io_s * tokens + par_s * (launches // args.steps)) * args.steps
         per_step.append({
             "step": s, "rows_per_token": q(s, 0), "K": q(s, 1), "cols": q(s, 2), "kernel_variant": q(s, 5),
             "ms_per_forward": ms / args.steps, "launches_per_forward": launches // args.steps,
             "avg_launch_us": 1e3 * ms / max(1, launches),
-            "tflops": step_flops[s] * tokens * args.steps / sec / 1e12 if sec > 0 else 0.0,
+            "tflops": flops_s * tokens * args.steps / sec / 1e12 if sec > 0 else 0.0,
             "algorithmic_GBps": nbytes / sec / 1e9 if sec > 0 else 0.0,
-            "flop_per_byte": step_flops[s] / step_io_bytes[s],
-            "fused_with_next": bool(q(s, 6))})
+            "flop_per_byte": flops_s / io_s,
+            "fused_with_next": fused})
     dom = max(range(n_steps), key=lambda s: per_step[s]["ms_per_forward"])
     ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if per_step[dom]["flop_per_byte"] >= ridge:
@@ -292,8 +305,14 @@ def main() -> int:
         roof = {"bound": "hbm", "achieved": per_step[dom]["algorithmic_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(args, dom)
-    roof["kernel"] = (f"contraction step {dom}: rows {q(dom, 0)} x K {q(dom, 1)} x cols {q(dom, 2)} per token, "
-                      f"{per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge of {ridge:.0f}")
+    if per_step[dom]["fused_with_next"]:
+        roof["kernel"] = (f"contraction steps {dom} and {dom + 1} in one launch (rows {q(dom, 0)} x K {q(dom, 1)} x cols "
+                          f"{q(dom, 2)}, then rows {q(dom + 1, 0)} x K {q(dom + 1, 1)} x cols {q(dom + 1, 2)} per token; "
+                          f"intermediate in registers), {per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge "
+                          f"of {ridge:.0f}")
+    else:
+        roof["kernel"] = (f"contraction step {dom}: rows {q(dom, 0)} x K {q(dom, 1)} x cols {q(dom, 2)} per token, "
+                          f"{per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge of {ridge:.0f}")
     roof["avg_launch_us"] = per_step[dom]["avg_launch_us"]
     roof["also_tflops"] = per_step[dom]["tflops"]
     roof["also_GBps"] = per_step[dom]["algorithmic_GBps"]

@@ -61,6 +61,8 @@ extern "C" {
 #define TN_FLAG_MERGE_GROW     16   /* trade memory for speed: also contract parameter tensors at create time
                                        when that ADDS parameters, as long as the layer stays under a quarter
                                        of the dense matrix (e.g. a ring of 4 cores becomes two half-rings) */
+#define TN_FLAG_NO_PAIR_CHAIN   32   /* never run a two-step plan as one chained launch (see TN_QUERY_PAIR_CHAINABLE):
+                                       always two launches with the intermediate in the workspace */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
@@ -79,13 +81,18 @@ extern "C" {
 #define TN_QUERY_OUT_FEATURES       7   /* M */
 #define TN_QUERY_IN_FEATURES        8   /* N */
 #define TN_QUERY_NUM_MERGES         9   /* parameter-tensor pairs contracted into one at create time */
+#define TN_QUERY_PAIR_CHAINABLE    10   /* 1 if the plan is a short-K step feeding a long-K step over a bond of 64
+                                           (a train whose end cores were merged into their neighbours): from
+                                           256 tokens on, forward runs both steps as one launch that keeps the
+                                           intermediate in registers */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=
                                              n_tensors name tensors merged at create time),
                                            5 kernel variant chosen (0 plain FMA, 2 narrow 256x32 tile, else
                                              the ids listed at TN_FLAG_VARIANT_SHIFT),
-                                           6 1 if this step and the next run as one fused launch */
+                                           6 1 if this step and the next run as one fused launch, 2 if they
+                                             do so from 256 tokens on (chained pair kernel) */
 
 typedef struct tn_linear_s* tn_linear_t;
 

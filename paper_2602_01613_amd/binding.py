@@ -22,6 +22,7 @@ TN_FLAG_NO_MERGE = 2
 TN_FLAG_NO_SPLIT_K = 4
 TN_FLAG_FUSE_SMALL_STEPS = 8
 TN_FLAG_MERGE_GROW = 16
+TN_FLAG_NO_PAIR_CHAIN = 32
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -32,6 +33,7 @@ TN_QUERY_MAX_INTERMEDIATE = 6
 TN_QUERY_OUT_FEATURES = 7
 TN_QUERY_IN_FEATURES = 8
 TN_QUERY_NUM_MERGES = 9
+TN_QUERY_PAIR_CHAINABLE = 10
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (

@@ -1241,6 +1241,204 @@ __global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Chained pair kernel: a short-K step followed by a long-K step whose K is (rows of the first
+// step) x (a bond of 64), the shape a tensor train takes once its end cores are contracted into
+// their neighbours (Section 3.5: fuse core contractions, specialise for shared ranks):
+//     Z[t][j][a][b] = sum_k  X[t][a*64 + k] * B0[j*64 + b][k]          K0 = 64, bond b < 64
+//     Y[t][yrow[j] + ycol[c]] = sum_{a, b} Z[t][j][a][b] * B1[c][a*64 + b]      c < C1 <= 128
+// Unfused, Z (A*J*64 values per token) is written to and read back from HBM and both launches are
+// bound by that traffic. Here Z never leaves the registers: a workgroup owns 32 tokens and 8
+// values of j (two per wave) and walks over a. For one a, a wave computes Z^T[b][t] for its two j
+// with the packed tensor of the first step as the row operand (kept in registers for the whole
+// walk) and the tokens as MFMA columns; the result lands in the accumulator layout (lane: token
+// l%32, b = 8*(v/4) + 4*(l/32) + v%4), which after rounding to bf16 IS the column operand of the
+// second contraction when that step's packed tensor is stored with the same permutation of b
+// inside each k-step of 16 (done once at create time by pair_repack_kernel). Per a the workgroup
+// streams a 16 KB slice of B1 and 4 KB of X into a ring of LDS stages with direct-to-LDS loads.
+// The 32 x C1 x 8 results of the workgroup are transposed through LDS and stored as 16-byte
+// pieces (8 consecutive j). Workgroups that share a token tile run back to back on one XCD, so
+// that their reads of X and their pieces of the same output lines meet in that XCD's L2.
+// ---------------------------------------------------------------------------------------------
+struct PairArgs {
+    const void* X;
+    void* Y;
+    const void* B0;        // first step's packed tensor, fragment-major [J*64][64]
+    const void* B1f;       // second step's packed tensor in the chained layout (pair_repack_kernel)
+    const int32_t* yrow;   // output offset of j (J entries, aligned runs of 8)
+    const int32_t* ycol;   // output offset of c (C1 entries, multiples of 8)
+    int64_t N, M;          // elements per token of X and Y
+    int32_t tokens, A, J, C1;
+    int32_t n_tok_tiles, n_jsets;
+};
+
+// B1f[((a*16 + ct*4 + s)*64 + l)*8 + e] = B1[c = 32*ct + l%32][k = a*64 + 16*s + 8*(e/4) + 4*(l/32) + e%4]
+__global__ void __launch_bounds__(256) pair_repack_kernel(const bf16_t* src, bf16_t* dst, int A, int nks, int Cp) {
+    int64_t total = int64_t(A) * 8192;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
+        int e = int(i & 7), l = int(i >> 3) & 63, blk = int(i >> 9) & 15;
+        int a = int(i >> 13);
+        int c = 32 * (blk >> 2) + (l & 31);
+        int k = a * 64 + 16 * (blk & 3) + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+        dst[i] = c < Cp ? src[bfrag_offset(c, k, nks)] : bf16_t(0.f);      // columns past Cp do not exist
+    }
+}
+
+__global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
+    constexpr int NS = 4, L = 5;                       // ring stages; direct-to-LDS loads per wave and stage
+    constexpr int STAGE_BYTES = 20 * 1024, X_OFF = 16 * 1024;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int tok_tile = (slot / p.n_jsets) * 8 + xcd;
+    const int jset = slot % p.n_jsets;
+    if (tok_tile >= p.n_tok_tiles) return;
+    const int t0 = tok_tile * 32;
+
+    const bf16_t* X = static_cast<const bf16_t*>(p.X);
+    const bf16_t* B0 = static_cast<const bf16_t*>(p.B0);
+    const bf16_t* B1f = static_cast<const bf16_t*>(p.B1f);
+    bf16_t* Y = static_cast<bf16_t*>(p.Y);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j0 = jset * 8 + wave * 2;
+    const int A = p.A;
+
+    // the wave's rows of the first packed tensor: [jj][32-row half of the bond][k-step]
+    bf16x8 p0[2][2][4];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                p0[jj][rt][s] = *reinterpret_cast<const bf16x8*>(B0 + (int64_t((j0 + jj) * 2 + rt) * 4 + s) * 512 + lane * 8);
+
+    // direct-to-LDS sources: wave w brings blocks w, w+4, w+8, w+12 of the B1 slice and k-step w of X
+    const int tl = min(t0 + (lane & 31), p.tokens - 1);             // rows past the end repeat the last token
+    const bf16_t* x_src = X + int64_t(tl) * p.N + 16 * wave + 8 * (lane >> 5);
+    const bf16_t* b_src = B1f + lane * 8;
+    auto issue = [&](int a, int stage) {
+        unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)(b_src + (int64_t(a) * 16 + wave + 4 * q) * 512),
+                (void __attribute__((address_space(3)))*)(sbase + (wave + 4 * q) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(x_src + int64_t(a) * 64),
+            (void __attribute__((address_space(3)))*)(sbase + X_OFF + wave * 1024), 16, 0, 0);
+    };
+    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform
+        if (n <= 0) wait_vmcnt<0>();
+        else if (n == 1) wait_vmcnt<L>();
+        else wait_vmcnt<2 * L>();
+    };
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[jj][ct][v] = 0.f;
+
+    int issued = 0;
+    for (; issued < NS - 1 && issued < A; ++issued) issue(issued, issued);
+    wait_outstanding_tiles(min(issued - 1, NS - 2));     // tile 0 has landed
+    __syncthreads();
+    bf16x8 xb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(dyn_smem + X_OFF + s * 1024 + lane * 16);
+
+    for (int a = 0; a < A; ++a) {
+        if (a + 1 < A) wait_outstanding_tiles(issued - (a + 2));   // tile a+1 has landed
+        __syncthreads();       // everyone is done with tile a-1: its stage may be refilled
+        if (issued < A) {
+            issue(issued, issued % NS);
+            ++issued;
+        }
+        const unsigned char* scur = dyn_smem + (a % NS) * STAGE_BYTES;
+        const unsigned char* snxt = dyn_smem + ((a + 1) % NS) * STAGE_BYTES;
+        bf16x8 p1[4][4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                p1[ct][s] = *reinterpret_cast<const bf16x8*>(scur + (ct * 4 + s) * 1024 + lane * 16);
+        // first contraction: Z^T[b][t] for the wave's two j
+        floatx16 z[2][2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[jj][rt][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt)
+                    z[jj][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0[jj][rt][s], xb[s], z[jj][rt], 0, 0, 0);
+        // registers 8*(s%2) .. +7 of half s/2 are the 8 values this lane supplies to k-step s
+        bf16x8 zb[2][4];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) zb[jj][s][e] = bf16_t(z[jj][s >> 1][8 * (s & 1) + e]);
+        bf16x8 xn[4];
+        if (a + 1 < A) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) xn[s] = *reinterpret_cast<const bf16x8*>(snxt + X_OFF + s * 1024 + lane * 16);
+        }
+        // second contraction: Y^T[c][t] += B1[c][(a, b)] Z^T[b][t]
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct)
+                    acc[jj][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1[ct][s], zb[jj][s], acc[jj][ct], 0, 0, 0);
+        if (a + 1 < A) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) xb[s] = xn[s];
+        }
+    }
+    __syncthreads();
+
+    // ---- epilogue: lane l, register v of acc[jj][ct] is token l%32, c = 32*ct + 8*(v/4) + 4*(l/32) + v%4.
+    //      LDS holds [32 tokens][128 c] pieces of 16 bytes (the 8 j of the workgroup), the piece of
+    //      (t, c) at position c ^ t of row t so that neither the 4-byte writes nor the 16-byte reads
+    //      pile up on a bank.
+    {
+        const int t = lane & 31;
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int c = 32 * ct + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                bf16x2 pr;
+                pr[0] = bf16_t(acc[0][ct][v]);
+                pr[1] = bf16_t(acc[1][ct][v]);
+                *reinterpret_cast<bf16x2*>(dyn_smem + (t * 128 + (c ^ t)) * 16 + wave * 4) = pr;
+            }
+    }
+    __syncthreads();
+    const int yj = p.yrow[jset * 8];
+#pragma unroll 4
+    for (int e = tid; e < 32 * 128; e += 256) {
+        int t = e >> 7, c = e & 127;
+        if (t0 + t >= p.tokens || c >= p.C1) continue;
+        bf16x8 v = *reinterpret_cast<const bf16x8*>(dyn_smem + (t * 128 + (c ^ t)) * 16);
+        *reinterpret_cast<bf16x8*>(Y + int64_t(t0 + t) * p.M + p.ycol[c] + yj) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 enum Variant : int {
@@ -1281,6 +1479,10 @@ struct tn_linear_s {
     bool owns_workspace = true;
     int device = 0;
     bool profiling = false;
+    // chained pair kernel (two-step plans of the train shape): second packed tensor in its layout
+    bool pair = false;
+    void* pair_b1f = nullptr;
+    int64_t pair_min_tokens = 0;
     struct ProfRec { int step; hipEvent_t start, stop; };
     std::vector<ProfRec> prof;
 };
@@ -1306,6 +1508,7 @@ void free_handle(tn_linear_s* h) {
         if (s.packed) (void)hipFree(s.packed);
         if (s.tables) (void)hipFree(s.tables);
     }
+    if (h->pair_b1f) (void)hipFree(h->pair_b1f);
     if (h->owns_workspace) {
         for (void* w : h->ws)
             if (w) (void)hipFree(w);
@@ -1617,6 +1820,54 @@ int launch_fused2(const DevStep& s1, const DevStep& s2, const void* A, void* Out
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
+// Token count from which the chained pair kernel replaces the two separate launches (below it a
+// launch has too few workgroups: 8 per 32 tokens).
+constexpr int64_t kPairMinTokens = 256;
+constexpr size_t kPairSmemBytes = 4 * 20 * 1024;
+
+int prepare_pair(tn_linear_s* h, hipStream_t st) {
+    if ((h->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS)) || !tn::pair_chainable(h->plan)) return TN_OK;
+    const DevStep& s0 = h->steps[0];
+    const DevStep& s1 = h->steps[1];
+    if (s0.Kp != 64 || s0.Cp < s0.plan.C || s1.Kp != s1.plan.K) return TN_OK;
+    const int A = int(s0.plan.R);
+    if (hipMalloc(&h->pair_b1f, size_t(A) * 8192 * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
+    h->packed_bytes += int64_t(A) * 8192 * int64_t(sizeof(bf16_t));
+    uint32_t blocks = uint32_t(std::min<int64_t>((int64_t(A) * 8192 + 255) / 256, 4096));
+    hipLaunchKernelGGL(pair_repack_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const bf16_t*>(s1.packed),
+                       static_cast<bf16_t*>(h->pair_b1f), A, s1.Kp >> 4, s1.Cp);
+    if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            int(kPairSmemBytes)) != hipSuccess)
+        return TN_ERR_HIP;
+    h->pair = true;
+    h->pair_min_tokens = kPairMinTokens;
+    return TN_OK;
+}
+
+int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+    const DevStep& s0 = h->steps[0];
+    const DevStep& s1 = h->steps[1];
+    PairArgs p;
+    p.X = x;
+    p.Y = y;
+    p.B0 = s0.packed;
+    p.B1f = h->pair_b1f;
+    p.yrow = s1.crow;
+    p.ycol = s1.ccol;
+    p.N = h->plan.N;
+    p.M = h->plan.M;
+    p.tokens = int32_t(tokens);
+    p.A = int32_t(s0.plan.R);
+    p.J = int32_t(s1.plan.R);
+    p.C1 = int32_t(s1.plan.C);
+    p.n_tok_tiles = int32_t((tokens + 31) / 32);
+    p.n_jsets = p.J / 8;
+    int64_t grid = int64_t((p.n_tok_tiles + 7) / 8 * 8) * p.n_jsets;
+    hipLaunchKernelGGL(step_pair_kernel, dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
 int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
     switch (what) {
         case TN_QUERY_PARAM_COUNT: *value = p.params; return TN_OK;
@@ -1626,6 +1877,7 @@ int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
         case TN_QUERY_OUT_FEATURES: *value = p.M; return TN_OK;
         case TN_QUERY_IN_FEATURES: *value = p.N; return TN_OK;
         case TN_QUERY_NUM_MERGES: *value = int64_t(p.merges.size()); return TN_OK;
+        case TN_QUERY_PAIR_CHAINABLE: *value = tn::pair_chainable(p) ? 1 : 0; return TN_OK;
         default: break;
     }
     if (what >= TN_QUERY_STEP_BASE) {
@@ -1911,6 +2163,12 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         release_temps();
     }
     plan_fusion(h);
+    rc = prepare_pair(h, st);
+    if (rc != TN_OK) {
+        (void)hipStreamSynchronize(st);
+        free_handle(h);
+        return rc;
+    }
     // workspace: two ping-pong buffers, each chunk_tokens * max_intermediate elements, and the
     // partial-sum buffer of the split-K kernel; allocated here, or carved out of the caller's block
     int64_t per_token = h->plan.max_intermediate * h->elt;
@@ -1991,6 +2249,26 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
     const char* xb = static_cast<const char*>(x);
     char* yb = static_cast<char*>(y);
     size_t ns = h->steps.size();
+    if (h->pair && tokens >= h->pair_min_tokens) {
+        // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
+        const int64_t pass = int64_t(1) << 24;
+        for (int64_t t0 = 0; t0 < tokens; t0 += pass) {
+            int64_t nt = std::min(pass, tokens - t0);
+            tn_linear_s::ProfRec rec{0, nullptr, nullptr};
+            if (h->profiling) {
+                if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess)
+                    return TN_ERR_HIP;
+                (void)hipEventRecord(rec.start, st);
+            }
+            int rc = launch_pair(h, xb + t0 * h->plan.N * h->elt, yb + t0 * h->plan.M * h->elt, nt, st);
+            if (h->profiling) {
+                (void)hipEventRecord(rec.stop, st);
+                h->prof.push_back(rec);
+            }
+            if (rc != TN_OK) return rc;
+        }
+        return TN_OK;
+    }
     for (int64_t t0 = 0; t0 < tokens; t0 += h->chunk_tokens) {
         int64_t nt = std::min(h->chunk_tokens, tokens - t0);
         for (size_t s = 0; s < ns; ++s) {
@@ -2063,7 +2341,7 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
     if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 == 6) {
         int s = (what - TN_QUERY_STEP_BASE) / 10;
         if (s >= int(h->steps.size())) return TN_ERR_INVALID_ARG;
-        *value = h->steps[size_t(s)].fuse_next ? 1 : 0;
+        *value = h->steps[size_t(s)].fuse_next ? 1 : ((h->pair && s == 0) ? 2 : 0);
         return TN_OK;
     }
     return plan_value(h->plan, what, value);

@@ -599,6 +599,27 @@ inline int merge_pass(Plan* p, double budget_elems = 0) {
     return made;
 }
 
+// Is the plan a short-K step feeding a long-K step over a bond of 64, laid out the way the chained
+// pair kernel walks it?  Z[t][j][a][b]: rows a of step 0 (plain x, K0 = 64), columns (j, b) of
+// step 0 with b < 64 innermost; step 1 reads rows j with K = (a, b) and has at most 128 columns;
+// the output takes 8 consecutive j as one aligned 16-byte piece. Checked on the tables themselves.
+inline bool pair_chainable(const Plan& p) {
+    if (p.dtype != TN_DTYPE_BF16 || p.steps.size() != 2) return false;
+    const Step& s0 = p.steps[0];
+    const Step& s1 = p.steps[1];
+    const int64_t B = 64;
+    if (!s0.a_plain || s0.K != 64 || s0.C % B) return false;
+    const int64_t J = s0.C / B, A = s0.R;
+    if (J % 8 || A < 1 || A > (int64_t(1) << 20)) return false;
+    if (!s1.a_plain || s1.R != J || s1.K != A * B || s1.C > 128) return false;
+    if (s0.c_tok_stride != J * A * B || s0.a_tok_stride != A * 64) return false;
+    for (int64_t r = 0; r < A; ++r)
+        if (s0.crow[size_t(r)] != r * B) return false;
+    for (int64_t c = 0; c < s0.C; ++c)
+        if (s0.ccol[size_t(c)] != (c / B) * (A * B) + c % B) return false;
+    return s1.r_vec == 8;
+}
+
 inline int make_plan(const tn_linear_desc* d, Plan* p) {
     int rc = build_network(d, p);
     if (rc != TN_OK) return rc;

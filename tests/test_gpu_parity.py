@@ -319,3 +319,52 @@ def test_shared_caller_workspace(dense_w):
         tn.TNLinear(spec1.format, tn.TN_DTYPE_BF16, spec1.out_modes, spec1.in_modes, spec1.ranks,
                     [to_dev(t, "bf16") for t in ts1], 8, workspace=tiny)
     assert e.value.status == -1
+
+
+PAIR_CASES = [
+    # (out modes, in modes, ranks): trains whose end bonds have full rank, so the four cores become two
+    # tensors at create time and the plan is a short-K step feeding a long-K step over a bond of 64
+    ((6, 8, 8, 8), (8, 2, 8, 8), (1, 48, 64, 64, 1)),       # A = 16, 48 output columns per j (ragged c tile)
+    ((8, 4, 8, 8), (8, 2, 8, 8), (1, 64, 64, 64, 1)),       # A = 16, 32 columns
+    ((8, 16, 4, 4), (3, 5, 8, 8), (1, 24, 64, 32, 1)),      # A = 15, 128 columns, 16 j (two j sets)
+]
+
+
+@pytest.mark.parametrize("case", range(len(PAIR_CASES)))
+def test_chained_pair_kernel_small(case):
+    """The chained pair kernel (both steps of a two-tensor train in one launch, intermediate in
+    registers) against the oracle and against the two separate launches, at token counts with
+    ragged 32-token tiles."""
+    om, im, rk = PAIR_CASES[case]
+    spec = _spec(tn.TN_FORMAT_TT, "bf16", om, im, rk)
+    ts = _rand_layer(spec, 700 + case)
+    assert tn.plan_query(spec.format, tn.TN_DTYPE_BF16, om, im, rk, tn.TN_QUERY_PAIR_CHAINABLE) == 1
+    w = O.dense_weight(spec.format, ts, len(om))
+    for tokens in (256, 257, 1000):
+        x = wl.round_to_dtype(np.random.default_rng(case + tokens).standard_normal((tokens, spec.N)), "bf16")
+        ref = O.apply_linear(w, x)
+        layer = make_layer(spec, ts, tokens)
+        assert layer.query(tn.TN_QUERY_STEP_BASE + 6) == 2
+        yd = layer(to_dev(x, "bf16"))
+        torch.cuda.synchronize()
+        assert torch.equal(yd, layer(to_dev(x, "bf16")))          # same bits on a second call
+        layer.close()
+        y = to_host(yd)
+        y_two = run_layer(spec, ts, x, flags=tn.TN_FLAG_NO_PAIR_CHAIN)
+        assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
+        assert O.rel_max_err(y_two, ref) <= TOL["bf16"], (case, tokens)
+        # both round the intermediate to bf16 once: they differ by summation order only
+        assert O.rel_max_err(y, y_two) <= 1e-2, (case, tokens)
+
+
+@pytest.mark.parametrize("tokens", [256, 300, 2049])
+def test_chained_pair_kernel_q_proj(tokens, dense_w):
+    spec, ts, w = dense_w(1)
+    x = wl.make_x(spec, tokens, 1)
+    layer = make_layer(spec, ts, tokens)
+    assert layer.query(tn.TN_QUERY_PAIR_CHAINABLE) == 1
+    y = to_host(layer(to_dev(x, "bf16")))
+    layer.close()
+    assert O.rel_max_err(y, O.apply_linear(w, x)) <= TOL["bf16"]
+    y_two = run_layer(spec, ts, x, flags=tn.TN_FLAG_NO_PAIR_CHAIN)
+    assert O.rel_max_err(y, y_two) <= 1e-2

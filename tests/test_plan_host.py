@@ -156,6 +156,26 @@ def test_create_time_merging():
     assert _q(small, tn.TN_QUERY_NUM_MERGES, 0) == 0
 
 
+def test_pair_chainable_plans():
+    """Which plans qualify for the chained pair kernel: two-tensor trains over a bond of 64 with a
+    64-long first contraction, and nothing else."""
+    q = lambda fmt, om, im, rk, flags=0: tn.plan_query(fmt, tn.TN_DTYPE_BF16, om, im, rk,
+                                                        tn.TN_QUERY_PAIR_CHAINABLE, flags=flags)
+    spec, _ = wl.baseline_spec(1)
+    assert q(spec.format, spec.out_modes, spec.in_modes, spec.ranks) == 1
+    assert q(spec.format, spec.out_modes, spec.in_modes, spec.ranks, tn.TN_FLAG_NO_MERGE) == 0     # four steps
+    assert tn.plan_query(spec.format, tn.TN_DTYPE_F32, spec.out_modes, spec.in_modes, spec.ranks,
+                         tn.TN_QUERY_PAIR_CHAINABLE) == 0                                        # bf16 only
+    assert q(tn.TN_FORMAT_TT, (6, 8, 8, 8), (8, 2, 8, 8), (1, 48, 64, 64, 1)) == 1
+    assert q(tn.TN_FORMAT_TT, (8, 16, 4, 4), (3, 5, 8, 8), (1, 24, 64, 32, 1)) == 1
+    assert q(tn.TN_FORMAT_TT, (8, 16, 8, 8), (8, 10, 8, 8), (1, 64, 32, 64, 1)) == 0              # bond of 32
+    assert q(tn.TN_FORMAT_TT, (8, 16, 4, 8), (8, 10, 4, 8), (1, 64, 64, 64, 1)) == 0              # K0 = 32
+    assert q(tn.TN_FORMAT_TT, (8, 10, 8, 8), (8, 16, 8, 8), (1, 64, 64, 64, 1)) == 0              # other order wins
+    for i in (2, 3):
+        s, _ = wl.baseline_spec(i)
+        assert q(s.format, s.out_modes, s.in_modes, s.ranks) == 0
+
+
 def test_growing_merges_half_ring():
     # TR down_proj with TN_FLAG_MERGE_GROW: cores (4,1) and (2,3) are contracted at create time
     # (23.6 M parameters, under a quarter of the dense 131 M) and the chain is two steps,
