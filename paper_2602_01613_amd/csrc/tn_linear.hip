@@ -16,6 +16,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/tn_linear.h"
@@ -1283,8 +1284,9 @@ __global__ void __launch_bounds__(256) pair_repack_kernel(const bf16_t* src, bf1
     }
 }
 
+template <int NS>
 __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
-    constexpr int NS = 4, L = 5;                       // ring stages; direct-to-LDS loads per wave and stage
+    constexpr int L = 5;                               // NS ring stages; L direct-to-LDS loads per wave and stage
     constexpr int STAGE_BYTES = 20 * 1024, X_OFF = 16 * 1024;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
 
@@ -1329,10 +1331,12 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
             (const void __attribute__((address_space(1)))*)(x_src + int64_t(a) * 64),
             (void __attribute__((address_space(3)))*)(sbase + X_OFF + wave * 1024), 16, 0, 0);
     };
-    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform
+    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform, at most NS - 2
         if (n <= 0) wait_vmcnt<0>();
         else if (n == 1) wait_vmcnt<L>();
-        else wait_vmcnt<2 * L>();
+        else if (n == 2 || NS <= 4) wait_vmcnt<2 * L>();
+        else if (n == 3 || NS <= 5) wait_vmcnt<3 * L>();
+        else wait_vmcnt<4 * L>();
     };
 
     floatx16 acc[2][4];
@@ -1351,8 +1355,40 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(dyn_smem + X_OFF + s * 1024 + lane * 16);
 
-    for (int a = 0; a < A; ++a) {
-        if (a + 1 < A) wait_outstanding_tiles(issued - (a + 2));   // tile a+1 has landed
+    // first contraction for one j: Z^T[b][t], two 32-row halves of the bond
+    auto contract0 = [&](const bf16x8 (&w)[2][4], const bf16x8 (&x)[4], floatx16 (&z)[2]) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[rt][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+                z[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[rt][s], x[s], z[rt], 0, 0, 0);
+    };
+    // second contraction for one j: Y^T[c][t] += B1[c][(a, b)] Z^T[b][t]. Registers 8*(s%2) .. +7 of
+    // half s/2 of z are the 8 values this lane supplies to k-step s.
+    auto contract1 = [&](const bf16x8 (&w)[4][4], const floatx16 (&z)[2], floatx16 (&y)[4]) {
+        bf16x8 zb[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) zb[s][e] = bf16_t(z[s >> 1][8 * (s & 1) + e]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+                y[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ct][s], zb[s], y[ct], 0, 0, 0);
+    };
+
+    // software pipeline over (a, j): the first contraction of the next unit is issued before the
+    // second contraction of the current one, so that reading back and rounding Z overlaps MFMAs
+    floatx16 z0[2], z1[2];
+    contract0(p0[0], xb, z0);
+    auto iteration = [&](int a, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value;
+        if (!LAST) wait_outstanding_tiles(issued - (a + 2));       // tile a+1 has landed
         __syncthreads();       // everyone is done with tile a-1: its stage may be refilled
         if (issued < A) {
             issue(issued, issued % NS);
@@ -1366,47 +1402,32 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 p1[ct][s] = *reinterpret_cast<const bf16x8*>(scur + (ct * 4 + s) * 1024 + lane * 16);
-        // first contraction: Z^T[b][t] for the wave's two j
-        floatx16 z[2][2];
+        // the scheduler would otherwise sink each LDS read next to its first use and expose the LDS
+        // latency 16 times per iteration
+        __builtin_amdgcn_sched_barrier(0);
+        contract0(p0[1], xb, z1);
+        if (!LAST) {
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) z[jj][rt][v] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                for (int rt = 0; rt < 2; ++rt)
-                    z[jj][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0[jj][rt][s], xb[s], z[jj][rt], 0, 0, 0);
-        // registers 8*(s%2) .. +7 of half s/2 are the 8 values this lane supplies to k-step s
-        bf16x8 zb[2][4];
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) zb[jj][s][e] = bf16_t(z[jj][s >> 1][8 * (s & 1) + e]);
-        bf16x8 xn[4];
-        if (a + 1 < A) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) xn[s] = *reinterpret_cast<const bf16x8*>(snxt + X_OFF + s * 1024 + lane * 16);
+            for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(snxt + X_OFF + s * 1024 + lane * 16);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // second contraction: Y^T[c][t] += B1[c][(a, b)] Z^T[b][t]
+        contract1(p1, z0, acc[0]);
+        if (!LAST) contract0(p0[0], xb, z0);
+        contract1(p1, z1, acc[1]);
+        // keep the accumulators in the accumulation registers across the back edge (the register
+        // allocator otherwise parks some of them in ordinary registers and copies them every
+        // iteration)
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int ct = 0; ct < 4; ++ct)
-                    acc[jj][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1[ct][s], zb[jj][s], acc[jj][ct], 0, 0, 0);
-        if (a + 1 < A) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) xb[s] = xn[s];
+            for (int ct = 0; ct < 4; ++ct) asm volatile("" : "+a"(acc[jj][ct]));
+        if (!LAST) {
+            asm volatile("" : "+a"(z0[0]));
+            asm volatile("" : "+a"(z0[1]));
         }
-    }
+    };
+    for (int a = 0; a + 1 < A; ++a) iteration(a, std::false_type());
+    iteration(A - 1, std::true_type());
     __syncthreads();
 
     // ---- epilogue: lane l, register v of acc[jj][ct] is token l%32, c = 32*ct + 8*(v/4) + 4*(l/32) + v%4.
@@ -1823,7 +1844,8 @@ int launch_fused2(const DevStep& s1, const DevStep& s2, const void* A, void* Out
 // Token count from which the chained pair kernel replaces the two separate launches (below it a
 // launch has too few workgroups: 8 per 32 tokens).
 constexpr int64_t kPairMinTokens = 256;
-constexpr size_t kPairSmemBytes = 4 * 20 * 1024;
+constexpr int kPairStages = 4;
+constexpr size_t kPairSmemBytes = kPairStages * 20 * 1024;
 
 int prepare_pair(tn_linear_s* h, hipStream_t st) {
     if ((h->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS)) || !tn::pair_chainable(h->plan)) return TN_OK;
@@ -1837,7 +1859,7 @@ int prepare_pair(tn_linear_s* h, hipStream_t st) {
     hipLaunchKernelGGL(pair_repack_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const bf16_t*>(s1.packed),
                        static_cast<bf16_t*>(h->pair_b1f), A, s1.Kp >> 4, s1.Cp);
     if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             int(kPairSmemBytes)) != hipSuccess)
         return TN_ERR_HIP;
     h->pair = true;
@@ -1864,7 +1886,7 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
     p.n_tok_tiles = int32_t((tokens + 31) / 32);
     p.n_jsets = p.J / 8;
     int64_t grid = int64_t((p.n_tok_tiles + 7) / 8 * 8) * p.n_jsets;
-    hipLaunchKernelGGL(step_pair_kernel, dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
+    hipLaunchKernelGGL(step_pair_kernel<kPairStages>, dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
@@ -2187,7 +2209,9 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             }
         return need;
     };
-    int64_t chunk = h->max_tokens;
+    // with the chained pair kernel only calls below its token threshold use the workspace
+    const int64_t ws_tokens = h->pair ? std::min<int64_t>(h->max_tokens, h->pair_min_tokens - 1) : h->max_tokens;
+    int64_t chunk = ws_tokens;
     if (desc->workspace) {
         // caller-owned block: [partial sums | buffer 0 | buffer 1], 256-byte aligned pieces
         h->owns_workspace = false;
@@ -2196,7 +2220,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         int64_t part = split_ok ? std::min<int64_t>(kMaxPartialBytes, avail / 4) & ~int64_t(255) : 0;
         int64_t half = ((avail - part) / 2) & ~int64_t(255);
         if (per_token > 0) {
-            chunk = std::min<int64_t>(std::min<int64_t>(h->max_tokens, half / per_token), row_cap);
+            chunk = std::min<int64_t>(std::min<int64_t>(ws_tokens, half / per_token), row_cap);
             if (chunk < 1) {
                 free_handle(h);
                 return TN_ERR_INVALID_ARG;      // the block cannot hold one token's intermediates
@@ -2214,7 +2238,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     } else {
         int64_t limit = desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes;
         if (per_token > 0) {
-            chunk = std::max<int64_t>(1, std::min<int64_t>(h->max_tokens, limit / (2 * per_token)));
+            chunk = std::max<int64_t>(1, std::min<int64_t>(ws_tokens, limit / (2 * per_token)));
             chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, row_cap));
             for (int b = 0; b < 2; ++b) {
                 if (hipMalloc(&h->ws[b], size_t(chunk * per_token)) != hipSuccess) {
