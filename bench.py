@@ -52,15 +52,15 @@ def cpu_baseline(spec, tensors, sample_tokens):
     }
 
 
-def measured_traffic(args, step):
-    """HBM bytes per launch of a step of the default workload, measured in separate rocprofv3
-    counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy) and recorded in profiles/."""
-    if args.workload != 1 or args.custom or args.no_merge or args.tokens != 8192:
+def measured_traffic(args, fused):
+    """HBM bytes per launch of the dominant kernel of the default workload, measured in separate
+    rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy) and recorded in profiles/."""
+    if args.workload != 1 or args.custom or args.no_merge or args.tokens != 8192 or not fused:
         return None
     path = os.path.join(ROOT, "profiles", "tt_q_proj_prefill8192_hbm_traffic.txt")
     try:
         import re
-        m = re.search(rf"TRAFFIC_BYTES_PER_LAUNCH step{step} = (\d+)", open(path).read())
+        m = re.search(r"TRAFFIC_BYTES_PER_LAUNCH pair = (\d+)", open(path).read())
         return int(m.group(1)) if m else None
     except OSError:
         return None
@@ -304,7 +304,7 @@ def main() -> int:
     else:
         roof = {"bound": "hbm", "achieved": per_step[dom]["algorithmic_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = measured_traffic(args, dom)
+    roof["traffic"] = measured_traffic(args, per_step[dom]["fused_with_next"])
     if per_step[dom]["fused_with_next"]:
         roof["kernel"] = (f"contraction steps {dom} and {dom + 1} in one launch (rows {q(dom, 0)} x K {q(dom, 1)} x cols "
                           f"{q(dom, 2)}, then rows {q(dom + 1, 0)} x K {q(dom + 1, 1)} x cols {q(dom + 1, 2)} per token; "
