@@ -204,6 +204,7 @@ def main() -> int:
     ap.add_argument("--shortk-mode", type=int, default=0, help="tuning override of the short-K kernel (0 = library choice, 1..3 = form 0..2)")
     ap.add_argument("--merge-grow", action="store_true",
                     help="allow create-time merges that add parameters (up to a quarter of the dense matrix)")
+    ap.add_argument("--flags", type=int, default=0, help="extra TN_FLAG_* bits for the layer (e.g. 64: one launch per step)")
     ap.add_argument("--no-pair-chain", action="store_true",
                     help="run a two-step train as two launches (intermediate in the workspace)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
@@ -238,7 +239,7 @@ def main() -> int:
     del x64
     layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
                         tokens, args.workspace_mb << 20, flags=(args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
-                        | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0))
+                        | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0) | args.flags)
     y = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 

@@ -63,6 +63,8 @@ extern "C" {
                                        of the dense matrix (e.g. a ring of 4 cores becomes two half-rings) */
 #define TN_FLAG_NO_PAIR_CHAIN   32   /* never run a two-step plan as one chained launch (see TN_QUERY_PAIR_CHAINABLE):
                                        always two launches with the intermediate in the workspace */
+#define TN_FLAG_NO_CHAIN2       64   /* never run two small transposing steps (Tucker factor products) as one
+                                       chained launch: always one launch per step */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide

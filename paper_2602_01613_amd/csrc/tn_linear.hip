@@ -1460,6 +1460,237 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Transposing chain of two small steps (the two in-factor or the two out-factor products of a
+// Tucker layer): the second step contracts the ROW index r of the first and keeps its column index
+// c1 as a row,
+//     T[r][c1] = sum_k  In[t][r][k] * Ba[c1][k]                    R1 x K1 input per token
+//     Out[t][off1[c1] + off2[c2]] = sum_r T[r][c1] * Bb[c2][r]
+// A wave owns one token at a time. The token's input travels from memory straight into a
+// wave-private LDS buffer in MFMA fragment order (direct-to-LDS loads, double buffered: the next
+// token's input is in flight while the current one is computed; no workgroup barrier anywhere).
+// For each tile of 32 values of c1 the wave computes T^T as accumulator tiles with r in the
+// registers and c1 across the lanes, rounds them to bf16 and feeds them - without leaving the
+// registers - to the second contraction, whose packed tensor is stored at create time with the
+// matching permutation of r inside each k-step (chain2_repack_kernel) and stays in registers for
+// all tokens. The intermediate T never exists in memory, one launch replaces two, and the HBM
+// traffic drops to the first step's input plus the second step's output.
+// RUN_C1 = 1: the output takes 8 consecutive c1 as an aligned 16-byte piece (T^T is the row operand
+// of the second MFMA, so a lane ends up with 4 consecutive c1); RUN_C1 = 0: 8 consecutive c2 (T^T is
+// the column operand). Either way the 32x32 result tiles pass through a wave-private LDS patch and
+// leave as 16-byte stores.
+// Limits: R1 <= 32*R1T, K1 <= 16*K1S, K1 % 8 == 0, C2 <= 32*C2T; any C1.
+// ---------------------------------------------------------------------------------------------
+struct Chain2Args {
+    const void* In;
+    void* Out;
+    const void* Ba;         // first step's packed tensor (fragment-major, nks_a k-steps per column block)
+    const void* Bbf;        // second step's packed tensor in the chained layout
+    const int32_t* off1;    // output offset of c1 (the second step's row table)
+    const int32_t* off2;    // output offset of c2 (the second step's column table)
+    int64_t in_tok_stride, out_tok_stride;
+    int32_t tokens, R1, K1, C1, C2;
+    int32_t nks_a;
+    int32_t c1_tiles;       // ceil(C1 / 32)
+    int32_t tiles_per_item; // c1 tiles one wave handles per visit of a token (all of them for large
+                            // batches; 1 spreads a single token over several waves)
+};
+
+// Bbf[((j*KS + s)*64 + l)*8 + e] = Bb[c2 = 32*j + l%32][r = 16*s + 8*(e/4) + 4*(l/32) + e%4], zero outside
+__global__ void __launch_bounds__(256) chain2_repack_kernel(const bf16_t* src, bf16_t* dst, int C2T, int KS,
+                                                            int nks_src, int Cp, int Kp) {
+    int total = C2T * KS * 512;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        int e = i & 7, l = (i >> 3) & 63, blk = i >> 9;
+        int j = blk / KS, sk = blk - j * KS;
+        int c = 32 * j + (l & 31);
+        int k = 16 * sk + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+        dst[i] = (c < Cp && k < Kp) ? src[bfrag_offset(c, k, nks_src)] : bf16_t(0.f);
+    }
+}
+
+template <int R1T, int K1S, int C2T>
+constexpr size_t chain2_smem_bytes() {
+    return size_t(4) * (R1T * K1S * 1024 + 2 * 32 * 80);
+}
+
+template <int R1T, int K1S, int C2T, int RUN_C1>
+__global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
+    constexpr int IN_BYTES = R1T * K1S * 1024;           // one token's input in fragment order
+    constexpr int KS2 = 2 * R1T;                         // k-steps of the second contraction
+    constexpr int PATCH_LD = 80;                         // bytes per patch row (64 + 16 of padding)
+    constexpr int PATCH_BYTES = 32 * PATCH_LD;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    const bf16_t* In = static_cast<const bf16_t*>(p.In);
+    const bf16_t* Ba = static_cast<const bf16_t*>(p.Ba);
+    const bf16_t* Bbf = static_cast<const bf16_t*>(p.Bbf);
+    bf16_t* Out = static_cast<bf16_t*>(p.Out);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    unsigned char* my_in = dyn_smem + wave * IN_BYTES;
+    unsigned char* my_patch = dyn_smem + 4 * IN_BYTES + wave * (2 * PATCH_BYTES);
+
+    // lanes whose (row, k) lies outside the input never load: their LDS slots keep these zeros
+    for (int i = lane; i < IN_BYTES / 16; i += 64) {
+        bf16x8 z;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
+        *reinterpret_cast<bf16x8*>(my_in + i * 16) = z;
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): the zeros are in LDS before any load lands
+    __builtin_amdgcn_wave_barrier();
+
+    // the second packed tensor stays in registers for every token of the wave
+    bf16x8 bb[C2T][KS2];
+#pragma unroll
+    for (int j = 0; j < C2T; ++j)
+#pragma unroll
+        for (int sk = 0; sk < KS2; ++sk)
+            bb[j][sk] = *reinterpret_cast<const bf16x8*>(Bbf + (int64_t(j) * KS2 + sk) * 512 + lane * 8);
+
+    const int nrt = (p.R1 + 31) >> 5, nks1 = (p.K1 + 15) >> 4;
+    const int nj = (p.C2 + 31) >> 5;
+    const int lrow = lane & 31, lk = 8 * (lane >> 5);
+    auto issue_in = [&](int t) {
+        const bf16_t* src = In + int64_t(t) * p.in_tok_stride + int64_t(lrow) * p.K1 + lk;
+#pragma unroll
+        for (int i = 0; i < R1T; ++i)
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk) {
+                if (i < nrt && sk < nks1) {                          // wave-uniform
+                    if (32 * i + lrow < p.R1 && 16 * sk + lk < p.K1)
+                        __builtin_amdgcn_global_load_lds(
+                            (const void __attribute__((address_space(1)))*)(src + int64_t(32 * i) * p.K1 + 16 * sk),
+                            (void __attribute__((address_space(3)))*)(my_in + (i * K1S + sk) * 1024), 16, 0, 0);
+                }
+            }
+    };
+    auto load_ba = [&](int ct1, bf16x8 (&ba)[K1S]) {
+#pragma unroll
+        for (int sk = 0; sk < K1S; ++sk)      // k-steps past the packed tensor's padding meet zero input: any finite block will do
+            ba[sk] = *reinterpret_cast<const bf16x8*>(Ba + (int64_t(ct1) * p.nks_a + min(sk, p.nks_a - 1)) * 512 + lane * 8);
+    };
+
+    // output offsets of the two 16-byte pieces a lane stores per 32x32 tile (patch row lane/4 + 16h,
+    // piece lane%4): those along c2 never change; those along c1 are fetched a tile ahead. -1 = outside.
+    const int prow = lane >> 2, pchunk = lane & 3;
+    int o2[C2T][2];
+#pragma unroll
+    for (int j = 0; j < C2T; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int c2 = 32 * j + (RUN_C1 ? prow + 16 * h : 8 * pchunk);
+            o2[j][h] = c2 < p.C2 ? p.off2[c2] : -1;
+        }
+    auto load_o1 = [&](int ct1, int (&o1)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int c1 = 32 * ct1 + (RUN_C1 ? 8 * pchunk : prow + 16 * h);
+            o1[h] = c1 < p.C1 ? p.off1[c1] : -1;
+        }
+    };
+
+    const int n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
+    const int64_t n_items = int64_t(p.tokens) * n_groups;
+    const int64_t gw = int64_t(blockIdx.x) * 4 + wave, GW = int64_t(gridDim.x) * 4;
+    // Vector memory operations a full item issues after its input request (the packed-tensor loads and
+    // the stores of every tile but a possibly ragged last one, a lower bound). Loads complete in issue
+    // order, so once at most 63 operations are in flight an input request older than that has landed,
+    // without waiting for the latest stores to be acknowledged.
+    const int ops_after = max(0, p.tiles_per_item - ((p.C1 & 31) ? 1 : 0)) * (K1S + 2 * (p.C2 >> 5));
+    if (gw < n_items) issue_in(int(gw / n_groups));
+    for (int64_t item = gw; item < n_items; item += GW) {
+        const int t = int(item / n_groups);
+        const int g = int(item - int64_t(t) * n_groups);
+        const int tile_begin = g * p.tiles_per_item;
+        const int tile_end = min(p.c1_tiles, tile_begin + p.tiles_per_item);
+        bf16x8 ba_next[K1S];
+        int o1_next[2];
+        load_ba(tile_begin, ba_next);
+        load_o1(tile_begin, o1_next);
+        if (item == gw || ops_after < 66 + K1S) wait_vmcnt<0>();
+        else wait_vmcnt<61 - K1S>();                                  // the loads above are younger still
+        // the token's input moves to registers; its LDS buffer then takes the next item's input,
+        // which travels while this item is computed
+        bf16x8 inf[R1T][K1S];
+#pragma unroll
+        for (int i = 0; i < R1T; ++i)
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk)      // slots outside the input hold zeros
+                inf[i][sk] = *reinterpret_cast<const bf16x8*>(my_in + (i * K1S + sk) * 1024 + lane * 16);
+        __builtin_amdgcn_s_waitcnt(0xc07f);                          // the reads are done before the buffer is refilled
+        if (item + GW < n_items) issue_in(int((item + GW) / n_groups));
+        bf16_t* out_t = Out + int64_t(t) * p.out_tok_stride;
+        for (int ct1 = tile_begin; ct1 < tile_end; ++ct1) {
+            bf16x8 ba[K1S];
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk) ba[sk] = ba_next[sk];
+            const int o1[2] = {o1_next[0], o1_next[1]};
+            if (ct1 + 1 < tile_end) {
+                load_ba(ct1 + 1, ba_next);
+                load_o1(ct1 + 1, o1_next);
+            }
+            // first contraction: accumulator tile i holds T^T for r in [32i, 32i+32): lane l has c1 = l%32,
+            // register v has r = 32i + 8*(v/4) + 4*(l/32) + v%4
+            floatx16 d[R1T];
+#pragma unroll
+            for (int i = 0; i < R1T; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) d[i][v] = 0.f;
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk)
+#pragma unroll
+                for (int i = 0; i < R1T; ++i)
+                    d[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(inf[i][sk], ba[sk], d[i], 0, 0, 0);
+            bf16x8 zb[KS2];
+#pragma unroll
+            for (int i = 0; i < R1T; ++i)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) zb[2 * i + u][e] = bf16_t(d[i][8 * u + e]);
+            // second contraction: all tiles of c2 (independent accumulators), then their way out
+            floatx16 acc[C2T];
+#pragma unroll
+            for (int j = 0; j < C2T; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+#pragma unroll
+            for (int sk = 0; sk < KS2; ++sk)
+#pragma unroll
+                for (int j = 0; j < C2T; ++j)
+                        acc[j] = RUN_C1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(zb[sk], bb[j][sk], acc[j], 0, 0, 0)
+                                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j][sk], zb[sk], acc[j], 0, 0, 0);
+            // RUN_C1: lane l holds c2 = 32j + l%32 and, in registers 4q..4q+3, c1 = 32*ct1 + 8q + 4*(l/32) + 0..3
+            // else  : lane l holds c1 = 32*ct1 + l%32 and c2 = 32j + 8q + 4*(l/32) + 0..3
+            // The 32x32 tiles pass through two alternating wave-private LDS patches and leave as 16-byte
+            // pieces; a patch is rewritten two tiles later, after the wave barrier of the tile between.
+#pragma unroll
+            for (int j = 0; j < C2T; ++j) {
+                if (j >= nj) continue;                                 // wave-uniform
+                unsigned char* patch = my_patch + (j & 1) * PATCH_BYTES;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[j][4 * q + u]);
+                    *reinterpret_cast<bf16x4*>(patch + (lane & 31) * PATCH_LD + (8 * q + 4 * (lane >> 5)) * 2) = pk;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    bf16x8 v = *reinterpret_cast<const bf16x8*>(patch + (prow + 16 * h) * PATCH_LD + pchunk * 16);
+                    if (o1[h] >= 0 && o2[j][h] >= 0) *reinterpret_cast<bf16x8*>(out_t + o1[h] + o2[j][h]) = v;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 enum Variant : int {
@@ -1480,7 +1711,11 @@ struct DevStep {
     int variant = VAR_SCALAR;
     int amode = 0, cmode = 0;
     int bn = 64, bm = 64;
-    bool fuse_next = false;       // this step and the next run as one step_fused2_kernel launch
+    bool fuse_next = false;       // this step and the next run as one launch
+    int fuse_kind = 0;            // 1 step_fused2_kernel (opt-in), 2 step_chain2_kernel
+    void* chain_bbf = nullptr;    // chain2: the next step's packed tensor in the chained layout
+    int chain_cfg = 0;            // chain2 instantiation: 0 <3,6,5>, 1 <2,8,2>
+    int chain_run_c1 = 0;         // chain2: output pieces run along c1 (else along c2)
     int fused_in_elems = 0, fused_mid_elems = 0;
     size_t fused_smem = 0;
 };
@@ -1499,6 +1734,7 @@ struct tn_linear_s {
     int flags = 0;
     bool owns_workspace = true;
     int device = 0;
+    int num_cus = 256;
     bool profiling = false;
     // chained pair kernel (two-step plans of the train shape): second packed tensor in its layout
     bool pair = false;
@@ -1528,6 +1764,7 @@ void free_handle(tn_linear_s* h) {
     for (auto& s : h->steps) {
         if (s.packed) (void)hipFree(s.packed);
         if (s.tables) (void)hipFree(s.tables);
+        if (s.chain_bbf) (void)hipFree(s.chain_bbf);
     }
     if (h->pair_b1f) (void)hipFree(h->pair_b1f);
     if (h->owns_workspace) {
@@ -1793,6 +2030,7 @@ void plan_fusion(tn_linear_s* h) {
         if (smem > 72 * 1024) continue;
         if (int64_t(a.Cp) * a.Kp > 65536 || int64_t(b.Cp) * b.Kp > 65536) continue;
         a.fuse_next = true;
+        a.fuse_kind = 1;
         a.fused_in_elems = int(in_elems);
         a.fused_mid_elems = int((mid_elems + 7) / 8 * 8);
         a.fused_smem = size_t((a.fused_in_elems + a.fused_mid_elems + 4 * 32 * 40) * 2 + tab * 4 + 64);
@@ -1887,6 +2125,91 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
     p.n_jsets = p.J / 8;
     int64_t grid = int64_t((p.n_tok_tiles + 7) / 8 * 8) * p.n_jsets;
     hipLaunchKernelGGL(step_pair_kernel<kPairStages>, dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+// Pairs of steps the transposing chain kernel can run (see step_chain2_kernel): both plain, the
+// first step's output stored transposed ([c1][r], which is what the second step reads as rows c1
+// with K = r), the output in aligned runs of 8 along c1 or along c2, and sizes within one of the
+// two instantiations.
+int plan_chain2(tn_linear_s* h, hipStream_t st) {
+    if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_CHAIN2 | TN_FLAG_FUSE_SMALL_STEPS)) ||
+        h->pair)
+        return TN_OK;
+    for (size_t i = 0; i + 1 < h->steps.size(); ++i) {
+        DevStep& a = h->steps[i];
+        DevStep& b = h->steps[i + 1];
+        if (i > 0 && h->steps[i - 1].fuse_next) continue;
+        const tn::Step& pa = a.plan;
+        const tn::Step& pb = b.plan;
+        if (a.variant == VAR_SCALAR || b.variant == VAR_SCALAR) continue;
+        if (!pa.a_plain || !pb.a_plain || pa.K % 8) continue;
+        if (pb.K != pa.R || pb.R != pa.C || pa.c_tok_stride != pa.C * pa.R) continue;
+        int cfg;
+        if (pa.R <= 96 && pa.K <= 96 && pb.C <= 160) cfg = 0;
+        else if (pa.R <= 64 && pa.K <= 128 && pb.C <= 64) cfg = 1;
+        else continue;
+        bool transposed = true;
+        for (int64_t r = 0; r < pa.R && transposed; ++r) transposed = pa.crow[size_t(r)] == r;
+        for (int64_t c = 0; c < pa.C && transposed; ++c) transposed = pa.ccol[size_t(c)] == c * pa.R;
+        if (!transposed) continue;
+        int run_c1;
+        if (pb.r_vec == 8) run_c1 = 1;
+        else if (pb.c_vec == 8) run_c1 = 0;
+        else continue;
+        const int C2T = cfg == 0 ? 5 : 2, KS = cfg == 0 ? 6 : 4;
+        size_t elems = size_t(C2T) * KS * 512;
+        if (hipMalloc(&a.chain_bbf, elems * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
+        h->packed_bytes += int64_t(elems * sizeof(bf16_t));
+        hipLaunchKernelGGL(chain2_repack_kernel, dim3(uint32_t((elems + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const bf16_t*>(b.packed), static_cast<bf16_t*>(a.chain_bbf), C2T, KS, b.Kp >> 4,
+                           b.Cp, b.Kp);
+        if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+        a.fuse_next = true;
+        a.fuse_kind = 2;
+        a.chain_cfg = cfg;
+        a.chain_run_c1 = run_c1;
+    }
+    return TN_OK;
+}
+
+int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens,
+                  hipStream_t st) {
+    Chain2Args p;
+    p.In = A;
+    p.Out = Out;
+    p.Ba = s1.packed;
+    p.Bbf = s1.chain_bbf;
+    p.off1 = s2.crow;
+    p.off2 = s2.ccol;
+    p.in_tok_stride = s1.plan.a_tok_stride;
+    p.out_tok_stride = s2.plan.c_tok_stride;
+    p.tokens = int32_t(tokens);
+    p.R1 = int32_t(s1.plan.R);
+    p.K1 = int32_t(s1.plan.K);
+    p.C1 = int32_t(s1.plan.C);
+    p.C2 = int32_t(s2.plan.C);
+    p.nks_a = s1.Kp >> 4;
+    p.c1_tiles = (p.C1 + 31) / 32;
+    // a wave per token when there are tokens enough to fill the chip, else a wave per (token, c1 tile)
+    const int64_t waves = int64_t(h->num_cus) * 4;
+    p.tiles_per_item = tokens >= waves ? p.c1_tiles : 1;
+    const int64_t n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
+    const int64_t items = tokens * n_groups;
+    dim3 grid(uint32_t(std::min<int64_t>((items + 3) / 4, h->num_cus)));
+    using k_t = void (*)(Chain2Args);
+    static const k_t kerns[4] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
+                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>};
+    static const size_t smem[2] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>()};
+    static bool configured = false;
+    if (!configured) {
+        for (int i = 0; i < 4; ++i)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(smem[i / 2])) != hipSuccess)
+                return TN_ERR_HIP;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kerns[s1.chain_cfg * 2 + s1.chain_run_c1], grid, dim3(256), smem[s1.chain_cfg], st, p);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
@@ -2088,6 +2411,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             delete h;
             return TN_ERR_UNSUPPORTED;
         }
+        h->num_cus = std::max(1, prop.multiProcessorCount);
     }
     hipStream_t st = static_cast<hipStream_t>(desc->stream);
     h->elt = desc->dtype == TN_DTYPE_BF16 ? 2 : 4;
@@ -2186,6 +2510,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     }
     plan_fusion(h);
     rc = prepare_pair(h, st);
+    if (rc == TN_OK) rc = plan_chain2(h, st);
     if (rc != TN_OK) {
         (void)hipStreamSynchronize(st);
         free_handle(h);
@@ -2306,8 +2631,9 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
                     return TN_ERR_HIP;
                 (void)hipEventRecord(rec.start, st);
             }
-            int rc = fused ? launch_fused2(h->steps[s], h->steps[s + 1], A, Out, nt, st)
-                           : launch_step(h, h->steps[s], A, Out, nt, st);
+            int rc = !fused ? launch_step(h, h->steps[s], A, Out, nt, st)
+                     : h->steps[s].fuse_kind == 2 ? launch_chain2(h, h->steps[s], h->steps[s + 1], A, Out, nt, st)
+                                                  : launch_fused2(h->steps[s], h->steps[s + 1], A, Out, nt, st);
             if (h->profiling) {
                 (void)hipEventRecord(rec.stop, st);
                 h->prof.push_back(rec);

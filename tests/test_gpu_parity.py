@@ -368,3 +368,41 @@ def test_chained_pair_kernel_q_proj(tokens, dense_w):
     assert O.rel_max_err(y, O.apply_linear(w, x)) <= TOL["bf16"]
     y_two = run_layer(spec, ts, x, flags=tn.TN_FLAG_NO_PAIR_CHAIN)
     assert O.rel_max_err(y, y_two) <= 1e-2
+
+
+CHAIN2_CASES = [
+    # Tucker layers whose factor products run as chained launches (out modes, in modes, ranks)
+    ((160, 160), (64, 80), (96, 96, 48, 48)),     # the up_proj workload: 64x80 -> 48x48, 96x96 -> 160x160
+    ((80, 96), (64, 128), (64, 64, 32, 32)),      # K1 = 128 (the 8-k-step instantiation), ragged c1 tiles
+    ((48, 40), (64, 80), (32, 32, 16, 16)),       # one row tile, two k-steps
+    ((40, 72), (24, 40), (24, 40, 16, 24)),       # nothing a multiple of 32; the in-factor order makes the
+                                                  # first step gather from x, so only the out-factors chain
+]
+CHAIN2_FUSED = [[1, 0, 0, 1, 0], [1, 0, 0, 1, 0], [1, 0, 0, 1, 0], [0, 0, 0, 1, 0]]
+
+
+@pytest.mark.parametrize("tokens", [1, 7, 130, 1100])
+@pytest.mark.parametrize("case", range(len(CHAIN2_CASES)))
+def test_chained_factor_products(case, tokens):
+    """Pairs of transposing small steps (Tucker in-factor and out-factor products) as one launch
+    with the intermediate in registers: against the oracle and against one launch per step, with a
+    wave per (token, column tile) (few tokens) and a wave per token (many)."""
+    om, im, rk = CHAIN2_CASES[case]
+    spec = _spec(tn.TN_FORMAT_TUCKER, "bf16", om, im, rk)
+    ts = _rand_layer(spec, 900 + case)
+    x = wl.round_to_dtype(np.random.default_rng(case * 31 + tokens).standard_normal((tokens, spec.N)), "bf16")
+    layer = make_layer(spec, ts, tokens)
+    n_steps = layer.query(tn.TN_QUERY_NUM_STEPS)
+    fused = [layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + 6) for s in range(n_steps)]
+    assert n_steps == 5 and fused == CHAIN2_FUSED[case], fused
+    xd = to_dev(x, "bf16")
+    yd = layer(xd)
+    torch.cuda.synchronize()
+    assert torch.equal(yd, layer(xd))
+    layer.close()
+    y = to_host(yd)
+    ref = O.forward(spec.format, ts, x, n_out_modes=len(om))
+    y_sep = run_layer(spec, ts, x, flags=tn.TN_FLAG_NO_CHAIN2)
+    assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
+    assert O.rel_max_err(y_sep, ref) <= TOL["bf16"], (case, tokens)
+    assert O.rel_max_err(y, y_sep) <= 1e-2, (case, tokens)
