@@ -204,6 +204,8 @@ def main() -> int:
     ap.add_argument("--shortk-mode", type=int, default=0, help="tuning override of the short-K kernel (0 = library choice, 1..3 = form 0..2)")
     ap.add_argument("--merge-grow", action="store_true",
                     help="allow create-time merges that add parameters (up to a quarter of the dense matrix)")
+    ap.add_argument("--graph-instances", type=int, default=16,
+                    help="distinct layer copies in the captured decode graph")
     ap.add_argument("--flags", type=int, default=0, help="extra TN_FLAG_* bits for the layer (e.g. 64: one launch per step)")
     ap.add_argument("--no-pair-chain", action="store_true",
                     help="run a two-step train as two launches (intermediate in the workspace)")
@@ -237,9 +239,10 @@ def main() -> int:
     dev = [torch.from_numpy(t).to(torch.float32).to(torch.bfloat16).cuda() for t in tensors]
     x = torch.from_numpy(x64).to(torch.float32).to(torch.bfloat16).cuda()
     del x64
+    layer_flags = ((args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
+                   | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0) | args.flags)
     layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
-                        tokens, args.workspace_mb << 20, flags=(args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
-                        | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0) | args.flags)
+                        tokens, args.workspace_mb << 20, flags=layer_flags)
     y = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 
@@ -353,7 +356,51 @@ def main() -> int:
                 "tflops": flops_tok * t / us / 1e6,
                 "sum_kernel_us": sum(p["kernel_us"] for p in steps), "per_step": steps}
 
+    def decode_graph_stats(t, instances):
+        """Steady-state decode: `instances` distinct copies of the layer (own packed tensors, so the
+        parameter stream cannot sit in the 256 MB last-level cache from one call to the next when their
+        sum exceeds it) run back to back inside one captured HIP graph, replayed many times; time per
+        layer call. This takes the host's launch cost out of the figure, which a serving loop does by
+        capturing its decode step the same way."""
+        copies = [layer]
+        for _ in range(instances - 1):
+            copies.append(tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
+                                      max(t, 1), flags=layer_flags))
+        xt = x[:t].contiguous()
+        yt = torch.empty((t, spec.M), dtype=torch.bfloat16, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for c in copies:
+                c.forward(xt, out=yt)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for c in copies:
+                c.forward(xt, out=yt)
+        for _ in range(5):
+            graph.replay()
+        torch.cuda.synchronize()
+        reps = 50
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / reps / instances * 1e6
+        # every replay must give what the eager call gives
+        y_eager = torch.empty_like(yt)
+        copies[-1].forward(xt, out=y_eager)
+        torch.cuda.synchronize()
+        ok = bool(torch.equal(y_eager, yt))
+        packed = layer.query(tn.TN_QUERY_PACKED_BYTES)
+        for c in copies[1:]:
+            c.close()
+        return {"tokens": t, "instances": instances, "us_per_layer_call": us, "tokens_per_s": t * 1e6 / us,
+                "param_GBps": packed / us / 1e3, "tflops": flops_tok * t / us / 1e6,
+                "param_MB_all_instances": packed * instances / 1e6, "replay_equals_eager": ok}
+
     dec1 = decode_stats(1)
+    dec1_graph = decode_graph_stats(1, args.graph_instances)
     dec8 = decode_stats(8)          # the size a speculative-decoding verifier sends (paper Section 3.6)
     dec64 = decode_stats(64)
     decode_us = dec1["us_per_call"]
@@ -384,6 +431,7 @@ def main() -> int:
         "per_step": per_step,
         "decode_1tok": dict(dec1, us_per_token=decode_us,
                             param_GBps=layer.query(tn.TN_QUERY_PACKED_BYTES) / decode_us / 1e3),
+        "decode_1tok_graph": dec1_graph,
         "verify_8tok": dec8,
         "decode_64tok": dec64,
         "paper_context": "paper reports ~40 -> ~50 -> ~75 tokens/s end-to-end decode on Qwen3-32B, 8K context, "

@@ -982,9 +982,11 @@ __global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
-    constexpr int U = 4;                               // k-steps in flight per wave
-    for (int ks0 = ks_begin + wave; ks0 < ks_end; ks0 += NW * U) {
-        bf16x8 bf[U], af[U][TM];
+    // U k-steps per batch and two batches in registers: the next batch is requested before the current
+    // one is multiplied, so a wave always has loads in flight (a decode-size launch is a pure stream of
+    // the packed tensor; with one batch the stream would drain at every wait)
+    constexpr int U = 4;
+    auto load_batch = [&](int ks0, bf16x8 (&bf)[U], bf16x8 (&af)[U][TM]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int ks = ks0 + NW * u;
@@ -1009,11 +1011,25 @@ __global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* 
                 af[u][i] = v;
             }
         }
+    };
+    auto multiply = [&](const bf16x8 (&bf)[U], const bf16x8 (&af)[U][TM]) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], af[u][i], acc[i], 0, 0, 0);
+    };
+    {
+        bf16x8 bf0[U], af0[U][TM], bf1[U], af1[U][TM];
+        constexpr int STEP = NW * U;
+        int ks0 = ks_begin + wave;
+        load_batch(ks0, bf0, af0);                       // batches past the end load nothing and multiply zeros
+        for (; ks0 < ks_end; ks0 += 2 * STEP) {
+            load_batch(ks0 + STEP, bf1, af1);
+            multiply(bf0, af0);
+            load_batch(ks0 + 2 * STEP, bf0, af0);
+            multiply(bf1, af1);
+        }
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -1049,8 +1065,17 @@ __global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, cons
     for (int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x; e < total; e += int64_t(gridDim.x) * 256) {
         uint32_t g = uint32_t(e / a.C);
         int c = int(e - int64_t(g) * a.C);
+        // 8 loads in flight at a time; the additions keep the split order
         float sum = 0.f;
-        for (int s = 0; s < nsplit; ++s) sum += partial[(int64_t(s) * rows_pad + g) * a.Cp + c];
+        const float* src = partial + int64_t(g) * a.Cp + c;
+        const int64_t sstride = int64_t(rows_pad) * a.Cp;
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = s0 + q < nsplit ? src[int64_t(s0 + q) * sstride] : 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) sum += v[q];
+        }
         uint32_t t = g / a.R;
         uint32_t r = g - t * a.R;
         Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
@@ -1529,13 +1554,23 @@ __global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
     unsigned char* my_in = dyn_smem + wave * IN_BYTES;
     unsigned char* my_patch = dyn_smem + 4 * IN_BYTES + wave * (2 * PATCH_BYTES);
 
-    // lanes whose (row, k) lies outside the input never load: their LDS slots keep these zeros
-    for (int i = lane; i < IN_BYTES / 16; i += 64) {
-        bf16x8 z;
+    const int n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
+    const int64_t n_items = int64_t(p.tokens) * n_groups;
+    const int64_t gw = int64_t(blockIdx.x) * 4 + wave, GW = int64_t(gridDim.x) * 4;
+    if (gw >= n_items) return;                           // no workgroup barrier below: a wave may leave
+
+    // lanes whose (row, k) lies outside the input never load: the fragment blocks they belong to are
+    // zeroed once and keep those zeros
 #pragma unroll
-        for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
-        *reinterpret_cast<bf16x8*>(my_in + i * 16) = z;
-    }
+    for (int i = 0; i < R1T; ++i)
+#pragma unroll
+        for (int sk = 0; sk < K1S; ++sk)
+            if (32 * i + 32 > p.R1 || 16 * sk + 16 > p.K1) {        // wave-uniform
+                bf16x8 z;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
+                *reinterpret_cast<bf16x8*>(my_in + (i * K1S + sk) * 1024 + lane * 16) = z;
+            }
     __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): the zeros are in LDS before any load lands
     __builtin_amdgcn_wave_barrier();
 
@@ -1589,15 +1624,12 @@ __global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
         }
     };
 
-    const int n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
-    const int64_t n_items = int64_t(p.tokens) * n_groups;
-    const int64_t gw = int64_t(blockIdx.x) * 4 + wave, GW = int64_t(gridDim.x) * 4;
     // Vector memory operations a full item issues after its input request (the packed-tensor loads and
     // the stores of every tile but a possibly ragged last one, a lower bound). Loads complete in issue
     // order, so once at most 63 operations are in flight an input request older than that has landed,
     // without waiting for the latest stores to be acknowledged.
     const int ops_after = max(0, p.tiles_per_item - ((p.C1 & 31) ? 1 : 0)) * (K1S + 2 * (p.C2 >> 5));
-    if (gw < n_items) issue_in(int(gw / n_groups));
+    issue_in(int(gw / n_groups));
     for (int64_t item = gw; item < n_items; item += GW) {
         const int t = int(item / n_groups);
         const int g = int(item - int64_t(t) * n_groups);
@@ -1837,7 +1869,7 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     int64_t base = int64_t(c.row_tiles) * c.col_blocks;
     // long K: wide workgroups (16 waves for up to 32 rows, 8 for up to 64), so that one split per
     // tile is enough to keep the weight stream busy and no reduction pass is needed
-    c.nw = nks >= 64 ? (c.tm == 1 ? 16 : 8) : 4;
+    c.nw = nks >= 64 ? 8 : 4;
     int64_t target_wgs = 3072 / c.nw;
     int want = int(std::max<int64_t>(1, target_wgs / base));
     int max_split = std::max(1, nks / (2 * c.nw));      // at least 2 k-steps per wave
@@ -1933,8 +1965,8 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
         using split_t = void (*)(StepArgs, float*, int);
         split_t k;
         if (sc.tm == 1)
-            k = sc.nw == 16 ? (s.amode == 0 ? step_split_kernel<1, 0, 16> : step_split_kernel<1, 1, 16>)
-                            : (s.amode == 0 ? step_split_kernel<1, 0, 4> : step_split_kernel<1, 1, 4>);
+            k = sc.nw == 8 ? (s.amode == 0 ? step_split_kernel<1, 0, 8> : step_split_kernel<1, 1, 8>)
+                           : (s.amode == 0 ? step_split_kernel<1, 0, 4> : step_split_kernel<1, 1, 4>);
         else
             k = sc.nw == 8 ? (s.amode == 0 ? step_split_kernel<2, 0, 8> : step_split_kernel<2, 1, 8>)
                            : (s.amode == 0 ? step_split_kernel<2, 0, 4> : step_split_kernel<2, 1, 4>);
@@ -2146,8 +2178,8 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
         if (!pa.a_plain || !pb.a_plain || pa.K % 8) continue;
         if (pb.K != pa.R || pb.R != pa.C || pa.c_tok_stride != pa.C * pa.R) continue;
         int cfg;
-        if (pa.R <= 96 && pa.K <= 96 && pb.C <= 160) cfg = 0;
-        else if (pa.R <= 64 && pa.K <= 128 && pb.C <= 64) cfg = 1;
+        if (pa.R <= 64 && pa.K <= 128 && pb.C <= 64) cfg = 1;
+        else if (pa.R <= 96 && pa.K <= 96 && pb.C <= 160) cfg = 0;
         else continue;
         bool transposed = true;
         for (int64_t r = 0; r < pa.R && transposed; ++r) transposed = pa.crow[size_t(r)] == r;
