@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA peak of MI355X
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(spec, tensors, sample_tokens):
+def cpu_baseline(spec, tensors, sample_tokens, transpose=False):
     """The fp64 oracle as it stands: rebuild dense W once, multiply a sample of tokens."""
     import numpy as np
     import oracle as O
@@ -36,12 +36,14 @@ def cpu_baseline(spec, tensors, sample_tokens):
     except Exception:
         threads = os.cpu_count() or 1
     x = wl.make_x(spec, sample_tokens, 1, instance=7)
+    if transpose:
+        x = np.random.Generator(np.random.PCG64([wl.SEED_BASE, 7, 1])).standard_normal((sample_tokens, spec.M))
     t0 = time.perf_counter()
     w = O.dense_weight(spec.format, tensors, len(spec.out_modes))
     t1 = time.perf_counter()
-    y = O.apply_linear(w, x)
+    y = O.apply_linear(w.T if transpose else w, x)
     t2 = time.perf_counter()
-    assert y.shape == (sample_tokens, spec.M)
+    assert y.shape == (sample_tokens, spec.N if transpose else spec.M)
     return {
         "value": sample_tokens / (t2 - t0),
         "unit": "tokens/s",
@@ -204,6 +206,8 @@ def main() -> int:
     ap.add_argument("--shortk-mode", type=int, default=0, help="tuning override of the short-K kernel (0 = library choice, 1..3 = form 0..2)")
     ap.add_argument("--merge-grow", action="store_true",
                     help="allow create-time merges that add parameters (up to a quarter of the dense matrix)")
+    ap.add_argument("--transpose", action="store_true",
+                    help="apply W^T (TN_FLAG_TRANSPOSE): the gradient of the forward with respect to its input")
     ap.add_argument("--graph-instances", type=int, default=16,
                     help="distinct layer copies in the captured decode graph")
     ap.add_argument("--flags", type=int, default=0, help="extra TN_FLAG_* bits for the layer (e.g. 64: one launch per step)")
@@ -236,14 +240,16 @@ def main() -> int:
     tensors = wl.make_tensors(spec, args.workload)
     tokens = args.tokens
     x64 = wl.make_x(spec, tokens, args.workload)
+    if args.transpose:
+        x64 = np.random.Generator(np.random.PCG64([wl.SEED_BASE, args.workload, 99])).standard_normal((tokens, spec.M))
     dev = [torch.from_numpy(t).to(torch.float32).to(torch.bfloat16).cuda() for t in tensors]
     x = torch.from_numpy(x64).to(torch.float32).to(torch.bfloat16).cuda()
     del x64
     layer_flags = ((args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
-                   | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0) | args.flags)
+                   | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0) | args.flags | (128 if args.transpose else 0))
     layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
                         tokens, args.workspace_mb << 20, flags=layer_flags)
-    y = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((tokens, layer.M), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 
     flops_tok = layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
@@ -325,7 +331,7 @@ def main() -> int:
     # then the per-kernel durations of the same calls from the library's HIP events
     def decode_stats(t):
         xt = x[:t].contiguous()
-        yt = torch.empty((t, spec.M), dtype=torch.bfloat16, device="cuda")
+        yt = torch.empty((t, layer.M), dtype=torch.bfloat16, device="cuda")
         for _ in range(20):
             layer.forward(xt, out=yt)
         torch.cuda.synchronize()
@@ -367,7 +373,7 @@ def main() -> int:
             copies.append(tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
                                       max(t, 1), flags=layer_flags))
         xt = x[:t].contiguous()
-        yt = torch.empty((t, spec.M), dtype=torch.bfloat16, device="cuda")
+        yt = torch.empty((t, layer.M), dtype=torch.bfloat16, device="cuda")
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -420,7 +426,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{spec.name}: {wl.FORMAT_NAMES[spec.format]} in {spec.N}={'x'.join(map(str, spec.in_modes))} "
                                f"out {spec.M}={'x'.join(map(str, spec.out_modes))} ranks {list(spec.ranks)}, "
-                               f"{tokens}-token prefill, bf16 storage, fp32 accumulate",
+                               f"{tokens}-token prefill, bf16 storage, fp32 accumulate"
+                               + (", applied transposed (Y = X W)" if args.transpose else ""),
                    "tokens": tokens, "chunk_tokens": chunk,
                    "create_time_merges": layer.query(tn.TN_QUERY_NUM_MERGES)},
         "flops_per_token": flops_tok,
@@ -446,7 +453,7 @@ def main() -> int:
         result["calib_copy_bytes"] = args.calib_copy_mb << 20
         del src, dst
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(spec, tensors, args.cpu_sample_tokens)
+        result["cpu_baseline"] = cpu_baseline(spec, tensors, args.cpu_sample_tokens, args.transpose)
     layer.close()
     print(json.dumps(result))
     return 0

@@ -65,6 +65,11 @@ extern "C" {
                                        always two launches with the intermediate in the workspace */
 #define TN_FLAG_NO_CHAIN2       64   /* never run two small transposing steps (Tucker factor products) as one
                                        chained launch: always one launch per step */
+#define TN_FLAG_TRANSPOSE      128   /* apply W^T instead of W: X is [tokens, M], Y is [tokens, N],
+                                       Y[t, j] = sum_i W[i, j] X[t, i]. Same tensors, same description; this is
+                                       the gradient of the forward pass with respect to its input, which the
+                                       fine-tuning of the factors (Section 3.4) back-propagates through every
+                                       layer. TN_QUERY_IN_FEATURES / OUT_FEATURES then report M / N. */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide

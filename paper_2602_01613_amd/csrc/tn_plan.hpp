@@ -104,8 +104,8 @@ inline bool contains(const std::vector<int>& v, int x) {
 
 }  // namespace detail
 
-// Validate the description and build the index network. Returns TN_OK or an error.
-inline int build_network(const tn_linear_desc* d, Plan* p) {
+// Validate the description and build the index network of y = W x. Returns TN_OK or an error.
+inline int build_network_forward(const tn_linear_desc* d, Plan* p) {
     using detail::mul_overflow;
     if (!d) return TN_ERR_INVALID_ARG;
     if (d->format < TN_FORMAT_DENSE || d->format > TN_FORMAT_TUCKER) return TN_ERR_INVALID_ARG;
@@ -229,6 +229,19 @@ inline int build_network(const tn_linear_desc* d, Plan* p) {
     for (int b = 0; b < qq; ++b) {
         rc = add_tensor(1 + pp + b, {ni[b], si[b]});
         if (rc != TN_OK) return rc;
+    }
+    return TN_OK;
+}
+
+// The network of the layer: y = W x, or with TN_FLAG_TRANSPOSE y = W^T x, which is the same network
+// with the roles of the out-modes and the in-modes exchanged (the activation then carries the
+// out-modes). The second form is the gradient of the first with respect to its input.
+inline int build_network(const tn_linear_desc* d, Plan* p) {
+    int rc = build_network_forward(d, p);
+    if (rc != TN_OK) return rc;
+    if (d->flags & TN_FLAG_TRANSPOSE) {
+        std::swap(p->x_idx, p->y_idx);
+        std::swap(p->M, p->N);
     }
     return TN_OK;
 }

@@ -406,3 +406,39 @@ def test_chained_factor_products(case, tokens):
     assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
     assert O.rel_max_err(y_sep, ref) <= TOL["bf16"], (case, tokens)
     assert O.rel_max_err(y, y_sep) <= 1e-2, (case, tokens)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_transposed_small_shapes(case, dtype):
+    """TN_FLAG_TRANSPOSE (Y = X W, the gradient of the forward with respect to its input) on the
+    small shapes, against the oracle's dense W."""
+    fmt, om, im, rk = SMALL[case]
+    spec = _spec(fmt, dtype, om, im, rk)
+    ts = _rand_layer(spec, 1100 + case)
+    w = O.dense_weight(fmt, ts, len(om))
+    for tokens in (1, 17, 130):
+        x = wl.round_to_dtype(np.random.default_rng(case * 5 + tokens).standard_normal((tokens, spec.M)), dtype)
+        y = run_layer(spec, ts, x, flags=tn.TN_FLAG_TRANSPOSE)
+        assert y.shape == (tokens, spec.N)
+        err = O.rel_max_err(y, O.apply_linear(w.T, x))
+        assert err <= TOL[dtype], (case, tokens, err)
+
+
+@pytest.mark.parametrize("i", [1, 2, 3])
+def test_transposed_baseline_configs(i, dense_w):
+    """The three bf16 workloads applied transposed, at decode size in full and at 2048 tokens on a
+    sample of rows."""
+    spec, ts, w = dense_w(i)
+    rng = np.random.default_rng(40 + i)
+    layer = make_layer(spec, ts, 2048, flags=tn.TN_FLAG_TRANSPOSE)
+    assert (layer.N, layer.M) == (spec.M, spec.N)
+    for tokens in (1, 64, 2048):
+        x = wl.round_to_dtype(rng.standard_normal((tokens, spec.M)), "bf16")
+        yd = layer(to_dev(x, "bf16"))
+        torch.cuda.synchronize()
+        rows = np.unique(np.concatenate([rng.choice(tokens, size=min(tokens, 16), replace=False), [0, tokens - 1]]))
+        err = O.rel_max_err(to_host(yd[torch.from_numpy(rows).cuda()]), O.apply_linear(w.T, x[rows]))
+        print(f"workload {i} transposed T={tokens} rel err {err:.3e}", flush=True)
+        assert err <= TOL["bf16"]
+    layer.close()

@@ -90,6 +90,26 @@ def test_plan_executes_to_oracle(host_exec, fmt, om, im, rk, flags):
     assert O.rel_max_err(y, ref) < 1e-12
 
 
+@pytest.mark.parametrize("fmt,om,im,rk", CASES)
+def test_transposed_plan_executes_to_oracle(host_exec, fmt, om, im, rk):
+    """TN_FLAG_TRANSPOSE: the same tensors applied as W^T (activations carry the out-modes), walked on
+    the host in double precision and compared with X W for the oracle's dense W."""
+    rng = np.random.default_rng(sum(om) * 17 + sum(im))
+    ts = _rand_tensors(rng, fmt, om, im, rk)
+    w = O.dense_weight(fmt, ts, len(om))
+    x = rng.standard_normal((3, w.shape[0]))
+    for flags in (tn.TN_FLAG_TRANSPOSE, tn.TN_FLAG_TRANSPOSE | tn.TN_FLAG_NO_MERGE):
+        d, keep = _make_desc(fmt, tn.TN_DTYPE_F32, om, im, rk, None, 1, 0, flags, None)
+        t64 = [np.ascontiguousarray(t, dtype=np.float64) for t in ts]
+        ptrs = (ctypes.c_void_p * len(t64))(*[t.ctypes.data for t in t64])
+        y = np.zeros((3, w.shape[1]))
+        xc = np.ascontiguousarray(x)
+        assert host_exec.plan_host_forward(ctypes.byref(d), ptrs, xc.ctypes.data, y.ctypes.data, 3) == 0
+        assert O.rel_max_err(y, O.apply_linear(w.T, x)) <= 1e-12
+    assert tn.plan_query(fmt, tn.TN_DTYPE_F32, om, im, rk, tn.TN_QUERY_IN_FEATURES, flags=tn.TN_FLAG_TRANSPOSE) == w.shape[0]
+    assert tn.plan_query(fmt, tn.TN_DTYPE_F32, om, im, rk, tn.TN_QUERY_OUT_FEATURES, flags=tn.TN_FLAG_TRANSPOSE) == w.shape[1]
+
+
 def test_plan_small_baseline_config(host_exec):
     spec, toks = wl.baseline_spec(0)
     tensors = wl.make_tensors(spec, 0)
