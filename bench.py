@@ -186,8 +186,9 @@ def run_stack(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps first; the shader clock needs some tens of milliseconds of load to settle")
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--workload", type=int, default=1,
                     help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR); 4 = the mixed 64-layer stack")
@@ -266,6 +267,10 @@ def main() -> int:
         layer.forward(x, out=y)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # the timed region: K steps between two synchronisations. The library brackets every kernel launch
+    # of these same steps with a HIP event pair on the stream the kernels run on (tn_linear_profile), so
+    # the per-kernel durations below are those of the timed launches themselves.
+    layer.profile(True)
     t0 = time.perf_counter()
     e0.record(stream)
     for _ in range(args.steps):
@@ -273,16 +278,9 @@ def main() -> int:
     e1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    layer.profile(False)
     ms_per_step = e0.elapsed_time(e1) / args.steps
     tokens_per_s = tokens * args.steps / wall
-
-    # per-kernel durations: the same steps again with a HIP event pair around every launch,
-    # recorded by the library on the stream the kernels run on
-    layer.profile(True)
-    for _ in range(args.steps):
-        layer.forward(x, out=y)
-    torch.cuda.synchronize()
-    layer.profile(False)
     per_step = []
     reads = [layer.profile_read(s) for s in range(n_steps)]
     for s in range(n_steps):
