@@ -361,6 +361,26 @@ __global__ void __launch_bounds__(256) step_mfma_kernel(StepArgs a, int cmode) {
 // ---------------------------------------------------------------------------------------------
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
+// Workgroup -> output tile, XCD-aware. Workgroup i runs on XCD i % 8 (round-robin dispatch) and an
+// XCD runs about 32 of these workgroups at a time, all reading through its own 4 MB L2. XCD x owns the
+// row tiles x, x+8, x+16, ...; its workgroups walk them in bands of 4 row tiles, row fastest, so
+// that the 32 tiles in flight are 4 row tiles x 8 column tiles: 4 + 8 operand panels move through the
+// L2 at a time instead of 1 + 32 (a band of one row tile per XCD streams the whole packed tensor
+// from the fabric once per row tile, which bounded the large-K launches).
+__device__ __forceinline__ void tile_of_workgroup(int id, int nrow_tiles, int ncol_tiles, int* row_tile, int* col_tile) {
+    constexpr int BAND = 4;
+    const int xcd = id & 7, slot = id >> 3;
+    const int rows_per_xcd = (nrow_tiles + 7) >> 3;                  // the grid is padded to whole XCD rows
+    const int band = slot / (BAND * ncol_tiles);
+    const int in_band = slot - band * (BAND * ncol_tiles);
+    const int band_rows = min(BAND, rows_per_xcd - band * BAND);
+    const int col = in_band / band_rows;
+    const int r = in_band - col * band_rows;
+    *row_tile = (band * BAND + r) * 8 + xcd;
+    *col_tile = col;
+}
+
+
 template <int WM, int WN, int TM, int TN, int AMODE, int STAGES, int MINB, int TRANS>
 __global__ void __launch_bounds__(WM * WN * 64, MINB)
 step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
@@ -374,10 +394,8 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
     bf16_t* smem = reinterpret_cast<bf16_t*>(dyn_smem);
 
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
-    const int row_tile = (slot / ncol_tiles) * 8 + xcd;
-    const int col_tile = slot % ncol_tiles;
+    int row_tile, col_tile;
+    tile_of_workgroup(blockIdx.x, nrow_tiles, ncol_tiles, &row_tile, &col_tile);
     if (row_tile >= nrow_tiles) return;
     const uint32_t row0 = uint32_t(row_tile) * BM;
     const int col0 = col_tile * BN;
@@ -590,10 +608,8 @@ step_mfma_dlds_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
     static_assert(NS >= 3 && NS <= 4 && 2 * L <= 63, "ring depth / vmcnt range");
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
 
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
-    const int row_tile = (slot / ncol_tiles) * 8 + xcd;
-    const int col_tile = slot % ncol_tiles;
+    int row_tile, col_tile;
+    tile_of_workgroup(blockIdx.x, nrow_tiles, ncol_tiles, &row_tile, &col_tile);
     if (row_tile >= nrow_tiles) return;
     const uint32_t row0 = uint32_t(row_tile) * BM;
     const int col0 = col_tile * BN;
@@ -639,10 +655,11 @@ step_mfma_dlds_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
                 (const void __attribute__((address_space(1)))*)(b_src[j] + int64_t(kt) * 2 * 512),
                 (void __attribute__((address_space(3)))*)(sbase + A_BYTES + (j * NWAVE + wave) * 1024), 16, 0, 0);
     };
-    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform
+    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform, at most NS - 2
         if (n <= 0) wait_vmcnt<0>();
         else if (n == 1) wait_vmcnt<L>();
-        else wait_vmcnt<2 * L>();
+        else if (n == 2 || NS <= 4) wait_vmcnt<2 * L>();
+        else wait_vmcnt<3 * L>();
     };
 
     floatx16 acc[TM][TN];
