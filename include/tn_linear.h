@@ -171,8 +171,10 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc);
  *  x  DEVICE [tokens, N] of the handle's dtype, read only
  *  y  DEVICE [tokens, M] of the handle's dtype, fully overwritten
  *  x and y must not overlap each other. Enqueues kernels on `stream`
- *  (hipStream_t) and returns without synchronising or allocating. tokens == 0
- *  is a no-op. One forward per handle may be in flight at a time (the
+ *  (hipStream_t) and returns without synchronising or allocating; with
+ *  profiling off it makes no other HIP call than kernel launches, so it may be
+ *  recorded into a HIP graph (stream capture) from the handle's first call on.
+ *  tokens == 0 is a no-op. One forward per handle may be in flight at a time (the
  *  workspace is shared); different handles are independent. Results are
  *  bit-identical from call to call for the same handle, inputs and token count.
  */

@@ -1921,13 +1921,12 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
     static const kern_t kerns[4] = {
         step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 0>, step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 0>,
         step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 1>, step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 1>};
-    static bool configured = false;   // per instantiation
-    if (!configured) {
+    if (!s.packed) {                       // configuration call (create time): raise the kernels' LDS limit
         for (kern_t k : kerns)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     int(smem)) != hipSuccess)
                 return TN_ERR_HIP;
-        configured = true;
+        return TN_OK;
     }
     kern_t k = kerns[(s.cmode == 2 ? 2 : 0) + (s.amode == 0 ? 0 : 1)];
     hipLaunchKernelGGL(k, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
@@ -1944,13 +1943,12 @@ int launch_dlds(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
     using kern_t = void (*)(StepArgs, int, int, int);
     static const kern_t kerns[2] = {step_mfma_dlds_kernel<WM, WN, TM, TN, NS, MINB, 0>,
                                     step_mfma_dlds_kernel<WM, WN, TM, TN, NS, MINB, 1>};
-    static bool configured = false;   // per instantiation
-    if (!configured) {
+    if (!s.packed) {                       // configuration call (create time)
         for (kern_t k : kerns)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     int(smem)) != hipSuccess)
                 return TN_ERR_HIP;
-        configured = true;
+        return TN_OK;
     }
     hipLaunchKernelGGL(kerns[s.cmode == 2 ? 1 : 0], grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
     return TN_OK;
@@ -2111,15 +2109,6 @@ int launch_fused2(const DevStep& s1, const DevStep& s2, const void* A, void* Out
     f.tokens = int32_t(tokens);
     f.in_elems = s1.fused_in_elems;
     f.mid_elems = s1.fused_mid_elems;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<0>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess)
-            return TN_ERR_HIP;
-        configured = true;
-    }
     dim3 grid(uint32_t(std::min<int64_t>(tokens, 1024)));
     if (s2.cmode == 1)
         hipLaunchKernelGGL(step_fused2_kernel<1>, grid, dim3(256), s1.fused_smem, st, f);
@@ -2146,9 +2135,6 @@ int prepare_pair(tn_linear_s* h, hipStream_t st) {
     hipLaunchKernelGGL(pair_repack_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const bf16_t*>(s1.packed),
                        static_cast<bf16_t*>(h->pair_b1f), A, s1.Kp >> 4, s1.Cp);
     if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            int(kPairSmemBytes)) != hipSuccess)
-        return TN_ERR_HIP;
     h->pair = true;
     h->pair_min_tokens = kPairMinTokens;
     return TN_OK;
@@ -2224,6 +2210,17 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
 
 int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens,
                   hipStream_t st) {
+    using k_t = void (*)(Chain2Args);
+    static const k_t kerns[4] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
+                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>};
+    static const size_t smem[2] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>()};
+    if (!s1.packed) {                      // configuration call (create time)
+        for (int i = 0; i < 4; ++i)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(smem[i / 2])) != hipSuccess)
+                return TN_ERR_HIP;
+        return TN_OK;
+    }
     Chain2Args p;
     p.In = A;
     p.Out = Out;
@@ -2246,20 +2243,34 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
     const int64_t n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const int64_t items = tokens * n_groups;
     dim3 grid(uint32_t(std::min<int64_t>((items + 3) / 4, h->num_cus)));
-    using k_t = void (*)(Chain2Args);
-    static const k_t kerns[4] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
-                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>};
-    static const size_t smem[2] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>()};
-    static bool configured = false;
-    if (!configured) {
-        for (int i = 0; i < 4; ++i)
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(smem[i / 2])) != hipSuccess)
-                return TN_ERR_HIP;
-        configured = true;
-    }
     hipLaunchKernelGGL(kerns[s1.chain_cfg * 2 + s1.chain_run_c1], grid, dim3(256), smem[s1.chain_cfg], st, p);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+// Kernels that use more than 64 KB of LDS need their limit raised once per device. Done at create
+// time (never inside tn_linear_forward, which must stay legal under stream capture from its first
+// call). The launchers double as configurators: called with an empty step they set the attribute of
+// every kernel they can launch and return.
+int configure_kernels(int device) {
+    static bool done[64] = {};
+    if (device >= 0 && device < 64 && done[device]) return TN_OK;
+    const DevStep none;                    // packed == nullptr: configuration call
+    const StepArgs a{};
+    const tn_linear_s* no_handle = nullptr;
+    int rc = launch_pipe<2, 2, 2, 4, 1, 2>(none, a, 0, nullptr);
+    if (rc == TN_OK) rc = launch_pipe<4, 1, 2, 4, 1, 2>(none, a, 0, nullptr);
+    if (rc == TN_OK) rc = launch_dlds<4, 2, 2, 4, 4, 1>(none, a, 0, nullptr);
+    if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
+    if (rc == TN_OK &&
+        (hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<0>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
+         hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<1>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
+         hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess))
+        rc = TN_ERR_HIP;
+    if (rc == TN_OK && device >= 0 && device < 64) done[device] = true;
+    return rc;
 }
 
 int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
@@ -2461,6 +2472,10 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             return TN_ERR_UNSUPPORTED;
         }
         h->num_cus = std::max(1, prop.multiProcessorCount);
+        if (configure_kernels(h->device) != TN_OK) {
+            delete h;
+            return TN_ERR_HIP;
+        }
     }
     hipStream_t st = static_cast<hipStream_t>(desc->stream);
     h->elt = desc->dtype == TN_DTYPE_BF16 ? 2 : 4;

@@ -442,3 +442,32 @@ def test_transposed_baseline_configs(i, dense_w):
         print(f"workload {i} transposed T={tokens} rel err {err:.3e}", flush=True)
         assert err <= TOL["bf16"]
     layer.close()
+
+
+@pytest.mark.parametrize("i", [1, 2])
+def test_forward_under_stream_capture(i, dense_w):
+    """tn_linear_forward neither allocates nor synchronises: the very first call of a fresh handle may be
+    recorded into a HIP graph. Replays (with eager work and synchronisations in between) must give the
+    eager result bit for bit, at a decode size and at a size that runs the chained kernels."""
+    spec, ts, w = dense_w(i)
+    for tokens in (1, 300):
+        x = to_dev(wl.make_x(spec, tokens, i), "bf16")
+        layer = make_layer(spec, ts, tokens)
+        y_graph = torch.empty((tokens, spec.M), dtype=torch.bfloat16, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(x, out=y_graph)
+        y_eager = layer(x)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            y_graph.fill_(0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_graph, y_eager)
+            assert torch.equal(layer(x), y_eager)
+        assert O.rel_max_err(to_host(y_graph), O.apply_linear(w, wl.make_x(spec, tokens, i))) <= TOL["bf16"]
+        del graph
+        layer.close()
