@@ -99,7 +99,11 @@ extern "C" {
                                            5 kernel variant chosen (0 plain FMA, 2 narrow 256x32 tile, else
                                              the ids listed at TN_FLAG_VARIANT_SHIFT),
                                            6 1 if this step and the next run as one fused launch, 2 if they
-                                             do so from 256 tokens on (chained pair kernel) */
+                                             do so from 256 tokens on (chained pair kernel),
+                                           7 shape test only (also from plan_query): 0, or 1 + the instantiation
+                                             of the transposing chain kernel that could run this step with the
+                                             next one (consecutive qualifying pairs overlap: create takes them
+                                             left to right) */
 
 typedef struct tn_linear_s* tn_linear_t;
 

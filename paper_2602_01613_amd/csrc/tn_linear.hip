@@ -2175,23 +2175,9 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
         DevStep& a = h->steps[i];
         DevStep& b = h->steps[i + 1];
         if (i > 0 && h->steps[i - 1].fuse_next) continue;
-        const tn::Step& pa = a.plan;
-        const tn::Step& pb = b.plan;
         if (a.variant == VAR_SCALAR || b.variant == VAR_SCALAR) continue;
-        if (!pa.a_plain || !pb.a_plain || pa.K % 8) continue;
-        if (pb.K != pa.R || pb.R != pa.C || pa.c_tok_stride != pa.C * pa.R) continue;
-        int cfg;
-        if (pa.R <= 64 && pa.K <= 128 && pb.C <= 64) cfg = 1;
-        else if (pa.R <= 96 && pa.K <= 96 && pb.C <= 160) cfg = 0;
-        else continue;
-        bool transposed = true;
-        for (int64_t r = 0; r < pa.R && transposed; ++r) transposed = pa.crow[size_t(r)] == r;
-        for (int64_t c = 0; c < pa.C && transposed; ++c) transposed = pa.ccol[size_t(c)] == c * pa.R;
-        if (!transposed) continue;
-        int run_c1;
-        if (pb.r_vec == 8) run_c1 = 1;
-        else if (pb.c_vec == 8) run_c1 = 0;
-        else continue;
+        int cfg = 0, run_c1 = 0;
+        if (!tn::chain2_shape(h->plan, a.plan, b.plan, &cfg, &run_c1)) continue;
         const int C2T = cfg == 0 ? 5 : 2, KS = cfg == 0 ? 6 : 4;
         size_t elems = size_t(C2T) * KS * 512;
         if (hipMalloc(&a.chain_bbf, elems * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
@@ -2295,6 +2281,12 @@ int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
             case 2: *value = st.C; return TN_OK;
             case 3: *value = st.flops; return TN_OK;
             case 4: *value = st.slot; return TN_OK;
+            case 7: {
+                int cfg = 0, run_c1 = 0;
+                *value = (size_t(s) + 1 < p.steps.size() && !tn::pair_chainable(p) &&
+                          tn::chain2_shape(p, st, p.steps[size_t(s) + 1], &cfg, &run_c1)) ? 1 + cfg : 0;
+                return TN_OK;
+            }
             default: return TN_ERR_INVALID_ARG;
         }
     }

@@ -633,6 +633,28 @@ inline bool pair_chainable(const Plan& p) {
     return s1.r_vec == 8;
 }
 
+// Can steps a and b (consecutive) run on the transposing chain kernel? Both plain; b contracts a's row
+// index and keeps a's column index as its row index, i.e. a's output is stored transposed ([c1][r]);
+// the output takes 8 consecutive c1 (run_c1 = 1) or 8 consecutive c2 (run_c1 = 0) as one aligned piece;
+// sizes within one of the two instantiations (cfg 1: R1 <= 64, K1 <= 128, C2 <= 64; cfg 0: R1 <= 96,
+// K1 <= 96, C2 <= 160).
+inline bool chain2_shape(const Plan& p, const Step& a, const Step& b, int* cfg, int* run_c1) {
+    if (p.dtype != TN_DTYPE_BF16) return false;
+    if (!a.a_plain || !b.a_plain || a.K % 8) return false;
+    if (b.K != a.R || b.R != a.C || a.c_tok_stride != a.C * a.R) return false;
+    if (a.R <= 64 && a.K <= 128 && b.C <= 64) *cfg = 1;
+    else if (a.R <= 96 && a.K <= 96 && b.C <= 160) *cfg = 0;
+    else return false;
+    for (int64_t r = 0; r < a.R; ++r)
+        if (a.crow[size_t(r)] != r) return false;
+    for (int64_t c = 0; c < a.C; ++c)
+        if (a.ccol[size_t(c)] != c * a.R) return false;
+    if (b.r_vec == 8) *run_c1 = 1;
+    else if (b.c_vec == 8) *run_c1 = 0;
+    else return false;
+    return true;
+}
+
 inline int make_plan(const tn_linear_desc* d, Plan* p) {
     int rc = build_network(d, p);
     if (rc != TN_OK) return rc;

@@ -196,6 +196,25 @@ def test_pair_chainable_plans():
         assert q(s.format, s.out_modes, s.in_modes, s.ranks) == 0
 
 
+def test_chain2_shapes():
+    """Which step pairs qualify for the transposing chain kernel: the factor products of Tucker layers
+    whose first step reads a plain matrix, in the smaller instantiation where it fits."""
+    def shapes(fmt, om, im, rk, flags=0):
+        n = tn.plan_query(fmt, tn.TN_DTYPE_BF16, om, im, rk, tn.TN_QUERY_NUM_STEPS, flags=flags)
+        return [tn.plan_query(fmt, tn.TN_DTYPE_BF16, om, im, rk, tn.TN_QUERY_STEP_BASE + 10 * s + 7, flags=flags)
+                for s in range(n)]
+    s2, _ = wl.baseline_spec(2)
+    # in-factors 64x80 -> 48x48 fit the small instantiation (2), out-factors 96x96 -> 160x160 the large one (1)
+    assert shapes(s2.format, s2.out_modes, s2.in_modes, s2.ranks) == [2, 0, 0, 1, 0]
+    assert shapes(tn.TN_FORMAT_TUCKER, (40, 72), (24, 40), (24, 40, 16, 24)) == [0, 0, 0, 2, 0]   # first step gathers
+    assert shapes(tn.TN_FORMAT_TUCKER, (160, 160), (160, 160), (96, 96, 48, 48))[0] == 0          # 160 input rows
+    for i in (1, 3):
+        s, _ = wl.baseline_spec(i)
+        assert not any(shapes(s.format, s.out_modes, s.in_modes, s.ranks))
+        assert not any(shapes(s.format, s.out_modes, s.in_modes, s.ranks, tn.TN_FLAG_NO_MERGE))
+    assert tn.plan_query(s2.format, tn.TN_DTYPE_F32, s2.out_modes, s2.in_modes, s2.ranks, tn.TN_QUERY_STEP_BASE + 7) == 0
+
+
 def test_growing_merges_half_ring():
     # TR down_proj with TN_FLAG_MERGE_GROW: cores (4,1) and (2,3) are contracted at create time
     # (23.6 M parameters, under a quarter of the dense 131 M) and the chain is two steps,
