@@ -199,7 +199,7 @@ def main() -> int:
                     help="one matrix of the stack instead of a numbered workload: format,in,out,rank "
                          "(e.g. tr,25600,5120,96)")
     ap.add_argument("--layers", type=int, default=64, help="layers of the stack (workload 4)")
-    ap.add_argument("--stack-workspace-gb", type=int, default=24, help="shared workspace of the stack in GiB")
+    ap.add_argument("--stack-workspace-gb", type=int, default=64, help="shared workspace of the stack in GiB")
     ap.add_argument("--workspace-mb", type=int, default=0, help="workspace limit in MiB (0 = library default)")
     ap.add_argument("--variant", type=int, default=0, help="tuning override: kernel variant id of the wide steps")
     ap.add_argument("--no-merge", action="store_true",

@@ -301,6 +301,15 @@ def test_invalid_descriptions_are_rejected():
         tn.plan_query(tn.TN_FORMAT_TT, 5, (4,), (4,), (1, 1), tn.TN_QUERY_FLOPS_PER_TOKEN)
 
 
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """There is no CPU or fallback path: without the built library the binding raises."""
+    import paper_2602_01613_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "library_path", lambda: str(tmp_path / "libtn_linear.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        b.load_library()
+
+
 def test_library_exports_every_declared_symbol():
     import re
     hdr = open(os.path.join(os.path.dirname(HERE), "include", "tn_linear.h")).read()
