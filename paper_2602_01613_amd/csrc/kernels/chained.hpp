@@ -1,0 +1,461 @@
+// Chained kernels: two contraction steps in one launch with the intermediate kept in the MFMA register layout.
+// Part of the tn_linear library's single translation unit: included by tn_linear.hip inside its
+// anonymous namespace, after <hip/hip_runtime.h> and tn_plan.hpp.
+#pragma once
+
+// ---------------------------------------------------------------------------------------------
+// Chained pair kernel: a short-K step followed by a long-K step whose K is (rows of the first
+// step) x (a bond of 64), the shape a tensor train takes once its end cores are contracted into
+// their neighbours (Section 3.5: fuse core contractions, specialise for shared ranks):
+//     Z[t][j][a][b] = sum_k  X[t][a*64 + k] * B0[j*64 + b][k]          K0 = 64, bond b < 64
+//     Y[t][yrow[j] + ycol[c]] = sum_{a, b} Z[t][j][a][b] * B1[c][a*64 + b]      c < C1 <= 128
+// Unfused, Z (A*J*64 values per token) is written to and read back from HBM and both launches are
+// bound by that traffic. Here Z never leaves the registers: a workgroup owns 32 tokens and 8
+// values of j (two per wave) and walks over a. For one a, a wave computes Z^T[b][t] for its two j
+// with the packed tensor of the first step as the row operand (kept in registers for the whole
+// walk) and the tokens as MFMA columns; the result lands in the accumulator layout (lane: token
+// l%32, b = 8*(v/4) + 4*(l/32) + v%4), which after rounding to bf16 IS the column operand of the
+// second contraction when that step's packed tensor is stored with the same permutation of b
+// inside each k-step of 16 (done once at create time by pair_repack_kernel). Per a the workgroup
+// streams a 16 KB slice of B1 and 4 KB of X into a ring of LDS stages with direct-to-LDS loads.
+// The 32 x C1 x 8 results of the workgroup are transposed through LDS and stored as 16-byte
+// pieces (8 consecutive j). Workgroups that share a token tile run back to back on one XCD, so
+// that their reads of X and their pieces of the same output lines meet in that XCD's L2.
+// ---------------------------------------------------------------------------------------------
+struct PairArgs {
+    const void* X;
+    void* Y;
+    const void* B0;        // first step's packed tensor, fragment-major [J*64][64]
+    const void* B1f;       // second step's packed tensor in the chained layout (pair_repack_kernel)
+    const int32_t* yrow;   // output offset of j (J entries, aligned runs of 8)
+    const int32_t* ycol;   // output offset of c (C1 entries, multiples of 8)
+    int64_t N, M;          // elements per token of X and Y
+    int32_t tokens, A, J, C1;
+    int32_t n_tok_tiles, n_jsets;
+};
+
+// B1f[((a*16 + ct*4 + s)*64 + l)*8 + e] = B1[c = 32*ct + l%32][k = a*64 + 16*s + 8*(e/4) + 4*(l/32) + e%4]
+__global__ void __launch_bounds__(256) pair_repack_kernel(const bf16_t* src, bf16_t* dst, int A, int nks, int Cp) {
+    int64_t total = int64_t(A) * 8192;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
+        int e = int(i & 7), l = int(i >> 3) & 63, blk = int(i >> 9) & 15;
+        int a = int(i >> 13);
+        int c = 32 * (blk >> 2) + (l & 31);
+        int k = a * 64 + 16 * (blk & 3) + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+        dst[i] = c < Cp ? src[bfrag_offset(c, k, nks)] : bf16_t(0.f);      // columns past Cp do not exist
+    }
+}
+
+template <int NS>
+__global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
+    constexpr int L = 5;                               // NS ring stages; L direct-to-LDS loads per wave and stage
+    constexpr int STAGE_BYTES = 20 * 1024, X_OFF = 16 * 1024;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int tok_tile = (slot / p.n_jsets) * 8 + xcd;
+    const int jset = slot % p.n_jsets;
+    if (tok_tile >= p.n_tok_tiles) return;
+    const int t0 = tok_tile * 32;
+
+    const bf16_t* X = static_cast<const bf16_t*>(p.X);
+    const bf16_t* B0 = static_cast<const bf16_t*>(p.B0);
+    const bf16_t* B1f = static_cast<const bf16_t*>(p.B1f);
+    bf16_t* Y = static_cast<bf16_t*>(p.Y);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j0 = jset * 8 + wave * 2;
+    const int A = p.A;
+
+    // the wave's rows of the first packed tensor: [jj][32-row half of the bond][k-step]
+    bf16x8 p0[2][2][4];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                p0[jj][rt][s] = *reinterpret_cast<const bf16x8*>(B0 + (int64_t((j0 + jj) * 2 + rt) * 4 + s) * 512 + lane * 8);
+
+    // direct-to-LDS sources: wave w brings blocks w, w+4, w+8, w+12 of the B1 slice and k-step w of X
+    const int tl = min(t0 + (lane & 31), p.tokens - 1);             // rows past the end repeat the last token
+    const bf16_t* x_src = X + int64_t(tl) * p.N + 16 * wave + 8 * (lane >> 5);
+    const bf16_t* b_src = B1f + lane * 8;
+    auto issue = [&](int a, int stage) {
+        unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)(b_src + (int64_t(a) * 16 + wave + 4 * q) * 512),
+                (void __attribute__((address_space(3)))*)(sbase + (wave + 4 * q) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(x_src + int64_t(a) * 64),
+            (void __attribute__((address_space(3)))*)(sbase + X_OFF + wave * 1024), 16, 0, 0);
+    };
+    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform, at most NS - 2
+        if (n <= 0) wait_vmcnt<0>();
+        else if (n == 1) wait_vmcnt<L>();
+        else if (n == 2 || NS <= 4) wait_vmcnt<2 * L>();
+        else if (n == 3 || NS <= 5) wait_vmcnt<3 * L>();
+        else wait_vmcnt<4 * L>();
+    };
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[jj][ct][v] = 0.f;
+
+    int issued = 0;
+    for (; issued < NS - 1 && issued < A; ++issued) issue(issued, issued);
+    wait_outstanding_tiles(min(issued - 1, NS - 2));     // tile 0 has landed
+    __syncthreads();
+    bf16x8 xb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(dyn_smem + X_OFF + s * 1024 + lane * 16);
+
+    // first contraction for one j: Z^T[b][t], two 32-row halves of the bond
+    auto contract0 = [&](const bf16x8 (&w)[2][4], const bf16x8 (&x)[4], floatx16 (&z)[2]) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[rt][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+                z[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[rt][s], x[s], z[rt], 0, 0, 0);
+    };
+    // second contraction for one j: Y^T[c][t] += B1[c][(a, b)] Z^T[b][t]. Registers 8*(s%2) .. +7 of
+    // half s/2 of z are the 8 values this lane supplies to k-step s.
+    auto contract1 = [&](const bf16x8 (&w)[4][4], const floatx16 (&z)[2], floatx16 (&y)[4]) {
+        bf16x8 zb[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) zb[s][e] = bf16_t(z[s >> 1][8 * (s & 1) + e]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+                y[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ct][s], zb[s], y[ct], 0, 0, 0);
+    };
+
+    // software pipeline over (a, j): the first contraction of the next unit is issued before the
+    // second contraction of the current one, so that reading back and rounding Z overlaps MFMAs
+    floatx16 z0[2], z1[2];
+    contract0(p0[0], xb, z0);
+    auto iteration = [&](int a, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value;
+        if (!LAST) wait_outstanding_tiles(issued - (a + 2));       // tile a+1 has landed
+        __syncthreads();       // everyone is done with tile a-1: its stage may be refilled
+        if (issued < A) {
+            issue(issued, issued % NS);
+            ++issued;
+        }
+        const unsigned char* scur = dyn_smem + (a % NS) * STAGE_BYTES;
+        const unsigned char* snxt = dyn_smem + ((a + 1) % NS) * STAGE_BYTES;
+        bf16x8 p1[4][4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                p1[ct][s] = *reinterpret_cast<const bf16x8*>(scur + (ct * 4 + s) * 1024 + lane * 16);
+        // the scheduler would otherwise sink each LDS read next to its first use and expose the LDS
+        // latency 16 times per iteration
+        __builtin_amdgcn_sched_barrier(0);
+        contract0(p0[1], xb, z1);
+        if (!LAST) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(snxt + X_OFF + s * 1024 + lane * 16);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        contract1(p1, z0, acc[0]);
+        if (!LAST) contract0(p0[0], xb, z0);
+        contract1(p1, z1, acc[1]);
+        // keep the accumulators in the accumulation registers across the back edge (the register
+        // allocator otherwise parks some of them in ordinary registers and copies them every
+        // iteration)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) asm volatile("" : "+a"(acc[jj][ct]));
+        if (!LAST) {
+            asm volatile("" : "+a"(z0[0]));
+            asm volatile("" : "+a"(z0[1]));
+        }
+    };
+    for (int a = 0; a + 1 < A; ++a) iteration(a, std::false_type());
+    iteration(A - 1, std::true_type());
+    __syncthreads();
+
+    // ---- epilogue: lane l, register v of acc[jj][ct] is token l%32, c = 32*ct + 8*(v/4) + 4*(l/32) + v%4.
+    //      LDS holds [32 tokens][128 c] pieces of 16 bytes (the 8 j of the workgroup), the piece of
+    //      (t, c) at position c ^ t of row t so that neither the 4-byte writes nor the 16-byte reads
+    //      pile up on a bank.
+    {
+        const int t = lane & 31;
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int c = 32 * ct + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                bf16x2 pr;
+                pr[0] = bf16_t(acc[0][ct][v]);
+                pr[1] = bf16_t(acc[1][ct][v]);
+                *reinterpret_cast<bf16x2*>(dyn_smem + (t * 128 + (c ^ t)) * 16 + wave * 4) = pr;
+            }
+    }
+    __syncthreads();
+    const int yj = p.yrow[jset * 8];
+#pragma unroll 4
+    for (int e = tid; e < 32 * 128; e += 256) {
+        int t = e >> 7, c = e & 127;
+        if (t0 + t >= p.tokens || c >= p.C1) continue;
+        bf16x8 v = *reinterpret_cast<const bf16x8*>(dyn_smem + (t * 128 + (c ^ t)) * 16);
+        *reinterpret_cast<bf16x8*>(Y + int64_t(t0 + t) * p.M + p.ycol[c] + yj) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transposing chain of two small steps (the two in-factor or the two out-factor products of a
+// Tucker layer): the second step contracts the ROW index r of the first and keeps its column index
+// c1 as a row,
+//     T[r][c1] = sum_k  In[t][r][k] * Ba[c1][k]                    R1 x K1 input per token
+//     Out[t][off1[c1] + off2[c2]] = sum_r T[r][c1] * Bb[c2][r]
+// A wave owns one token at a time. The token's input travels from memory straight into a
+// wave-private LDS buffer in MFMA fragment order (direct-to-LDS loads, double buffered: the next
+// token's input is in flight while the current one is computed; no workgroup barrier anywhere).
+// For each tile of 32 values of c1 the wave computes T^T as accumulator tiles with r in the
+// registers and c1 across the lanes, rounds them to bf16 and feeds them - without leaving the
+// registers - to the second contraction, whose packed tensor is stored at create time with the
+// matching permutation of r inside each k-step (chain2_repack_kernel) and stays in registers for
+// all tokens. The intermediate T never exists in memory, one launch replaces two, and the HBM
+// traffic drops to the first step's input plus the second step's output.
+// RUN_C1 = 1: the output takes 8 consecutive c1 as an aligned 16-byte piece (T^T is the row operand
+// of the second MFMA, so a lane ends up with 4 consecutive c1); RUN_C1 = 0: 8 consecutive c2 (T^T is
+// the column operand). Either way the 32x32 result tiles pass through a wave-private LDS patch and
+// leave as 16-byte stores.
+// Limits: R1 <= 32*R1T, K1 <= 16*K1S, K1 % 8 == 0, C2 <= 32*C2T; any C1.
+// ---------------------------------------------------------------------------------------------
+struct Chain2Args {
+    const void* In;
+    void* Out;
+    const void* Ba;         // first step's packed tensor (fragment-major, nks_a k-steps per column block)
+    const void* Bbf;        // second step's packed tensor in the chained layout
+    const int32_t* off1;    // output offset of c1 (the second step's row table)
+    const int32_t* off2;    // output offset of c2 (the second step's column table)
+    int64_t in_tok_stride, out_tok_stride;
+    int32_t tokens, R1, K1, C1, C2;
+    int32_t nks_a;
+    int32_t c1_tiles;       // ceil(C1 / 32)
+    int32_t tiles_per_item; // c1 tiles one wave handles per visit of a token (all of them for large
+                            // batches; 1 spreads a single token over several waves)
+};
+
+// Bbf[((j*KS + s)*64 + l)*8 + e] = Bb[c2 = 32*j + l%32][r = 16*s + 8*(e/4) + 4*(l/32) + e%4], zero outside
+__global__ void __launch_bounds__(256) chain2_repack_kernel(const bf16_t* src, bf16_t* dst, int C2T, int KS,
+                                                            int nks_src, int Cp, int Kp) {
+    int total = C2T * KS * 512;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        int e = i & 7, l = (i >> 3) & 63, blk = i >> 9;
+        int j = blk / KS, sk = blk - j * KS;
+        int c = 32 * j + (l & 31);
+        int k = 16 * sk + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+        dst[i] = (c < Cp && k < Kp) ? src[bfrag_offset(c, k, nks_src)] : bf16_t(0.f);
+    }
+}
+
+template <int R1T, int K1S, int C2T>
+constexpr size_t chain2_smem_bytes() {
+    return size_t(4) * (R1T * K1S * 1024 + 2 * 32 * 80);
+}
+
+template <int R1T, int K1S, int C2T, int RUN_C1>
+__global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
+    constexpr int IN_BYTES = R1T * K1S * 1024;           // one token's input in fragment order
+    constexpr int KS2 = 2 * R1T;                         // k-steps of the second contraction
+    constexpr int PATCH_LD = 80;                         // bytes per patch row (64 + 16 of padding)
+    constexpr int PATCH_BYTES = 32 * PATCH_LD;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    const bf16_t* In = static_cast<const bf16_t*>(p.In);
+    const bf16_t* Ba = static_cast<const bf16_t*>(p.Ba);
+    const bf16_t* Bbf = static_cast<const bf16_t*>(p.Bbf);
+    bf16_t* Out = static_cast<bf16_t*>(p.Out);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    unsigned char* my_in = dyn_smem + wave * IN_BYTES;
+    unsigned char* my_patch = dyn_smem + 4 * IN_BYTES + wave * (2 * PATCH_BYTES);
+
+    const int n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
+    const int64_t n_items = int64_t(p.tokens) * n_groups;
+    const int64_t gw = int64_t(blockIdx.x) * 4 + wave, GW = int64_t(gridDim.x) * 4;
+    if (gw >= n_items) return;                           // no workgroup barrier below: a wave may leave
+
+    // lanes whose (row, k) lies outside the input never load: the fragment blocks they belong to are
+    // zeroed once and keep those zeros
+#pragma unroll
+    for (int i = 0; i < R1T; ++i)
+#pragma unroll
+        for (int sk = 0; sk < K1S; ++sk)
+            if (32 * i + 32 > p.R1 || 16 * sk + 16 > p.K1) {        // wave-uniform
+                bf16x8 z;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
+                *reinterpret_cast<bf16x8*>(my_in + (i * K1S + sk) * 1024 + lane * 16) = z;
+            }
+    __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): the zeros are in LDS before any load lands
+    __builtin_amdgcn_wave_barrier();
+
+    // the second packed tensor stays in registers for every token of the wave
+    bf16x8 bb[C2T][KS2];
+#pragma unroll
+    for (int j = 0; j < C2T; ++j)
+#pragma unroll
+        for (int sk = 0; sk < KS2; ++sk)
+            bb[j][sk] = *reinterpret_cast<const bf16x8*>(Bbf + (int64_t(j) * KS2 + sk) * 512 + lane * 8);
+
+    const int nrt = (p.R1 + 31) >> 5, nks1 = (p.K1 + 15) >> 4;
+    const int nj = (p.C2 + 31) >> 5;
+    const int lrow = lane & 31, lk = 8 * (lane >> 5);
+    auto issue_in = [&](int t) {
+        const bf16_t* src = In + int64_t(t) * p.in_tok_stride + int64_t(lrow) * p.K1 + lk;
+#pragma unroll
+        for (int i = 0; i < R1T; ++i)
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk) {
+                if (i < nrt && sk < nks1) {                          // wave-uniform
+                    if (32 * i + lrow < p.R1 && 16 * sk + lk < p.K1)
+                        __builtin_amdgcn_global_load_lds(
+                            (const void __attribute__((address_space(1)))*)(src + int64_t(32 * i) * p.K1 + 16 * sk),
+                            (void __attribute__((address_space(3)))*)(my_in + (i * K1S + sk) * 1024), 16, 0, 0);
+                }
+            }
+    };
+    auto load_ba = [&](int ct1, bf16x8 (&ba)[K1S]) {
+#pragma unroll
+        for (int sk = 0; sk < K1S; ++sk)      // k-steps past the packed tensor's padding meet zero input: any finite block will do
+            ba[sk] = *reinterpret_cast<const bf16x8*>(Ba + (int64_t(ct1) * p.nks_a + min(sk, p.nks_a - 1)) * 512 + lane * 8);
+    };
+
+    // output offsets of the two 16-byte pieces a lane stores per 32x32 tile (patch row lane/4 + 16h,
+    // piece lane%4): those along c2 never change; those along c1 are fetched a tile ahead. -1 = outside.
+    const int prow = lane >> 2, pchunk = lane & 3;
+    int o2[C2T][2];
+#pragma unroll
+    for (int j = 0; j < C2T; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int c2 = 32 * j + (RUN_C1 ? prow + 16 * h : 8 * pchunk);
+            o2[j][h] = c2 < p.C2 ? p.off2[c2] : -1;
+        }
+    auto load_o1 = [&](int ct1, int (&o1)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int c1 = 32 * ct1 + (RUN_C1 ? 8 * pchunk : prow + 16 * h);
+            o1[h] = c1 < p.C1 ? p.off1[c1] : -1;
+        }
+    };
+
+    // Vector memory operations a full item issues after its input request (the packed-tensor loads and
+    // the stores of every tile but a possibly ragged last one, a lower bound). Loads complete in issue
+    // order, so once at most 63 operations are in flight an input request older than that has landed,
+    // without waiting for the latest stores to be acknowledged.
+    const int ops_after = max(0, p.tiles_per_item - ((p.C1 & 31) ? 1 : 0)) * (K1S + 2 * (p.C2 >> 5));
+    issue_in(int(gw / n_groups));
+    for (int64_t item = gw; item < n_items; item += GW) {
+        const int t = int(item / n_groups);
+        const int g = int(item - int64_t(t) * n_groups);
+        const int tile_begin = g * p.tiles_per_item;
+        const int tile_end = min(p.c1_tiles, tile_begin + p.tiles_per_item);
+        bf16x8 ba_next[K1S];
+        int o1_next[2];
+        load_ba(tile_begin, ba_next);
+        load_o1(tile_begin, o1_next);
+        if (item == gw || ops_after < 66 + K1S) wait_vmcnt<0>();
+        else wait_vmcnt<61 - K1S>();                                  // the loads above are younger still
+        // the token's input moves to registers; its LDS buffer then takes the next item's input,
+        // which travels while this item is computed
+        bf16x8 inf[R1T][K1S];
+#pragma unroll
+        for (int i = 0; i < R1T; ++i)
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk)      // slots outside the input hold zeros
+                inf[i][sk] = *reinterpret_cast<const bf16x8*>(my_in + (i * K1S + sk) * 1024 + lane * 16);
+        __builtin_amdgcn_s_waitcnt(0xc07f);                          // the reads are done before the buffer is refilled
+        if (item + GW < n_items) issue_in(int((item + GW) / n_groups));
+        bf16_t* out_t = Out + int64_t(t) * p.out_tok_stride;
+        for (int ct1 = tile_begin; ct1 < tile_end; ++ct1) {
+            bf16x8 ba[K1S];
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk) ba[sk] = ba_next[sk];
+            const int o1[2] = {o1_next[0], o1_next[1]};
+            if (ct1 + 1 < tile_end) {
+                load_ba(ct1 + 1, ba_next);
+                load_o1(ct1 + 1, o1_next);
+            }
+            // first contraction: accumulator tile i holds T^T for r in [32i, 32i+32): lane l has c1 = l%32,
+            // register v has r = 32i + 8*(v/4) + 4*(l/32) + v%4
+            floatx16 d[R1T];
+#pragma unroll
+            for (int i = 0; i < R1T; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) d[i][v] = 0.f;
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk)
+#pragma unroll
+                for (int i = 0; i < R1T; ++i)
+                    d[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(inf[i][sk], ba[sk], d[i], 0, 0, 0);
+            bf16x8 zb[KS2];
+#pragma unroll
+            for (int i = 0; i < R1T; ++i)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) zb[2 * i + u][e] = bf16_t(d[i][8 * u + e]);
+            // second contraction: all tiles of c2 (independent accumulators), then their way out
+            floatx16 acc[C2T];
+#pragma unroll
+            for (int j = 0; j < C2T; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+#pragma unroll
+            for (int sk = 0; sk < KS2; ++sk)
+#pragma unroll
+                for (int j = 0; j < C2T; ++j)
+                        acc[j] = RUN_C1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(zb[sk], bb[j][sk], acc[j], 0, 0, 0)
+                                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j][sk], zb[sk], acc[j], 0, 0, 0);
+            // RUN_C1: lane l holds c2 = 32j + l%32 and, in registers 4q..4q+3, c1 = 32*ct1 + 8q + 4*(l/32) + 0..3
+            // else  : lane l holds c1 = 32*ct1 + l%32 and c2 = 32j + 8q + 4*(l/32) + 0..3
+            // The 32x32 tiles pass through two alternating wave-private LDS patches and leave as 16-byte
+            // pieces; a patch is rewritten two tiles later, after the wave barrier of the tile between.
+#pragma unroll
+            for (int j = 0; j < C2T; ++j) {
+                if (j >= nj) continue;                                 // wave-uniform
+                unsigned char* patch = my_patch + (j & 1) * PATCH_BYTES;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[j][4 * q + u]);
+                    *reinterpret_cast<bf16x4*>(patch + (lane & 31) * PATCH_LD + (8 * q + 4 * (lane >> 5)) * 2) = pk;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    bf16x8 v = *reinterpret_cast<const bf16x8*>(patch + (prow + 16 * h) * PATCH_LD + pchunk * 16);
+                    if (o1[h] >= 0 && o2[j][h] >= 0) *reinterpret_cast<bf16x8*>(out_t + o1[h] + o2[j][h]) = v;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+

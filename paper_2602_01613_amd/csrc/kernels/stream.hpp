@@ -1,0 +1,473 @@
+// Store-bound and decode-size step kernels: short-K, split-K with its reduction, and the opt-in LDS-fused pair of small steps.
+// Part of the tn_linear library's single translation unit: included by tn_linear.hip inside its
+// anonymous namespace, after <hip/hip_runtime.h> and tn_plan.hpp.
+#pragma once
+
+// ---------------------------------------------------------------------------------------------
+// Short-K kernel (K <= 64): steps such as the first contraction of a chain read little and write
+// a lot, so they are bound by the store stream. A workgroup owns 128 rows and walks over all
+// columns, 128 at a time. The A fragments of its rows (the whole K) stay in registers for the whole
+// walk; the packed tensor's fragment blocks are loaded from memory straight into MFMA operand
+// registers (double-buffered across column iterations); each wave turns its 64x64 result into
+// row-contiguous 16-byte pieces through a private LDS patch and stores it. No workgroup barrier
+// is used anywhere, so the stores of one wave overlap the loads and MFMAs of the others.
+// Requires Kp == 64, aligned runs of 8 columns in the output (CMODE 1) and Cp % 128 == 0.
+// ---------------------------------------------------------------------------------------------
+template <int AMODE, int TMW, int DBUF, int MINB>
+__global__ void __launch_bounds__(256, MINB) step_shortk_kernel(StepArgs a) {
+    // TMW = 32-row tiles per wave (1 or 2): the workgroup covers 4 * TMW * 32 / 2 ... rows, see below
+    constexpr int LDP = 64 + 8;                          // padded row of the wave's LDS patch
+    constexpr int WROWS = TMW * 32;                      // rows per wave
+    __shared__ __attribute__((aligned(16))) bf16_t patch[4][WROWS * LDP];
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;             // 2 x 2 waves: rows wm, 64-column half wn
+    const uint32_t row0 = blockIdx.x * (2 * WROWS) + wm * WROWS;
+    bf16_t* sP = patch[wave];
+
+    // A fragments for the wave's rows and all 4 k-steps
+    bf16x8 af[TMW][4];
+#pragma unroll
+    for (int i = 0; i < TMW; ++i) {
+        uint32_t g = row0 + i * 32 + (lane & 31);
+        int64_t base = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            base = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 v;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
+            int k = ks * 16 + 8 * (lane >> 5);
+            if (base >= 0) {
+                if (AMODE == 0) {
+                    if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + base + k);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (k + q < a.K) v[q] = A[base + (a.acol ? a.acol[k + q] : k + q)];
+                }
+            }
+            af[i][ks] = v;
+        }
+    }
+    // output bases of the rows this lane stores per iteration (row p*8 + lane/8), in units of 8
+    // elements (every run of 8 columns is 16-byte aligned), so that they fit 32 bits
+    constexpr int NP = WROWS / 8;
+    uint32_t obase8[NP];
+    bool ovalid[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        uint32_t g = row0 + p * 8 + (lane >> 3);
+        ovalid[p] = g < a.total_rows;
+        obase8[p] = 0;
+        if (ovalid[p]) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            obase8[p] = uint32_t((int64_t(t) * a.c_tok_stride + a.crow[r]) >> 3);
+        }
+    }
+    const int ncol_iters = a.Cp >> 7;
+    const bf16_t* bp = B + lane * 8;                     // Kp == 64: 4 k-step blocks per column block
+    auto load_b = [&](int it, bf16x8 (&bf)[2][4]) {
+        int cb = it * 4 + wn * 2;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                bf[j][ks] = *reinterpret_cast<const bf16x8*>(bp + (int64_t(cb + j) * 4 + ks) * 512);
+    };
+    // column iterations are dealt round-robin over gridDim.y workgroups (1 when there are enough
+    // row tiles to fill the chip)
+    const int it_step = gridDim.y;
+    bf16x8 bcur[2][4], bnext[2][4];
+    if (DBUF && int(blockIdx.y) < ncol_iters) load_b(blockIdx.y, bcur);
+    for (int it = blockIdx.y; it < ncol_iters; it += it_step) {
+        if (DBUF) {
+            if (it + it_step < ncol_iters) load_b(it + it_step, bnext);
+        } else {
+            load_b(it, bcur);
+        }
+        floatx16 acc[TMW][2];
+#pragma unroll
+        for (int i = 0; i < TMW; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int i = 0; i < TMW; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bcur[j][ks], af[i][ks], acc[i][j], 0, 0, 0);
+        // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
+#pragma unroll
+        for (int i = 0; i < TMW; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
+                    *reinterpret_cast<bf16x4*>(sP + (i * 32 + (lane & 31)) * LDP + j * 32 + 8 * q + 4 * (lane >> 5)) = pk;
+                }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int c = it * 128 + wn * 64 + (lane & 7) * 8;
+        if (c < a.C) {
+            const uint32_t coff8 = uint32_t(a.ccol[c]) >> 3;
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                bf16x8 v = *reinterpret_cast<const bf16x8*>(sP + (p * 8 + (lane >> 3)) * LDP + (lane & 7) * 8);
+                if (ovalid[p]) *reinterpret_cast<bf16x8*>(Out + (int64_t(obase8[p] + coff8) << 3)) = v;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (DBUF) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bcur[j][ks] = bnext[j][ks];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Split-K kernel for launches whose output has too few tiles to fill the chip: decode (1-64
+// tokens) and small batches. Grid = (row tiles of TM*32 rows) x (32-column blocks) x (K splits).
+// The NW waves of a workgroup (4, 8 or 16: more waves keep more of the weight stream in flight)
+// take the 16-wide k-steps of the split round-robin; each wave loads
+// the packed tensor's 1 KB fragment blocks straight from memory into MFMA operand registers (no
+// LDS staging, fully coalesced: this is the stream that is HBM-bound at decode) and the matching
+// A fragments (a few rows) from global memory. The per-wave accumulators are summed through LDS
+// in a fixed order. With one split the result is stored through the scatter tables; otherwise it
+// goes to an fp32 partial buffer that step_split_reduce_kernel sums in split order, so results
+// stay bit-reproducible (no atomics). A single-pass variant in which the last workgroup to arrive
+// at a tile does the sum was measured 8x slower: a device-scope fence on this chip writes back the
+// L2 of the workgroup's XCD.
+// ---------------------------------------------------------------------------------------------
+template <int TM, int AMODE, int NW>
+__global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
+    __shared__ float red[NW][TM][16][64];
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t row0 = blockIdx.x * (TM * 32);
+    const int cb = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
+    const int nks = a.Kp >> 4;
+    const int ks_begin = split * ksteps_per_split;
+    const int ks_end = min(nks, ks_begin + ksteps_per_split);
+
+    int64_t a_base[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        uint32_t g = row0 + i * 32 + (lane & 31);
+        a_base[i] = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            a_base[i] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+        }
+    }
+    const bf16_t* bp = B + (int64_t(cb) * nks) * 512 + lane * 8;
+    floatx16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    // U k-steps per batch and two batches in registers: the next batch is requested before the current
+    // one is multiplied, so a wave always has loads in flight (a decode-size launch is a pure stream of
+    // the packed tensor; with one batch the stream would drain at every wait)
+    constexpr int U = 4;
+    auto load_batch = [&](int ks0, bf16x8 (&bf)[U], bf16x8 (&af)[U][TM]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int ks = ks0 + NW * u;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) bf[u][q] = bf16_t(0.f);
+            if (ks < ks_end) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(ks) * 512);
+            int k = ks * 16 + 8 * (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                bf16x8 v;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
+                if (ks < ks_end && a_base[i] >= 0) {
+                    if (AMODE == 0) {
+                        if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + a_base[i] + k);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            if (k + q < a.K) v[q] = A[a_base[i] + (a.acol ? a.acol[k + q] : k + q)];
+                    }
+                }
+                af[u][i] = v;
+            }
+        }
+    };
+    auto multiply = [&](const bf16x8 (&bf)[U], const bf16x8 (&af)[U][TM]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], af[u][i], acc[i], 0, 0, 0);
+    };
+    {
+        bf16x8 bf0[U], af0[U][TM], bf1[U], af1[U][TM];
+        constexpr int STEP = NW * U;
+        int ks0 = ks_begin + wave;
+        load_batch(ks0, bf0, af0);                       // batches past the end load nothing and multiply zeros
+        for (; ks0 < ks_end; ks0 += 2 * STEP) {
+            load_batch(ks0 + STEP, bf1, af1);
+            multiply(bf0, af0);
+            load_batch(ks0 + 2 * STEP, bf0, af0);
+            multiply(bf1, af1);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][i][v][lane] = acc[i][v];
+    __syncthreads();
+    // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
+    const uint32_t rows_pad = gridDim.x * (TM * 32);
+    const float* rw = &red[0][0][0][0];
+    for (int e = tid; e < TM * 1024; e += NW * 64) {
+        int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += rw[w * TM * 1024 + e];
+        uint32_t g = row0 + i * 32 + (l & 31);
+        int c = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+        if (g >= a.total_rows || c >= a.C) continue;
+        if (nsplit == 1) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
+        } else {
+            partial[(int64_t(split) * rows_pad + g) * a.Cp + c] = sum;
+        }
+    }
+}
+
+// Sums the partial results of the split-K kernel in split order and stores through the tables.
+__global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, const float* partial, int nsplit,
+                                                                uint32_t rows_pad) {
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    int64_t total = int64_t(a.total_rows) * a.C;
+    for (int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x; e < total; e += int64_t(gridDim.x) * 256) {
+        uint32_t g = uint32_t(e / a.C);
+        int c = int(e - int64_t(g) * a.C);
+        // 8 loads in flight at a time; the additions keep the split order
+        float sum = 0.f;
+        const float* src = partial + int64_t(g) * a.Cp + c;
+        const int64_t sstride = int64_t(rows_pad) * a.Cp;
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = s0 + q < nsplit ? src[int64_t(s0 + q) * sstride] : 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) sum += v[q];
+        }
+        uint32_t t = g / a.R;
+        uint32_t r = g - t * a.R;
+        Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fused pair of small steps (e.g. the two out-factor or the two in-factor products of a Tucker
+// layer): when one token's input of the first step and its intermediate fit in LDS, a workgroup
+// takes tokens one at a time, stages the token's [R1, K1] input in LDS, runs step 1 with MFMA into
+// an LDS copy of the intermediate (written through step 1's scatter tables, i.e. already in the
+// layout step 2 reads), runs step 2 from LDS and stores its result through step 2's tables. Each
+// wave owns up to two 32-column tiles of either packed tensor and keeps their fragment blocks in
+// registers for all the tokens of the workgroup (K <= 96, C <= 256); the next token's input is
+// prefetched into registers while the current one is computed. The intermediate never touches HBM and one launch
+// replaces two. Needs K1 % 16 == 0 and K2 % 16 == 0 (no padded k-steps are ever read).
+// CM2 = 1: step 2's columns come in aligned runs of 8 -> 16-byte stores via a per-wave LDS patch;
+// CM2 = 0: scalar stores.
+// ---------------------------------------------------------------------------------------------
+struct Fused2Args {
+    StepArgs s1, s2;
+    int32_t tokens;
+    int32_t in_elems;     // LDS elements reserved for the staged input: roundup(R1, 32) * (K1 + 8)
+    int32_t mid_elems;    // LDS elements reserved for the intermediate: roundup(R2, 32) * K2
+};
+
+template <int CM2>
+__global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    const StepArgs& a1 = f.s1;
+    const StepArgs& a2 = f.s2;
+    const int R1 = int(a1.R), K1 = a1.K, C1 = a1.C, R2 = int(a2.R), K2 = a2.K, C2 = a2.C;
+    const int LD1 = K1 + 8;
+    bf16_t* sIn = reinterpret_cast<bf16_t*>(dyn_smem);
+    bf16_t* sMid = sIn + f.in_elems;
+    bf16_t* sPatch = sMid + f.mid_elems;                       // 4 waves x 32 x 40
+    int32_t* sTab = reinterpret_cast<int32_t*>(sPatch + 4 * 32 * 40);
+    int32_t* t_crow1 = sTab;
+    int32_t* t_ccol1 = t_crow1 + R1;
+    int32_t* t_crow2 = t_ccol1 + C1;
+    int32_t* t_ccol2 = t_crow2 + R2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < R1; i += 256) t_crow1[i] = a1.crow[i];
+    for (int i = tid; i < C1; i += 256) t_ccol1[i] = a1.ccol[i];
+    for (int i = tid; i < R2; i += 256) t_crow2[i] = a2.crow[i];
+    for (int i = tid; i < C2; i += 256) t_ccol2[i] = a2.ccol[i];
+    // rows past R1 / R2 of the last row tile are read by the MFMAs (their results are dropped):
+    // give them defined contents once
+    for (int i = tid; i < f.in_elems; i += 256) sIn[i] = bf16_t(0.f);
+    for (int i = tid; i < f.mid_elems; i += 256) sMid[i] = bf16_t(0.f);
+    __syncthreads();
+
+    const bf16_t* A = static_cast<const bf16_t*>(a1.A);
+    const bf16_t* B1 = static_cast<const bf16_t*>(a1.B);
+    const bf16_t* B2 = static_cast<const bf16_t*>(a2.B);
+    bf16_t* Out = static_cast<bf16_t*>(a2.Out);
+    const int nks1 = K1 >> 4, nks2 = K2 >> 4;                  // real k-steps (<= 6)
+    const int bks1 = a1.Kp >> 4, bks2 = a2.Kp >> 4;            // k-steps per column block in the packed tensors
+    const int nrt1 = (R1 + 31) >> 5, nct1 = (C1 + 31) >> 5;
+    const int nrt2 = (R2 + 31) >> 5, nct2 = (C2 + 31) >> 5;     // nct <= 8: column tiles j = wave, wave + 4
+    const int chunks_per_row = K1 >> 3;
+    bf16_t* myPatch = sPatch + wave * 32 * 40;
+
+    // the wave's column tiles of both packed tensors stay in registers for all of its tokens
+    bf16x8 bw1[2][6], bw2[2][6];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int ks = 0; ks < 6; ++ks) {
+            bf16x8 z;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
+            int j = wave + 4 * jj;
+            bw1[jj][ks] = (j < nct1 && ks < nks1)
+                              ? *reinterpret_cast<const bf16x8*>(B1 + (int64_t(j) * bks1 + ks) * 512 + lane * 8) : z;
+            bw2[jj][ks] = (j < nct2 && ks < nks2)
+                              ? *reinterpret_cast<const bf16x8*>(B2 + (int64_t(j) * bks2 + ks) * 512 + lane * 8) : z;
+        }
+
+    // the next token's input is fetched into registers while the current token is computed
+    // (at most 6 chunks of 16 bytes per thread: R1 * K1 <= 12288)
+    const int n_chunks = R1 * chunks_per_row;
+    int my_off[6];                                             // LDS element offset of each of my chunks
+#pragma unroll
+    for (int q = 0; q < 6; ++q) {
+        int e = tid + 256 * q;
+        int r = e / chunks_per_row;
+        my_off[q] = e < n_chunks ? r * LD1 + (e - r * chunks_per_row) * 8 : -1;
+    }
+    bf16x8 pre[6];
+    auto fetch_in = [&](int t) {
+        const bf16_t* in = A + int64_t(t) * a1.a_tok_stride + tid * 8;
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+            if (my_off[q] >= 0) pre[q] = *reinterpret_cast<const bf16x8*>(in + 2048 * q);
+    };
+    if (int(blockIdx.x) < f.tokens) fetch_in(blockIdx.x);
+    for (int t = blockIdx.x; t < f.tokens; t += gridDim.x) {
+        // ---- stage the token's input
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+            if (my_off[q] >= 0) *reinterpret_cast<bf16x8*>(sIn + my_off[q]) = pre[q];
+        __syncthreads();
+        if (t + int(gridDim.x) < f.tokens) fetch_in(t + gridDim.x);
+        // ---- step 1
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = wave + 4 * jj;
+            if (j >= nct1) continue;
+            for (int i = 0; i < nrt1; ++i) {
+                floatx16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                const bf16_t* ap = sIn + (i * 32 + (lane & 31)) * LD1 + 8 * (lane >> 5);
+                bf16x8 af[6];                 // all fragment reads first, then the MFMA chain
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks1) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw1[jj][ks], af[ks], acc, 0, 0, 0);
+                // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
+                int r = i * 32 + (lane & 31);
+                if (r < R1) {
+                    int rbase = t_crow1[r];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                        if (c < C1) sMid[rbase + t_ccol1[c]] = bf16_t(acc[v]);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // ---- step 2 from the LDS intermediate
+        bf16_t* out_t = Out + int64_t(t) * a2.c_tok_stride;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = wave + 4 * jj;
+            if (j >= nct2) continue;
+            for (int i = 0; i < nrt2; ++i) {
+                floatx16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                const bf16_t* ap = sMid + (i * 32 + (lane & 31)) * K2 + 8 * (lane >> 5);
+                bf16x8 af[6];
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks2) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < nks2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw2[jj][ks], af[ks], acc, 0, 0, 0);
+                if (CM2 == 1) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        bf16x4 pk;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[4 * q + u]);
+                        *reinterpret_cast<bf16x4*>(myPatch + (lane & 31) * 40 + 8 * q + 4 * (lane >> 5)) = pk;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    int c = j * 32 + (lane & 3) * 8;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        int rr = h * 16 + (lane >> 2);
+                        int r = i * 32 + rr;
+                        bf16x8 v = *reinterpret_cast<const bf16x8*>(myPatch + rr * 40 + (lane & 3) * 8);
+                        if (r < R2 && c < C2) *reinterpret_cast<bf16x8*>(out_t + t_crow2[r] + t_ccol2[c]) = v;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                } else {
+                    int r = i * 32 + (lane & 31);
+                    if (r < R2) {
+                        int rbase = t_crow2[r];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                            if (c < C2) out_t[rbase + t_ccol2[c]] = bf16_t(acc[v]);
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();   // sIn and sMid are rewritten for the next token
+    }
+}
+

@@ -24,1720 +24,11 @@
 
 namespace {
 
-// ---------------------------------------------------------------------------------------------
-// device-side argument blocks
-// ---------------------------------------------------------------------------------------------
-struct StepArgs {
-    const void* A;
-    const void* B;
-    void* Out;
-    const int32_t* arow;   // gather tables for A (null when A is plain)
-    const int32_t* acol;
-    const int32_t* crow;   // scatter tables for Out
-    const int32_t* ccol;
-    int64_t a_tok_stride;
-    int64_t c_tok_stride;
-    uint32_t total_rows;   // tokens * R
-    uint32_t R;
-    int32_t K, Kp, C, Cp;
-};
-
-struct PackArgs {
-    const void* src;
-    void* dst;
-    int32_t K, Kp, C, Cp;
-    int32_t nk, nc;
-    int64_t kext[tn::kMaxGatherDims], kstr[tn::kMaxGatherDims];
-    int64_t cext[tn::kMaxGatherDims], cstr[tn::kMaxGatherDims];
-    int64_t trace_extent, trace_stride;
-};
-
-typedef __bf16 bf16_t;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-// Packed parameter tensors are stored "fragment-major": the [Cp][Kp] matrix is cut into blocks of
-// 32 columns x 16 k; a block is 64 chunks of 8 consecutive k (16 bytes in bf16), chunk l holding
-// column l%32 and k offset 8*(l/32) - exactly the operand one lane of v_mfma_f32_32x32x16_bf16
-// wants. A wave that reads a block with one 16-byte load per lane therefore fetches 1 KB of
-// contiguous memory straight into MFMA operand registers (decode path), and the tiled kernels
-// read whole 1 KB blocks as well. Element (c, k) lives at:
-__host__ __device__ __forceinline__ int64_t bfrag_offset(int c, int k, int nks /* Kp / 16 */) {
-    return (int64_t(c >> 5) * nks + (k >> 4)) * 512 + ((c & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7);
-}
-
-__device__ __forceinline__ float to_float(float v) { return v; }
-__device__ __forceinline__ float to_float(bf16_t v) { return float(v); }
-template <typename T> __device__ __forceinline__ T from_float(float v);
-template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
-template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) { return bf16_t(v); }
-
-// ---------------------------------------------------------------------------------------------
-// create-time repack: Bp(c, k) = sum_a src[off_c(c) + off_k(k) + a*trace_stride], zero padded to
-// [Cp][Kp] and stored fragment-major
-// ---------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void __launch_bounds__(256) pack_kernel(PackArgs p) {
-    int64_t total = int64_t(p.Cp) * p.Kp;
-    for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
-         i += int64_t(gridDim.x) * blockDim.x) {
-        int32_t c = int32_t(i / p.Kp);
-        int32_t k = int32_t(i - int64_t(c) * p.Kp);
-        float v = 0.f;
-        if (c < p.C && k < p.K) {
-            int64_t off = 0;
-            int32_t rem = k;
-            for (int j = p.nk - 1; j >= 0; --j) {
-                int32_t e = int32_t(p.kext[j]);
-                int32_t q = rem / e;
-                off += int64_t(rem - q * e) * p.kstr[j];
-                rem = q;
-            }
-            rem = c;
-            for (int j = p.nc - 1; j >= 0; --j) {
-                int32_t e = int32_t(p.cext[j]);
-                int32_t q = rem / e;
-                off += int64_t(rem - q * e) * p.cstr[j];
-                rem = q;
-            }
-            const T* s = static_cast<const T*>(p.src);
-            if (p.trace_extent == 1) {
-                static_cast<T*>(p.dst)[bfrag_offset(c, k, p.Kp >> 4)] = s[off];
-                continue;
-            }
-            for (int64_t a = 0; a < p.trace_extent; ++a) v += to_float(s[off + a * p.trace_stride]);
-        }
-        static_cast<T*>(p.dst)[bfrag_offset(c, k, p.Kp >> 4)] = from_float<T>(v);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// plain FMA step kernel: any dtype, any addressing. 64x64 tile, 256 threads, 4x4 per thread.
-// ---------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void __launch_bounds__(256) step_scalar_kernel(StepArgs a) {
-    constexpr int BM = 64, BN = 64, BK = 16;
-    __shared__ float As[BK][BM + 4];
-    __shared__ float Bs[BK][BN + 4];
-    const T* A = static_cast<const T*>(a.A);
-    const T* B = static_cast<const T*>(a.B);
-    T* Out = static_cast<T*>(a.Out);
-    const int tid = threadIdx.x;
-    const uint32_t row0 = blockIdx.x * BM;
-    const int col0 = blockIdx.y * BN;
-    const int tx = tid & 15, ty = tid >> 4;
-    float acc[4][4] = {};
-
-    // each thread loads 4 elements of A and 4 of B per K chunk: element e = tid + 256*j
-    for (int k0 = 0; k0 < a.K; k0 += BK) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int e = tid + 256 * j;
-            int kk = e & (BK - 1);
-            int rr = e >> 4;
-            uint32_t g = row0 + rr;
-            int k = k0 + kk;
-            float v = 0.f;
-            if (g < a.total_rows && k < a.K) {
-                uint32_t t = g / a.R;
-                uint32_t r = g - t * a.R;
-                int64_t off = int64_t(t) * a.a_tok_stride +
-                              (a.arow ? int64_t(a.arow[r]) + a.acol[k] : int64_t(r) * a.K + k);
-                v = to_float(A[off]);
-            }
-            As[kk][rr] = v;
-            int c = col0 + rr;
-            float w = 0.f;
-            if (c < a.Cp && k < a.Kp) w = to_float(B[bfrag_offset(c, k, a.Kp >> 4)]);
-            Bs[kk][rr] = w;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < BK; ++kk) {
-            float av[4], bv[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t g = row0 + ty * 4 + i;
-        if (g >= a.total_rows) continue;
-        uint32_t t = g / a.R;
-        uint32_t r = g - t * a.R;
-        int64_t base = int64_t(t) * a.c_tok_stride + a.crow[r];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int c = col0 + tx * 4 + j;
-            if (c < a.C) Out[base + a.ccol[c]] = from_float<T>(acc[i][j]);
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// bf16 MFMA step kernel. 256 threads = 4 waves arranged WM x WN; each wave owns TM x TN tiles of
-// v_mfma_f32_32x32x16_bf16. A and B tiles are staged through LDS with K contiguous so that one
-// ds_read_b128 feeds one MFMA operand (lane l: row l%32, k = 8*(l/32) .. +7). The fp32
-// accumulators are rounded to bf16, transposed through LDS and scattered with 16-byte stores
-// along whichever direction (columns or rows) is contiguous in the output layout.
-//   AMODE 0: A rows are plain and K % 8 == 0 -> 16-byte global loads
-//   AMODE 1: element-wise gather (tables, or K not a multiple of 8)
-//   CMODE 0: scalar stores; 1: 8 contiguous columns per store; 2: 8 contiguous rows per store
-// ---------------------------------------------------------------------------------------------
-template <int WM, int WN, int TM, int TN, int AMODE>
-__global__ void __launch_bounds__(256) step_mfma_kernel(StepArgs a, int cmode) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
-    constexpr int LDK = BK + 8;                       // padded LDS row (elements)
-    constexpr int A_ELEMS = BM * LDK, B_ELEMS = BN * LDK;
-    constexpr int LDC = BN + 8;
-    constexpr int SMEM_ELEMS = (A_ELEMS + B_ELEMS) > (BM * LDC) ? (A_ELEMS + B_ELEMS) : (BM * LDC);
-    __shared__ __attribute__((aligned(16))) bf16_t smem[SMEM_ELEMS];
-    bf16_t* sA = smem;
-    bf16_t* sB = smem + A_ELEMS;
-
-    const bf16_t* A = static_cast<const bf16_t*>(a.A);
-    const bf16_t* B = static_cast<const bf16_t*>(a.B);
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const uint32_t row0 = blockIdx.x * BM;
-    const int col0 = blockIdx.y * BN;
-
-    // global -> LDS assignment: a tile row has BK/8 = 8 chunks of 16 bytes
-    constexpr int A_CHUNKS = BM * 8 / 256;            // chunks per thread
-    constexpr int B_CHUNKS = BN * 8 / 256;
-    int64_t a_base[A_CHUNKS];                         // element offset of the row start, -1 if out of range
-#pragma unroll
-    for (int j = 0; j < A_CHUNKS; ++j) {
-        int e = tid + 256 * j;
-        uint32_t g = row0 + (e >> 3);
-        if (g < a.total_rows) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            a_base[j] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
-        } else {
-            a_base[j] = -1;
-        }
-    }
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    for (int k0 = 0; k0 < a.Kp; k0 += BK) {
-        // ---- stage A
-#pragma unroll
-        for (int j = 0; j < A_CHUNKS; ++j) {
-            int e = tid + 256 * j;
-            int rr = e >> 3, kc = (e & 7) * 8;
-            bf16x8 v;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
-            int k = k0 + kc;
-            if (a_base[j] >= 0) {
-                if (AMODE == 0) {
-                    if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + a_base[j] + k);
-                } else {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        if (k + q < a.K) v[q] = A[a_base[j] + (a.acol ? a.acol[k + q] : k + q)];
-                }
-            }
-            *reinterpret_cast<bf16x8*>(sA + rr * LDK + kc) = v;
-        }
-        // ---- stage B (always in range: Bp is padded to [Cp][Kp])
-#pragma unroll
-        for (int j = 0; j < B_CHUNKS; ++j) {
-            int e = tid + 256 * j;
-            int cc = e >> 3, kc = (e & 7) * 8;
-            bf16x8 v = *reinterpret_cast<const bf16x8*>(B + bfrag_offset(col0 + cc, k0 + kc, a.Kp >> 4));
-            *reinterpret_cast<bf16x8*>(sB + cc * LDK + kc) = v;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int ks = 0; ks < BK; ks += 16) {
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(sA + ((wm * TM + i) * 32 + (lane & 31)) * LDK + ks +
-                                                         8 * (lane >> 5));
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(sB + ((wn * TN + j) * 32 + (lane & 31)) * LDK + ks +
-                                                          8 * (lane >> 5));
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-
-    // ---- epilogue: accumulators -> bf16 tile in LDS (row-major [BM][LDC])
-    // D layout of the 32x32 MFMA: lane l, register v: col = l%32, row = 8*(v/4) + 4*(l/32) + v%4
-    bf16_t* sC = smem;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int rr = (wm * TM + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                int cc = (wn * TN + j) * 32 + (lane & 31);
-                sC[rr * LDC + cc] = bf16_t(acc[i][j][v]);
-            }
-    __syncthreads();
-
-    if (cmode == 1) {
-        // thread -> (row, group of 8 columns), columns fastest
-        constexpr int GROUPS = BM * BN / 8;
-        for (int e = tid; e < GROUPS; e += 256) {
-            int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
-            uint32_t g = row0 + rr;
-            int c = col0 + cg;
-            if (g >= a.total_rows || c >= a.C) continue;
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            int64_t off = int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c];
-            *reinterpret_cast<bf16x8*>(Out + off) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
-        }
-    } else if (cmode == 2) {
-        // thread -> (group of 8 rows, column), rows fastest
-        constexpr int GROUPS = BM * BN / 8;
-        for (int e = tid; e < GROUPS; e += 256) {
-            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
-            uint32_t g = row0 + rg;
-            int c = col0 + cc;
-            if (g >= a.total_rows || c >= a.C) continue;
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            int64_t off = int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c];
-            bf16x8 v;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = sC[(rg + q) * LDC + cc];
-            *reinterpret_cast<bf16x8*>(Out + off) = v;
-        }
-    } else {
-        for (int e = tid; e < BM * BN; e += 256) {
-            int rr = e / BN, cc = e % BN;
-            uint32_t g = row0 + rr;
-            int c = col0 + cc;
-            if (g >= a.total_rows || c >= a.C) continue;
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = sC[rr * LDC + cc];
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Pipelined bf16 MFMA step kernel for the FLOP-heavy steps (wide C, plain A with K % 8 == 0 or
-// gathered A). Differences from the kernel above:
-//   * the next K tile is fetched from global memory into registers while the current one is
-//     multiplied (and, with STAGES == 2, written to the other LDS buffer: one barrier per tile);
-//   * the MFMA operands are swapped (packed tensor first), so a lane ends up with 4 consecutive
-//     columns of one row and the epilogue writes 8-byte pieces to LDS;
-//   * tiles are numbered so that the column tiles of one row tile run back to back on the same
-//     XCD (workgroup i goes to XCD i % 8): the second read of an A tile hits that XCD's L2;
-//   * per-row output offsets are computed once per tile and kept in LDS;
-//   * TRANS = 1 serves outputs whose contiguous direction is along rows (CMODE 2): the operands
-//     are not swapped, a lane holds 4 consecutive rows of one column, and the tile is staged in LDS
-//     column-major so that the stores again move 16 contiguous bytes per lane.
-// ---------------------------------------------------------------------------------------------
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-
-// Workgroup -> output tile, XCD-aware. Workgroup i runs on XCD i % 8 (round-robin dispatch) and an
-// XCD runs about 32 of these workgroups at a time, all reading through its own 4 MB L2. XCD x owns the
-// row tiles x, x+8, x+16, ...; its workgroups walk them in bands of 4 row tiles, row fastest, so
-// that the 32 tiles in flight are 4 row tiles x 8 column tiles: 4 + 8 operand panels move through the
-// L2 at a time instead of 1 + 32 (a band of one row tile per XCD streams the whole packed tensor
-// from the fabric once per row tile, which bounded the large-K launches).
-__device__ __forceinline__ void tile_of_workgroup(int id, int nrow_tiles, int ncol_tiles, int* row_tile, int* col_tile) {
-    constexpr int BAND = 4;
-    const int xcd = id & 7, slot = id >> 3;
-    const int rows_per_xcd = (nrow_tiles + 7) >> 3;                  // the grid is padded to whole XCD rows
-    const int band = slot / (BAND * ncol_tiles);
-    const int in_band = slot - band * (BAND * ncol_tiles);
-    const int band_rows = min(BAND, rows_per_xcd - band * BAND);
-    const int col = in_band / band_rows;
-    const int r = in_band - col * band_rows;
-    *row_tile = (band * BAND + r) * 8 + xcd;
-    *col_tile = col;
-}
-
-
-template <int WM, int WN, int TM, int TN, int AMODE, int STAGES, int MINB, int TRANS>
-__global__ void __launch_bounds__(WM * WN * 64, MINB)
-step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
-    constexpr int LDK = BK + 8;
-    constexpr int A_ELEMS = BM * LDK, B_ELEMS = BN * LDK, STAGE_ELEMS = A_ELEMS + B_ELEMS;
-    constexpr int LDC = BN + 8;
-    constexpr int NT = WM * WN * 64;                 // threads per workgroup
-    constexpr int RPP = NT / 8;                       // tile rows covered by one pass of 16-byte loads
-    constexpr int A_CHUNKS = BM / RPP, B_CHUNKS = BN / RPP;
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-    bf16_t* smem = reinterpret_cast<bf16_t*>(dyn_smem);
-
-    int row_tile, col_tile;
-    tile_of_workgroup(blockIdx.x, nrow_tiles, ncol_tiles, &row_tile, &col_tile);
-    if (row_tile >= nrow_tiles) return;
-    const uint32_t row0 = uint32_t(row_tile) * BM;
-    const int col0 = col_tile * BN;
-
-    const bf16_t* A = static_cast<const bf16_t*>(a.A);
-    const bf16_t* B = static_cast<const bf16_t*>(a.B);
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int lrow = tid >> 3, lkc = (tid & 7) * 8;      // this thread's row (mod 32) and k offset in a tile
-
-    // A addressing: AMODE 0 -> one pointer, rows 32*j apart; AMODE 1 -> per-row element offsets
-    const bf16_t* a_ptr = A + int64_t(row0 + lrow) * a.K + lkc;
-    int64_t a_base[AMODE == 1 ? A_CHUNKS : 1];
-    if (AMODE == 1) {
-#pragma unroll
-        for (int j = 0; j < A_CHUNKS; ++j) {
-            uint32_t g = row0 + lrow + RPP * j;
-            a_base[j] = -1;
-            if (g < a.total_rows) {
-                uint32_t t = g / a.R;
-                uint32_t r = g - t * a.R;
-                a_base[j] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
-            }
-        }
-    }
-    // B: chunk e = tid + NT*j of a K tile is lane e%64 of block e/64; block b = (column block b/4,
-    // k-step b%4): every wave reads whole 1 KB blocks
-    const int nks = a.Kp >> 4;
-    const bf16_t* b_ptr = B + (int64_t(col0 >> 5) * nks) * 512 + (tid & 63) * 8;
-
-    bf16x8 ra[A_CHUNKS], rb[B_CHUNKS];
-    auto load_tile = [&](int k0) {
-#pragma unroll
-        for (int j = 0; j < A_CHUNKS; ++j) {
-            bf16x8 v;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
-            int k = k0 + lkc;
-            if (AMODE == 0) {
-                if (row0 + lrow + RPP * j < a.total_rows && k < a.K)
-                    v = *reinterpret_cast<const bf16x8*>(a_ptr + int64_t(RPP * j) * a.K + k0);
-            } else if (a_base[j] >= 0) {
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (k + q < a.K) v[q] = A[a_base[j] + (a.acol ? a.acol[k + q] : k + q)];
-            }
-            ra[j] = v;
-        }
-#pragma unroll
-        for (int j = 0; j < B_CHUNKS; ++j)
-        {
-            int blk = (tid >> 6) + (NT / 64) * j;
-            rb[j] = *reinterpret_cast<const bf16x8*>(b_ptr + (int64_t(blk >> 2) * nks + (k0 >> 4) + (blk & 3)) * 512);
-        }
-    };
-    auto store_tile = [&](int stage) {
-        bf16_t* sA = smem + stage * STAGE_ELEMS;
-        bf16_t* sB = sA + A_ELEMS;
-#pragma unroll
-        for (int j = 0; j < A_CHUNKS; ++j)
-            *reinterpret_cast<bf16x8*>(sA + (lrow + RPP * j) * LDK + lkc) = ra[j];
-#pragma unroll
-        for (int j = 0; j < B_CHUNKS; ++j) {
-            int blk = (tid >> 6) + (NT / 64) * j;
-            int col = (blk >> 2) * 32 + (lane & 31), kc = (blk & 3) * 16 + 8 * (lane >> 5);
-            *reinterpret_cast<bf16x8*>(sB + col * LDK + kc) = rb[j];
-        }
-    };
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int nk = a.Kp / BK;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = (STAGES == 2) ? (kt & 1) : 0;
-        if (kt + 1 < nk) load_tile((kt + 1) * BK);
-        const bf16_t* sA = smem + cur * STAGE_ELEMS + ((wm * TM) * 32 + (lane & 31)) * LDK + 8 * (lane >> 5);
-        const bf16_t* sB = smem + cur * STAGE_ELEMS + A_ELEMS + ((wn * TN) * 32 + (lane & 31)) * LDK + 8 * (lane >> 5);
-#pragma unroll
-        for (int ks = 0; ks < BK; ks += 16) {
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * LDK + ks);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * LDK + ks);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = TRANS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0)
-                                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-        }
-        if (STAGES == 1) __syncthreads();
-        if (kt + 1 < nk) store_tile((STAGES == 2) ? (cur ^ 1) : 0);
-        __syncthreads();
-    }
-
-    // ---- epilogue. Operands swapped (TRANS = 0): lane l, register v of a tile holds
-    //      row = l%32, col = 8*(v/4) + 4*(l/32) + v%4; staged row-major [BM][LDC].
-    //      Not swapped (TRANS = 1): col = l%32, row = 8*(v/4) + 4*(l/32) + v%4; staged
-    //      column-major [BN][LDR].
-    constexpr int LDR = BM + 8;
-    constexpr size_t C_ELEMS = size_t(BM) * LDC > size_t(BN) * LDR ? size_t(BM) * LDC : size_t(BN) * LDR;
-    bf16_t* sC = smem;
-    int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + C_ELEMS * sizeof(bf16_t));
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                bf16x4 pk;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
-                if (TRANS) {
-                    int cc = (wn * TN + j) * 32 + (lane & 31);
-                    int rr = (wm * TM + i) * 32 + 8 * q + 4 * (lane >> 5);
-                    *reinterpret_cast<bf16x4*>(sC + cc * LDR + rr) = pk;
-                } else {
-                    int rr = (wm * TM + i) * 32 + (lane & 31);
-                    int cc = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
-                    *reinterpret_cast<bf16x4*>(sC + rr * LDC + cc) = pk;
-                }
-            }
-    for (int rr = tid; rr < BM; rr += NT) {
-        uint32_t g = row0 + rr;
-        int64_t base = -1;
-        if (g < a.total_rows) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            base = int64_t(t) * a.c_tok_stride + a.crow[r];
-        }
-        sBase[rr] = base;
-    }
-    __syncthreads();
-
-    constexpr int GROUPS = BM * BN / 8;
-    if (TRANS) {
-        // rows come in aligned contiguous runs of 8: thread -> (group of 8 rows, column), rows fastest
-#pragma unroll 4
-        for (int e = tid; e < GROUPS; e += NT) {
-            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
-            int c = col0 + cc;
-            int64_t base = sBase[rg];
-            if (base < 0 || c >= a.C) continue;
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + cc * LDR + rg);
-        }
-    } else if (cmode == 1) {
-#pragma unroll 4
-        for (int e = tid; e < GROUPS; e += NT) {
-            int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
-            int c = col0 + cg;
-            int64_t base = sBase[rr];
-            if (base < 0 || c >= a.C) continue;
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
-        }
-    } else {
-        for (int e = tid; e < BM * BN; e += NT) {
-            int rr = e / BN, cc = e % BN;
-            int c = col0 + cc;
-            int64_t base = sBase[rr];
-            if (base < 0 || c >= a.C) continue;
-            Out[base + a.ccol[c]] = sC[rr * LDC + cc];
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Direct-to-LDS bf16 MFMA step kernel (the fastest tiled kernel; needs a plain A with K % 32 == 0).
-//   * K tiles of 32 travel from global memory straight into LDS with global_load_lds_dwordx4
-//     (16 bytes per lane, no staging registers, no LDS write instructions) into a ring of NS
-//     stages; a wave waits on its own loads with s_waitcnt vmcnt(n) and a workgroup barrier makes
-//     the other waves' loads visible;
-//   * tile kt+1 is known to have landed before tile kt is multiplied, and the MFMA operand
-//     fragments are double-buffered in registers, so the LDS reads of the next k-step are in
-//     flight while the current MFMAs run, across the barrier as well;
-//   * an LDS tile row is 64 bytes (4 chunks of 16 B); chunk c of row r sits at chunk position
-//     c ^ ((r >> 2) & 3), which makes the fragment reads of 16 consecutive rows conflict-free. The
-//     swizzle costs nothing: each lane simply fetches the global chunk that belongs at its LDS slot.
-// Tile numbering (XCD-aware), epilogue (CMODE 1, TRANS, scalar) and tables are those of the kernel
-// above. Rows past the end are clamped to the last row when loading and masked when storing.
-// ---------------------------------------------------------------------------------------------
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
-    constexpr int imm = (N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14);
-    __builtin_amdgcn_s_waitcnt(imm);
-}
-
-template <int WM, int WN, int TM, int TN, int NS, int MINB, int TRANS>
-__global__ void __launch_bounds__(WM * WN * 64, MINB)
-step_mfma_dlds_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
-    constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 32;
-    constexpr int ROWB = BK * 2;                       // bytes per LDS tile row
-    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
-    constexpr int A_PER_WAVE = BM / 16 / NWAVE, B_PER_WAVE = BN / 16 / NWAVE;   // 1 KB loads per wave and stage
-    constexpr int L = A_PER_WAVE + B_PER_WAVE;
-    constexpr int LDC = BN + 8, LDR = BM + 8;
-    static_assert((BM / 16) % NWAVE == 0 && (BN / 16) % NWAVE == 0, "16-row blocks per wave");
-    static_assert(NS >= 3 && NS <= 4 && 2 * L <= 63, "ring depth / vmcnt range");
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-
-    int row_tile, col_tile;
-    tile_of_workgroup(blockIdx.x, nrow_tiles, ncol_tiles, &row_tile, &col_tile);
-    if (row_tile >= nrow_tiles) return;
-    const uint32_t row0 = uint32_t(row_tile) * BM;
-    const int col0 = col_tile * BN;
-
-    const bf16_t* A = static_cast<const bf16_t*>(a.A);
-    const bf16_t* B = static_cast<const bf16_t*>(a.B);
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int nks = a.Kp >> 4;
-
-    // per-lane sources: lane l of a 1 KB load fills LDS row l/4, chunk position l%4 of its block
-    const int lr = lane >> 2, lpc = lane & 3;
-    const bf16_t* a_src[A_PER_WAVE];
-    const bf16_t* b_src[B_PER_WAVE];
-#pragma unroll
-    for (int j = 0; j < A_PER_WAVE; ++j) {
-        int r = (j * NWAVE + wave) * 16 + lr;
-        int c = lpc ^ ((r >> 2) & 3);
-        uint32_t g = row0 + r;
-        if (g >= a.total_rows) g = a.total_rows - 1;
-        a_src[j] = A + int64_t(g) * a.K + c * 8;
-    }
-#pragma unroll
-    for (int j = 0; j < B_PER_WAVE; ++j) {
-        int r = (j * NWAVE + wave) * 16 + lr;              // column within the tile
-        int c = lpc ^ ((r >> 2) & 3);                       // logical chunk: k = kt*32 + c*8
-        int col = col0 + r;
-        // fragment-major: block (col/32, k/16), chunk (col%32) + 32*((k/8)%2)
-        b_src[j] = B + (int64_t(col >> 5) * nks + (c >> 1)) * 512 + ((col & 31) + 32 * (c & 1)) * 8;
-    }
-    auto issue = [&](int kt, int stage) {
-        unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < A_PER_WAVE; ++j)
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)(a_src[j] + kt * BK),
-                (void __attribute__((address_space(3)))*)(sbase + (j * NWAVE + wave) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < B_PER_WAVE; ++j)
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)(b_src[j] + int64_t(kt) * 2 * 512),
-                (void __attribute__((address_space(3)))*)(sbase + A_BYTES + (j * NWAVE + wave) * 1024), 16, 0, 0);
-    };
-    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform, at most NS - 2
-        if (n <= 0) wait_vmcnt<0>();
-        else if (n == 1) wait_vmcnt<L>();
-        else if (n == 2 || NS <= 4) wait_vmcnt<2 * L>();
-        else wait_vmcnt<3 * L>();
-    };
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    // fragment read offsets: lane reads row lane%32, logical chunk ks*2 + lane/32
-    int a_off[TM][2], b_off[TN][2];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            int r = (wm * TM + i) * 32 + (lane & 31);
-            a_off[i][ks] = r * ROWB + (((ks * 2 + (lane >> 5)) ^ ((r >> 2) & 3)) * 16);
-        }
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            int r = (wn * TN + j) * 32 + (lane & 31);
-            b_off[j][ks] = A_BYTES + r * ROWB + (((ks * 2 + (lane >> 5)) ^ ((r >> 2) & 3)) * 16);
-        }
-
-    const int nk = a.Kp / BK;                            // K % 32 == 0, so tiles past K are all padding
-    const int nk_real = a.K / BK;                        // only these hold data; B is zero beyond
-    int issued = 0;
-    for (; issued < NS - 1 && issued < nk_real; ++issued) issue(issued, issued);
-    wait_outstanding_tiles(min(issued - 1, NS - 2));     // tile 0 has landed
-    __syncthreads();
-    bf16x8 af[2][TM], bfr[2][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(dyn_smem + a_off[i][0]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(dyn_smem + b_off[j][0]);
-    (void)nk;
-
-    for (int kt = 0; kt < nk_real; ++kt) {
-        if (kt + 1 < nk_real) wait_outstanding_tiles(issued - (kt + 2));   // tile kt+1 has landed
-        __syncthreads();       // everyone is done with tile kt-1: its stage may be refilled
-        if (issued < nk_real) {
-            issue(issued, issued % NS);
-            ++issued;
-        }
-        const unsigned char* scur = dyn_smem + (kt % NS) * STAGE_BYTES;
-        const unsigned char* snxt = dyn_smem + ((kt + 1) % NS) * STAGE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const int cb = ks & 1, nb = cb ^ 1;
-            if (ks == 0) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) af[nb][i] = *reinterpret_cast<const bf16x8*>(scur + a_off[i][1]);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) bfr[nb][j] = *reinterpret_cast<const bf16x8*>(scur + b_off[j][1]);
-            } else if (kt + 1 < nk_real) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) af[nb][i] = *reinterpret_cast<const bf16x8*>(snxt + a_off[i][0]);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) bfr[nb][j] = *reinterpret_cast<const bf16x8*>(snxt + b_off[j][0]);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = TRANS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0)
-                                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][j], af[cb][i], acc[i][j], 0, 0, 0);
-        }
-    }
-    __syncthreads();
-
-    // ---- epilogue (see step_mfma_pipe_kernel)
-    constexpr size_t C_ELEMS = size_t(BM) * LDC > size_t(BN) * LDR ? size_t(BM) * LDC : size_t(BN) * LDR;
-    bf16_t* sC = reinterpret_cast<bf16_t*>(dyn_smem);
-    int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + C_ELEMS * sizeof(bf16_t));
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                bf16x4 pk;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
-                if (TRANS) {
-                    int cc = (wn * TN + j) * 32 + (lane & 31);
-                    int rr = (wm * TM + i) * 32 + 8 * q + 4 * (lane >> 5);
-                    *reinterpret_cast<bf16x4*>(sC + cc * LDR + rr) = pk;
-                } else {
-                    int rr = (wm * TM + i) * 32 + (lane & 31);
-                    int cc = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
-                    *reinterpret_cast<bf16x4*>(sC + rr * LDC + cc) = pk;
-                }
-            }
-    for (int rr = tid; rr < BM; rr += NT) {
-        uint32_t g = row0 + rr;
-        int64_t base = -1;
-        if (g < a.total_rows) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            base = int64_t(t) * a.c_tok_stride + a.crow[r];
-        }
-        sBase[rr] = base;
-    }
-    __syncthreads();
-    constexpr int GROUPS = BM * BN / 8;
-    if (TRANS) {
-#pragma unroll 4
-        for (int e = tid; e < GROUPS; e += NT) {
-            int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
-            int c = col0 + cc;
-            int64_t base = sBase[rg];
-            if (base < 0 || c >= a.C) continue;
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + cc * LDR + rg);
-        }
-    } else if (cmode == 1) {
-#pragma unroll 4
-        for (int e = tid; e < GROUPS; e += NT) {
-            int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
-            int c = col0 + cg;
-            int64_t base = sBase[rr];
-            if (base < 0 || c >= a.C) continue;
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
-        }
-    } else {
-        for (int e = tid; e < BM * BN; e += NT) {
-            int rr = e / BN, cc = e % BN;
-            int c = col0 + cc;
-            int64_t base = sBase[rr];
-            if (base < 0 || c >= a.C) continue;
-            Out[base + a.ccol[c]] = sC[rr * LDC + cc];
-        }
-    }
-}
-
-template <int WM, int WN, int TM, int TN, int NS>
-constexpr size_t dlds_smem_bytes() {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t stage = size_t(BM + BN) * 64 * NS;
-    constexpr size_t c_elems = size_t(BM) * (BN + 8) > size_t(BN) * (BM + 8) ? size_t(BM) * (BN + 8) : size_t(BN) * (BM + 8);
-    constexpr size_t epi = c_elems * 2 + size_t(BM) * 8;
-    return stage > epi ? stage : epi;
-}
-
-template <int WM, int WN, int TM, int TN, int STAGES>
-constexpr size_t pipe_smem_bytes() {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t stage = size_t(BM + BN) * (64 + 8) * 2 * STAGES;
-    constexpr size_t c_elems = size_t(BM) * (BN + 8) > size_t(BN) * (BM + 8) ? size_t(BM) * (BN + 8) : size_t(BN) * (BM + 8);
-    constexpr size_t epi = c_elems * 2 + size_t(BM) * 8;
-    return stage > epi ? stage : epi;
-}
-
-// ---------------------------------------------------------------------------------------------
-// Short-K kernel (K <= 64): steps such as the first contraction of a chain read little and write
-// a lot, so they are bound by the store stream. A workgroup owns 128 rows and walks over all
-// columns, 128 at a time. The A fragments of its rows (the whole K) stay in registers for the whole
-// walk; the packed tensor's fragment blocks are loaded from memory straight into MFMA operand
-// registers (double-buffered across column iterations); each wave turns its 64x64 result into
-// row-contiguous 16-byte pieces through a private LDS patch and stores it. No workgroup barrier
-// is used anywhere, so the stores of one wave overlap the loads and MFMAs of the others.
-// Requires Kp == 64, aligned runs of 8 columns in the output (CMODE 1) and Cp % 128 == 0.
-// ---------------------------------------------------------------------------------------------
-template <int AMODE, int TMW, int DBUF, int MINB>
-__global__ void __launch_bounds__(256, MINB) step_shortk_kernel(StepArgs a) {
-    // TMW = 32-row tiles per wave (1 or 2): the workgroup covers 4 * TMW * 32 / 2 ... rows, see below
-    constexpr int LDP = 64 + 8;                          // padded row of the wave's LDS patch
-    constexpr int WROWS = TMW * 32;                      // rows per wave
-    __shared__ __attribute__((aligned(16))) bf16_t patch[4][WROWS * LDP];
-    const bf16_t* A = static_cast<const bf16_t*>(a.A);
-    const bf16_t* B = static_cast<const bf16_t*>(a.B);
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;             // 2 x 2 waves: rows wm, 64-column half wn
-    const uint32_t row0 = blockIdx.x * (2 * WROWS) + wm * WROWS;
-    bf16_t* sP = patch[wave];
-
-    // A fragments for the wave's rows and all 4 k-steps
-    bf16x8 af[TMW][4];
-#pragma unroll
-    for (int i = 0; i < TMW; ++i) {
-        uint32_t g = row0 + i * 32 + (lane & 31);
-        int64_t base = -1;
-        if (g < a.total_rows) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            base = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 v;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
-            int k = ks * 16 + 8 * (lane >> 5);
-            if (base >= 0) {
-                if (AMODE == 0) {
-                    if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + base + k);
-                } else {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        if (k + q < a.K) v[q] = A[base + (a.acol ? a.acol[k + q] : k + q)];
-                }
-            }
-            af[i][ks] = v;
-        }
-    }
-    // output bases of the rows this lane stores per iteration (row p*8 + lane/8), in units of 8
-    // elements (every run of 8 columns is 16-byte aligned), so that they fit 32 bits
-    constexpr int NP = WROWS / 8;
-    uint32_t obase8[NP];
-    bool ovalid[NP];
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        uint32_t g = row0 + p * 8 + (lane >> 3);
-        ovalid[p] = g < a.total_rows;
-        obase8[p] = 0;
-        if (ovalid[p]) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            obase8[p] = uint32_t((int64_t(t) * a.c_tok_stride + a.crow[r]) >> 3);
-        }
-    }
-    const int ncol_iters = a.Cp >> 7;
-    const bf16_t* bp = B + lane * 8;                     // Kp == 64: 4 k-step blocks per column block
-    auto load_b = [&](int it, bf16x8 (&bf)[2][4]) {
-        int cb = it * 4 + wn * 2;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                bf[j][ks] = *reinterpret_cast<const bf16x8*>(bp + (int64_t(cb + j) * 4 + ks) * 512);
-    };
-    // column iterations are dealt round-robin over gridDim.y workgroups (1 when there are enough
-    // row tiles to fill the chip)
-    const int it_step = gridDim.y;
-    bf16x8 bcur[2][4], bnext[2][4];
-    if (DBUF && int(blockIdx.y) < ncol_iters) load_b(blockIdx.y, bcur);
-    for (int it = blockIdx.y; it < ncol_iters; it += it_step) {
-        if (DBUF) {
-            if (it + it_step < ncol_iters) load_b(it + it_step, bnext);
-        } else {
-            load_b(it, bcur);
-        }
-        floatx16 acc[TMW][2];
-#pragma unroll
-        for (int i = 0; i < TMW; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int i = 0; i < TMW; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bcur[j][ks], af[i][ks], acc[i][j], 0, 0, 0);
-        // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
-#pragma unroll
-        for (int i = 0; i < TMW; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    bf16x4 pk;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[i][j][4 * q + u]);
-                    *reinterpret_cast<bf16x4*>(sP + (i * 32 + (lane & 31)) * LDP + j * 32 + 8 * q + 4 * (lane >> 5)) = pk;
-                }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int c = it * 128 + wn * 64 + (lane & 7) * 8;
-        if (c < a.C) {
-            const uint32_t coff8 = uint32_t(a.ccol[c]) >> 3;
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                bf16x8 v = *reinterpret_cast<const bf16x8*>(sP + (p * 8 + (lane >> 3)) * LDP + (lane & 7) * 8);
-                if (ovalid[p]) *reinterpret_cast<bf16x8*>(Out + (int64_t(obase8[p] + coff8) << 3)) = v;
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        if (DBUF) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) bcur[j][ks] = bnext[j][ks];
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Split-K kernel for launches whose output has too few tiles to fill the chip: decode (1-64
-// tokens) and small batches. Grid = (row tiles of TM*32 rows) x (32-column blocks) x (K splits).
-// The NW waves of a workgroup (4, 8 or 16: more waves keep more of the weight stream in flight)
-// take the 16-wide k-steps of the split round-robin; each wave loads
-// the packed tensor's 1 KB fragment blocks straight from memory into MFMA operand registers (no
-// LDS staging, fully coalesced: this is the stream that is HBM-bound at decode) and the matching
-// A fragments (a few rows) from global memory. The per-wave accumulators are summed through LDS
-// in a fixed order. With one split the result is stored through the scatter tables; otherwise it
-// goes to an fp32 partial buffer that step_split_reduce_kernel sums in split order, so results
-// stay bit-reproducible (no atomics). A single-pass variant in which the last workgroup to arrive
-// at a tile does the sum was measured 8x slower: a device-scope fence on this chip writes back the
-// L2 of the workgroup's XCD.
-// ---------------------------------------------------------------------------------------------
-template <int TM, int AMODE, int NW>
-__global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
-    __shared__ float red[NW][TM][16][64];
-    const bf16_t* A = static_cast<const bf16_t*>(a.A);
-    const bf16_t* B = static_cast<const bf16_t*>(a.B);
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t row0 = blockIdx.x * (TM * 32);
-    const int cb = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
-    const int nks = a.Kp >> 4;
-    const int ks_begin = split * ksteps_per_split;
-    const int ks_end = min(nks, ks_begin + ksteps_per_split);
-
-    int64_t a_base[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        uint32_t g = row0 + i * 32 + (lane & 31);
-        a_base[i] = -1;
-        if (g < a.total_rows) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            a_base[i] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
-        }
-    }
-    const bf16_t* bp = B + (int64_t(cb) * nks) * 512 + lane * 8;
-    floatx16 acc[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-
-    // U k-steps per batch and two batches in registers: the next batch is requested before the current
-    // one is multiplied, so a wave always has loads in flight (a decode-size launch is a pure stream of
-    // the packed tensor; with one batch the stream would drain at every wait)
-    constexpr int U = 4;
-    auto load_batch = [&](int ks0, bf16x8 (&bf)[U], bf16x8 (&af)[U][TM]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int ks = ks0 + NW * u;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) bf[u][q] = bf16_t(0.f);
-            if (ks < ks_end) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(ks) * 512);
-            int k = ks * 16 + 8 * (lane >> 5);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                bf16x8 v;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] = bf16_t(0.f);
-                if (ks < ks_end && a_base[i] >= 0) {
-                    if (AMODE == 0) {
-                        if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + a_base[i] + k);
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < 8; ++q)
-                            if (k + q < a.K) v[q] = A[a_base[i] + (a.acol ? a.acol[k + q] : k + q)];
-                    }
-                }
-                af[u][i] = v;
-            }
-        }
-    };
-    auto multiply = [&](const bf16x8 (&bf)[U], const bf16x8 (&af)[U][TM]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], af[u][i], acc[i], 0, 0, 0);
-    };
-    {
-        bf16x8 bf0[U], af0[U][TM], bf1[U], af1[U][TM];
-        constexpr int STEP = NW * U;
-        int ks0 = ks_begin + wave;
-        load_batch(ks0, bf0, af0);                       // batches past the end load nothing and multiply zeros
-        for (; ks0 < ks_end; ks0 += 2 * STEP) {
-            load_batch(ks0 + STEP, bf1, af1);
-            multiply(bf0, af0);
-            load_batch(ks0 + 2 * STEP, bf0, af0);
-            multiply(bf1, af1);
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) red[wave][i][v][lane] = acc[i][v];
-    __syncthreads();
-    // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
-    const uint32_t rows_pad = gridDim.x * (TM * 32);
-    const float* rw = &red[0][0][0][0];
-    for (int e = tid; e < TM * 1024; e += NW * 64) {
-        int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
-        float sum = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) sum += rw[w * TM * 1024 + e];
-        uint32_t g = row0 + i * 32 + (l & 31);
-        int c = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
-        if (g >= a.total_rows || c >= a.C) continue;
-        if (nsplit == 1) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
-        } else {
-            partial[(int64_t(split) * rows_pad + g) * a.Cp + c] = sum;
-        }
-    }
-}
-
-// Sums the partial results of the split-K kernel in split order and stores through the tables.
-__global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, const float* partial, int nsplit,
-                                                                uint32_t rows_pad) {
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
-    int64_t total = int64_t(a.total_rows) * a.C;
-    for (int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x; e < total; e += int64_t(gridDim.x) * 256) {
-        uint32_t g = uint32_t(e / a.C);
-        int c = int(e - int64_t(g) * a.C);
-        // 8 loads in flight at a time; the additions keep the split order
-        float sum = 0.f;
-        const float* src = partial + int64_t(g) * a.Cp + c;
-        const int64_t sstride = int64_t(rows_pad) * a.Cp;
-        for (int s0 = 0; s0 < nsplit; s0 += 8) {
-            float v[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = s0 + q < nsplit ? src[int64_t(s0 + q) * sstride] : 0.f;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) sum += v[q];
-        }
-        uint32_t t = g / a.R;
-        uint32_t r = g - t * a.R;
-        Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Fused pair of small steps (e.g. the two out-factor or the two in-factor products of a Tucker
-// layer): when one token's input of the first step and its intermediate fit in LDS, a workgroup
-// takes tokens one at a time, stages the token's [R1, K1] input in LDS, runs step 1 with MFMA into
-// an LDS copy of the intermediate (written through step 1's scatter tables, i.e. already in the
-// layout step 2 reads), runs step 2 from LDS and stores its result through step 2's tables. Each
-// wave owns up to two 32-column tiles of either packed tensor and keeps their fragment blocks in
-// registers for all the tokens of the workgroup (K <= 96, C <= 256); the next token's input is
-// prefetched into registers while the current one is computed. The intermediate never touches HBM and one launch
-// replaces two. Needs K1 % 16 == 0 and K2 % 16 == 0 (no padded k-steps are ever read).
-// CM2 = 1: step 2's columns come in aligned runs of 8 -> 16-byte stores via a per-wave LDS patch;
-// CM2 = 0: scalar stores.
-// ---------------------------------------------------------------------------------------------
-struct Fused2Args {
-    StepArgs s1, s2;
-    int32_t tokens;
-    int32_t in_elems;     // LDS elements reserved for the staged input: roundup(R1, 32) * (K1 + 8)
-    int32_t mid_elems;    // LDS elements reserved for the intermediate: roundup(R2, 32) * K2
-};
-
-template <int CM2>
-__global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-    const StepArgs& a1 = f.s1;
-    const StepArgs& a2 = f.s2;
-    const int R1 = int(a1.R), K1 = a1.K, C1 = a1.C, R2 = int(a2.R), K2 = a2.K, C2 = a2.C;
-    const int LD1 = K1 + 8;
-    bf16_t* sIn = reinterpret_cast<bf16_t*>(dyn_smem);
-    bf16_t* sMid = sIn + f.in_elems;
-    bf16_t* sPatch = sMid + f.mid_elems;                       // 4 waves x 32 x 40
-    int32_t* sTab = reinterpret_cast<int32_t*>(sPatch + 4 * 32 * 40);
-    int32_t* t_crow1 = sTab;
-    int32_t* t_ccol1 = t_crow1 + R1;
-    int32_t* t_crow2 = t_ccol1 + C1;
-    int32_t* t_ccol2 = t_crow2 + R2;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < R1; i += 256) t_crow1[i] = a1.crow[i];
-    for (int i = tid; i < C1; i += 256) t_ccol1[i] = a1.ccol[i];
-    for (int i = tid; i < R2; i += 256) t_crow2[i] = a2.crow[i];
-    for (int i = tid; i < C2; i += 256) t_ccol2[i] = a2.ccol[i];
-    // rows past R1 / R2 of the last row tile are read by the MFMAs (their results are dropped):
-    // give them defined contents once
-    for (int i = tid; i < f.in_elems; i += 256) sIn[i] = bf16_t(0.f);
-    for (int i = tid; i < f.mid_elems; i += 256) sMid[i] = bf16_t(0.f);
-    __syncthreads();
-
-    const bf16_t* A = static_cast<const bf16_t*>(a1.A);
-    const bf16_t* B1 = static_cast<const bf16_t*>(a1.B);
-    const bf16_t* B2 = static_cast<const bf16_t*>(a2.B);
-    bf16_t* Out = static_cast<bf16_t*>(a2.Out);
-    const int nks1 = K1 >> 4, nks2 = K2 >> 4;                  // real k-steps (<= 6)
-    const int bks1 = a1.Kp >> 4, bks2 = a2.Kp >> 4;            // k-steps per column block in the packed tensors
-    const int nrt1 = (R1 + 31) >> 5, nct1 = (C1 + 31) >> 5;
-    const int nrt2 = (R2 + 31) >> 5, nct2 = (C2 + 31) >> 5;     // nct <= 8: column tiles j = wave, wave + 4
-    const int chunks_per_row = K1 >> 3;
-    bf16_t* myPatch = sPatch + wave * 32 * 40;
-
-    // the wave's column tiles of both packed tensors stay in registers for all of its tokens
-    bf16x8 bw1[2][6], bw2[2][6];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int ks = 0; ks < 6; ++ks) {
-            bf16x8 z;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
-            int j = wave + 4 * jj;
-            bw1[jj][ks] = (j < nct1 && ks < nks1)
-                              ? *reinterpret_cast<const bf16x8*>(B1 + (int64_t(j) * bks1 + ks) * 512 + lane * 8) : z;
-            bw2[jj][ks] = (j < nct2 && ks < nks2)
-                              ? *reinterpret_cast<const bf16x8*>(B2 + (int64_t(j) * bks2 + ks) * 512 + lane * 8) : z;
-        }
-
-    // the next token's input is fetched into registers while the current token is computed
-    // (at most 6 chunks of 16 bytes per thread: R1 * K1 <= 12288)
-    const int n_chunks = R1 * chunks_per_row;
-    int my_off[6];                                             // LDS element offset of each of my chunks
-#pragma unroll
-    for (int q = 0; q < 6; ++q) {
-        int e = tid + 256 * q;
-        int r = e / chunks_per_row;
-        my_off[q] = e < n_chunks ? r * LD1 + (e - r * chunks_per_row) * 8 : -1;
-    }
-    bf16x8 pre[6];
-    auto fetch_in = [&](int t) {
-        const bf16_t* in = A + int64_t(t) * a1.a_tok_stride + tid * 8;
-#pragma unroll
-        for (int q = 0; q < 6; ++q)
-            if (my_off[q] >= 0) pre[q] = *reinterpret_cast<const bf16x8*>(in + 2048 * q);
-    };
-    if (int(blockIdx.x) < f.tokens) fetch_in(blockIdx.x);
-    for (int t = blockIdx.x; t < f.tokens; t += gridDim.x) {
-        // ---- stage the token's input
-#pragma unroll
-        for (int q = 0; q < 6; ++q)
-            if (my_off[q] >= 0) *reinterpret_cast<bf16x8*>(sIn + my_off[q]) = pre[q];
-        __syncthreads();
-        if (t + int(gridDim.x) < f.tokens) fetch_in(t + gridDim.x);
-        // ---- step 1
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int j = wave + 4 * jj;
-            if (j >= nct1) continue;
-            for (int i = 0; i < nrt1; ++i) {
-                floatx16 acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-                const bf16_t* ap = sIn + (i * 32 + (lane & 31)) * LD1 + 8 * (lane >> 5);
-                bf16x8 af[6];                 // all fragment reads first, then the MFMA chain
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks1) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw1[jj][ks], af[ks], acc, 0, 0, 0);
-                // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
-                int r = i * 32 + (lane & 31);
-                if (r < R1) {
-                    int rbase = t_crow1[r];
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                        if (c < C1) sMid[rbase + t_ccol1[c]] = bf16_t(acc[v]);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        // ---- step 2 from the LDS intermediate
-        bf16_t* out_t = Out + int64_t(t) * a2.c_tok_stride;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int j = wave + 4 * jj;
-            if (j >= nct2) continue;
-            for (int i = 0; i < nrt2; ++i) {
-                floatx16 acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-                const bf16_t* ap = sMid + (i * 32 + (lane & 31)) * K2 + 8 * (lane >> 5);
-                bf16x8 af[6];
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks2) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw2[jj][ks], af[ks], acc, 0, 0, 0);
-                if (CM2 == 1) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        bf16x4 pk;
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[4 * q + u]);
-                        *reinterpret_cast<bf16x4*>(myPatch + (lane & 31) * 40 + 8 * q + 4 * (lane >> 5)) = pk;
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    int c = j * 32 + (lane & 3) * 8;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        int rr = h * 16 + (lane >> 2);
-                        int r = i * 32 + rr;
-                        bf16x8 v = *reinterpret_cast<const bf16x8*>(myPatch + rr * 40 + (lane & 3) * 8);
-                        if (r < R2 && c < C2) *reinterpret_cast<bf16x8*>(out_t + t_crow2[r] + t_ccol2[c]) = v;
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                } else {
-                    int r = i * 32 + (lane & 31);
-                    if (r < R2) {
-                        int rbase = t_crow2[r];
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                            if (c < C2) out_t[rbase + t_ccol2[c]] = bf16_t(acc[v]);
-                        }
-                    }
-                }
-            }
-        }
-        __syncthreads();   // sIn and sMid are rewritten for the next token
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Chained pair kernel: a short-K step followed by a long-K step whose K is (rows of the first
-// step) x (a bond of 64), the shape a tensor train takes once its end cores are contracted into
-// their neighbours (Section 3.5: fuse core contractions, specialise for shared ranks):
-//     Z[t][j][a][b] = sum_k  X[t][a*64 + k] * B0[j*64 + b][k]          K0 = 64, bond b < 64
-//     Y[t][yrow[j] + ycol[c]] = sum_{a, b} Z[t][j][a][b] * B1[c][a*64 + b]      c < C1 <= 128
-// Unfused, Z (A*J*64 values per token) is written to and read back from HBM and both launches are
-// bound by that traffic. Here Z never leaves the registers: a workgroup owns 32 tokens and 8
-// values of j (two per wave) and walks over a. For one a, a wave computes Z^T[b][t] for its two j
-// with the packed tensor of the first step as the row operand (kept in registers for the whole
-// walk) and the tokens as MFMA columns; the result lands in the accumulator layout (lane: token
-// l%32, b = 8*(v/4) + 4*(l/32) + v%4), which after rounding to bf16 IS the column operand of the
-// second contraction when that step's packed tensor is stored with the same permutation of b
-// inside each k-step of 16 (done once at create time by pair_repack_kernel). Per a the workgroup
-// streams a 16 KB slice of B1 and 4 KB of X into a ring of LDS stages with direct-to-LDS loads.
-// The 32 x C1 x 8 results of the workgroup are transposed through LDS and stored as 16-byte
-// pieces (8 consecutive j). Workgroups that share a token tile run back to back on one XCD, so
-// that their reads of X and their pieces of the same output lines meet in that XCD's L2.
-// ---------------------------------------------------------------------------------------------
-struct PairArgs {
-    const void* X;
-    void* Y;
-    const void* B0;        // first step's packed tensor, fragment-major [J*64][64]
-    const void* B1f;       // second step's packed tensor in the chained layout (pair_repack_kernel)
-    const int32_t* yrow;   // output offset of j (J entries, aligned runs of 8)
-    const int32_t* ycol;   // output offset of c (C1 entries, multiples of 8)
-    int64_t N, M;          // elements per token of X and Y
-    int32_t tokens, A, J, C1;
-    int32_t n_tok_tiles, n_jsets;
-};
-
-// B1f[((a*16 + ct*4 + s)*64 + l)*8 + e] = B1[c = 32*ct + l%32][k = a*64 + 16*s + 8*(e/4) + 4*(l/32) + e%4]
-__global__ void __launch_bounds__(256) pair_repack_kernel(const bf16_t* src, bf16_t* dst, int A, int nks, int Cp) {
-    int64_t total = int64_t(A) * 8192;
-    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
-        int e = int(i & 7), l = int(i >> 3) & 63, blk = int(i >> 9) & 15;
-        int a = int(i >> 13);
-        int c = 32 * (blk >> 2) + (l & 31);
-        int k = a * 64 + 16 * (blk & 3) + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
-        dst[i] = c < Cp ? src[bfrag_offset(c, k, nks)] : bf16_t(0.f);      // columns past Cp do not exist
-    }
-}
-
-template <int NS>
-__global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
-    constexpr int L = 5;                               // NS ring stages; L direct-to-LDS loads per wave and stage
-    constexpr int STAGE_BYTES = 20 * 1024, X_OFF = 16 * 1024;
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
-    const int tok_tile = (slot / p.n_jsets) * 8 + xcd;
-    const int jset = slot % p.n_jsets;
-    if (tok_tile >= p.n_tok_tiles) return;
-    const int t0 = tok_tile * 32;
-
-    const bf16_t* X = static_cast<const bf16_t*>(p.X);
-    const bf16_t* B0 = static_cast<const bf16_t*>(p.B0);
-    const bf16_t* B1f = static_cast<const bf16_t*>(p.B1f);
-    bf16_t* Y = static_cast<bf16_t*>(p.Y);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int j0 = jset * 8 + wave * 2;
-    const int A = p.A;
-
-    // the wave's rows of the first packed tensor: [jj][32-row half of the bond][k-step]
-    bf16x8 p0[2][2][4];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                p0[jj][rt][s] = *reinterpret_cast<const bf16x8*>(B0 + (int64_t((j0 + jj) * 2 + rt) * 4 + s) * 512 + lane * 8);
-
-    // direct-to-LDS sources: wave w brings blocks w, w+4, w+8, w+12 of the B1 slice and k-step w of X
-    const int tl = min(t0 + (lane & 31), p.tokens - 1);             // rows past the end repeat the last token
-    const bf16_t* x_src = X + int64_t(tl) * p.N + 16 * wave + 8 * (lane >> 5);
-    const bf16_t* b_src = B1f + lane * 8;
-    auto issue = [&](int a, int stage) {
-        unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)(b_src + (int64_t(a) * 16 + wave + 4 * q) * 512),
-                (void __attribute__((address_space(3)))*)(sbase + (wave + 4 * q) * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(
-            (const void __attribute__((address_space(1)))*)(x_src + int64_t(a) * 64),
-            (void __attribute__((address_space(3)))*)(sbase + X_OFF + wave * 1024), 16, 0, 0);
-    };
-    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform, at most NS - 2
-        if (n <= 0) wait_vmcnt<0>();
-        else if (n == 1) wait_vmcnt<L>();
-        else if (n == 2 || NS <= 4) wait_vmcnt<2 * L>();
-        else if (n == 3 || NS <= 5) wait_vmcnt<3 * L>();
-        else wait_vmcnt<4 * L>();
-    };
-
-    floatx16 acc[2][4];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[jj][ct][v] = 0.f;
-
-    int issued = 0;
-    for (; issued < NS - 1 && issued < A; ++issued) issue(issued, issued);
-    wait_outstanding_tiles(min(issued - 1, NS - 2));     // tile 0 has landed
-    __syncthreads();
-    bf16x8 xb[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(dyn_smem + X_OFF + s * 1024 + lane * 16);
-
-    // first contraction for one j: Z^T[b][t], two 32-row halves of the bond
-    auto contract0 = [&](const bf16x8 (&w)[2][4], const bf16x8 (&x)[4], floatx16 (&z)[2]) {
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) z[rt][v] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-                z[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[rt][s], x[s], z[rt], 0, 0, 0);
-    };
-    // second contraction for one j: Y^T[c][t] += B1[c][(a, b)] Z^T[b][t]. Registers 8*(s%2) .. +7 of
-    // half s/2 of z are the 8 values this lane supplies to k-step s.
-    auto contract1 = [&](const bf16x8 (&w)[4][4], const floatx16 (&z)[2], floatx16 (&y)[4]) {
-        bf16x8 zb[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) zb[s][e] = bf16_t(z[s >> 1][8 * (s & 1) + e]);
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
-                y[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ct][s], zb[s], y[ct], 0, 0, 0);
-    };
-
-    // software pipeline over (a, j): the first contraction of the next unit is issued before the
-    // second contraction of the current one, so that reading back and rounding Z overlaps MFMAs
-    floatx16 z0[2], z1[2];
-    contract0(p0[0], xb, z0);
-    auto iteration = [&](int a, auto last_tag) {
-        constexpr bool LAST = decltype(last_tag)::value;
-        if (!LAST) wait_outstanding_tiles(issued - (a + 2));       // tile a+1 has landed
-        __syncthreads();       // everyone is done with tile a-1: its stage may be refilled
-        if (issued < A) {
-            issue(issued, issued % NS);
-            ++issued;
-        }
-        const unsigned char* scur = dyn_smem + (a % NS) * STAGE_BYTES;
-        const unsigned char* snxt = dyn_smem + ((a + 1) % NS) * STAGE_BYTES;
-        bf16x8 p1[4][4];
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                p1[ct][s] = *reinterpret_cast<const bf16x8*>(scur + (ct * 4 + s) * 1024 + lane * 16);
-        // the scheduler would otherwise sink each LDS read next to its first use and expose the LDS
-        // latency 16 times per iteration
-        __builtin_amdgcn_sched_barrier(0);
-        contract0(p0[1], xb, z1);
-        if (!LAST) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(snxt + X_OFF + s * 1024 + lane * 16);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        contract1(p1, z0, acc[0]);
-        if (!LAST) contract0(p0[0], xb, z0);
-        contract1(p1, z1, acc[1]);
-        // keep the accumulators in the accumulation registers across the back edge (the register
-        // allocator otherwise parks some of them in ordinary registers and copies them every
-        // iteration)
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-            for (int ct = 0; ct < 4; ++ct) asm volatile("" : "+a"(acc[jj][ct]));
-        if (!LAST) {
-            asm volatile("" : "+a"(z0[0]));
-            asm volatile("" : "+a"(z0[1]));
-        }
-    };
-    for (int a = 0; a + 1 < A; ++a) iteration(a, std::false_type());
-    iteration(A - 1, std::true_type());
-    __syncthreads();
-
-    // ---- epilogue: lane l, register v of acc[jj][ct] is token l%32, c = 32*ct + 8*(v/4) + 4*(l/32) + v%4.
-    //      LDS holds [32 tokens][128 c] pieces of 16 bytes (the 8 j of the workgroup), the piece of
-    //      (t, c) at position c ^ t of row t so that neither the 4-byte writes nor the 16-byte reads
-    //      pile up on a bank.
-    {
-        const int t = lane & 31;
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int c = 32 * ct + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                bf16x2 pr;
-                pr[0] = bf16_t(acc[0][ct][v]);
-                pr[1] = bf16_t(acc[1][ct][v]);
-                *reinterpret_cast<bf16x2*>(dyn_smem + (t * 128 + (c ^ t)) * 16 + wave * 4) = pr;
-            }
-    }
-    __syncthreads();
-    const int yj = p.yrow[jset * 8];
-#pragma unroll 4
-    for (int e = tid; e < 32 * 128; e += 256) {
-        int t = e >> 7, c = e & 127;
-        if (t0 + t >= p.tokens || c >= p.C1) continue;
-        bf16x8 v = *reinterpret_cast<const bf16x8*>(dyn_smem + (t * 128 + (c ^ t)) * 16);
-        *reinterpret_cast<bf16x8*>(Y + int64_t(t0 + t) * p.M + p.ycol[c] + yj) = v;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Transposing chain of two small steps (the two in-factor or the two out-factor products of a
-// Tucker layer): the second step contracts the ROW index r of the first and keeps its column index
-// c1 as a row,
-//     T[r][c1] = sum_k  In[t][r][k] * Ba[c1][k]                    R1 x K1 input per token
-//     Out[t][off1[c1] + off2[c2]] = sum_r T[r][c1] * Bb[c2][r]
-// A wave owns one token at a time. The token's input travels from memory straight into a
-// wave-private LDS buffer in MFMA fragment order (direct-to-LDS loads, double buffered: the next
-// token's input is in flight while the current one is computed; no workgroup barrier anywhere).
-// For each tile of 32 values of c1 the wave computes T^T as accumulator tiles with r in the
-// registers and c1 across the lanes, rounds them to bf16 and feeds them - without leaving the
-// registers - to the second contraction, whose packed tensor is stored at create time with the
-// matching permutation of r inside each k-step (chain2_repack_kernel) and stays in registers for
-// all tokens. The intermediate T never exists in memory, one launch replaces two, and the HBM
-// traffic drops to the first step's input plus the second step's output.
-// RUN_C1 = 1: the output takes 8 consecutive c1 as an aligned 16-byte piece (T^T is the row operand
-// of the second MFMA, so a lane ends up with 4 consecutive c1); RUN_C1 = 0: 8 consecutive c2 (T^T is
-// the column operand). Either way the 32x32 result tiles pass through a wave-private LDS patch and
-// leave as 16-byte stores.
-// Limits: R1 <= 32*R1T, K1 <= 16*K1S, K1 % 8 == 0, C2 <= 32*C2T; any C1.
-// ---------------------------------------------------------------------------------------------
-struct Chain2Args {
-    const void* In;
-    void* Out;
-    const void* Ba;         // first step's packed tensor (fragment-major, nks_a k-steps per column block)
-    const void* Bbf;        // second step's packed tensor in the chained layout
-    const int32_t* off1;    // output offset of c1 (the second step's row table)
-    const int32_t* off2;    // output offset of c2 (the second step's column table)
-    int64_t in_tok_stride, out_tok_stride;
-    int32_t tokens, R1, K1, C1, C2;
-    int32_t nks_a;
-    int32_t c1_tiles;       // ceil(C1 / 32)
-    int32_t tiles_per_item; // c1 tiles one wave handles per visit of a token (all of them for large
-                            // batches; 1 spreads a single token over several waves)
-};
-
-// Bbf[((j*KS + s)*64 + l)*8 + e] = Bb[c2 = 32*j + l%32][r = 16*s + 8*(e/4) + 4*(l/32) + e%4], zero outside
-__global__ void __launch_bounds__(256) chain2_repack_kernel(const bf16_t* src, bf16_t* dst, int C2T, int KS,
-                                                            int nks_src, int Cp, int Kp) {
-    int total = C2T * KS * 512;
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
-        int e = i & 7, l = (i >> 3) & 63, blk = i >> 9;
-        int j = blk / KS, sk = blk - j * KS;
-        int c = 32 * j + (l & 31);
-        int k = 16 * sk + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
-        dst[i] = (c < Cp && k < Kp) ? src[bfrag_offset(c, k, nks_src)] : bf16_t(0.f);
-    }
-}
-
-template <int R1T, int K1S, int C2T>
-constexpr size_t chain2_smem_bytes() {
-    return size_t(4) * (R1T * K1S * 1024 + 2 * 32 * 80);
-}
-
-template <int R1T, int K1S, int C2T, int RUN_C1>
-__global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
-    constexpr int IN_BYTES = R1T * K1S * 1024;           // one token's input in fragment order
-    constexpr int KS2 = 2 * R1T;                         // k-steps of the second contraction
-    constexpr int PATCH_LD = 80;                         // bytes per patch row (64 + 16 of padding)
-    constexpr int PATCH_BYTES = 32 * PATCH_LD;
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-    const bf16_t* In = static_cast<const bf16_t*>(p.In);
-    const bf16_t* Ba = static_cast<const bf16_t*>(p.Ba);
-    const bf16_t* Bbf = static_cast<const bf16_t*>(p.Bbf);
-    bf16_t* Out = static_cast<bf16_t*>(p.Out);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    unsigned char* my_in = dyn_smem + wave * IN_BYTES;
-    unsigned char* my_patch = dyn_smem + 4 * IN_BYTES + wave * (2 * PATCH_BYTES);
-
-    const int n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
-    const int64_t n_items = int64_t(p.tokens) * n_groups;
-    const int64_t gw = int64_t(blockIdx.x) * 4 + wave, GW = int64_t(gridDim.x) * 4;
-    if (gw >= n_items) return;                           // no workgroup barrier below: a wave may leave
-
-    // lanes whose (row, k) lies outside the input never load: the fragment blocks they belong to are
-    // zeroed once and keep those zeros
-#pragma unroll
-    for (int i = 0; i < R1T; ++i)
-#pragma unroll
-        for (int sk = 0; sk < K1S; ++sk)
-            if (32 * i + 32 > p.R1 || 16 * sk + 16 > p.K1) {        // wave-uniform
-                bf16x8 z;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
-                *reinterpret_cast<bf16x8*>(my_in + (i * K1S + sk) * 1024 + lane * 16) = z;
-            }
-    __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): the zeros are in LDS before any load lands
-    __builtin_amdgcn_wave_barrier();
-
-    // the second packed tensor stays in registers for every token of the wave
-    bf16x8 bb[C2T][KS2];
-#pragma unroll
-    for (int j = 0; j < C2T; ++j)
-#pragma unroll
-        for (int sk = 0; sk < KS2; ++sk)
-            bb[j][sk] = *reinterpret_cast<const bf16x8*>(Bbf + (int64_t(j) * KS2 + sk) * 512 + lane * 8);
-
-    const int nrt = (p.R1 + 31) >> 5, nks1 = (p.K1 + 15) >> 4;
-    const int nj = (p.C2 + 31) >> 5;
-    const int lrow = lane & 31, lk = 8 * (lane >> 5);
-    auto issue_in = [&](int t) {
-        const bf16_t* src = In + int64_t(t) * p.in_tok_stride + int64_t(lrow) * p.K1 + lk;
-#pragma unroll
-        for (int i = 0; i < R1T; ++i)
-#pragma unroll
-            for (int sk = 0; sk < K1S; ++sk) {
-                if (i < nrt && sk < nks1) {                          // wave-uniform
-                    if (32 * i + lrow < p.R1 && 16 * sk + lk < p.K1)
-                        __builtin_amdgcn_global_load_lds(
-                            (const void __attribute__((address_space(1)))*)(src + int64_t(32 * i) * p.K1 + 16 * sk),
-                            (void __attribute__((address_space(3)))*)(my_in + (i * K1S + sk) * 1024), 16, 0, 0);
-                }
-            }
-    };
-    auto load_ba = [&](int ct1, bf16x8 (&ba)[K1S]) {
-#pragma unroll
-        for (int sk = 0; sk < K1S; ++sk)      // k-steps past the packed tensor's padding meet zero input: any finite block will do
-            ba[sk] = *reinterpret_cast<const bf16x8*>(Ba + (int64_t(ct1) * p.nks_a + min(sk, p.nks_a - 1)) * 512 + lane * 8);
-    };
-
-    // output offsets of the two 16-byte pieces a lane stores per 32x32 tile (patch row lane/4 + 16h,
-    // piece lane%4): those along c2 never change; those along c1 are fetched a tile ahead. -1 = outside.
-    const int prow = lane >> 2, pchunk = lane & 3;
-    int o2[C2T][2];
-#pragma unroll
-    for (int j = 0; j < C2T; ++j)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            int c2 = 32 * j + (RUN_C1 ? prow + 16 * h : 8 * pchunk);
-            o2[j][h] = c2 < p.C2 ? p.off2[c2] : -1;
-        }
-    auto load_o1 = [&](int ct1, int (&o1)[2]) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            int c1 = 32 * ct1 + (RUN_C1 ? 8 * pchunk : prow + 16 * h);
-            o1[h] = c1 < p.C1 ? p.off1[c1] : -1;
-        }
-    };
-
-    // Vector memory operations a full item issues after its input request (the packed-tensor loads and
-    // the stores of every tile but a possibly ragged last one, a lower bound). Loads complete in issue
-    // order, so once at most 63 operations are in flight an input request older than that has landed,
-    // without waiting for the latest stores to be acknowledged.
-    const int ops_after = max(0, p.tiles_per_item - ((p.C1 & 31) ? 1 : 0)) * (K1S + 2 * (p.C2 >> 5));
-    issue_in(int(gw / n_groups));
-    for (int64_t item = gw; item < n_items; item += GW) {
-        const int t = int(item / n_groups);
-        const int g = int(item - int64_t(t) * n_groups);
-        const int tile_begin = g * p.tiles_per_item;
-        const int tile_end = min(p.c1_tiles, tile_begin + p.tiles_per_item);
-        bf16x8 ba_next[K1S];
-        int o1_next[2];
-        load_ba(tile_begin, ba_next);
-        load_o1(tile_begin, o1_next);
-        if (item == gw || ops_after < 66 + K1S) wait_vmcnt<0>();
-        else wait_vmcnt<61 - K1S>();                                  // the loads above are younger still
-        // the token's input moves to registers; its LDS buffer then takes the next item's input,
-        // which travels while this item is computed
-        bf16x8 inf[R1T][K1S];
-#pragma unroll
-        for (int i = 0; i < R1T; ++i)
-#pragma unroll
-            for (int sk = 0; sk < K1S; ++sk)      // slots outside the input hold zeros
-                inf[i][sk] = *reinterpret_cast<const bf16x8*>(my_in + (i * K1S + sk) * 1024 + lane * 16);
-        __builtin_amdgcn_s_waitcnt(0xc07f);                          // the reads are done before the buffer is refilled
-        if (item + GW < n_items) issue_in(int((item + GW) / n_groups));
-        bf16_t* out_t = Out + int64_t(t) * p.out_tok_stride;
-        for (int ct1 = tile_begin; ct1 < tile_end; ++ct1) {
-            bf16x8 ba[K1S];
-#pragma unroll
-            for (int sk = 0; sk < K1S; ++sk) ba[sk] = ba_next[sk];
-            const int o1[2] = {o1_next[0], o1_next[1]};
-            if (ct1 + 1 < tile_end) {
-                load_ba(ct1 + 1, ba_next);
-                load_o1(ct1 + 1, o1_next);
-            }
-            // first contraction: accumulator tile i holds T^T for r in [32i, 32i+32): lane l has c1 = l%32,
-            // register v has r = 32i + 8*(v/4) + 4*(l/32) + v%4
-            floatx16 d[R1T];
-#pragma unroll
-            for (int i = 0; i < R1T; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) d[i][v] = 0.f;
-#pragma unroll
-            for (int sk = 0; sk < K1S; ++sk)
-#pragma unroll
-                for (int i = 0; i < R1T; ++i)
-                    d[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(inf[i][sk], ba[sk], d[i], 0, 0, 0);
-            bf16x8 zb[KS2];
-#pragma unroll
-            for (int i = 0; i < R1T; ++i)
-#pragma unroll
-                for (int u = 0; u < 2; ++u)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) zb[2 * i + u][e] = bf16_t(d[i][8 * u + e]);
-            // second contraction: all tiles of c2 (independent accumulators), then their way out
-            floatx16 acc[C2T];
-#pragma unroll
-            for (int j = 0; j < C2T; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-#pragma unroll
-            for (int sk = 0; sk < KS2; ++sk)
-#pragma unroll
-                for (int j = 0; j < C2T; ++j)
-                        acc[j] = RUN_C1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(zb[sk], bb[j][sk], acc[j], 0, 0, 0)
-                                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j][sk], zb[sk], acc[j], 0, 0, 0);
-            // RUN_C1: lane l holds c2 = 32j + l%32 and, in registers 4q..4q+3, c1 = 32*ct1 + 8q + 4*(l/32) + 0..3
-            // else  : lane l holds c1 = 32*ct1 + l%32 and c2 = 32j + 8q + 4*(l/32) + 0..3
-            // The 32x32 tiles pass through two alternating wave-private LDS patches and leave as 16-byte
-            // pieces; a patch is rewritten two tiles later, after the wave barrier of the tile between.
-#pragma unroll
-            for (int j = 0; j < C2T; ++j) {
-                if (j >= nj) continue;                                 // wave-uniform
-                unsigned char* patch = my_patch + (j & 1) * PATCH_BYTES;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    bf16x4 pk;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[j][4 * q + u]);
-                    *reinterpret_cast<bf16x4*>(patch + (lane & 31) * PATCH_LD + (8 * q + 4 * (lane >> 5)) * 2) = pk;
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    bf16x8 v = *reinterpret_cast<const bf16x8*>(patch + (prow + 16 * h) * PATCH_LD + pchunk * 16);
-                    if (o1[h] >= 0 && o2[j][h] >= 0) *reinterpret_cast<bf16x8*>(out_t + o1[h] + o2[j][h]) = v;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-    }
-}
+#include "kernels/common.hpp"
+#include "kernels/pack.hpp"
+#include "kernels/tiled.hpp"
+#include "kernels/stream.hpp"
+#include "kernels/chained.hpp"
 
 // ---------------------------------------------------------------------------------------------
 // host side
