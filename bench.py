@@ -191,7 +191,8 @@ def main() -> int:
                     help="untimed steps first; the shader clock needs some tens of milliseconds of load to settle")
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--workload", type=int, default=1,
-                    help="single-layer workload 1 (TT), 2 (Tucker), 3 (TR); 4 = the mixed 64-layer stack")
+                    help="single-layer workload 0 (small fp32 TT; use --tokens 16), 1 (TT), 2 (Tucker), 3 (TR); "
+                         "4 = the mixed 64-layer stack")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to "
                          "calibrate the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -243,14 +244,17 @@ def main() -> int:
     x64 = wl.make_x(spec, tokens, args.workload)
     if args.transpose:
         x64 = np.random.Generator(np.random.PCG64([wl.SEED_BASE, args.workload, 99])).standard_normal((tokens, spec.M))
-    dev = [torch.from_numpy(t).to(torch.float32).to(torch.bfloat16).cuda() for t in tensors]
-    x = torch.from_numpy(x64).to(torch.float32).to(torch.bfloat16).cuda()
+    tdt = torch.bfloat16 if spec.dtype == "bf16" else torch.float32
+    code = tn.TN_DTYPE_BF16 if spec.dtype == "bf16" else tn.TN_DTYPE_F32
+    esize = 2 if spec.dtype == "bf16" else 4
+    dev = [torch.from_numpy(t).to(torch.float32).to(tdt).cuda() for t in tensors]
+    x = torch.from_numpy(x64).to(torch.float32).to(tdt).cuda()
     del x64
     layer_flags = ((args.variant << 8) | (2 if args.no_merge else 0) | (16 if args.merge_grow else 0)
                    | (args.shortk_mode << 16) | (32 if args.no_pair_chain else 0) | args.flags | (128 if args.transpose else 0))
-    layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
+    layer = tn.TNLinear(spec.format, code, spec.out_modes, spec.in_modes, spec.ranks, dev,
                         tokens, args.workspace_mb << 20, flags=layer_flags)
-    y = torch.empty((tokens, layer.M), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((tokens, layer.M), dtype=tdt, device="cuda")
     stream = torch.cuda.current_stream()
 
     flops_tok = layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
@@ -260,8 +264,8 @@ def main() -> int:
     step_flops = [q(s, 3) for s in range(n_steps)]
     # algorithmic bytes of a step per token: read its [rows, K] input, write its [rows, cols]
     # output (bf16), plus its packed parameter tensor once per launch
-    step_io_bytes = [2 * q(s, 0) * (q(s, 1) + q(s, 2)) for s in range(n_steps)]
-    step_param_bytes = [2 * q(s, 1) * q(s, 2) for s in range(n_steps)]
+    step_io_bytes = [esize * q(s, 0) * (q(s, 1) + q(s, 2)) for s in range(n_steps)]
+    step_param_bytes = [esize * q(s, 1) * q(s, 2) for s in range(n_steps)]
 
     for _ in range(args.warmup):
         layer.forward(x, out=y)
@@ -290,12 +294,15 @@ def main() -> int:
                              "ms_per_forward": 0.0, "launches_per_forward": 0, "fused_into_previous": True})
             continue
         sec = ms * 1e-3
-        fused = s + 1 < n_steps and reads[s + 1][1] == 0
-        flops_s = step_flops[s] + (step_flops[s + 1] if fused else 0)
-        # one launch for both steps: it reads the first step's input and writes the second step's
-        # output; the intermediate never reaches memory
-        io_s = 2 * (q(s, 0) * q(s, 1) + q(s + 1, 0) * q(s + 1, 2)) if fused else step_io_bytes[s]
-        par_s = step_param_bytes[s] + (step_param_bytes[s + 1] if fused else 0)
+        # steps without launches of their own ran inside this step's launch: it reads this step's input
+        # and writes the last of those steps' output; the intermediates never reach memory
+        last = s
+        while last + 1 < n_steps and reads[last + 1][1] == 0:
+            last += 1
+        fused = last > s
+        flops_s = sum(step_flops[s:last + 1])
+        io_s = esize * (q(s, 0) * q(s, 1) + q(last, 0) * q(last, 2)) if fused else step_io_bytes[s]
+        par_s = sum(step_param_bytes[s:last + 1])
         nbytes = (io_s * tokens + par_s * (launches // args.steps)) * args.steps
         per_step.append({
             "step": s, "rows_per_token": q(s, 0), "K": q(s, 1), "cols": q(s, 2), "kernel_variant": q(s, 5),
@@ -304,7 +311,7 @@ def main() -> int:
             "tflops": flops_s * tokens * args.steps / sec / 1e12 if sec > 0 else 0.0,
             "algorithmic_GBps": nbytes / sec / 1e9 if sec > 0 else 0.0,
             "flop_per_byte": flops_s / io_s,
-            "fused_with_next": fused})
+            "fused_with_next": fused, "steps_in_launch": last - s + 1})
     dom = max(range(n_steps), key=lambda s: per_step[s]["ms_per_forward"])
     ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if per_step[dom]["flop_per_byte"] >= ridge:
@@ -314,10 +321,10 @@ def main() -> int:
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(args, per_step[dom]["fused_with_next"])
     if per_step[dom]["fused_with_next"]:
-        roof["kernel"] = (f"contraction steps {dom} and {dom + 1} in one launch (rows {q(dom, 0)} x K {q(dom, 1)} x cols "
-                          f"{q(dom, 2)}, then rows {q(dom + 1, 0)} x K {q(dom + 1, 1)} x cols {q(dom + 1, 2)} per token; "
-                          f"intermediate in registers), {per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge "
-                          f"of {ridge:.0f}")
+        n_in = per_step[dom]["steps_in_launch"]
+        shapes = ", then ".join(f"rows {q(j, 0)} x K {q(j, 1)} x cols {q(j, 2)}" for j in range(dom, dom + n_in))
+        roof["kernel"] = (f"contraction steps {dom}..{dom + n_in - 1} in one launch ({shapes} per token; intermediates "
+                          f"on chip), {per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge of {ridge:.0f}")
     else:
         roof["kernel"] = (f"contraction step {dom}: rows {q(dom, 0)} x K {q(dom, 1)} x cols {q(dom, 2)} per token, "
                           f"{per_step[dom]['flop_per_byte']:.0f} FLOP/B against a ridge of {ridge:.0f}")
@@ -328,8 +335,9 @@ def main() -> int:
     # decode: 1-token (and 64-token) latency of the same layer, back-to-back calls on one stream,
     # then the per-kernel durations of the same calls from the library's HIP events
     def decode_stats(t):
+        t = min(t, tokens)
         xt = x[:t].contiguous()
-        yt = torch.empty((t, layer.M), dtype=torch.bfloat16, device="cuda")
+        yt = torch.empty((t, layer.M), dtype=tdt, device="cuda")
         for _ in range(20):
             layer.forward(xt, out=yt)
         torch.cuda.synchronize()
@@ -368,10 +376,10 @@ def main() -> int:
         capturing its decode step the same way."""
         copies = [layer]
         for _ in range(instances - 1):
-            copies.append(tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev,
+            copies.append(tn.TNLinear(spec.format, code, spec.out_modes, spec.in_modes, spec.ranks, dev,
                                       max(t, 1), flags=layer_flags))
         xt = x[:t].contiguous()
-        yt = torch.empty((t, layer.M), dtype=torch.bfloat16, device="cuda")
+        yt = torch.empty((t, layer.M), dtype=tdt, device="cuda")
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -420,11 +428,11 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": spec.dtype,
         "data": "synthetic",
         "config": {"workload": f"{spec.name}: {wl.FORMAT_NAMES[spec.format]} in {spec.N}={'x'.join(map(str, spec.in_modes))} "
                                f"out {spec.M}={'x'.join(map(str, spec.out_modes))} ranks {list(spec.ranks)}, "
-                               f"{tokens}-token prefill, bf16 storage, fp32 accumulate"
+                               f"{tokens} tokens, {spec.dtype} storage, fp32 accumulate"
                                + (", applied transposed (Y = X W)" if args.transpose else ""),
                    "tokens": tokens, "chunk_tokens": chunk,
                    "create_time_merges": layer.query(tn.TN_QUERY_NUM_MERGES)},

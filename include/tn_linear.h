@@ -70,6 +70,7 @@ extern "C" {
                                        the gradient of the forward pass with respect to its input, which the
                                        fine-tuning of the factors (Section 3.4) back-propagates through every
                                        layer. TN_QUERY_IN_FEATURES / OUT_FEATURES then report M / N. */
+#define TN_FLAG_NO_SMALL_CHAIN (1 << 20) /* never run a small layer as one launch with all its tensors in LDS */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
@@ -99,7 +100,9 @@ extern "C" {
                                            5 kernel variant chosen (0 plain FMA, 2 narrow 256x32 tile, else
                                              the ids listed at TN_FLAG_VARIANT_SHIFT),
                                            6 1 if this step and the next run as one fused launch, 2 if they
-                                             do so from 256 tokens on (chained pair kernel),
+                                             do so from 256 tokens on (chained pair kernel), 3 if the whole chain
+                                             runs as one launch with its tensors in LDS (small layers: fp32 at any
+                                             token count, bf16 up to 32 tokens),
                                            7 shape test only (also from plan_query): 0, or 1 + the instantiation
                                              of the transposing chain kernel that could run this step with the
                                              next one (consecutive qualifying pairs overlap: create takes them

@@ -25,6 +25,7 @@ TN_FLAG_MERGE_GROW = 16
 TN_FLAG_NO_PAIR_CHAIN = 32
 TN_FLAG_NO_CHAIN2 = 64
 TN_FLAG_TRANSPOSE = 128
+TN_FLAG_NO_SMALL_CHAIN = 1 << 20
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2

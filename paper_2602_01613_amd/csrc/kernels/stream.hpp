@@ -471,3 +471,126 @@ __global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Whole-chain kernel for small layers: when every packed tensor of the plan and two copies of the
+// largest per-token tensor fit in LDS together (the small fp32 train: 19 KB of cores, 8 KB per
+// intermediate), one launch runs all steps. At create time the tensors (as fp32, rows padded) and
+// the offset tables of all steps are laid out as one contiguous image (small_chain_image_kernel); a
+// workgroup copies that image into LDS with 16-byte loads, then takes tokens one at a time: the
+// token's input goes to an LDS buffer, every step reads one buffer and scatters into the other
+// through its tables - the same tables the one-launch-per-step kernels use - and the last step
+// stores to memory. Plain fp32 FMA, 256 threads over the R*C outputs of a step (consecutive threads
+// take consecutive columns, so the input value is an LDS broadcast and the tensor rows of a wave are
+// 4 banks apart). Intermediates are rounded to the storage type between steps, as on the other
+// paths. For layers this small the cost is launch latency, and this is one launch instead of one
+// per step.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSmallChainMaxSteps = 8;
+struct SmallChainStep {
+    const void* B;                         // packed tensor (fragment-major); read by the image kernel only
+    const int32_t *arow, *acol;            // gather tables of the step's input (null: plain); image kernel only
+    const int32_t *crow, *ccol;            // scatter tables of its output; image kernel only
+    int32_t R, K, C, nks;                  // nks = Kp / 16 of the packing
+    int32_t b_off;                         // offset of the tensor in the image, in 4-byte words (a multiple of 4)
+    int32_t ldb;                           // its row length: K + 4 when K % 4 == 0 (16-byte reads), else K + 1
+    int32_t t_off;                         // offset of the tables in the image: crow[R], ccol[C], then arow[R],
+                                           // acol[K] when the input is gathered
+    int32_t gathered;
+};
+struct SmallChainArgs {
+    const void* X;
+    void* Y;
+    const float* image;                    // tensors and tables of all steps, image_words long (a multiple of 4)
+    int64_t N, M;
+    int32_t tokens, nsteps, image_words;
+    int32_t buf_off[2];                    // offsets of the two per-token buffers in LDS, in words
+    SmallChainStep st[kSmallChainMaxSteps];
+};
+
+template <typename T>
+__global__ void __launch_bounds__(256) small_chain_image_kernel(SmallChainArgs a, float* image) {
+    int32_t* imagei = reinterpret_cast<int32_t*>(image);
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < a.image_words; i += gridDim.x * 256) image[i] = 0.f;
+    __syncthreads();                       // single workgroup launch: zero fill before the pieces
+    for (int s = 0; s < a.nsteps; ++s) {
+        const SmallChainStep& st = a.st[s];
+        const T* B = static_cast<const T*>(st.B);
+        for (int i = threadIdx.x; i < st.C * st.K; i += 256) {
+            int c = i / st.K, k = i - c * st.K;
+            image[st.b_off + c * st.ldb + k] = to_float(B[bfrag_offset(c, k, st.nks)]);
+        }
+        int32_t* tab = imagei + st.t_off;
+        for (int i = threadIdx.x; i < st.R; i += 256) tab[i] = st.crow[i];
+        for (int i = threadIdx.x; i < st.C; i += 256) tab[st.R + i] = st.ccol[i];
+        if (st.gathered) {
+            for (int i = threadIdx.x; i < st.R; i += 256) tab[st.R + st.C + i] = st.arow[i];
+            for (int i = threadIdx.x; i < st.K; i += 256) tab[2 * st.R + st.C + i] = st.acol[i];
+        }
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) small_chain_kernel(SmallChainArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    float* lds = reinterpret_cast<float*>(dyn_smem);
+    const int32_t* ldsi = reinterpret_cast<const int32_t*>(dyn_smem);
+    const int tid = threadIdx.x;
+    {
+        const floatx4* src = reinterpret_cast<const floatx4*>(a.image);
+        floatx4* dst = reinterpret_cast<floatx4*>(lds);
+#pragma unroll 4
+        for (int i = tid; i < (a.image_words >> 2); i += 256) dst[i] = src[i];
+    }
+    const T* X = static_cast<const T*>(a.X);
+    T* Y = static_cast<T*>(a.Y);
+    for (int t = blockIdx.x; t < a.tokens; t += gridDim.x) {
+        __syncthreads();                   // image loaded / previous token's buffers no longer read
+        float* in = lds + a.buf_off[0];
+        float* out = lds + a.buf_off[1];
+        for (int i = tid; i < int(a.N); i += 256) in[i] = to_float(X[int64_t(t) * a.N + i]);
+        __syncthreads();
+        for (int s = 0; s < a.nsteps; ++s) {
+            const SmallChainStep& st = a.st[s];
+            const float* Bs = lds + st.b_off;
+            const int32_t* t_crow = ldsi + st.t_off;
+            const int32_t* t_ccol = t_crow + st.R;
+            const int32_t* t_arow = t_ccol + st.C;
+            const int32_t* t_acol = t_arow + st.R;
+            const bool last = s + 1 == a.nsteps;
+            for (int i = tid; i < st.R * st.C; i += 256) {
+                int r = i / st.C, c = i - r * st.C;
+                const float* brow = Bs + c * st.ldb;
+                float acc = 0.f;
+                if (st.gathered) {
+                    const int base = t_arow[r];
+                    for (int k = 0; k < st.K; ++k) acc = fmaf(in[base + t_acol[k]], brow[k], acc);
+                } else if ((st.K & 3) == 0) {
+                    // 16-byte LDS reads, several in flight
+                    const floatx4* a4 = reinterpret_cast<const floatx4*>(in + r * st.K);
+                    const floatx4* b4 = reinterpret_cast<const floatx4*>(brow);
+                    float acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+#pragma unroll 4
+                    for (int k = 0; k < (st.K >> 2); ++k) {
+                        floatx4 av = a4[k], bv = b4[k];
+                        acc = fmaf(av[0], bv[0], acc);
+                        acc1 = fmaf(av[1], bv[1], acc1);
+                        acc2 = fmaf(av[2], bv[2], acc2);
+                        acc3 = fmaf(av[3], bv[3], acc3);
+                    }
+                    acc = (acc + acc1) + (acc2 + acc3);
+                } else {
+                    const float* arow = in + r * st.K;
+                    for (int k = 0; k < st.K; ++k) acc = fmaf(arow[k], brow[k], acc);
+                }
+                const int o = t_crow[r] + t_ccol[c];
+                if (last) Y[int64_t(t) * a.M + o] = from_float<T>(acc);
+                else out[o] = to_float(from_float<T>(acc));
+            }
+            __syncthreads();
+            float* tmp = in;
+            in = out;
+            out = tmp;
+        }
+    }
+}

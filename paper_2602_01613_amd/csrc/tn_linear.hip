@@ -76,6 +76,14 @@ struct tn_linear_s {
     int device = 0;
     int num_cus = 256;
     bool profiling = false;
+    // whole chain in one launch with everything in LDS (small layers)
+    bool small_chain = false;
+    size_t small_chain_smem = 0;
+    int small_chain_b_off[kSmallChainMaxSteps] = {};
+    int small_chain_t_off[kSmallChainMaxSteps] = {};
+    void* small_chain_image = nullptr;    // tensors (fp32, padded rows) and tables of all steps, as they sit in LDS
+    int small_chain_image_words = 0;
+    int small_chain_buf_off[2] = {0, 0};
     // chained pair kernel (two-step plans of the train shape): second packed tensor in its layout
     bool pair = false;
     void* pair_b1f = nullptr;
@@ -107,6 +115,7 @@ void free_handle(tn_linear_s* h) {
         if (s.chain_bbf) (void)hipFree(s.chain_bbf);
     }
     if (h->pair_b1f) (void)hipFree(h->pair_b1f);
+    if (h->small_chain_image) (void)hipFree(h->small_chain_image);
     if (h->owns_workspace) {
         for (void* w : h->ws)
             if (w) (void)hipFree(w);
@@ -408,6 +417,94 @@ int launch_fused2(const DevStep& s1, const DevStep& s2, const void* A, void* Out
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
+// Small layers: all steps in one launch when the packed tensors (as fp32, rows padded by one) and two
+// per-token buffers fit in 96 KB of LDS. Used for fp32 layers at any token count (their other path is
+// the plain FMA kernel, one launch per step) and for bf16 layers up to 32 tokens.
+constexpr size_t kSmallChainMaxSmem = 96 * 1024;
+constexpr int64_t kSmallChainMaxBf16Tokens = 32;
+
+void fill_small_chain_args(const tn_linear_s* h, SmallChainArgs* a) {
+    a->image = static_cast<const float*>(h->small_chain_image);
+    a->N = h->plan.N;
+    a->M = h->plan.M;
+    a->nsteps = int32_t(h->steps.size());
+    a->image_words = h->small_chain_image_words;
+    a->buf_off[0] = h->small_chain_buf_off[0];
+    a->buf_off[1] = h->small_chain_buf_off[1];
+    for (size_t s = 0; s < h->steps.size(); ++s) {
+        const DevStep& d = h->steps[s];
+        SmallChainStep& o = a->st[s];
+        o.B = d.packed;
+        o.arow = d.arow;
+        o.acol = d.acol;
+        o.crow = d.crow;
+        o.ccol = d.ccol;
+        o.R = int32_t(d.plan.R);
+        o.K = int32_t(d.plan.K);
+        o.C = int32_t(d.plan.C);
+        o.nks = d.Kp >> 4;
+        o.b_off = h->small_chain_b_off[s];
+        o.ldb = (o.K & 3) ? o.K + 1 : o.K + 4;
+        o.t_off = h->small_chain_t_off[s];
+        o.gathered = d.plan.a_plain ? 0 : 1;
+    }
+}
+
+int plan_small_chain(tn_linear_s* h, hipStream_t st) {
+    if (h->flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_SMALL_CHAIN)) return TN_OK;
+    const size_t ns = h->steps.size();
+    if (ns == 0 || ns > size_t(kSmallChainMaxSteps)) return TN_OK;
+    int64_t off = 0;
+    for (size_t s = 0; s < ns; ++s) {
+        const tn::Step& p = h->steps[s].plan;
+        if (p.R * p.C > (int64_t(1) << 20)) return TN_OK;
+        h->small_chain_b_off[s] = int(off);
+        off += (p.C * ((p.K & 3) ? p.K + 1 : p.K + 4) + 3) & ~int64_t(3);      // every tensor starts 16-byte aligned
+        if (off > int64_t(kSmallChainMaxSmem / 4)) return TN_OK;
+    }
+    for (size_t s = 0; s < ns; ++s) {              // the offset tables
+        const tn::Step& p = h->steps[s].plan;
+        h->small_chain_t_off[s] = int(off);
+        off += p.R + p.C + (p.a_plain ? 0 : p.R + p.K);
+        if (off > int64_t(kSmallChainMaxSmem / 4)) return TN_OK;
+    }
+    off = (off + 3) & ~int64_t(3);
+    const int64_t image_words = off;
+    const int64_t buf = (std::max(h->plan.N, h->plan.max_intermediate) + 3) & ~int64_t(3);
+    if ((off + 2 * buf) * 4 > int64_t(kSmallChainMaxSmem)) return TN_OK;
+    h->small_chain_buf_off[0] = int(off);
+    h->small_chain_buf_off[1] = int(off + buf);
+    h->small_chain_smem = size_t(off + 2 * buf) * 4;
+    h->small_chain_image_words = int(image_words);
+    if (hipMalloc(&h->small_chain_image, size_t(image_words) * 4) != hipSuccess) return TN_ERR_ALLOC;
+    h->packed_bytes += image_words * 4;
+    SmallChainArgs a;
+    memset(&a, 0, sizeof(a));
+    fill_small_chain_args(h, &a);
+    if (h->elt == 2)
+        hipLaunchKernelGGL(small_chain_image_kernel<bf16_t>, dim3(1), dim3(256), 0, st, a, static_cast<float*>(h->small_chain_image));
+    else
+        hipLaunchKernelGGL(small_chain_image_kernel<float>, dim3(1), dim3(256), 0, st, a, static_cast<float*>(h->small_chain_image));
+    if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    h->small_chain = true;
+    return TN_OK;
+}
+
+int launch_small_chain(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+    SmallChainArgs a;
+    memset(&a, 0, sizeof(a));
+    fill_small_chain_args(h, &a);
+    a.X = x;
+    a.Y = y;
+    a.tokens = int32_t(tokens);
+    dim3 grid(uint32_t(std::min<int64_t>(tokens, int64_t(h->num_cus) * 2)));
+    if (h->elt == 2)
+        hipLaunchKernelGGL(small_chain_kernel<bf16_t>, grid, dim3(256), h->small_chain_smem, st, a);
+    else
+        hipLaunchKernelGGL(small_chain_kernel<float>, grid, dim3(256), h->small_chain_smem, st, a);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
 // Token count from which the chained pair kernel replaces the two separate launches (below it a
 // launch has too few workgroups: 8 per 32 tokens).
 constexpr int64_t kPairMinTokens = 256;
@@ -544,7 +641,11 @@ int configure_kernels(int device) {
          hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<1>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
          hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess))
+                             hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
+         hipFuncSetAttribute(reinterpret_cast<const void*>(small_chain_kernel<float>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, int(kSmallChainMaxSmem)) != hipSuccess ||
+         hipFuncSetAttribute(reinterpret_cast<const void*>(small_chain_kernel<bf16_t>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, int(kSmallChainMaxSmem)) != hipSuccess))
         rc = TN_ERR_HIP;
     if (rc == TN_OK && device >= 0 && device < 64) done[device] = true;
     return rc;
@@ -856,7 +957,8 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         release_temps();
     }
     plan_fusion(h);
-    rc = prepare_pair(h, st);
+    rc = plan_small_chain(h, st);
+    if (rc == TN_OK) rc = prepare_pair(h, st);
     if (rc == TN_OK) rc = plan_chain2(h, st);
     if (rc != TN_OK) {
         (void)hipStreamSynchronize(st);
@@ -945,6 +1047,26 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
     const char* xb = static_cast<const char*>(x);
     char* yb = static_cast<char*>(y);
     size_t ns = h->steps.size();
+    if (h->small_chain && (h->elt == 4 || tokens <= kSmallChainMaxBf16Tokens)) {
+        // every step in one launch, tensors and intermediates in LDS
+        const int64_t pass = int64_t(1) << 24;
+        for (int64_t t0 = 0; t0 < tokens; t0 += pass) {
+            int64_t nt = std::min(pass, tokens - t0);
+            tn_linear_s::ProfRec rec{0, nullptr, nullptr};
+            if (h->profiling) {
+                if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess)
+                    return TN_ERR_HIP;
+                (void)hipEventRecord(rec.start, st);
+            }
+            int rc = launch_small_chain(h, xb + t0 * h->plan.N * h->elt, yb + t0 * h->plan.M * h->elt, nt, st);
+            if (h->profiling) {
+                (void)hipEventRecord(rec.stop, st);
+                h->prof.push_back(rec);
+            }
+            if (rc != TN_OK) return rc;
+        }
+        return TN_OK;
+    }
     if (h->pair && tokens >= h->pair_min_tokens) {
         // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
         const int64_t pass = int64_t(1) << 24;
@@ -1039,6 +1161,7 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
         int s = (what - TN_QUERY_STEP_BASE) / 10;
         if (s >= int(h->steps.size())) return TN_ERR_INVALID_ARG;
         *value = h->steps[size_t(s)].fuse_next ? 1 : ((h->pair && s == 0) ? 2 : 0);
+        if (h->small_chain && size_t(s) + 1 < h->steps.size()) *value = 3;
         return TN_OK;
     }
     return plan_value(h->plan, what, value);

@@ -471,3 +471,39 @@ def test_forward_under_stream_capture(i, dense_w):
         assert O.rel_max_err(to_host(y_graph), O.apply_linear(w, wl.make_x(spec, tokens, i))) <= TOL["bf16"]
         del graph
         layer.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_layers_in_one_launch(case, dtype):
+    """Layers whose tensors and intermediates fit in LDS run all their steps as one launch (fp32 at any
+    token count, bf16 up to 32 tokens): against the oracle and against one launch per step."""
+    fmt, om, im, rk = SMALL[case]
+    spec = _spec(fmt, dtype, om, im, rk)
+    ts = _rand_layer(spec, 1300 + case)
+    for tokens in (1, 17, 32, 700):
+        x = wl.round_to_dtype(np.random.default_rng(case * 3 + tokens).standard_normal((tokens, spec.N)), dtype)
+        ref = O.forward(fmt, ts, x, n_out_modes=len(om))
+        layer = make_layer(spec, ts, tokens)
+        n_steps = layer.query(tn.TN_QUERY_NUM_STEPS)
+        one_launch = n_steps > 1 and layer.query(tn.TN_QUERY_STEP_BASE + 6) == 3
+        y = to_host(layer(to_dev(x, dtype)))
+        layer.close()
+        y_steps = run_layer(spec, ts, x, flags=tn.TN_FLAG_NO_SMALL_CHAIN)
+        assert O.rel_max_err(y, ref) <= TOL[dtype], (case, tokens, one_launch)
+        assert O.rel_max_err(y_steps, ref) <= TOL[dtype], (case, tokens)
+    if case in (1, 5):       # the two MFMA-sized trains do not fit
+        assert not one_launch
+    if case == 2:            # the small fp32 train of the baseline configs
+        assert one_launch
+
+
+def test_config0_one_launch():
+    spec, toks = wl.baseline_spec(0)
+    ts = wl.make_tensors(spec, 0)
+    layer = make_layer(spec, ts, toks[0])
+    assert [layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + 6) for s in range(3)] == [3, 3, 0]
+    x = wl.make_x(spec, toks[0], 0)
+    y = to_host(layer(to_dev(x, "f32")))
+    layer.close()
+    assert O.rel_max_err(y, O.forward(spec.format, ts, x)) <= 1e-5
