@@ -50,14 +50,11 @@ extern "C" {
 #define TN_DTYPE_F32   0    /* fp32 storage, fp32 FMA arithmetic, fp32 intermediates */
 #define TN_DTYPE_BF16  1    /* bf16 storage, bf16 MFMA with fp32 accumulate, bf16 intermediates */
 
-/* desc.flags */
+/* desc.flags (bit 3 is unused) */
 #define TN_FLAG_SCALAR_KERNELS  1   /* run every contraction step on the plain FMA kernel (debug aid) */
 #define TN_FLAG_NO_MERGE        2   /* keep every parameter tensor separate: do not contract adjacent
                                        tensors into one at create time even where that is free */
 #define TN_FLAG_NO_SPLIT_K      4   /* never use the split-K kernel for small launches (tuning/debug aid) */
-#define TN_FLAG_FUSE_SMALL_STEPS 8  /* run pairs of small adjacent steps (e.g. Tucker factor products) as one
-                                       launch with the intermediate in LDS; off by default: saves HBM traffic
-                                       but measured slower than two launches on MI355X */
 #define TN_FLAG_MERGE_GROW     16   /* trade memory for speed: also contract parameter tensors at create time
                                        when that ADDS parameters, as long as the layer stays under a quarter
                                        of the dense matrix (e.g. a ring of 4 cores becomes two half-rings) */

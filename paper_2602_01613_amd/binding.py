@@ -20,7 +20,6 @@ TN_DTYPE_F32, TN_DTYPE_BF16 = 0, 1
 TN_FLAG_SCALAR_KERNELS = 1
 TN_FLAG_NO_MERGE = 2
 TN_FLAG_NO_SPLIT_K = 4
-TN_FLAG_FUSE_SMALL_STEPS = 8
 TN_FLAG_MERGE_GROW = 16
 TN_FLAG_NO_PAIR_CHAIN = 32
 TN_FLAG_NO_CHAIN2 = 64

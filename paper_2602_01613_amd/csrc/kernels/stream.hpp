@@ -1,4 +1,4 @@
-// Store-bound and decode-size step kernels: short-K, split-K with its reduction, and the opt-in LDS-fused pair of small steps.
+// Store-bound and decode-size step kernels: short-K, split-K with its reduction, and the whole-chain kernel for small layers.
 // Part of the tn_linear library's single translation unit: included by tn_linear.hip inside its
 // anonymous namespace, after <hip/hip_runtime.h> and tn_plan.hpp.
 #pragma once
@@ -286,191 +286,6 @@ __global__ void __launch_bounds__(256) step_split_reduce_kernel(StepArgs a, cons
         Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
     }
 }
-
-// ---------------------------------------------------------------------------------------------
-// Fused pair of small steps (e.g. the two out-factor or the two in-factor products of a Tucker
-// layer): when one token's input of the first step and its intermediate fit in LDS, a workgroup
-// takes tokens one at a time, stages the token's [R1, K1] input in LDS, runs step 1 with MFMA into
-// an LDS copy of the intermediate (written through step 1's scatter tables, i.e. already in the
-// layout step 2 reads), runs step 2 from LDS and stores its result through step 2's tables. Each
-// wave owns up to two 32-column tiles of either packed tensor and keeps their fragment blocks in
-// registers for all the tokens of the workgroup (K <= 96, C <= 256); the next token's input is
-// prefetched into registers while the current one is computed. The intermediate never touches HBM and one launch
-// replaces two. Needs K1 % 16 == 0 and K2 % 16 == 0 (no padded k-steps are ever read).
-// CM2 = 1: step 2's columns come in aligned runs of 8 -> 16-byte stores via a per-wave LDS patch;
-// CM2 = 0: scalar stores.
-// ---------------------------------------------------------------------------------------------
-struct Fused2Args {
-    StepArgs s1, s2;
-    int32_t tokens;
-    int32_t in_elems;     // LDS elements reserved for the staged input: roundup(R1, 32) * (K1 + 8)
-    int32_t mid_elems;    // LDS elements reserved for the intermediate: roundup(R2, 32) * K2
-};
-
-template <int CM2>
-__global__ void __launch_bounds__(256, 2) step_fused2_kernel(Fused2Args f) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-    const StepArgs& a1 = f.s1;
-    const StepArgs& a2 = f.s2;
-    const int R1 = int(a1.R), K1 = a1.K, C1 = a1.C, R2 = int(a2.R), K2 = a2.K, C2 = a2.C;
-    const int LD1 = K1 + 8;
-    bf16_t* sIn = reinterpret_cast<bf16_t*>(dyn_smem);
-    bf16_t* sMid = sIn + f.in_elems;
-    bf16_t* sPatch = sMid + f.mid_elems;                       // 4 waves x 32 x 40
-    int32_t* sTab = reinterpret_cast<int32_t*>(sPatch + 4 * 32 * 40);
-    int32_t* t_crow1 = sTab;
-    int32_t* t_ccol1 = t_crow1 + R1;
-    int32_t* t_crow2 = t_ccol1 + C1;
-    int32_t* t_ccol2 = t_crow2 + R2;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < R1; i += 256) t_crow1[i] = a1.crow[i];
-    for (int i = tid; i < C1; i += 256) t_ccol1[i] = a1.ccol[i];
-    for (int i = tid; i < R2; i += 256) t_crow2[i] = a2.crow[i];
-    for (int i = tid; i < C2; i += 256) t_ccol2[i] = a2.ccol[i];
-    // rows past R1 / R2 of the last row tile are read by the MFMAs (their results are dropped):
-    // give them defined contents once
-    for (int i = tid; i < f.in_elems; i += 256) sIn[i] = bf16_t(0.f);
-    for (int i = tid; i < f.mid_elems; i += 256) sMid[i] = bf16_t(0.f);
-    __syncthreads();
-
-    const bf16_t* A = static_cast<const bf16_t*>(a1.A);
-    const bf16_t* B1 = static_cast<const bf16_t*>(a1.B);
-    const bf16_t* B2 = static_cast<const bf16_t*>(a2.B);
-    bf16_t* Out = static_cast<bf16_t*>(a2.Out);
-    const int nks1 = K1 >> 4, nks2 = K2 >> 4;                  // real k-steps (<= 6)
-    const int bks1 = a1.Kp >> 4, bks2 = a2.Kp >> 4;            // k-steps per column block in the packed tensors
-    const int nrt1 = (R1 + 31) >> 5, nct1 = (C1 + 31) >> 5;
-    const int nrt2 = (R2 + 31) >> 5, nct2 = (C2 + 31) >> 5;     // nct <= 8: column tiles j = wave, wave + 4
-    const int chunks_per_row = K1 >> 3;
-    bf16_t* myPatch = sPatch + wave * 32 * 40;
-
-    // the wave's column tiles of both packed tensors stay in registers for all of its tokens
-    bf16x8 bw1[2][6], bw2[2][6];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int ks = 0; ks < 6; ++ks) {
-            bf16x8 z;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) z[q] = bf16_t(0.f);
-            int j = wave + 4 * jj;
-            bw1[jj][ks] = (j < nct1 && ks < nks1)
-                              ? *reinterpret_cast<const bf16x8*>(B1 + (int64_t(j) * bks1 + ks) * 512 + lane * 8) : z;
-            bw2[jj][ks] = (j < nct2 && ks < nks2)
-                              ? *reinterpret_cast<const bf16x8*>(B2 + (int64_t(j) * bks2 + ks) * 512 + lane * 8) : z;
-        }
-
-    // the next token's input is fetched into registers while the current token is computed
-    // (at most 6 chunks of 16 bytes per thread: R1 * K1 <= 12288)
-    const int n_chunks = R1 * chunks_per_row;
-    int my_off[6];                                             // LDS element offset of each of my chunks
-#pragma unroll
-    for (int q = 0; q < 6; ++q) {
-        int e = tid + 256 * q;
-        int r = e / chunks_per_row;
-        my_off[q] = e < n_chunks ? r * LD1 + (e - r * chunks_per_row) * 8 : -1;
-    }
-    bf16x8 pre[6];
-    auto fetch_in = [&](int t) {
-        const bf16_t* in = A + int64_t(t) * a1.a_tok_stride + tid * 8;
-#pragma unroll
-        for (int q = 0; q < 6; ++q)
-            if (my_off[q] >= 0) pre[q] = *reinterpret_cast<const bf16x8*>(in + 2048 * q);
-    };
-    if (int(blockIdx.x) < f.tokens) fetch_in(blockIdx.x);
-    for (int t = blockIdx.x; t < f.tokens; t += gridDim.x) {
-        // ---- stage the token's input
-#pragma unroll
-        for (int q = 0; q < 6; ++q)
-            if (my_off[q] >= 0) *reinterpret_cast<bf16x8*>(sIn + my_off[q]) = pre[q];
-        __syncthreads();
-        if (t + int(gridDim.x) < f.tokens) fetch_in(t + gridDim.x);
-        // ---- step 1
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int j = wave + 4 * jj;
-            if (j >= nct1) continue;
-            for (int i = 0; i < nrt1; ++i) {
-                floatx16 acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-                const bf16_t* ap = sIn + (i * 32 + (lane & 31)) * LD1 + 8 * (lane >> 5);
-                bf16x8 af[6];                 // all fragment reads first, then the MFMA chain
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks1) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw1[jj][ks], af[ks], acc, 0, 0, 0);
-                // lane l, register v: row l%32, column 8*(v/4) + 4*(l/32) + v%4
-                int r = i * 32 + (lane & 31);
-                if (r < R1) {
-                    int rbase = t_crow1[r];
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                        if (c < C1) sMid[rbase + t_ccol1[c]] = bf16_t(acc[v]);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        // ---- step 2 from the LDS intermediate
-        bf16_t* out_t = Out + int64_t(t) * a2.c_tok_stride;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int j = wave + 4 * jj;
-            if (j >= nct2) continue;
-            for (int i = 0; i < nrt2; ++i) {
-                floatx16 acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-                const bf16_t* ap = sMid + (i * 32 + (lane & 31)) * K2 + 8 * (lane >> 5);
-                bf16x8 af[6];
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks2) af[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 16);
-#pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
-                    if (ks < nks2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw2[jj][ks], af[ks], acc, 0, 0, 0);
-                if (CM2 == 1) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        bf16x4 pk;
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[4 * q + u]);
-                        *reinterpret_cast<bf16x4*>(myPatch + (lane & 31) * 40 + 8 * q + 4 * (lane >> 5)) = pk;
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    int c = j * 32 + (lane & 3) * 8;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        int rr = h * 16 + (lane >> 2);
-                        int r = i * 32 + rr;
-                        bf16x8 v = *reinterpret_cast<const bf16x8*>(myPatch + rr * 40 + (lane & 3) * 8);
-                        if (r < R2 && c < C2) *reinterpret_cast<bf16x8*>(out_t + t_crow2[r] + t_ccol2[c]) = v;
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                } else {
-                    int r = i * 32 + (lane & 31);
-                    if (r < R2) {
-                        int rbase = t_crow2[r];
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            int c = j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                            if (c < C2) out_t[rbase + t_ccol2[c]] = bf16_t(acc[v]);
-                        }
-                    }
-                }
-            }
-        }
-        __syncthreads();   // sIn and sMid are rewritten for the next token
-    }
-}
-
 
 // ---------------------------------------------------------------------------------------------
 // Whole-chain kernel for small layers: when every packed tensor of the plan and two copies of the

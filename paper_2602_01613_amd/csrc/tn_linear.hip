@@ -52,12 +52,9 @@ struct DevStep {
     int amode = 0, cmode = 0;
     int bn = 64, bm = 64;
     bool fuse_next = false;       // this step and the next run as one launch
-    int fuse_kind = 0;            // 1 step_fused2_kernel (opt-in), 2 step_chain2_kernel
     void* chain_bbf = nullptr;    // chain2: the next step's packed tensor in the chained layout
     int chain_cfg = 0;            // chain2 instantiation: 0 <3,6,5>, 1 <2,8,2>
     int chain_run_c1 = 0;         // chain2: output pieces run along c1 (else along c2)
-    int fused_in_elems = 0, fused_mid_elems = 0;
-    size_t fused_smem = 0;
 };
 
 }  // namespace
@@ -355,68 +352,6 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
-// Can steps s and s+1 run as one fused launch? (small per-token tensors, k-steps without padding)
-void plan_fusion(tn_linear_s* h) {
-    // opt-in: measured slower than the two separate launches on MI355X (the per-token work is a
-    // chain of small dependent LDS reads and MFMAs that 8 waves per CU cannot overlap)
-    if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & TN_FLAG_SCALAR_KERNELS) || !(h->flags & TN_FLAG_FUSE_SMALL_STEPS)) return;
-    for (size_t s = 0; s + 1 < h->steps.size(); ++s) {
-        DevStep& a = h->steps[s];
-        DevStep& b = h->steps[s + 1];
-        if (s > 0 && h->steps[s - 1].fuse_next) continue;
-        const tn::Step& p1 = a.plan;
-        const tn::Step& p2 = b.plan;
-        if (!p1.a_plain || !p2.a_plain || p1.K % 16 || p2.K % 16) continue;
-        if (p1.K > 96 || p2.K > 96 || p1.C > 256 || p2.C > 256) continue;      // register-resident packed tensors
-        if (p1.R * p1.K > 12288) continue;                                      // register-prefetched input
-        if (p1.c_tok_stride != p2.R * p2.K) continue;
-        int64_t in_elems = int64_t((p1.R + 31) / 32 * 32) * (p1.K + 8);
-        int64_t mid_elems = int64_t((p2.R + 31) / 32 * 32) * p2.K;
-        int64_t tab = p1.R + p1.C + p2.R + p2.C;
-        int64_t smem = (in_elems + mid_elems + 4 * 32 * 40) * 2 + tab * 4 + 64;
-        if (smem > 72 * 1024) continue;
-        if (int64_t(a.Cp) * a.Kp > 65536 || int64_t(b.Cp) * b.Kp > 65536) continue;
-        a.fuse_next = true;
-        a.fuse_kind = 1;
-        a.fused_in_elems = int(in_elems);
-        a.fused_mid_elems = int((mid_elems + 7) / 8 * 8);
-        a.fused_smem = size_t((a.fused_in_elems + a.fused_mid_elems + 4 * 32 * 40) * 2 + tab * 4 + 64);
-    }
-}
-
-void fill_args(const DevStep& s, const void* A, void* Out, int64_t tokens, StepArgs* a) {
-    a->A = A;
-    a->B = s.packed;
-    a->Out = Out;
-    a->arow = s.arow;
-    a->acol = s.acol;
-    a->crow = s.crow;
-    a->ccol = s.ccol;
-    a->a_tok_stride = s.plan.a_tok_stride;
-    a->c_tok_stride = s.plan.c_tok_stride;
-    a->total_rows = uint32_t(tokens * s.plan.R);
-    a->R = uint32_t(s.plan.R);
-    a->K = int32_t(s.plan.K);
-    a->Kp = s.Kp;
-    a->C = int32_t(s.plan.C);
-    a->Cp = s.Cp;
-}
-
-int launch_fused2(const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens, hipStream_t st) {
-    Fused2Args f;
-    fill_args(s1, A, nullptr, tokens, &f.s1);
-    fill_args(s2, nullptr, Out, tokens, &f.s2);
-    f.tokens = int32_t(tokens);
-    f.in_elems = s1.fused_in_elems;
-    f.mid_elems = s1.fused_mid_elems;
-    dim3 grid(uint32_t(std::min<int64_t>(tokens, 1024)));
-    if (s2.cmode == 1)
-        hipLaunchKernelGGL(step_fused2_kernel<1>, grid, dim3(256), s1.fused_smem, st, f);
-    else
-        hipLaunchKernelGGL(step_fused2_kernel<0>, grid, dim3(256), s1.fused_smem, st, f);
-    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
-}
-
 // Small layers: all steps in one launch when the packed tensors (as fp32, rows padded by one) and two
 // per-token buffers fit in 96 KB of LDS. Used for fp32 layers at any token count (their other path is
 // the plain FMA kernel, one launch per step) and for bf16 layers up to 32 tokens.
@@ -556,7 +491,7 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
 // with K = r), the output in aligned runs of 8 along c1 or along c2, and sizes within one of the
 // two instantiations.
 int plan_chain2(tn_linear_s* h, hipStream_t st) {
-    if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_CHAIN2 | TN_FLAG_FUSE_SMALL_STEPS)) ||
+    if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_CHAIN2)) ||
         h->pair)
         return TN_OK;
     for (size_t i = 0; i + 1 < h->steps.size(); ++i) {
@@ -575,7 +510,6 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
                            b.Cp, b.Kp);
         if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
         a.fuse_next = true;
-        a.fuse_kind = 2;
         a.chain_cfg = cfg;
         a.chain_run_c1 = run_c1;
     }
@@ -636,11 +570,7 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = launch_dlds<4, 2, 2, 4, 4, 1>(none, a, 0, nullptr);
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK &&
-        (hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<0>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
-         hipFuncSetAttribute(reinterpret_cast<const void*>(step_fused2_kernel<1>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024) != hipSuccess ||
-         hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),
+        (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
          hipFuncSetAttribute(reinterpret_cast<const void*>(small_chain_kernel<float>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kSmallChainMaxSmem)) != hipSuccess ||
@@ -956,7 +886,6 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         }
         release_temps();
     }
-    plan_fusion(h);
     rc = plan_small_chain(h, st);
     if (rc == TN_OK) rc = prepare_pair(h, st);
     if (rc == TN_OK) rc = plan_chain2(h, st);
@@ -1100,9 +1029,8 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
                     return TN_ERR_HIP;
                 (void)hipEventRecord(rec.start, st);
             }
-            int rc = !fused ? launch_step(h, h->steps[s], A, Out, nt, st)
-                     : h->steps[s].fuse_kind == 2 ? launch_chain2(h, h->steps[s], h->steps[s + 1], A, Out, nt, st)
-                                                  : launch_fused2(h->steps[s], h->steps[s + 1], A, Out, nt, st);
+            int rc = fused ? launch_chain2(h, h->steps[s], h->steps[s + 1], A, Out, nt, st)
+                           : launch_step(h, h->steps[s], A, Out, nt, st);
             if (h->profiling) {
                 (void)hipEventRecord(rec.stop, st);
                 h->prof.push_back(rec);

@@ -265,31 +265,6 @@ def test_split_k_small_launches(tokens):
         assert np.array_equal(y, run_layer(spec, ts, x))
 
 
-@pytest.mark.parametrize("tokens", [1, 5, 70, 1500])
-def test_fused_small_steps(tokens):
-    """Opt-in: pairs of small adjacent steps (Tucker in-factors, out-factors) run as one fused
-    launch with the intermediate in LDS; checked against the oracle and against the default path."""
-    cases = [
-        _spec(tn.TN_FORMAT_TUCKER, "bf16", (32, 48), (32, 48), (16, 32, 16, 16)),
-        _spec(tn.TN_FORMAT_TUCKER, "bf16", (40, 24), (16, 80), (32, 16, 16, 32)),
-        _spec(tn.TN_FORMAT_TUCKER, "bf16", (160, 160), (64, 80), (96, 96, 48, 48)),
-        _spec(tn.TN_FORMAT_TT, "bf16", (4, 6, 4), (16, 2, 16), (1, 16, 16, 1)),
-    ]
-    for n, spec in enumerate(cases):
-        ts = wl.make_tensors(spec, 7, instance=n) if spec.format == tn.TN_FORMAT_TUCKER else _rand_layer(spec, 700 + n)
-        x = wl.round_to_dtype(np.random.default_rng(n + tokens).standard_normal((tokens, spec.N)), "bf16")
-        ref = O.forward(spec.format, ts, x, n_out_modes=len(spec.out_modes))
-        layer = make_layer(spec, ts, tokens, flags=tn.TN_FLAG_FUSE_SMALL_STEPS)
-        n_fused = sum(layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + 6) for s in range(layer.query(tn.TN_QUERY_NUM_STEPS)))
-        y = to_host(layer(to_dev(x, "bf16")))
-        layer.close()
-        if spec.format == tn.TN_FORMAT_TUCKER:
-            assert n_fused >= 1, n
-        y_unfused = run_layer(spec, ts, x)
-        assert O.rel_max_err(y, ref) <= TOL["bf16"], (n, tokens)
-        assert O.rel_max_err(y_unfused, ref) <= TOL["bf16"], (n, tokens)
-
-
 def test_shared_caller_workspace(dense_w):
     """Several handles keep their intermediates in one caller-owned block (run one after the
     other on one stream); results equal those of handles with their own workspace."""
