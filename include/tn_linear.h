@@ -73,7 +73,9 @@ extern "C" {
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
                                        bf16 steps (0 = library's choice): 3 = 128x256 and 8 = 256x128
                                        register-prefetch tiles, 9 = short-K store kernel, 12 = 256x256
-                                       direct-to-LDS ring; ignored where the variant cannot run the step */
+                                       direct-to-LDS ring; 20 = the Kronecker-sum kernel for every two-step
+                                       plan whose layout allows it, whatever its size (see
+                                       TN_QUERY_KRON_CHAINABLE); ignored where the variant cannot run the step */
 
 /* tn_linear_query / tn_linear_plan_query: what */
 #define TN_QUERY_PARAM_COUNT        0   /* number of parameters in the caller's tensors */
@@ -90,6 +92,10 @@ extern "C" {
                                            (a train whose end cores were merged into their neighbours): from
                                            256 tokens on, forward runs both steps as one launch that keeps the
                                            intermediate in registers */
+#define TN_QUERY_KRON_CHAINABLE   11   /* 0, or 1 + instantiation when the plan is two steps over a shared bond
+                                           that the Kronecker-sum kernel runs as one launch with the
+                                           intermediate in registers (e.g. a ring contracted into two half
+                                           rings under TN_FLAG_MERGE_GROW) */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=
@@ -99,7 +105,8 @@ extern "C" {
                                            6 1 if this step and the next run as one fused launch, 2 if they
                                              do so from 256 tokens on (chained pair kernel), 3 if the whole chain
                                              runs as one launch with its tensors in LDS (small layers: fp32 at any
-                                             token count, bf16 up to 32 tokens),
+                                             token count, bf16 up to 32 tokens), 4 if both steps run as one launch
+                                             of the Kronecker-sum kernel at every token count,
                                            7 shape test only (also from plan_query): 0, or 1 + the instantiation
                                              of the transposing chain kernel that could run this step with the
                                              next one (consecutive qualifying pairs overlap: create takes them

@@ -25,6 +25,7 @@ TN_FLAG_NO_PAIR_CHAIN = 32
 TN_FLAG_NO_CHAIN2 = 64
 TN_FLAG_TRANSPOSE = 128
 TN_FLAG_NO_SMALL_CHAIN = 1 << 20
+TN_FLAG_VARIANT_SHIFT = 8
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -36,6 +37,7 @@ TN_QUERY_OUT_FEATURES = 7
 TN_QUERY_IN_FEATURES = 8
 TN_QUERY_NUM_MERGES = 9
 TN_QUERY_PAIR_CHAINABLE = 10
+TN_QUERY_KRON_CHAINABLE = 11
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (

@@ -1,0 +1,268 @@
+// Kronecker-sum kernel: both steps of a two-tensor plan in one launch, per token, with the intermediate in
+// MFMA registers. Part of the tn_linear library's single translation unit: included by tn_linear.hip inside
+// its anonymous namespace, after kernels/tiled.hpp.
+#pragma once
+
+// ---------------------------------------------------------------------------------------------
+// A network of two parameter tensors that share a bond rho (a tensor ring whose cores were contracted
+// in pairs at create time into two half rings, a tensor train of two cores) is a sum over rho of
+// Kronecker products: with the token's input seen as a matrix X_t[k][a],
+//     Y_t[o1][o2] = sum_rho sum_a ( sum_k X_t[k][a] * B0[(o1, rho)][k] ) * B1[o2][(a, rho)]
+// As two launches the intermediate Z[t][o1][a][rho] (A*O1*P values per token, 21 MB for the ring
+// 25600 -> 5120 at rank 32) crosses HBM twice and both launches are bound by it (Section 3.5: the time
+// goes to memory locality, not to FLOPs). Here every term of the sum over rho is finished on chip:
+//   * a wave owns one token and a chunk of 64 values of o1; X_t sits in its registers as MFMA row
+//     operands (a along the rows, k contracted) for the whole launch;
+//   * per rho the workgroup (4 waves = 4 tokens) streams the two slices B0[(o1 chunk, rho)][:] and
+//     B1[:][(:, rho)] (tens of KB, stored contiguously per rho at create time by the repack kernels) into
+//     a ring of 3 LDS stages with direct-to-LDS loads;
+//   * D[a][o1] = X_t^T B0_rho^T lands in the accumulator layout (lane: o1 = l%32, a = 8*(v/4) + 4*(l/32)
+//     + v%4), which after rounding to bf16 IS the column operand of the second contraction
+//     Y^T[o2][o1] += B1_rho[o2][a] D[a][o1] when B1's slice is stored with the same permutation of a
+//     inside each k-step of 16.
+// The slices are the same for every token, so the workgroups of an XCD, which walk rho in step, read
+// them from that XCD's L2; HBM sees X once, Y once and the packed tensors once per XCD.
+// Few tokens: the range of rho is split over workgroups, each writes fp32 partial sums, and a second
+// small kernel adds them in a fixed order.
+// Template: AT tiles of 32 values of a, KS0 k-steps of 16 in the first contraction, O2T tiles of 32
+// values of o2; smaller shapes run on zero padding (the repacked slices hold zeros there).
+// ---------------------------------------------------------------------------------------------
+struct KronArgs {
+    const void* X;
+    void* Y;               // bf16 output, or fp32 partial sums [split][tokens][M] when n_splits > 1
+    const void* H0f;       // [o1 chunk][rho][o1 tile (2)][k-step (KS0)] blocks of 512
+    const void* H1f;       // [rho][o2 tile (O2T)][a k-step (2*AT)] blocks of 512
+    const int32_t* xrow;   // offset of a in a token of x (null: a*K0)
+    const int32_t* xcol;   // offset of k (null: k)
+    const int32_t* yrow;   // output offset of o1
+    const int32_t* ycol;   // output offset of o2
+    int64_t N, M;          // elements per token of X and Y
+    int32_t tokens, A, K0, O1, C1, P;
+    int32_t n_chunks;      // ceil(O1 / 64)
+    int32_t n_splits;      // workgroups sharing one (token quad, chunk): each takes rho_per_split values of rho
+    int32_t rho_per_split;
+    int32_t x_vec8;        // 8 consecutive k of one a are one aligned 16-byte piece of x
+};
+
+template <int AT, int KS0, int O2T>
+struct KronShape {
+    static constexpr int NB0 = 2 * KS0;                 // blocks of 1 KB per rho: first slice
+    static constexpr int NB1 = O2T * 2 * AT;            // second slice
+    static constexpr int L = (NB0 + NB1 + 3) / 4;       // direct-to-LDS loads per wave and stage
+    static constexpr int STAGE_BYTES = 4 * L * 1024;
+    static constexpr int NS = 3;
+    static constexpr size_t SMEM = size_t(NS) * STAGE_BYTES;
+};
+
+// H0f[((chunk*P + rho)*2*KS0 + o1t*KS0 + ks)*512 + l*8 + e] = B0[c = o1*P + rho][k = 16*ks + 8*(l/32) + e],
+// o1 = 64*chunk + 32*o1t + l%32; zero outside the tensor.
+__global__ void __launch_bounds__(256) kron_repack0_kernel(const bf16_t* src, bf16_t* dst, int n_chunks, int P, int KS0,
+                                                           int O1, int K0, int nks_src) {
+    const int64_t total = int64_t(n_chunks) * P * 2 * KS0 * 512;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
+        int e = int(i & 7), l = int(i >> 3) & 63;
+        int64_t blk = i >> 9;
+        int ks = int(blk % KS0);
+        blk /= KS0;
+        int o1t = int(blk & 1);
+        blk >>= 1;
+        int rho = int(blk % P);
+        int chunk = int(blk / P);
+        int o1 = 64 * chunk + 32 * o1t + (l & 31);
+        int k = 16 * ks + 8 * (l >> 5) + e;
+        dst[i] = (o1 < O1 && k < K0) ? src[bfrag_offset(o1 * P + rho, k, nks_src)] : bf16_t(0.f);
+    }
+}
+
+// H1f[((rho*O2T + j)*2*AT + 2*i + s)*512 + l*8 + e] = B1[c = 32*j + l%32][k = a*P + rho],
+// a = 32*i + 16*s + 8*(e/4) + 4*(l/32) + e%4; zero outside the tensor.
+__global__ void __launch_bounds__(256) kron_repack1_kernel(const bf16_t* src, bf16_t* dst, int P, int O2T, int AT, int C1,
+                                                           int A, int nks_src) {
+    const int64_t total = int64_t(P) * O2T * 2 * AT * 512;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
+        int e = int(i & 7), l = int(i >> 3) & 63;
+        int64_t blk = i >> 9;
+        int is = int(blk % (2 * AT));
+        blk /= 2 * AT;
+        int j = int(blk % O2T);
+        int rho = int(blk / O2T);
+        int c = 32 * j + (l & 31);
+        int a = 16 * is + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+        dst[i] = (c < C1 && a < A) ? src[bfrag_offset(c, a * P + rho, nks_src)] : bf16_t(0.f);
+    }
+}
+
+template <int AT, int KS0, int O2T>
+__global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
+    using S = KronShape<AT, KS0, O2T>;
+    constexpr int L = S::L, NS = S::NS, NB0 = S::NB0, NB1 = S::NB1, STAGE_BYTES = S::STAGE_BYTES;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+
+    const bf16_t* X = static_cast<const bf16_t*>(p.X);
+    const bf16_t* H0f = static_cast<const bf16_t*>(p.H0f);
+    const bf16_t* H1f = static_cast<const bf16_t*>(p.H1f);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // workgroup -> (token quad, chunk of o1, split of rho)
+    int id = blockIdx.x;
+    const int split = id % p.n_splits;
+    id /= p.n_splits;
+    const int chunk = id % p.n_chunks;
+    const int quad = id / p.n_chunks;
+    const int t = quad * 4 + wave;
+    const int tl = min(t, p.tokens - 1);                 // waves past the end repeat the last token and store nothing
+    const int rho_begin = split * p.rho_per_split;
+    const int rho_end = min(p.P, rho_begin + p.rho_per_split);
+    const int n_rho = rho_end - rho_begin;               // >= 1 by construction of the grid
+
+    // the token's input as row operands of the first contraction: tile i, k-step ks: lane l holds
+    // a = 32*i + l%32, k = 16*ks + 8*(l/32) .. +7
+    bf16x8 xa[AT][KS0];
+    {
+        const bf16_t* xt = X + int64_t(tl) * p.N;
+#pragma unroll
+        for (int i = 0; i < AT; ++i) {
+            const int a = 32 * i + (lane & 31);
+            const int ro = a < p.A ? (p.xrow ? p.xrow[a] : a * p.K0) : -1;
+#pragma unroll
+            for (int ks = 0; ks < KS0; ++ks) {
+                const int k = 16 * ks + 8 * (lane >> 5);
+                bf16x8 v;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = bf16_t(0.f);
+                if (ro >= 0 && k < p.K0) {
+                    if (p.x_vec8) {
+                        v = *reinterpret_cast<const bf16x8*>(xt + ro + (p.xcol ? p.xcol[k] : k));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = xt[ro + p.xcol[k + e]];
+                    }
+                }
+                xa[i][ks] = v;
+            }
+        }
+    }
+
+    // direct-to-LDS: wave w brings blocks w, w+4, ... of a stage (L each; blocks past the two slices repeat the
+    // last one into the stage's padding so that every wave has the same number of loads in flight)
+    const bf16_t* h0_src = H0f + (int64_t(chunk) * p.P) * (NB0 * 512) + lane * 8;
+    const bf16_t* h1_src = H1f + lane * 8;
+    auto issue = [&](int rho, int stage) {
+        unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
+#pragma unroll
+        for (int q = 0; q < L; ++q) {
+            const int b = wave + 4 * q;                  // wave-uniform
+            const int bs = min(b, NB0 + NB1 - 1);
+            const bf16_t* src = bs < NB0 ? h0_src + (int64_t(rho) * NB0 + bs) * 512
+                                         : h1_src + (int64_t(rho) * NB1 + (bs - NB0)) * 512;
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                             (void __attribute__((address_space(3)))*)(sbase + b * 1024), 16, 0, 0);
+        }
+    };
+
+    floatx16 acc[O2T][2];
+#pragma unroll
+    for (int j = 0; j < O2T; ++j)
+#pragma unroll
+        for (int o = 0; o < 2; ++o)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][o][v] = 0.f;
+
+    issue(rho_begin, 0);
+    if (n_rho > 1) issue(rho_begin + 1, 1);
+    for (int r = 0; r < n_rho; ++r) {
+        if (r + 1 < n_rho) wait_vmcnt<L>();              // stage r has landed (r+1 may be in flight)
+        else wait_vmcnt<0>();
+        __syncthreads();                                 // ... for every wave, and stage r-1 is free
+        if (r + 2 < n_rho) issue(rho_begin + r + 2, (r + 2) % NS);
+        const unsigned char* sb = dyn_smem + (r % NS) * STAGE_BYTES + lane * 16;
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            bf16x8 h0[KS0];
+#pragma unroll
+            for (int ks = 0; ks < KS0; ++ks) h0[ks] = *reinterpret_cast<const bf16x8*>(sb + (o * KS0 + ks) * 1024);
+#pragma unroll
+            for (int i = 0; i < AT; ++i) {
+                bf16x8 h1[O2T][2];
+#pragma unroll
+                for (int j = 0; j < O2T; ++j)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s)
+                        h1[j][s] = *reinterpret_cast<const bf16x8*>(sb + (NB0 + (j * AT + i) * 2 + s) * 1024);
+                floatx16 d;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) d[v] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS0; ++ks) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i][ks], h0[ks], d, 0, 0, 0);
+                // registers 8s .. 8s+7 are the 8 values of a this lane supplies to k-step s
+                bf16x8 zb[2];
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) zb[s][e] = bf16_t(d[8 * s + e]);
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int j = 0; j < O2T; ++j)
+                        acc[j][o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(h1[j][s], zb[s], acc[j][o], 0, 0, 0);
+            }
+        }
+        // keep the accumulators in the accumulation registers across the back edge
+#pragma unroll
+        for (int j = 0; j < O2T; ++j)
+#pragma unroll
+            for (int o = 0; o < 2; ++o) asm volatile("" : "+a"(acc[j][o]));
+    }
+
+    // lane l, register v of acc[j][o]: o2 = 32*j + 8*(v/4) + 4*(l/32) + v%4, o1 = 64*chunk + 32*o + l%32
+    if (t >= p.tokens) return;
+    int yr[2];
+#pragma unroll
+    for (int o = 0; o < 2; ++o) {
+        const int o1 = 64 * chunk + 32 * o + (lane & 31);
+        yr[o] = o1 < p.O1 ? p.yrow[o1] : -1;
+    }
+    bf16_t* yb = static_cast<bf16_t*>(p.Y) + int64_t(t) * p.M;
+    float* yf = static_cast<float*>(p.Y) + (int64_t(split) * p.tokens + t) * p.M;
+#pragma unroll
+    for (int j = 0; j < O2T; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int o2 = 32 * j + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (o2 >= p.C1) continue;
+            const int yc = p.ycol[o2];
+#pragma unroll
+            for (int o = 0; o < 2; ++o) {
+                if (yr[o] < 0) continue;
+                if (p.n_splits > 1) yf[yr[o] + yc] = acc[j][o][v];
+                else yb[yr[o] + yc] = bf16_t(acc[j][o][v]);
+            }
+        }
+}
+
+// Y[i] = bf16( sum_s partial[s][i] ) for n = tokens * M values (n % 4 == 0). A workgroup owns 64 consecutive
+// values: thread (g, q) adds the splits q, q+16, ... of values 4g .. 4g+3, then the 16 partial sums are added in
+// the order of q. The order of the additions depends only on n_splits.
+__global__ void __launch_bounds__(256) kron_reduce_kernel(const float* partial, bf16_t* Y, int64_t n, int n_splits) {
+    __shared__ floatx4 part[16][16];
+    const int g = threadIdx.x & 15, q = threadIdx.x >> 4;
+    const int64_t i = (int64_t(blockIdx.x) * 16 + g) * 4;
+    floatx4 s = {0.f, 0.f, 0.f, 0.f};
+    if (i < n) {
+#pragma unroll 4
+        for (int k = q; k < n_splits; k += 16) s += *reinterpret_cast<const floatx4*>(partial + int64_t(k) * n + i);
+    }
+    part[q][g] = s;
+    __syncthreads();
+    if (q == 0 && i < n) {
+        floatx4 t = part[0][g];
+#pragma unroll
+        for (int k = 1; k < 16; ++k) t += part[k][g];
+        typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+        bf16x4_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = bf16_t(t[e]);
+        *reinterpret_cast<bf16x4_t*>(Y + i) = o;
+    }
+}

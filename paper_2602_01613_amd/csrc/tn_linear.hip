@@ -29,6 +29,7 @@ namespace {
 #include "kernels/tiled.hpp"
 #include "kernels/stream.hpp"
 #include "kernels/chained.hpp"
+#include "kernels/kronsum.hpp"
 
 // ---------------------------------------------------------------------------------------------
 // host side
@@ -40,6 +41,8 @@ enum Variant : int {
     VAR_PIPE_256x128 = 8,     // same, 4 waves stacked along rows
     VAR_SHORTK = 9,           // K <= 64, store-bound: registers-only operands, barrier-free
     VAR_DLDS8_256x256 = 12,   // direct-to-LDS ring, 8 waves, 4 stages, 1 workgroup per CU
+    VAR_KRONSUM = 20,         // (as a forced id only, read by tn::kron_shape) the Kronecker-sum kernel wherever
+                              // the plan's layout allows it
 };
 
 struct DevStep {
@@ -85,6 +88,12 @@ struct tn_linear_s {
     bool pair = false;
     void* pair_b1f = nullptr;
     int64_t pair_min_tokens = 0;
+    // Kronecker-sum kernel (two-step plans over a shared bond): both packed tensors in per-bond slices
+    bool kron = false;
+    tn::KronDims kron_dims;
+    void* kron_h0f = nullptr;
+    void* kron_h1f = nullptr;
+    int64_t kron_min_tokens = 0;
     struct ProfRec { int step; hipEvent_t start, stop; };
     std::vector<ProfRec> prof;
 };
@@ -112,6 +121,8 @@ void free_handle(tn_linear_s* h) {
         if (s.chain_bbf) (void)hipFree(s.chain_bbf);
     }
     if (h->pair_b1f) (void)hipFree(h->pair_b1f);
+    if (h->kron_h0f) (void)hipFree(h->kron_h0f);
+    if (h->kron_h1f) (void)hipFree(h->kron_h1f);
     if (h->small_chain_image) (void)hipFree(h->small_chain_image);
     if (h->owns_workspace) {
         for (void* w : h->ws)
@@ -486,13 +497,146 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
+// Kronecker-sum kernel: instantiations (see tn::kron_shape for the order) and launch geometry.
+// From kKronMinTokens tokens on it replaces the two launches. A workgroup holds 4 tokens; when there are
+// fewer workgroups than compute units the shared bond is split over several of them (fp32 partial sums,
+// added by kron_reduce_kernel).
+constexpr int64_t kKronMinTokens = 1;
+
+template <int AT, int KS0, int O2T>
+int kron_entry(const KronArgs* p, uint32_t grid, hipStream_t st, int* at, int* ks0, int* o2t, size_t* smem) {
+    using S = KronShape<AT, KS0, O2T>;
+    if (at) {
+        *at = AT;
+        *ks0 = KS0;
+        *o2t = O2T;
+        *smem = S::SMEM;
+        return TN_OK;
+    }
+    if (!p)         // configuration call (create time)
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess
+                   ? TN_OK : TN_ERR_HIP;
+    hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    return TN_OK;
+}
+
+int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, int* at = nullptr, int* ks0 = nullptr,
+                  int* o2t = nullptr, size_t* smem = nullptr) {
+    switch (cfg) {
+        case 0: return kron_entry<tn::kKronConfig[0][0], tn::kKronConfig[0][1], tn::kKronConfig[0][2]>(p, grid, st, at, ks0, o2t, smem);
+        case 1: return kron_entry<tn::kKronConfig[1][0], tn::kKronConfig[1][1], tn::kKronConfig[1][2]>(p, grid, st, at, ks0, o2t, smem);
+        case 2: return kron_entry<tn::kKronConfig[2][0], tn::kKronConfig[2][1], tn::kKronConfig[2][2]>(p, grid, st, at, ks0, o2t, smem);
+        case 3: return kron_entry<tn::kKronConfig[3][0], tn::kKronConfig[3][1], tn::kKronConfig[3][2]>(p, grid, st, at, ks0, o2t, smem);
+        case 4: return kron_entry<tn::kKronConfig[4][0], tn::kKronConfig[4][1], tn::kKronConfig[4][2]>(p, grid, st, at, ks0, o2t, smem);
+        default: return TN_ERR_INVALID_ARG;
+    }
+}
+
+struct KronGeom {
+    int n_chunks = 1, n_splits = 1, rho_per_split = 1;
+    int64_t quads = 1, partial_bytes = 0;
+};
+
+KronGeom kron_geometry(const tn_linear_s* h, int64_t tokens, int64_t partial_cap) {
+    KronGeom g;
+    const tn::KronDims& d = h->kron_dims;
+    g.n_chunks = int((d.O1 + 63) / 64);
+    g.quads = (tokens + 3) / 4;
+    int64_t base = g.quads * g.n_chunks;
+    int64_t want = std::max<int64_t>(1, (2 * int64_t(h->num_cus) + base - 1) / base);
+    if (base >= h->num_cus) want = 1;
+    // at least 4 values of the bond per workgroup, partial sums within their buffer
+    want = std::min<int64_t>(want, std::max<int64_t>(1, d.P / 4));
+    want = std::min<int64_t>(want, std::max<int64_t>(1, partial_cap / (tokens * h->plan.M * 4)));
+    g.rho_per_split = int((d.P + want - 1) / want);
+    g.n_splits = int((d.P + g.rho_per_split - 1) / g.rho_per_split);      // no empty split
+    g.partial_bytes = g.n_splits > 1 ? int64_t(g.n_splits) * tokens * h->plan.M * 4 : 0;
+    return g;
+}
+
+int prepare_kron(tn_linear_s* h, hipStream_t st) {
+    if ((h->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS)) || h->pair || h->small_chain) return TN_OK;
+    tn::KronDims d;
+    if (!tn::kron_shape(h->plan, &d)) return TN_OK;
+    const DevStep& s0 = h->steps[0];
+    const DevStep& s1 = h->steps[1];
+    if (s0.variant == VAR_SCALAR || s1.variant == VAR_SCALAR) return TN_OK;
+    int at = 0, ks0 = 0, o2t = 0;
+    size_t smem = 0;
+    if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &at, &ks0, &o2t, &smem) != TN_OK) return TN_OK;
+    const int n_chunks = int((d.O1 + 63) / 64);
+    const int64_t e0 = int64_t(n_chunks) * d.P * 2 * ks0 * 512;
+    const int64_t e1 = d.P * int64_t(o2t) * 2 * at * 512;
+    if (hipMalloc(&h->kron_h0f, size_t(e0) * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
+    if (hipMalloc(&h->kron_h1f, size_t(e1) * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
+    h->packed_bytes += (e0 + e1) * int64_t(sizeof(bf16_t));
+    hipLaunchKernelGGL(kron_repack0_kernel, dim3(uint32_t(std::min<int64_t>((e0 + 255) / 256, 8192))), dim3(256), 0, st,
+                       static_cast<const bf16_t*>(s0.packed), static_cast<bf16_t*>(h->kron_h0f), n_chunks, int(d.P), ks0,
+                       int(d.O1), int(d.K0), s0.Kp >> 4);
+    hipLaunchKernelGGL(kron_repack1_kernel, dim3(uint32_t(std::min<int64_t>((e1 + 255) / 256, 8192))), dim3(256), 0, st,
+                       static_cast<const bf16_t*>(s1.packed), static_cast<bf16_t*>(h->kron_h1f), int(d.P), o2t, at,
+                       int(d.C1), int(d.A), s1.Kp >> 4);
+    if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    h->kron = true;
+    h->kron_dims = d;
+    h->kron_min_tokens = kKronMinTokens;
+    if (h->kron_min_tokens <= 1) {
+        // every call runs the one-launch kernel: the per-step packed tensors are not needed any more
+        if (hipStreamSynchronize(st) != hipSuccess) return TN_ERR_HIP;
+        for (DevStep& s : h->steps) {
+            h->packed_bytes -= int64_t(s.Cp) * s.Kp * h->elt;
+            (void)hipFree(s.packed);
+            s.packed = nullptr;
+        }
+    }
+    return TN_OK;
+}
+
+int launch_kron(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+    const DevStep& s0 = h->steps[0];
+    const DevStep& s1 = h->steps[1];
+    const tn::KronDims& d = h->kron_dims;
+    const KronGeom g = kron_geometry(h, tokens, h->partial_bytes);
+    KronArgs p;
+    p.X = x;
+    p.Y = g.n_splits > 1 ? h->partial : y;
+    p.H0f = h->kron_h0f;
+    p.H1f = h->kron_h1f;
+    p.xrow = s0.plan.a_plain ? nullptr : s0.arow;
+    p.xcol = s0.plan.a_plain ? nullptr : s0.acol;
+    p.yrow = s1.crow;
+    p.ycol = s1.ccol;
+    p.N = h->plan.N;
+    p.M = h->plan.M;
+    p.tokens = int32_t(tokens);
+    p.A = int32_t(d.A);
+    p.K0 = int32_t(d.K0);
+    p.O1 = int32_t(d.O1);
+    p.C1 = int32_t(d.C1);
+    p.P = int32_t(d.P);
+    p.n_chunks = g.n_chunks;
+    p.n_splits = g.n_splits;
+    p.rho_per_split = g.rho_per_split;
+    p.x_vec8 = d.x_vec8 ? 1 : 0;
+    const int64_t grid = g.quads * g.n_chunks * g.n_splits;
+    int rc = kron_dispatch(d.cfg, &p, uint32_t(grid), st);
+    if (rc != TN_OK) return rc;
+    if (g.n_splits > 1) {
+        const int64_t n = tokens * h->plan.M;
+        hipLaunchKernelGGL(kron_reduce_kernel, dim3(uint32_t((n + 63) / 64)), dim3(256), 0, st,
+                           static_cast<const float*>(h->partial), static_cast<bf16_t*>(y), n, g.n_splits);
+    }
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
 // Pairs of steps the transposing chain kernel can run (see step_chain2_kernel): both plain, the
 // first step's output stored transposed ([c1][r], which is what the second step reads as rows c1
 // with K = r), the output in aligned runs of 8 along c1 or along c2, and sizes within one of the
 // two instantiations.
 int plan_chain2(tn_linear_s* h, hipStream_t st) {
     if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_CHAIN2)) ||
-        h->pair)
+        h->pair || h->kron)
         return TN_OK;
     for (size_t i = 0; i + 1 < h->steps.size(); ++i) {
         DevStep& a = h->steps[i];
@@ -577,6 +721,7 @@ int configure_kernels(int device) {
          hipFuncSetAttribute(reinterpret_cast<const void*>(small_chain_kernel<bf16_t>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kSmallChainMaxSmem)) != hipSuccess))
         rc = TN_ERR_HIP;
+    for (int cfg = 0; cfg < tn::kKronConfigs && rc == TN_OK; ++cfg) rc = kron_dispatch(cfg, nullptr, 0, nullptr);
     if (rc == TN_OK && device >= 0 && device < 64) done[device] = true;
     return rc;
 }
@@ -591,6 +736,11 @@ int plan_value(const tn::Plan& p, int32_t what, int64_t* value) {
         case TN_QUERY_IN_FEATURES: *value = p.N; return TN_OK;
         case TN_QUERY_NUM_MERGES: *value = int64_t(p.merges.size()); return TN_OK;
         case TN_QUERY_PAIR_CHAINABLE: *value = tn::pair_chainable(p) ? 1 : 0; return TN_OK;
+        case TN_QUERY_KRON_CHAINABLE: {
+            tn::KronDims d;
+            *value = (!tn::pair_chainable(p) && tn::kron_shape(p, &d)) ? 1 + d.cfg : 0;
+            return TN_OK;
+        }
         default: break;
     }
     if (what >= TN_QUERY_STEP_BASE) {
@@ -888,6 +1038,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     }
     rc = plan_small_chain(h, st);
     if (rc == TN_OK) rc = prepare_pair(h, st);
+    if (rc == TN_OK) rc = prepare_kron(h, st);
     if (rc == TN_OK) rc = plan_chain2(h, st);
     if (rc != TN_OK) {
         (void)hipStreamSynchronize(st);
@@ -897,6 +1048,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     // workspace: two ping-pong buffers, each chunk_tokens * max_intermediate elements, and the
     // partial-sum buffer of the split-K kernel; allocated here, or carved out of the caller's block
     int64_t per_token = h->plan.max_intermediate * h->elt;
+    if (h->kron && h->kron_min_tokens <= 1) per_token = 0;      // every call runs the one-launch kernel: no intermediates
     int64_t max_r = 1;
     for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
     const int64_t row_cap = ((int64_t(1) << 31) - 1024) / max_r;      // rows of a pass are indexed with 32 bits
@@ -904,6 +1056,11 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     auto partial_need = [&](int64_t chunk) {
         int64_t need = 0;
         if (!split_ok) return need;
+        if (h->kron) {
+            for (int64_t t = 1; t <= std::min<int64_t>(h->max_tokens, 4 * int64_t(h->num_cus)); ++t)
+                need = std::max(need, kron_geometry(h, t, kMaxPartialBytes).partial_bytes);
+            if (h->kron_min_tokens <= 1) return need;
+        }
         for (const auto& s : h->steps)
             for (int64_t t = 1; t <= chunk; ++t) {
                 SplitCfg c = split_config(s, t * s.plan.R);
@@ -996,9 +1153,12 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
         }
         return TN_OK;
     }
-    if (h->pair && tokens >= h->pair_min_tokens) {
+    const bool use_pair = h->pair && tokens >= h->pair_min_tokens;
+    const bool use_kron = h->kron && tokens >= h->kron_min_tokens;
+    if (use_pair || use_kron) {
         // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
-        const int64_t pass = int64_t(1) << 24;
+        // (and, for the Kronecker-sum kernel, keep a call's partial sums within their buffer)
+        const int64_t pass = use_pair ? int64_t(1) << 24 : int64_t(1) << 20;
         for (int64_t t0 = 0; t0 < tokens; t0 += pass) {
             int64_t nt = std::min(pass, tokens - t0);
             tn_linear_s::ProfRec rec{0, nullptr, nullptr};
@@ -1007,7 +1167,9 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
                     return TN_ERR_HIP;
                 (void)hipEventRecord(rec.start, st);
             }
-            int rc = launch_pair(h, xb + t0 * h->plan.N * h->elt, yb + t0 * h->plan.M * h->elt, nt, st);
+            const void* xp = xb + t0 * h->plan.N * h->elt;
+            void* yp = yb + t0 * h->plan.M * h->elt;
+            int rc = use_pair ? launch_pair(h, xp, yp, nt, st) : launch_kron(h, xp, yp, nt, st);
             if (h->profiling) {
                 (void)hipEventRecord(rec.stop, st);
                 h->prof.push_back(rec);
@@ -1088,7 +1250,7 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
     if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 == 6) {
         int s = (what - TN_QUERY_STEP_BASE) / 10;
         if (s >= int(h->steps.size())) return TN_ERR_INVALID_ARG;
-        *value = h->steps[size_t(s)].fuse_next ? 1 : ((h->pair && s == 0) ? 2 : 0);
+        *value = h->steps[size_t(s)].fuse_next ? 1 : ((h->pair && s == 0) ? 2 : ((h->kron && s == 0) ? 4 : 0));
         if (h->small_chain && size_t(s) + 1 < h->steps.size()) *value = 3;
         return TN_OK;
     }

@@ -74,6 +74,7 @@ struct MergeOp {
 
 struct Plan {
     int format = 0, dtype = 0;
+    int flags = 0;                  // the description's flags
     int n_caller_tensors = 0;
     std::vector<MergeOp> merges;
     int64_t M = 1, N = 1;
@@ -633,6 +634,73 @@ inline bool pair_chainable(const Plan& p) {
     return s1.r_vec == 8;
 }
 
+// Is the plan two steps of the form  Z[t][o1][a][rho] = sum_k X_t[k][a] B0[(o1, rho)][k],
+// Y[t][o1][o2] = sum_{a, rho} Z[t][o1][a][rho] B1[o2][(a, rho)]  (a sum over the shared bond rho of Kronecker
+// products), laid out the way the Kronecker-sum kernel walks it? Rows a of step 0 (K0 a multiple of 8; x plain
+// or gathered), columns (o1, rho) with rho innermost; step 1 reads rows
+// o1 with K = (a, rho). cfg names the instantiation <AT tiles of a, KS0 k-steps, O2T tiles of o2> that holds the
+// shape with the least padding. Unless the flags force the kernel (variant id 20) the shape must also be one
+// where it pays: an intermediate of at least 32768 values per token, a bond of at least 8, and at least 35 %
+// of the padded MFMA work real.
+struct KronDims {
+    int64_t A = 0, K0 = 0, O1 = 0, C1 = 0, P = 0;
+    int cfg = -1;
+    bool x_vec8 = true;
+};
+
+constexpr int kKronConfigs = 5;
+constexpr int kKronConfig[kKronConfigs][3] = {{5, 10, 3}, {3, 4, 5}, {4, 4, 3}, {2, 6, 5}, {2, 8, 3}};
+
+inline bool kron_shape(const Plan& p, KronDims* d) {
+    if (p.dtype != TN_DTYPE_BF16 || p.steps.size() != 2) return false;
+    if (p.flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS)) return false;
+    const bool any_size = ((p.flags >> TN_FLAG_VARIANT_SHIFT) & 0xff) == 20;      // forced (tests)
+    const Step& s0 = p.steps[0];
+    const Step& s1 = p.steps[1];
+    const int64_t A = s0.R, K0 = s0.K, O1 = s1.R, C1 = s1.C;
+    if (!s1.a_plain || A < 1 || s1.K % A || K0 % 8 || p.N % 8 || p.M % 4) return false;
+    const int64_t P = s1.K / A;
+    if (P < 2 || s0.C != O1 * P || s0.c_tok_stride != O1 * A * P || s1.a_tok_stride != O1 * A * P) return false;
+    if (s0.C > (int64_t(1) << 30) || s1.K > (int64_t(1) << 30)) return false;
+    for (int64_t r = 0; r < A; ++r)
+        if (s0.crow[size_t(r)] != r * P) return false;
+    for (int64_t c = 0; c < s0.C; ++c)
+        if (s0.ccol[size_t(c)] != (c / P) * (A * P) + c % P) return false;
+    bool x_vec8 = true;             // 8 consecutive k of one a are one aligned 16-byte piece of x
+    if (!s0.a_plain) {
+        for (int64_t r = 0; r < A; ++r)
+            if (s0.arow[size_t(r)] % 8) x_vec8 = false;
+        for (int64_t k = 0; k < K0; ++k)
+            if (s0.acol[size_t(k)] != s0.acol[size_t(k & ~int64_t(7))] + (k & 7) || (!(k & 7) && s0.acol[size_t(k)] % 8))
+                x_vec8 = false;
+    }
+    int cfg = -1;
+    int64_t best = 0;
+    const int64_t n_chunks = (O1 + 63) / 64;
+    for (int c = 0; c < kKronConfigs; ++c) {
+        const int64_t at = kKronConfig[c][0], ks0 = kKronConfig[c][1], o2t = kKronConfig[c][2];
+        if (A > 32 * at || K0 > 16 * ks0 || C1 > 32 * o2t) continue;
+        const int64_t mfmas = n_chunks * 2 * at * (ks0 + 2 * o2t);
+        if (cfg < 0 || mfmas < best) {
+            cfg = c;
+            best = mfmas;
+        }
+    }
+    if (cfg < 0) return false;
+    if (!any_size) {
+        const double real = double(A) * double(O1) * double(K0 + C1);
+        if (A * O1 * P < 32768 || P < 8 || real < 0.35 * double(best) * 16384.0) return false;
+    }
+    d->A = A;
+    d->K0 = K0;
+    d->O1 = O1;
+    d->C1 = C1;
+    d->P = P;
+    d->cfg = cfg;
+    d->x_vec8 = x_vec8;
+    return true;
+}
+
 // Can steps a and b (consecutive) run on the transposing chain kernel? Both plain; b contracts a's row
 // index and keeps a's column index as its row index, i.e. a's output is stored transposed ([c1][r]);
 // the output takes 8 consecutive c1 (run_c1 = 1) or 8 consecutive c2 (run_c1 = 0) as one aligned piece;
@@ -658,6 +726,7 @@ inline bool chain2_shape(const Plan& p, const Step& a, const Step& b, int* cfg, 
 inline int make_plan(const tn_linear_desc* d, Plan* p) {
     int rc = build_network(d, p);
     if (rc != TN_OK) return rc;
+    p->flags = d->flags;
     std::vector<int> order;
     rc = choose_order(*p, &order);
     if (rc != TN_OK) return rc;

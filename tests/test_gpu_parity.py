@@ -345,6 +345,65 @@ def test_chained_pair_kernel_q_proj(tokens, dense_w):
     assert O.rel_max_err(y, y_two) <= 1e-2
 
 
+KRON_FORCE = 20 << tn.TN_FLAG_VARIANT_SHIFT
+KRON_CASES = [
+    # (format, out modes, in modes, ranks, flags, instantiation): two-step plans over a shared bond
+    (tn.TN_FORMAT_TT, (40, 36), (10, 64), (1, 40, 1), KRON_FORCE, 4),          # plain x, K0 = 64, one chunk of o1
+    (tn.TN_FORMAT_TT, (70, 150), (4, 32), (1, 40, 1), KRON_FORCE, 4),          # 150 values of o1: three chunks, ragged
+    (tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), KRON_FORCE, 2),          # A = 120: four tiles of a, ragged
+    (tn.TN_FORMAT_TR, (4, 6, 5, 8), (2, 5, 7, 8), (3, 4, 2, 5, 3),             # a ring as two half rings, x gathered
+     KRON_FORCE | tn.TN_FLAG_MERGE_GROW | tn.TN_FLAG_NO_SMALL_CHAIN, 4),       # in 16-byte pieces, K0 = 56
+    (tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, tn.TN_FLAG_MERGE_GROW, 1),   # taken without forcing
+    (tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, tn.TN_FLAG_MERGE_GROW, 4),   # x gathered element-wise
+]
+
+
+@pytest.mark.parametrize("case", range(len(KRON_CASES)))
+def test_kronecker_sum_kernel(case):
+    """Both steps of a two-tensor plan in one launch (intermediate in MFMA registers, the shared bond
+    streamed through LDS) against the oracle and against the two separate launches: one token (the bond
+    split over workgroups, partial sums reduced), a ragged group of four, and enough tokens that nothing
+    is split."""
+    fmt, om, im, rk, flags, cfg = KRON_CASES[case]
+    spec = _spec(fmt, "bf16", om, im, rk)
+    ts = _rand_layer(spec, 900 + case)
+    assert tn.plan_query(fmt, tn.TN_DTYPE_BF16, om, im, rk, tn.TN_QUERY_KRON_CHAINABLE, flags=flags) == 1 + cfg
+    w = O.dense_weight(fmt, ts, len(om))
+    unfused = (flags & (tn.TN_FLAG_MERGE_GROW | tn.TN_FLAG_NO_SMALL_CHAIN)) | tn.TN_FLAG_NO_PAIR_CHAIN
+    for tokens in (1, 6, 1100):
+        print(f"kron case {case} tokens {tokens}", flush=True)
+        x = wl.round_to_dtype(np.random.default_rng(case + tokens).standard_normal((tokens, spec.N)), "bf16")
+        ref = O.apply_linear(w, x)
+        layer = make_layer(spec, ts, tokens, flags=flags)
+        assert layer.query(tn.TN_QUERY_NUM_STEPS) == 2 and layer.query(tn.TN_QUERY_STEP_BASE + 6) == 4
+        yd = layer(to_dev(x, "bf16"))
+        torch.cuda.synchronize()
+        assert torch.equal(yd, layer(to_dev(x, "bf16")))          # same bits on a second call
+        layer.close()
+        y = to_host(yd)
+        y_two = run_layer(spec, ts, x, flags=unfused)
+        assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
+        assert O.rel_max_err(y_two, ref) <= TOL["bf16"], (case, tokens)
+        # both round the intermediate to bf16 once: they differ by summation order only
+        assert O.rel_max_err(y, y_two) <= 1e-2, (case, tokens)
+
+
+def test_kronecker_sum_kernel_caller_workspace(dense_w):
+    """The ring workload as two half rings with a caller-owned workspace: the partial sums of small calls
+    live in the caller's block, and a block too small for many splits only lowers their number."""
+    spec, ts, w = dense_w(3)
+    for ws_bytes in (1 << 20, 64 << 20):
+        block = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks,
+                            [to_dev(t, "bf16") for t in ts], 8, flags=tn.TN_FLAG_MERGE_GROW, workspace=block)
+        assert layer.query(tn.TN_QUERY_STEP_BASE + 6) == 4
+        for tokens in (1, 5):
+            x = wl.make_x(spec, tokens, 3)
+            y = to_host(layer(to_dev(x, "bf16")))
+            assert O.rel_max_err(y, O.apply_linear(w, x)) <= TOL["bf16"], (ws_bytes, tokens)
+        layer.close()
+
+
 CHAIN2_CASES = [
     # Tucker layers whose factor products run as chained launches (out modes, in modes, ranks)
     ((160, 160), (64, 80), (96, 96, 48, 48)),     # the up_proj workload: 64x80 -> 48x48, 96x96 -> 160x160

@@ -196,6 +196,30 @@ def test_pair_chainable_plans():
         assert q(s.format, s.out_modes, s.in_modes, s.ranks) == 0
 
 
+def test_kronecker_sum_plans():
+    """Which plans run on the Kronecker-sum kernel: two steps over a shared bond whose intermediate is
+    large (a ring contracted into two half rings), in the instantiation with the least padding; small
+    shapes only when forced; never the plans of the chained pair kernel, fp32, or with chaining off."""
+    q = lambda fmt, om, im, rk, flags=0, dt=tn.TN_DTYPE_BF16: tn.plan_query(fmt, dt, om, im, rk,
+                                                                             tn.TN_QUERY_KRON_CHAINABLE, flags=flags)
+    ring, _ = wl.baseline_spec(3)
+    grow, force = tn.TN_FLAG_MERGE_GROW, 20 << tn.TN_FLAG_VARIANT_SHIFT
+    assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks) == 0                  # four steps
+    assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow) == 1            # <5, 10, 3>
+    assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow | tn.TN_FLAG_NO_PAIR_CHAIN) == 0
+    assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow, tn.TN_DTYPE_F32) == 0
+    assert q(ring.format, ring.in_modes[:0] + (10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5, grow) == 4    # <2, 6, 5>
+    assert q(tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, grow) == 2          # <3, 4, 5>
+    assert q(tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, grow) == 5          # <2, 8, 3>
+    train, _ = wl.baseline_spec(1)
+    assert q(train.format, train.out_modes, train.in_modes, train.ranks) == 0             # the pair kernel's plan
+    small = (tn.TN_FORMAT_TT, (40, 36), (10, 64), (1, 40, 1))
+    assert q(*small) == 0 and q(*small, force) == 5
+    assert q(tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), force) == 3                  # <4, 4, 3>
+    assert q(tn.TN_FORMAT_TT, (8, 12), (16, 8), (1, 24, 1), force) == 5                    # x gathered element-wise
+    assert q(tn.TN_FORMAT_TT, (20, 6), (24, 10), (1, 40, 1), force) == 0                   # K0 = 10: not 8-aligned
+
+
 def test_chain2_shapes():
     """Which step pairs qualify for the transposing chain kernel: the factor products of Tucker layers
     whose first step reads a plain matrix, in the smaller instantiation where it fits."""
