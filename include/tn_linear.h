@@ -70,6 +70,8 @@ extern "C" {
 #define TN_FLAG_NO_SMALL_CHAIN (1 << 20) /* never run a small layer as one launch with all its tensors in LDS */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */
+#define TN_FLAG_NO_LAZY_MERGE (1 << 21)  /* never run large calls on a merged plan rebuilt in the workspace (see
+                                       TN_QUERY_LAZY_MIN_TOKENS): every call runs the compact steps */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
                                        bf16 steps (0 = library's choice): 3 = 128x256 and 8 = 256x128
                                        register-prefetch tiles, 9 = short-K store kernel, 12 = 256x256
@@ -96,6 +98,13 @@ extern "C" {
                                            that the Kronecker-sum kernel runs as one launch with the
                                            intermediate in registers (e.g. a ring contracted into two half
                                            rings under TN_FLAG_MERGE_GROW) */
+#define TN_QUERY_LAZY_MIN_TOKENS   12   /* handle only: 0, or the token count from which a call runs on a lazily
+                                           merged plan: the plan TN_FLAG_MERGE_GROW would give (two half rings for
+                                           a ring of four cores) is cheaper and fits the Kronecker-sum kernel, so
+                                           such calls rebuild its tensors in the workspace from the caller's
+                                           compact ones (microseconds) and run that one launch; the layer stores
+                                           only the compact tensors, and smaller calls run the compact steps */
+#define TN_QUERY_LAZY_FLOPS_PER_TOKEN 13 /* handle only: FLOPs per token of that plan (0 if none) */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=

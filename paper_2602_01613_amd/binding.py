@@ -26,6 +26,7 @@ TN_FLAG_NO_CHAIN2 = 64
 TN_FLAG_TRANSPOSE = 128
 TN_FLAG_NO_SMALL_CHAIN = 1 << 20
 TN_FLAG_VARIANT_SHIFT = 8
+TN_FLAG_NO_LAZY_MERGE = 1 << 21
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -38,6 +39,8 @@ TN_QUERY_IN_FEATURES = 8
 TN_QUERY_NUM_MERGES = 9
 TN_QUERY_PAIR_CHAINABLE = 10
 TN_QUERY_KRON_CHAINABLE = 11
+TN_QUERY_LAZY_MIN_TOKENS = 12
+TN_QUERY_LAZY_FLOPS_PER_TOKEN = 13
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (

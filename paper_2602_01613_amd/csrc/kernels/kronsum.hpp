@@ -266,3 +266,121 @@ __global__ void __launch_bounds__(256) kron_reduce_kernel(const float* partial, 
         *reinterpret_cast<bf16x4_t*>(Y + i) = o;
     }
 }
+
+// ---------------------------------------------------------------------------------------------
+// The two slice arrays above, computed from the caller's tensors instead of read from a stored merged
+// tensor: each element is one entry of the contraction of two tensors P and Q over the indices they
+// share (a half ring: two neighbouring cores over their common bond),
+//     merged[r][c] = sum_s P[off_r(r) + off_s(s)] * Q[off_c(c) + off_s'(s)]        row-major [R][C],
+// taken at the position the step's packing and the slice layout assign to it. This lets a layer keep
+// only its compact tensors: the slices (tens of MB) are rebuilt in the shared workspace by every large
+// call, which costs a fraction of a millisecond against the milliseconds of the call itself.
+// The library keeps P and Q as matrices with the shared indices innermost (Pc[r][s], Qc[c][s], rows padded
+// with zeros to a multiple of 8), written once at create time by kron_source_kernel, so that an entry is
+// the dot product of two contiguous rows.
+// ---------------------------------------------------------------------------------------------
+struct GenDims {
+    int32_t n;
+    int32_t ext[tn::kMaxGatherDims];
+    int64_t str[tn::kMaxGatherDims];
+};
+
+__device__ __forceinline__ int64_t gen_offset(const GenDims& d, int64_t idx) {
+    int64_t off = 0;
+    for (int j = d.n - 1; j >= 0; --j) {
+        int64_t q = idx / d.ext[j];
+        off += (idx - q * d.ext[j]) * d.str[j];
+        idx = q;
+    }
+    return off;
+}
+
+// dst[r*Sp + s] = src[off_free(r) + off_shared(s)], zero for s >= S
+__global__ void __launch_bounds__(256) kron_source_kernel(const bf16_t* src, bf16_t* dst, GenDims free_dims, GenDims shared_dims,
+                                                          int64_t rows, int32_t S, int32_t Sp) {
+    const int64_t total = rows * Sp;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
+        const int64_t r = i / Sp;
+        const int32_t sidx = int32_t(i - r * Sp);
+        dst[i] = sidx < S ? src[gen_offset(free_dims, r) + gen_offset(shared_dims, sidx)] : bf16_t(0.f);
+    }
+}
+
+struct KronGenArgs {
+    const void* Pc;        // [R][Sp]
+    const void* Qc;        // [C][Sp]
+    void* dst;
+    GenDims sc, sk;        // the step's column / k index -> offset in the merged tensor (row-major [R][C])
+    int64_t merged_C;
+    int32_t Sp;            // padded length of the shared indices, a multiple of 8
+    int32_t which;         // 0: first slice array (H0f), 1: second (H1f)
+    int32_t n_chunks, P, KS0, O1, K0;        // layout of H0f
+    int32_t O2T, AT, C1, A;                  // layout of H1f
+};
+
+// One thread per 16-byte piece (8 consecutive elements) of a slice array.
+__global__ void __launch_bounds__(256) kron_generate_kernel(KronGenArgs p) {
+    const int64_t pieces = p.which == 0 ? int64_t(p.n_chunks) * p.P * 2 * p.KS0 * 64 : int64_t(p.P) * p.O2T * 2 * p.AT * 64;
+    const bf16_t* Pc = static_cast<const bf16_t*>(p.Pc);
+    const bf16_t* Qc = static_cast<const bf16_t*>(p.Qc);
+    bf16x8* dst = static_cast<bf16x8*>(p.dst);
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < pieces; i += int64_t(gridDim.x) * 256) {
+        const int l = int(i & 63);
+        int64_t blk = i >> 6;
+        // position of the piece's 8 elements in the step's packed matrix B[c][k]
+        int64_t c0, k0;
+        int64_t k_step4, k_step1;              // element e: c = c0, k = k0 + (e/4)*k_step4 + (e%4)*k_step1
+        int n_inside = 8;                      // first array: elements e < n_inside are inside the tensor
+        bool row_inside;
+        int limit_a = 0;
+        if (p.which == 0) {
+            int ks = int(blk % p.KS0);
+            blk /= p.KS0;
+            int o1t = int(blk & 1);
+            blk >>= 1;
+            int rho = int(blk % p.P);
+            int chunk = int(blk / p.P);
+            int o1 = 64 * chunk + 32 * o1t + (l & 31);
+            k0 = 16 * ks + 8 * (l >> 5);
+            c0 = int64_t(o1) * p.P + rho;
+            row_inside = o1 < p.O1;
+            k_step4 = 4;
+            k_step1 = 1;
+            n_inside = int(max(int64_t(0), min(int64_t(8), int64_t(p.K0) - k0)));
+        } else {
+            int is = int(blk % (2 * p.AT));
+            blk /= 2 * p.AT;
+            int j = int(blk % p.O2T);
+            int rho = int(blk / p.O2T);
+            c0 = 32 * j + (l & 31);
+            int a0 = 16 * is + 4 * (l >> 5);            // a = a0 + 8*(e/4) + e%4
+            k0 = int64_t(a0) * p.P + rho;
+            row_inside = c0 < p.C1;
+            k_step4 = 8 * int64_t(p.P);
+            k_step1 = p.P;
+            limit_a = a0;
+        }
+        bf16x8 out;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = 0.f;
+            bool inside = row_inside;
+            if (p.which == 0) inside = inside && e < n_inside;
+            else inside = inside && (limit_a + 8 * (e >> 2) + (e & 3)) < p.A;
+            if (inside) {
+                const int64_t k = k0 + (e >> 2) * k_step4 + (e & 3) * k_step1;
+                const int64_t m = gen_offset(p.sc, c0) + gen_offset(p.sk, k);
+                const int64_t r = m / p.merged_C, cc = m - r * p.merged_C;
+                const bf16x8* pr = reinterpret_cast<const bf16x8*>(Pc + r * p.Sp);
+                const bf16x8* qr = reinterpret_cast<const bf16x8*>(Qc + cc * p.Sp);
+                for (int j = 0; j < (p.Sp >> 3); ++j) {
+                    const bf16x8 a = pr[j], b = qr[j];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) v += float(a[q]) * float(b[q]);
+                }
+            }
+            out[e] = bf16_t(v);
+        }
+        dst[i] = out;
+    }
+}

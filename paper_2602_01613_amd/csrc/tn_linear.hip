@@ -94,6 +94,19 @@ struct tn_linear_s {
     void* kron_h0f = nullptr;
     void* kron_h1f = nullptr;
     int64_t kron_min_tokens = 0;
+    // the same kernel on a plan that exists only for large calls: the layer keeps its compact tensors and
+    // steps, and calls of at least lazy_min_tokens tokens rebuild the merged plan's slices in the workspace
+    bool lazy = false;
+    tn::Plan lazy_plan;
+    tn::KronDims lazy_dims;
+    int64_t lazy_min_tokens = 0;
+    int64_t lazy_slice_bytes = 0;             // both slice arrays
+    int64_t lazy_h1_offset = 0;               // byte offset of the second array inside the slice buffer
+    void* lazy_slices = nullptr;              // in the workspace (owned or caller's)
+    std::vector<void*> lazy_sources;          // per half: the two tensors it is made of, as matrices [free][shared]
+    int32_t* lazy_tables = nullptr;           // xrow | xcol | yrow | ycol of the merged plan
+    const int32_t *lazy_xrow = nullptr, *lazy_xcol = nullptr, *lazy_yrow = nullptr, *lazy_ycol = nullptr;
+    KronGenArgs lazy_gen[2];
     struct ProfRec { int step; hipEvent_t start, stop; };
     std::vector<ProfRec> prof;
 };
@@ -123,6 +136,10 @@ void free_handle(tn_linear_s* h) {
     if (h->pair_b1f) (void)hipFree(h->pair_b1f);
     if (h->kron_h0f) (void)hipFree(h->kron_h0f);
     if (h->kron_h1f) (void)hipFree(h->kron_h1f);
+    for (void* v : h->lazy_sources)
+        if (v) (void)hipFree(v);
+    if (h->lazy_tables) (void)hipFree(h->lazy_tables);
+    if (h->lazy_slices && h->owns_workspace) (void)hipFree(h->lazy_slices);
     if (h->small_chain_image) (void)hipFree(h->small_chain_image);
     if (h->owns_workspace) {
         for (void* w : h->ws)
@@ -538,9 +555,8 @@ struct KronGeom {
     int64_t quads = 1, partial_bytes = 0;
 };
 
-KronGeom kron_geometry(const tn_linear_s* h, int64_t tokens, int64_t partial_cap) {
+KronGeom kron_geometry(const tn_linear_s* h, const tn::KronDims& d, int64_t tokens, int64_t partial_cap) {
     KronGeom g;
-    const tn::KronDims& d = h->kron_dims;
     g.n_chunks = int((d.O1 + 63) / 64);
     g.quads = (tokens + 3) / 4;
     int64_t base = g.quads * g.n_chunks;
@@ -593,20 +609,24 @@ int prepare_kron(tn_linear_s* h, hipStream_t st) {
     return TN_OK;
 }
 
-int launch_kron(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
-    const DevStep& s0 = h->steps[0];
-    const DevStep& s1 = h->steps[1];
-    const tn::KronDims& d = h->kron_dims;
-    const KronGeom g = kron_geometry(h, tokens, h->partial_bytes);
+struct KronSetup {
+    const tn::KronDims* dims;
+    const void *h0f, *h1f;
+    const int32_t *xrow, *xcol, *yrow, *ycol;
+};
+
+int launch_kron(const tn_linear_s* h, const KronSetup& k, const void* x, void* y, int64_t tokens, hipStream_t st) {
+    const tn::KronDims& d = *k.dims;
+    const KronGeom g = kron_geometry(h, d, tokens, h->partial_bytes);
     KronArgs p;
     p.X = x;
     p.Y = g.n_splits > 1 ? h->partial : y;
-    p.H0f = h->kron_h0f;
-    p.H1f = h->kron_h1f;
-    p.xrow = s0.plan.a_plain ? nullptr : s0.arow;
-    p.xcol = s0.plan.a_plain ? nullptr : s0.acol;
-    p.yrow = s1.crow;
-    p.ycol = s1.ccol;
+    p.H0f = k.h0f;
+    p.H1f = k.h1f;
+    p.xrow = k.xrow;
+    p.xcol = k.xcol;
+    p.yrow = k.yrow;
+    p.ycol = k.ycol;
     p.N = h->plan.N;
     p.M = h->plan.M;
     p.tokens = int32_t(tokens);
@@ -628,6 +648,142 @@ int launch_kron(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
                            static_cast<const float*>(h->partial), static_cast<bf16_t*>(y), n, g.n_splits);
     }
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+int launch_kron_eager(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+    const DevStep& s0 = h->steps[0];
+    const DevStep& s1 = h->steps[1];
+    KronSetup k{&h->kron_dims, h->kron_h0f, h->kron_h1f, s0.plan.a_plain ? nullptr : s0.arow,
+                s0.plan.a_plain ? nullptr : s0.acol, s1.crow, s1.ccol};
+    return launch_kron(h, k, x, y, tokens, st);
+}
+
+// Large calls of a layer with a lazily merged plan: rebuild the two slice arrays in the workspace from the
+// library's copies of the caller's tensors, then run the Kronecker-sum kernel on them.
+int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+    for (int w = 0; w < 2; ++w) {
+        const KronGenArgs& g = h->lazy_gen[w];
+        const int64_t pieces = w == 0 ? int64_t(g.n_chunks) * g.P * 2 * g.KS0 * 64 : int64_t(g.P) * g.O2T * 2 * g.AT * 64;
+        hipLaunchKernelGGL(kron_generate_kernel, dim3(uint32_t(std::min<int64_t>((pieces + 255) / 256, 1 << 20))), dim3(256),
+                           0, st, g);
+    }
+    if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    KronSetup k{&h->lazy_dims, h->lazy_slices, static_cast<const char*>(h->lazy_slices) + h->lazy_h1_offset,
+                h->lazy_xrow, h->lazy_xcol, h->lazy_yrow, h->lazy_ycol};
+    return launch_kron(h, k, x, y, tokens, st);
+}
+
+// Token count from which a lazily merged plan replaces the compact steps.
+constexpr int64_t kLazyMinTokens = 16;
+
+void fill_gen_dims(GenDims* g, const std::vector<tn::GatherDim>& d) {
+    g->n = int32_t(d.size());
+    for (size_t j = 0; j < d.size(); ++j) {
+        g->ext[j] = int32_t(d[j].extent);
+        g->str[j] = d[j].stride;
+    }
+}
+
+// Decide whether the layer gets a lazily merged plan, and prepare it: the plan TN_FLAG_MERGE_GROW would give
+// must be two steps the Kronecker-sum kernel takes (large intermediate, little padding), each absorbing a
+// tensor merged from two of the caller's, and cheaper than the compact plan. Nothing of that plan is stored
+// except copies of the caller's tensors involved and four offset tables.
+int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
+    if (h->plan.dtype != TN_DTYPE_BF16 || h->pair || h->kron || h->small_chain) return TN_OK;
+    if (desc->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_MERGE | TN_FLAG_MERGE_GROW |
+                       TN_FLAG_NO_LAZY_MERGE))
+        return TN_OK;
+    if (((desc->flags >> TN_FLAG_VARIANT_SHIFT) & 0xff) != 0) return TN_OK;      // tuning overrides: keep what they ask
+    if (desc->max_tokens < kLazyMinTokens) return TN_OK;
+    tn_linear_desc grow = *desc;
+    grow.flags |= TN_FLAG_MERGE_GROW;
+    tn::Plan& q = h->lazy_plan;
+    if (tn::make_plan(&grow, &q) != TN_OK || q.steps.size() != 2 || q.merges.size() != 2 || q.flops >= h->plan.flops)
+        return TN_OK;
+    tn::KronDims d;
+    if (!tn::kron_shape(q, &d)) return TN_OK;
+    const tn::MergeOp* mo[2];
+    for (int w = 0; w < 2; ++w) {
+        int mi = q.steps[size_t(w)].slot - q.n_caller_tensors;
+        if (mi < 0 || mi >= 2) return TN_OK;
+        mo[w] = &q.merges[size_t(mi)];
+        if (mo[w]->p_slot >= q.n_caller_tensors || mo[w]->q_slot >= q.n_caller_tensors) return TN_OK;
+        if (mo[w]->kp.empty() || q.steps[size_t(w)].trace_extent != 1) return TN_OK;
+    }
+    int at = 0, ks0 = 0, o2t = 0;
+    size_t smem = 0;
+    if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &at, &ks0, &o2t, &smem) != TN_OK) return TN_OK;
+    // the four source matrices (shared indices innermost), written from the caller's tensors
+    const int32_t sp_len[2] = {round_up(int(mo[0]->K), 8), round_up(int(mo[1]->K), 8)};
+    for (int w = 0; w < 2; ++w)
+        for (int side = 0; side < 2; ++side) {
+            const int64_t rows = side == 0 ? mo[w]->R : mo[w]->C;
+            const int64_t n = rows * sp_len[w];
+            void* buf = nullptr;
+            if (hipMalloc(&buf, size_t(n) * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
+            h->lazy_sources.push_back(buf);
+            h->packed_bytes += n * int64_t(sizeof(bf16_t));
+            GenDims fd, sd;
+            memset(&fd, 0, sizeof(fd));
+            memset(&sd, 0, sizeof(sd));
+            fill_gen_dims(&fd, side == 0 ? mo[w]->rdims : mo[w]->cdims);
+            fill_gen_dims(&sd, side == 0 ? mo[w]->kp : mo[w]->kq);
+            hipLaunchKernelGGL(kron_source_kernel, dim3(uint32_t(std::min<int64_t>((n + 255) / 256, 65536))), dim3(256), 0, st,
+                               static_cast<const bf16_t*>(desc->tensors[side == 0 ? mo[w]->p_slot : mo[w]->q_slot]),
+                               static_cast<bf16_t*>(buf), fd, sd, rows, int32_t(mo[w]->K), sp_len[w]);
+        }
+    if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    // tables of the merged plan
+    const tn::Step& s0 = q.steps[0];
+    const tn::Step& s1 = q.steps[1];
+    std::vector<int32_t> tab;
+    const size_t n_xrow = s0.a_plain ? 0 : s0.arow.size(), n_xcol = s0.a_plain ? 0 : s0.acol.size();
+    if (!s0.a_plain) {
+        tab.insert(tab.end(), s0.arow.begin(), s0.arow.end());
+        tab.insert(tab.end(), s0.acol.begin(), s0.acol.end());
+    }
+    tab.insert(tab.end(), s1.crow.begin(), s1.crow.end());
+    tab.insert(tab.end(), s1.ccol.begin(), s1.ccol.end());
+    if (hipMalloc(reinterpret_cast<void**>(&h->lazy_tables), tab.size() * sizeof(int32_t)) != hipSuccess) return TN_ERR_ALLOC;
+    if (hipMemcpyAsync(h->lazy_tables, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return TN_ERR_HIP;
+    if (!s0.a_plain) {
+        h->lazy_xrow = h->lazy_tables;
+        h->lazy_xcol = h->lazy_tables + n_xrow;
+    }
+    h->lazy_yrow = h->lazy_tables + n_xrow + n_xcol;
+    h->lazy_ycol = h->lazy_yrow + s1.crow.size();
+    const int n_chunks = int((d.O1 + 63) / 64);
+    const int64_t e0 = int64_t(n_chunks) * d.P * 2 * ks0 * 512;
+    const int64_t e1 = d.P * int64_t(o2t) * 2 * at * 512;
+    h->lazy_h1_offset = (e0 * 2 + 255) & ~int64_t(255);
+    h->lazy_slice_bytes = h->lazy_h1_offset + ((e1 * 2 + 255) & ~int64_t(255));
+    for (int w = 0; w < 2; ++w) {
+        KronGenArgs& g = h->lazy_gen[w];
+        memset(&g, 0, sizeof(g));
+        const tn::Step& sp = q.steps[size_t(w)];
+        g.Pc = h->lazy_sources[size_t(2 * w)];
+        g.Qc = h->lazy_sources[size_t(2 * w + 1)];
+        fill_gen_dims(&g.sc, sp.cdims);
+        fill_gen_dims(&g.sk, sp.kdims);
+        g.merged_C = mo[w]->C;
+        g.Sp = sp_len[w];
+        g.which = w;
+        g.n_chunks = n_chunks;
+        g.P = int32_t(d.P);
+        g.KS0 = ks0;
+        g.O1 = int32_t(d.O1);
+        g.K0 = int32_t(d.K0);
+        g.O2T = o2t;
+        g.AT = at;
+        g.C1 = int32_t(d.C1);
+        g.A = int32_t(d.A);
+    }
+    h->lazy = true;
+    h->lazy_dims = d;
+    h->lazy_min_tokens = kLazyMinTokens;
+    return TN_OK;
 }
 
 // Pairs of steps the transposing chain kernel can run (see step_chain2_kernel): both plain, the
@@ -1040,6 +1196,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     if (rc == TN_OK) rc = prepare_pair(h, st);
     if (rc == TN_OK) rc = prepare_kron(h, st);
     if (rc == TN_OK) rc = plan_chain2(h, st);
+    if (rc == TN_OK) rc = prepare_lazy(h, desc, st);
     if (rc != TN_OK) {
         (void)hipStreamSynchronize(st);
         free_handle(h);
@@ -1058,9 +1215,12 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         if (!split_ok) return need;
         if (h->kron) {
             for (int64_t t = 1; t <= std::min<int64_t>(h->max_tokens, 4 * int64_t(h->num_cus)); ++t)
-                need = std::max(need, kron_geometry(h, t, kMaxPartialBytes).partial_bytes);
+                need = std::max(need, kron_geometry(h, h->kron_dims, t, kMaxPartialBytes).partial_bytes);
             if (h->kron_min_tokens <= 1) return need;
         }
+        if (h->lazy)
+            for (int64_t t = h->lazy_min_tokens; t <= std::min<int64_t>(h->max_tokens, 4 * int64_t(h->num_cus)); ++t)
+                need = std::max(need, kron_geometry(h, h->lazy_dims, t, kMaxPartialBytes).partial_bytes);
         for (const auto& s : h->steps)
             for (int64_t t = 1; t <= chunk; ++t) {
                 SplitCfg c = split_config(s, t * s.plan.R);
@@ -1069,8 +1229,17 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             }
         return need;
     };
-    // with the chained pair kernel only calls below its token threshold use the workspace
-    const int64_t ws_tokens = h->pair ? std::min<int64_t>(h->max_tokens, h->pair_min_tokens - 1) : h->max_tokens;
+    // a lazily merged plan needs room for its slices: in the caller's block they share the space of the two
+    // buffers (never in use at the same time), otherwise they get an allocation of their own
+    if (h->lazy) {
+        const int64_t room = desc->workspace
+                                 ? desc->workspace_bytes - (split_ok ? std::min<int64_t>(kMaxPartialBytes, desc->workspace_bytes / 4) : 0) - 512
+                                 : (desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes);
+        if (room < h->lazy_slice_bytes) h->lazy = false;
+    }
+    // with the chained pair kernel or a lazily merged plan only calls below the token threshold use the buffers
+    int64_t ws_tokens = h->pair ? std::min<int64_t>(h->max_tokens, h->pair_min_tokens - 1) : h->max_tokens;
+    if (h->lazy) ws_tokens = std::min<int64_t>(ws_tokens, h->lazy_min_tokens - 1);
     int64_t chunk = ws_tokens;
     if (desc->workspace) {
         // caller-owned block: [partial sums | buffer 0 | buffer 1], 256-byte aligned pieces
@@ -1094,6 +1263,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             h->partial = base;
             h->partial_bytes = part;
         }
+        if (h->lazy) h->lazy_slices = base + part;
         h->workspace_bytes = 0;
     } else {
         int64_t limit = desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes;
@@ -1119,7 +1289,16 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             h->partial_bytes = need;
             h->workspace_bytes += need;
         }
+        if (h->lazy) {
+            if (hipMalloc(&h->lazy_slices, size_t(h->lazy_slice_bytes)) != hipSuccess) {
+                free_handle(h);
+                return TN_ERR_ALLOC;
+            }
+            h->workspace_bytes += h->lazy_slice_bytes;
+        }
     }
+    for (int w = 0; w < 2 && h->lazy; ++w)
+        h->lazy_gen[w].dst = static_cast<char*>(h->lazy_slices) + (w == 0 ? 0 : h->lazy_h1_offset);
     h->chunk_tokens = chunk;
     *out = h;
     return TN_OK;
@@ -1155,7 +1334,8 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
     }
     const bool use_pair = h->pair && tokens >= h->pair_min_tokens;
     const bool use_kron = h->kron && tokens >= h->kron_min_tokens;
-    if (use_pair || use_kron) {
+    const bool use_lazy = h->lazy && tokens >= h->lazy_min_tokens;
+    if (use_pair || use_kron || use_lazy) {
         // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
         // (and, for the Kronecker-sum kernel, keep a call's partial sums within their buffer)
         const int64_t pass = use_pair ? int64_t(1) << 24 : int64_t(1) << 20;
@@ -1169,7 +1349,8 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
             }
             const void* xp = xb + t0 * h->plan.N * h->elt;
             void* yp = yb + t0 * h->plan.M * h->elt;
-            int rc = use_pair ? launch_pair(h, xp, yp, nt, st) : launch_kron(h, xp, yp, nt, st);
+            int rc = use_pair ? launch_pair(h, xp, yp, nt, st)
+                              : (use_kron ? launch_kron_eager(h, xp, yp, nt, st) : launch_kron_lazy(h, xp, yp, nt, st));
             if (h->profiling) {
                 (void)hipEventRecord(rec.stop, st);
                 h->prof.push_back(rec);
@@ -1239,6 +1420,8 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
         case TN_QUERY_PACKED_BYTES: *value = h->packed_bytes; return TN_OK;
         case TN_QUERY_WORKSPACE_BYTES: *value = h->workspace_bytes; return TN_OK;
         case TN_QUERY_CHUNK_TOKENS: *value = h->chunk_tokens; return TN_OK;
+        case TN_QUERY_LAZY_MIN_TOKENS: *value = h->lazy ? h->lazy_min_tokens : 0; return TN_OK;
+        case TN_QUERY_LAZY_FLOPS_PER_TOKEN: *value = h->lazy ? h->lazy_plan.flops : 0; return TN_OK;
         default: break;
     }
     if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 == 5) {
