@@ -101,13 +101,17 @@ def run_stack(args) -> int:
         return out
 
     t0 = time.perf_counter()
-    layers, flops, params, packed = [], [], [], []
+    layers, flops, flops_prefill, params, packed = [], [], [], [], []
     for spec in specs:
         ts = draw(spec)
         layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, ts,
                             tokens, flags=(2 if args.no_merge else 0) | (16 if args.merge_grow else 0), workspace=ws)
         layers.append(layer)
         flops.append(layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN))
+        # large calls of some layers run on a cheaper plan rebuilt per call: count the work actually done
+        lazy_min = layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS)
+        flops_prefill.append(layer.query(tn.TN_QUERY_LAZY_FLOPS_PER_TOKEN) if lazy_min and tokens >= lazy_min
+                             else flops[-1])
         params.append(spec.n_params)
         packed.append(layer.query(tn.TN_QUERY_PACKED_BYTES))
         del ts
@@ -147,19 +151,24 @@ def run_stack(args) -> int:
         torch.cuda.synchronize()
         if wall is None:
             wall = time.perf_counter() - t0
-        by_fmt = {}
+        by_fmt, by_shape = {}, {}
         for spec, (e0, e1) in zip(specs, evs):
             k = wl.FORMAT_NAMES[spec.format]
-            by_fmt[k] = by_fmt.get(k, 0.0) + e0.elapsed_time(e1)
-        return wall, by_fmt
+            ms = e0.elapsed_time(e1)
+            by_fmt[k] = by_fmt.get(k, 0.0) + ms
+            if spec.format != wl.FORMAT_DENSE:
+                k2 = f"{k} {spec.N}->{spec.M} r{max(spec.ranks)}"
+                n, tot = by_shape.get(k2, (0, 0.0))
+                by_shape[k2] = (n + 1, tot + ms)
+        return wall, by_fmt, {k: {"matrices": n, "ms_each": tot / n} for k, (n, tot) in sorted(by_shape.items())}
 
-    dec_wall, dec_fmt = timed(1, args.steps)
-    pre_wall, pre_fmt = timed(tokens, 0)
+    dec_wall, dec_fmt, dec_shape = timed(1, args.steps)
+    pre_wall, pre_fmt, pre_shape = timed(tokens, 0)
     counts = {}
     for spec in specs:
         k = f"{wl.FORMAT_NAMES[spec.format]}"
         counts[k] = counts.get(k, 0) + 1
-    total_flops = sum(flops)
+    total_flops = sum(flops_prefill)
     result = {
         "metric": METRIC, "value": tokens / pre_wall, "unit": "tokens/s", "n_gpus": 1, "steps": 1, "warmup": 0,
         "ms_per_step": 1e3 * pre_wall, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -171,8 +180,10 @@ def run_stack(args) -> int:
         "flops_per_token_all_matrices": total_flops,
         "tflops_factorised": total_flops * tokens / pre_wall / 1e12,
         "prefill_ms_by_format": pre_fmt,
+        "prefill_ms_by_shape": pre_shape,
         "decode_1tok": {"ms_per_token_all_matrices": 1e3 * dec_wall, "tokens_per_s": 1.0 / dec_wall,
-                        "ms_by_format": dec_fmt, "packed_GB": sum(packed) / 1e9,
+                        "ms_by_format": dec_fmt, "us_by_shape": {k: round(1e3 * v["ms_each"], 1) for k, v in dec_shape.items()},
+                        "packed_GB": sum(packed) / 1e9,
                         "packed_GBps": sum(packed) / dec_wall / 1e9},
         "parameters": sum(params), "create_seconds": create_s,
         "roofline": None, "cpu_baseline": None,
@@ -257,15 +268,33 @@ def main() -> int:
     y = torch.empty((tokens, layer.M), dtype=tdt, device="cuda")
     stream = torch.cuda.current_stream()
 
-    flops_tok = layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
-    n_steps = layer.query(tn.TN_QUERY_NUM_STEPS)
     chunk = layer.query(tn.TN_QUERY_CHUNK_TOKENS)
-    q = lambda s, f: layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + f)
-    step_flops = [q(s, 3) for s in range(n_steps)]
-    # algorithmic bytes of a step per token: read its [rows, K] input, write its [rows, cols]
-    # output (bf16), plus its packed parameter tensor once per launch
-    step_io_bytes = [esize * q(s, 0) * (q(s, 1) + q(s, 2)) for s in range(n_steps)]
-    step_param_bytes = [esize * q(s, 1) * q(s, 2) for s in range(n_steps)]
+    # Calls of at least lazy_min tokens (0: never) run on a plan whose merged tensors are rebuilt in the
+    # workspace per call: its steps, not the compact plan's, are the work such a call does.
+    lazy_min = layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS)
+
+    def plan_view(t):
+        """Steps, FLOPs and algorithmic bytes of the plan a call of t tokens executes."""
+        if lazy_min and t >= lazy_min:
+            pq = lambda what: tn.plan_query(spec.format, code, spec.out_modes, spec.in_modes, spec.ranks, what,
+                                            flags=layer_flags | tn.TN_FLAG_MERGE_HALVES)
+            qq = lambda s, f: 20 if f == 5 else pq(tn.TN_QUERY_STEP_BASE + 10 * s + f)
+            n = pq(tn.TN_QUERY_NUM_STEPS)
+            fl = pq(tn.TN_QUERY_FLOPS_PER_TOKEN)
+        else:
+            qq = lambda s, f: layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + f)
+            n = layer.query(tn.TN_QUERY_NUM_STEPS)
+            fl = layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
+        return {"n_steps": n, "flops_tok": fl, "q": qq,
+                "step_flops": [qq(s, 3) for s in range(n)],
+                # algorithmic bytes of a step per token: read its [rows, K] input, write its [rows, cols]
+                # output (bf16), plus its packed parameter tensor once per launch
+                "step_io_bytes": [esize * qq(s, 0) * (qq(s, 1) + qq(s, 2)) for s in range(n)],
+                "step_param_bytes": [esize * qq(s, 1) * qq(s, 2) for s in range(n)]}
+
+    view = plan_view(tokens)
+    flops_tok, n_steps, q = view["flops_tok"], view["n_steps"], view["q"]
+    step_flops, step_io_bytes, step_param_bytes = view["step_flops"], view["step_io_bytes"], view["step_param_bytes"]
 
     for _ in range(args.warmup):
         layer.forward(x, out=y)
@@ -336,6 +365,9 @@ def main() -> int:
     # then the per-kernel durations of the same calls from the library's HIP events
     def decode_stats(t):
         t = min(t, tokens)
+        v = plan_view(t)
+        n_steps, flops_tok = v["n_steps"], v["flops_tok"]
+        step_flops, step_io_bytes, step_param_bytes = v["step_flops"], v["step_io_bytes"], v["step_param_bytes"]
         xt = x[:t].contiguous()
         yt = torch.empty((t, layer.M), dtype=tdt, device="cuda")
         for _ in range(20):
@@ -408,7 +440,7 @@ def main() -> int:
         for c in copies[1:]:
             c.close()
         return {"tokens": t, "instances": instances, "us_per_layer_call": us, "tokens_per_s": t * 1e6 / us,
-                "param_GBps": packed / us / 1e3, "tflops": flops_tok * t / us / 1e6,
+                "param_GBps": packed / us / 1e3, "tflops": plan_view(t)["flops_tok"] * t / us / 1e6,
                 "param_MB_all_instances": packed * instances / 1e6, "replay_equals_eager": ok}
 
     dec1 = decode_stats(1)
@@ -435,7 +467,8 @@ def main() -> int:
                                f"{tokens} tokens, {spec.dtype} storage, fp32 accumulate"
                                + (", applied transposed (Y = X W)" if args.transpose else ""),
                    "tokens": tokens, "chunk_tokens": chunk,
-                   "create_time_merges": layer.query(tn.TN_QUERY_NUM_MERGES)},
+                   "create_time_merges": layer.query(tn.TN_QUERY_NUM_MERGES),
+                   "lazy_merge_from_tokens": lazy_min},
         "flops_per_token": flops_tok,
         "tflops_factorised": flops_tok * tokens_per_s / 1e12,
         "gpu_ms_per_step_events": ms_per_step,

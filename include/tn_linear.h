@@ -70,6 +70,11 @@ extern "C" {
 #define TN_FLAG_NO_SMALL_CHAIN (1 << 20) /* never run a small layer as one launch with all its tensors in LDS */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */
+#define TN_FLAG_MERGE_HALVES  (1 << 22)  /* like TN_FLAG_MERGE_GROW, but whatever the size (up to 1e9 elements): contract
+                                       parameter tensors at create time until two are left (a ring of four cores
+                                       becomes two half rings), and keep them. This is the plan large calls of a
+                                       default layer run on with the merged tensors rebuilt per call
+                                       (TN_QUERY_LAZY_MIN_TOKENS); with this flag every call runs on it. */
 #define TN_FLAG_NO_LAZY_MERGE (1 << 21)  /* never run large calls on a merged plan rebuilt in the workspace (see
                                        TN_QUERY_LAZY_MIN_TOKENS): every call runs the compact steps */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
@@ -99,7 +104,7 @@ extern "C" {
                                            intermediate in registers (e.g. a ring contracted into two half
                                            rings under TN_FLAG_MERGE_GROW) */
 #define TN_QUERY_LAZY_MIN_TOKENS   12   /* handle only: 0, or the token count from which a call runs on a lazily
-                                           merged plan: the plan TN_FLAG_MERGE_GROW would give (two half rings for
+                                           merged plan: the plan TN_FLAG_MERGE_HALVES would give (two half rings for
                                            a ring of four cores) is cheaper and fits the Kronecker-sum kernel, so
                                            such calls rebuild its tensors in the workspace from the caller's
                                            compact ones (microseconds) and run that one launch; the layer stores

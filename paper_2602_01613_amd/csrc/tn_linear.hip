@@ -546,6 +546,7 @@ int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, int
         case 2: return kron_entry<tn::kKronConfig[2][0], tn::kKronConfig[2][1], tn::kKronConfig[2][2]>(p, grid, st, at, ks0, o2t, smem);
         case 3: return kron_entry<tn::kKronConfig[3][0], tn::kKronConfig[3][1], tn::kKronConfig[3][2]>(p, grid, st, at, ks0, o2t, smem);
         case 4: return kron_entry<tn::kKronConfig[4][0], tn::kKronConfig[4][1], tn::kKronConfig[4][2]>(p, grid, st, at, ks0, o2t, smem);
+        case 5: return kron_entry<tn::kKronConfig[5][0], tn::kKronConfig[5][1], tn::kKronConfig[5][2]>(p, grid, st, at, ks0, o2t, smem);
         default: return TN_ERR_INVALID_ARG;
     }
 }
@@ -691,12 +692,12 @@ void fill_gen_dims(GenDims* g, const std::vector<tn::GatherDim>& d) {
 int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
     if (h->plan.dtype != TN_DTYPE_BF16 || h->pair || h->kron || h->small_chain) return TN_OK;
     if (desc->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_MERGE | TN_FLAG_MERGE_GROW |
-                       TN_FLAG_NO_LAZY_MERGE))
+                       TN_FLAG_MERGE_HALVES | TN_FLAG_NO_LAZY_MERGE))
         return TN_OK;
     if (((desc->flags >> TN_FLAG_VARIANT_SHIFT) & 0xff) != 0) return TN_OK;      // tuning overrides: keep what they ask
     if (desc->max_tokens < kLazyMinTokens) return TN_OK;
     tn_linear_desc grow = *desc;
-    grow.flags |= TN_FLAG_MERGE_GROW;
+    grow.flags |= TN_FLAG_MERGE_HALVES;
     tn::Plan& q = h->lazy_plan;
     if (tn::make_plan(&grow, &q) != TN_OK || q.steps.size() != 2 || q.merges.size() != 2 || q.flops >= h->plan.flops)
         return TN_OK;

@@ -522,9 +522,10 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
 
 // Merge pairs of parameter tensors whose contraction is no larger than the pair. Returns the
 // number of merges made. Only indices owned by exactly these two tensors are summed.
-inline int merge_pass(Plan* p, double budget_elems = 0) {
+inline int merge_pass(Plan* p, double budget_elems = 0, int min_tensors = 1) {
     int made = 0;
     for (;;) {
+        if (int(p->tensors.size()) <= min_tensors) break;
         int best_a = -1, best_b = -1;
         double best_ratio = 1e300;
         int n = int(p->tensors.size());
@@ -648,8 +649,8 @@ struct KronDims {
     bool x_vec8 = true;
 };
 
-constexpr int kKronConfigs = 5;
-constexpr int kKronConfig[kKronConfigs][3] = {{5, 10, 3}, {3, 4, 5}, {4, 4, 3}, {2, 6, 5}, {2, 8, 3}};
+constexpr int kKronConfigs = 6;
+constexpr int kKronConfig[kKronConfigs][3] = {{5, 10, 3}, {3, 4, 5}, {4, 4, 3}, {2, 6, 5}, {2, 8, 3}, {2, 6, 1}};
 
 inline bool kron_shape(const Plan& p, KronDims* d) {
     if (p.dtype != TN_DTYPE_BF16 || p.steps.size() != 2) return false;
@@ -723,7 +724,11 @@ inline bool chain2_shape(const Plan& p, const Step& a, const Step& b, int* cfg, 
     return true;
 }
 
+// TN_FLAG_MERGE_HALVES: merges may grow up to kMaxHalvesElems elements in total but stop at two parameter tensors.
+constexpr double kMaxHalvesElems = 1.0e9;
+
 inline int make_plan(const tn_linear_desc* d, Plan* p) {
+    const double halves_budget = (d->flags & TN_FLAG_MERGE_HALVES) ? kMaxHalvesElems : 0.0;
     int rc = build_network(d, p);
     if (rc != TN_OK) return rc;
     p->flags = d->flags;
@@ -737,7 +742,8 @@ inline int make_plan(const tn_linear_desc* d, Plan* p) {
         q.steps.clear();
         // TN_FLAG_MERGE_GROW: merges may add parameters up to a quarter of the dense matrix
         double budget = (d->flags & TN_FLAG_MERGE_GROW) ? double(p->M) * double(p->N) / 4.0 : 0.0;
-        if (merge_pass(&q, budget) > 0) {
+        if (halves_budget > 0) budget = halves_budget;
+        if (merge_pass(&q, budget, halves_budget > 0 ? 2 : 1) > 0) {
             std::vector<int> qorder;
             if (choose_order(q, &qorder) == TN_OK && build_steps(&q, qorder) == TN_OK && q.flops < p->flops)
                 *p = q;

@@ -352,7 +352,7 @@ KRON_CASES = [
     (tn.TN_FORMAT_TT, (70, 150), (4, 32), (1, 40, 1), KRON_FORCE, 4),          # 150 values of o1: three chunks, ragged
     (tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), KRON_FORCE, 2),          # A = 120: four tiles of a, ragged
     (tn.TN_FORMAT_TR, (4, 6, 5, 8), (2, 5, 7, 8), (3, 4, 2, 5, 3),             # a ring as two half rings, x gathered
-     KRON_FORCE | tn.TN_FLAG_MERGE_GROW | tn.TN_FLAG_NO_SMALL_CHAIN, 4),       # in 16-byte pieces, K0 = 56
+     KRON_FORCE | tn.TN_FLAG_MERGE_GROW | tn.TN_FLAG_NO_SMALL_CHAIN, 5),       # in 16-byte pieces, K0 = 56
     (tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, tn.TN_FLAG_MERGE_GROW, 1),   # taken without forcing
     (tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, tn.TN_FLAG_MERGE_GROW, 4),   # x gathered element-wise
 ]
@@ -402,6 +402,81 @@ def test_kronecker_sum_kernel_caller_workspace(dense_w):
             y = to_host(layer(to_dev(x, "bf16")))
             assert O.rel_max_err(y, O.apply_linear(w, x)) <= TOL["bf16"], (ws_bytes, tokens)
         layer.close()
+
+
+LAZY_CASES = [
+    # rings of four cores whose large calls run on the two-half-ring plan rebuilt in the workspace
+    ((8, 10, 8, 8), (10, 16, 10, 16), (32,) * 5),       # the down_proj workload
+    ((10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5),       # three chunks of o1, x gathered element-wise
+    ((8, 16, 8, 8), (8, 10, 8, 8), (48,) * 5),          # 2304 values of the shared bond: over a quarter of dense
+    ((4, 8, 4, 8), (8, 10, 8, 8), (32,) * 5),           # 32 x 32 outputs per term: the smallest instantiation
+]
+
+
+@pytest.mark.parametrize("case", range(len(LAZY_CASES)))
+def test_lazily_merged_ring(case):
+    """A default ring layer stores its compact cores; calls of 16 tokens or more rebuild the half-ring
+    slices in the workspace and run the Kronecker-sum kernel. Both regimes against the oracle, the lazy one
+    against the compact steps and against a layer that keeps the merged tensors, and again after a small
+    call has used the same workspace."""
+    om, im, rk = LAZY_CASES[case]
+    spec = _spec(tn.TN_FORMAT_TR, "bf16", om, im, rk)
+    ts = wl.make_tensors(spec, 40 + case)
+    w = O.dense_weight(spec.format, ts, len(om))
+    layer = make_layer(spec, ts, 64)
+    assert layer.query(tn.TN_QUERY_NUM_STEPS) == 4 and layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 16
+    assert 0 < layer.query(tn.TN_QUERY_LAZY_FLOPS_PER_TOKEN) < layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
+    compact = make_layer(spec, ts, 64, flags=tn.TN_FLAG_NO_LAZY_MERGE)
+    assert compact.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 0
+    stored = make_layer(spec, ts, 64, flags=tn.TN_FLAG_MERGE_HALVES)
+    assert stored.query(tn.TN_QUERY_NUM_STEPS) == 2 and stored.query(tn.TN_QUERY_STEP_BASE + 6) == 4
+    first = None
+    for tokens in (40, 3, 15, 16, 40):
+        print(f"lazy case {case} tokens {tokens}", flush=True)
+        x = wl.make_x(spec, tokens, 40 + case)
+        xd = to_dev(x, "bf16")
+        yd = layer(xd)
+        torch.cuda.synchronize()
+        y = to_host(yd)
+        ref = O.apply_linear(w, x)
+        assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
+        yc = to_host(compact(xd))
+        assert O.rel_max_err(yc, ref) <= TOL["bf16"], (case, tokens)
+        if tokens < 16:
+            assert np.array_equal(y, yc)                      # same steps, same bits
+        else:
+            assert O.rel_max_err(y, yc) <= 1e-2
+            assert O.rel_max_err(y, to_host(stored(xd))) <= 1e-2     # rebuilt vs stored slices
+        if tokens == 40:
+            if first is None:
+                first = yd.clone()
+            else:
+                assert torch.equal(first, yd)                 # the workspace was reused in between
+    for l in (layer, compact, stored):
+        l.close()
+
+
+def test_lazily_merged_ring_workspace_limits(dense_w):
+    """The slices of a lazily merged plan live in the workspace: in a caller's block they share the space of
+    the two intermediate buffers; a workspace limit too small for them switches the lazy plan off and every
+    call runs the compact steps."""
+    spec, ts, w = dense_w(3)
+    dev = [to_dev(t, "bf16") for t in ts]
+    x = wl.make_x(spec, 20, 3)
+    ref = O.apply_linear(w, x)
+    for ws_bytes, lazy in ((256 << 20, True),):
+        block = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev, 20,
+                            workspace=block)
+        assert (layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) > 0) == lazy
+        for tokens in (20, 2, 20):
+            y = to_host(layer(to_dev(x[:tokens], "bf16")))
+            assert O.rel_max_err(y, ref[:tokens]) <= TOL["bf16"], (ws_bytes, tokens)
+        layer.close()
+    small = make_layer(spec, ts, 20, workspace_limit_bytes=32 << 20)
+    assert small.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 0
+    assert O.rel_max_err(to_host(small(to_dev(x, "bf16"))), ref) <= TOL["bf16"]
+    small.close()
 
 
 CHAIN2_CASES = [

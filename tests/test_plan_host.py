@@ -216,7 +216,12 @@ def test_kronecker_sum_plans():
     small = (tn.TN_FORMAT_TT, (40, 36), (10, 64), (1, 40, 1))
     assert q(*small) == 0 and q(*small, force) == 5
     assert q(tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), force) == 3                  # <4, 4, 3>
-    assert q(tn.TN_FORMAT_TT, (8, 12), (16, 8), (1, 24, 1), force) == 5                    # x gathered element-wise
+    assert q(tn.TN_FORMAT_TT, (8, 12), (16, 8), (1, 24, 1), force) == 6                    # <2, 6, 1>; x gathered element-wise
+    # the plan large calls of a default ring layer run on: two half rings whatever their size
+    halves = tn.TN_FLAG_MERGE_HALVES
+    assert q(ring.format, ring.out_modes, ring.in_modes, (96,) * 5, grow) == 0             # over a quarter of dense
+    assert q(ring.format, ring.out_modes, ring.in_modes, (96,) * 5, halves) == 1
+    assert q(tn.TN_FORMAT_TR, (4, 8, 4, 8), (8, 10, 8, 8), (32,) * 5, halves) == 6
     assert q(tn.TN_FORMAT_TT, (20, 6), (24, 10), (1, 40, 1), force) == 0                   # K0 = 10: not 8-aligned
 
 
