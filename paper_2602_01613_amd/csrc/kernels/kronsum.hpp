@@ -11,7 +11,7 @@
 // As two launches the intermediate Z[t][o1][a][rho] (A*O1*P values per token, 21 MB for the ring
 // 25600 -> 5120 at rank 32) crosses HBM twice and both launches are bound by it (Section 3.5: the time
 // goes to memory locality, not to FLOPs). Here every term of the sum over rho is finished on chip:
-//   * a wave owns one token and a chunk of 64 values of o1; X_t sits in its registers as MFMA row
+//   * a wave owns one token and a chunk of 32*O1T values of o1; X_t sits in its registers as MFMA row
 //     operands (a along the rows, k contracted) for the whole launch;
 //   * per rho the workgroup (4 waves = 4 tokens) streams the two slices B0[(o1 chunk, rho)][:] and
 //     B1[:][(:, rho)] (tens of KB, stored contiguously per rho at create time by the repack kernels) into
@@ -25,12 +25,13 @@
 // Few tokens: the range of rho is split over workgroups, each writes fp32 partial sums, and a second
 // small kernel adds them in a fixed order.
 // Template: AT tiles of 32 values of a, KS0 k-steps of 16 in the first contraction, O2T tiles of 32
-// values of o2; smaller shapes run on zero padding (the repacked slices hold zeros there).
+// values of o2, O1T tiles of 32 values of o1 per chunk; smaller shapes run on zero padding (the repacked
+// slices hold zeros there).
 // ---------------------------------------------------------------------------------------------
 struct KronArgs {
     const void* X;
     void* Y;               // bf16 output, or fp32 partial sums [split][tokens][M] when n_splits > 1
-    const void* H0f;       // [o1 chunk][rho][o1 tile (2)][k-step (KS0)] blocks of 512
+    const void* H0f;       // [o1 chunk][rho][o1 tile (O1T)][k-step (KS0)] blocks of 512
     const void* H1f;       // [rho][o2 tile (O2T)][a k-step (2*AT)] blocks of 512
     const int32_t* xrow;   // offset of a in a token of x (null: a*K0)
     const int32_t* xcol;   // offset of k (null: k)
@@ -38,15 +39,15 @@ struct KronArgs {
     const int32_t* ycol;   // output offset of o2
     int64_t N, M;          // elements per token of X and Y
     int32_t tokens, A, K0, O1, C1, P;
-    int32_t n_chunks;      // ceil(O1 / 64)
+    int32_t n_chunks;      // ceil(O1 / (32*O1T))
     int32_t n_splits;      // workgroups sharing one (token quad, chunk): each takes rho_per_split values of rho
     int32_t rho_per_split;
     int32_t x_vec8;        // 8 consecutive k of one a are one aligned 16-byte piece of x
 };
 
-template <int AT, int KS0, int O2T>
+template <int AT, int KS0, int O2T, int O1T>
 struct KronShape {
-    static constexpr int NB0 = 2 * KS0;                 // blocks of 1 KB per rho: first slice
+    static constexpr int NB0 = O1T * KS0;               // blocks of 1 KB per rho: first slice
     static constexpr int NB1 = O2T * 2 * AT;            // second slice
     static constexpr int L = (NB0 + NB1 + 3) / 4;       // direct-to-LDS loads per wave and stage
     static constexpr int STAGE_BYTES = 4 * L * 1024;
@@ -54,21 +55,21 @@ struct KronShape {
     static constexpr size_t SMEM = size_t(NS) * STAGE_BYTES;
 };
 
-// H0f[((chunk*P + rho)*2*KS0 + o1t*KS0 + ks)*512 + l*8 + e] = B0[c = o1*P + rho][k = 16*ks + 8*(l/32) + e],
-// o1 = 64*chunk + 32*o1t + l%32; zero outside the tensor.
+// H0f[((chunk*P + rho)*O1T*KS0 + o1t*KS0 + ks)*512 + l*8 + e] = B0[c = o1*P + rho][k = 16*ks + 8*(l/32) + e],
+// o1 = 32*O1T*chunk + 32*o1t + l%32; zero outside the tensor.
 __global__ void __launch_bounds__(256) kron_repack0_kernel(const bf16_t* src, bf16_t* dst, int n_chunks, int P, int KS0,
-                                                           int O1, int K0, int nks_src) {
-    const int64_t total = int64_t(n_chunks) * P * 2 * KS0 * 512;
+                                                           int O1T, int O1, int K0, int nks_src) {
+    const int64_t total = int64_t(n_chunks) * P * O1T * KS0 * 512;
     for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
         int e = int(i & 7), l = int(i >> 3) & 63;
         int64_t blk = i >> 9;
         int ks = int(blk % KS0);
         blk /= KS0;
-        int o1t = int(blk & 1);
-        blk >>= 1;
+        int o1t = int(blk % O1T);
+        blk /= O1T;
         int rho = int(blk % P);
         int chunk = int(blk / P);
-        int o1 = 64 * chunk + 32 * o1t + (l & 31);
+        int o1 = 32 * O1T * chunk + 32 * o1t + (l & 31);
         int k = 16 * ks + 8 * (l >> 5) + e;
         dst[i] = (o1 < O1 && k < K0) ? src[bfrag_offset(o1 * P + rho, k, nks_src)] : bf16_t(0.f);
     }
@@ -92,9 +93,9 @@ __global__ void __launch_bounds__(256) kron_repack1_kernel(const bf16_t* src, bf
     }
 }
 
-template <int AT, int KS0, int O2T>
+template <int AT, int KS0, int O2T, int O1T>
 __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
-    using S = KronShape<AT, KS0, O2T>;
+    using S = KronShape<AT, KS0, O2T, O1T>;
     constexpr int L = S::L, NS = S::NS, NB0 = S::NB0, NB1 = S::NB1, STAGE_BYTES = S::STAGE_BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
 
@@ -161,11 +162,11 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
         }
     };
 
-    floatx16 acc[O2T][2];
+    floatx16 acc[O2T][O1T];
 #pragma unroll
     for (int j = 0; j < O2T; ++j)
 #pragma unroll
-        for (int o = 0; o < 2; ++o)
+        for (int o = 0; o < O1T; ++o)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][o][v] = 0.f;
 
@@ -178,7 +179,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
         if (r + 2 < n_rho) issue(rho_begin + r + 2, (r + 2) % NS);
         const unsigned char* sb = dyn_smem + (r % NS) * STAGE_BYTES + lane * 16;
 #pragma unroll
-        for (int o = 0; o < 2; ++o) {
+        for (int o = 0; o < O1T; ++o) {
             bf16x8 h0[KS0];
 #pragma unroll
             for (int ks = 0; ks < KS0; ++ks) h0[ks] = *reinterpret_cast<const bf16x8*>(sb + (o * KS0 + ks) * 1024);
@@ -212,15 +213,15 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
 #pragma unroll
         for (int j = 0; j < O2T; ++j)
 #pragma unroll
-            for (int o = 0; o < 2; ++o) asm volatile("" : "+a"(acc[j][o]));
+            for (int o = 0; o < O1T; ++o) asm volatile("" : "+a"(acc[j][o]));
     }
 
-    // lane l, register v of acc[j][o]: o2 = 32*j + 8*(v/4) + 4*(l/32) + v%4, o1 = 64*chunk + 32*o + l%32
+    // lane l, register v of acc[j][o]: o2 = 32*j + 8*(v/4) + 4*(l/32) + v%4, o1 = 32*O1T*chunk + 32*o + l%32
     if (t >= p.tokens) return;
-    int yr[2];
+    int yr[O1T];
 #pragma unroll
-    for (int o = 0; o < 2; ++o) {
-        const int o1 = 64 * chunk + 32 * o + (lane & 31);
+    for (int o = 0; o < O1T; ++o) {
+        const int o1 = 32 * O1T * chunk + 32 * o + (lane & 31);
         yr[o] = o1 < p.O1 ? p.yrow[o1] : -1;
     }
     bf16_t* yb = static_cast<bf16_t*>(p.Y) + int64_t(t) * p.M;
@@ -233,7 +234,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
             if (o2 >= p.C1) continue;
             const int yc = p.ycol[o2];
 #pragma unroll
-            for (int o = 0; o < 2; ++o) {
+            for (int o = 0; o < O1T; ++o) {
                 if (yr[o] < 0) continue;
                 if (p.n_splits > 1) yf[yr[o] + yc] = acc[j][o][v];
                 else yb[yr[o] + yc] = bf16_t(acc[j][o][v]);
@@ -314,13 +315,13 @@ struct KronGenArgs {
     int64_t merged_C;
     int32_t Sp;            // padded length of the shared indices, a multiple of 8
     int32_t which;         // 0: first slice array (H0f), 1: second (H1f)
-    int32_t n_chunks, P, KS0, O1, K0;        // layout of H0f
+    int32_t n_chunks, P, KS0, O1T, O1, K0;   // layout of H0f
     int32_t O2T, AT, C1, A;                  // layout of H1f
 };
 
 // One thread per 16-byte piece (8 consecutive elements) of a slice array.
 __global__ void __launch_bounds__(256) kron_generate_kernel(KronGenArgs p) {
-    const int64_t pieces = p.which == 0 ? int64_t(p.n_chunks) * p.P * 2 * p.KS0 * 64 : int64_t(p.P) * p.O2T * 2 * p.AT * 64;
+    const int64_t pieces = p.which == 0 ? int64_t(p.n_chunks) * p.P * p.O1T * p.KS0 * 64 : int64_t(p.P) * p.O2T * 2 * p.AT * 64;
     const bf16_t* Pc = static_cast<const bf16_t*>(p.Pc);
     const bf16_t* Qc = static_cast<const bf16_t*>(p.Qc);
     bf16x8* dst = static_cast<bf16x8*>(p.dst);
@@ -336,11 +337,11 @@ __global__ void __launch_bounds__(256) kron_generate_kernel(KronGenArgs p) {
         if (p.which == 0) {
             int ks = int(blk % p.KS0);
             blk /= p.KS0;
-            int o1t = int(blk & 1);
-            blk >>= 1;
+            int o1t = int(blk % p.O1T);
+            blk /= p.O1T;
             int rho = int(blk % p.P);
             int chunk = int(blk / p.P);
-            int o1 = 64 * chunk + 32 * o1t + (l & 31);
+            int o1 = 32 * p.O1T * chunk + 32 * o1t + (l & 31);
             k0 = 16 * ks + 8 * (l >> 5);
             c0 = int64_t(o1) * p.P + rho;
             row_inside = o1 < p.O1;

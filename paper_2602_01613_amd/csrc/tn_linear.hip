@@ -520,36 +520,45 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
 // added by kron_reduce_kernel).
 constexpr int64_t kKronMinTokens = 1;
 
-template <int AT, int KS0, int O2T>
-int kron_entry(const KronArgs* p, uint32_t grid, hipStream_t st, int* at, int* ks0, int* o2t, size_t* smem) {
-    using S = KronShape<AT, KS0, O2T>;
-    if (at) {
-        *at = AT;
-        *ks0 = KS0;
-        *o2t = O2T;
-        *smem = S::SMEM;
+struct KronTiles {
+    int at = 0, ks0 = 0, o2t = 0, o1t = 0;
+    size_t smem = 0;
+};
+
+template <int AT, int KS0, int O2T, int O1T>
+int kron_entry(const KronArgs* p, uint32_t grid, hipStream_t st, KronTiles* tiles) {
+    using S = KronShape<AT, KS0, O2T, O1T>;
+    if (tiles) {
+        *tiles = KronTiles{AT, KS0, O2T, O1T, S::SMEM};
         return TN_OK;
     }
     if (!p)         // configuration call (create time)
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T>),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess
                    ? TN_OK : TN_ERR_HIP;
-    hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T>), dim3(grid), dim3(256), S::SMEM, st, *p);
     return TN_OK;
 }
 
-int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, int* at = nullptr, int* ks0 = nullptr,
-                  int* o2t = nullptr, size_t* smem = nullptr) {
+#define TN_KRON_CASE(i)                                                                                        \
+    case i:                                                                                                   \
+        return kron_entry<tn::kKronConfig[i][0], tn::kKronConfig[i][1], tn::kKronConfig[i][2], tn::kKronConfig[i][3]>( \
+            p, grid, st, tiles);
+
+int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, KronTiles* tiles = nullptr) {
+    static_assert(tn::kKronConfigs == 7, "one case per instantiation");
     switch (cfg) {
-        case 0: return kron_entry<tn::kKronConfig[0][0], tn::kKronConfig[0][1], tn::kKronConfig[0][2]>(p, grid, st, at, ks0, o2t, smem);
-        case 1: return kron_entry<tn::kKronConfig[1][0], tn::kKronConfig[1][1], tn::kKronConfig[1][2]>(p, grid, st, at, ks0, o2t, smem);
-        case 2: return kron_entry<tn::kKronConfig[2][0], tn::kKronConfig[2][1], tn::kKronConfig[2][2]>(p, grid, st, at, ks0, o2t, smem);
-        case 3: return kron_entry<tn::kKronConfig[3][0], tn::kKronConfig[3][1], tn::kKronConfig[3][2]>(p, grid, st, at, ks0, o2t, smem);
-        case 4: return kron_entry<tn::kKronConfig[4][0], tn::kKronConfig[4][1], tn::kKronConfig[4][2]>(p, grid, st, at, ks0, o2t, smem);
-        case 5: return kron_entry<tn::kKronConfig[5][0], tn::kKronConfig[5][1], tn::kKronConfig[5][2]>(p, grid, st, at, ks0, o2t, smem);
+        TN_KRON_CASE(0)
+        TN_KRON_CASE(1)
+        TN_KRON_CASE(2)
+        TN_KRON_CASE(3)
+        TN_KRON_CASE(4)
+        TN_KRON_CASE(5)
+        TN_KRON_CASE(6)
         default: return TN_ERR_INVALID_ARG;
     }
 }
+#undef TN_KRON_CASE
 
 struct KronGeom {
     int n_chunks = 1, n_splits = 1, rho_per_split = 1;
@@ -558,7 +567,8 @@ struct KronGeom {
 
 KronGeom kron_geometry(const tn_linear_s* h, const tn::KronDims& d, int64_t tokens, int64_t partial_cap) {
     KronGeom g;
-    g.n_chunks = int((d.O1 + 63) / 64);
+    const int o1_chunk = 32 * tn::kKronConfig[d.cfg][3];
+    g.n_chunks = int((d.O1 + o1_chunk - 1) / o1_chunk);
     g.quads = (tokens + 3) / 4;
     int64_t base = g.quads * g.n_chunks;
     int64_t want = std::max<int64_t>(1, (2 * int64_t(h->num_cus) + base - 1) / base);
@@ -579,18 +589,18 @@ int prepare_kron(tn_linear_s* h, hipStream_t st) {
     const DevStep& s0 = h->steps[0];
     const DevStep& s1 = h->steps[1];
     if (s0.variant == VAR_SCALAR || s1.variant == VAR_SCALAR) return TN_OK;
-    int at = 0, ks0 = 0, o2t = 0;
-    size_t smem = 0;
-    if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &at, &ks0, &o2t, &smem) != TN_OK) return TN_OK;
-    const int n_chunks = int((d.O1 + 63) / 64);
-    const int64_t e0 = int64_t(n_chunks) * d.P * 2 * ks0 * 512;
+    KronTiles kt;
+    if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &kt) != TN_OK) return TN_OK;
+    const int at = kt.at, ks0 = kt.ks0, o2t = kt.o2t, o1t = kt.o1t;
+    const int n_chunks = int((d.O1 + 32 * o1t - 1) / (32 * o1t));
+    const int64_t e0 = int64_t(n_chunks) * d.P * o1t * ks0 * 512;
     const int64_t e1 = d.P * int64_t(o2t) * 2 * at * 512;
     if (hipMalloc(&h->kron_h0f, size_t(e0) * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
     if (hipMalloc(&h->kron_h1f, size_t(e1) * sizeof(bf16_t)) != hipSuccess) return TN_ERR_ALLOC;
     h->packed_bytes += (e0 + e1) * int64_t(sizeof(bf16_t));
     hipLaunchKernelGGL(kron_repack0_kernel, dim3(uint32_t(std::min<int64_t>((e0 + 255) / 256, 8192))), dim3(256), 0, st,
                        static_cast<const bf16_t*>(s0.packed), static_cast<bf16_t*>(h->kron_h0f), n_chunks, int(d.P), ks0,
-                       int(d.O1), int(d.K0), s0.Kp >> 4);
+                       o1t, int(d.O1), int(d.K0), s0.Kp >> 4);
     hipLaunchKernelGGL(kron_repack1_kernel, dim3(uint32_t(std::min<int64_t>((e1 + 255) / 256, 8192))), dim3(256), 0, st,
                        static_cast<const bf16_t*>(s1.packed), static_cast<bf16_t*>(h->kron_h1f), int(d.P), o2t, at,
                        int(d.C1), int(d.A), s1.Kp >> 4);
@@ -664,7 +674,7 @@ int launch_kron_eager(const tn_linear_s* h, const void* x, void* y, int64_t toke
 int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
     for (int w = 0; w < 2; ++w) {
         const KronGenArgs& g = h->lazy_gen[w];
-        const int64_t pieces = w == 0 ? int64_t(g.n_chunks) * g.P * 2 * g.KS0 * 64 : int64_t(g.P) * g.O2T * 2 * g.AT * 64;
+        const int64_t pieces = w == 0 ? int64_t(g.n_chunks) * g.P * g.O1T * g.KS0 * 64 : int64_t(g.P) * g.O2T * 2 * g.AT * 64;
         hipLaunchKernelGGL(kron_generate_kernel, dim3(uint32_t(std::min<int64_t>((pieces + 255) / 256, 1 << 20))), dim3(256),
                            0, st, g);
     }
@@ -711,9 +721,9 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
         if (mo[w]->p_slot >= q.n_caller_tensors || mo[w]->q_slot >= q.n_caller_tensors) return TN_OK;
         if (mo[w]->kp.empty() || q.steps[size_t(w)].trace_extent != 1) return TN_OK;
     }
-    int at = 0, ks0 = 0, o2t = 0;
-    size_t smem = 0;
-    if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &at, &ks0, &o2t, &smem) != TN_OK) return TN_OK;
+    KronTiles kt;
+    if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &kt) != TN_OK) return TN_OK;
+    const int at = kt.at, ks0 = kt.ks0, o2t = kt.o2t, o1t = kt.o1t;
     // the four source matrices (shared indices innermost), written from the caller's tensors
     const int32_t sp_len[2] = {round_up(int(mo[0]->K), 8), round_up(int(mo[1]->K), 8)};
     for (int w = 0; w < 2; ++w)
@@ -755,8 +765,8 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
     }
     h->lazy_yrow = h->lazy_tables + n_xrow + n_xcol;
     h->lazy_ycol = h->lazy_yrow + s1.crow.size();
-    const int n_chunks = int((d.O1 + 63) / 64);
-    const int64_t e0 = int64_t(n_chunks) * d.P * 2 * ks0 * 512;
+    const int n_chunks = int((d.O1 + 32 * o1t - 1) / (32 * o1t));
+    const int64_t e0 = int64_t(n_chunks) * d.P * o1t * ks0 * 512;
     const int64_t e1 = d.P * int64_t(o2t) * 2 * at * 512;
     h->lazy_h1_offset = (e0 * 2 + 255) & ~int64_t(255);
     h->lazy_slice_bytes = h->lazy_h1_offset + ((e1 * 2 + 255) & ~int64_t(255));
@@ -774,6 +784,7 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
         g.n_chunks = n_chunks;
         g.P = int32_t(d.P);
         g.KS0 = ks0;
+        g.O1T = o1t;
         g.O1 = int32_t(d.O1);
         g.K0 = int32_t(d.K0);
         g.O2T = o2t;

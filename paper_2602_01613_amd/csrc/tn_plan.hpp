@@ -639,8 +639,8 @@ inline bool pair_chainable(const Plan& p) {
 // Y[t][o1][o2] = sum_{a, rho} Z[t][o1][a][rho] B1[o2][(a, rho)]  (a sum over the shared bond rho of Kronecker
 // products), laid out the way the Kronecker-sum kernel walks it? Rows a of step 0 (K0 a multiple of 8; x plain
 // or gathered), columns (o1, rho) with rho innermost; step 1 reads rows
-// o1 with K = (a, rho). cfg names the instantiation <AT tiles of a, KS0 k-steps, O2T tiles of o2> that holds the
-// shape with the least padding. Unless the flags force the kernel (variant id 20) the shape must also be one
+// o1 with K = (a, rho). cfg names the instantiation <AT tiles of a, KS0 k-steps, O2T tiles of o2, O1T tiles of
+// o1 per chunk> that holds the shape with the least padding. Unless the flags force the kernel (variant id 20) the shape must also be one
 // where it pays: an intermediate of at least 32768 values per token, a bond of at least 8, and at least 35 %
 // of the padded MFMA work real.
 struct KronDims {
@@ -649,8 +649,9 @@ struct KronDims {
     bool x_vec8 = true;
 };
 
-constexpr int kKronConfigs = 6;
-constexpr int kKronConfig[kKronConfigs][3] = {{5, 10, 3}, {3, 4, 5}, {4, 4, 3}, {2, 6, 5}, {2, 8, 3}, {2, 6, 1}};
+constexpr int kKronConfigs = 7;
+constexpr int kKronConfig[kKronConfigs][4] = {{5, 10, 3, 2}, {3, 4, 5, 2}, {4, 4, 3, 2}, {2, 5, 5, 2},
+                                              {2, 8, 2, 3}, {2, 5, 1, 1}, {3, 4, 4, 2}};
 
 inline bool kron_shape(const Plan& p, KronDims* d) {
     if (p.dtype != TN_DTYPE_BF16 || p.steps.size() != 2) return false;
@@ -677,11 +678,11 @@ inline bool kron_shape(const Plan& p, KronDims* d) {
     }
     int cfg = -1;
     int64_t best = 0;
-    const int64_t n_chunks = (O1 + 63) / 64;
     for (int c = 0; c < kKronConfigs; ++c) {
-        const int64_t at = kKronConfig[c][0], ks0 = kKronConfig[c][1], o2t = kKronConfig[c][2];
+        const int64_t at = kKronConfig[c][0], ks0 = kKronConfig[c][1], o2t = kKronConfig[c][2], o1t = kKronConfig[c][3];
         if (A > 32 * at || K0 > 16 * ks0 || C1 > 32 * o2t) continue;
-        const int64_t mfmas = n_chunks * 2 * at * (ks0 + 2 * o2t);
+        const int64_t n_chunks = (O1 + 32 * o1t - 1) / (32 * o1t);
+        const int64_t mfmas = n_chunks * o1t * at * (ks0 + 2 * o2t);
         if (cfg < 0 || mfmas < best) {
             cfg = c;
             best = mfmas;

@@ -205,18 +205,18 @@ def test_kronecker_sum_plans():
     ring, _ = wl.baseline_spec(3)
     grow, force = tn.TN_FLAG_MERGE_GROW, 20 << tn.TN_FLAG_VARIANT_SHIFT
     assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks) == 0                  # four steps
-    assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow) == 1            # <5, 10, 3>
+    assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow) == 1            # <5, 10, 3, 2>
     assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow | tn.TN_FLAG_NO_PAIR_CHAIN) == 0
     assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow, tn.TN_DTYPE_F32) == 0
-    assert q(ring.format, ring.in_modes[:0] + (10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5, grow) == 4    # <2, 6, 5>
-    assert q(tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, grow) == 2          # <3, 4, 5>
-    assert q(tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, grow) == 5          # <2, 8, 3>
+    assert q(ring.format, ring.in_modes[:0] + (10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5, grow) == 4    # <2, 5, 5, 2>
+    assert q(tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, grow) == 7          # <3, 4, 4, 2>
+    assert q(tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, grow) == 5          # <2, 8, 2, 3>
     train, _ = wl.baseline_spec(1)
     assert q(train.format, train.out_modes, train.in_modes, train.ranks) == 0             # the pair kernel's plan
     small = (tn.TN_FORMAT_TT, (40, 36), (10, 64), (1, 40, 1))
-    assert q(*small) == 0 and q(*small, force) == 5
-    assert q(tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), force) == 3                  # <4, 4, 3>
-    assert q(tn.TN_FORMAT_TT, (8, 12), (16, 8), (1, 24, 1), force) == 6                    # <2, 6, 1>; x gathered element-wise
+    assert q(*small) == 0 and q(*small, force) == 4                                        # <2, 5, 5, 2>
+    assert q(tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), force) == 3                  # <4, 4, 3, 2>
+    assert q(tn.TN_FORMAT_TT, (8, 12), (16, 8), (1, 24, 1), force) == 6                    # <2, 5, 1, 1>; x gathered element-wise
     # the plan large calls of a default ring layer run on: two half rings whatever their size
     halves = tn.TN_FLAG_MERGE_HALVES
     assert q(ring.format, ring.out_modes, ring.in_modes, (96,) * 5, grow) == 0             # over a quarter of dense
