@@ -55,14 +55,18 @@ def cpu_baseline(spec, tensors, sample_tokens, transpose=False):
 
 
 def measured_traffic(args, fused):
-    """HBM bytes per launch of the dominant kernel of the default workload, measured in separate
-    rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy) and recorded in profiles/."""
-    if args.workload != 1 or args.custom or args.no_merge or args.tokens != 8192 or not fused:
+    """HBM-side bytes per launch of the dominant kernel of workloads 1 and 3 at their default settings, measured in
+    separate rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy) and recorded in profiles/."""
+    if (args.custom or args.no_merge or args.merge_grow or args.flags or args.variant or args.transpose
+            or args.no_pair_chain or args.tokens != 8192 or not fused):
         return None
-    path = os.path.join(ROOT, "profiles", "tt_q_proj_prefill8192_hbm_traffic.txt")
+    name, key = {1: ("tt_q_proj_prefill8192_hbm_traffic.txt", "pair"),
+                 3: ("tr_down_proj_prefill8192_hbm_traffic.txt", "kronsum")}.get(args.workload, (None, None))
+    if name is None:
+        return None
     try:
         import re
-        m = re.search(r"TRAFFIC_BYTES_PER_LAUNCH pair = (\d+)", open(path).read())
+        m = re.search(rf"TRAFFIC_BYTES_PER_LAUNCH {key} = (\d+)", open(os.path.join(ROOT, "profiles", name)).read())
         return int(m.group(1)) if m else None
     except OSError:
         return None

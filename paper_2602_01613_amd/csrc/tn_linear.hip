@@ -670,15 +670,18 @@ int launch_kron_eager(const tn_linear_s* h, const void* x, void* y, int64_t toke
 }
 
 // Large calls of a layer with a lazily merged plan: rebuild the two slice arrays in the workspace from the
-// library's copies of the caller's tensors, then run the Kronecker-sum kernel on them.
-int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+// library's copies of the caller's tensors (once per call), then run the Kronecker-sum kernel on them.
+int launch_lazy_generate(const tn_linear_s* h, hipStream_t st) {
     for (int w = 0; w < 2; ++w) {
         const KronGenArgs& g = h->lazy_gen[w];
         const int64_t pieces = w == 0 ? int64_t(g.n_chunks) * g.P * g.O1T * g.KS0 * 64 : int64_t(g.P) * g.O2T * 2 * g.AT * 64;
         hipLaunchKernelGGL(kron_generate_kernel, dim3(uint32_t(std::min<int64_t>((pieces + 255) / 256, 1 << 20))), dim3(256),
                            0, st, g);
     }
-    if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
     KronSetup k{&h->lazy_dims, h->lazy_slices, static_cast<const char*>(h->lazy_slices) + h->lazy_h1_offset,
                 h->lazy_xrow, h->lazy_xcol, h->lazy_yrow, h->lazy_ycol};
     return launch_kron(h, k, x, y, tokens, st);
@@ -1351,6 +1354,10 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
         // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
         // (and, for the Kronecker-sum kernel, keep a call's partial sums within their buffer)
         const int64_t pass = use_pair ? int64_t(1) << 24 : int64_t(1) << 20;
+        if (!use_pair && !use_kron) {
+            int rc = launch_lazy_generate(h, st);          // not part of the profiled launch: a kernel of its own
+            if (rc != TN_OK) return rc;
+        }
         for (int64_t t0 = 0; t0 < tokens; t0 += pass) {
             int64_t nt = std::min(pass, tokens - t0);
             tn_linear_s::ProfRec rec{0, nullptr, nullptr};
