@@ -75,6 +75,8 @@ extern "C" {
                                        becomes two half rings), and keep them. This is the plan large calls of a
                                        default layer run on with the merged tensors rebuilt per call
                                        (TN_QUERY_LAZY_MIN_TOKENS); with this flag every call runs on it. */
+#define TN_FLAG_SCALAR_GENERATE (1 << 23) /* debug: rebuild the slices of a lazily merged plan with the plain FMA kernel
+                                       instead of the MFMA one */
 #define TN_FLAG_NO_LAZY_MERGE (1 << 21)  /* never run large calls on a merged plan rebuilt in the workspace (see
                                        TN_QUERY_LAZY_MIN_TOKENS): every call runs the compact steps */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide

@@ -286,7 +286,7 @@ struct GenDims {
     int64_t str[tn::kMaxGatherDims];
 };
 
-__device__ __forceinline__ int64_t gen_offset(const GenDims& d, int64_t idx) {
+__host__ __device__ __forceinline__ int64_t gen_offset(const GenDims& d, int64_t idx) {
     int64_t off = 0;
     for (int j = d.n - 1; j >= 0; --j) {
         int64_t q = idx / d.ext[j];
@@ -383,5 +383,96 @@ __global__ void __launch_bounds__(256) kron_generate_kernel(KronGenArgs p) {
             out[e] = bf16_t(v);
         }
         dst[i] = out;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same slices by MFMA, one workgroup per value rho of the shared bond. For a fixed rho the entries of
+// a slice array are all products of one row of Pc with one row of Qc: with u numbering the rows of Pc that
+// occur (rho's own contribution taken out) and v those of Qc,
+//     G[u][v] = sum_s Pc[rhoP[rho] + rowP[u]][s] * Qc[rhoQ[rho] + rowQ[v]][s]
+// is a small matrix product (at most 160 x 160 x 128). The workgroup computes it in 32x32 tiles straight
+// from the two source matrices (their rows are MFMA operand fragments as they lie in memory), writes the
+// tiles to LDS as a bf16 matrix, and then assembles the slice's 16-byte pieces from it: a table made at
+// create time gives, for each piece of one rho, the LDS positions of its 8 elements (the map does not
+// depend on rho). 40-120 MFMAs replace the 10^4 dot products of 32-96 terms that the scalar kernel above
+// spends per rho, which matters for calls of tens of tokens at high rank.
+// ---------------------------------------------------------------------------------------------
+struct KronGenMfmaArgs {
+    const void* Pc;            // [rows][Sp], Sp a multiple of 16, zero padded
+    const void* Qc;
+    void* dst;                 // the slice array, in 16-byte pieces
+    const int32_t* rowP;       // U row numbers of Pc (for rho = 0)
+    const int32_t* rowQ;       // V row numbers of Qc
+    const int32_t* rhoP;       // P row offsets: what rho adds to a row number of Pc
+    const int32_t* rhoQ;
+    const void* tab;           // per piece of one rho: 8 x uint16 positions u*LDV + v in the LDS matrix, 0xFFFF = zero
+    int32_t U, V, LDV, Sp;
+    int32_t pieces_per_rho;    // over all chunks
+    int32_t pieces_per_chunk;  // blocks per rho and chunk x 64
+    int32_t P;
+};
+
+template <int KSS /* k-steps of 16 along the shared bond */>
+__global__ void __launch_bounds__(256) kron_generate_mfma_kernel(KronGenMfmaArgs p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    bf16_t* G = reinterpret_cast<bf16_t*>(dyn_smem);
+    const bf16_t* Pc = static_cast<const bf16_t*>(p.Pc);
+    const bf16_t* Qc = static_cast<const bf16_t*>(p.Qc);
+    const int rho = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int UT = (p.U + 31) >> 5, VT = (p.V + 31) >> 5;
+    const int64_t baseP = p.rhoP[rho], baseQ = p.rhoQ[rho];
+    const int kofs = 8 * (lane >> 5);
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = bf16_t(0.f);
+
+    // tiles (ut, vt): wave w takes the column tiles vt = w, w+4, ...
+    for (int vt = wave; vt < VT; vt += 4) {
+        const int v = 32 * vt + (lane & 31);
+        bf16x8 b[KSS];
+        {
+            const bf16_t* row = Qc + (baseQ + (v < p.V ? p.rowQ[v] : 0)) * p.Sp + kofs;
+#pragma unroll
+            for (int ks = 0; ks < KSS; ++ks)
+                b[ks] = (v < p.V && 16 * ks < p.Sp) ? *reinterpret_cast<const bf16x8*>(row + 16 * ks) : zero;
+        }
+        for (int ut = 0; ut < UT; ++ut) {
+            const int u = 32 * ut + (lane & 31);
+            const bf16_t* row = Pc + (baseP + (u < p.U ? p.rowP[u] : 0)) * p.Sp + kofs;
+            floatx16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSS; ++ks) {
+                const bf16x8 a = (u < p.U && 16 * ks < p.Sp) ? *reinterpret_cast<const bf16x8*>(row + 16 * ks) : zero;
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[ks], acc, 0, 0, 0);
+            }
+            // lane l, register i: row u = 32*ut + 8*(i/4) + 4*(l/32) + i%4, column v
+            if (v < p.V) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int uu = 32 * ut + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                    if (uu < p.U) G[uu * p.LDV + v] = bf16_t(acc[i]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+    const uintx4* tab = static_cast<const uintx4*>(p.tab);
+    bf16x8* dst = static_cast<bf16x8*>(p.dst);
+    for (int lp = tid; lp < p.pieces_per_rho; lp += 256) {
+        const uintx4 t = tab[lp];
+        bf16x8 out;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned pos = (t[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+            out[e] = pos == 0xFFFFu ? bf16_t(0.f) : G[pos];
+        }
+        const int chunk = lp / p.pieces_per_chunk, rem = lp - chunk * p.pieces_per_chunk;
+        dst[(int64_t(chunk) * p.P + rho) * p.pieces_per_chunk + rem] = out;
     }
 }

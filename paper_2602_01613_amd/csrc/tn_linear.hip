@@ -107,6 +107,11 @@ struct tn_linear_s {
     int32_t* lazy_tables = nullptr;           // xrow | xcol | yrow | ycol of the merged plan
     const int32_t *lazy_xrow = nullptr, *lazy_xcol = nullptr, *lazy_yrow = nullptr, *lazy_ycol = nullptr;
     KronGenArgs lazy_gen[2];
+    // the same slices by MFMA (one workgroup per value of the bond), where the half's shape allows it
+    bool lazy_mfma[2] = {false, false};
+    KronGenMfmaArgs lazy_gen_mfma[2];
+    size_t lazy_gen_smem[2] = {0, 0};
+    void* lazy_gen_tables[2] = {nullptr, nullptr};
     struct ProfRec { int step; hipEvent_t start, stop; };
     std::vector<ProfRec> prof;
 };
@@ -139,6 +144,8 @@ void free_handle(tn_linear_s* h) {
     for (void* v : h->lazy_sources)
         if (v) (void)hipFree(v);
     if (h->lazy_tables) (void)hipFree(h->lazy_tables);
+    for (void* v : h->lazy_gen_tables)
+        if (v) (void)hipFree(v);
     if (h->lazy_slices && h->owns_workspace) (void)hipFree(h->lazy_slices);
     if (h->small_chain_image) (void)hipFree(h->small_chain_image);
     if (h->owns_workspace) {
@@ -671,14 +678,143 @@ int launch_kron_eager(const tn_linear_s* h, const void* x, void* y, int64_t toke
 
 // Large calls of a layer with a lazily merged plan: rebuild the two slice arrays in the workspace from the
 // library's copies of the caller's tensors (once per call), then run the Kronecker-sum kernel on them.
+constexpr size_t kGenMfmaMaxSmem = 160 * 168 * 2;
+
+int gen_mfma_dispatch(const KronGenMfmaArgs* a, size_t smem, hipStream_t st) {
+    using kern_t = void (*)(KronGenMfmaArgs);
+    static const kern_t kerns[4] = {kron_generate_mfma_kernel<2>, kron_generate_mfma_kernel<4>, kron_generate_mfma_kernel<6>,
+                                    kron_generate_mfma_kernel<8>};
+    if (!a) {               // configuration call (create time)
+        for (kern_t k : kerns)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(kGenMfmaMaxSmem)) != hipSuccess)
+                return TN_ERR_HIP;
+        return TN_OK;
+    }
+    const int idx = (a->Sp + 31) / 32 - 1;
+    if (idx < 0 || idx > 3) return TN_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(kerns[idx], dim3(uint32_t(a->P)), dim3(256), smem, st, *a);
+    return TN_OK;
+}
+
 int launch_lazy_generate(const tn_linear_s* h, hipStream_t st) {
     for (int w = 0; w < 2; ++w) {
+        if (h->lazy_mfma[w]) {
+            int rc = gen_mfma_dispatch(&h->lazy_gen_mfma[w], h->lazy_gen_smem[w], st);
+            if (rc != TN_OK) return rc;
+            continue;
+        }
         const KronGenArgs& g = h->lazy_gen[w];
         const int64_t pieces = w == 0 ? int64_t(g.n_chunks) * g.P * g.O1T * g.KS0 * 64 : int64_t(g.P) * g.O2T * 2 * g.AT * 64;
         hipLaunchKernelGGL(kron_generate_kernel, dim3(uint32_t(std::min<int64_t>((pieces + 255) / 256, 1 << 20))), dim3(256),
                            0, st, g);
     }
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+// Tables of the MFMA form of the slice generation for half w (see kron_generate_mfma_kernel): which rows of the
+// two source matrices a value of the bond uses, and where each element of a slice sits in their product.
+// Returns false (and leaves the scalar kernel in charge) when the half does not fit: more than 160 distinct rows
+// on a side or a shared bond longer than 128.
+bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::KronDims& d, int64_t merged_C, hipStream_t st) {
+    if (g.Sp > 128 || g.Sp % 16) return false;
+    const int64_t P = d.P;
+    struct Elem { int64_t rP, rQ; };
+    const int64_t pieces = w == 0 ? int64_t(g.n_chunks) * g.O1T * g.KS0 * 64 : int64_t(g.O2T) * 2 * g.AT * 64;
+    std::vector<Elem> elems(size_t(pieces) * 8, Elem{-1, -1});
+    for (int64_t lp = 0; lp < pieces; ++lp) {
+        const int l = int(lp & 63);
+        int64_t blk = lp >> 6;
+        for (int e = 0; e < 8; ++e) {
+            int64_t cB, kB;
+            bool inside;
+            if (w == 0) {
+                int64_t b2 = blk;
+                const int ks = int(b2 % g.KS0);
+                b2 /= g.KS0;
+                const int o1t = int(b2 % g.O1T);
+                const int chunk = int(b2 / g.O1T);
+                const int64_t o1 = int64_t(32) * g.O1T * chunk + 32 * o1t + (l & 31);
+                const int64_t k = 16 * ks + 8 * (l >> 5) + e;
+                inside = o1 < d.O1 && k < d.K0;
+                cB = o1 * P;
+                kB = k;
+            } else {
+                const int is = int(blk % (2 * g.AT));
+                const int j = int(blk / (2 * g.AT));
+                const int64_t c = 32 * j + (l & 31);
+                const int64_t a = 16 * is + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+                inside = c < d.C1 && a < d.A;
+                cB = c;
+                kB = a * P;
+            }
+            if (!inside) continue;
+            const int64_t m = gen_offset(g.sc, cB) + gen_offset(g.sk, kB);
+            elems[size_t(lp) * 8 + e] = Elem{m / merged_C, m % merged_C};
+        }
+    }
+    std::vector<int64_t> rows_p, rows_q;
+    for (const Elem& el : elems)
+        if (el.rP >= 0) {
+            rows_p.push_back(el.rP);
+            rows_q.push_back(el.rQ);
+        }
+    auto uniq = [](std::vector<int64_t>* v) {
+        std::sort(v->begin(), v->end());
+        v->erase(std::unique(v->begin(), v->end()), v->end());
+    };
+    uniq(&rows_p);
+    uniq(&rows_q);
+    const int64_t U = int64_t(rows_p.size()), V = int64_t(rows_q.size());
+    if (U < 1 || V < 1 || U > 160 || V > 160) return false;
+    const int LDV = int(V) + 8;
+    // one allocation: rowP | rowQ | rhoP | rhoQ (int32), then the piece table (8 x uint16 per piece, 16-byte aligned)
+    const size_t n_int = size_t(U + V + 2 * P);
+    const size_t tab_off = (n_int * 4 + 15) & ~size_t(15);
+    std::vector<unsigned char> host(tab_off + size_t(pieces) * 16);
+    int32_t* ints = reinterpret_cast<int32_t*>(host.data());
+    for (int64_t u = 0; u < U; ++u) ints[u] = int32_t(rows_p[size_t(u)]);
+    for (int64_t v = 0; v < V; ++v) ints[U + v] = int32_t(rows_q[size_t(v)]);
+    for (int64_t rho = 0; rho < P; ++rho) {
+        const int64_t m = w == 0 ? gen_offset(g.sc, rho) : gen_offset(g.sk, rho);
+        ints[U + V + rho] = int32_t(m / merged_C);
+        ints[U + V + P + rho] = int32_t(m % merged_C);
+    }
+    uint16_t* tab = reinterpret_cast<uint16_t*>(host.data() + tab_off);
+    for (size_t i = 0; i < elems.size(); ++i) {
+        if (elems[i].rP < 0) {
+            tab[i] = 0xFFFF;
+            continue;
+        }
+        const int64_t u = std::lower_bound(rows_p.begin(), rows_p.end(), elems[i].rP) - rows_p.begin();
+        const int64_t v = std::lower_bound(rows_q.begin(), rows_q.end(), elems[i].rQ) - rows_q.begin();
+        tab[i] = uint16_t(u * LDV + v);
+    }
+    if (hipMalloc(&h->lazy_gen_tables[w], host.size()) != hipSuccess) return false;
+    if (hipMemcpyAsync(h->lazy_gen_tables[w], host.data(), host.size(), hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return false;
+    h->packed_bytes += int64_t(host.size());
+    KronGenMfmaArgs& a = h->lazy_gen_mfma[w];
+    memset(&a, 0, sizeof(a));
+    a.Pc = g.Pc;
+    a.Qc = g.Qc;
+    const int32_t* dints = static_cast<const int32_t*>(h->lazy_gen_tables[w]);
+    a.rowP = dints;
+    a.rowQ = dints + U;
+    a.rhoP = dints + U + V;
+    a.rhoQ = dints + U + V + P;
+    a.tab = static_cast<const unsigned char*>(h->lazy_gen_tables[w]) + tab_off;
+    a.U = int32_t(U);
+    a.V = int32_t(V);
+    a.LDV = LDV;
+    a.Sp = g.Sp;
+    a.pieces_per_rho = int32_t(pieces);
+    a.pieces_per_chunk = int32_t(pieces / (w == 0 ? g.n_chunks : 1));
+    a.P = int32_t(P);
+    h->lazy_gen_smem[w] = size_t(U) * LDV * 2;
+    h->lazy_mfma[w] = true;
+    return true;
 }
 
 int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
@@ -688,7 +824,7 @@ int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t token
 }
 
 // Token count from which a lazily merged plan replaces the compact steps.
-constexpr int64_t kLazyMinTokens = 16;
+constexpr int64_t kLazyMinTokens = 2;
 
 void fill_gen_dims(GenDims* g, const std::vector<tn::GatherDim>& d) {
     g->n = int32_t(d.size());
@@ -728,7 +864,7 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
     if (kron_dispatch(d.cfg, nullptr, 0, nullptr, &kt) != TN_OK) return TN_OK;
     const int at = kt.at, ks0 = kt.ks0, o2t = kt.o2t, o1t = kt.o1t;
     // the four source matrices (shared indices innermost), written from the caller's tensors
-    const int32_t sp_len[2] = {round_up(int(mo[0]->K), 8), round_up(int(mo[1]->K), 8)};
+    const int32_t sp_len[2] = {round_up(int(mo[0]->K), 16), round_up(int(mo[1]->K), 16)};
     for (int w = 0; w < 2; ++w)
         for (int side = 0; side < 2; ++side) {
             const int64_t rows = side == 0 ? mo[w]->R : mo[w]->C;
@@ -794,6 +930,7 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
         g.AT = at;
         g.C1 = int32_t(d.C1);
         g.A = int32_t(d.A);
+        if (!(desc->flags & TN_FLAG_SCALAR_GENERATE)) (void)prepare_gen_mfma(h, w, g, d, mo[w]->C, st);
     }
     h->lazy = true;
     h->lazy_dims = d;
@@ -893,6 +1030,7 @@ int configure_kernels(int device) {
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kSmallChainMaxSmem)) != hipSuccess))
         rc = TN_ERR_HIP;
     for (int cfg = 0; cfg < tn::kKronConfigs && rc == TN_OK; ++cfg) rc = kron_dispatch(cfg, nullptr, 0, nullptr);
+    if (rc == TN_OK) rc = gen_mfma_dispatch(nullptr, 0, nullptr);
     if (rc == TN_OK && device >= 0 && device < 64) done[device] = true;
     return rc;
 }
@@ -1312,8 +1450,10 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
             h->workspace_bytes += h->lazy_slice_bytes;
         }
     }
-    for (int w = 0; w < 2 && h->lazy; ++w)
+    for (int w = 0; w < 2 && h->lazy; ++w) {
         h->lazy_gen[w].dst = static_cast<char*>(h->lazy_slices) + (w == 0 ? 0 : h->lazy_h1_offset);
+        h->lazy_gen_mfma[w].dst = h->lazy_gen[w].dst;
+    }
     h->chunk_tokens = chunk;
     *out = h;
     return TN_OK;

@@ -415,7 +415,7 @@ LAZY_CASES = [
 
 @pytest.mark.parametrize("case", range(len(LAZY_CASES)))
 def test_lazily_merged_ring(case):
-    """A default ring layer stores its compact cores; calls of 16 tokens or more rebuild the half-ring
+    """A default ring layer stores its compact cores; calls of 2 tokens or more rebuild the half-ring
     slices in the workspace and run the Kronecker-sum kernel. Both regimes against the oracle, the lazy one
     against the compact steps and against a layer that keeps the merged tensors, and again after a small
     call has used the same workspace."""
@@ -424,14 +424,15 @@ def test_lazily_merged_ring(case):
     ts = wl.make_tensors(spec, 40 + case)
     w = O.dense_weight(spec.format, ts, len(om))
     layer = make_layer(spec, ts, 64)
-    assert layer.query(tn.TN_QUERY_NUM_STEPS) == 4 and layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 16
+    assert layer.query(tn.TN_QUERY_NUM_STEPS) == 4 and layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 2
     assert 0 < layer.query(tn.TN_QUERY_LAZY_FLOPS_PER_TOKEN) < layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
     compact = make_layer(spec, ts, 64, flags=tn.TN_FLAG_NO_LAZY_MERGE)
     assert compact.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 0
     stored = make_layer(spec, ts, 64, flags=tn.TN_FLAG_MERGE_HALVES)
     assert stored.query(tn.TN_QUERY_NUM_STEPS) == 2 and stored.query(tn.TN_QUERY_STEP_BASE + 6) == 4
+    scalar_gen = make_layer(spec, ts, 64, flags=tn.TN_FLAG_SCALAR_GENERATE)      # slices rebuilt without MFMA
     first = None
-    for tokens in (40, 3, 15, 16, 40):
+    for tokens in (40, 1, 2, 15, 40):
         print(f"lazy case {case} tokens {tokens}", flush=True)
         x = wl.make_x(spec, tokens, 40 + case)
         xd = to_dev(x, "bf16")
@@ -442,17 +443,18 @@ def test_lazily_merged_ring(case):
         assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
         yc = to_host(compact(xd))
         assert O.rel_max_err(yc, ref) <= TOL["bf16"], (case, tokens)
-        if tokens < 16:
+        if tokens < 2:
             assert np.array_equal(y, yc)                      # same steps, same bits
         else:
             assert O.rel_max_err(y, yc) <= 1e-2
             assert O.rel_max_err(y, to_host(stored(xd))) <= 1e-2     # rebuilt vs stored slices
+            assert O.rel_max_err(y, to_host(scalar_gen(xd))) <= 1e-2  # the two rebuild kernels: summation order only
         if tokens == 40:
             if first is None:
                 first = yd.clone()
             else:
                 assert torch.equal(first, yd)                 # the workspace was reused in between
-    for l in (layer, compact, stored):
+    for l in (layer, compact, stored, scalar_gen):
         l.close()
 
 
@@ -469,7 +471,7 @@ def test_lazily_merged_ring_workspace_limits(dense_w):
         layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev, 20,
                             workspace=block)
         assert (layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) > 0) == lazy
-        for tokens in (20, 2, 20):
+        for tokens in (20, 1, 20):
             y = to_host(layer(to_dev(x[:tokens], "bf16")))
             assert O.rel_max_err(y, ref[:tokens]) <= TOL["bf16"], (ws_bytes, tokens)
         layer.close()
