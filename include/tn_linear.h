@@ -155,8 +155,10 @@ typedef struct tn_linear_s* tn_linear_t;
  *  stream             hipStream_t on which create enqueues its repacking work.
  *  workspace, workspace_bytes
  *                     optional DEVICE block owned by the caller (NULL = the library allocates its
- *                     own, bounded by workspace_limit_bytes). The handle then keeps its intermediates
- *                     and split-K partial sums inside this block and allocates no workspace; the block
+ *                     own, bounded by workspace_limit_bytes). The handle then keeps its intermediates,
+ *                     split-K partial sums and the per-call tensors of a lazily merged plan
+ *                     (TN_QUERY_LAZY_MIN_TOKENS; switched off if they do not fit) inside this block and
+ *                     allocates no workspace; the block
  *                     must outlive the handle and be 256-byte aligned. Several handles may share one
  *                     block as long as their forwards never overlap in time (e.g. all layers of a model
  *                     run on one stream). Too small for one token's intermediates: TN_ERR_INVALID_ARG.
