@@ -370,7 +370,7 @@ def test_kronecker_sum_kernel(case):
     assert tn.plan_query(fmt, tn.TN_DTYPE_BF16, om, im, rk, tn.TN_QUERY_KRON_CHAINABLE, flags=flags) == 1 + cfg
     w = O.dense_weight(fmt, ts, len(om))
     unfused = (flags & (tn.TN_FLAG_MERGE_GROW | tn.TN_FLAG_NO_SMALL_CHAIN)) | tn.TN_FLAG_NO_PAIR_CHAIN
-    for tokens in (1, 6, 1100):
+    for tokens in (1, 3, 6, 1100):
         print(f"kron case {case} tokens {tokens}", flush=True)
         x = wl.round_to_dtype(np.random.default_rng(case + tokens).standard_normal((tokens, spec.N)), "bf16")
         ref = O.apply_linear(w, x)
@@ -555,11 +555,12 @@ def test_transposed_baseline_configs(i, dense_w):
     layer.close()
 
 
-@pytest.mark.parametrize("i", [1, 2])
+@pytest.mark.parametrize("i", [1, 2, 3])
 def test_forward_under_stream_capture(i, dense_w):
     """tn_linear_forward neither allocates nor synchronises: the very first call of a fresh handle may be
     recorded into a HIP graph. Replays (with eager work and synchronisations in between) must give the
-    eager result bit for bit, at a decode size and at a size that runs the chained kernels."""
+    eager result bit for bit, at a decode size and at a size that runs the chained kernels (for the ring:
+    the rebuild of the half-ring slices, the Kronecker-sum launch and the reduction of its partial sums)."""
     spec, ts, w = dense_w(i)
     for tokens in (1, 300):
         x = to_dev(wl.make_x(spec, tokens, i), "bf16")
