@@ -109,7 +109,8 @@ def run_stack(args) -> int:
     for spec in specs:
         ts = draw(spec)
         layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, ts,
-                            tokens, flags=(2 if args.no_merge else 0) | (16 if args.merge_grow else 0), workspace=ws)
+                            tokens, flags=(2 if args.no_merge else 0) | (16 if args.merge_grow else 0) | args.flags,
+                            workspace=ws)
         layers.append(layer)
         flops.append(layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN))
         # large calls of some layers run on a cheaper plan rebuilt per call: count the work actually done
