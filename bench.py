@@ -55,12 +55,13 @@ def cpu_baseline(spec, tensors, sample_tokens, transpose=False):
 
 
 def measured_traffic(args, fused):
-    """HBM-side bytes per launch of the dominant kernel of workloads 1 and 3 at their default settings, measured in
+    """HBM-side bytes per launch of the dominant kernel of workloads 1 to 3 at their default settings, measured in
     separate rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy) and recorded in profiles/."""
     if (args.custom or args.no_merge or args.merge_grow or args.flags or args.variant or args.transpose
-            or args.no_pair_chain or args.tokens != 8192 or not fused):
+            or args.no_pair_chain or args.tokens != 8192 or fused != (args.workload != 2)):
         return None
     name, key = {1: ("tt_q_proj_prefill8192_hbm_traffic.txt", "pair"),
+                 2: ("tucker_up_proj_prefill8192_hbm_traffic.txt", "core"),
                  3: ("tr_down_proj_prefill8192_hbm_traffic.txt", "kronsum")}.get(args.workload, (None, None))
     if name is None:
         return None
