@@ -76,7 +76,7 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("flags", [0, tn.TN_FLAG_NO_MERGE, tn.TN_FLAG_MERGE_GROW])
+@pytest.mark.parametrize("flags", [0, tn.TN_FLAG_NO_MERGE, tn.TN_FLAG_MERGE_GROW, tn.TN_FLAG_MERGE_HALVES])
 @pytest.mark.parametrize("fmt,om,im,rk", CASES)
 def test_plan_executes_to_oracle(host_exec, fmt, om, im, rk, flags):
     rng = np.random.default_rng(hash((fmt, om, im, rk)) % (2 ** 32))
@@ -256,6 +256,13 @@ def test_growing_merges_half_ring():
     # rank 96: every merge would exceed the budget, the plan is unchanged
     big = wl.stack_spec(wl.FORMAT_TR, 25600, 5120, 96)
     assert _q(big, tn.TN_QUERY_NUM_MERGES, g) == 0
+    # TN_FLAG_MERGE_HALVES (the plan large calls of a default ring layer run on, rebuilt per call): two half
+    # rings whatever the size. Per token 2*A*O1*P*(K0 + C1) with A = K0 = 160, O1 = 64, C1 = 80, P = r*r.
+    hv = tn.TN_FLAG_MERGE_HALVES
+    for spec_r, r in ((spec, 32), (big, 96)):
+        assert _q(spec_r, tn.TN_QUERY_NUM_MERGES, hv) == 2 and _q(spec_r, tn.TN_QUERY_NUM_STEPS, hv) == 2
+        assert _q(spec_r, tn.TN_QUERY_FLOPS_PER_TOKEN, hv) == 2 * 160 * 64 * r * r * (160 + 80)
+    assert _q(big, tn.TN_QUERY_FLOPS_PER_TOKEN, 0) == 331433902080           # its compact four steps
 
 
 def test_planned_flops_equal_brute_force_minimum():
