@@ -388,74 +388,116 @@ __global__ void __launch_bounds__(256) kron_generate_kernel(KronGenArgs p) {
 
 // ---------------------------------------------------------------------------------------------
 // The same slices by MFMA, one workgroup per value rho of the shared bond. For a fixed rho the entries of
-// a slice array are all products of one row of Pc with one row of Qc: with u numbering the rows of Pc that
-// occur (rho's own contribution taken out) and v those of Qc,
-//     G[u][v] = sum_s Pc[rhoP[rho] + rowP[u]][s] * Qc[rhoQ[rho] + rowQ[v]][s]
+// a slice array are all products of one row of one source matrix with one row of the other: with r numbering
+// the rows that occur of the "row-side" matrix Rc (rho's own contribution taken out) and c those of the
+// "column-side" matrix Cc,
+//     G[r][c] = sum_s Rc[rhoR[rho] + rowR[r]][s] * Cc[rhoC[rho] + rowC[c]][s]
 // is a small matrix product (at most 160 x 160 x 128). The workgroup computes it in 32x32 tiles straight
 // from the two source matrices (their rows are MFMA operand fragments as they lie in memory), writes the
-// tiles to LDS as a bf16 matrix, and then assembles the slice's 16-byte pieces from it: a table made at
-// create time gives, for each piece of one rho, the LDS positions of its 8 elements (the map does not
-// depend on rho). 40-120 MFMAs replace the 10^4 dot products of 32-96 terms that the scalar kernel above
-// spends per rho, which matters for calls of tens of tokens at high rank.
+// tiles to LDS as a bf16 matrix (a lane holds one r and runs of 4 consecutive c: 8-byte writes), and then
+// assembles the slice's 16-byte pieces from it: a table made at create time gives, for each piece of one
+// rho, the LDS positions of its 8 elements (the map does not depend on rho). The host picks which of the
+// merge's two tensors is the column side, and the order in which the kernels number k and a, such that the 8
+// elements of a piece are consecutive columns of G wherever the shapes allow (contig 1: one 16-byte read;
+// contig 2: two runs of 4, for the slice whose k-steps are permuted; 0: eight 2-byte reads). 40-120 MFMAs
+// replace the 10^4 dot products of 32-96 terms that the scalar kernel above spends per rho, which matters for
+// calls of tens of tokens at high rank.
 // ---------------------------------------------------------------------------------------------
 struct KronGenMfmaArgs {
-    const void* Pc;            // [rows][Sp], Sp a multiple of 16, zero padded
-    const void* Qc;
+    const void* Rc;            // row-side source matrix [rows][Sp], Sp a multiple of 16, zero padded
+    const void* Cc;            // column-side source matrix
     void* dst;                 // the slice array, in 16-byte pieces
-    const int32_t* rowP;       // U row numbers of Pc (for rho = 0)
-    const int32_t* rowQ;       // V row numbers of Qc
-    const int32_t* rhoP;       // P row offsets: what rho adds to a row number of Pc
-    const int32_t* rhoQ;
-    const void* tab;           // per piece of one rho: 8 x uint16 positions u*LDV + v in the LDS matrix, 0xFFFF = zero
-    int32_t U, V, LDV, Sp;
+    const int32_t* rowR;       // NR row numbers of Rc (for rho = 0)
+    const int32_t* rowC;       // NC row numbers of Cc
+    const int32_t* rhoR;       // P row offsets: what rho adds to a row number of Rc
+    const int32_t* rhoC;
+    const void* tab;           // per piece of one rho: 8 x uint16 positions r*LDC + c in the LDS matrix, 0xFFFF = zero
+    int32_t NR, NC, LDC, Sp;   // LDC >= NC rounded up to 32, a multiple of 8
     int32_t pieces_per_rho;    // over all chunks
     int32_t pieces_per_chunk;  // blocks per rho and chunk x 64
     int32_t P;
+    int32_t contig;
 };
+
+// One 16-byte piece from the product matrix in LDS.
+__device__ __forceinline__ bf16x8 kron_gather_piece(const bf16_t* G, const unsigned (&t)[4], int contig) {
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    bf16x8 out;
+    const unsigned p0 = t[0] & 0xFFFFu, p4 = t[2] & 0xFFFFu;
+    if (contig == 1) {
+        if (p0 == 0xFFFFu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out[e] = bf16_t(0.f);
+        } else {
+            out = *reinterpret_cast<const bf16x8*>(G + p0);
+        }
+    } else if (contig == 2) {
+        bf16x4_t lo, hi;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lo[e] = hi[e] = bf16_t(0.f);
+        if (p0 != 0xFFFFu) lo = *reinterpret_cast<const bf16x4_t*>(G + p0);
+        if (p4 != 0xFFFFu) hi = *reinterpret_cast<const bf16x4_t*>(G + p4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            out[e] = lo[e];
+            out[4 + e] = hi[e];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned pos = (t[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+            out[e] = pos == 0xFFFFu ? bf16_t(0.f) : G[pos];
+        }
+    }
+    return out;
+}
 
 template <int KSS /* k-steps of 16 along the shared bond */>
 __global__ void __launch_bounds__(256) kron_generate_mfma_kernel(KronGenMfmaArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
     bf16_t* G = reinterpret_cast<bf16_t*>(dyn_smem);
-    const bf16_t* Pc = static_cast<const bf16_t*>(p.Pc);
-    const bf16_t* Qc = static_cast<const bf16_t*>(p.Qc);
+    const bf16_t* Rc = static_cast<const bf16_t*>(p.Rc);
+    const bf16_t* Cc = static_cast<const bf16_t*>(p.Cc);
     const int rho = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int UT = (p.U + 31) >> 5, VT = (p.V + 31) >> 5;
-    const int64_t baseP = p.rhoP[rho], baseQ = p.rhoQ[rho];
+    const int RT = (p.NR + 31) >> 5, CT = (p.NC + 31) >> 5;
+    const int64_t baseR = p.rhoR[rho], baseC = p.rhoC[rho];
     const int kofs = 8 * (lane >> 5);
     bf16x8 zero;
 #pragma unroll
     for (int e = 0; e < 8; ++e) zero[e] = bf16_t(0.f);
 
-    // tiles (ut, vt): wave w takes the column tiles vt = w, w+4, ...
-    for (int vt = wave; vt < VT; vt += 4) {
-        const int v = 32 * vt + (lane & 31);
+    // tiles (ct, rt): wave w takes the row tiles rt = w, w+4, ...; the MFMA's row operand is the column side, so
+    // that a lane ends up with one r (l%32) and, in registers 4q..4q+3, the columns 32*ct + 8q + 4*(l/32) + 0..3
+    for (int rt = wave; rt < RT; rt += 4) {
+        const int r = 32 * rt + (lane & 31);
         bf16x8 b[KSS];
         {
-            const bf16_t* row = Qc + (baseQ + (v < p.V ? p.rowQ[v] : 0)) * p.Sp + kofs;
+            const bf16_t* row = Rc + (baseR + (r < p.NR ? p.rowR[r] : 0)) * p.Sp + kofs;
 #pragma unroll
             for (int ks = 0; ks < KSS; ++ks)
-                b[ks] = (v < p.V && 16 * ks < p.Sp) ? *reinterpret_cast<const bf16x8*>(row + 16 * ks) : zero;
+                b[ks] = (r < p.NR && 16 * ks < p.Sp) ? *reinterpret_cast<const bf16x8*>(row + 16 * ks) : zero;
         }
-        for (int ut = 0; ut < UT; ++ut) {
-            const int u = 32 * ut + (lane & 31);
-            const bf16_t* row = Pc + (baseP + (u < p.U ? p.rowP[u] : 0)) * p.Sp + kofs;
+        for (int ct = 0; ct < CT; ++ct) {
+            const int c = 32 * ct + (lane & 31);
+            const bf16_t* row = Cc + (baseC + (c < p.NC ? p.rowC[c] : 0)) * p.Sp + kofs;
             floatx16 acc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < KSS; ++ks) {
-                const bf16x8 a = (u < p.U && 16 * ks < p.Sp) ? *reinterpret_cast<const bf16x8*>(row + 16 * ks) : zero;
+                const bf16x8 a = (c < p.NC && 16 * ks < p.Sp) ? *reinterpret_cast<const bf16x8*>(row + 16 * ks) : zero;
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[ks], acc, 0, 0, 0);
             }
-            // lane l, register i: row u = 32*ut + 8*(i/4) + 4*(l/32) + i%4, column v
-            if (v < p.V) {
+            if (r < p.NR) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int uu = 32 * ut + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                    if (uu < p.U) G[uu * p.LDV + v] = bf16_t(acc[i]);
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4_t pk;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) pk[j] = bf16_t(acc[4 * q + j]);
+                    *reinterpret_cast<bf16x4_t*>(G + r * p.LDC + 32 * ct + 8 * q + 4 * (lane >> 5)) = pk;
                 }
             }
         }
@@ -465,13 +507,9 @@ __global__ void __launch_bounds__(256) kron_generate_mfma_kernel(KronGenMfmaArgs
     const uintx4* tab = static_cast<const uintx4*>(p.tab);
     bf16x8* dst = static_cast<bf16x8*>(p.dst);
     for (int lp = tid; lp < p.pieces_per_rho; lp += 256) {
-        const uintx4 t = tab[lp];
-        bf16x8 out;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const unsigned pos = (t[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-            out[e] = pos == 0xFFFFu ? bf16_t(0.f) : G[pos];
-        }
+        const uintx4 tv = tab[lp];
+        const unsigned t[4] = {tv[0], tv[1], tv[2], tv[3]};
+        const bf16x8 out = kron_gather_piece(G, t, p.contig);
         const int chunk = lp / p.pieces_per_chunk, rem = lp - chunk * p.pieces_per_chunk;
         dst[(int64_t(chunk) * p.P + rho) * p.pieces_per_chunk + rem] = out;
     }

@@ -714,9 +714,11 @@ int launch_lazy_generate(const tn_linear_s* h, hipStream_t st) {
 
 // Tables of the MFMA form of the slice generation for half w (see kron_generate_mfma_kernel): which rows of the
 // two source matrices a value of the bond uses, and where each element of a slice sits in their product.
-// Returns false (and leaves the scalar kernel in charge) when the half does not fit: more than 160 distinct rows
-// on a side or a shared bond longer than 128.
-bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::KronDims& d, int64_t merged_C, hipStream_t st) {
+// perm maps the kernels' numbering of k (w = 0) or a (w = 1) to the plan's. Returns false (and leaves the scalar
+// kernel in charge) when the half does not fit: more than 160 distinct rows on a side or a shared bond longer
+// than 128.
+bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::KronDims& d, int64_t merged_C,
+                      const std::vector<int32_t>& perm, hipStream_t st) {
     if (g.Sp > 128 || g.Sp % 16) return false;
     const int64_t P = d.P;
     struct Elem { int64_t rP, rQ; };
@@ -738,7 +740,7 @@ bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::Kro
                 const int64_t k = 16 * ks + 8 * (l >> 5) + e;
                 inside = o1 < d.O1 && k < d.K0;
                 cB = o1 * P;
-                kB = k;
+                kB = inside ? perm[size_t(k)] : 0;
             } else {
                 const int is = int(blk % (2 * g.AT));
                 const int j = int(blk / (2 * g.AT));
@@ -746,39 +748,46 @@ bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::Kro
                 const int64_t a = 16 * is + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
                 inside = c < d.C1 && a < d.A;
                 cB = c;
-                kB = a * P;
+                kB = inside ? int64_t(perm[size_t(a)]) * P : 0;
             }
             if (!inside) continue;
             const int64_t m = gen_offset(g.sc, cB) + gen_offset(g.sk, kB);
             elems[size_t(lp) * 8 + e] = Elem{m / merged_C, m % merged_C};
         }
     }
-    std::vector<int64_t> rows_p, rows_q;
+    // the column side of the product is the tensor whose row changes from one element of a piece to the next
+    bool cols_from_q = true;
+    for (size_t i = 0; i + 1 < elems.size(); i += 8)
+        if (elems[i].rP >= 0 && elems[i + 1].rP >= 0) {
+            cols_from_q = elems[i].rQ != elems[i + 1].rQ;
+            break;
+        }
+    std::vector<int64_t> rows_r, rows_c;
     for (const Elem& el : elems)
         if (el.rP >= 0) {
-            rows_p.push_back(el.rP);
-            rows_q.push_back(el.rQ);
+            rows_r.push_back(cols_from_q ? el.rP : el.rQ);
+            rows_c.push_back(cols_from_q ? el.rQ : el.rP);
         }
     auto uniq = [](std::vector<int64_t>* v) {
         std::sort(v->begin(), v->end());
         v->erase(std::unique(v->begin(), v->end()), v->end());
     };
-    uniq(&rows_p);
-    uniq(&rows_q);
-    const int64_t U = int64_t(rows_p.size()), V = int64_t(rows_q.size());
-    if (U < 1 || V < 1 || U > 160 || V > 160) return false;
-    const int LDV = int(V) + 8;
-    // one allocation: rowP | rowQ | rhoP | rhoQ (int32), then the piece table (8 x uint16 per piece, 16-byte aligned)
-    const size_t n_int = size_t(U + V + 2 * P);
+    uniq(&rows_r);
+    uniq(&rows_c);
+    const int64_t NR = int64_t(rows_r.size()), NC = int64_t(rows_c.size());
+    if (NR < 1 || NC < 1 || NR > 160 || NC > 160) return false;
+    const int LDC = round_up(int(NC), 32) + 8;
+    // one allocation: rowR | rowC | rhoR | rhoC (int32), then the piece table (8 x uint16 per piece, 16-byte aligned)
+    const size_t n_int = size_t(NR + NC + 2 * P);
     const size_t tab_off = (n_int * 4 + 15) & ~size_t(15);
     std::vector<unsigned char> host(tab_off + size_t(pieces) * 16);
     int32_t* ints = reinterpret_cast<int32_t*>(host.data());
-    for (int64_t u = 0; u < U; ++u) ints[u] = int32_t(rows_p[size_t(u)]);
-    for (int64_t v = 0; v < V; ++v) ints[U + v] = int32_t(rows_q[size_t(v)]);
+    for (int64_t r = 0; r < NR; ++r) ints[r] = int32_t(rows_r[size_t(r)]);
+    for (int64_t c = 0; c < NC; ++c) ints[NR + c] = int32_t(rows_c[size_t(c)]);
     for (int64_t rho = 0; rho < P; ++rho) {
         const int64_t m = w == 0 ? gen_offset(g.sc, rho) : gen_offset(g.sk, rho);
-        ints[U + V + rho] = int32_t(m / merged_C);
-        ints[U + V + P + rho] = int32_t(m % merged_C);
+        ints[NR + NC + rho] = int32_t(cols_from_q ? m / merged_C : m % merged_C);
+        ints[NR + NC + P + rho] = int32_t(cols_from_q ? m % merged_C : m / merged_C);
     }
     uint16_t* tab = reinterpret_cast<uint16_t*>(host.data() + tab_off);
     for (size_t i = 0; i < elems.size(); ++i) {
@@ -786,9 +795,21 @@ bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::Kro
             tab[i] = 0xFFFF;
             continue;
         }
-        const int64_t u = std::lower_bound(rows_p.begin(), rows_p.end(), elems[i].rP) - rows_p.begin();
-        const int64_t v = std::lower_bound(rows_q.begin(), rows_q.end(), elems[i].rQ) - rows_q.begin();
-        tab[i] = uint16_t(u * LDV + v);
+        const int64_t vr = cols_from_q ? elems[i].rP : elems[i].rQ, vc = cols_from_q ? elems[i].rQ : elems[i].rP;
+        const int64_t r = std::lower_bound(rows_r.begin(), rows_r.end(), vr) - rows_r.begin();
+        const int64_t c = std::lower_bound(rows_c.begin(), rows_c.end(), vc) - rows_c.begin();
+        tab[i] = uint16_t(r * LDC + c);
+    }
+    // are the pieces runs of consecutive columns? (first slice: 8 in a row; second: two runs of 4); a run is
+    // either wholly inside the tensor or wholly outside, and starts at a multiple of its length
+    const int run = w == 0 ? 8 : 4;
+    bool contig = true;
+    for (size_t i = 0; i < elems.size() && contig; i += size_t(run)) {
+        const bool out0 = tab[i] == 0xFFFF;
+        for (int e = 0; e < run && contig; ++e) {
+            if ((tab[i + e] == 0xFFFF) != out0) contig = false;
+            else if (!out0 && (tab[i + e] != tab[i] + e || tab[i] % run)) contig = false;
+        }
     }
     if (hipMalloc(&h->lazy_gen_tables[w], host.size()) != hipSuccess) return false;
     if (hipMemcpyAsync(h->lazy_gen_tables[w], host.data(), host.size(), hipMemcpyHostToDevice, st) != hipSuccess ||
@@ -797,24 +818,57 @@ bool prepare_gen_mfma(tn_linear_s* h, int w, const KronGenArgs& g, const tn::Kro
     h->packed_bytes += int64_t(host.size());
     KronGenMfmaArgs& a = h->lazy_gen_mfma[w];
     memset(&a, 0, sizeof(a));
-    a.Pc = g.Pc;
-    a.Qc = g.Qc;
+    a.Rc = cols_from_q ? g.Pc : g.Qc;
+    a.Cc = cols_from_q ? g.Qc : g.Pc;
     const int32_t* dints = static_cast<const int32_t*>(h->lazy_gen_tables[w]);
-    a.rowP = dints;
-    a.rowQ = dints + U;
-    a.rhoP = dints + U + V;
-    a.rhoQ = dints + U + V + P;
+    a.rowR = dints;
+    a.rowC = dints + NR;
+    a.rhoR = dints + NR + NC;
+    a.rhoC = dints + NR + NC + P;
     a.tab = static_cast<const unsigned char*>(h->lazy_gen_tables[w]) + tab_off;
-    a.U = int32_t(U);
-    a.V = int32_t(V);
-    a.LDV = LDV;
+    a.NR = int32_t(NR);
+    a.NC = int32_t(NC);
+    a.LDC = LDC;
     a.Sp = g.Sp;
     a.pieces_per_rho = int32_t(pieces);
     a.pieces_per_chunk = int32_t(pieces / (w == 0 ? g.n_chunks : 1));
     a.P = int32_t(P);
-    h->lazy_gen_smem[w] = size_t(U) * LDV * 2;
+    a.contig = contig ? (w == 0 ? 1 : 2) : 0;
+    h->lazy_gen_smem[w] = size_t(NR) * LDC * 2;
     h->lazy_mfma[w] = true;
     return true;
+}
+
+// The kernels may number k and a in any order as long as x is gathered through the same numbering. Pick the one that
+// makes an index of extent % unit == 0 the fastest-running digit (it is then a run of consecutive columns of the
+// product matrix the slices are assembled from): returns new number -> the plan's number.
+std::vector<int32_t> minor_digit_permutation(const std::vector<int64_t>& extents, int unit) {
+    int64_t total = 1;
+    for (int64_t e : extents) total *= e;
+    std::vector<int32_t> perm(static_cast<size_t>(total));
+    for (int64_t i = 0; i < total; ++i) perm[size_t(i)] = int32_t(i);
+    const int n = int(extents.size());
+    if (n < 2 || extents[size_t(n - 1)] % unit == 0) return perm;      // already so (or nothing to choose)
+    int pick = -1;
+    for (int j = 0; j < n; ++j)
+        if (extents[size_t(j)] % unit == 0 && (pick < 0 || extents[size_t(j)] > extents[size_t(pick)])) pick = j;
+    if (pick < 0) return perm;
+    std::vector<int> order;                 // digits of the new number, outer -> inner
+    for (int j = 0; j < n; ++j)
+        if (j != pick) order.push_back(j);
+    order.push_back(pick);
+    std::vector<int64_t> weight(size_t(n), 1);      // of each digit in the plan's number
+    for (int j = n - 2; j >= 0; --j) weight[size_t(j)] = weight[size_t(j + 1)] * extents[size_t(j + 1)];
+    for (int64_t i = 0; i < total; ++i) {
+        int64_t rem = i, orig = 0;
+        for (int q = n - 1; q >= 0; --q) {
+            const int j = order[size_t(q)];
+            orig += (rem % extents[size_t(j)]) * weight[size_t(j)];
+            rem /= extents[size_t(j)];
+        }
+        perm[size_t(i)] = int32_t(orig);
+    }
+    return perm;
 }
 
 int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
@@ -883,27 +937,8 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
                                static_cast<bf16_t*>(buf), fd, sd, rows, int32_t(mo[w]->K), sp_len[w]);
         }
     if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
-    // tables of the merged plan
     const tn::Step& s0 = q.steps[0];
     const tn::Step& s1 = q.steps[1];
-    std::vector<int32_t> tab;
-    const size_t n_xrow = s0.a_plain ? 0 : s0.arow.size(), n_xcol = s0.a_plain ? 0 : s0.acol.size();
-    if (!s0.a_plain) {
-        tab.insert(tab.end(), s0.arow.begin(), s0.arow.end());
-        tab.insert(tab.end(), s0.acol.begin(), s0.acol.end());
-    }
-    tab.insert(tab.end(), s1.crow.begin(), s1.crow.end());
-    tab.insert(tab.end(), s1.ccol.begin(), s1.ccol.end());
-    if (hipMalloc(reinterpret_cast<void**>(&h->lazy_tables), tab.size() * sizeof(int32_t)) != hipSuccess) return TN_ERR_ALLOC;
-    if (hipMemcpyAsync(h->lazy_tables, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess ||
-        hipStreamSynchronize(st) != hipSuccess)
-        return TN_ERR_HIP;
-    if (!s0.a_plain) {
-        h->lazy_xrow = h->lazy_tables;
-        h->lazy_xcol = h->lazy_tables + n_xrow;
-    }
-    h->lazy_yrow = h->lazy_tables + n_xrow + n_xcol;
-    h->lazy_ycol = h->lazy_yrow + s1.crow.size();
     const int n_chunks = int((d.O1 + 32 * o1t - 1) / (32 * o1t));
     const int64_t e0 = int64_t(n_chunks) * d.P * o1t * ks0 * 512;
     const int64_t e1 = d.P * int64_t(o2t) * 2 * at * 512;
@@ -930,8 +965,65 @@ int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
         g.AT = at;
         g.C1 = int32_t(d.C1);
         g.A = int32_t(d.A);
-        if (!(desc->flags & TN_FLAG_SCALAR_GENERATE)) (void)prepare_gen_mfma(h, w, g, d, mo[w]->C, st);
     }
+    // The MFMA form of the rebuild, with k and a numbered so that the pieces of the slices are runs of columns of
+    // the products; if a half does not fit that form, both keep the plan's numbering (the plain-FMA kernel knows no
+    // other) and the halves that fit still use MFMA.
+    std::vector<int32_t> perm_k(size_t(d.K0)), perm_a(size_t(d.A));
+    for (int64_t i = 0; i < d.K0; ++i) perm_k[size_t(i)] = int32_t(i);
+    for (int64_t i = 0; i < d.A; ++i) perm_a[size_t(i)] = int32_t(i);
+    if (!(desc->flags & TN_FLAG_SCALAR_GENERATE)) {
+        std::vector<int64_t> kext;
+        for (const tn::GatherDim& gd : s0.kdims) kext.push_back(gd.extent);
+        const std::vector<int32_t> pk = minor_digit_permutation(kext, 8), pa = minor_digit_permutation(s0.rext, 4);
+        const bool ok = int64_t(pk.size()) == d.K0 && int64_t(pa.size()) == d.A &&
+                        prepare_gen_mfma(h, 0, h->lazy_gen[0], d, mo[0]->C, pk, st) &&
+                        prepare_gen_mfma(h, 1, h->lazy_gen[1], d, mo[1]->C, pa, st);
+        if (ok) {
+            perm_k = pk;
+            perm_a = pa;
+        } else {
+            for (int w = 0; w < 2; ++w) {
+                if (h->lazy_gen_tables[w]) (void)hipFree(h->lazy_gen_tables[w]);
+                h->lazy_gen_tables[w] = nullptr;
+                h->lazy_mfma[w] = false;
+            }
+            (void)prepare_gen_mfma(h, 0, h->lazy_gen[0], d, mo[0]->C, perm_k, st);
+            (void)prepare_gen_mfma(h, 1, h->lazy_gen[1], d, mo[1]->C, perm_a, st);
+        }
+    }
+    // tables of the merged plan: where a and k (in the kernels' numbering) sit in a token of x, where o1 and o2 go
+    std::vector<int32_t> tab;
+    bool identity = s0.a_plain;
+    for (int64_t i = 0; i < d.K0 && identity; ++i) identity = perm_k[size_t(i)] == i;
+    for (int64_t i = 0; i < d.A && identity; ++i) identity = perm_a[size_t(i)] == i;
+    const size_t n_xrow = identity ? 0 : size_t(d.A), n_xcol = identity ? 0 : size_t(d.K0);
+    if (!identity) {
+        for (int64_t a = 0; a < d.A; ++a)
+            tab.push_back(s0.a_plain ? int32_t(perm_a[size_t(a)] * d.K0) : s0.arow[size_t(perm_a[size_t(a)])]);
+        for (int64_t k = 0; k < d.K0; ++k)
+            tab.push_back(s0.a_plain ? perm_k[size_t(k)] : s0.acol[size_t(perm_k[size_t(k)])]);
+        // 8 consecutive k of one a as one aligned 16-byte piece of x?
+        d.x_vec8 = true;
+        for (int64_t a = 0; a < d.A; ++a)
+            if (tab[size_t(a)] % 8) d.x_vec8 = false;
+        for (int64_t k = 0; k < d.K0; ++k) {
+            const int32_t v = tab[size_t(d.A + k)], v0 = tab[size_t(d.A + (k & ~int64_t(7)))];
+            if (v != v0 + (k & 7) || (!(k & 7) && v % 8)) d.x_vec8 = false;
+        }
+    }
+    tab.insert(tab.end(), s1.crow.begin(), s1.crow.end());
+    tab.insert(tab.end(), s1.ccol.begin(), s1.ccol.end());
+    if (hipMalloc(reinterpret_cast<void**>(&h->lazy_tables), tab.size() * sizeof(int32_t)) != hipSuccess) return TN_ERR_ALLOC;
+    if (hipMemcpyAsync(h->lazy_tables, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return TN_ERR_HIP;
+    if (!identity) {
+        h->lazy_xrow = h->lazy_tables;
+        h->lazy_xcol = h->lazy_tables + n_xrow;
+    }
+    h->lazy_yrow = h->lazy_tables + n_xrow + n_xcol;
+    h->lazy_ycol = h->lazy_yrow + s1.crow.size();
     h->lazy = true;
     h->lazy_dims = d;
     h->lazy_min_tokens = kLazyMinTokens;

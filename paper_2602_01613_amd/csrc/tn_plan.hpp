@@ -51,6 +51,7 @@ struct Step {
     int64_t trace_extent = 1, trace_stride = 0;
     bool a_plain = true;            // A is row-major [tokens*R, K] with leading dimension K
     std::vector<int32_t> arow, acol;       // gather tables when !a_plain
+    std::vector<int64_t> rext;             // extents of the indices the row number runs over, outer -> inner
     int64_t a_tok_stride = 0;       // elements per token of the step's input
     std::vector<int32_t> crow, ccol;       // scatter tables of the output
     int64_t c_tok_stride = 0;       // elements per token of the step's output
@@ -440,6 +441,7 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
             if (layout[j] != rows[j]) plain = false;
         st.a_plain = plain;
         st.R = detail::prod_extents(rows, ext);
+        for (int i : rows) st.rext.push_back(ext[size_t(i)]);
         st.K = detail::prod_extents(kset, ext);
         st.a_tok_stride = detail::prod_extents(layout, ext);
         if (!plain) {
