@@ -82,7 +82,7 @@ extern "C" {
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
                                        bf16 steps (0 = library's choice): 3 = 128x256 and 8 = 256x128
                                        register-prefetch tiles, 9 = short-K store kernel, 12 = 256x256
-                                       direct-to-LDS ring; 20 = the Kronecker-sum kernel for every two-step
+                                       ping-pong kernel; 20 = the Kronecker-sum kernel for every two-step
                                        plan whose layout allows it, whatever its size (see
                                        TN_QUERY_KRON_CHAINABLE); ignored where the variant cannot run the step */
 

@@ -40,7 +40,7 @@ enum Variant : int {
     VAR_PIPE_128x256 = 3,     // register-prefetch tiles, 4 waves, 2 workgroups per CU, one LDS stage
     VAR_PIPE_256x128 = 8,     // same, 4 waves stacked along rows
     VAR_SHORTK = 9,           // K <= 64, store-bound: registers-only operands, barrier-free
-    VAR_DLDS8_256x256 = 12,   // direct-to-LDS ring, 8 waves, 4 stages, 1 workgroup per CU
+    VAR_PINGPONG_256x256 = 12,   // 8 waves in two alternating groups, 1 workgroup per CU
     VAR_KRONSUM = 20,         // (as a forced id only, read by tn::kron_shape) the Kronecker-sum kernel wherever
                               // the plan's layout allows it
 };
@@ -173,20 +173,20 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
         const bool shortk_ok = p.K <= 64 && p.c_vec == 8;
         int v = round_up(int(p.C), 128) < round_up(int(p.C), 256) ? VAR_PIPE_256x128 : VAR_PIPE_128x256;
         // direct-to-LDS tiles where A is a plain matrix whose K is a whole number of 32-wide tiles
-        const bool dlds_ok = p.a_plain && p.K % 32 == 0 && p.K >= 64;
+        const bool pingpong_ok = p.a_plain && p.K % 32 == 0 && p.K >= 64;
         // (measured: the 8-wave 256x256 ring beats the register-prefetch tiles on every shape it
         // fits without extra column padding; the 4-wave direct-to-LDS tiles do not)
-        if (dlds_ok && p.C >= 256 && round_up(int(p.C), 256) == round_up(int(p.C), 128)) v = VAR_DLDS8_256x256;
+        if (pingpong_ok && p.C >= 256 && round_up(int(p.C), 256) == round_up(int(p.C), 128)) v = VAR_PINGPONG_256x256;
         if (shortk_ok && p.C >= 256) v = VAR_SHORTK;
         if (forced == VAR_PIPE_128x256 || forced == VAR_PIPE_256x128 || (forced == VAR_SHORTK && shortk_ok) ||
-            (forced == VAR_DLDS8_256x256 && dlds_ok))
+            (forced == VAR_PINGPONG_256x256 && pingpong_ok))
             v = forced;
         s->variant = v;
         switch (v) {
             case VAR_SHORTK: s->bm = 128; s->bn = 128; break;
             case VAR_PIPE_128x256: s->bm = 128; s->bn = 256; break;
             case VAR_PIPE_256x128: s->bm = 256; s->bn = 128; break;
-            default: s->bm = 256; s->bn = 256; break;      // VAR_DLDS8_256x256
+            default: s->bm = 256; s->bn = 256; break;      // VAR_PINGPONG_256x256
         }
     }
     s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : 1;
@@ -266,15 +266,15 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
 }
 
 template <int WM, int WN, int TM, int TN, int NS, int MINB>
-int launch_dlds(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t st) {
+int launch_pingpong(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t st) {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t smem = dlds_smem_bytes<WM, WN, TM, TN, NS>();
+    constexpr size_t smem = pingpong_smem_bytes<WM, WN, TM, TN, NS>();
     int nrow = int((rows + BM - 1) / BM), ncol = s.Cp / BN;
     int nrow_pad = (nrow + 7) / 8 * 8;
     dim3 grid(uint32_t(nrow_pad) * uint32_t(ncol));
     using kern_t = void (*)(StepArgs, int, int, int);
-    static const kern_t kerns[2] = {step_mfma_dlds_kernel<WM, WN, TM, TN, NS, MINB, 0>,
-                                    step_mfma_dlds_kernel<WM, WN, TM, TN, NS, MINB, 1>};
+    static const kern_t kerns[2] = {step_mfma_pingpong_kernel<WM, WN, TM, TN, NS, MINB, 0>,
+                                    step_mfma_pingpong_kernel<WM, WN, TM, TN, NS, MINB, 1>};
     if (!s.packed) {                       // configuration call (create time)
         for (kern_t k : kerns)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -342,8 +342,8 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
             if (rc != TN_OK) return rc;
             break;
         }
-        case VAR_DLDS8_256x256: {
-            int rc = launch_dlds<4, 2, 2, 4, 4, 1>(s, a, rows, st);
+        case VAR_PINGPONG_256x256: {
+            int rc = launch_pingpong<4, 2, 2, 4, 2, 1>(s, a, rows, st);
             if (rc != TN_OK) return rc;
             break;
         }
@@ -1111,7 +1111,7 @@ int configure_kernels(int device) {
     const tn_linear_s* no_handle = nullptr;
     int rc = launch_pipe<2, 2, 2, 4, 1, 2>(none, a, 0, nullptr);
     if (rc == TN_OK) rc = launch_pipe<4, 1, 2, 4, 1, 2>(none, a, 0, nullptr);
-    if (rc == TN_OK) rc = launch_dlds<4, 2, 2, 4, 4, 1>(none, a, 0, nullptr);
+    if (rc == TN_OK) rc = launch_pingpong<4, 2, 2, 4, 2, 1>(none, a, 0, nullptr);
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK &&
         (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),
