@@ -495,7 +495,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 
 template <int WM, int WN, int TM, int TN, int NS, int MINB, int TRANS>
 __global__ void __launch_bounds__(WM * WN * 64, MINB)
-step_mfma_pingpong_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
+step_mfma_pingpong_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles, int slot_base, int halves) {
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 32;
     constexpr int ROWB = BK * 2;                       // bytes per LDS tile row
@@ -508,8 +508,23 @@ step_mfma_pingpong_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles)
     static_assert(NS >= 2, "a stage is refilled while its neighbour is read");
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
 
+    // A launch covers the tiles of slots slot_base .. of every XCD's walk (see tile_of_workgroup); with
+    // halves = 1 the walk is that of tiles twice as wide as this kernel's (ncol_tiles counts those) and two
+    // consecutive workgroups of an XCD take the two halves of one of them: the host runs the last, partly
+    // filled round of a launch that way, on twice as many workgroups for half as long.
     int row_tile, col_tile;
-    tile_of_workgroup(blockIdx.x, nrow_tiles, ncol_tiles, &row_tile, &col_tile);
+    {
+        const int xcd = blockIdx.x & 7;
+        int slot = blockIdx.x >> 3, half = 0;
+        if (halves) {
+            half = slot & 1;
+            slot >>= 1;
+        }
+        slot += slot_base;
+        if (slot >= ((nrow_tiles + 7) >> 3) * ncol_tiles) return;
+        tile_of_workgroup((slot << 3) | xcd, nrow_tiles, ncol_tiles, &row_tile, &col_tile);
+        if (halves) col_tile = 2 * col_tile + half;
+    }
     if (row_tile >= nrow_tiles) return;
     const uint32_t row0 = uint32_t(row_tile) * BM;
     const int col0 = col_tile * BN;

@@ -265,24 +265,46 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
     return TN_OK;
 }
 
-template <int WM, int WN, int TM, int TN, int NS, int MINB>
-int launch_pingpong(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t st) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t smem = pingpong_smem_bytes<WM, WN, TM, TN, NS>();
-    int nrow = int((rows + BM - 1) / BM), ncol = s.Cp / BN;
-    int nrow_pad = (nrow + 7) / 8 * 8;
-    dim3 grid(uint32_t(nrow_pad) * uint32_t(ncol));
-    using kern_t = void (*)(StepArgs, int, int, int);
-    static const kern_t kerns[2] = {step_mfma_pingpong_kernel<WM, WN, TM, TN, NS, MINB, 0>,
-                                    step_mfma_pingpong_kernel<WM, WN, TM, TN, NS, MINB, 1>};
-    if (!s.packed) {                       // configuration call (create time)
-        for (kern_t k : kerns)
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(smem)) != hipSuccess)
-                return TN_ERR_HIP;
-        return TN_OK;
+// The 256x256 ping-pong kernel and its 256x128 form. A CU holds one workgroup, so a launch runs in rounds of
+// num_cus tiles; when the last round would fill at most half of the CUs, its tiles run as a second launch of
+// half-width tiles on twice as many workgroups (same walk over the tiles, see the kernel), which takes half a round.
+using pingpong_kern_t = void (*)(StepArgs, int, int, int, int, int);
+
+template <int TN, int TRANS>
+pingpong_kern_t pingpong_kernel() { return step_mfma_pingpong_kernel<4, 2, 2, TN, 2, 1, TRANS>; }
+
+int configure_pingpong() {
+    const pingpong_kern_t wide[2] = {pingpong_kernel<4, 0>(), pingpong_kernel<4, 1>()};
+    const pingpong_kern_t narrow[2] = {pingpong_kernel<2, 0>(), pingpong_kernel<2, 1>()};
+    for (int i = 0; i < 2; ++i)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(wide[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(pingpong_smem_bytes<4, 2, 2, 4, 2>())) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(narrow[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(pingpong_smem_bytes<4, 2, 2, 2, 2>())) != hipSuccess)
+            return TN_ERR_HIP;
+    return TN_OK;
+}
+
+int launch_pingpong(const tn_linear_s* h, const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t st) {
+    const int nrow = int((rows + 255) / 256), ncol = s.Cp / 256;
+    const int trans = s.cmode == 2 ? 1 : 0;
+    const pingpong_kern_t wide = trans ? pingpong_kernel<4, 1>() : pingpong_kernel<4, 0>();
+    const pingpong_kern_t narrow = trans ? pingpong_kernel<2, 1>() : pingpong_kernel<2, 0>();
+    const int slots = ((nrow + 7) / 8) * ncol;             // per XCD (workgroup i runs on XCD i % 8)
+    const int per_xcd = h->num_cus / 8;
+    int full = slots, rest = 0;
+    if (nrow % 8 == 0 && h->num_cus % 8 == 0 && per_xcd > 0) {
+        const int r = slots % per_xcd;
+        if (r > 0 && 2 * r <= per_xcd) {
+            rest = r;
+            full = slots - r;
+        }
     }
-    hipLaunchKernelGGL(kerns[s.cmode == 2 ? 1 : 0], grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
+    constexpr size_t wide_smem = pingpong_smem_bytes<4, 2, 2, 4, 2>(), narrow_smem = pingpong_smem_bytes<4, 2, 2, 2, 2>();
+    if (full > 0)
+        hipLaunchKernelGGL(wide, dim3(uint32_t(8 * full)), dim3(512), wide_smem, st, a, s.cmode, nrow, ncol, 0, 0);
+    if (rest > 0)
+        hipLaunchKernelGGL(narrow, dim3(uint32_t(16 * rest)), dim3(512), narrow_smem, st, a, s.cmode, nrow, ncol, full, 1);
     return TN_OK;
 }
 
@@ -343,7 +365,7 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
             break;
         }
         case VAR_PINGPONG_256x256: {
-            int rc = launch_pingpong<4, 2, 2, 4, 2, 1>(s, a, rows, st);
+            int rc = launch_pingpong(h, s, a, rows, st);
             if (rc != TN_OK) return rc;
             break;
         }
@@ -1111,7 +1133,7 @@ int configure_kernels(int device) {
     const tn_linear_s* no_handle = nullptr;
     int rc = launch_pipe<2, 2, 2, 4, 1, 2>(none, a, 0, nullptr);
     if (rc == TN_OK) rc = launch_pipe<4, 1, 2, 4, 1, 2>(none, a, 0, nullptr);
-    if (rc == TN_OK) rc = launch_pingpong<4, 2, 2, 4, 2, 1>(none, a, 0, nullptr);
+    if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK &&
         (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),

@@ -216,6 +216,20 @@ def test_stack_sample_matrices():
         assert err <= TOL["bf16"], (fmt, n_in, n_out, r, err)
 
 
+@pytest.mark.parametrize("n_out,n_in", [(9216, 64), (8448, 96), (1024, 160), (4352, 64)])
+def test_partly_filled_last_round(n_out, n_in):
+    """The 256x256 kernel at 2048 rows (8 row tiles, one per XCD): 36 and 33 column tiles leave a last
+    round of 4 and 1 tiles per XCD, which runs as half-width tiles in a second launch; 4 column tiles run
+    as half-width tiles altogether; 17 stay as they are. Whole output against the oracle."""
+    spec = _spec(tn.TN_FORMAT_DENSE, "bf16", (n_out,), (n_in,), ())
+    ts = _rand_layer(spec, 900 + n_out)
+    x = wl.round_to_dtype(np.random.default_rng(n_out).standard_normal((2048, spec.N)), "bf16")
+    y = run_layer(spec, ts, x, flags=(12 << 8) | tn.TN_FLAG_NO_SPLIT_K)
+    err = O.rel_max_err(y, O.forward(spec.format, ts, x, n_out_modes=1))
+    print(f"dense {n_in}->{n_out} rel err {err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("variant", [3, 8, 9, 12])
 def test_wide_step_kernel_variants(variant):
     """Every tile variant of the wide bf16 steps (tuning override) on shapes with ragged row
