@@ -56,7 +56,7 @@ struct DevStep {
     int bn = 64, bm = 64;
     bool fuse_next = false;       // this step and the next run as one launch
     void* chain_bbf = nullptr;    // chain2: the next step's packed tensor in the chained layout
-    int chain_cfg = 0;            // chain2 instantiation: 0 <3,6,5>, 1 <2,8,2>
+    int chain_cfg = 0;            // chain2 instantiation: 0 <3,6,5>, 1 <2,8,2>, 2 <2,5,2>
     int chain_run_c1 = 0;         // chain2: output pieces run along c1 (else along c2)
 };
 
@@ -1076,6 +1076,7 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
                            b.Cp, b.Kp);
         if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
         a.fuse_next = true;
+        if (cfg == 1 && a.plan.K <= 80) cfg = 2;         // <2,5,2>: the same layouts with 5 k-steps instead of 8
         a.chain_cfg = cfg;
         a.chain_run_c1 = run_c1;
     }
@@ -1085,11 +1086,12 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
 int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens,
                   hipStream_t st) {
     using k_t = void (*)(Chain2Args);
-    static const k_t kerns[4] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
-                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>};
-    static const size_t smem[2] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>()};
+    static const k_t kerns[6] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
+                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>,
+                                 step_chain2_kernel<2, 5, 2, 0>, step_chain2_kernel<2, 5, 2, 1>};
+    static const size_t smem[3] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>(), chain2_smem_bytes<2, 5, 2>()};
     if (!s1.packed) {                      // configuration call (create time)
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 6; ++i)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     int(smem[i / 2])) != hipSuccess)
                 return TN_ERR_HIP;
@@ -1116,7 +1118,9 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
     p.tiles_per_item = tokens >= waves ? p.c1_tiles : 1;
     const int64_t n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const int64_t items = tokens * n_groups;
-    dim3 grid(uint32_t(std::min<int64_t>((items + 3) / 4, h->num_cus)));
+    // the narrow instantiation leaves room for two workgroups per CU
+    const int64_t wgs = int64_t(h->num_cus) * (s1.chain_cfg == 2 ? 2 : 1);
+    dim3 grid(uint32_t(std::min<int64_t>((items + 3) / 4, wgs)));
     hipLaunchKernelGGL(kerns[s1.chain_cfg * 2 + s1.chain_run_c1], grid, dim3(256), smem[s1.chain_cfg], st, p);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
