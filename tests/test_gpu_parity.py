@@ -216,6 +216,32 @@ def test_stack_sample_matrices():
         assert err <= TOL["bf16"], (fmt, n_in, n_out, r, err)
 
 
+@pytest.mark.parametrize("fmt,n_in,n_out,r", [
+    (wl.FORMAT_DENSE, 5120, 1024, 0), (wl.FORMAT_DENSE, 25600, 5120, 0), (wl.FORMAT_DENSE, 5120, 25600, 0),
+    (wl.FORMAT_TUCKER, 25600, 5120, 80), (wl.FORMAT_TT, 5120, 25600, 96), (wl.FORMAT_TR, 5120, 1024, 32),
+])
+def test_stack_shapes_prefill_8192(fmt, n_in, n_out, r):
+    """Matrices of the 64-layer stack at 8192 tokens, in the launch configuration the stack benchmark times
+    (dense: 128 tiles run as half-width tiles, 640 tiles = two rounds and a half, 3200 tiles; a Tucker layer,
+    a merged train and a ring on its rebuilt half-ring plan): a seeded sample of token rows in full."""
+    tokens = 8192
+    spec = wl.stack_spec(fmt, n_in, n_out, r)
+    ts = wl.make_tensors(spec, 4, instance=7)
+    print(f"[stack 8192] {wl.FORMAT_NAMES[fmt]} {n_in}->{n_out} r={r}: x", flush=True)
+    x = wl.make_x(spec, tokens, 4, instance=7)
+    layer = make_layer(spec, ts, tokens)
+    yd = layer(to_dev(x, spec.dtype))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.random.default_rng(n_in + n_out).choice(tokens, size=12, replace=False),
+                                     [0, 255, 256, tokens - 1]]))
+    y = to_host(yd[torch.from_numpy(rows).cuda()])
+    layer.close()
+    ref = O.forward(fmt, ts, x[rows], n_out_modes=len(spec.out_modes))
+    err = O.rel_max_err(y, ref)
+    print(f"[stack 8192] rel err {err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("n_out,n_in", [(9216, 64), (8448, 96), (1024, 160), (4352, 64)])
 def test_partly_filled_last_round(n_out, n_in):
     """The 256x256 kernel at 2048 rows (8 row tiles, one per XCD): 36 and 33 column tiles leave a last
