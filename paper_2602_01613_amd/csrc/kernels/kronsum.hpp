@@ -453,13 +453,12 @@ __device__ __forceinline__ bf16x8 kron_gather_piece(const bf16_t* G, const unsig
 }
 
 template <int KSS /* k-steps of 16 along the shared bond */>
-__global__ void __launch_bounds__(256) kron_generate_mfma_kernel(KronGenMfmaArgs p) {
+__device__ __forceinline__ void kron_generate_mfma_body(const KronGenMfmaArgs& p, int rho) {
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
     typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
     bf16_t* G = reinterpret_cast<bf16_t*>(dyn_smem);
     const bf16_t* Rc = static_cast<const bf16_t*>(p.Rc);
     const bf16_t* Cc = static_cast<const bf16_t*>(p.Cc);
-    const int rho = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int RT = (p.NR + 31) >> 5, CT = (p.NC + 31) >> 5;
@@ -513,4 +512,16 @@ __global__ void __launch_bounds__(256) kron_generate_mfma_kernel(KronGenMfmaArgs
         const int chunk = lp / p.pieces_per_chunk, rem = lp - chunk * p.pieces_per_chunk;
         dst[(int64_t(chunk) * p.P + rho) * p.pieces_per_chunk + rem] = out;
     }
+}
+
+template <int KSS>
+__global__ void __launch_bounds__(256) kron_generate_mfma_kernel(KronGenMfmaArgs p) {
+    kron_generate_mfma_body<KSS>(p, blockIdx.x);
+}
+
+// Both halves in one launch (the usual case): workgroups 0 .. P0-1 build the first half's slices, the others the second's.
+template <int KSS>
+__global__ void __launch_bounds__(256) kron_generate_mfma_both_kernel(KronGenMfmaArgs p0, KronGenMfmaArgs p1) {
+    if (int(blockIdx.x) < p0.P) kron_generate_mfma_body<KSS>(p0, blockIdx.x);
+    else kron_generate_mfma_body<KSS>(p1, int(blockIdx.x) - p0.P);
 }

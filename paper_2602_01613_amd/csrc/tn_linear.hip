@@ -719,7 +719,30 @@ int gen_mfma_dispatch(const KronGenMfmaArgs* a, size_t smem, hipStream_t st) {
     return TN_OK;
 }
 
+int gen_mfma_both_dispatch(const KronGenMfmaArgs* a0, const KronGenMfmaArgs* a1, size_t smem, hipStream_t st) {
+    using kern_t = void (*)(KronGenMfmaArgs, KronGenMfmaArgs);
+    static const kern_t kerns[4] = {kron_generate_mfma_both_kernel<2>, kron_generate_mfma_both_kernel<4>,
+                                    kron_generate_mfma_both_kernel<6>, kron_generate_mfma_both_kernel<8>};
+    if (!a0) {              // configuration call (create time)
+        for (kern_t k : kerns)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(kGenMfmaMaxSmem)) != hipSuccess)
+                return TN_ERR_HIP;
+        return TN_OK;
+    }
+    const int idx = (std::max(a0->Sp, a1->Sp) + 31) / 32 - 1;
+    if (idx < 0 || idx > 3) return TN_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(kerns[idx], dim3(uint32_t(a0->P + a1->P)), dim3(256), smem, st, *a0, *a1);
+    return TN_OK;
+}
+
 int launch_lazy_generate(const tn_linear_s* h, hipStream_t st) {
+    if (h->lazy_mfma[0] && h->lazy_mfma[1]) {
+        int rc = gen_mfma_both_dispatch(&h->lazy_gen_mfma[0], &h->lazy_gen_mfma[1],
+                                        std::max(h->lazy_gen_smem[0], h->lazy_gen_smem[1]), st);
+        if (rc != TN_OK) return rc;
+        return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+    }
     for (int w = 0; w < 2; ++w) {
         if (h->lazy_mfma[w]) {
             int rc = gen_mfma_dispatch(&h->lazy_gen_mfma[w], h->lazy_gen_smem[w], st);
@@ -1149,6 +1172,7 @@ int configure_kernels(int device) {
         rc = TN_ERR_HIP;
     for (int cfg = 0; cfg < tn::kKronConfigs && rc == TN_OK; ++cfg) rc = kron_dispatch(cfg, nullptr, 0, nullptr);
     if (rc == TN_OK) rc = gen_mfma_dispatch(nullptr, 0, nullptr);
+    if (rc == TN_OK) rc = gen_mfma_both_dispatch(nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK && device >= 0 && device < 64) done[device] = true;
     return rc;
 }
