@@ -122,25 +122,54 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
     bf16x8 xa[AT][KS0];
     {
         const bf16_t* xt = X + int64_t(tl) * p.N;
+        if (p.x_vec8) {
+            // Straight-line code: offsets first (clamped into the tables), then all AT * KS0 loads back to back,
+            // values outside the matrix replaced by zeros afterwards. With a branch around every load each one
+            // waited for the one before, which cost a small call more than its contractions.
+            int ro[AT], co[KS0];
+            bool va[AT], vk[KS0];
 #pragma unroll
-        for (int i = 0; i < AT; ++i) {
-            const int a = 32 * i + (lane & 31);
-            const int ro = a < p.A ? (p.xrow ? p.xrow[a] : a * p.K0) : -1;
+            for (int i = 0; i < AT; ++i) {
+                const int a = 32 * i + (lane & 31);
+                va[i] = a < p.A;
+                const int ac = min(a, p.A - 1);
+                ro[i] = p.xrow ? p.xrow[ac] : ac * p.K0;
+            }
 #pragma unroll
             for (int ks = 0; ks < KS0; ++ks) {
                 const int k = 16 * ks + 8 * (lane >> 5);
-                bf16x8 v;
+                vk[ks] = k < p.K0;                       // K0 % 8 == 0: then k + 8 <= K0 as well
+                const int kc = min(k, p.K0 - 8);
+                co[ks] = p.xcol ? p.xcol[kc] : kc;
+            }
+            bf16x8 zero;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = bf16_t(0.f);
-                if (ro >= 0 && k < p.K0) {
-                    if (p.x_vec8) {
-                        v = *reinterpret_cast<const bf16x8*>(xt + ro + (p.xcol ? p.xcol[k] : k));
-                    } else {
+            for (int e = 0; e < 8; ++e) zero[e] = bf16_t(0.f);
+#pragma unroll
+            for (int i = 0; i < AT; ++i)
+#pragma unroll
+                for (int ks = 0; ks < KS0; ++ks) {
+                    const bf16x8 v = *reinterpret_cast<const bf16x8*>(xt + ro[i] + co[ks]);
+                    xa[i][ks] = (va[i] && vk[ks]) ? v : zero;
+                }
+        } else {
+            // element-wise gather (the k of one a are not contiguous in x); the straight-line form measured slower here
+#pragma unroll
+            for (int i = 0; i < AT; ++i) {
+                const int a = 32 * i + (lane & 31);
+                const int ro = a < p.A ? (p.xrow ? p.xrow[a] : a * p.K0) : -1;
+#pragma unroll
+                for (int ks = 0; ks < KS0; ++ks) {
+                    const int k = 16 * ks + 8 * (lane >> 5);
+                    bf16x8 v;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = bf16_t(0.f);
+                    if (ro >= 0 && k < p.K0) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = xt[ro + p.xcol[k + e]];
                     }
+                    xa[i][ks] = v;
                 }
-                xa[i][ks] = v;
             }
         }
     }
