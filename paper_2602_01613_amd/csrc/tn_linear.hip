@@ -603,7 +603,8 @@ KronGeom kron_geometry(const tn_linear_s* h, const tn::KronDims& d, int64_t toke
     // workgroups a CU holds at a time: one when the three LDS stages take more than half of its 160 KB
     const int* cfg = tn::kKronConfig[d.cfg];
     const int64_t stage_bytes = 4096 * int64_t((cfg[3] * cfg[1] + cfg[2] * 2 * cfg[0] + 3) / 4);
-    const int64_t per_cu = 3 * stage_bytes > 80 * 1024 ? 1 : 2;
+    // (measured: with several chunks of o1 the two-round split is the faster one at rank 96, so it is kept there)
+    const int64_t per_cu = (3 * stage_bytes > 80 * 1024 && g.n_chunks == 1) ? 1 : 2;
     int64_t want = std::max<int64_t>(1, (per_cu * int64_t(h->num_cus) + base - 1) / base);
     if (base >= h->num_cus) want = 1;
     // at least 4 values of the bond per workgroup, partial sums within their buffer
