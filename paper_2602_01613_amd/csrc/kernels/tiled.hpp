@@ -644,6 +644,7 @@ step_mfma_pingpong_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles,
     constexpr size_t C_ELEMS = size_t(BM) * LDC > size_t(BN) * LDR ? size_t(BM) * LDC : size_t(BN) * LDR;
     bf16_t* sC = reinterpret_cast<bf16_t*>(dyn_smem);
     int64_t* sBase = reinterpret_cast<int64_t*>(dyn_smem + C_ELEMS * sizeof(bf16_t));
+    int32_t* sCol = reinterpret_cast<int32_t*>(sBase + BM);    // output offsets of the tile's columns (-1: no such column)
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -673,33 +674,35 @@ step_mfma_pingpong_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles,
         }
         sBase[rr] = base;
     }
+    // (looked up once per tile: inside the store loops every lookup would sit between two stores)
+    for (int cc = tid; cc < BN; cc += NT) sCol[cc] = col0 + cc < a.C ? a.ccol[col0 + cc] : -1;
     __syncthreads();
     constexpr int GROUPS = BM * BN / 8;
     if (TRANS) {
 #pragma unroll 4
         for (int e = tid; e < GROUPS; e += NT) {
             int rg = (e % (BM / 8)) * 8, cc = e / (BM / 8);
-            int c = col0 + cc;
             int64_t base = sBase[rg];
-            if (base < 0 || c >= a.C) continue;
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + cc * LDR + rg);
+            const int co = sCol[cc];
+            if (base < 0 || co < 0) continue;
+            *reinterpret_cast<bf16x8*>(Out + base + co) = *reinterpret_cast<const bf16x8*>(sC + cc * LDR + rg);
         }
     } else if (cmode == 1) {
 #pragma unroll 4
         for (int e = tid; e < GROUPS; e += NT) {
             int rr = e / (BN / 8), cg = (e % (BN / 8)) * 8;
-            int c = col0 + cg;
             int64_t base = sBase[rr];
-            if (base < 0 || c >= a.C) continue;
-            *reinterpret_cast<bf16x8*>(Out + base + a.ccol[c]) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
+            const int co = sCol[cg];
+            if (base < 0 || co < 0) continue;
+            *reinterpret_cast<bf16x8*>(Out + base + co) = *reinterpret_cast<const bf16x8*>(sC + rr * LDC + cg);
         }
     } else {
         for (int e = tid; e < BM * BN; e += NT) {
             int rr = e / BN, cc = e % BN;
-            int c = col0 + cc;
             int64_t base = sBase[rr];
-            if (base < 0 || c >= a.C) continue;
-            Out[base + a.ccol[c]] = sC[rr * LDC + cc];
+            const int co = sCol[cc];
+            if (base < 0 || co < 0) continue;
+            Out[base + co] = sC[rr * LDC + cc];
         }
     }
 }
@@ -709,7 +712,7 @@ constexpr size_t pingpong_smem_bytes() {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t stage = size_t(BM + BN) * 64 * NS;
     constexpr size_t c_elems = size_t(BM) * (BN + 8) > size_t(BN) * (BM + 8) ? size_t(BM) * (BN + 8) : size_t(BN) * (BM + 8);
-    constexpr size_t epi = c_elems * 2 + size_t(BM) * 8;
+    constexpr size_t epi = c_elems * 2 + size_t(BM) * 8 + size_t(BN) * 4;
     return stage > epi ? stage : epi;
 }
 
