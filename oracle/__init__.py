@@ -7,6 +7,7 @@ HIP library and never imports it.
 from .tn_oracle import (  # noqa: F401
     tt_dense,
     tr_dense,
+    tr_dense_rows,
     tucker_dense,
     dense_weight,
     apply_linear,

@@ -310,3 +310,57 @@ def test_rel_max_err():
     b = a + np.array([[0.0, 0.0], [0.0, 0.04]])
     assert abs(O.rel_max_err(b, a) - 0.01) < 1e-15
     assert O.rel_max_err(np.zeros((0, 3)), np.zeros((0, 3))) == 0.0
+
+
+# ---- row-sampled ring rebuild: per-entry traces, brute force, ring of one core, boundary rank 1 ----
+def test_tr_rows_entries_are_traces_of_matrix_products():
+    rng = np.random.default_rng(21)
+    ms, ns, rs = (2, 3, 2, 3), (3, 2, 4, 2), (3, 2, 4, 2, 3)      # non-square modes, unequal bonds
+    cores = _cores(rng, ms, ns, rs)
+    rows = [0, 7, 17, 35, 20]
+    w = O.tr_dense_rows(cores, rows)
+    assert w.shape == (5, prod(ns))
+    for n, fi in enumerate(rows):
+        i = np.unravel_index(fi, ms)
+        for fj in (0, 5, 13, 47, 30):
+            j = np.unravel_index(fj, ns)
+            mat = np.eye(rs[0])
+            for k in range(4):
+                mat = mat @ cores[k][:, i[k], j[k], :]
+            assert abs(w[n, fj] - np.trace(mat)) < 1e-12
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 5])
+def test_tr_rows_brute_force_and_train(d):
+    rng = np.random.default_rng(30 + d)
+    ms = [2, 3, 2, 2, 2][:d]
+    ns = [3, 2, 2, 3, 2][:d]
+    rs = ([2] + [3, 2, 2, 3][: d - 1] + [2]) if d > 1 else [3, 3]
+    cores = _cores(rng, ms, ns, rs)
+    rows = list(range(prod(ms)))[::-1]                              # every row, in reverse order
+    brute = O.brute_force_weight(TR, cores)
+    np.testing.assert_allclose(O.tr_dense_rows(cores, rows), brute[rows], atol=1e-12)
+    # boundary rank 1: the ring is a train, whose rows the Kronecker-pinned tt_dense gives
+    rs1 = [1] + rs[1:-1] + [1]
+    train = _cores(rng, ms, ns, rs1)
+    np.testing.assert_allclose(O.tr_dense_rows(train, rows[:3]), O.tt_dense(train)[rows[:3]], atol=1e-12)
+
+
+def test_planted_row_digit_mistake_is_detected():
+    """A little-endian reading of the sampled row's digits must not pass the trace pin."""
+    rng = np.random.default_rng(33)
+    ms, ns, rs = (2, 3), (3, 2), (2, 3, 2)
+    cores = _cores(rng, ms, ns, rs)
+    fi = 1                                                          # digits (0, 1); little-endian would read (1, 0)
+    wrong = np.trace(cores[0][:, 1, 0, :] @ cores[1][:, 0, 0, :])
+    assert abs(O.tr_dense_rows(cores, [fi])[0, 0] - wrong) > 1e-6
+
+
+# ---- a dense matrix handed over as a single core [1, M, N, 1] --------------------------------
+def test_dense_weight_accepts_a_single_core():
+    rng = np.random.default_rng(34)
+    w = rng.standard_normal((5, 7))                                 # non-square: a transposed reshape fails
+    np.testing.assert_array_equal(O.dense_weight(DENSE, [w.reshape(1, 5, 7, 1)]), w)
+    np.testing.assert_array_equal(O.dense_weight(DENSE, [w.reshape(1, 5, 7, 1)]), O.tt_dense([w.reshape(1, 5, 7, 1)]))
+    x = rng.standard_normal((3, 7))
+    np.testing.assert_allclose(O.forward(DENSE, [w.reshape(1, 5, 7, 1)], x), x @ w.T, atol=1e-13)
