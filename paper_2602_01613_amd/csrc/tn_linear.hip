@@ -15,6 +15,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -48,7 +49,6 @@ enum Variant : int {
 struct DevStep {
     tn::Step plan;
     void* packed = nullptr;       // [Cp][Kp]
-    int32_t* tables = nullptr;    // arow | acol | crow | ccol in one allocation
     const int32_t *arow = nullptr, *acol = nullptr, *crow = nullptr, *ccol = nullptr;
     int Kp = 0, Cp = 0;
     int variant = VAR_SCALAR;
@@ -68,9 +68,11 @@ struct tn_linear_s {
     int elt = 4;
     int64_t max_tokens = 0, chunk_tokens = 0;
     int64_t packed_bytes = 0, workspace_bytes = 0;
+    int32_t* tables = nullptr;        // arow | acol | crow | ccol of every step, one allocation
     void* ws[2] = {nullptr, nullptr};
     void* partial = nullptr;          // fp32 partial sums of the split-K kernel
     int64_t partial_bytes = 0;
+    std::vector<tn::LaunchIO> schedule;   // launches of one pass over the chain and the buffers they use
     int flags = 0;
     bool owns_workspace = true;
     int device = 0;
@@ -100,6 +102,7 @@ struct tn_linear_s {
     tn::Plan lazy_plan;
     tn::KronDims lazy_dims;
     int64_t lazy_min_tokens = 0;
+    int64_t lazy_kept_bytes = 0;              // what the lazy plan added to packed_bytes (sources and tables)
     int64_t lazy_slice_bytes = 0;             // both slice arrays
     int64_t lazy_h1_offset = 0;               // byte offset of the second array inside the slice buffer
     void* lazy_slices = nullptr;              // in the workspace (owned or caller's)
@@ -118,7 +121,16 @@ struct tn_linear_s {
 
 namespace {
 
-constexpr int64_t kDefaultWorkspaceBytes = int64_t(16) << 30;
+constexpr int64_t kDefaultWorkspaceBytes = int64_t(4) << 30;
+
+// The scratch memory a forward call works in: the two intermediate buffers (each holds chunk_tokens tokens
+// of the largest intermediate) and the fp32 partial sums of the split kernels: the handle's own workspace.
+struct Workspace {
+    void* ws[2] = {nullptr, nullptr};
+    void* partial = nullptr;
+    int64_t partial_bytes = 0;
+    int64_t chunk_tokens = 0;
+};
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
@@ -135,9 +147,9 @@ void free_handle(tn_linear_s* h) {
     clear_profile(h);
     for (auto& s : h->steps) {
         if (s.packed) (void)hipFree(s.packed);
-        if (s.tables) (void)hipFree(s.tables);
         if (s.chain_bbf) (void)hipFree(s.chain_bbf);
     }
+    if (h->tables) (void)hipFree(h->tables);
     if (h->pair_b1f) (void)hipFree(h->pair_b1f);
     if (h->kron_h0f) (void)hipFree(h->kron_h0f);
     if (h->kron_h1f) (void)hipFree(h->kron_h1f);
@@ -308,7 +320,7 @@ int launch_pingpong(const tn_linear_s* h, const DevStep& s, const StepArgs& a, i
     return TN_OK;
 }
 
-int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out, int64_t tokens,
+int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, const void* A, void* Out, int64_t tokens,
                 hipStream_t st) {
     StepArgs a;
     a.A = A;
@@ -328,9 +340,9 @@ int launch_step(const tn_linear_s* h, const DevStep& s, const void* A, void* Out
     a.C = int32_t(s.plan.C);
     a.Cp = s.Cp;
     SplitCfg sc = (h->flags & TN_FLAG_NO_SPLIT_K) ? SplitCfg() : split_config(s, rows);
-    if (sc.use && (sc.partial_bytes == 0 || (h->partial && sc.partial_bytes <= h->partial_bytes))) {
+    if (sc.use && (sc.partial_bytes == 0 || (w.partial && sc.partial_bytes <= w.partial_bytes))) {
         dim3 sgrid(uint32_t(sc.row_tiles), uint32_t(sc.col_blocks), uint32_t(sc.nsplit));
-        float* part = static_cast<float*>(h->partial);
+        float* part = static_cast<float*>(w.partial);
         using split_t = void (*)(StepArgs, float*, int);
         split_t k;
         if (sc.tm == 1)
@@ -660,12 +672,13 @@ struct KronSetup {
     const int32_t *xrow, *xcol, *yrow, *ycol;
 };
 
-int launch_kron(const tn_linear_s* h, const KronSetup& k, const void* x, void* y, int64_t tokens, hipStream_t st) {
+int launch_kron(const tn_linear_s* h, const Workspace& w, const KronSetup& k, const void* x, void* y, int64_t tokens,
+                hipStream_t st) {
     const tn::KronDims& d = *k.dims;
-    const KronGeom g = kron_geometry(h, d, tokens, h->partial_bytes);
+    const KronGeom g = kron_geometry(h, d, tokens, w.partial_bytes);
     KronArgs p;
     p.X = x;
-    p.Y = g.n_splits > 1 ? h->partial : y;
+    p.Y = g.n_splits > 1 ? w.partial : y;
     p.H0f = k.h0f;
     p.H1f = k.h1f;
     p.xrow = k.xrow;
@@ -690,17 +703,17 @@ int launch_kron(const tn_linear_s* h, const KronSetup& k, const void* x, void* y
     if (g.n_splits > 1) {
         const int64_t n = tokens * h->plan.M;
         hipLaunchKernelGGL(kron_reduce_kernel, dim3(uint32_t((n + 63) / 64)), dim3(256), 0, st,
-                           static_cast<const float*>(h->partial), static_cast<bf16_t*>(y), n, g.n_splits);
+                           static_cast<const float*>(w.partial), static_cast<bf16_t*>(y), n, g.n_splits);
     }
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
-int launch_kron_eager(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+int launch_kron_eager(const tn_linear_s* h, const Workspace& w, const void* x, void* y, int64_t tokens, hipStream_t st) {
     const DevStep& s0 = h->steps[0];
     const DevStep& s1 = h->steps[1];
     KronSetup k{&h->kron_dims, h->kron_h0f, h->kron_h1f, s0.plan.a_plain ? nullptr : s0.arow,
                 s0.plan.a_plain ? nullptr : s0.acol, s1.crow, s1.ccol};
-    return launch_kron(h, k, x, y, tokens, st);
+    return launch_kron(h, w, k, x, y, tokens, st);
 }
 
 // Large calls of a layer with a lazily merged plan: rebuild the two slice arrays in the workspace from the
@@ -921,10 +934,10 @@ std::vector<int32_t> minor_digit_permutation(const std::vector<int64_t>& extents
     return perm;
 }
 
-int launch_kron_lazy(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+int launch_kron_lazy(const tn_linear_s* h, const Workspace& w, const void* x, void* y, int64_t tokens, hipStream_t st) {
     KronSetup k{&h->lazy_dims, h->lazy_slices, static_cast<const char*>(h->lazy_slices) + h->lazy_h1_offset,
                 h->lazy_xrow, h->lazy_xcol, h->lazy_yrow, h->lazy_ycol};
-    return launch_kron(h, k, x, y, tokens, st);
+    return launch_kron(h, w, k, x, y, tokens, st);
 }
 
 // Token count from which a lazily merged plan replaces the compact steps.
@@ -1088,11 +1101,11 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
     if (h->plan.dtype != TN_DTYPE_BF16 || (h->flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_CHAIN2)) ||
         h->pair || h->kron)
         return TN_OK;
+    const std::vector<int> pairs = tn::chain2_pairs(h->plan);
     for (size_t i = 0; i + 1 < h->steps.size(); ++i) {
         DevStep& a = h->steps[i];
         DevStep& b = h->steps[i + 1];
-        if (i > 0 && h->steps[i - 1].fuse_next) continue;
-        if (a.variant == VAR_SCALAR || b.variant == VAR_SCALAR) continue;
+        if (!pairs[i] || a.variant == VAR_SCALAR || b.variant == VAR_SCALAR) continue;
         int cfg = 0, run_c1 = 0;
         if (!tn::chain2_shape(h->plan, a.plan, b.plan, &cfg, &run_c1)) continue;
         const int C2T = cfg == 0 ? 5 : 2, KS = cfg == 0 ? 6 : 4;
@@ -1159,6 +1172,8 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
 // every kernel they can launch and return.
 int configure_kernels(int device) {
     static bool done[64] = {};
+    static std::mutex lock;                // handles may be created from several host threads
+    std::lock_guard<std::mutex> guard(lock);
     if (device >= 0 && device < 64 && done[device]) return TN_OK;
     const DevStep none;                    // packed == nullptr: configuration call
     const StepArgs a{};
@@ -1414,46 +1429,44 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         free_handle(h);
         return rc;
     }
-    for (size_t i = 0; i < h->steps.size(); ++i) {
-        DevStep& s = h->steps[i];
-        s.plan = h->plan.steps[i];
-        choose_variant(h, &s, desc->flags);
-        const tn::Step& p = s.plan;
-        // offset tables
-        size_t n_tab = p.arow.size() + p.acol.size() + p.crow.size() + p.ccol.size();
-        std::vector<int32_t> host_tab;
-        host_tab.reserve(n_tab);
-        host_tab.insert(host_tab.end(), p.arow.begin(), p.arow.end());
-        host_tab.insert(host_tab.end(), p.acol.begin(), p.acol.end());
-        host_tab.insert(host_tab.end(), p.crow.begin(), p.crow.end());
-        host_tab.insert(host_tab.end(), p.ccol.begin(), p.ccol.end());
-        if (hipMalloc(reinterpret_cast<void**>(&s.tables), n_tab * sizeof(int32_t)) != hipSuccess) {
+    // offset tables of every step (arow | acol | crow | ccol each): one allocation, one copy; the host copy
+    // lives until create's final synchronisation
+    std::vector<int32_t> host_tab;
+    {
+        std::vector<size_t> tab_off(h->steps.size());
+        for (size_t i = 0; i < h->steps.size(); ++i) {
+            DevStep& s = h->steps[i];
+            s.plan = h->plan.steps[i];
+            choose_variant(h, &s, desc->flags);
+            const tn::Step& p = s.plan;
+            tab_off[i] = host_tab.size();
+            host_tab.insert(host_tab.end(), p.arow.begin(), p.arow.end());
+            host_tab.insert(host_tab.end(), p.acol.begin(), p.acol.end());
+            host_tab.insert(host_tab.end(), p.crow.begin(), p.crow.end());
+            host_tab.insert(host_tab.end(), p.ccol.begin(), p.ccol.end());
+        }
+        if (hipMalloc(reinterpret_cast<void**>(&h->tables), std::max<size_t>(1, host_tab.size()) * sizeof(int32_t)) != hipSuccess ||
+            hipMemcpyAsync(h->tables, host_tab.data(), host_tab.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess) {
             (void)hipStreamSynchronize(st);
             release_temps();
             free_handle(h);
             return TN_ERR_ALLOC;
         }
-        // pageable source: the copy is staged before the call returns, so host_tab may go away
-        if (hipMemcpyAsync(s.tables, host_tab.data(), n_tab * sizeof(int32_t), hipMemcpyHostToDevice, st) !=
-            hipSuccess) {
-            (void)hipStreamSynchronize(st);
-            release_temps();
-            free_handle(h);
-            return TN_ERR_HIP;
+        for (size_t i = 0; i < h->steps.size(); ++i) {
+            DevStep& s = h->steps[i];
+            const tn::Step& p = s.plan;
+            const int32_t* t = h->tables + tab_off[i];
+            if (!p.a_plain) {
+                s.arow = t;
+                s.acol = t + p.arow.size();
+            }
+            s.crow = t + p.arow.size() + p.acol.size();
+            s.ccol = s.crow + p.crow.size();
         }
-        if (hipStreamSynchronize(st) != hipSuccess) {
-            (void)hipStreamSynchronize(st);
-            release_temps();
-            free_handle(h);
-            return TN_ERR_HIP;
-        }
-        const int32_t* t = s.tables;
-        if (!p.a_plain) {
-            s.arow = t;
-            s.acol = t + p.arow.size();
-        }
-        s.crow = t + p.arow.size() + p.acol.size();
-        s.ccol = s.crow + p.crow.size();
+    }
+    for (size_t i = 0; i < h->steps.size(); ++i) {
+        DevStep& s = h->steps[i];
+        const tn::Step& p = s.plan;
         // packed parameter tensor
         int64_t bytes = int64_t(s.Cp) * s.Kp * h->elt;
         if (hipMalloc(&s.packed, size_t(bytes)) != hipSuccess) {
@@ -1496,7 +1509,11 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     if (rc == TN_OK) rc = prepare_pair(h, st);
     if (rc == TN_OK) rc = prepare_kron(h, st);
     if (rc == TN_OK) rc = plan_chain2(h, st);
-    if (rc == TN_OK) rc = prepare_lazy(h, desc, st);
+    if (rc == TN_OK) {
+        const int64_t before = h->packed_bytes;
+        rc = prepare_lazy(h, desc, st);
+        h->lazy_kept_bytes = h->packed_bytes - before;
+    }
     if (rc != TN_OK) {
         (void)hipStreamSynchronize(st);
         free_handle(h);
@@ -1535,7 +1552,27 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         const int64_t room = desc->workspace
                                  ? desc->workspace_bytes - (split_ok ? std::min<int64_t>(kMaxPartialBytes, desc->workspace_bytes / 4) : 0) - 512
                                  : (desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes);
-        if (room < h->lazy_slice_bytes) h->lazy = false;
+        if (room < h->lazy_slice_bytes) {
+            // no room for the slices: every call runs the compact steps, and what the lazy plan kept goes away
+            // (the kernels that wrote these buffers may still be running on the stream)
+            if (hipStreamSynchronize(st) != hipSuccess) {
+                free_handle(h);
+                return TN_ERR_HIP;
+            }
+            h->lazy = false;
+            h->packed_bytes -= h->lazy_kept_bytes;
+            h->lazy_kept_bytes = 0;
+            for (void* v : h->lazy_sources) (void)hipFree(v);
+            h->lazy_sources.clear();
+            for (int w = 0; w < 2; ++w)
+                if (h->lazy_gen_tables[w]) {
+                    (void)hipFree(h->lazy_gen_tables[w]);
+                    h->lazy_gen_tables[w] = nullptr;
+                    h->lazy_mfma[w] = false;
+                }
+            if (h->lazy_tables) (void)hipFree(h->lazy_tables);
+            h->lazy_tables = nullptr;
+        }
     }
     // with the chained pair kernel or a lazily merged plan only calls below the token threshold use the buffers
     int64_t ws_tokens = h->pair ? std::min<int64_t>(h->max_tokens, h->pair_min_tokens - 1) : h->max_tokens;
@@ -1602,41 +1639,65 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         h->lazy_gen_mfma[w].dst = h->lazy_gen[w].dst;
     }
     h->chunk_tokens = chunk;
+    {
+        std::vector<int> fuse(h->steps.size(), 0);
+        for (size_t i = 0; i < h->steps.size(); ++i) fuse[i] = h->steps[i].fuse_next ? 1 : 0;
+        h->schedule = tn::launch_schedule(h->steps.size(), fuse);
+    }
+    // everything create enqueued (repacking, table uploads) is done before the handle is handed out, so
+    // that a forward on any stream may follow without further ordering
+    if (hipStreamSynchronize(st) != hipSuccess) {
+        free_handle(h);
+        return TN_ERR_HIP;
+    }
     *out = h;
     return TN_OK;
 }
 
-int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
-    if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
-    if (tokens == 0) return TN_OK;
-    if (!x || !y) return TN_ERR_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+}  // extern "C"
+
+namespace {
+
+// Brackets one launch with a pair of HIP events when the handle is being profiled.
+struct ProfScope {
+    tn_linear_s* h;
+    hipStream_t st;
+    tn_linear_s::ProfRec rec;
+    bool ok = true;
+    ProfScope(tn_linear_s* handle, int step, hipStream_t stream) : h(handle), st(stream), rec{step, nullptr, nullptr} {
+        if (!h->profiling) return;
+        ok = hipEventCreate(&rec.start) == hipSuccess && hipEventCreate(&rec.stop) == hipSuccess;
+        if (ok) (void)hipEventRecord(rec.start, st);
+    }
+    void done() {
+        if (!h->profiling || !ok) return;
+        (void)hipEventRecord(rec.stop, st);
+        h->prof.push_back(rec);
+    }
+};
+
+// One forward call in the workspace `w`. allow_lazy: calls large enough may run on the lazily merged plan,
+// whose slices live in the handle's own workspace.
+int forward_in(tn_linear_s* h, const Workspace& w, bool allow_lazy, const void* x, void* y, int64_t tokens,
+               hipStream_t st) {
     const char* xb = static_cast<const char*>(x);
     char* yb = static_cast<char*>(y);
-    size_t ns = h->steps.size();
     if (h->small_chain && (h->elt == 4 || tokens <= kSmallChainMaxBf16Tokens)) {
         // every step in one launch, tensors and intermediates in LDS
         const int64_t pass = int64_t(1) << 24;
         for (int64_t t0 = 0; t0 < tokens; t0 += pass) {
             int64_t nt = std::min(pass, tokens - t0);
-            tn_linear_s::ProfRec rec{0, nullptr, nullptr};
-            if (h->profiling) {
-                if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess)
-                    return TN_ERR_HIP;
-                (void)hipEventRecord(rec.start, st);
-            }
+            ProfScope prof(h, 0, st);
+            if (!prof.ok) return TN_ERR_HIP;
             int rc = launch_small_chain(h, xb + t0 * h->plan.N * h->elt, yb + t0 * h->plan.M * h->elt, nt, st);
-            if (h->profiling) {
-                (void)hipEventRecord(rec.stop, st);
-                h->prof.push_back(rec);
-            }
+            prof.done();
             if (rc != TN_OK) return rc;
         }
         return TN_OK;
     }
     const bool use_pair = h->pair && tokens >= h->pair_min_tokens;
     const bool use_kron = h->kron && tokens >= h->kron_min_tokens;
-    const bool use_lazy = h->lazy && tokens >= h->lazy_min_tokens;
+    const bool use_lazy = allow_lazy && h->lazy && tokens >= h->lazy_min_tokens;
     if (use_pair || use_kron || use_lazy) {
         // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
         // (and, for the Kronecker-sum kernel, keep a call's partial sums within their buffer)
@@ -1647,48 +1708,50 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
         }
         for (int64_t t0 = 0; t0 < tokens; t0 += pass) {
             int64_t nt = std::min(pass, tokens - t0);
-            tn_linear_s::ProfRec rec{0, nullptr, nullptr};
-            if (h->profiling) {
-                if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess)
-                    return TN_ERR_HIP;
-                (void)hipEventRecord(rec.start, st);
-            }
+            ProfScope prof(h, 0, st);
+            if (!prof.ok) return TN_ERR_HIP;
             const void* xp = xb + t0 * h->plan.N * h->elt;
             void* yp = yb + t0 * h->plan.M * h->elt;
             int rc = use_pair ? launch_pair(h, xp, yp, nt, st)
-                              : (use_kron ? launch_kron_eager(h, xp, yp, nt, st) : launch_kron_lazy(h, xp, yp, nt, st));
-            if (h->profiling) {
-                (void)hipEventRecord(rec.stop, st);
-                h->prof.push_back(rec);
-            }
+                              : (use_kron ? launch_kron_eager(h, w, xp, yp, nt, st) : launch_kron_lazy(h, w, xp, yp, nt, st));
+            prof.done();
             if (rc != TN_OK) return rc;
         }
         return TN_OK;
     }
-    for (int64_t t0 = 0; t0 < tokens; t0 += h->chunk_tokens) {
-        int64_t nt = std::min(h->chunk_tokens, tokens - t0);
-        for (size_t s = 0; s < ns; ++s) {
-            const bool fused = h->steps[s].fuse_next;
-            const size_t so = fused ? s + 1 : s;                 // step whose output this launch writes
-            const void* A = (s == 0) ? static_cast<const void*>(xb + t0 * h->plan.N * h->elt) : h->ws[(s - 1) & 1];
-            void* Out = (so == ns - 1) ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : h->ws[so & 1];
-            tn_linear_s::ProfRec rec{int(s), nullptr, nullptr};
-            if (h->profiling) {
-                if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess)
-                    return TN_ERR_HIP;
-                (void)hipEventRecord(rec.start, st);
-            }
-            int rc = fused ? launch_chain2(h, h->steps[s], h->steps[s + 1], A, Out, nt, st)
-                           : launch_step(h, h->steps[s], A, Out, nt, st);
-            if (h->profiling) {
-                (void)hipEventRecord(rec.stop, st);
-                h->prof.push_back(rec);
-            }
+    if (w.chunk_tokens < 1) return TN_ERR_INVALID_ARG;
+    for (int64_t t0 = 0; t0 < tokens; t0 += w.chunk_tokens) {
+        int64_t nt = std::min(w.chunk_tokens, tokens - t0);
+        for (const tn::LaunchIO& l : h->schedule) {
+            const void* A = l.in == tn::kBufX ? static_cast<const void*>(xb + t0 * h->plan.N * h->elt) : w.ws[l.in];
+            void* Out = l.out == tn::kBufY ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : w.ws[l.out];
+            ProfScope prof(h, l.first, st);
+            if (!prof.ok) return TN_ERR_HIP;
+            const DevStep& s = h->steps[size_t(l.first)];
+            int rc = l.steps == 2 ? launch_chain2(h, s, h->steps[size_t(l.first) + 1], A, Out, nt, st)
+                                  : launch_step(h, w, s, A, Out, nt, st);
+            prof.done();
             if (rc != TN_OK) return rc;
-            if (fused) ++s;
         }
     }
     return TN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
+    if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
+    if (tokens == 0) return TN_OK;
+    if (!x || !y) return TN_ERR_INVALID_ARG;
+    Workspace w;
+    w.ws[0] = h->ws[0];
+    w.ws[1] = h->ws[1];
+    w.partial = h->partial;
+    w.partial_bytes = h->partial_bytes;
+    w.chunk_tokens = h->chunk_tokens;
+    return forward_in(h, w, true, x, y, tokens, static_cast<hipStream_t>(stream));
 }
 
 int tn_linear_profile(tn_linear_t h, int32_t enable) {

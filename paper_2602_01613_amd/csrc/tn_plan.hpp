@@ -727,6 +727,46 @@ inline bool chain2_shape(const Plan& p, const Step& a, const Step& b, int* cfg, 
     return true;
 }
 
+// Which consecutive step pairs run as one launch of the transposing chain kernel: qualifying pairs are
+// taken left to right, a step belongs to at most one pair. fuse[i] = 1 + instantiation when steps i and
+// i + 1 are one launch, else 0.
+inline std::vector<int> chain2_pairs(const Plan& p) {
+    std::vector<int> fuse(p.steps.size(), 0);
+    if (p.dtype != TN_DTYPE_BF16 || (p.flags & (TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_CHAIN2))) return fuse;
+    for (size_t i = 0; i + 1 < p.steps.size(); ++i) {
+        if (i > 0 && fuse[i - 1]) continue;
+        int cfg = 0, run_c1 = 0;
+        if (chain2_shape(p, p.steps[i], p.steps[i + 1], &cfg, &run_c1)) fuse[i] = 1 + cfg;
+    }
+    return fuse;
+}
+
+// Buffers of the launches of one pass over the chain. A launch covers step `first` (and `first + 1` when
+// fused) and reads `in`, writes `out`: kBufX is the caller's x, kBufY the caller's y, 0 and 1 the two
+// workspace buffers. The buffer alternates per LAUNCH, not per step, so that a launch never writes the
+// buffer it reads, wherever fused pairs sit in the chain.
+constexpr int kBufX = -1, kBufY = -2;
+struct LaunchIO {
+    int first = 0, steps = 1, in = kBufX, out = kBufY;
+};
+
+inline std::vector<LaunchIO> launch_schedule(size_t n_steps, const std::vector<int>& fuse) {
+    std::vector<LaunchIO> out;
+    int in = kBufX, next = 0;
+    for (size_t s = 0; s < n_steps;) {
+        LaunchIO l;
+        l.first = int(s);
+        l.steps = (s < fuse.size() && fuse[s] && s + 1 < n_steps) ? 2 : 1;
+        l.in = in;
+        s += size_t(l.steps);
+        l.out = s >= n_steps ? kBufY : next;
+        out.push_back(l);
+        in = l.out;
+        next ^= 1;
+    }
+    return out;
+}
+
 // TN_FLAG_MERGE_HALVES: merges may grow up to kMaxHalvesElems elements in total but stop at two parameter tensors.
 constexpr double kMaxHalvesElems = 1.0e9;
 

@@ -96,3 +96,20 @@ extern "C" int plan_host_step_hint(const tn_linear_desc* d, int step, int field,
     *value = field == 0 ? st.c_vec : field == 1 ? st.r_vec : field == 2 ? int64_t(st.a_plain) : int64_t(p.merges.size());
     return 0;
 }
+
+// Buffers of the launches of one pass (see tn::launch_schedule) with the chained factor pairs the plan
+// allows: in_buf / out_buf receive one entry per launch (-1 = x, -2 = y, 0 / 1 = workspace buffers),
+// steps the number of steps each launch covers. Returns the number of launches, or a negative status.
+extern "C" int plan_host_launch_buffers(const tn_linear_desc* d, int cap, int* in_buf, int* out_buf, int* steps) {
+    tn::Plan p;
+    int rc = tn::make_plan(d, &p);
+    if (rc != TN_OK) return rc;
+    const std::vector<tn::LaunchIO> sched = tn::launch_schedule(p.steps.size(), tn::chain2_pairs(p));
+    if (int(sched.size()) > cap) return TN_ERR_INVALID_ARG;
+    for (size_t i = 0; i < sched.size(); ++i) {
+        in_buf[i] = sched[i].in;
+        out_buf[i] = sched[i].out;
+        steps[i] = sched[i].steps;
+    }
+    return int(sched.size());
+}

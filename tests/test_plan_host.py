@@ -26,6 +26,9 @@ def host_exec():
     lib.plan_host_forward.restype = ctypes.c_int
     lib.plan_host_forward.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(ctypes.c_void_p),
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+    lib.plan_host_launch_buffers.restype = ctypes.c_int
+    lib.plan_host_launch_buffers.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                             ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.plan_host_step_hint.restype = ctypes.c_int
     lib.plan_host_step_hint.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int, ctypes.c_int,
                                         ctypes.POINTER(ctypes.c_int64)]
@@ -242,6 +245,39 @@ def test_chain2_shapes():
         assert not any(shapes(s.format, s.out_modes, s.in_modes, s.ranks))
         assert not any(shapes(s.format, s.out_modes, s.in_modes, s.ranks, tn.TN_FLAG_NO_MERGE))
     assert tn.plan_query(s2.format, tn.TN_DTYPE_F32, s2.out_modes, s2.in_modes, s2.ranks, tn.TN_QUERY_STEP_BASE + 7) == 0
+
+
+def _launch_buffers(lib, fmt, om, im, rk, flags=0):
+    d, keep = _make_desc(fmt, tn.TN_DTYPE_BF16, om, im, rk, None, 1, 0, flags, None)
+    cap = 32
+    a, b, c = (ctypes.c_int * cap)(), (ctypes.c_int * cap)(), (ctypes.c_int * cap)()
+    n = lib.plan_host_launch_buffers(ctypes.byref(d), cap, a, b, c)
+    assert n > 0, n
+    return [(a[i], b[i], c[i]) for i in range(n)]
+
+
+def test_no_launch_writes_the_buffer_it_reads(host_exec):
+    """Buffers alternate per launch, not per step: a chained pair in the middle of a chain (a Tucker layer
+    with three modes on one side and an axis of extent 1) must not get the same workspace buffer as input
+    and output. Also over random descriptions with small extents (1 included)."""
+    sched = _launch_buffers(host_exec, tn.TN_FORMAT_TUCKER, (160, 96, 16), (64,), (48, 32, 1, 16))
+    assert any(steps == 2 and first_in >= 0 and out >= 0 for first_in, out, steps in sched), sched
+    rng = np.random.default_rng(77)
+    seen_mid_pair = 0
+    for trial in range(3000):
+        p, q = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        om = tuple(int(v) for v in rng.choice([1, 8, 16, 32, 48, 64, 96, 160], p))
+        im = tuple(int(v) for v in rng.choice([1, 8, 16, 32, 48, 64, 96, 160], q))
+        rk = tuple(int(min(m, v)) for m, v in zip(om + im, rng.choice([1, 8, 16, 32, 48, 64, 96], p + q)))
+        sched = _launch_buffers(host_exec, tn.TN_FORMAT_TUCKER, om, im, rk)
+        assert sched[0][0] == -1 and sched[-1][1] == -2
+        for n, (src, dst, steps) in enumerate(sched):
+            assert src != dst, (om, im, rk, sched)
+            if n:
+                assert src == sched[n - 1][1]
+            if steps == 2 and 0 < n < len(sched) - 1:
+                seen_mid_pair += 1
+    assert seen_mid_pair > 0
 
 
 def test_growing_merges_half_ring():
