@@ -39,6 +39,8 @@ extern "C" {
 #define TN_ERR_UNSUPPORTED   (-2)   /* valid request this build cannot run (e.g. too many modes) */
 #define TN_ERR_ALLOC         (-3)   /* host or device allocation failed */
 #define TN_ERR_HIP           (-4)   /* a HIP runtime call or kernel launch failed */
+#define TN_ERR_SCRATCH       (-5)   /* tn_linear_forward_scratch: the call needs more scratch memory than the
+                                       library's static buffer holds (use tn_linear_forward) */
 
 /* desc.format */
 #define TN_FORMAT_DENSE   0
@@ -208,6 +210,26 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc);
  *  bit-identical from call to call for the same handle, inputs and token count.
  */
 int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream);
+
+/*
+ * tn_linear_forward for callers that cannot allocate and want no workspace tied to the handle: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, same result bits
+ * as tn_linear_forward for calls that take the same kernels; the intermediates between contraction steps and
+ * the fp32 partial sums of the split kernels live in a static device array of the library
+ * (TN_SCRATCH_BYTES = 32 MiB per GPU, held until the process ends) instead of the handle's workspace, which
+ * this call never touches. It calls no allocating routine and no HIP call other than kernel launches.
+ *   - The whole call runs as one pass: it needs tokens * 2 * (largest per-token intermediate) bytes plus the
+ *     partial sums of its split launches. More than TN_SCRATCH_BYTES: TN_ERR_SCRATCH, nothing is launched.
+ *     Calls that run as one launch with no intermediate in memory (small layers, the chained pair kernel)
+ *     need none and are never refused; a layer on the Kronecker-sum kernel takes as many splits as fit.
+ *   - Large calls of a lazily merged ring (TN_QUERY_LAZY_MIN_TOKENS) run the compact steps here: the rebuilt
+ *     slices belong to the handle's workspace.
+ *   - Every call on one GPU, from any handle, shares that GPU's array: calls that overlap in time on one GPU
+ *     race. Nothing in it needs to start at zero (every element is written before it is read within a call).
+ *   - A handle with profiling enabled is refused (TN_ERR_INVALID_ARG): profiling creates events.
+ */
+#define TN_SCRATCH_BYTES (32 << 20)
+int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream);
 
 /* Free packed tensors and workspace. No forward may be in flight. NULL is accepted. */
 int tn_linear_destroy(tn_linear_t h);

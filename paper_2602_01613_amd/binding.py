@@ -48,6 +48,7 @@ TN_QUERY_STEP_BASE = 100
 EXPORTED_SYMBOLS = (
     "tn_linear_create",
     "tn_linear_forward",
+    "tn_linear_forward_scratch",
     "tn_linear_destroy",
     "tn_linear_query",
     "tn_linear_plan_query",
@@ -108,6 +109,8 @@ def load_library():
     lib.tn_linear_forward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                       ctypes.c_void_p]
     lib.tn_linear_forward.restype = ctypes.c_int
+    lib.tn_linear_forward_scratch.argtypes = lib.tn_linear_forward.argtypes
+    lib.tn_linear_forward_scratch.restype = ctypes.c_int
     lib.tn_linear_destroy.argtypes = [ctypes.c_void_p]
     lib.tn_linear_destroy.restype = ctypes.c_int
     lib.tn_linear_query.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
@@ -196,6 +199,12 @@ def tn_linear_forward(handle: int, x_ptr: int, y_ptr: int, tokens: int, stream) 
         raise TNLinearError(rc, "tn_linear_forward")
 
 
+def tn_linear_forward_scratch(handle: int, x_ptr: int, y_ptr: int, tokens: int, stream) -> None:
+    rc = load_library().tn_linear_forward_scratch(handle, x_ptr, y_ptr, int(tokens), stream)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_forward_scratch")
+
+
 def tn_linear_destroy(handle: Optional[int]) -> None:
     rc = load_library().tn_linear_destroy(handle)
     if rc != 0:
@@ -255,7 +264,9 @@ class TNLinear:
         self.M = tn_linear_query(self._handle, TN_QUERY_OUT_FEATURES)
         self.N = tn_linear_query(self._handle, TN_QUERY_IN_FEATURES)
 
-    def forward(self, x: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, out: Optional[torch.Tensor] = None, scratch: bool = False) -> torch.Tensor:
+        """scratch=True calls tn_linear_forward_scratch (intermediates in the library's static array); out is
+        then required, since that entry point is for callers that do not allocate."""
         if self._handle is None:
             raise RuntimeError("layer was closed")
         if not (x.is_cuda and x.is_contiguous() and x.dtype == self.torch_dtype and x.dim() == 2
@@ -267,8 +278,8 @@ class TNLinear:
         elif not (out.is_cuda and out.is_contiguous() and out.dtype == self.torch_dtype
                   and tuple(out.shape) == (tokens, self.M)):
             raise ValueError("out has the wrong shape, dtype or layout")
-        tn_linear_forward(self._handle, x.data_ptr(), out.data_ptr(), tokens,
-                          torch.cuda.current_stream().cuda_stream)
+        call = tn_linear_forward_scratch if scratch else tn_linear_forward
+        call(self._handle, x.data_ptr(), out.data_ptr(), tokens, torch.cuda.current_stream().cuda_stream)
         return out
 
     __call__ = forward

@@ -23,6 +23,12 @@
 #include "../../include/tn_linear.h"
 #include "tn_plan.hpp"
 
+// Scratch memory of tn_linear_forward_scratch: one array per GPU the library is loaded on, held until the
+// process ends. Host code never uses this name as an address; it asks the runtime for the device address once
+// per device (scratch_address) and passes that pointer on.
+constexpr int64_t kScratchBytes = int64_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 #include "kernels/common.hpp"
@@ -124,7 +130,8 @@ namespace {
 constexpr int64_t kDefaultWorkspaceBytes = int64_t(4) << 30;
 
 // The scratch memory a forward call works in: the two intermediate buffers (each holds chunk_tokens tokens
-// of the largest intermediate) and the fp32 partial sums of the split kernels: the handle's own workspace.
+// of the largest intermediate) and the fp32 partial sums of the split kernels. Normally the handle's own
+// workspace; tn_linear_forward_scratch carves it out of the library's static device array instead.
 struct Workspace {
     void* ws[2] = {nullptr, nullptr};
     void* partial = nullptr;
@@ -1170,6 +1177,10 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
 // time (never inside tn_linear_forward, which must stay legal under stream capture from its first
 // call). The launchers double as configurators: called with an empty step they set the attribute of
 // every kernel they can launch and return.
+// Device address of the static scratch array on each GPU, looked up once per device at create time with that
+// device current (every GPU holds its own copy of the array at its own address).
+void* g_scratch_ptr[64] = {};
+
 int configure_kernels(int device) {
     static bool done[64] = {};
     static std::mutex lock;                // handles may be created from several host threads
@@ -1193,6 +1204,11 @@ int configure_kernels(int device) {
     for (int cfg = 0; cfg < tn::kKronConfigs && rc == TN_OK; ++cfg) rc = kron_dispatch(cfg, nullptr, 0, nullptr);
     if (rc == TN_OK) rc = gen_mfma_dispatch(nullptr, 0, nullptr);
     if (rc == TN_OK) rc = gen_mfma_both_dispatch(nullptr, nullptr, 0, nullptr);
+    if (rc == TN_OK && device >= 0 && device < 64) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) rc = TN_ERR_HIP;
+        else g_scratch_ptr[device] = ptr;
+    }
     if (rc == TN_OK && device >= 0 && device < 64) done[device] = true;
     return rc;
 }
@@ -1341,7 +1357,7 @@ int materialise_merges(const tn::Plan& plan, const tn_linear_desc* desc, int elt
 
 extern "C" {
 
-int tn_linear_version(void) { return 2; }
+int tn_linear_version(void) { return 3; }
 
 const char* tn_linear_strerror(int status) {
     switch (status) {
@@ -1350,6 +1366,7 @@ const char* tn_linear_strerror(int status) {
         case TN_ERR_UNSUPPORTED: return "unsupported configuration";
         case TN_ERR_ALLOC: return "allocation failed";
         case TN_ERR_HIP: return "HIP runtime error";
+        case TN_ERR_SCRATCH: return "the call needs more scratch memory than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -1752,6 +1769,49 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
     w.partial_bytes = h->partial_bytes;
     w.chunk_tokens = h->chunk_tokens;
     return forward_in(h, w, true, x, y, tokens, static_cast<hipStream_t>(stream));
+}
+
+int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
+    if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
+    if (tokens == 0) return TN_OK;
+    if (!x || !y || h->profiling) return TN_ERR_INVALID_ARG;       // profiling creates events, i.e. allocates
+    void* base = (h->device >= 0 && h->device < 64) ? g_scratch_ptr[h->device] : nullptr;
+    if (!base) return TN_ERR_UNSUPPORTED;
+    Workspace w;
+    const bool one_launch = (h->small_chain && (h->elt == 4 || tokens <= kSmallChainMaxBf16Tokens)) ||
+                            (h->pair && tokens >= h->pair_min_tokens);
+    if (one_launch) {
+        // nothing but x and y is touched
+    } else if (h->kron && tokens >= h->kron_min_tokens) {
+        // only partial sums: the launch takes as many splits of the bond as fit
+        w.partial = base;
+        w.partial_bytes = kScratchBytes;
+    } else {
+        // the compact steps in one pass: [partial sums | buffer 0 | buffer 1], 256-byte aligned pieces
+        int64_t part = 0;
+        if (!(h->flags & TN_FLAG_NO_SPLIT_K) && h->elt == 2)
+            for (const tn::LaunchIO& l : h->schedule)
+                if (l.steps == 1) {
+                    const DevStep& s = h->steps[size_t(l.first)];
+                    const SplitCfg c = split_config(s, tokens * s.plan.R);
+                    if (c.use) part = std::max(part, c.partial_bytes);
+                }
+        part = (part + 255) & ~int64_t(255);
+        int64_t max_r = 1;
+        for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
+        if (tokens > ((int64_t(1) << 31) - 1024) / max_r) return TN_ERR_SCRATCH;      // rows of a pass are indexed with 32 bits
+        const int64_t per_token = h->plan.max_intermediate * h->elt;
+        if (per_token > 0 && tokens > kScratchBytes / per_token) return TN_ERR_SCRATCH;
+        const int64_t buf = (tokens * per_token + 255) & ~int64_t(255);
+        if (part + 2 * buf > kScratchBytes) return TN_ERR_SCRATCH;
+        char* b = static_cast<char*>(base);
+        w.partial = part > 0 ? b : nullptr;
+        w.partial_bytes = part;
+        w.ws[0] = b + part;
+        w.ws[1] = b + part + buf;
+        w.chunk_tokens = tokens;
+    }
+    return forward_in(h, w, false, x, y, tokens, static_cast<hipStream_t>(stream));
 }
 
 int tn_linear_profile(tn_linear_t h, int32_t enable) {
