@@ -46,9 +46,12 @@ __global__ void __launch_bounds__(256) pair_repack_kernel(const bf16_t* src, bf1
     }
 }
 
-template <int NS>
+template <int NS, int BAR>
 __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
-    constexpr int L = 5;                               // NS ring stages; L direct-to-LDS loads per wave and stage
+    // A ring of NS LDS stages, one value of a each; L direct-to-LDS loads per wave and stage. Stages are requested
+    // BAR at a time, with one workgroup barrier per BAR values of a.
+    constexpr int L = 5;
+    static_assert(NS >= 2 * BAR + 1 && NS - 2 * BAR - 1 <= 4, "ring depth");
     constexpr int STAGE_BYTES = 20 * 1024, X_OFF = 16 * 1024;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
 
@@ -93,11 +96,11 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
             (const void __attribute__((address_space(1)))*)(x_src + int64_t(a) * 64),
             (void __attribute__((address_space(3)))*)(sbase + X_OFF + wave * 1024), 16, 0, 0);
     };
-    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform, at most NS - 2
+    auto wait_outstanding_tiles = [&](int n) {            // n is wave-uniform
         if (n <= 0) wait_vmcnt<0>();
         else if (n == 1) wait_vmcnt<L>();
-        else if (n == 2 || NS <= 4) wait_vmcnt<2 * L>();
-        else if (n == 3 || NS <= 5) wait_vmcnt<3 * L>();
+        else if (n == 2) wait_vmcnt<2 * L>();
+        else if (n == 3) wait_vmcnt<3 * L>();
         else wait_vmcnt<4 * L>();
     };
 
@@ -109,13 +112,26 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[jj][ct][v] = 0.f;
 
+    // Stage of a is a % NS. At the barrier before a group of BAR values a .. a+BAR-1 the stages of a+1 .. a+BAR must
+    // have landed (they are read while the group is computed: see the refills below), and the stages requested
+    // there, those of a+NS-BAR .. a+NS-1, are the ones of a-BAR .. a-1, whose last reads were issued a full group
+    // earlier.
     int issued = 0;
-    for (; issued < NS - 1 && issued < A; ++issued) issue(issued, issued);
-    wait_outstanding_tiles(min(issued - 1, NS - 2));     // tile 0 has landed
+    for (; issued < NS - BAR && issued < A; ++issued) issue(issued, issued);
+    wait_outstanding_tiles(min(issued - 1, 4));          // tile 0 has landed
     __syncthreads();
     bf16x8 xb[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(dyn_smem + X_OFF + s * 1024 + lane * 16);
+    // the B1 slice of the current tile, in registers: p1[ct][s]. Each fragment is used twice per tile (once per j
+    // of the wave); right after its second use it is refilled from the NEXT tile's stage, so that the LDS reads of
+    // a tile are spread over the MFMAs of the tile before and none of them is waited for after the barrier.
+    bf16x8 p1[4][4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            p1[ct][s] = *reinterpret_cast<const bf16x8*>(dyn_smem + (ct * 4 + s) * 1024 + lane * 16);
 
     // first contraction for one j: Z^T[b][t], two 32-row halves of the bond
     auto contract0 = [&](const bf16x8 (&w)[2][4], const bf16x8 (&x)[4], floatx16 (&z)[2]) {
@@ -130,18 +146,26 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
                 z[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[rt][s], x[s], z[rt], 0, 0, 0);
     };
     // second contraction for one j: Y^T[c][t] += B1[c][(a, b)] Z^T[b][t]. Registers 8*(s%2) .. +7 of
-    // half s/2 of z are the 8 values this lane supplies to k-step s.
-    auto contract1 = [&](const bf16x8 (&w)[4][4], const floatx16 (&z)[2], floatx16 (&y)[4]) {
+    // half s/2 of z are the 8 values this lane supplies to k-step s. With REFILL, the four fragments of a k-step
+    // are reloaded from `next` (the following tile's slice in LDS) as soon as their MFMAs have been issued.
+    auto contract1 = [&](const floatx16 (&z)[2], floatx16 (&y)[4], const unsigned char* next, auto refill_tag) {
+        constexpr bool REFILL = decltype(refill_tag)::value;
         bf16x8 zb[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int e = 0; e < 8; ++e) zb[s][e] = bf16_t(z[s >> 1][8 * (s & 1) + e]);
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s) {
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct)
-                y[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ct][s], zb[s], y[ct], 0, 0, 0);
+                y[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1[ct][s], zb[s], y[ct], 0, 0, 0);
+            if (REFILL) {
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct)
+                    p1[ct][s] = *reinterpret_cast<const bf16x8*>(next + (ct * 4 + s) * 1024 + lane * 16);
+            }
+        }
     };
 
     // software pipeline over (a, j): the first contraction of the next unit is issued before the
@@ -150,22 +174,17 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
     contract0(p0[0], xb, z0);
     auto iteration = [&](int a, auto last_tag) {
         constexpr bool LAST = decltype(last_tag)::value;
-        if (!LAST) wait_outstanding_tiles(issued - (a + 2));       // tile a+1 has landed
-        __syncthreads();       // everyone is done with tile a-1: its stage may be refilled
-        if (issued < A) {
-            issue(issued, issued % NS);
-            ++issued;
+        if (BAR == 1 || a % BAR == 0) {                      // wave-uniform
+            wait_outstanding_tiles(min(max(issued - 1 - (a + BAR), 0), 4));       // tiles a+1 .. a+BAR have landed
+            __syncthreads();   // ... for every wave; everyone's reads of the stages refilled now were issued long ago
+#pragma unroll
+            for (int g = 0; g < BAR; ++g)
+                if (issued < A) {
+                    issue(issued, issued % NS);
+                    ++issued;
+                }
         }
-        const unsigned char* scur = dyn_smem + (a % NS) * STAGE_BYTES;
         const unsigned char* snxt = dyn_smem + ((a + 1) % NS) * STAGE_BYTES;
-        bf16x8 p1[4][4];
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                p1[ct][s] = *reinterpret_cast<const bf16x8*>(scur + (ct * 4 + s) * 1024 + lane * 16);
-        // the scheduler would otherwise sink each LDS read next to its first use and expose the LDS
-        // latency 16 times per iteration
         __builtin_amdgcn_sched_barrier(0);
         contract0(p0[1], xb, z1);
         if (!LAST) {
@@ -173,9 +192,10 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
             for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8*>(snxt + X_OFF + s * 1024 + lane * 16);
             __builtin_amdgcn_sched_barrier(0);
         }
-        contract1(p1, z0, acc[0]);
+        contract1(z0, acc[0], snxt, std::false_type());
         if (!LAST) contract0(p0[0], xb, z0);
-        contract1(p1, z1, acc[1]);
+        if (!LAST) contract1(z1, acc[1], snxt, std::true_type());
+        else contract1(z1, acc[1], snxt, std::false_type());
         // keep the accumulators in the accumulation registers across the back edge (the register
         // allocator otherwise parks some of them in ordinary registers and copies them every
         // iteration)

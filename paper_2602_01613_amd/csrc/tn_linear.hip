@@ -519,7 +519,11 @@ int launch_small_chain(const tn_linear_s* h, const void* x, void* y, int64_t tok
 // Token count from which the chained pair kernel replaces the two separate launches (below it a
 // launch has too few workgroups: 8 per 32 tokens).
 constexpr int64_t kPairMinTokens = 256;
-constexpr int kPairStages = 4;
+#ifndef TN_PAIR_STAGES
+#define TN_PAIR_STAGES 4
+#define TN_PAIR_BAR 1
+#endif
+constexpr int kPairStages = TN_PAIR_STAGES, kPairBar = TN_PAIR_BAR;
 constexpr size_t kPairSmemBytes = kPairStages * 20 * 1024;
 
 int prepare_pair(tn_linear_s* h, hipStream_t st) {
@@ -558,7 +562,7 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
     p.n_tok_tiles = int32_t((tokens + 31) / 32);
     p.n_jsets = p.J / 8;
     int64_t grid = int64_t((p.n_tok_tiles + 7) / 8 * 8) * p.n_jsets;
-    hipLaunchKernelGGL(step_pair_kernel<kPairStages>, dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
+    hipLaunchKernelGGL((step_pair_kernel<kPairStages, kPairBar>), dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
@@ -1194,7 +1198,7 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK &&
-        (hipFuncSetAttribute(reinterpret_cast<const void*>(step_pair_kernel<kPairStages>),
+        (hipFuncSetAttribute(reinterpret_cast<const void*>(&step_pair_kernel<kPairStages, kPairBar>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
          hipFuncSetAttribute(reinterpret_cast<const void*>(small_chain_kernel<float>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kSmallChainMaxSmem)) != hipSuccess ||
