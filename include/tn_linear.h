@@ -69,6 +69,8 @@ extern "C" {
                                        the gradient of the forward pass with respect to its input, which the
                                        fine-tuning of the factors (Section 3.4) back-propagates through every
                                        layer. TN_QUERY_IN_FEATURES / OUT_FEATURES then report M / N. */
+#define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* never run a chained factor pair and the wide step after it as one launch
+                                       (calls of a few tokens: the in-factor products and the core of a Tucker layer) */
 #define TN_FLAG_NO_SMALL_CHAIN (1 << 20) /* never run a small layer as one launch with all its tensors in LDS */
 #define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
                                        choice) */

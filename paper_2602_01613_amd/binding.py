@@ -29,6 +29,7 @@ TN_FLAG_VARIANT_SHIFT = 8
 TN_FLAG_NO_LAZY_MERGE = 1 << 21
 TN_FLAG_MERGE_HALVES = 1 << 22
 TN_FLAG_SCALAR_GENERATE = 1 << 23
+TN_FLAG_NO_DECODE_FUSION = 1 << 24
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2

@@ -295,25 +295,25 @@ constexpr size_t chain2_smem_bytes() {
     return size_t(4) * (R1T * K1S * 1024 + 2 * 32 * 80);
 }
 
+// The work of one wave: items gw, gw + GW, ... of the tokens * (c1 tile groups) items. `smem` is the area of
+// chain2_smem_bytes: wave slot `wave` (0..3) uses its own input buffer and patches in it. Out may be memory or
+// LDS (generic address). No workgroup barrier inside: waves come and go independently.
 template <int R1T, int K1S, int C2T, int RUN_C1>
-__global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
+__device__ __forceinline__ void chain2_run(const Chain2Args& p, unsigned char* smem, int wave, int64_t gw, int64_t GW) {
     constexpr int IN_BYTES = R1T * K1S * 1024;           // one token's input in fragment order
     constexpr int KS2 = 2 * R1T;                         // k-steps of the second contraction
     constexpr int PATCH_LD = 80;                         // bytes per patch row (64 + 16 of padding)
     constexpr int PATCH_BYTES = 32 * PATCH_LD;
-    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
     const bf16_t* In = static_cast<const bf16_t*>(p.In);
     const bf16_t* Ba = static_cast<const bf16_t*>(p.Ba);
     const bf16_t* Bbf = static_cast<const bf16_t*>(p.Bbf);
     bf16_t* Out = static_cast<bf16_t*>(p.Out);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    unsigned char* my_in = dyn_smem + wave * IN_BYTES;
-    unsigned char* my_patch = dyn_smem + 4 * IN_BYTES + wave * (2 * PATCH_BYTES);
+    const int lane = threadIdx.x & 63;
+    unsigned char* my_in = smem + wave * IN_BYTES;
+    unsigned char* my_patch = smem + 4 * IN_BYTES + wave * (2 * PATCH_BYTES);
 
     const int n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const int64_t n_items = int64_t(p.tokens) * n_groups;
-    const int64_t gw = int64_t(blockIdx.x) * 4 + wave, GW = int64_t(gridDim.x) * 4;
     if (gw >= n_items) return;                           // no workgroup barrier below: a wave may leave
 
     // lanes whose (row, k) lies outside the input never load: the fragment blocks they belong to are
@@ -476,6 +476,212 @@ __global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
+    }
+}
+
+template <int R1T, int K1S, int C2T, int RUN_C1>
+__global__ void __launch_bounds__(256, 1) step_chain2_kernel(Chain2Args p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    chain2_run<R1T, K1S, C2T, RUN_C1>(p, dyn_smem, wave, int64_t(blockIdx.x) * 4 + wave, int64_t(gridDim.x) * 4);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode-size fusion of a chained factor pair with the wide step that follows it (a Tucker layer's two in-factor
+// products and its core): one launch instead of two, for calls of a few tokens. Every workgroup of the wide
+// step's grid (one per block of 32 columns, 8 waves, the whole K) recomputes the pair's small result for the
+// call's tokens (2304 values per token for the up_proj layer) instead of reading it from memory:
+//   1. the waves that have an item (token, tile of 32 values of c1) request that item's operands - the token's
+//      input rows, the two small packed tensors, the offsets of its outputs - straight into registers;
+//   2. every wave requests ALL its k-steps of the wide step's packed tensor (KPW fragments of 1 KB per wave, the
+//      workgroup's whole block): from here on the parameter stream, which is what bounds a call this small, is
+//      in flight, and everything below runs in its shadow;
+//   3. the item waves wait for their operands only (they were requested first, and loads return in order), run
+//      the two chained MFMA contractions as step_chain2_kernel does and store the rounded result to LDS;
+//   4. after one barrier every wave multiplies its fragments with the LDS buffer as the other operand, and the
+//      eight partial tiles are summed through LDS in wave order (as in step_split_kernel).
+// Limits (checked by the host): R1 <= 64, C2 <= 64, K1 <= 16*K1S, tokens * ceil(C1/32) <= 8 items, K of the wide
+// step <= 128 * KPW, its rows are the tokens (R = 1), output offsets in aligned runs of 8.
+// ---------------------------------------------------------------------------------------------
+// One (token, tile of 32 values of c1) item of a chained pair with every operand requested up front, straight into
+// registers: nothing is staged through LDS and there is a single memory round trip before the MFMAs, which is what
+// a call of a few tokens needs (step_chain2_kernel pipelines tokens through LDS instead, which pays once a wave has
+// many of them). Register layouts as in chain2_run.
+template <int R1T, int K1S, int C2T, int RUN_C1>
+struct Chain2Item {
+    static constexpr int KS2 = 2 * R1T;
+    bf16x8 inf[R1T][K1S], ba[K1S], bb[C2T][KS2];
+    int o_lane[C2T];             // offset of the index this lane holds one value of (c2 when RUN_C1; else c1, entry 0 only)
+    int o_run[C2T][4];           // offsets of the runs of 4 it holds in its registers (c1 when RUN_C1, entries [0][q]; else c2)
+    int t, ct1;
+
+    __device__ __forceinline__ void load(const Chain2Args& c, int token, int tile) {
+        const bf16_t* In = static_cast<const bf16_t*>(c.In);
+        const bf16_t* Ba = static_cast<const bf16_t*>(c.Ba);
+        const bf16_t* Bbf = static_cast<const bf16_t*>(c.Bbf);
+        const int lane = threadIdx.x & 63, lrow = lane & 31, lhalf = lane >> 5;
+        t = token;
+        ct1 = tile;
+        const bf16_t* in_t = In + int64_t(t) * c.in_tok_stride;
+        // straight-line loads from clamped addresses; what lies outside the input is replaced by zeros later
+#pragma unroll
+        for (int i = 0; i < R1T; ++i) {
+            const int r = min(32 * i + lrow, c.R1 - 1);
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk) {
+                const int k = min(16 * sk + 8 * lhalf, c.K1 - 8);
+                inf[i][sk] = *reinterpret_cast<const bf16x8*>(in_t + int64_t(r) * c.K1 + k);
+            }
+        }
+#pragma unroll
+        for (int sk = 0; sk < K1S; ++sk)      // k-steps past the packed tensor's padding meet zero input: any finite block will do
+            ba[sk] = *reinterpret_cast<const bf16x8*>(Ba + (int64_t(ct1) * c.nks_a + min(sk, c.nks_a - 1)) * 512 + lane * 8);
+#pragma unroll
+        for (int j = 0; j < C2T; ++j)
+#pragma unroll
+            for (int sk = 0; sk < KS2; ++sk)
+                bb[j][sk] = *reinterpret_cast<const bf16x8*>(Bbf + (int64_t(j) * KS2 + sk) * 512 + lane * 8);
+        // output offsets come in aligned runs of 8 along the direction the pieces run (checked by the planner)
+        if (RUN_C1) {
+#pragma unroll
+            for (int j = 0; j < C2T; ++j) o_lane[j] = c.off2[min(32 * j + lrow, c.C2 - 1)];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o_run[0][q] = c.off1[min(32 * ct1 + 8 * q, c.C1 - 1)] + 4 * lhalf;
+        } else {
+            o_lane[0] = c.off1[min(32 * ct1 + lrow, c.C1 - 1)];
+#pragma unroll
+            for (int j = 0; j < C2T; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) o_run[j][q] = c.off2[min(32 * j + 8 * q, c.C2 - 1)] + 4 * lhalf;
+        }
+    }
+
+    // Both contractions; the result goes to out (memory or LDS) in 8-byte pieces of 4 consecutive values.
+    __device__ __forceinline__ void compute(const Chain2Args& c, bf16_t* out) const {
+        const int lane = threadIdx.x & 63, lrow = lane & 31, lhalf = lane >> 5;
+        bf16x8 zero;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) zero[e] = bf16_t(0.f);
+        floatx16 d[R1T];
+#pragma unroll
+        for (int i = 0; i < R1T; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d[i][v] = 0.f;
+            const bool rv = 32 * i + lrow < c.R1;
+#pragma unroll
+            for (int sk = 0; sk < K1S; ++sk) {
+                const bf16x8 x = (rv && 16 * sk + 8 * lhalf < c.K1) ? inf[i][sk] : zero;
+                d[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, ba[sk], d[i], 0, 0, 0);
+            }
+        }
+        bf16x8 zb[KS2];
+#pragma unroll
+        for (int i = 0; i < R1T; ++i)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) zb[2 * i + u][e] = bf16_t(d[i][8 * u + e]);
+        bf16_t* out_t = out + int64_t(t) * c.out_tok_stride;
+#pragma unroll
+        for (int j = 0; j < C2T; ++j) {
+            if (32 * j >= c.C2) continue;                                  // wave-uniform
+            floatx16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int sk = 0; sk < KS2; ++sk)
+                acc = RUN_C1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(zb[sk], bb[j][sk], acc, 0, 0, 0)
+                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j][sk], zb[sk], acc, 0, 0, 0);
+            // RUN_C1: lane l holds c2 = 32j + l%32 and, in registers 4q..4q+3, c1 = 32*ct1 + 8q + 4*(l/32) + 0..3
+            // else  : lane l holds c1 = 32*ct1 + l%32 and c2 = 32j + 8q + 4*(l/32) + 0..3
+            const bool lane_ok = RUN_C1 ? 32 * j + lrow < c.C2 : 32 * ct1 + lrow < c.C1;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool run_ok = RUN_C1 ? 32 * ct1 + 8 * q < c.C1 : 32 * j + 8 * q < c.C2;      // runs of 8 are whole
+                if (!lane_ok || !run_ok) continue;
+                const int base = RUN_C1 ? o_lane[j] + o_run[0][q] : o_lane[0] + o_run[j][q];
+                bf16x4 pk;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) pk[u] = bf16_t(acc[4 * q + u]);
+                *reinterpret_cast<bf16x4*>(out_t + base) = pk;
+            }
+        }
+    }
+};
+
+// A chained pair for a few tokens: one wave per (token, c1 tile) item, four items per workgroup.
+template <int R1T, int K1S, int C2T, int RUN_C1>
+__global__ void __launch_bounds__(256) step_chain2_small_kernel(Chain2Args c) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int item = blockIdx.x * 4 + wave;
+    if (item >= c.tokens * c.c1_tiles) return;
+    Chain2Item<R1T, K1S, C2T, RUN_C1> it;
+    it.load(c, item / c.c1_tiles, item % c.c1_tiles);
+    it.compute(c, static_cast<bf16_t*>(c.Out));
+}
+
+template <int K1S, int RUN_C1, int KPW>
+__global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c, StepArgs a, int z_bytes) {
+    constexpr int NW = 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    bf16_t* z = reinterpret_cast<bf16_t*>(dyn_smem);                       // [tokens][a.a_tok_stride]
+    float* red = reinterpret_cast<float*>(dyn_smem + z_bytes);             // NW x 1024
+    const bf16_t* B = static_cast<const bf16_t*>(a.B);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cb = blockIdx.x;
+    const int nks = a.Kp >> 4;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = bf16_t(0.f);
+
+    // ---- 1. operands of this wave's item
+    const bool has_item = wave < c.tokens * c.c1_tiles;                    // wave-uniform
+    Chain2Item<2, K1S, 2, RUN_C1> item;
+    if (has_item) item.load(c, wave / c.c1_tiles, wave % c.c1_tiles);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- 2. the wave's share of the parameter stream: k-steps wave, wave + 8, ...
+    bf16x8 bf[KPW];
+    {
+        const bf16_t* bp = B + (int64_t(cb) * nks) * 512 + lane * 8;
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(min(wave + NW * u, nks - 1)) * 512);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- 3. the chained pair for the item, into LDS
+    if (has_item) item.compute(c, z);
+    __syncthreads();
+    // ---- 4. the wide step: lane l supplies token l%32, k = 16*ks + 8*(l/32) .. +7 from the LDS buffer
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    {
+        const bool tv = lrow < int(a.total_rows);
+        const bf16_t* zrow = z + int64_t(tv ? lrow : 0) * a.a_tok_stride + 8 * lhalf;
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) {
+            const int ks = wave + NW * u;
+            if (ks < nks) {                                                // wave-uniform
+                const bf16x8 x = (tv && 16 * ks + 8 * lhalf < a.K) ? *reinterpret_cast<const bf16x8*>(zrow + 16 * ks) : zero;
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], x, acc, 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = acc[v];
+    __syncthreads();
+    // lane l, register v holds row (token) l%32, column 8*(v/4) + 4*(l/32) + v%4
+    for (int e = tid; e < 1024; e += NW * 64) {
+        const int v = (e >> 6) & 15, l = e & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += red[w * 1024 + e];
+        const uint32_t g = uint32_t(l & 31);
+        const int col = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+        if (g >= a.total_rows || col >= a.C) continue;
+        Out[int64_t(g) * a.c_tok_stride + a.crow[0] + a.ccol[col]] = bf16_t(sum);
     }
 }
 

@@ -156,15 +156,16 @@ __global__ void __launch_bounds__(256, MINB) step_shortk_kernel(StepArgs a) {
 // at a tile does the sum was measured 8x slower: a device-scope fence on this chip writes back the
 // L2 of the workgroup's XCD.
 // ---------------------------------------------------------------------------------------------
+// The work of one workgroup (row tile bx, column block cb, split `split` of nsplit). red is NW * TM * 1024 floats of
+// LDS. A may be memory or LDS (generic address).
 template <int TM, int AMODE, int NW>
-__global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
-    __shared__ float red[NW][TM][16][64];
+__device__ __forceinline__ void split_run(const StepArgs& a, float* partial, int ksteps_per_split, float* red, int bx,
+                                          int cb, int split, int nsplit, uint32_t rows_pad) {
     const bf16_t* A = static_cast<const bf16_t*>(a.A);
     const bf16_t* B = static_cast<const bf16_t*>(a.B);
     bf16_t* Out = static_cast<bf16_t*>(a.Out);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t row0 = blockIdx.x * (TM * 32);
-    const int cb = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
+    const uint32_t row0 = uint32_t(bx) * (TM * 32);
     const int nks = a.Kp >> 4;
     const int ks_begin = split * ksteps_per_split;
     const int ks_end = min(nks, ks_begin + ksteps_per_split);
@@ -239,11 +240,10 @@ __global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* 
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) red[wave][i][v][lane] = acc[i][v];
+        for (int v = 0; v < 16; ++v) red[((wave * TM + i) * 16 + v) * 64 + lane] = acc[i][v];
     __syncthreads();
     // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
-    const uint32_t rows_pad = gridDim.x * (TM * 32);
-    const float* rw = &red[0][0][0][0];
+    const float* rw = red;
     for (int e = tid; e < TM * 1024; e += NW * 64) {
         int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
         float sum = 0.f;
@@ -260,6 +260,13 @@ __global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* 
             partial[(int64_t(split) * rows_pad + g) * a.Cp + c] = sum;
         }
     }
+}
+
+template <int TM, int AMODE, int NW>
+__global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* partial, int ksteps_per_split) {
+    __shared__ float red[NW * TM * 1024];
+    split_run<TM, AMODE, NW>(a, partial, ksteps_per_split, red, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z,
+                             gridDim.x * (TM * 32));
 }
 
 // Sums the partial results of the split-K kernel in split order and stores through the tables.

@@ -1165,8 +1165,18 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
     p.C2 = int32_t(s2.plan.C);
     p.nks_a = s1.Kp >> 4;
     p.c1_tiles = (p.C1 + 31) / 32;
-    // a wave per token when there are tokens enough to fill the chip, else a wave per (token, c1 tile)
     const int64_t waves = int64_t(h->num_cus) * 4;
+    if (tokens * p.c1_tiles <= waves && !(h->flags & TN_FLAG_NO_DECODE_FUSION)) {
+        // few tokens: every (token, c1 tile) item gets a wave of its own, operands requested up front
+        static const k_t small[6] = {step_chain2_small_kernel<3, 6, 5, 0>, step_chain2_small_kernel<3, 6, 5, 1>,
+                                     step_chain2_small_kernel<2, 8, 2, 0>, step_chain2_small_kernel<2, 8, 2, 1>,
+                                     step_chain2_small_kernel<2, 5, 2, 0>, step_chain2_small_kernel<2, 5, 2, 1>};
+        p.tiles_per_item = 1;
+        const int64_t items = tokens * p.c1_tiles;
+        hipLaunchKernelGGL(small[s1.chain_cfg * 2 + s1.chain_run_c1], dim3(uint32_t((items + 3) / 4)), dim3(256), 0, st, p);
+        return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+    }
+    // a wave per token when there are tokens enough to fill the chip, else a wave per (token, c1 tile)
     p.tiles_per_item = tokens >= waves ? p.c1_tiles : 1;
     const int64_t n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const int64_t items = tokens * n_groups;
@@ -1174,6 +1184,75 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
     const int64_t wgs = int64_t(h->num_cus) * (s1.chain_cfg == 2 ? 2 : 1);
     dim3 grid(uint32_t(std::min<int64_t>((items + 3) / 4, wgs)));
     hipLaunchKernelGGL(kerns[s1.chain_cfg * 2 + s1.chain_run_c1], grid, dim3(256), smem[s1.chain_cfg], st, p);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+// A chained factor pair and the wide step after it as one launch (step_chain2_split_kernel), for calls of a few
+// tokens: applicable when the pair runs on one of the two small instantiations, the wide step would run on the
+// split-K kernel with one split and 8 waves, its rows are the tokens themselves (R = 1), its K fits the kernel's
+// register budget and every (token, column tile) item of the pair gets a wave of its own.
+constexpr int64_t kFusedDecodeMaxZBytes = 32 * 1024;
+constexpr size_t kFusedDecodeRedBytes = 8 * 1024 * sizeof(float);
+constexpr int kFusedDecodeKPW = 18;          // k-steps of the wide step per wave: K <= 8 * 18 * 16 = 2304
+
+bool chain2_split_applies(const tn_linear_s* h, const DevStep& s1, const DevStep& s3, int64_t tokens) {
+    if (!s1.fuse_next || s1.chain_cfg == 0 || (h->flags & (TN_FLAG_NO_SPLIT_K | TN_FLAG_NO_DECODE_FUSION))) return false;
+    if (s3.fuse_next || s3.variant == VAR_SCALAR || s3.amode != 0 || s3.plan.R != 1) return false;
+    if (tokens * ((s1.plan.C + 31) / 32) > 8 || s3.Kp > 8 * kFusedDecodeKPW * 16) return false;
+    if (tokens * s3.plan.a_tok_stride * 2 > kFusedDecodeMaxZBytes) return false;
+    const SplitCfg sc = split_config(s3, tokens);
+    return sc.use && sc.nsplit == 1 && sc.tm == 1 && sc.nw == 8 && sc.row_tiles == 1;
+}
+
+int launch_chain2_split(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const DevStep& s3, const void* A,
+                        void* Out, int64_t tokens, hipStream_t st) {
+    using k_t = void (*)(Chain2Args, StepArgs, int);
+    static const k_t kerns[4] = {step_chain2_split_kernel<8, 0, kFusedDecodeKPW>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW>,
+                                 step_chain2_split_kernel<5, 0, kFusedDecodeKPW>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW>};
+    if (!s1.packed) {                      // configuration call (create time)
+        for (int i = 0; i < 4; ++i)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(kFusedDecodeRedBytes + size_t(kFusedDecodeMaxZBytes))) != hipSuccess)
+                return TN_ERR_HIP;
+        return TN_OK;
+    }
+    Chain2Args p;
+    p.In = A;
+    p.Out = nullptr;                       // the pair's result stays in LDS
+    p.Ba = s1.packed;
+    p.Bbf = s1.chain_bbf;
+    p.off1 = s2.crow;
+    p.off2 = s2.ccol;
+    p.in_tok_stride = s1.plan.a_tok_stride;
+    p.out_tok_stride = s2.plan.c_tok_stride;
+    p.tokens = int32_t(tokens);
+    p.R1 = int32_t(s1.plan.R);
+    p.K1 = int32_t(s1.plan.K);
+    p.C1 = int32_t(s1.plan.C);
+    p.C2 = int32_t(s2.plan.C);
+    p.nks_a = s1.Kp >> 4;
+    p.c1_tiles = (p.C1 + 31) / 32;
+    p.tiles_per_item = 1;
+    StepArgs a;
+    a.A = nullptr;                         // likewise
+    a.B = s3.packed;
+    a.Out = Out;
+    a.arow = nullptr;
+    a.acol = nullptr;
+    a.crow = s3.crow;
+    a.ccol = s3.ccol;
+    a.a_tok_stride = s3.plan.a_tok_stride;
+    a.c_tok_stride = s3.plan.c_tok_stride;
+    a.total_rows = uint32_t(tokens);
+    a.R = 1;
+    a.K = int32_t(s3.plan.K);
+    a.Kp = s3.Kp;
+    a.C = int32_t(s3.plan.C);
+    a.Cp = s3.Cp;
+    const int z_bytes = int((tokens * s3.plan.a_tok_stride * 2 + 255) & ~int64_t(255));
+    const uint32_t col_blocks = uint32_t((s3.plan.C + 31) / 32);
+    hipLaunchKernelGGL(kerns[(s1.chain_cfg - 1) * 2 + s1.chain_run_c1], dim3(col_blocks), dim3(512),
+                       kFusedDecodeRedBytes + size_t(z_bytes), st, p, a, z_bytes);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
@@ -1197,6 +1276,7 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = launch_pipe<4, 1, 2, 4, 1, 2>(none, a, 0, nullptr);
     if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
+    if (rc == TN_OK) rc = launch_chain2_split(no_handle, none, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK &&
         (hipFuncSetAttribute(reinterpret_cast<const void*>(&step_pair_kernel<kPairStages, kPairBar>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
@@ -1743,14 +1823,25 @@ int forward_in(tn_linear_s* h, const Workspace& w, bool allow_lazy, const void* 
     if (w.chunk_tokens < 1) return TN_ERR_INVALID_ARG;
     for (int64_t t0 = 0; t0 < tokens; t0 += w.chunk_tokens) {
         int64_t nt = std::min(w.chunk_tokens, tokens - t0);
-        for (const tn::LaunchIO& l : h->schedule) {
+        for (size_t li = 0; li < h->schedule.size(); ++li) {
+            const tn::LaunchIO& l = h->schedule[li];
             const void* A = l.in == tn::kBufX ? static_cast<const void*>(xb + t0 * h->plan.N * h->elt) : w.ws[l.in];
             void* Out = l.out == tn::kBufY ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : w.ws[l.out];
             ProfScope prof(h, l.first, st);
             if (!prof.ok) return TN_ERR_HIP;
             const DevStep& s = h->steps[size_t(l.first)];
-            int rc = l.steps == 2 ? launch_chain2(h, s, h->steps[size_t(l.first) + 1], A, Out, nt, st)
+            int rc;
+            if (l.steps == 2 && li + 1 < h->schedule.size() && h->schedule[li + 1].steps == 1 &&
+                chain2_split_applies(h, s, h->steps[size_t(l.first) + 2], nt)) {
+                // few tokens: the pair and the wide step after it in one launch, the pair's result in LDS
+                const tn::LaunchIO& l2 = h->schedule[li + 1];
+                void* Out2 = l2.out == tn::kBufY ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : w.ws[l2.out];
+                rc = launch_chain2_split(h, s, h->steps[size_t(l.first) + 1], h->steps[size_t(l.first) + 2], A, Out2, nt, st);
+                ++li;
+            } else {
+                rc = l.steps == 2 ? launch_chain2(h, s, h->steps[size_t(l.first) + 1], A, Out, nt, st)
                                   : launch_step(h, w, s, A, Out, nt, st);
+            }
             prof.done();
             if (rc != TN_OK) return rc;
         }

@@ -614,6 +614,40 @@ def test_chained_factor_products(case, tokens):
     assert O.rel_max_err(y, y_sep) <= 1e-2, (case, tokens)
 
 
+DECODE_FUSION_CASES = [
+    # Tucker layers whose in-factor pair and core run as one launch at a few tokens (out modes, in modes, ranks)
+    ((160, 160), (64, 80), (96, 96, 48, 48)),     # the up_proj workload: 2304 core inputs, 18 k-steps per wave
+    ((64, 128), (64, 128), (64, 64, 32, 32)),     # K1 = 128: the 8-k-step instantiation, 1024 core inputs
+    ((32, 40), (64, 72), (24, 40, 40, 24)),       # ragged tiles everywhere (C1 = 40: two c1 tiles, one of them of 8)
+]
+
+
+@pytest.mark.parametrize("case", range(len(DECODE_FUSION_CASES)))
+def test_factor_pair_and_core_in_one_launch(case):
+    """Calls of one or two tokens of a Tucker layer run the in-factor pair and the core step as one launch (the
+    pair's result recomputed per workgroup into LDS), and every chained pair with its operands requested up front:
+    against the oracle and against the separate launches; three tokens and more take the separate launches."""
+    om, im, rk = DECODE_FUSION_CASES[case]
+    spec = _spec(tn.TN_FORMAT_TUCKER, "bf16", om, im, rk)
+    ts = _rand_layer(spec, 1700 + case)
+    w = O.dense_weight(spec.format, ts, 2)
+    layer = make_layer(spec, ts, 8)
+    plain = make_layer(spec, ts, 8, flags=tn.TN_FLAG_NO_DECODE_FUSION)
+    for tokens in (1, 2, 3, 8):
+        x = wl.round_to_dtype(np.random.default_rng(case * 13 + tokens).standard_normal((tokens, spec.N)), "bf16")
+        xd = to_dev(x, "bf16")
+        yd = layer(xd)
+        torch.cuda.synchronize()
+        assert torch.equal(yd, layer(xd))
+        ref = O.apply_linear(w, x)
+        assert O.rel_max_err(to_host(yd), ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(to_host(yd), ref))
+        yp = to_host(plain(xd))
+        assert O.rel_max_err(yp, ref) <= TOL["bf16"], (case, tokens)
+        assert O.rel_max_err(to_host(yd), yp) <= 1e-2, (case, tokens)
+    layer.close()
+    plain.close()
+
+
 @pytest.mark.parametrize("tokens", [1, 40, 1100])
 def test_chained_pair_in_the_middle_of_a_chain(tokens):
     """A Tucker layer with three out-modes and an axis of extent 1: its five steps hold a chained pair that is
