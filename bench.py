@@ -360,6 +360,71 @@ def layer_record(spec, config_id, args, flags, steps, warmup, workload_id=None, 
     return rec, keep
 
 
+def pair_record(spec, config_id, args, instances=8):
+    """Two layers of one shape applied to the same activations (the gate and up projections of an MLP block):
+    tn_linear_forward2 against two tn_linear_forward calls, as a captured decode graph over `instances` distinct
+    pairs (time per pair) and at 8192 tokens."""
+    import torch
+    import workloads as wl
+    import paper_2602_01613_amd as tn
+    ts = [wl.make_tensors(spec, config_id, instance=i) for i in range(2)]
+    dev = [[torch.from_numpy(t).to(torch.float32).to(torch.bfloat16).cuda() for t in tt] for tt in ts]
+    pairs = [(tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev[0], args.tokens),
+              tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, dev[1], args.tokens))
+             for _ in range(instances)]
+    x = torch.from_numpy(wl.make_x(spec, args.tokens, config_id)).to(torch.float32).to(torch.bfloat16).cuda()
+    out = {"workload": f"two {wl.FORMAT_NAMES[spec.format]} layers {spec.N}->{spec.M} ranks {list(spec.ranks)} on the same activations",
+           "instances": instances}
+    packed = 2 * pairs[0][0].query(tn.TN_QUERY_PACKED_BYTES)
+    for t in (1, args.tokens):
+        xt = x[:t].contiguous()
+        ya = torch.empty((t, spec.M), dtype=torch.bfloat16, device="cuda")
+        yb = torch.empty_like(ya)
+        res = {}
+        for mode in ("forward2", "separate"):
+            def run():
+                for a, b in (pairs if t == 1 else pairs[:1]):
+                    if mode == "forward2":
+                        tn.forward2(a, b, xt, ya, yb)
+                    else:
+                        a.forward(xt, out=ya)
+                        b.forward(xt, out=yb)
+            n_pairs = len(pairs) if t == 1 else 1
+            if t == 1:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    run()
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    run()
+                go, reps = graph.replay, 50
+            else:
+                go, reps = run, max(3, args.steps // 2)
+            for _ in range(3):
+                go()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                go()
+            torch.cuda.synchronize()
+            res[mode] = (time.perf_counter() - t0) / reps / n_pairs * 1e6
+            res[mode + "_ya"] = ya.clone()
+        rec = {"us_per_pair_forward2": res["forward2"], "us_per_pair_two_calls": res["separate"],
+               "speedup": res["separate"] / res["forward2"], "same_bits": bool(torch.equal(res["forward2_ya"], res["separate_ya"]))}
+        if t == 1:
+            rec["param_GBps_forward2"] = packed / res["forward2"] / 1e3
+            rec["frac_of_hbm_peak"] = packed / res["forward2"] / 1e3 / PEAK_HBM_GBS
+        else:
+            rec["tokens_per_s_forward2"] = t * 1e6 / res["forward2"]
+        out["decode_1tok_graph" if t == 1 else f"prefill_{t}tok"] = rec
+    for a, b in pairs:
+        a.close()
+        b.close()
+    return out
+
+
 def draw_on_device(spec, gen):
     """Parameter tensors of one stack matrix drawn on the GPU (the stack holds 60 GB of them), same
     distributions as workloads.make_tensors, rounded to bf16: these are the inputs of both sides."""
@@ -681,6 +746,8 @@ def main() -> int:
             sub_rec, sub_keep = layer_record(sub_spec, cid, args, 0, steps, min(args.warmup, steps), workload_id=wid)
             configs[name] = sub_rec
             pending_cpu.append((name, sub_keep))
+        if time.perf_counter() - t_start <= args.time_budget_s:
+            configs["tucker_gate_up_pair"] = pair_record(wl.baseline_spec(2)[0], 2, args)
 
     pre = rec["prefill"]
     result = {

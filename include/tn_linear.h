@@ -214,6 +214,19 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc);
 int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream);
 
 /*
+ * Two layers applied to the same activations in one call (Section 3.5: fuse core contractions and factor
+ * multiplications where possible), e.g. the gate and up projections of an MLP block:
+ *   ya = X Wa^T, yb = X Wb^T for `tokens` rows of x [tokens, N]; both handles must have the same dtype and N.
+ * Where the two layers have the same launch structure, calls of a few tokens run each decode-size launch once for
+ * both layers (a Tucker pair's in-factor products + cores are one launch, its out-factor products another: two
+ * launches for two layers instead of six); every other case runs the two forwards back to back on `stream`, the
+ * second of which finds x in the last-level cache. Same conditions as tn_linear_forward (asynchronous, no
+ * allocation, capturable); each result agrees with that of tn_linear_forward on its handle (bit for bit where the
+ * same kernels run).
+ */
+int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, void* yb, int64_t tokens, void* stream);
+
+/*
  * tn_linear_forward for callers that cannot allocate and want no workspace tied to the handle: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, same result bits
  * as tn_linear_forward for calls that take the same kernels; the intermediates between contraction steps and

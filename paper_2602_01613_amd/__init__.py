@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     tn_linear_destroy,
     tn_linear_forward,
     tn_linear_forward_scratch,
+    tn_linear_forward2,
+    forward2,
     tn_linear_plan_query,
     tn_linear_profile,
     tn_linear_profile_read,

@@ -50,6 +50,7 @@ EXPORTED_SYMBOLS = (
     "tn_linear_create",
     "tn_linear_forward",
     "tn_linear_forward_scratch",
+    "tn_linear_forward2",
     "tn_linear_destroy",
     "tn_linear_query",
     "tn_linear_plan_query",
@@ -112,6 +113,9 @@ def load_library():
     lib.tn_linear_forward.restype = ctypes.c_int
     lib.tn_linear_forward_scratch.argtypes = lib.tn_linear_forward.argtypes
     lib.tn_linear_forward_scratch.restype = ctypes.c_int
+    lib.tn_linear_forward2.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_int64, ctypes.c_void_p]
+    lib.tn_linear_forward2.restype = ctypes.c_int
     lib.tn_linear_destroy.argtypes = [ctypes.c_void_p]
     lib.tn_linear_destroy.restype = ctypes.c_int
     lib.tn_linear_query.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
@@ -204,6 +208,31 @@ def tn_linear_forward_scratch(handle: int, x_ptr: int, y_ptr: int, tokens: int, 
     rc = load_library().tn_linear_forward_scratch(handle, x_ptr, y_ptr, int(tokens), stream)
     if rc != 0:
         raise TNLinearError(rc, "tn_linear_forward_scratch")
+
+
+def tn_linear_forward2(handle_a: int, handle_b: int, x_ptr: int, ya_ptr: int, yb_ptr: int, tokens: int, stream) -> None:
+    rc = load_library().tn_linear_forward2(handle_a, handle_b, x_ptr, ya_ptr, yb_ptr, int(tokens), stream)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_forward2")
+
+
+def forward2(layer_a: "TNLinear", layer_b: "TNLinear", x: torch.Tensor, out_a: Optional[torch.Tensor] = None,
+             out_b: Optional[torch.Tensor] = None):
+    """Both layers applied to x through tn_linear_forward2; returns (ya, yb)."""
+    if not (x.is_cuda and x.is_contiguous() and x.dtype == layer_a.torch_dtype and x.dim() == 2
+            and x.shape[1] == layer_a.N == layer_b.N):
+        raise ValueError("x must be a contiguous CUDA [tokens, N] tensor of the layers' dtype")
+    tokens = x.shape[0]
+    outs = []
+    for layer, out in ((layer_a, out_a), (layer_b, out_b)):
+        if out is None:
+            out = torch.empty((tokens, layer.M), dtype=layer.torch_dtype, device=x.device)
+        elif not (out.is_cuda and out.is_contiguous() and tuple(out.shape) == (tokens, layer.M)):
+            raise ValueError("out has the wrong shape or layout")
+        outs.append(out)
+    tn_linear_forward2(layer_a._handle, layer_b._handle, x.data_ptr(), outs[0].data_ptr(), outs[1].data_ptr(), tokens,
+                       torch.cuda.current_stream().cuda_stream)
+    return outs[0], outs[1]
 
 
 def tn_linear_destroy(handle: Optional[int]) -> None:

@@ -609,9 +609,12 @@ struct Chain2Item {
     }
 };
 
-// A chained pair for a few tokens: one wave per (token, c1 tile) item, four items per workgroup.
+// A chained pair for a few tokens: one wave per (token, c1 tile) item, four items per workgroup. With two
+// argument blocks (two layers applied to the same input, e.g. the gate and up projections of an MLP) the
+// workgroups of blockIdx.y = 1 work on the second layer: one launch serves both.
 template <int R1T, int K1S, int C2T, int RUN_C1>
-__global__ void __launch_bounds__(256) step_chain2_small_kernel(Chain2Args c) {
+__global__ void __launch_bounds__(256) step_chain2_small_kernel(Chain2Args c0, Chain2Args c1) {
+    const Chain2Args& c = blockIdx.y ? c1 : c0;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int item = blockIdx.x * 4 + wave;
     if (item >= c.tokens * c.c1_tiles) return;
@@ -621,9 +624,14 @@ __global__ void __launch_bounds__(256) step_chain2_small_kernel(Chain2Args c) {
 }
 
 template <int K1S, int RUN_C1, int KPW>
-__global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c, StepArgs a, int z_bytes) {
+__global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, StepArgs a0, int z_bytes0, Chain2Args c1,
+                                                                StepArgs a1, int z_bytes1) {
     constexpr int NW = 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    // blockIdx.y = 1: the second of two layers applied to the same input (see step_chain2_small_kernel)
+    const Chain2Args& c = blockIdx.y ? c1 : c0;
+    const StepArgs& a = blockIdx.y ? a1 : a0;
+    const int z_bytes = blockIdx.y ? z_bytes1 : z_bytes0;
     bf16_t* z = reinterpret_cast<bf16_t*>(dyn_smem);                       // [tokens][a.a_tok_stride]
     float* red = reinterpret_cast<float*>(dyn_smem + z_bytes);             // NW x 1024
     const bf16_t* B = static_cast<const bf16_t*>(a.B);
@@ -631,6 +639,7 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c, St
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cb = blockIdx.x;
+    if (cb * 32 >= a.C) return;                                            // the two layers' grids may differ
     const int nks = a.Kp >> 4;
     const int lrow = lane & 31, lhalf = lane >> 5;
     bf16x8 zero;

@@ -1135,20 +1135,7 @@ int plan_chain2(tn_linear_s* h, hipStream_t st) {
     return TN_OK;
 }
 
-int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens,
-                  hipStream_t st) {
-    using k_t = void (*)(Chain2Args);
-    static const k_t kerns[6] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
-                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>,
-                                 step_chain2_kernel<2, 5, 2, 0>, step_chain2_kernel<2, 5, 2, 1>};
-    static const size_t smem[3] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>(), chain2_smem_bytes<2, 5, 2>()};
-    if (!s1.packed) {                      // configuration call (create time)
-        for (int i = 0; i < 6; ++i)
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(smem[i / 2])) != hipSuccess)
-                return TN_ERR_HIP;
-        return TN_OK;
-    }
+Chain2Args chain2_args(const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens) {
     Chain2Args p;
     p.In = A;
     p.Out = Out;
@@ -1165,18 +1152,46 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
     p.C2 = int32_t(s2.plan.C);
     p.nks_a = s1.Kp >> 4;
     p.c1_tiles = (p.C1 + 31) / 32;
-    const int64_t waves = int64_t(h->num_cus) * 4;
-    if (tokens * p.c1_tiles <= waves && !(h->flags & TN_FLAG_NO_DECODE_FUSION)) {
-        // few tokens: every (token, c1 tile) item gets a wave of its own, operands requested up front
-        static const k_t small[6] = {step_chain2_small_kernel<3, 6, 5, 0>, step_chain2_small_kernel<3, 6, 5, 1>,
-                                     step_chain2_small_kernel<2, 8, 2, 0>, step_chain2_small_kernel<2, 8, 2, 1>,
-                                     step_chain2_small_kernel<2, 5, 2, 0>, step_chain2_small_kernel<2, 5, 2, 1>};
-        p.tiles_per_item = 1;
-        const int64_t items = tokens * p.c1_tiles;
-        hipLaunchKernelGGL(small[s1.chain_cfg * 2 + s1.chain_run_c1], dim3(uint32_t((items + 3) / 4)), dim3(256), 0, st, p);
-        return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+    p.tiles_per_item = 1;
+    return p;
+}
+
+// Few tokens: every (token, c1 tile) item of a chained pair gets a wave of its own, operands requested up front.
+bool chain2_small_applies(const tn_linear_s* h, const DevStep& s1, int64_t tokens) {
+    return tokens * ((s1.plan.C + 31) / 32) <= int64_t(h->num_cus) * 4 && !(h->flags & TN_FLAG_NO_DECODE_FUSION);
+}
+
+// One launch for the pair of one layer (p1 == nullptr) or of two layers with the same instantiation.
+int launch_chain2_small(const DevStep& s1, const Chain2Args& p0, const Chain2Args* p1, hipStream_t st) {
+    using k_t = void (*)(Chain2Args, Chain2Args);
+    static const k_t small[6] = {step_chain2_small_kernel<3, 6, 5, 0>, step_chain2_small_kernel<3, 6, 5, 1>,
+                                 step_chain2_small_kernel<2, 8, 2, 0>, step_chain2_small_kernel<2, 8, 2, 1>,
+                                 step_chain2_small_kernel<2, 5, 2, 0>, step_chain2_small_kernel<2, 5, 2, 1>};
+    int64_t items = int64_t(p0.tokens) * p0.c1_tiles;
+    if (p1) items = std::max(items, int64_t(p1->tokens) * p1->c1_tiles);
+    hipLaunchKernelGGL(small[s1.chain_cfg * 2 + s1.chain_run_c1], dim3(uint32_t((items + 3) / 4), p1 ? 2 : 1), dim3(256), 0, st,
+                       p0, p1 ? *p1 : p0);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const void* A, void* Out, int64_t tokens,
+                  hipStream_t st) {
+    using k_t = void (*)(Chain2Args);
+    static const k_t kerns[6] = {step_chain2_kernel<3, 6, 5, 0>, step_chain2_kernel<3, 6, 5, 1>,
+                                 step_chain2_kernel<2, 8, 2, 0>, step_chain2_kernel<2, 8, 2, 1>,
+                                 step_chain2_kernel<2, 5, 2, 0>, step_chain2_kernel<2, 5, 2, 1>};
+    static const size_t smem[3] = {chain2_smem_bytes<3, 6, 5>(), chain2_smem_bytes<2, 8, 2>(), chain2_smem_bytes<2, 5, 2>()};
+    if (!s1.packed) {                      // configuration call (create time)
+        for (int i = 0; i < 6; ++i)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(smem[i / 2])) != hipSuccess)
+                return TN_ERR_HIP;
+        return TN_OK;
     }
+    Chain2Args p = chain2_args(s1, s2, A, Out, tokens);
+    if (chain2_small_applies(h, s1, tokens)) return launch_chain2_small(s1, p, nullptr, st);
     // a wave per token when there are tokens enough to fill the chip, else a wave per (token, c1 tile)
+    const int64_t waves = int64_t(h->num_cus) * 4;
     p.tiles_per_item = tokens >= waves ? p.c1_tiles : 1;
     const int64_t n_groups = (p.c1_tiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const int64_t items = tokens * n_groups;
@@ -1204,37 +1219,20 @@ bool chain2_split_applies(const tn_linear_s* h, const DevStep& s1, const DevStep
     return sc.use && sc.nsplit == 1 && sc.tm == 1 && sc.nw == 8 && sc.row_tiles == 1;
 }
 
-int launch_chain2_split(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, const DevStep& s3, const void* A,
-                        void* Out, int64_t tokens, hipStream_t st) {
-    using k_t = void (*)(Chain2Args, StepArgs, int);
-    static const k_t kerns[4] = {step_chain2_split_kernel<8, 0, kFusedDecodeKPW>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW>,
-                                 step_chain2_split_kernel<5, 0, kFusedDecodeKPW>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW>};
-    if (!s1.packed) {                      // configuration call (create time)
-        for (int i = 0; i < 4; ++i)
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(kFusedDecodeRedBytes + size_t(kFusedDecodeMaxZBytes))) != hipSuccess)
-                return TN_ERR_HIP;
-        return TN_OK;
-    }
-    Chain2Args p;
-    p.In = A;
-    p.Out = nullptr;                       // the pair's result stays in LDS
-    p.Ba = s1.packed;
-    p.Bbf = s1.chain_bbf;
-    p.off1 = s2.crow;
-    p.off2 = s2.ccol;
-    p.in_tok_stride = s1.plan.a_tok_stride;
-    p.out_tok_stride = s2.plan.c_tok_stride;
-    p.tokens = int32_t(tokens);
-    p.R1 = int32_t(s1.plan.R);
-    p.K1 = int32_t(s1.plan.K);
-    p.C1 = int32_t(s1.plan.C);
-    p.C2 = int32_t(s2.plan.C);
-    p.nks_a = s1.Kp >> 4;
-    p.c1_tiles = (p.C1 + 31) / 32;
-    p.tiles_per_item = 1;
+struct Chain2SplitArgs {
+    Chain2Args c;
     StepArgs a;
-    a.A = nullptr;                         // likewise
+    int z_bytes = 0;
+    int kern = 0;
+    uint32_t col_blocks = 0;
+};
+
+Chain2SplitArgs chain2_split_args(const DevStep& s1, const DevStep& s2, const DevStep& s3, const void* A, void* Out,
+                                  int64_t tokens) {
+    Chain2SplitArgs r;
+    r.c = chain2_args(s1, s2, A, nullptr, tokens);      // the pair's result stays in LDS
+    StepArgs& a = r.a;
+    a.A = nullptr;                                       // likewise
     a.B = s3.packed;
     a.Out = Out;
     a.arow = nullptr;
@@ -1249,10 +1247,29 @@ int launch_chain2_split(const tn_linear_s* h, const DevStep& s1, const DevStep& 
     a.Kp = s3.Kp;
     a.C = int32_t(s3.plan.C);
     a.Cp = s3.Cp;
-    const int z_bytes = int((tokens * s3.plan.a_tok_stride * 2 + 255) & ~int64_t(255));
-    const uint32_t col_blocks = uint32_t((s3.plan.C + 31) / 32);
-    hipLaunchKernelGGL(kerns[(s1.chain_cfg - 1) * 2 + s1.chain_run_c1], dim3(col_blocks), dim3(512),
-                       kFusedDecodeRedBytes + size_t(z_bytes), st, p, a, z_bytes);
+    r.z_bytes = int((tokens * s3.plan.a_tok_stride * 2 + 255) & ~int64_t(255));
+    r.kern = (s1.chain_cfg - 1) * 2 + s1.chain_run_c1;
+    r.col_blocks = uint32_t((s3.plan.C + 31) / 32);
+    return r;
+}
+
+// One launch for one layer (p1 == nullptr) or for two layers on the same instantiation (grid.y = 2).
+int launch_chain2_split(const Chain2SplitArgs* p0, const Chain2SplitArgs* p1, hipStream_t st) {
+    using k_t = void (*)(Chain2Args, StepArgs, int, Chain2Args, StepArgs, int);
+    static const k_t kerns[4] = {step_chain2_split_kernel<8, 0, kFusedDecodeKPW>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW>,
+                                 step_chain2_split_kernel<5, 0, kFusedDecodeKPW>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW>};
+    if (!p0) {                             // configuration call (create time)
+        for (int i = 0; i < 4; ++i)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(kFusedDecodeRedBytes + size_t(kFusedDecodeMaxZBytes))) != hipSuccess)
+                return TN_ERR_HIP;
+        return TN_OK;
+    }
+    const Chain2SplitArgs& q = p1 ? *p1 : *p0;
+    const uint32_t blocks = std::max(p0->col_blocks, q.col_blocks);
+    const size_t smem = kFusedDecodeRedBytes + size_t(std::max(p0->z_bytes, q.z_bytes));
+    hipLaunchKernelGGL(kerns[p0->kern], dim3(blocks, p1 ? 2 : 1), dim3(512), smem, st, p0->c, p0->a, p0->z_bytes, q.c, q.a,
+                       q.z_bytes);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
@@ -1276,7 +1293,7 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = launch_pipe<4, 1, 2, 4, 1, 2>(none, a, 0, nullptr);
     if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
-    if (rc == TN_OK) rc = launch_chain2_split(no_handle, none, none, none, nullptr, nullptr, 0, nullptr);
+    if (rc == TN_OK) rc = launch_chain2_split(nullptr, nullptr, nullptr);
     if (rc == TN_OK &&
         (hipFuncSetAttribute(reinterpret_cast<const void*>(&step_pair_kernel<kPairStages, kPairBar>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
@@ -1441,7 +1458,7 @@ int materialise_merges(const tn::Plan& plan, const tn_linear_desc* desc, int elt
 
 extern "C" {
 
-int tn_linear_version(void) { return 3; }
+int tn_linear_version(void) { return 4; }
 
 const char* tn_linear_strerror(int status) {
     switch (status) {
@@ -1836,7 +1853,8 @@ int forward_in(tn_linear_s* h, const Workspace& w, bool allow_lazy, const void* 
                 // few tokens: the pair and the wide step after it in one launch, the pair's result in LDS
                 const tn::LaunchIO& l2 = h->schedule[li + 1];
                 void* Out2 = l2.out == tn::kBufY ? static_cast<void*>(yb + t0 * h->plan.M * h->elt) : w.ws[l2.out];
-                rc = launch_chain2_split(h, s, h->steps[size_t(l.first) + 1], h->steps[size_t(l.first) + 2], A, Out2, nt, st);
+                const Chain2SplitArgs fa = chain2_split_args(s, h->steps[size_t(l.first) + 1], h->steps[size_t(l.first) + 2], A, Out2, nt);
+                rc = launch_chain2_split(&fa, nullptr, st);
                 ++li;
             } else {
                 rc = l.steps == 2 ? launch_chain2(h, s, h->steps[size_t(l.first) + 1], A, Out, nt, st)
@@ -1864,6 +1882,77 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
     w.partial_bytes = h->partial_bytes;
     w.chunk_tokens = h->chunk_tokens;
     return forward_in(h, w, true, x, y, tokens, static_cast<hipStream_t>(stream));
+}
+
+int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, void* yb, int64_t tokens, void* stream) {
+    if (!ha || !hb || tokens < 0) return TN_ERR_INVALID_ARG;
+    if (ha->elt != hb->elt || ha->plan.N != hb->plan.N) return TN_ERR_INVALID_ARG;
+    if (tokens == 0) return TN_OK;
+    if (!x || !ya || !yb) return TN_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Launch by launch in step when the two layers have the same launch structure and the call is one pass of
+    // the per-step path for both: where a launch of the decode-size kernels serves both layers, it does.
+    auto per_step_path = [&](const tn_linear_s* h) {
+        return !h->profiling && !(h->small_chain && (h->elt == 4 || tokens <= kSmallChainMaxBf16Tokens)) &&
+               !(h->pair && tokens >= h->pair_min_tokens) && !(h->kron && tokens >= h->kron_min_tokens) &&
+               !(h->lazy && tokens >= h->lazy_min_tokens) && tokens <= h->chunk_tokens;
+    };
+    bool together = ha != hb && per_step_path(ha) && per_step_path(hb) && ha->schedule.size() == hb->schedule.size();
+    for (size_t li = 0; together && li < ha->schedule.size(); ++li) {
+        const tn::LaunchIO &la = ha->schedule[li], &lb = hb->schedule[li];
+        if (la.first != lb.first || la.steps != lb.steps) together = false;
+        else if (la.steps == 2 && (ha->steps[size_t(la.first)].chain_cfg != hb->steps[size_t(lb.first)].chain_cfg ||
+                                   ha->steps[size_t(la.first)].chain_run_c1 != hb->steps[size_t(lb.first)].chain_run_c1))
+            together = false;
+    }
+    if (!together) {
+        int rc = tn_linear_forward(ha, x, ya, tokens, stream);
+        return rc != TN_OK ? rc : tn_linear_forward(hb, x, yb, tokens, stream);
+    }
+    tn_linear_s* hs[2] = {ha, hb};
+    void* ys[2] = {ya, yb};
+    Workspace ws[2];
+    for (int n = 0; n < 2; ++n) {
+        ws[n].ws[0] = hs[n]->ws[0];
+        ws[n].ws[1] = hs[n]->ws[1];
+        ws[n].partial = hs[n]->partial;
+        ws[n].partial_bytes = hs[n]->partial_bytes;
+        ws[n].chunk_tokens = hs[n]->chunk_tokens;
+    }
+    auto buffer = [&](int n, int id) -> void* {
+        return id == tn::kBufX ? const_cast<void*>(x) : (id == tn::kBufY ? ys[n] : ws[n].ws[id]);
+    };
+    for (size_t li = 0; li < ha->schedule.size(); ++li) {
+        const tn::LaunchIO& l = ha->schedule[li];
+        const size_t f = size_t(l.first);
+        const bool has_next = li + 1 < ha->schedule.size() && ha->schedule[li + 1].steps == 1;
+        int rc = TN_OK;
+        if (l.steps == 2 && has_next && chain2_split_applies(ha, ha->steps[f], ha->steps[f + 2], tokens) &&
+            chain2_split_applies(hb, hb->steps[f], hb->steps[f + 2], tokens)) {
+            // pair and wide step of both layers in one launch
+            Chain2SplitArgs fa[2];
+            for (int n = 0; n < 2; ++n)
+                fa[n] = chain2_split_args(hs[n]->steps[f], hs[n]->steps[f + 1], hs[n]->steps[f + 2],
+                                          buffer(n, hs[n]->schedule[li].in), buffer(n, hs[n]->schedule[li + 1].out), tokens);
+            rc = launch_chain2_split(&fa[0], &fa[1], st);
+            ++li;
+        } else if (l.steps == 2 && chain2_small_applies(ha, ha->steps[f], tokens) && chain2_small_applies(hb, hb->steps[f], tokens)) {
+            Chain2Args ca[2];
+            for (int n = 0; n < 2; ++n)
+                ca[n] = chain2_args(hs[n]->steps[f], hs[n]->steps[f + 1], buffer(n, hs[n]->schedule[li].in),
+                                    buffer(n, hs[n]->schedule[li].out), tokens);
+            rc = launch_chain2_small(ha->steps[f], ca[0], &ca[1], st);
+        } else {
+            for (int n = 0; n < 2 && rc == TN_OK; ++n) {
+                const tn::LaunchIO& ln = hs[n]->schedule[li];
+                const DevStep& s = hs[n]->steps[f];
+                rc = ln.steps == 2 ? launch_chain2(hs[n], s, hs[n]->steps[f + 1], buffer(n, ln.in), buffer(n, ln.out), tokens, st)
+                                   : launch_step(hs[n], ws[n], s, buffer(n, ln.in), buffer(n, ln.out), tokens, st);
+            }
+        }
+        if (rc != TN_OK) return rc;
+    }
+    return TN_OK;
 }
 
 int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {

@@ -767,3 +767,62 @@ def test_config0_one_launch():
     y = to_host(layer(to_dev(x, "f32")))
     layer.close()
     assert O.rel_max_err(y, O.forward(spec.format, ts, x)) <= 1e-5
+
+
+FORWARD2_CASES = [
+    # (spec of layer a, spec of layer b): same input width
+    (wl.baseline_spec(2)[0], wl.baseline_spec(2)[0]),                                                   # gate / up as Tucker layers
+    (wl.stack_spec(wl.FORMAT_TUCKER, 8192, 5120, 64), wl.stack_spec(wl.FORMAT_TUCKER, 8192, 5120, 64)),   # K1 = 128 instantiation
+    (wl.baseline_spec(2)[0], wl.stack_spec(wl.FORMAT_TUCKER, 5120, 25600, 64)),                         # different ranks: other core widths
+    (wl.baseline_spec(2)[0], wl.stack_spec(wl.FORMAT_DENSE, 5120, 8192, 0)),                            # different formats: back to back
+    (wl.baseline_spec(1)[0], wl.baseline_spec(1)[0]),                                                   # trains: back to back
+]
+
+
+@pytest.mark.parametrize("case", range(len(FORWARD2_CASES)))
+def test_two_layers_in_one_call(case):
+    """tn_linear_forward2 (two layers on the same activations, e.g. gate and up projections): both results against
+    two separate oracle forwards and against tn_linear_forward on each handle, at token counts that take the shared
+    decode-size launches (1, 2), the per-step path (5, 40) and the large-call kernels (300)."""
+    sa, sb = FORWARD2_CASES[case]
+    ta, tb = wl.make_tensors(sa, 80 + case, instance=0), wl.make_tensors(sb, 80 + case, instance=1)
+    wa, wb = O.dense_weight(sa.format, ta, len(sa.out_modes)), O.dense_weight(sb.format, tb, len(sb.out_modes))
+    la, lb = make_layer(sa, ta, 300), make_layer(sb, tb, 300)
+    for tokens in (1, 2, 5, 40, 300):
+        x = wl.make_x(sa, tokens, 80 + case)
+        xd = to_dev(x, "bf16")
+        ya, yb = tn.forward2(la, lb, xd)
+        torch.cuda.synchronize()
+        for y, w, layer in ((ya, wa, la), (yb, wb, lb)):
+            err = O.rel_max_err(to_host(y), O.apply_linear(w, x))
+            assert err <= TOL["bf16"], (case, tokens, err)
+            assert torch.equal(y, layer(xd)), (case, tokens)             # the same kernels on the same data
+    # under stream capture: both layers in one graph, replayed
+    xd = to_dev(wl.make_x(sa, 1, 80 + case), "bf16")
+    ga = torch.empty((1, sa.M), dtype=torch.bfloat16, device="cuda")
+    gb = torch.empty((1, sb.M), dtype=torch.bfloat16, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        tn.forward2(la, lb, xd, ga, gb)
+    ea, eb = tn.forward2(la, lb, xd)
+    torch.cuda.synchronize()
+    for _ in range(2):
+        ga.fill_(0)
+        gb.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ga, ea) and torch.equal(gb, eb)
+    del graph
+    la.close()
+    lb.close()
+    with pytest.raises(tn.TNLinearError):                                  # different input widths
+        l1 = make_layer(wl.baseline_spec(2)[0], wl.make_tensors(wl.baseline_spec(2)[0], 2), 4)
+        l3 = make_layer(wl.stack_spec(wl.FORMAT_DENSE, 8192, 5120, 0), wl.make_tensors(wl.stack_spec(wl.FORMAT_DENSE, 8192, 5120, 0), 4), 4)
+        try:
+            tn.tn_linear_forward2(l1._handle, l3._handle, xd.data_ptr(), ga.data_ptr(), gb.data_ptr(), 1, None)
+        finally:
+            l1.close()
+            l3.close()
