@@ -15,4 +15,5 @@ from .tn_oracle import (  # noqa: F401
     brute_force_weight,
     tt_svd,
     rel_max_err,
+    param_gradients,
 )

@@ -33,7 +33,10 @@ rotation of a ring; closed-form output variance and Frobenius norms; a stepwise
 chain contraction of the activations agrees with rebuild-then-multiply; the
 row-sampled ring rebuild (tr_dense_rows) agrees entry by entry with traces of
 matrix products taken with numpy and with the nested-loop evaluator; a dense
-weight handed over as a [1, M, N, 1] core equals the plain matrix.
+weight handed over as a [1, M, N, 1] core equals the plain matrix; the parameter
+gradients (param_gradients) equal, entry by entry, the loss evaluated with that
+tensor replaced by a unit tensor (the loss is linear in each tensor alone), and
+central finite differences of the loss.
 """
 from __future__ import annotations
 
@@ -192,6 +195,71 @@ def forward(fmt: int, tensors: Sequence[np.ndarray], x: np.ndarray,
             n_out_modes: int | None = None) -> np.ndarray:
     """Rebuild W, then multiply: the reference result for one layer."""
     return apply_linear(dense_weight(fmt, tensors, n_out_modes), x)
+
+
+def _network_labels(fmt: int, tensors: Sequence[np.ndarray], n_out_modes: int | None):
+    """The layer as a labelled tensor network: (labels of every tensor, out-mode labels, in-mode labels), integer
+    labels, such that W[out..., in...] = sum over every other label of the product of the tensors."""
+    if fmt == FORMAT_DENSE:
+        return [[0, 1]], [0], [1]
+    if fmt in (FORMAT_TT, FORMAT_TR):
+        d = len(tensors)
+        out = list(range(d))
+        inn = list(range(d, 2 * d))
+        bond = list(range(2 * d, 3 * d + 1))
+        bond[d] = bond[0]                            # the ring bond: one label, two owners (a train is a ring of boundary rank 1)
+        return [[bond[k], out[k], inn[k], bond[k + 1]] for k in range(d)], out, inn
+    if fmt == FORMAT_TUCKER:
+        p = n_out_modes
+        q = len(tensors) - 1 - p
+        out = list(range(p))
+        inn = list(range(p, p + q))
+        ranks = list(range(p + q, 2 * (p + q)))
+        labels = [ranks]
+        labels += [[out[a], ranks[a]] for a in range(p)]
+        labels += [[inn[b], ranks[p + b]] for b in range(q)]
+        return labels, out, inn
+    raise ValueError("unknown format")
+
+
+def param_gradients(fmt: int, tensors: Sequence[np.ndarray], x: np.ndarray, dy: np.ndarray,
+                    n_out_modes: int | None = None) -> List[np.ndarray]:
+    """Gradients of L = sum_{t,i} dY[t,i] Y[t,i], Y = X W^T, with respect to every parameter tensor (what the
+    fine-tuning of the factors, Section 3.4, back-propagates), each in its tensor's own shape.
+
+    dL/dW = D = dY^T X. W is linear in each tensor taken alone, so dL/dtheta_k is the network of W with theta_k
+    taken out and D put in over the out- and in-mode labels: one einsum per tensor, written from the definitions
+    of the formats (Section 3.3) and not from the chain the GPU walks. A ring of one core carries its bond label
+    twice: its gradient is D on the diagonal of the two bond axes.
+    """
+    ts = [_f64(t) for t in tensors]
+    d_w = _f64(dy).T @ _f64(x)                                            # [M, N]
+    if fmt == FORMAT_DENSE:
+        return [d_w.reshape(ts[0].shape)]
+    labels, out, inn = _network_labels(fmt, ts, n_out_modes)
+    if fmt in (FORMAT_TT, FORMAT_TR) and len(ts) == 1:
+        r, m, n, _ = ts[0].shape
+        g = np.zeros_like(ts[0])
+        for a in range(r):
+            g[a, :, :, a] = d_w
+        return [g]
+    if fmt in (FORMAT_TT, FORMAT_TR):
+        ms = [t.shape[1] for t in ts]
+        ns = [t.shape[2] for t in ts]
+    else:
+        p = n_out_modes
+        ms = [u.shape[0] for u in ts[1:1 + p]]
+        ns = [v.shape[0] for v in ts[1 + p:]]
+    d_t = d_w.reshape(*ms, *ns)
+    grads = []
+    for k in range(len(ts)):
+        operands = [d_t, out + inn]
+        for l in range(len(ts)):
+            if l != k:
+                operands += [ts[l], labels[l]]
+        g = np.einsum(*operands, labels[k], optimize="greedy")
+        grads.append(np.ascontiguousarray(g))
+    return grads
 
 
 def brute_force_weight(fmt: int, tensors: Sequence[np.ndarray], n_out_modes: int | None = None) -> np.ndarray:

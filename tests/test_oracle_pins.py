@@ -364,3 +364,70 @@ def test_dense_weight_accepts_a_single_core():
     np.testing.assert_array_equal(O.dense_weight(DENSE, [w.reshape(1, 5, 7, 1)]), O.tt_dense([w.reshape(1, 5, 7, 1)]))
     x = rng.standard_normal((3, 7))
     np.testing.assert_allclose(O.forward(DENSE, [w.reshape(1, 5, 7, 1)], x), x @ w.T, atol=1e-13)
+
+
+# ---- parameter gradients: the loss is linear in each tensor alone, so an entry of the gradient is the loss with
+#      that tensor replaced by the unit tensor of the entry; plus central differences and the dense closed form ----
+GRAD_CASES = [
+    (TT, (2, 3, 2), (3, 2, 2), (1, 2, 3, 1), None),
+    (TT, (3,), (4,), (1, 1), None),
+    (TR, (2, 3, 2), (3, 2, 2), (2, 3, 2, 2), None),
+    (TR, (2, 2), (3, 2), (3, 2, 3), None),
+    (TR, (3,), (4,), (2, 2), None),                       # a ring of one core: the bond is traced inside the tensor
+    (TUCKER, (3, 2), (2, 4), (2, 2, 2, 3), 2),
+    (TUCKER, (3, 2, 2), (5,), (2, 2, 1, 3), 3),
+    (DENSE, (5,), (7,), (), None),
+]
+
+
+def _loss(fmt, ts, x, dy, p):
+    return float(np.sum(dy * O.forward(fmt, ts, x, n_out_modes=p)))
+
+
+@pytest.mark.parametrize("fmt,ms,ns,rs,p", GRAD_CASES)
+def test_param_gradients_equal_the_loss_on_unit_tensors(fmt, ms, ns, rs, p):
+    rng = np.random.default_rng(50 + len(ms) + 7 * fmt)
+    spec = wl.TNSpec(fmt, "f32", tuple(ms), tuple(ns), tuple(rs))
+    ts = [rng.standard_normal(s) for s in spec.tensor_shapes()]
+    x = rng.standard_normal((4, spec.N))
+    dy = rng.standard_normal((4, spec.M))
+    grads = O.param_gradients(fmt, ts, x, dy, n_out_modes=p)
+    assert [g.shape for g in grads] == [t.shape for t in ts]
+    for k, t in enumerate(ts):
+        for e in range(t.size):
+            unit = np.zeros(t.size)
+            unit[e] = 1.0
+            probe = list(ts)
+            probe[k] = unit.reshape(t.shape)
+            assert abs(grads[k].reshape(-1)[e] - _loss(fmt, probe, x, dy, p)) < 1e-10, (k, e)
+
+
+@pytest.mark.parametrize("fmt,ms,ns,rs,p", GRAD_CASES[:6])
+def test_param_gradients_match_central_differences(fmt, ms, ns, rs, p):
+    rng = np.random.default_rng(60 + len(ms) + 7 * fmt)
+    spec = wl.TNSpec(fmt, "f32", tuple(ms), tuple(ns), tuple(rs))
+    ts = [rng.standard_normal(s) for s in spec.tensor_shapes()]
+    x = rng.standard_normal((3, spec.N))
+    dy = rng.standard_normal((3, spec.M))
+    grads = O.param_gradients(fmt, ts, x, dy, n_out_modes=p)
+    h = 1e-5
+    for k, t in enumerate(ts):
+        for e in rng.choice(t.size, size=min(t.size, 6), replace=False):
+            up, dn = [a.copy() for a in ts], [a.copy() for a in ts]
+            up[k].reshape(-1)[e] += h
+            dn[k].reshape(-1)[e] -= h
+            fd = (_loss(fmt, up, x, dy, p) - _loss(fmt, dn, x, dy, p)) / (2 * h)
+            assert abs(fd - grads[k].reshape(-1)[e]) < 1e-6 * max(1.0, abs(fd))
+
+
+def test_param_gradient_of_a_dense_layer_is_dyT_x():
+    rng = np.random.default_rng(70)
+    w, x, dy = rng.standard_normal((5, 7)), rng.standard_normal((4, 7)), rng.standard_normal((4, 5))
+    np.testing.assert_allclose(O.param_gradients(DENSE, [w], x, dy)[0], dy.T @ x, atol=1e-13)
+    # and the gradients are linear in dY and additive over tokens
+    ts = _cores(rng, (2, 3), (3, 2), (1, 2, 1))
+    x, dy = rng.standard_normal((6, 6)), rng.standard_normal((6, 6))
+    whole = O.param_gradients(TT, ts, x, dy)
+    parts = [O.param_gradients(TT, ts, x[a:b], dy[a:b]) for a, b in ((0, 2), (2, 6))]
+    for k in range(2):
+        np.testing.assert_allclose(whole[k], parts[0][k] + parts[1][k], atol=1e-12)
