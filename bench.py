@@ -425,6 +425,45 @@ def pair_record(spec, config_id, args, instances=8):
     return out
 
 
+def gradient_record(spec, config_id, tokens, reps=3):
+    """tn_linear_param_gradients (gradients of a loss with respect to every parameter tensor, Section 3.4) on a
+    trainable copy of the layer: tokens/s of one call (forward with saved intermediates + backward) and the FLOP/s of
+    its executed contractions (per step: the forward product, the parameter gradient and, except for the first step,
+    the input gradient)."""
+    import torch
+    import workloads as wl
+    import paper_2602_01613_amd as tn
+    ts = wl.make_tensors(spec, config_id)
+    tdt = torch.bfloat16 if spec.dtype == "bf16" else torch.float32
+    code = tn.TN_DTYPE_BF16 if spec.dtype == "bf16" else tn.TN_DTYPE_F32
+    dev = [torch.from_numpy(t).to(torch.float32).to(tdt).cuda() for t in ts]
+    layer = tn.TNLinear(spec.format, code, spec.out_modes, spec.in_modes, spec.ranks, dev, tokens, flags=tn.TN_FLAG_TRAINABLE)
+    x = torch.from_numpy(wl.make_x(spec, tokens, config_id)).to(torch.float32).to(tdt).cuda()
+    dy = torch.from_numpy(wl.make_x(wl.TNSpec(spec.format, spec.dtype, spec.in_modes, spec.out_modes, spec.ranks), tokens,
+                                    config_id, instance=3)).to(torch.float32).to(tdt).cuda()
+    grads = layer.param_gradients(x, dy)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        layer.param_gradients(x, dy, out=grads)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / reps
+    n = layer.query(tn.TN_QUERY_NUM_STEPS)
+    step_flops = [layer.query(tn.TN_QUERY_STEP_BASE + 10 * s + 3) for s in range(n)]
+    flops = sum(step_flops[:-1]) + sum(step_flops) + sum(step_flops[1:])
+    out = {"workload": f"{spec.name}: parameter gradients, {tokens} tokens, {n} steps (no create-time merges)",
+           "tokens": tokens, "ms_per_call": 1e3 * sec, "tokens_per_s": tokens / sec,
+           "flops_per_token": flops, "tflops": flops * tokens / sec / 1e12,
+           "backward_chunk_tokens": layer.query(tn.TN_QUERY_BACKWARD_CHUNK_TOKENS),
+           "backward_workspace_MB": layer.query(tn.TN_QUERY_BACKWARD_WORKSPACE_BYTES) / 1e6,
+           "roofline": {"bound": "alu", "achieved": flops * tokens / sec / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                        "frac": flops * tokens / sec / 1e12 / 157.3,
+                        "kernel": "whole call; its parameter-gradient contractions run on plain fp32 FMA (the forward and "
+                                  "input-gradient steps on the MFMA step kernels), so the fp32 vector peak is the yardstick"}}
+    layer.close()
+    return out
+
+
 def draw_on_device(spec, gen):
     """Parameter tensors of one stack matrix drawn on the GPU (the stack holds 60 GB of them), same
     distributions as workloads.make_tensors, rounded to bf16: these are the inputs of both sides."""
@@ -748,6 +787,9 @@ def main() -> int:
             pending_cpu.append((name, sub_keep))
         if time.perf_counter() - t_start <= args.time_budget_s:
             configs["tucker_gate_up_pair"] = pair_record(wl.baseline_spec(2)[0], 2, args)
+        if time.perf_counter() - t_start <= args.time_budget_s:
+            configs["param_gradients"] = {"tt_q_proj": gradient_record(wl.baseline_spec(1)[0], 1, 1024),
+                                          "tucker_up_proj": gradient_record(wl.baseline_spec(2)[0], 2, 1024)}
 
     pre = rec["prefill"]
     result = {

@@ -69,6 +69,10 @@ extern "C" {
                                        the gradient of the forward pass with respect to its input, which the
                                        fine-tuning of the factors (Section 3.4) back-propagates through every
                                        layer. TN_QUERY_IN_FEATURES / OUT_FEATURES then report M / N. */
+#define TN_FLAG_TRAINABLE (1 << 25)      /* the layer can also give the gradients of a loss with respect to its tensors
+                                       (tn_linear_param_gradients, Section 3.4): every parameter tensor of the caller
+                                       stays separate (as with TN_FLAG_NO_MERGE; no lazily merged plan either) and the
+                                       handle holds a second workspace for the saved intermediates of a backward pass */
 #define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* never run a chained factor pair and the wide step after it as one launch
                                        (calls of a few tokens: the in-factor products and the core of a Tucker layer) */
 #define TN_FLAG_NO_SMALL_CHAIN (1 << 20) /* never run a small layer as one launch with all its tensors in LDS */
@@ -116,6 +120,8 @@ extern "C" {
                                            compact ones (microseconds) and run that one launch; the layer stores
                                            only the compact tensors, and smaller calls run the compact steps */
 #define TN_QUERY_LAZY_FLOPS_PER_TOKEN 13 /* handle only: FLOPs per token of that plan (0 if none) */
+#define TN_QUERY_BACKWARD_CHUNK_TOKENS 14 /* handle only: tokens per pass of tn_linear_param_gradients (0: not trainable) */
+#define TN_QUERY_BACKWARD_WORKSPACE_BYTES 15 /* handle only: device memory held for those passes */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=
@@ -225,6 +231,23 @@ int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, voi
  * same kernels run).
  */
 int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, void* yb, int64_t tokens, void* stream);
+
+/*
+ * Gradients with respect to the parameter tensors (Section 3.4: after compression the factors are fine-tuned, so a
+ * loss is back-propagated through every factorised layer). For L = sum_{t,i} dY[t,i] Y[t,i] with Y = X W^T:
+ *   grads[s]  DEVICE fp32 array of the shape of desc.tensors[s] (canonical layout), overwritten with dL/d tensors[s];
+ *             a NULL entry skips that tensor. The array of pointers is host memory, n_tensors entries.
+ *   x  DEVICE [tokens, N], dy DEVICE [tokens, M], of the handle's dtype, read only.
+ * The call re-runs the contraction steps keeping every intermediate, then walks them backwards: for each step the
+ * gradient of its parameter tensor is the step's own contraction with the token and row indices summed (fp32
+ * accumulation, partial sums over row ranges added in a fixed order: bit-reproducible), and the gradient handed to
+ * the step before is the step with its tensor transposed. Intermediates are rounded to the handle's dtype as in the
+ * forward pass. Needs a handle created with TN_FLAG_TRAINABLE (else TN_ERR_INVALID_ARG); tokens beyond the backward
+ * workspace are processed in passes whose gradients are added. The gradient with respect to x is what a handle
+ * created with TN_FLAG_TRANSPOSE computes. Asynchronous on `stream`, no allocation.
+ */
+int tn_linear_param_gradients(tn_linear_t h, const void* x, const void* dy, void* const* grads, int64_t tokens,
+                              void* stream);
 
 /*
  * tn_linear_forward for callers that cannot allocate and want no workspace tied to the handle: code under

@@ -30,6 +30,7 @@ TN_FLAG_NO_LAZY_MERGE = 1 << 21
 TN_FLAG_MERGE_HALVES = 1 << 22
 TN_FLAG_SCALAR_GENERATE = 1 << 23
 TN_FLAG_NO_DECODE_FUSION = 1 << 24
+TN_FLAG_TRAINABLE = 1 << 25
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -44,6 +45,8 @@ TN_QUERY_PAIR_CHAINABLE = 10
 TN_QUERY_KRON_CHAINABLE = 11
 TN_QUERY_LAZY_MIN_TOKENS = 12
 TN_QUERY_LAZY_FLOPS_PER_TOKEN = 13
+TN_QUERY_BACKWARD_CHUNK_TOKENS = 14
+TN_QUERY_BACKWARD_WORKSPACE_BYTES = 15
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (
@@ -51,6 +54,7 @@ EXPORTED_SYMBOLS = (
     "tn_linear_forward",
     "tn_linear_forward_scratch",
     "tn_linear_forward2",
+    "tn_linear_param_gradients",
     "tn_linear_destroy",
     "tn_linear_query",
     "tn_linear_plan_query",
@@ -116,6 +120,9 @@ def load_library():
     lib.tn_linear_forward2.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_int64, ctypes.c_void_p]
     lib.tn_linear_forward2.restype = ctypes.c_int
+    lib.tn_linear_param_gradients.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64, ctypes.c_void_p]
+    lib.tn_linear_param_gradients.restype = ctypes.c_int
     lib.tn_linear_destroy.argtypes = [ctypes.c_void_p]
     lib.tn_linear_destroy.restype = ctypes.c_int
     lib.tn_linear_query.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
@@ -235,6 +242,14 @@ def forward2(layer_a: "TNLinear", layer_b: "TNLinear", x: torch.Tensor, out_a: O
     return outs[0], outs[1]
 
 
+def tn_linear_param_gradients(handle: int, x_ptr: int, dy_ptr: int, grad_ptrs: Sequence[Optional[int]], tokens: int,
+                              stream) -> None:
+    arr = (ctypes.c_void_p * max(1, len(grad_ptrs)))(*grad_ptrs)
+    rc = load_library().tn_linear_param_gradients(handle, x_ptr, dy_ptr, arr, int(tokens), stream)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_param_gradients")
+
+
 def tn_linear_destroy(handle: Optional[int]) -> None:
     rc = load_library().tn_linear_destroy(handle)
     if rc != 0:
@@ -288,6 +303,7 @@ class TNLinear:
             if not (workspace.is_cuda and workspace.is_contiguous()):
                 raise ValueError("workspace must be a contiguous CUDA tensor")
             ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        self._tensor_shapes = [tuple(t.shape) for t in tensors]
         self._handle = tn_linear_create(fmt, dtype, out_modes, in_modes, ranks,
                                         [t.data_ptr() for t in tensors], max_tokens,
                                         workspace_limit_bytes, flags, stream, ws_ptr, ws_bytes)
@@ -313,6 +329,22 @@ class TNLinear:
         return out
 
     __call__ = forward
+
+    def param_gradients(self, x: torch.Tensor, dy: torch.Tensor, out: Optional[List[torch.Tensor]] = None):
+        """fp32 gradients of sum(dy * forward(x)) with respect to every parameter tensor (the layer must have been
+        created with TN_FLAG_TRAINABLE); returns one tensor per parameter tensor, in the caller's shapes."""
+        if self._handle is None:
+            raise RuntimeError("layer was closed")
+        tokens = x.shape[0]
+        if not (x.is_cuda and x.is_contiguous() and x.dtype == self.torch_dtype and tuple(x.shape) == (tokens, self.N)
+                and dy.is_cuda and dy.is_contiguous() and dy.dtype == self.torch_dtype
+                and tuple(dy.shape) == (tokens, self.M)):
+            raise ValueError("x [tokens, N] and dy [tokens, M] must be contiguous CUDA tensors of the layer dtype")
+        if out is None:
+            out = [torch.empty(shp, dtype=torch.float32, device=x.device) for shp in self._tensor_shapes]
+        tn_linear_param_gradients(self._handle, x.data_ptr(), dy.data_ptr(), [g.data_ptr() for g in out], tokens,
+                                  torch.cuda.current_stream().cuda_stream)
+        return out
 
     def query(self, what: int) -> int:
         return tn_linear_query(self._handle, what)

@@ -37,6 +37,7 @@ namespace {
 #include "kernels/stream.hpp"
 #include "kernels/chained.hpp"
 #include "kernels/kronsum.hpp"
+#include "kernels/grad.hpp"
 
 // ---------------------------------------------------------------------------------------------
 // host side
@@ -121,6 +122,16 @@ struct tn_linear_s {
     KronGenMfmaArgs lazy_gen_mfma[2];
     size_t lazy_gen_smem[2] = {0, 0};
     void* lazy_gen_tables[2] = {nullptr, nullptr};
+    // gradients with respect to the parameter tensors (TN_FLAG_TRAINABLE)
+    bool trainable = false;
+    std::vector<DevStep> bwd;                 // per step s >= 1: the step with its tensor transposed (gives dIn_s from dOut_s)
+    int32_t* bwd_tables = nullptr;            // plain output tables of those steps
+    void* bwd_ws = nullptr;                   // saved step inputs | two gradient buffers, for bwd_chunk tokens
+    std::vector<int64_t> bwd_saved_off;       // element offset (per token block) of the saved input of step s
+    int64_t bwd_saved_elems = 0;              // per token
+    int64_t bwd_chunk = 0, bwd_ws_bytes = 0;
+    float* bwd_partial = nullptr;
+    int64_t bwd_partial_bytes = 0;
     struct ProfRec { int step; hipEvent_t start, stop; };
     std::vector<ProfRec> prof;
 };
@@ -157,6 +168,11 @@ void free_handle(tn_linear_s* h) {
         if (s.chain_bbf) (void)hipFree(s.chain_bbf);
     }
     if (h->tables) (void)hipFree(h->tables);
+    for (auto& b : h->bwd)
+        if (b.packed) (void)hipFree(b.packed);
+    if (h->bwd_tables) (void)hipFree(h->bwd_tables);
+    if (h->bwd_ws) (void)hipFree(h->bwd_ws);
+    if (h->bwd_partial) (void)hipFree(h->bwd_partial);
     if (h->pair_b1f) (void)hipFree(h->pair_b1f);
     if (h->kron_h0f) (void)hipFree(h->kron_h0f);
     if (h->kron_h1f) (void)hipFree(h->kron_h1f);
@@ -969,7 +985,7 @@ void fill_gen_dims(GenDims* g, const std::vector<tn::GatherDim>& d) {
 int prepare_lazy(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
     if (h->plan.dtype != TN_DTYPE_BF16 || h->pair || h->kron || h->small_chain) return TN_OK;
     if (desc->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_MERGE | TN_FLAG_MERGE_GROW |
-                       TN_FLAG_MERGE_HALVES | TN_FLAG_NO_LAZY_MERGE))
+                       TN_FLAG_MERGE_HALVES | TN_FLAG_NO_LAZY_MERGE | TN_FLAG_TRAINABLE))
         return TN_OK;
     if (((desc->flags >> TN_FLAG_VARIANT_SHIFT) & 0xff) != 0) return TN_OK;      // tuning overrides: keep what they ask
     if (desc->max_tokens < kLazyMinTokens) return TN_OK;
@@ -1389,6 +1405,162 @@ void launch_pack(const PackArgs& pa, int elt, hipStream_t st) {
         hipLaunchKernelGGL(pack_kernel<float>, dim3(blocks), dim3(256), 0, st, pa);
 }
 
+// ---- gradients with respect to the parameter tensors (TN_FLAG_TRAINABLE) ----
+constexpr int64_t kMaxGradPartialBytes = int64_t(256) << 20;
+
+// Row ranges a gradient launch is split into: enough workgroups to fill the chip, at least 64 rows each, partial
+// tiles within `cap` bytes.
+int grad_splits(const tn_linear_s* h, const tn::Step& p, int64_t rows, int64_t cap) {
+    const int64_t tiles = ((p.C + 63) / 64) * ((p.K + 63) / 64);
+    int64_t n = std::max<int64_t>(1, (4 * int64_t(h->num_cus) + tiles - 1) / tiles);
+    n = std::min<int64_t>(n, std::max<int64_t>(1, rows / 64));
+    n = std::min<int64_t>(n, std::max<int64_t>(1, cap / (p.C * p.K * 4)));
+    return int(std::min<int64_t>(n, 65535));
+}
+
+int prepare_backward(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
+    const size_t n = h->steps.size();
+    if (!h->plan.merges.empty()) return TN_ERR_UNSUPPORTED;
+    h->bwd.resize(n);
+    std::vector<int32_t> tab;
+    std::vector<size_t> off(n, 0);
+    for (size_t s = 1; s < n; ++s) {
+        const tn::Step& f = h->steps[s].plan;
+        if (!f.a_plain) return TN_ERR_UNSUPPORTED;      // only a first step gathers
+        off[s] = tab.size();
+        for (int64_t r = 0; r < f.R; ++r) tab.push_back(int32_t(r * f.K));
+        for (int64_t k = 0; k < f.K; ++k) tab.push_back(int32_t(k));
+    }
+    if (hipMalloc(reinterpret_cast<void**>(&h->bwd_tables), std::max<size_t>(1, tab.size()) * sizeof(int32_t)) != hipSuccess)
+        return TN_ERR_ALLOC;
+    if (hipMemcpyAsync(h->bwd_tables, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return TN_ERR_HIP;
+    for (size_t s = 1; s < n; ++s) {
+        const DevStep& fs = h->steps[s];
+        const tn::Step& f = fs.plan;
+        DevStep& b = h->bwd[s];
+        b.plan.tensor = f.tensor;
+        b.plan.slot = f.slot;
+        b.plan.R = f.R;
+        b.plan.K = f.C;
+        b.plan.C = f.K;
+        b.plan.a_plain = false;                         // dOut is read through the forward step's scatter tables
+        b.plan.a_tok_stride = f.c_tok_stride;
+        b.plan.c_tok_stride = f.a_tok_stride;
+        b.plan.c_vec = (f.K % 8 == 0) ? 8 : 1;
+        b.plan.r_vec = 1;
+        b.plan.kdims = f.cdims;
+        b.plan.cdims = f.kdims;
+        b.plan.trace_extent = f.trace_extent;
+        b.plan.trace_stride = f.trace_stride;
+        b.plan.flops = f.flops;
+        b.arow = fs.crow;
+        b.acol = fs.ccol;
+        b.crow = h->bwd_tables + off[s];
+        b.ccol = b.crow + f.R;
+        choose_variant(h, &b, desc->flags);
+        const int64_t bytes = int64_t(b.Cp) * b.Kp * h->elt;
+        if (hipMalloc(&b.packed, size_t(bytes)) != hipSuccess) return TN_ERR_ALLOC;
+        h->packed_bytes += bytes;
+        PackArgs pa;
+        memset(&pa, 0, sizeof(pa));
+        pa.src = desc->tensors[f.slot];
+        pa.dst = b.packed;
+        pa.K = int32_t(b.plan.K);
+        pa.Kp = b.Kp;
+        pa.C = int32_t(b.plan.C);
+        pa.Cp = b.Cp;
+        fill_pack_dims(&pa, b.plan.kdims, b.plan.cdims);
+        pa.trace_extent = f.trace_extent;
+        pa.trace_stride = f.trace_stride;
+        launch_pack(pa, h->elt, st);
+        if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    }
+    // workspace of a backward pass: the saved inputs of steps 1 .. n-1 and two gradient buffers
+    h->bwd_saved_off.assign(n, 0);
+    int64_t saved = 0;
+    for (size_t s = 1; s < n; ++s) {
+        h->bwd_saved_off[s] = saved;
+        saved += (h->steps[s].plan.a_tok_stride + 127) & ~int64_t(127);
+    }
+    h->bwd_saved_elems = saved;
+    const int64_t dbuf = (h->plan.max_intermediate + 127) & ~int64_t(127);
+    const int64_t per_token = (saved + 2 * dbuf) * h->elt;
+    int64_t max_r = 1;
+    for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
+    const int64_t limit = desc->workspace_limit_bytes > 0 ? desc->workspace_limit_bytes : kDefaultWorkspaceBytes;
+    int64_t chunk = h->max_tokens;
+    if (per_token > 0) chunk = std::min<int64_t>(chunk, std::max<int64_t>(1, limit / per_token));
+    chunk = std::max<int64_t>(1, std::min<int64_t>(chunk, ((int64_t(1) << 31) - 1024) / max_r));
+    h->bwd_chunk = chunk;
+    h->bwd_ws_bytes = std::max<int64_t>(256, chunk * per_token);
+    if (hipMalloc(&h->bwd_ws, size_t(h->bwd_ws_bytes)) != hipSuccess) return TN_ERR_ALLOC;
+    int64_t need = 0;
+    for (const auto& s : h->steps)
+        need = std::max(need, int64_t(grad_splits(h, s.plan, chunk * s.plan.R, kMaxGradPartialBytes)) * s.plan.C * s.plan.K * 4);
+    h->bwd_partial_bytes = need;
+    if (hipMalloc(reinterpret_cast<void**>(&h->bwd_partial), size_t(need)) != hipSuccess) return TN_ERR_ALLOC;
+    h->trainable = true;
+    return TN_OK;
+}
+
+// dP of one step from dOut and the step's saved input, into the caller's tensor.
+int launch_param_gradient(const tn_linear_s* h, const DevStep& s, const void* dOut, const void* In, float* grad,
+                          int64_t grad_elems, int64_t tokens, bool accumulate, hipStream_t st) {
+    const tn::Step& p = s.plan;
+    const int64_t rows = tokens * p.R;
+    const int n_split = grad_splits(h, p, rows, h->bwd_partial_bytes);
+    if (int64_t(n_split) * p.C * p.K * 4 > h->bwd_partial_bytes) return TN_ERR_UNSUPPORTED;
+    GradArgs a;
+    a.dOut = dOut;
+    a.In = In;
+    a.partial = h->bwd_partial;
+    a.crow = s.crow;
+    a.ccol = s.ccol;
+    a.arow = s.arow;
+    a.acol = s.acol;
+    a.c_tok_stride = p.c_tok_stride;
+    a.a_tok_stride = p.a_tok_stride;
+    a.total_rows = uint32_t(rows);
+    a.R = uint32_t(p.R);
+    a.K = int32_t(p.K);
+    a.C = int32_t(p.C);
+    a.rows_per_split = uint32_t((rows + n_split - 1) / n_split);
+    dim3 grid(uint32_t((p.C + 63) / 64), uint32_t((p.K + 63) / 64), uint32_t(n_split));
+    if (grid.y > 65535) return TN_ERR_UNSUPPORTED;
+    if (h->elt == 2)
+        hipLaunchKernelGGL(grad_param_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(grad_param_kernel<float>, grid, dim3(256), 0, st, a);
+    if (p.trace_extent > 1 && !accumulate)
+        hipLaunchKernelGGL(grad_fill_kernel, dim3(uint32_t(std::min<int64_t>((grad_elems + 255) / 256, 4096))), dim3(256), 0, st,
+                           grad, grad_elems);
+    GradOutArgs o;
+    memset(&o, 0, sizeof(o));
+    o.partial = h->bwd_partial;
+    o.grad = grad;
+    o.C = int32_t(p.C);
+    o.K = int32_t(p.K);
+    o.n_split = n_split;
+    o.accumulate = accumulate ? 1 : 0;
+    o.nk = int32_t(p.kdims.size());
+    o.nc = int32_t(p.cdims.size());
+    for (int j = 0; j < o.nk; ++j) {
+        o.kext[j] = p.kdims[size_t(j)].extent;
+        o.kstr[j] = p.kdims[size_t(j)].stride;
+    }
+    for (int j = 0; j < o.nc; ++j) {
+        o.cext[j] = p.cdims[size_t(j)].extent;
+        o.cstr[j] = p.cdims[size_t(j)].stride;
+    }
+    o.trace_extent = p.trace_extent;
+    o.trace_stride = p.trace_stride;
+    const int64_t total = p.C * p.K;
+    hipLaunchKernelGGL(grad_reduce_kernel, dim3(uint32_t(std::min<int64_t>((total + 255) / 256, 8192))), dim3(256), 0, st, o);
+    return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
 // Contract pairs of parameter tensors at create time (tn::MergeOp) with the plain FMA kernel
 // (fp32 accumulate, one rounding to the storage type). `virt` receives one device buffer per merge;
 // `temps` receives scratch buffers the caller frees once the stream has drained.
@@ -1458,7 +1630,7 @@ int materialise_merges(const tn::Plan& plan, const tn_linear_desc* desc, int elt
 
 extern "C" {
 
-int tn_linear_version(void) { return 4; }
+int tn_linear_version(void) { return 5; }
 
 const char* tn_linear_strerror(int status) {
     switch (status) {
@@ -1632,6 +1804,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         rc = prepare_lazy(h, desc, st);
         h->lazy_kept_bytes = h->packed_bytes - before;
     }
+    if (rc == TN_OK && (desc->flags & TN_FLAG_TRAINABLE)) rc = prepare_backward(h, desc, st);
     if (rc != TN_OK) {
         (void)hipStreamSynchronize(st);
         free_handle(h);
@@ -1955,6 +2128,55 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
     return TN_OK;
 }
 
+int tn_linear_param_gradients(tn_linear_t h, const void* x, const void* dy, void* const* grads, int64_t tokens,
+                              void* stream) {
+    if (!h || tokens < 0 || !grads || !h->trainable) return TN_ERR_INVALID_ARG;
+    if (tokens == 0) return TN_OK;
+    if (!x || !dy) return TN_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t n = h->steps.size();
+    Workspace w;                                   // the forward workspace serves the split-K partial sums
+    w.partial = h->partial;
+    w.partial_bytes = h->partial_bytes;
+    w.chunk_tokens = h->bwd_chunk;
+    char* base = static_cast<char*>(h->bwd_ws);
+    const int64_t dbuf = (h->plan.max_intermediate + 127) & ~int64_t(127);
+    void* dbufs[2] = {base + h->bwd_chunk * h->bwd_saved_elems * h->elt,
+                      base + h->bwd_chunk * (h->bwd_saved_elems + dbuf) * h->elt};
+    auto saved = [&](size_t s) -> void* { return base + h->bwd_chunk * h->bwd_saved_off[s] * h->elt; };
+    for (int64_t t0 = 0; t0 < tokens; t0 += h->bwd_chunk) {
+        const int64_t nt = std::min(h->bwd_chunk, tokens - t0);
+        const void* xc = static_cast<const char*>(x) + t0 * h->plan.N * h->elt;
+        // forward, one launch per step, every step's input kept
+        const void* cur = xc;
+        for (size_t s = 0; s + 1 < n; ++s) {
+            int rc = launch_step(h, w, h->steps[s], cur, saved(s + 1), nt, st);
+            if (rc != TN_OK) return rc;
+            cur = saved(s + 1);
+        }
+        // backward
+        const void* dcur = static_cast<const char*>(dy) + t0 * h->plan.M * h->elt;
+        int toggle = 0;
+        for (size_t s = n; s-- > 0;) {
+            const DevStep& fs = h->steps[s];
+            const void* in_s = s == 0 ? xc : saved(s);
+            void* g = grads[fs.plan.slot];
+            if (g) {
+                const int64_t elems = h->plan.tensors[size_t(fs.plan.tensor)].n_elems;
+                int rc = launch_param_gradient(h, fs, dcur, in_s, static_cast<float*>(g), elems, nt, t0 > 0, st);
+                if (rc != TN_OK) return rc;
+            }
+            if (s > 0) {
+                int rc = launch_step(h, w, h->bwd[s], dcur, dbufs[toggle], nt, st);
+                if (rc != TN_OK) return rc;
+                dcur = dbufs[toggle];
+                toggle ^= 1;
+            }
+        }
+    }
+    return TN_OK;
+}
+
 int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
     if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
     if (tokens == 0) return TN_OK;
@@ -2035,6 +2257,8 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
         case TN_QUERY_CHUNK_TOKENS: *value = h->chunk_tokens; return TN_OK;
         case TN_QUERY_LAZY_MIN_TOKENS: *value = h->lazy ? h->lazy_min_tokens : 0; return TN_OK;
         case TN_QUERY_LAZY_FLOPS_PER_TOKEN: *value = h->lazy ? h->lazy_plan.flops : 0; return TN_OK;
+        case TN_QUERY_BACKWARD_CHUNK_TOKENS: *value = h->trainable ? h->bwd_chunk : 0; return TN_OK;
+        case TN_QUERY_BACKWARD_WORKSPACE_BYTES: *value = h->trainable ? h->bwd_ws_bytes + h->bwd_partial_bytes : 0; return TN_OK;
         default: break;
     }
     if (what >= TN_QUERY_STEP_BASE && (what - TN_QUERY_STEP_BASE) % 10 == 5) {

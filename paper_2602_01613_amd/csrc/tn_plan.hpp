@@ -780,7 +780,8 @@ inline int make_plan(const tn_linear_desc* d, Plan* p) {
     if (rc != TN_OK) return rc;
     rc = build_steps(p, order);
     if (rc != TN_OK) return rc;
-    if (!(d->flags & TN_FLAG_NO_MERGE)) {
+    // a trainable layer keeps every parameter tensor of the caller separate: gradients are taken with respect to those
+    if (!(d->flags & (TN_FLAG_NO_MERGE | TN_FLAG_TRAINABLE))) {
         Plan q = *p;
         q.steps.clear();
         // TN_FLAG_MERGE_GROW: merges may add parameters up to a quarter of the dense matrix

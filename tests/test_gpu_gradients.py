@@ -1,0 +1,100 @@
+"""GPU parity of tn_linear_param_gradients (gradients of sum(dY * Y) with respect to every parameter tensor)
+against the fp64 oracle. Tolerance per tensor: max|g - g_ref| / max|g_ref| <= 2e-2 (bf16: intermediates and the
+back-propagated gradients are rounded to bf16 between steps) or 1e-4 (fp32: sums over tokens x rows of up to 1e5
+terms accumulated in fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import workloads as wl
+import paper_2602_01613_amd as tn
+from gpu_util import make_layer, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+GRAD_TOL = {"bf16": 2e-2, "f32": 1e-4}
+
+CASES = [
+    (tn.TN_FORMAT_TT, (2, 3, 2, 2), (2, 2, 3, 2), (1, 4, 2, 4, 1)),      # would merge at create time without the flag
+    (tn.TN_FORMAT_TT, (8, 16, 8), (8, 10, 8), (1, 32, 16, 1)),
+    (tn.TN_FORMAT_TT, (3, 4, 2), (2, 5, 3), (1, 3, 4, 1)),               # odd extents
+    (tn.TN_FORMAT_TT, (2, 3, 2, 2), (5, 2, 3, 2), (1, 2, 5, 3, 1)),      # first step gathers from x
+    (tn.TN_FORMAT_TR, (2, 3, 2), (3, 2, 2), (3, 2, 4, 3)),
+    (tn.TN_FORMAT_TR, (4, 6, 4), (6, 4, 8), (8, 16, 8, 8)),
+    (tn.TN_FORMAT_TR, (5,), (7,), (3, 3)),                               # a ring of one core: gradient on the bond diagonal
+    (tn.TN_FORMAT_TUCKER, (4, 5), (3, 6), (2, 3, 2, 4)),
+    (tn.TN_FORMAT_TUCKER, (16, 24), (8, 40), (8, 16, 8, 16)),
+    (tn.TN_FORMAT_TUCKER, (3, 2, 4), (5,), (2, 2, 3, 4)),
+    (tn.TN_FORMAT_DENSE, (200,), (136,), ()),
+]
+
+
+def _check(spec, ts, tokens, seed, flags=0, max_tokens=None, workspace_limit_bytes=0):
+    rng = np.random.default_rng(seed)
+    x = wl.round_to_dtype(rng.standard_normal((tokens, spec.N)), spec.dtype)
+    dy = wl.round_to_dtype(rng.standard_normal((tokens, spec.M)), spec.dtype)
+    layer = make_layer(spec, ts, max_tokens or tokens, workspace_limit_bytes, flags=tn.TN_FLAG_TRAINABLE | flags)
+    assert layer.query(tn.TN_QUERY_NUM_MERGES) == 0
+    grads = layer.param_gradients(to_dev(x, spec.dtype), to_dev(dy, spec.dtype))
+    torch.cuda.synchronize()
+    again = layer.param_gradients(to_dev(x, spec.dtype), to_dev(dy, spec.dtype))
+    torch.cuda.synchronize()
+    ref = O.param_gradients(spec.format, ts, x, dy, n_out_modes=len(spec.out_modes))
+    errs = []
+    for g, g2, r in zip(grads, again, ref):
+        assert tuple(g.shape) == r.shape
+        assert torch.equal(g, g2)                                        # fixed-order sums: same bits
+        errs.append(O.rel_max_err(to_host(g), r))
+    # the forward of a trainable layer is the ordinary forward
+    y = to_host(layer(to_dev(x, spec.dtype)))
+    assert O.rel_max_err(y, O.forward(spec.format, ts, x, n_out_modes=len(spec.out_modes))) <= (2e-2 if spec.dtype == "bf16" else 1e-5)
+    layer.close()
+    return errs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_param_gradients_small_shapes(case, dtype):
+    fmt, om, im, rk = CASES[case]
+    spec = wl.TNSpec(fmt, dtype, tuple(om), tuple(im), tuple(rk))
+    rng = np.random.default_rng(2000 + case)
+    ts = [wl.round_to_dtype(rng.standard_normal(s) / np.sqrt(max(1, s[-1])), dtype) for s in spec.tensor_shapes()]
+    for tokens in (1, 17, 130):
+        errs = _check(spec, ts, tokens, 3000 + case * 7 + tokens)
+        assert max(errs) <= GRAD_TOL[dtype], (case, tokens, errs)
+
+
+def test_param_gradients_in_several_passes():
+    """More tokens than the backward workspace holds: passes whose gradients are added."""
+    spec = wl.TNSpec(tn.TN_FORMAT_TT, "bf16", (8, 16, 8), (8, 10, 8), (1, 32, 16, 1))
+    rng = np.random.default_rng(2100)
+    ts = [wl.round_to_dtype(rng.standard_normal(s) / np.sqrt(s[-1]), "bf16") for s in spec.tensor_shapes()]
+    layer = make_layer(spec, ts, 100, 1 << 20, flags=tn.TN_FLAG_TRAINABLE)
+    chunk = layer.query(tn.TN_QUERY_BACKWARD_CHUNK_TOKENS)
+    layer.close()
+    assert 0 < chunk < 100
+    errs = _check(spec, ts, 100, 2101, workspace_limit_bytes=1 << 20)
+    assert max(errs) <= GRAD_TOL["bf16"], errs
+
+
+@pytest.mark.parametrize("i", [0, 1, 2, 3])
+def test_param_gradients_baseline_configs(i):
+    """The four single-layer workloads at 64 tokens (the ring at 8: its intermediates are 26 MB per token)."""
+    spec, _ = wl.baseline_spec(i)
+    ts = wl.make_tensors(spec, i)
+    tokens = 8 if i == 3 else (16 if i == 0 else 64)
+    errs = _check(spec, ts, tokens, 2200 + i)
+    print(f"workload {i}: gradient rel errs {['%.2e' % e for e in errs]}", flush=True)
+    assert max(errs) <= GRAD_TOL[spec.dtype], errs
+
+
+def test_param_gradients_need_a_trainable_handle():
+    spec, _ = wl.baseline_spec(0)
+    ts = wl.make_tensors(spec, 0)
+    layer = make_layer(spec, ts, 4)
+    x = to_dev(wl.make_x(spec, 4, 0), "f32")
+    with pytest.raises(tn.TNLinearError) as e:
+        layer.param_gradients(x, x)
+    assert e.value.status == -1
+    layer.close()
