@@ -16,4 +16,6 @@ from .tn_oracle import (  # noqa: F401
     tt_svd,
     rel_max_err,
     param_gradients,
+    mxfp4_quantize,
+    mxfp4_dequantized,
 )

@@ -36,7 +36,9 @@ matrix products taken with numpy and with the nested-loop evaluator; a dense
 weight handed over as a [1, M, N, 1] core equals the plain matrix; the parameter
 gradients (param_gradients) equal, entry by entry, the loss evaluated with that
 tensor replaced by a unit tensor (the loss is linear in each tensor alone), and
-central finite differences of the loss.
+central finite differences of the loss; the MXFP4 quantiser (mxfp4_quantize)
+agrees with a brute-force nearest-value search over the code table built from the
+E2M1 bit fields, is idempotent, and keeps the block scale within (amax/8, amax/4].
 """
 from __future__ import annotations
 
@@ -260,6 +262,47 @@ def param_gradients(fmt: int, tensors: Sequence[np.ndarray], x: np.ndarray, dy: 
         g = np.einsum(*operands, labels[k], optimize="greedy")
         grads.append(np.ascontiguousarray(g))
     return grads
+
+
+# ---- 4-bit quantisation of the parameter tensors (Section 6 names 4-bit quantisation of the cores as the next
+#      step and gives no scheme; the reading taken is the OCP microscaling format MXFP4, weight-only) -------------
+MX_BLOCK = 32
+# the eight magnitudes an E2M1 code (2 exponent bits with bias 1, 1 mantissa bit) can take, in code order
+E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+def mxfp4_quantize(t: np.ndarray):
+    """MXFP4 quantisation of one tensor: (codes, scale exponents, dequantised tensor).
+
+    The tensor is cut into blocks of 32 consecutive elements of its row-major flattening (the last block may be
+    shorter). A block shares the scale X = 2^(floor(log2(max|v|)) - 2), clamped to the E8M0 range 2^-127 .. 2^127
+    (an all-zero block takes 2^-127); an element is v / X rounded to the nearest E2M1 value, ties to the value with
+    an even mantissa bit, saturating at +-6. codes: uint8, bit 3 = sign, bits 0..2 = index into E2M1_GRID;
+    exponents: int16, one per block; dequantised = sign * grid[code] * X, in the tensor's shape (float64, exact).
+    """
+    v = _f64(t).reshape(-1)
+    n = v.size
+    nb = (n + MX_BLOCK - 1) // MX_BLOCK
+    pad = np.zeros(nb * MX_BLOCK)
+    pad[:n] = v
+    blocks = pad.reshape(nb, MX_BLOCK)
+    amax = np.max(np.abs(blocks), axis=1)
+    _, ex = np.frexp(amax)                              # amax = m * 2^ex, m in [0.5, 1): floor(log2 amax) = ex - 1
+    e = np.where(amax > 0, ex - 1 - 2, -127)
+    e = np.clip(e, -127, 127).astype(np.int16)
+    q = np.abs(blocks) / np.exp2(e.astype(np.float64))[:, None]
+    # nearest grid value; at a midpoint the neighbour whose mantissa bit is 0 (codes 0, 2, 4, 6)
+    code = ((q > 0.25).astype(np.uint8) + (q >= 0.75) + (q > 1.25) + (q >= 1.75) + (q > 2.5) + (q >= 3.5) + (q > 5.0))
+    code = code.astype(np.uint8)
+    sign = (blocks < 0) & (code > 0)
+    deq = np.where(sign, -1.0, 1.0) * E2M1_GRID[code] * np.exp2(e.astype(np.float64))[:, None]
+    codes = (code | (sign.astype(np.uint8) << 3)).reshape(-1)[:n]
+    return codes, e, deq.reshape(-1)[:n].reshape(np.shape(t))
+
+
+def mxfp4_dequantized(tensors: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Every tensor replaced by its MXFP4 quantisation, dequantised: what a layer with 4-bit tensors applies."""
+    return [mxfp4_quantize(t)[2] for t in tensors]
 
 
 def brute_force_weight(fmt: int, tensors: Sequence[np.ndarray], n_out_modes: int | None = None) -> np.ndarray:

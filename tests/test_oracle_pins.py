@@ -431,3 +431,56 @@ def test_param_gradient_of_a_dense_layer_is_dyT_x():
     parts = [O.param_gradients(TT, ts, x[a:b], dy[a:b]) for a, b in ((0, 2), (2, 6))]
     for k in range(2):
         np.testing.assert_allclose(whole[k], parts[0][k] + parts[1][k], atol=1e-12)
+
+
+# ---- MXFP4 quantiser: against the format's bit-field definition by brute force, plus invariants ------------------
+def _e2m1_values():
+    """The 16 values of a 4-bit E2M1 code from its fields: sign, 2 exponent bits (bias 1), 1 mantissa bit."""
+    vals = []
+    for code in range(16):
+        s, e, m = code >> 3, (code >> 1) & 3, code & 1
+        mag = (m / 2.0) if e == 0 else (1.0 + m / 2.0) * 2.0 ** (e - 1)
+        vals.append(-mag if s else mag)
+    return np.array(vals)
+
+
+def test_mxfp4_codes_are_nearest_e2m1_values_ties_to_even():
+    rng = np.random.default_rng(80)
+    vals = _e2m1_values()
+    # one block whose maximum is exactly 4 * 2^e pins the scale to 2^e... use 7.5 (scale 1: floor(log2 7.5) - 2 = 0)
+    probes = np.concatenate([rng.uniform(-7.4, 7.4, 1000), [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, -0.25, -2.5, -5.0, 0.0,
+                                                            6.0, 6.9, -6.9, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0]])
+    for start in range(0, probes.size, 31):
+        chunk = np.concatenate([probes[start:start + 31], [7.5]])          # amax 7.5 -> X = 1
+        codes, e, deq = O.mxfp4_quantize(chunk)
+        assert e.tolist() == [0]
+        for v, c, d in zip(chunk, codes, deq):
+            mags = np.abs(vals[:8])
+            dist = np.abs(abs(v) - mags)
+            best = np.flatnonzero(dist == dist.min())
+            want = best[0] if len(best) == 1 else [b for b in best if b % 2 == 0][0]     # tie: even mantissa bit
+            assert (c & 7) == want, (v, c)
+            assert d == (np.sign(v) if want else 1.0) * mags[want] or (want == 0 and d == 0)
+            assert (c >> 3) == (1 if (v < 0 and want) else 0)
+
+
+def test_mxfp4_scale_and_invariants():
+    rng = np.random.default_rng(81)
+    t = rng.standard_normal((7, 45)) * np.exp2(rng.integers(-20, 20, size=(7, 1)))      # 315 elements: a short last block
+    codes, e, deq = O.mxfp4_quantize(t)
+    assert codes.shape == (315,) and e.shape == (10,) and deq.shape == t.shape
+    flat = np.abs(t).reshape(-1)
+    for b in range(10):
+        amax = flat[32 * b:32 * b + 32].max()
+        x = 2.0 ** int(e[b])
+        assert amax / 8 < x <= amax / 4                                    # amax / X in [4, 8)
+        assert np.all(np.abs(deq.reshape(-1)[32 * b:32 * b + 32]) <= 6 * x)
+        assert np.max(np.abs(deq.reshape(-1)[32 * b:32 * b + 32] - t.reshape(-1)[32 * b:32 * b + 32])) <= 2 * x
+    # quantising what was dequantised changes nothing
+    c2, e2, d2 = O.mxfp4_quantize(deq)
+    np.testing.assert_array_equal(d2, deq)
+    # zero blocks and the dequantised values are exact in bf16 (three significant bits)
+    cz, ez, dz = O.mxfp4_quantize(np.zeros(40))
+    assert not cz.any() and ez.tolist() == [-127, -127] and not dz.any()
+    np.testing.assert_array_equal(wl.round_to_dtype(deq, "bf16"), deq)
+    assert [a.shape for a in O.mxfp4_dequantized([t, t[:2]])] == [(7, 45), (2, 45)]
