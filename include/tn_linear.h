@@ -69,6 +69,15 @@ extern "C" {
                                        the gradient of the forward pass with respect to its input, which the
                                        fine-tuning of the factors (Section 3.4) back-propagates through every
                                        layer. TN_QUERY_IN_FEATURES / OUT_FEATURES then report M / N. */
+#define TN_FLAG_QUANT_MXFP4 (1 << 26)    /* 4-bit tensors (Section 6: 4-bit quantisation of the cores; the paper gives no scheme,
+                                       the one taken is the OCP microscaling format MXFP4, weight-only): at create every
+                                       tensor of the caller is quantised in blocks of 32 consecutive elements of its
+                                       row-major flattening (last block shorter): shared scale 2^(floor(log2 max|v|) - 2)
+                                       (E8M0 exponent, clamped to -127..127, -127 for a zero block), element = v / scale
+                                       rounded to the nearest of 0, 0.5, 1, 1.5, 2, 3, 4, 6 (ties to an even mantissa bit,
+                                       saturating) with a sign. The layer then applies the DEQUANTISED tensors (exact in
+                                       bf16) and keeps codes and exponents (tn_linear_quantized_tensor,
+                                       TN_QUERY_QUANT_BYTES). bf16 layers only; not with TN_FLAG_TRAINABLE. */
 #define TN_FLAG_TRAINABLE (1 << 25)      /* the layer can also give the gradients of a loss with respect to its tensors
                                        (tn_linear_param_gradients, Section 3.4): every parameter tensor of the caller
                                        stays separate (as with TN_FLAG_NO_MERGE; no lazily merged plan either) and the
@@ -122,6 +131,7 @@ extern "C" {
 #define TN_QUERY_LAZY_FLOPS_PER_TOKEN 13 /* handle only: FLOPs per token of that plan (0 if none) */
 #define TN_QUERY_BACKWARD_CHUNK_TOKENS 14 /* handle only: tokens per pass of tn_linear_param_gradients (0: not trainable) */
 #define TN_QUERY_BACKWARD_WORKSPACE_BYTES 15 /* handle only: device memory held for those passes */
+#define TN_QUERY_QUANT_BYTES       16   /* handle only: bytes of the 4-bit codes and block exponents of all tensors (0: not quantised) */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=
@@ -248,6 +258,15 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
  */
 int tn_linear_param_gradients(tn_linear_t h, const void* x, const void* dy, void* const* grads, int64_t tokens,
                               void* stream);
+
+/*
+ * The 4-bit form of tensor `slot` of a layer created with TN_FLAG_QUANT_MXFP4, copied on `stream`:
+ *   codes      DEVICE, ceil(n / 2) bytes: element 2i in the low nibble of byte i, 2i + 1 in the high one; a nibble is
+ *              sign (bit 3) and the index of its magnitude in 0, 0.5, 1, 1.5, 2, 3, 4, 6 (bits 0..2)
+ *   exponents  DEVICE, ceil(n / 32) signed bytes: block b scales elements 32b .. 32b + 31 by 2^exponents[b]
+ * n is the element count of desc.tensors[slot]. Either pointer may be NULL.
+ */
+int tn_linear_quantized_tensor(tn_linear_t h, int32_t slot, void* codes, void* exponents, void* stream);
 
 /*
  * tn_linear_forward for callers that cannot allocate and want no workspace tied to the handle: code under

@@ -31,6 +31,7 @@ TN_FLAG_MERGE_HALVES = 1 << 22
 TN_FLAG_SCALAR_GENERATE = 1 << 23
 TN_FLAG_NO_DECODE_FUSION = 1 << 24
 TN_FLAG_TRAINABLE = 1 << 25
+TN_FLAG_QUANT_MXFP4 = 1 << 26
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -47,6 +48,7 @@ TN_QUERY_LAZY_MIN_TOKENS = 12
 TN_QUERY_LAZY_FLOPS_PER_TOKEN = 13
 TN_QUERY_BACKWARD_CHUNK_TOKENS = 14
 TN_QUERY_BACKWARD_WORKSPACE_BYTES = 15
+TN_QUERY_QUANT_BYTES = 16
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (
@@ -55,6 +57,7 @@ EXPORTED_SYMBOLS = (
     "tn_linear_forward_scratch",
     "tn_linear_forward2",
     "tn_linear_param_gradients",
+    "tn_linear_quantized_tensor",
     "tn_linear_destroy",
     "tn_linear_query",
     "tn_linear_plan_query",
@@ -123,6 +126,9 @@ def load_library():
     lib.tn_linear_param_gradients.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64, ctypes.c_void_p]
     lib.tn_linear_param_gradients.restype = ctypes.c_int
+    lib.tn_linear_quantized_tensor.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p]
+    lib.tn_linear_quantized_tensor.restype = ctypes.c_int
     lib.tn_linear_destroy.argtypes = [ctypes.c_void_p]
     lib.tn_linear_destroy.restype = ctypes.c_int
     lib.tn_linear_query.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
@@ -250,6 +256,12 @@ def tn_linear_param_gradients(handle: int, x_ptr: int, dy_ptr: int, grad_ptrs: S
         raise TNLinearError(rc, "tn_linear_param_gradients")
 
 
+def tn_linear_quantized_tensor(handle: int, slot: int, codes_ptr, exps_ptr, stream) -> None:
+    rc = load_library().tn_linear_quantized_tensor(handle, int(slot), codes_ptr, exps_ptr, stream)
+    if rc != 0:
+        raise TNLinearError(rc, "tn_linear_quantized_tensor")
+
+
 def tn_linear_destroy(handle: Optional[int]) -> None:
     rc = load_library().tn_linear_destroy(handle)
     if rc != 0:
@@ -345,6 +357,17 @@ class TNLinear:
         tn_linear_param_gradients(self._handle, x.data_ptr(), dy.data_ptr(), [g.data_ptr() for g in out], tokens,
                                   torch.cuda.current_stream().cuda_stream)
         return out
+
+    def quantized_tensor(self, slot: int):
+        """(codes uint8 [ceil(n/2)], exponents int8 [ceil(n/32)]) of tensor `slot` of a TN_FLAG_QUANT_MXFP4 layer."""
+        n = 1
+        for e in self._tensor_shapes[slot]:
+            n *= e
+        codes = torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda")
+        exps = torch.empty((n + 31) // 32, dtype=torch.int8, device="cuda")
+        tn_linear_quantized_tensor(self._handle, slot, codes.data_ptr(), exps.data_ptr(),
+                                   torch.cuda.current_stream().cuda_stream)
+        return codes, exps
 
     def query(self, what: int) -> int:
         return tn_linear_query(self._handle, what)

@@ -33,6 +33,7 @@ namespace {
 
 #include "kernels/common.hpp"
 #include "kernels/pack.hpp"
+#include "kernels/quant.hpp"
 #include "kernels/tiled.hpp"
 #include "kernels/stream.hpp"
 #include "kernels/chained.hpp"
@@ -122,6 +123,11 @@ struct tn_linear_s {
     KronGenMfmaArgs lazy_gen_mfma[2];
     size_t lazy_gen_smem[2] = {0, 0};
     void* lazy_gen_tables[2] = {nullptr, nullptr};
+    // 4-bit form of the caller's tensors (TN_FLAG_QUANT_MXFP4): packed codes and block exponents per tensor
+    std::vector<void*> quant_codes, quant_exps;
+    std::vector<int64_t> quant_elems;
+    int64_t quant_bytes = 0;
+    std::vector<void*> create_temps;          // device buffers that only live until create returns
     // gradients with respect to the parameter tensors (TN_FLAG_TRAINABLE)
     bool trainable = false;
     std::vector<DevStep> bwd;                 // per step s >= 1: the step with its tensor transposed (gives dIn_s from dOut_s)
@@ -168,6 +174,12 @@ void free_handle(tn_linear_s* h) {
         if (s.chain_bbf) (void)hipFree(s.chain_bbf);
     }
     if (h->tables) (void)hipFree(h->tables);
+    for (void* v : h->quant_codes)
+        if (v) (void)hipFree(v);
+    for (void* v : h->quant_exps)
+        if (v) (void)hipFree(v);
+    for (void* v : h->create_temps)
+        if (v) (void)hipFree(v);
     for (auto& b : h->bwd)
         if (b.packed) (void)hipFree(b.packed);
     if (h->bwd_tables) (void)hipFree(h->bwd_tables);
@@ -1630,7 +1642,7 @@ int materialise_merges(const tn::Plan& plan, const tn_linear_desc* desc, int elt
 
 extern "C" {
 
-int tn_linear_version(void) { return 5; }
+int tn_linear_version(void) { return 6; }
 
 const char* tn_linear_strerror(int status) {
     switch (status) {
@@ -1668,8 +1680,13 @@ int tn_linear_plan_query(const tn_linear_desc* desc, int32_t what, int64_t* valu
     return plan_value(p, what, value);
 }
 
-int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
-    if (!out || !desc || !desc->tensors) return TN_ERR_INVALID_ARG;
+int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
+    if (!out || !desc_in || !desc_in->tensors) return TN_ERR_INVALID_ARG;
+    tn_linear_desc eff = *desc_in;             // the description create works with: tensors may be replaced below
+    const tn_linear_desc* desc = &eff;
+    std::vector<const void*> eff_tensors;
+    if ((desc->flags & TN_FLAG_QUANT_MXFP4) && (desc->dtype != TN_DTYPE_BF16 || (desc->flags & TN_FLAG_TRAINABLE)))
+        return TN_ERR_INVALID_ARG;
     tn_linear_s* h = new (std::nothrow) tn_linear_s;
     if (!h) return TN_ERR_ALLOC;
     int rc = tn::make_plan(desc, &h->plan);
@@ -1706,6 +1723,41 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
     h->elt = desc->dtype == TN_DTYPE_BF16 ? 2 : 4;
     h->max_tokens = desc->max_tokens;
     h->flags = desc->flags;
+    if (desc->flags & TN_FLAG_QUANT_MXFP4) {
+        // quantise every tensor; everything below (merging, packing, lazily merged plans) sees the dequantised copies
+        for (int i = 0; i < desc->n_tensors; ++i) {
+            const int64_t n = tn::caller_tensor_elems(desc, i);
+            void *codes = nullptr, *exps = nullptr, *deq = nullptr;
+            if (n <= 0 || hipMalloc(&codes, size_t((n + 1) / 2)) != hipSuccess) {
+                free_handle(h);
+                return TN_ERR_ALLOC;
+            }
+            h->quant_codes.push_back(codes);
+            if (hipMalloc(&exps, size_t((n + 31) / 32)) != hipSuccess) {
+                free_handle(h);
+                return TN_ERR_ALLOC;
+            }
+            h->quant_exps.push_back(exps);
+            if (hipMalloc(&deq, size_t(n) * 2) != hipSuccess) {
+                free_handle(h);
+                return TN_ERR_ALLOC;
+            }
+            h->create_temps.push_back(deq);
+            h->quant_elems.push_back(n);
+            h->quant_bytes += (n + 1) / 2 + (n + 31) / 32;
+            const int64_t blocks = (n + 31) / 32;
+            hipLaunchKernelGGL(mxfp4_quantize_kernel, dim3(uint32_t(std::min<int64_t>((blocks + 255) / 256, 16384))), dim3(256), 0,
+                               st, static_cast<const bf16_t*>(desc_in->tensors[i]), n, static_cast<unsigned char*>(codes),
+                               static_cast<signed char*>(exps), static_cast<bf16_t*>(deq));
+            eff_tensors.push_back(deq);
+        }
+        if (hipGetLastError() != hipSuccess) {
+            (void)hipStreamSynchronize(st);
+            free_handle(h);
+            return TN_ERR_HIP;
+        }
+        eff.tensors = eff_tensors.data();
+    }
     h->steps.resize(h->plan.steps.size());
     std::vector<void*> virt, temps;     // merged tensors and scratch: freed before create returns
     auto release_temps = [&]() {
@@ -1941,6 +1993,8 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc) {
         free_handle(h);
         return TN_ERR_HIP;
     }
+    for (void* v : h->create_temps) (void)hipFree(v);
+    h->create_temps.clear();
     *out = h;
     return TN_OK;
 }
@@ -2177,6 +2231,18 @@ int tn_linear_param_gradients(tn_linear_t h, const void* x, const void* dy, void
     return TN_OK;
 }
 
+int tn_linear_quantized_tensor(tn_linear_t h, int32_t slot, void* codes, void* exponents, void* stream) {
+    if (!h || slot < 0 || size_t(slot) >= h->quant_codes.size()) return TN_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n = h->quant_elems[size_t(slot)];
+    if (codes && hipMemcpyAsync(codes, h->quant_codes[size_t(slot)], size_t((n + 1) / 2), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return TN_ERR_HIP;
+    if (exponents &&
+        hipMemcpyAsync(exponents, h->quant_exps[size_t(slot)], size_t((n + 31) / 32), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return TN_ERR_HIP;
+    return TN_OK;
+}
+
 int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
     if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
     if (tokens == 0) return TN_OK;
@@ -2257,6 +2323,7 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
         case TN_QUERY_CHUNK_TOKENS: *value = h->chunk_tokens; return TN_OK;
         case TN_QUERY_LAZY_MIN_TOKENS: *value = h->lazy ? h->lazy_min_tokens : 0; return TN_OK;
         case TN_QUERY_LAZY_FLOPS_PER_TOKEN: *value = h->lazy ? h->lazy_plan.flops : 0; return TN_OK;
+        case TN_QUERY_QUANT_BYTES: *value = h->quant_bytes; return TN_OK;
         case TN_QUERY_BACKWARD_CHUNK_TOKENS: *value = h->trainable ? h->bwd_chunk : 0; return TN_OK;
         case TN_QUERY_BACKWARD_WORKSPACE_BYTES: *value = h->trainable ? h->bwd_ws_bytes + h->bwd_partial_bytes : 0; return TN_OK;
         default: break;

@@ -235,6 +235,28 @@ inline int build_network_forward(const tn_linear_desc* d, Plan* p) {
     return TN_OK;
 }
 
+// Element count of the caller's tensor `slot` (canonical layouts of tn_linear_desc); 0 for a slot that does not exist.
+inline int64_t caller_tensor_elems(const tn_linear_desc* d, int slot) {
+    int64_t M = 1, N = 1;
+    for (int i = 0; i < d->n_out_modes; ++i) M *= d->out_modes[i];
+    for (int i = 0; i < d->n_in_modes; ++i) N *= d->in_modes[i];
+    if (slot < 0) return 0;
+    if (d->format == TN_FORMAT_DENSE) return slot == 0 ? M * N : 0;
+    if (d->format == TN_FORMAT_TT || d->format == TN_FORMAT_TR) {
+        if (slot >= d->n_out_modes) return 0;
+        return int64_t(d->ranks[slot]) * d->out_modes[slot] * d->in_modes[slot] * d->ranks[slot + 1];
+    }
+    const int p = d->n_out_modes, q = d->n_in_modes;
+    if (slot == 0) {
+        int64_t n = 1;
+        for (int i = 0; i < p + q; ++i) n *= d->ranks[i];
+        return n;
+    }
+    if (slot <= p) return int64_t(d->out_modes[slot - 1]) * d->ranks[slot - 1];
+    if (slot <= p + q) return int64_t(d->in_modes[slot - 1 - p]) * d->ranks[slot - 1];
+    return 0;
+}
+
 // The network of the layer: y = W x, or with TN_FLAG_TRANSPOSE y = W^T x, which is the same network
 // with the roles of the out-modes and the in-modes exchanged (the activation then carries the
 // out-modes). The second form is the gradient of the first with respect to its input.

@@ -391,6 +391,6 @@ def test_library_exports_every_declared_symbol():
     lib = tn.load_library()
     for name in declared:
         assert hasattr(lib, name), name
-    assert tn.tn_linear_version() == 5
+    assert tn.tn_linear_version() == 6
     assert tn.tn_linear_strerror(0) == "success"
     assert "invalid" in tn.tn_linear_strerror(-1)
