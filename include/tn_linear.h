@@ -52,23 +52,28 @@ extern "C" {
 #define TN_DTYPE_F32   0    /* fp32 storage, fp32 FMA arithmetic, fp32 intermediates */
 #define TN_DTYPE_BF16  1    /* bf16 storage, bf16 MFMA with fp32 accumulate, bf16 intermediates */
 
-/* desc.flags (bit 3 is unused) */
-#define TN_FLAG_SCALAR_KERNELS  1   /* run every contraction step on the plain FMA kernel (debug aid) */
+/*
+ * desc.flags, part 1: what the layer is and how much memory it may trade for speed. These are the interface.
+ */
 #define TN_FLAG_NO_MERGE        2   /* keep every parameter tensor separate: do not contract adjacent
                                        tensors into one at create time even where that is free */
-#define TN_FLAG_NO_SPLIT_K      4   /* never use the split-K kernel for small launches (tuning/debug aid) */
 #define TN_FLAG_MERGE_GROW     16   /* trade memory for speed: also contract parameter tensors at create time
                                        when that ADDS parameters, as long as the layer stays under a quarter
                                        of the dense matrix (e.g. a ring of 4 cores becomes two half-rings) */
-#define TN_FLAG_NO_PAIR_CHAIN   32   /* never run a two-step plan as one chained launch (see TN_QUERY_PAIR_CHAINABLE):
-                                       always two launches with the intermediate in the workspace */
-#define TN_FLAG_NO_CHAIN2       64   /* never run two small transposing steps (Tucker factor products) as one
-                                       chained launch: always one launch per step */
+#define TN_FLAG_MERGE_HALVES  (1 << 22)  /* like TN_FLAG_MERGE_GROW, but whatever the size (up to 1e9 elements): contract
+                                       parameter tensors at create time until two are left (a ring of four cores
+                                       becomes two half rings), and keep them. This is the plan large calls of a
+                                       default layer run on with the merged tensors rebuilt per call
+                                       (TN_QUERY_LAZY_MIN_TOKENS); with this flag every call runs on it. */
 #define TN_FLAG_TRANSPOSE      128   /* apply W^T instead of W: X is [tokens, M], Y is [tokens, N],
                                        Y[t, j] = sum_i W[i, j] X[t, i]. Same tensors, same description; this is
                                        the gradient of the forward pass with respect to its input, which the
                                        fine-tuning of the factors (Section 3.4) back-propagates through every
                                        layer. TN_QUERY_IN_FEATURES / OUT_FEATURES then report M / N. */
+#define TN_FLAG_TRAINABLE (1 << 25)      /* the layer can also give the gradients of a loss with respect to its tensors
+                                       (tn_linear_param_gradients, Section 3.4): every parameter tensor of the caller
+                                       stays separate (as with TN_FLAG_NO_MERGE; no lazily merged plan either) and the
+                                       handle holds a second workspace for the saved intermediates of a backward pass */
 #define TN_FLAG_QUANT_MXFP4 (1 << 26)    /* 4-bit tensors (Section 6: 4-bit quantisation of the cores; the paper gives no scheme,
                                        the one taken is the OCP microscaling format MXFP4, weight-only): at create every
                                        tensor of the caller is quantised in blocks of 32 consecutive elements of its
@@ -78,30 +83,32 @@ extern "C" {
                                        saturating) with a sign. The layer then applies the DEQUANTISED tensors (exact in
                                        bf16) and keeps codes and exponents (tn_linear_quantized_tensor,
                                        TN_QUERY_QUANT_BYTES). bf16 layers only; not with TN_FLAG_TRAINABLE. */
-#define TN_FLAG_TRAINABLE (1 << 25)      /* the layer can also give the gradients of a loss with respect to its tensors
-                                       (tn_linear_param_gradients, Section 3.4): every parameter tensor of the caller
-                                       stays separate (as with TN_FLAG_NO_MERGE; no lazily merged plan either) and the
-                                       handle holds a second workspace for the saved intermediates of a backward pass */
-#define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* never run a chained factor pair and the wide step after it as one launch
-                                       (calls of a few tokens: the in-factor products and the core of a Tucker layer) */
+
+/*
+ * desc.flags, part 2: switches that take a kernel path away, and tuning overrides. They exist for the library's own
+ * tests and measurements (every fused or specialised path is compared with the plain one it replaces); results
+ * stay within tolerance under any of them, only speed changes. Not meant for applications; bit 3 is unused.
+ */
+#define TN_FLAG_SCALAR_KERNELS  1   /* run every contraction step on the plain FMA kernel */
+#define TN_FLAG_NO_SPLIT_K      4   /* never use the split-K kernel for small launches */
+#define TN_FLAG_NO_PAIR_CHAIN   32   /* never run a two-step plan as one chained launch (see TN_QUERY_PAIR_CHAINABLE):
+                                       always two launches with the intermediate in the workspace */
+#define TN_FLAG_NO_CHAIN2       64   /* never run two small transposing steps (Tucker factor products) as one
+                                       chained launch: always one launch per step */
 #define TN_FLAG_NO_SMALL_CHAIN (1 << 20) /* never run a small layer as one launch with all its tensors in LDS */
-#define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: tuning override of the short-K kernel's form (0 = library's
-                                       choice) */
-#define TN_FLAG_MERGE_HALVES  (1 << 22)  /* like TN_FLAG_MERGE_GROW, but whatever the size (up to 1e9 elements): contract
-                                       parameter tensors at create time until two are left (a ring of four cores
-                                       becomes two half rings), and keep them. This is the plan large calls of a
-                                       default layer run on with the merged tensors rebuilt per call
-                                       (TN_QUERY_LAZY_MIN_TOKENS); with this flag every call runs on it. */
-#define TN_FLAG_SCALAR_GENERATE (1 << 23) /* debug: rebuild the slices of a lazily merged plan with the plain FMA kernel
-                                       instead of the MFMA one */
 #define TN_FLAG_NO_LAZY_MERGE (1 << 21)  /* never run large calls on a merged plan rebuilt in the workspace (see
                                        TN_QUERY_LAZY_MIN_TOKENS): every call runs the compact steps */
-#define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: tuning override, kernel variant id for the wide
-                                       bf16 steps (0 = library's choice): 3 = 128x256 and 8 = 256x128
-                                       register-prefetch tiles, 9 = short-K store kernel, 12 = 256x256
-                                       ping-pong kernel; 20 = the Kronecker-sum kernel for every two-step
-                                       plan whose layout allows it, whatever its size (see
-                                       TN_QUERY_KRON_CHAINABLE); ignored where the variant cannot run the step */
+#define TN_FLAG_SCALAR_GENERATE (1 << 23) /* rebuild the slices of a lazily merged plan with the plain FMA kernel
+                                       instead of the MFMA one */
+#define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* never run a chained factor pair and the wide step after it as one launch
+                                       (calls of a few tokens: the in-factor products and the core of a Tucker layer),
+                                       nor chained pairs of few tokens on the kernel that requests its operands up front */
+#define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: kernel variant id for the wide bf16 steps (0 = library's choice):
+                                       3 = 128x256 and 8 = 256x128 register-prefetch tiles, 9 = short-K store kernel,
+                                       12 = 256x256 ping-pong kernel; 20 = the Kronecker-sum kernel for every two-step
+                                       plan whose layout allows it, whatever its size (see TN_QUERY_KRON_CHAINABLE);
+                                       ignored where the variant cannot run the step */
+#define TN_FLAG_SHORTK_SHIFT   16   /* bits 16..19: form of the short-K kernel (0 = library's choice) */
 
 /* tn_linear_query / tn_linear_plan_query: what */
 #define TN_QUERY_PARAM_COUNT        0   /* number of parameters in the caller's tensors */
@@ -169,8 +176,8 @@ typedef struct tn_linear_s* tn_linear_t;
  *                     forward calls are processed in several passes.
  *  workspace_limit_bytes
  *                     upper bound for the handle's device workspace; 0 = library default
- *                     (16 GiB): a pass then covers as many tokens as fit, which keeps every
- *                     launch large enough to fill the chip.
+ *                     (4 GiB): the handle allocates what max_tokens needs, up to this bound; with less,
+ *                     a call is processed in passes of as many tokens as fit.
  *  flags              TN_FLAG_* bits.
  *  stream             hipStream_t on which create enqueues its repacking work.
  *  workspace, workspace_bytes

@@ -32,6 +32,10 @@ struct PairArgs {
     int64_t N, M;          // elements per token of X and Y
     int32_t tokens, A, J, C1;
     int32_t n_tok_tiles, n_jsets;
+    // few token tiles: the range of a is split over n_splits workgroups per (token tile, j set), each of which
+    // writes fp32 partial sums [split][tokens][M] to `partial`; a second kernel adds them in split order
+    int32_t n_splits, a_per_split;
+    float* partial;
 };
 
 // B1f[((a*16 + ct*4 + s)*64 + l)*8 + e] = B1[c = 32*ct + l%32][k = a*64 + 16*s + 8*(e/4) + 4*(l/32) + e%4]
@@ -55,12 +59,22 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
     constexpr int STAGE_BYTES = 20 * 1024, X_OFF = 16 * 1024;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
 
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
-    const int tok_tile = (slot / p.n_jsets) * 8 + xcd;
-    const int jset = slot % p.n_jsets;
+    int id = blockIdx.x;
+    const int split = id % p.n_splits;                  // n_splits = 1: no split
+    id /= p.n_splits;
+    int tok_tile, jset;
+    if (p.n_splits > 1) {
+        // few token tiles: an exact grid (a workgroup that only returns still costs a CU's worth of LDS and registers)
+        tok_tile = id / p.n_jsets;
+        jset = id % p.n_jsets;
+    } else {
+        const int xcd = id & 7, slot = id >> 3;
+        tok_tile = (slot / p.n_jsets) * 8 + xcd;
+        jset = slot % p.n_jsets;
+    }
     if (tok_tile >= p.n_tok_tiles) return;
     const int t0 = tok_tile * 32;
+    const int a_begin = split * p.a_per_split;          // this workgroup's values of a: a_begin .. a_begin + A - 1
 
     const bf16_t* X = static_cast<const bf16_t*>(p.X);
     const bf16_t* B0 = static_cast<const bf16_t*>(p.B0);
@@ -69,7 +83,7 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j0 = jset * 8 + wave * 2;
-    const int A = p.A;
+    const int A = min(p.A, a_begin + p.a_per_split) - a_begin;          // >= 1 by construction of the grid
 
     // the wave's rows of the first packed tensor: [jj][32-row half of the bond][k-step]
     bf16x8 p0[2][2][4];
@@ -85,7 +99,8 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
     const int tl = min(t0 + (lane & 31), p.tokens - 1);             // rows past the end repeat the last token
     const bf16_t* x_src = X + int64_t(tl) * p.N + 16 * wave + 8 * (lane >> 5);
     const bf16_t* b_src = B1f + lane * 8;
-    auto issue = [&](int a, int stage) {
+    auto issue = [&](int a_rel, int stage) {             // a_rel counts from a_begin, as everything below does
+        const int a = a_begin + a_rel;
         unsigned char* sbase = dyn_smem + stage * STAGE_BYTES;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
@@ -212,6 +227,38 @@ __global__ void __launch_bounds__(256, 1) step_pair_kernel(PairArgs p) {
     iteration(A - 1, std::true_type());
     __syncthreads();
 
+    if (p.n_splits > 1) {
+        // Partial sums of this workgroup's range of a: fp32, in the output's own layout, [split][tokens][M]. As in the
+        // epilogue below the tiles are transposed through LDS so that the stores run along j: in two passes (waves
+        // 0-1, then waves 2-3), each leaving 16-byte pieces of 4 consecutive j per (token, c).
+        const int t = lane & 31;
+        const int yj = p.yrow[jset * 8];
+        float* dst = p.partial + int64_t(split) * p.tokens * p.M;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (half) __syncthreads();                  // the first pass has been read out
+            if ((wave >> 1) == half) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int c = 32 * ct + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                            *reinterpret_cast<float*>(dyn_smem + (t * 128 + (c ^ t)) * 16 + ((wave & 1) * 2 + jj) * 4) = acc[jj][ct][v];
+                        }
+            }
+            __syncthreads();
+#pragma unroll 4
+            for (int e = tid; e < 32 * 128; e += 256) {
+                const int tt = e >> 7, c = e & 127;
+                if (t0 + tt >= p.tokens || c >= p.C1) continue;
+                const floatx4 v4 = *reinterpret_cast<const floatx4*>(dyn_smem + (tt * 128 + (c ^ tt)) * 16);
+                *reinterpret_cast<floatx4*>(dst + int64_t(t0 + tt) * p.M + p.ycol[c] + yj + 4 * half) = v4;
+            }
+        }
+        return;
+    }
     // ---- epilogue: lane l, register v of acc[jj][ct] is token l%32, c = 32*ct + 8*(v/4) + 4*(l/32) + v%4.
     //      LDS holds [32 tokens][128 c] pieces of 16 bytes (the 8 j of the workgroup), the piece of
     //      (t, c) at position c ^ t of row t so that neither the 4-byte writes nor the 16-byte reads

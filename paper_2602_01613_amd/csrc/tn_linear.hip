@@ -12,6 +12,7 @@
 // permutation kernel ever runs.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -544,15 +545,45 @@ int launch_small_chain(const tn_linear_s* h, const void* x, void* y, int64_t tok
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
-// Token count from which the chained pair kernel replaces the two separate launches (below it a
-// launch has too few workgroups: 8 per 32 tokens).
-constexpr int64_t kPairMinTokens = 256;
+// The chained pair kernel runs every call of a layer it fits. With few token tiles (8 workgroups per 32 tokens) the
+// range of a is split over workgroups, fp32 partial sums are written to the partial buffer and kron_reduce_kernel
+// adds them in split order.
+constexpr int64_t kPairMinTokens = 1;
 #ifndef TN_PAIR_STAGES
 #define TN_PAIR_STAGES 4
 #define TN_PAIR_BAR 1
 #endif
 constexpr int kPairStages = TN_PAIR_STAGES, kPairBar = TN_PAIR_BAR;
 constexpr size_t kPairSmemBytes = kPairStages * 20 * 1024;
+
+struct PairGeom {
+    int n_tok_tiles = 1, n_jsets = 1, n_splits = 1, a_per_split = 1;
+    int64_t partial_bytes = 0;
+};
+
+PairGeom pair_geometry(const tn_linear_s* h, int64_t tokens, int64_t partial_cap) {
+    PairGeom g;
+    const int64_t A = h->steps[0].plan.R, J = h->steps[1].plan.R;
+    g.n_tok_tiles = int((tokens + 31) / 32);
+    g.n_jsets = int(J / 8);
+    const int64_t base = int64_t(g.n_tok_tiles) * g.n_jsets;
+    // one round of workgroups (a CU holds one): as many splits as keep the grid within the number of CUs
+    int64_t want = std::max<int64_t>(1, int64_t(h->num_cus) / base);
+    want = std::min<int64_t>(want, std::max<int64_t>(1, A / 2));                      // at least two values of a each
+    // every split writes tokens * M floats that the reduction reads back: within one token tile the number of splits
+    // that balances the two (measured at 8, 16 and 32 tokens: 16-20, 16, 13) grows as tokens^-1/2; with several
+    // token tiles filling the chip matters more
+    if (want > 1 && tokens <= 32) {
+        const double per_split_mb = double(tokens) * double(h->plan.M) * 8.0 / 1e6;      // written and read
+        const double best = std::sqrt(double(A) * 4.8 / per_split_mb);
+        want = std::min<int64_t>(want, std::max<int64_t>(1, int64_t(best + 0.5)));
+    }
+    want = std::min<int64_t>(want, std::max<int64_t>(1, partial_cap / (tokens * h->plan.M * 4)));       // stays the last word
+    g.a_per_split = int((A + want - 1) / want);
+    g.n_splits = int((A + g.a_per_split - 1) / g.a_per_split);                        // no empty split
+    g.partial_bytes = g.n_splits > 1 ? int64_t(g.n_splits) * tokens * h->plan.M * 4 : 0;
+    return g;
+}
 
 int prepare_pair(tn_linear_s* h, hipStream_t st) {
     if ((h->flags & (TN_FLAG_NO_PAIR_CHAIN | TN_FLAG_SCALAR_KERNELS)) || !tn::pair_chainable(h->plan)) return TN_OK;
@@ -571,9 +602,11 @@ int prepare_pair(tn_linear_s* h, hipStream_t st) {
     return TN_OK;
 }
 
-int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hipStream_t st) {
+int launch_pair(const tn_linear_s* h, const Workspace& w, const void* x, void* y, int64_t tokens, hipStream_t st) {
     const DevStep& s0 = h->steps[0];
     const DevStep& s1 = h->steps[1];
+    const PairGeom g = pair_geometry(h, tokens, w.partial ? w.partial_bytes : 0);
+    if (g.partial_bytes > (w.partial ? w.partial_bytes : 0)) return TN_ERR_UNSUPPORTED;      // never write past the buffer
     PairArgs p;
     p.X = x;
     p.Y = y;
@@ -587,10 +620,19 @@ int launch_pair(const tn_linear_s* h, const void* x, void* y, int64_t tokens, hi
     p.A = int32_t(s0.plan.R);
     p.J = int32_t(s1.plan.R);
     p.C1 = int32_t(s1.plan.C);
-    p.n_tok_tiles = int32_t((tokens + 31) / 32);
-    p.n_jsets = p.J / 8;
-    int64_t grid = int64_t((p.n_tok_tiles + 7) / 8 * 8) * p.n_jsets;
+    p.n_tok_tiles = g.n_tok_tiles;
+    p.n_jsets = g.n_jsets;
+    p.n_splits = g.n_splits;
+    p.a_per_split = g.a_per_split;
+    p.partial = static_cast<float*>(w.partial);
+    const int64_t grid = p.n_splits > 1 ? int64_t(p.n_tok_tiles) * p.n_jsets * p.n_splits
+                                        : int64_t((p.n_tok_tiles + 7) / 8 * 8) * p.n_jsets;
     hipLaunchKernelGGL((step_pair_kernel<kPairStages, kPairBar>), dim3(uint32_t(grid)), dim3(256), kPairSmemBytes, st, p);
+    if (g.n_splits > 1) {
+        const int64_t n = tokens * h->plan.M;
+        hipLaunchKernelGGL(kron_reduce_kernel, dim3(uint32_t((n + 63) / 64)), dim3(256), 0, st,
+                           static_cast<const float*>(w.partial), static_cast<bf16_t*>(y), n, g.n_splits);
+    }
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
 }
 
@@ -714,7 +756,8 @@ struct KronSetup {
 int launch_kron(const tn_linear_s* h, const Workspace& w, const KronSetup& k, const void* x, void* y, int64_t tokens,
                 hipStream_t st) {
     const tn::KronDims& d = *k.dims;
-    const KronGeom g = kron_geometry(h, d, tokens, w.partial_bytes);
+    const KronGeom g = kron_geometry(h, d, tokens, w.partial ? w.partial_bytes : 0);
+    if (g.partial_bytes > (w.partial ? w.partial_bytes : 0)) return TN_ERR_UNSUPPORTED;      // never write past the buffer
     KronArgs p;
     p.X = x;
     p.Y = g.n_splits > 1 ? w.partial : y;
@@ -1866,6 +1909,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
     // partial-sum buffer of the split-K kernel; allocated here, or carved out of the caller's block
     int64_t per_token = h->plan.max_intermediate * h->elt;
     if (h->kron && h->kron_min_tokens <= 1) per_token = 0;      // every call runs the one-launch kernel: no intermediates
+    if (h->pair && h->pair_min_tokens <= 1) per_token = 0;
     int64_t max_r = 1;
     for (const auto& s : h->steps) max_r = std::max(max_r, s.plan.R);
     const int64_t row_cap = ((int64_t(1) << 31) - 1024) / max_r;      // rows of a pass are indexed with 32 bits
@@ -1877,6 +1921,11 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
             for (int64_t t = 1; t <= std::min<int64_t>(h->max_tokens, 4 * int64_t(h->num_cus)); ++t)
                 need = std::max(need, kron_geometry(h, h->kron_dims, t, kMaxPartialBytes).partial_bytes);
             if (h->kron_min_tokens <= 1) return need;
+        }
+        if (h->pair) {
+            for (int64_t t = h->pair_min_tokens; t <= std::min<int64_t>(h->max_tokens, 32 * int64_t(h->num_cus)); ++t)
+                need = std::max(need, pair_geometry(h, t, kMaxPartialBytes).partial_bytes);
+            if (h->pair_min_tokens <= 1) return need;
         }
         if (h->lazy)
             for (int64_t t = h->lazy_min_tokens; t <= std::min<int64_t>(h->max_tokens, 4 * int64_t(h->num_cus)); ++t)
@@ -2057,7 +2106,7 @@ int forward_in(tn_linear_s* h, const Workspace& w, bool allow_lazy, const void* 
             if (!prof.ok) return TN_ERR_HIP;
             const void* xp = xb + t0 * h->plan.N * h->elt;
             void* yp = yb + t0 * h->plan.M * h->elt;
-            int rc = use_pair ? launch_pair(h, xp, yp, nt, st)
+            int rc = use_pair ? launch_pair(h, w, xp, yp, nt, st)
                               : (use_kron ? launch_kron_eager(h, w, xp, yp, nt, st) : launch_kron_lazy(h, w, xp, yp, nt, st));
             prof.done();
             if (rc != TN_OK) return rc;
@@ -2250,11 +2299,10 @@ int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tok
     void* base = (h->device >= 0 && h->device < 64) ? g_scratch_ptr[h->device] : nullptr;
     if (!base) return TN_ERR_UNSUPPORTED;
     Workspace w;
-    const bool one_launch = (h->small_chain && (h->elt == 4 || tokens <= kSmallChainMaxBf16Tokens)) ||
-                            (h->pair && tokens >= h->pair_min_tokens);
+    const bool one_launch = h->small_chain && (h->elt == 4 || tokens <= kSmallChainMaxBf16Tokens);
     if (one_launch) {
         // nothing but x and y is touched
-    } else if (h->kron && tokens >= h->kron_min_tokens) {
+    } else if ((h->pair && tokens >= h->pair_min_tokens) || (h->kron && tokens >= h->kron_min_tokens)) {
         // only partial sums: the launch takes as many splits of the bond as fit
         w.partial = base;
         w.partial_bytes = kScratchBytes;

@@ -153,14 +153,16 @@ def test_token_count_boundaries(tokens, dense_w):
 def test_chunked_passes_match_single_pass(dense_w):
     spec, ts, w = dense_w(1)
     x = wl.make_x(spec, 75, 1)
-    # 16 MiB of workspace, two buffers of the largest intermediate (bf16) per token
-    layer = make_layer(spec, ts, 75, workspace_limit_bytes=16 << 20)
+    # the per-step path (the chained pair kernel keeps no intermediates): 16 MiB of workspace, two buffers of the
+    # largest intermediate (bf16) per token
+    two = tn.TN_FLAG_NO_PAIR_CHAIN
+    layer = make_layer(spec, ts, 75, workspace_limit_bytes=16 << 20, flags=two)
     per_token = 2 * 2 * layer.query(tn.TN_QUERY_MAX_INTERMEDIATE)
     assert layer.query(tn.TN_QUERY_CHUNK_TOKENS) == (16 << 20) // per_token < 75
     y_small = layer(to_dev(x, "bf16"))
     torch.cuda.synchronize()
     layer.close()
-    layer = make_layer(spec, ts, 75)
+    layer = make_layer(spec, ts, 75, flags=two)
     assert layer.query(tn.TN_QUERY_CHUNK_TOKENS) == 75
     y_big = layer(to_dev(x, "bf16"))
     torch.cuda.synchronize()
@@ -172,7 +174,7 @@ def test_chunked_passes_match_single_pass(dense_w):
     assert O.rel_max_err(to_host(y_big), ref) <= TOL["bf16"]
     assert O.rel_max_err(to_host(y_small), to_host(y_big)) <= 1e-2
     # more tokens than max_tokens: processed in several passes
-    layer = make_layer(spec, ts, 10)
+    layer = make_layer(spec, ts, 10, flags=two)
     y_cap = layer(to_dev(x, "bf16"))
     torch.cuda.synchronize()
     layer.close()
@@ -386,8 +388,8 @@ def test_shared_caller_workspace(dense_w):
     # a block that cannot hold one token's intermediates is refused
     tiny = torch.empty(4096, dtype=torch.uint8, device="cuda")
     with pytest.raises(tn.TNLinearError) as e:
-        tn.TNLinear(spec1.format, tn.TN_DTYPE_BF16, spec1.out_modes, spec1.in_modes, spec1.ranks,
-                    [to_dev(t, "bf16") for t in ts1], 8, workspace=tiny)
+        tn.TNLinear(spec2.format, tn.TN_DTYPE_BF16, spec2.out_modes, spec2.in_modes, spec2.ranks,
+                    [to_dev(t, "bf16") for t in ts2], 8, workspace=tiny)
     assert e.value.status == -1
 
 
@@ -410,7 +412,7 @@ def test_chained_pair_kernel_small(case):
     ts = _rand_layer(spec, 700 + case)
     assert tn.plan_query(spec.format, tn.TN_DTYPE_BF16, om, im, rk, tn.TN_QUERY_PAIR_CHAINABLE) == 1
     w = O.dense_weight(spec.format, ts, len(om))
-    for tokens in (256, 257, 1000):
+    for tokens in (1, 5, 33, 256, 257, 1000):          # up to 8 token tiles the range of a is split over workgroups
         x = wl.round_to_dtype(np.random.default_rng(case + tokens).standard_normal((tokens, spec.N)), "bf16")
         ref = O.apply_linear(w, x)
         layer = make_layer(spec, ts, tokens)
@@ -427,7 +429,7 @@ def test_chained_pair_kernel_small(case):
         assert O.rel_max_err(y, y_two) <= 1e-2, (case, tokens)
 
 
-@pytest.mark.parametrize("tokens", [256, 300, 2049])
+@pytest.mark.parametrize("tokens", [1, 8, 31, 64, 100, 256, 300, 2049])
 def test_chained_pair_kernel_q_proj(tokens, dense_w):
     spec, ts, w = dense_w(1)
     x = wl.make_x(spec, tokens, 1)

@@ -25,7 +25,8 @@ CASES = [
     (_spec(tn.TN_FORMAT_TUCKER, (160, 96, 16), (64,), (48, 32, 1, 16)), 0, (64, 7)),           # chained pair mid-chain
     (wl.stack_spec(wl.FORMAT_DENSE, 5120, 8192, 0), 0, (64, 2)),                               # split-K with partial sums only
     (wl.baseline_spec(3)[0], tn.TN_FLAG_MERGE_GROW, (9, 2)),                                   # Kronecker-sum kernel, bond split
-    (_spec(tn.TN_FORMAT_TT, (8, 4, 8, 8), (8, 2, 8, 8), (1, 64, 64, 64, 1)), 0, (300, 256)),   # chained pair kernel: no scratch at all
+    (_spec(tn.TN_FORMAT_TT, (8, 4, 8, 8), (8, 2, 8, 8), (1, 64, 64, 64, 1)), 0, (300, 256)),   # chained pair kernel: partial sums only
+    (wl.baseline_spec(1)[0], tn.TN_FLAG_NO_PAIR_CHAIN, (20, 3)),                               # the same train as two launches
 ]
 
 
@@ -55,7 +56,7 @@ def test_forward_scratch_matches_forward(case):
 def test_forward_scratch_refuses_what_does_not_fit():
     spec = wl.baseline_spec(1)[0]
     ts = wl.make_tensors(spec, 1)
-    layer = make_layer(spec, ts, 64)
+    layer = make_layer(spec, ts, 64, flags=tn.TN_FLAG_NO_PAIR_CHAIN)     # two launches with the intermediate in memory
     x = to_dev(wl.make_x(spec, 64, 1), "bf16")
     y = torch.empty((64, spec.M), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(tn.TNLinearError) as e:                            # 64 tokens x 2 x 655 KB > 32 MiB
