@@ -72,14 +72,15 @@ def cpu_baseline(spec, tensors, sample_tokens, transpose=False, x_used=None, y_g
 
 
 def measured_traffic(workload, flags, tokens, fused):
-    """HBM-side bytes per launch of the dominant kernel of workloads 1 to 3 at their default settings, as
+    """HBM-side bytes per launch of the dominant kernel of workloads 1 to 3 and of the dense matrix (4) at their default settings, as
     measured in separate rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, calibrated on a copy kernel) and
     recorded in profiles/: counters cannot be read from inside this process. Returns (bytes, file) or (None, None)."""
-    if flags or tokens != 8192 or fused != (workload != 2):
+    if flags or tokens != 8192 or fused != (workload in (1, 3)):
         return None, None
     name, key = {1: ("tt_q_proj_prefill8192_hbm_traffic.txt", "pair"),
                  2: ("tucker_up_proj_prefill8192_hbm_traffic.txt", "core"),
-                 3: ("tr_down_proj_prefill8192_hbm_traffic.txt", "kronsum")}.get(workload, (None, None))
+                 3: ("tr_down_proj_prefill8192_hbm_traffic.txt", "kronsum"),
+                 4: ("dense_q_proj_prefill8192_hbm_traffic.txt", "gemm")}.get(workload, (None, None))
     if name is None:
         return None, None
     try:
@@ -787,7 +788,7 @@ def main() -> int:
     if everything:
         subs = [("tucker_up_proj", wl.baseline_spec(2)[0], 2, 2, args.steps),
                 ("tr_down_proj", wl.baseline_spec(3)[0], 3, 3, max(3, args.steps // 4)),
-                ("dense_q_proj", wl.stack_spec(wl.FORMAT_DENSE, 5120, 8192, 0, "dense_q_proj"), 4, None, args.steps)]
+                ("dense_q_proj", wl.stack_spec(wl.FORMAT_DENSE, 5120, 8192, 0, "dense_q_proj"), 4, 4, args.steps)]
         for name, sub_spec, cid, wid, steps in subs:
             if time.perf_counter() - t_start > args.time_budget_s:
                 configs[name] = {"skipped": "time budget of the default run exhausted"}
