@@ -82,7 +82,12 @@ extern "C" {
                                        rounded to the nearest of 0, 0.5, 1, 1.5, 2, 3, 4, 6 (ties to an even mantissa bit,
                                        saturating) with a sign. The layer then applies the DEQUANTISED tensors (exact in
                                        bf16) and keeps codes and exponents (tn_linear_quantized_tensor,
-                                       TN_QUERY_QUANT_BYTES). bf16 layers only; not with TN_FLAG_TRAINABLE. */
+                                       TN_QUERY_QUANT_BYTES). Calls of up to 64 rows read a tensor in its 4-bit form
+                                       (0.53 bytes per parameter, converted in registers: same values, a quarter of the
+                                       memory traffic) where the contraction walks the caller's tensor in memory order
+                                       and K is a multiple of 32 - a dense matrix, the core of a Tucker layer
+                                       (TN_QUERY_QUANT_STREAM_BYTES); larger calls and all other tensors use the bf16
+                                       copies. bf16 layers only; not with TN_FLAG_TRAINABLE. */
 
 /*
  * desc.flags, part 2: switches that take a kernel path away, and tuning overrides. They exist for the library's own
@@ -103,6 +108,8 @@ extern "C" {
 #define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* never run a chained factor pair and the wide step after it as one launch
                                        (calls of a few tokens: the in-factor products and the core of a Tucker layer),
                                        nor chained pairs of few tokens on the kernel that requests its operands up front */
+#define TN_FLAG_NO_Q4_STREAM (1 << 27)   /* a TN_FLAG_QUANT_MXFP4 layer never reads the 4-bit form in its kernels: every call
+                                       multiplies with the bf16 copies of the dequantised tensors */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: kernel variant id for the wide bf16 steps (0 = library's choice):
                                        3 = 128x256 and 8 = 256x128 register-prefetch tiles, 9 = short-K store kernel,
                                        12 = 256x256 ping-pong kernel; 20 = the Kronecker-sum kernel for every two-step
@@ -139,6 +146,8 @@ extern "C" {
 #define TN_QUERY_BACKWARD_CHUNK_TOKENS 14 /* handle only: tokens per pass of tn_linear_param_gradients (0: not trainable) */
 #define TN_QUERY_BACKWARD_WORKSPACE_BYTES 15 /* handle only: device memory held for those passes */
 #define TN_QUERY_QUANT_BYTES       16   /* handle only: bytes of the 4-bit codes and block exponents of all tensors (0: not quantised) */
+#define TN_QUERY_QUANT_STREAM_BYTES 17  /* handle only: bytes of the 4-bit streams that decode-size calls read instead of the
+                                           bf16 tensors (0: no step of the layer qualifies, or not quantised) */
 #define TN_QUERY_STEP_BASE        100   /* 100 + 10*s + f: field f of step s:
                                            f=0 rows per token, 1 K, 2 columns, 3 FLOPs per token,
                                            4 id of the absorbed tensor (index into desc.tensors; ids >=

@@ -32,6 +32,7 @@ TN_FLAG_SCALAR_GENERATE = 1 << 23
 TN_FLAG_NO_DECODE_FUSION = 1 << 24
 TN_FLAG_TRAINABLE = 1 << 25
 TN_FLAG_QUANT_MXFP4 = 1 << 26
+TN_FLAG_NO_Q4_STREAM = 1 << 27
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2
@@ -49,6 +50,7 @@ TN_QUERY_LAZY_FLOPS_PER_TOKEN = 13
 TN_QUERY_BACKWARD_CHUNK_TOKENS = 14
 TN_QUERY_BACKWARD_WORKSPACE_BYTES = 15
 TN_QUERY_QUANT_BYTES = 16
+TN_QUERY_QUANT_STREAM_BYTES = 17
 TN_QUERY_STEP_BASE = 100
 
 EXPORTED_SYMBOLS = (

@@ -670,7 +670,9 @@ __global__ void __launch_bounds__(256) step_chain2_small_kernel(Chain2Args c0, C
     it.compute(c, static_cast<bf16_t*>(c.Out));
 }
 
-template <int K1S, int RUN_C1, int KPW>
+// Q4: the wide step's tensor is read in its 4-bit form (see q4_stream_pack_kernel): KPW then counts pieces of 64 k
+// per wave (one 16-byte load of codes and one scale byte per lane and piece) instead of k-steps.
+template <int K1S, int RUN_C1, int KPW, int Q4>
 __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, StepArgs a0, int z_bytes0, Chain2Args c1,
                                                                 StepArgs a1, int z_bytes1) {
     constexpr int NW = 8;
@@ -698,9 +700,21 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, S
     Chain2Item<2, K1S, 2, RUN_C1> item;
     if (has_item) item.load(c, wave / c.c1_tiles, wave % c.c1_tiles);
     __builtin_amdgcn_sched_barrier(0);
-    // ---- 2. the wave's share of the parameter stream: k-steps wave, wave + 8, ...
-    bf16x8 bf[KPW];
-    {
+    // ---- 2. the wave's share of the parameter stream: k-steps (pieces of 64 k when Q4) wave, wave + 8, ...
+    bf16x8 bf[Q4 ? 1 : KPW];
+    uint4 qc[Q4 ? KPW : 1];
+    unsigned qs[Q4 ? KPW : 1];
+    const int n_chunks = nks >> 2;
+    if (Q4) {
+        const uint4* qp = static_cast<const uint4*>(a.B) + int64_t(cb) * n_chunks * 64 + lane;
+        const unsigned char* sp = static_cast<const unsigned char*>(a.Bs) + int64_t(cb) * n_chunks * 64 + lane;
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) {
+            const int ch = min(wave + NW * u, n_chunks - 1);
+            qc[u] = qp[int64_t(ch) * 64];
+            qs[u] = sp[int64_t(ch) * 64];
+        }
+    } else {
         const bf16_t* bp = B + (int64_t(cb) * nks) * 512 + lane * 8;
 #pragma unroll
         for (int u = 0; u < KPW; ++u) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(min(wave + NW * u, nks - 1)) * 512);
@@ -716,6 +730,24 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, S
     {
         const bool tv = lrow < int(a.total_rows);
         const bf16_t* zrow = z + int64_t(tv ? lrow : 0) * a.a_tok_stride + 8 * lhalf;
+        if (Q4) {
+            // lanes 0-31 hold block 2*ch, lanes 32-63 block 2*ch + 1: k-step u of a piece takes k = 64*ch + 32*(l/32) + 8u ..
+            const bf16_t* zq = z + int64_t(tv ? lrow : 0) * a.a_tok_stride + 32 * lhalf;
+#pragma unroll
+            for (int u = 0; u < KPW; ++u) {
+                const int ch = wave + NW * u;
+                if (ch < n_chunks) {                                           // wave-uniform
+                    bf16x8 w[4];
+                    q4_dequant_block(qc[u], qs[u], w);
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const int k = 64 * ch + 8 * ks;
+                        const bf16x8 x = (tv && k + 32 * lhalf < a.K) ? *reinterpret_cast<const bf16x8*>(zq + k) : zero;
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ks], x, acc, 0, 0, 0);
+                    }
+                }
+            }
+        } else {
 #pragma unroll
         for (int u = 0; u < KPW; ++u) {
             const int ks = wave + NW * u;
@@ -723,6 +755,7 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, S
                 const bf16x8 x = (tv && 16 * ks + 8 * lhalf < a.K) ? *reinterpret_cast<const bf16x8*>(zrow + 16 * ks) : zero;
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], x, acc, 0, 0, 0);
             }
+        }
         }
     }
 #pragma unroll

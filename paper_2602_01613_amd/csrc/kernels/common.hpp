@@ -19,6 +19,7 @@ struct StepArgs {
     uint32_t total_rows;   // tokens * R
     uint32_t R;
     int32_t K, Kp, C, Cp;
+    const void* Bs = nullptr;   // 4-bit stream: the block scales (B then holds the codes)
 };
 
 struct PackArgs {

@@ -156,6 +156,38 @@ __global__ void __launch_bounds__(256, MINB) step_shortk_kernel(StepArgs a) {
 // at a tile does the sum was measured 8x slower: a device-scope fence on this chip writes back the
 // L2 of the workgroup's XCD.
 // ---------------------------------------------------------------------------------------------
+// End of a split-K workgroup: the per-wave accumulators are summed through LDS in wave order; with one split the
+// result is stored through the scatter tables, else into the fp32 partial buffer.
+template <int TM, int NW>
+__device__ __forceinline__ void split_finish(const StepArgs& a, float* partial, float* red, const floatx16 (&acc)[TM],
+                                             uint32_t row0, int cb, int split, int nsplit, uint32_t rows_pad) {
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[((wave * TM + i) * 16 + v) * 64 + lane] = acc[i][v];
+    __syncthreads();
+    // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
+    const float* rw = red;
+    for (int e = tid; e < TM * 1024; e += NW * 64) {
+        int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += rw[w * TM * 1024 + e];
+        uint32_t g = row0 + i * 32 + (l & 31);
+        int c = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+        if (g >= a.total_rows || c >= a.C) continue;
+        if (nsplit == 1) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
+        } else {
+            partial[(int64_t(split) * rows_pad + g) * a.Cp + c] = sum;
+        }
+    }
+}
+
 // The work of one workgroup (row tile bx, column block cb, split `split` of nsplit). red is NW * TM * 1024 floats of
 // LDS. A may be memory or LDS (generic address).
 template <int TM, int AMODE, int NW>
@@ -163,7 +195,6 @@ __device__ __forceinline__ void split_run(const StepArgs& a, float* partial, int
                                           int cb, int split, int nsplit, uint32_t rows_pad) {
     const bf16_t* A = static_cast<const bf16_t*>(a.A);
     const bf16_t* B = static_cast<const bf16_t*>(a.B);
-    bf16_t* Out = static_cast<bf16_t*>(a.Out);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row0 = uint32_t(bx) * (TM * 32);
     const int nks = a.Kp >> 4;
@@ -237,29 +268,7 @@ __device__ __forceinline__ void split_run(const StepArgs& a, float* partial, int
             multiply(bf1, af1);
         }
     }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) red[((wave * TM + i) * 16 + v) * 64 + lane] = acc[i][v];
-    __syncthreads();
-    // operands swapped: lane l, register v holds row l%32, column 8*(v/4) + 4*(l/32) + v%4
-    const float* rw = red;
-    for (int e = tid; e < TM * 1024; e += NW * 64) {
-        int i = e >> 10, v = (e >> 6) & 15, l = e & 63;
-        float sum = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) sum += rw[w * TM * 1024 + e];
-        uint32_t g = row0 + i * 32 + (l & 31);
-        int c = cb * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
-        if (g >= a.total_rows || c >= a.C) continue;
-        if (nsplit == 1) {
-            uint32_t t = g / a.R;
-            uint32_t r = g - t * a.R;
-            Out[int64_t(t) * a.c_tok_stride + a.crow[r] + a.ccol[c]] = bf16_t(sum);
-        } else {
-            partial[(int64_t(split) * rows_pad + g) * a.Cp + c] = sum;
-        }
-    }
+    split_finish<TM, NW>(a, partial, red, acc, row0, cb, split, nsplit, rows_pad);
 }
 
 template <int TM, int AMODE, int NW>
@@ -267,6 +276,110 @@ __global__ void __launch_bounds__(NW * 64) step_split_kernel(StepArgs a, float* 
     __shared__ float red[NW * TM * 1024];
     split_run<TM, AMODE, NW>(a, partial, ksteps_per_split, red, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z,
                              gridDim.x * (TM * 32));
+}
+
+// The same workgroup with the packed tensor read in its 4-bit form (see q4_stream_pack_kernel): a lane's 16-byte load
+// is one block of 32 codes, converted in registers to the operands of four k-steps. A wave takes whole pieces of 64 k
+// (wave, wave + NW, ...) of its split; ksteps_per_split is a multiple of 4. The weight stream is a quarter of the
+// bf16 one, so the pieces in flight per wave are what keeps it busy: UC pieces per batch, two batches in registers.
+template <int TM, int AMODE, int NW>
+__device__ __forceinline__ void split_run_q4(const StepArgs& a, float* partial, int ksteps_per_split, float* red, int bx,
+                                             int cb, int split, int nsplit, uint32_t rows_pad) {
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const uint4* Q = static_cast<const uint4*>(a.B);
+    const unsigned char* S = static_cast<const unsigned char*>(a.Bs);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t row0 = uint32_t(bx) * (TM * 32);
+    const int n_chunks = a.Kp >> 6;
+    const int ch_begin = split * (ksteps_per_split >> 2);
+    const int ch_end = min(n_chunks, ch_begin + (ksteps_per_split >> 2));
+
+    int64_t a_base[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        uint32_t g = row0 + i * 32 + (lane & 31);
+        a_base[i] = -1;
+        if (g < a.total_rows) {
+            uint32_t t = g / a.R;
+            uint32_t r = g - t * a.R;
+            a_base[i] = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+        }
+    }
+    const int64_t piece0 = int64_t(cb) * n_chunks;
+    floatx16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    constexpr int UC = TM == 1 ? 4 : 2;
+    auto load_batch = [&](int c0, uint4 (&q)[UC], unsigned (&sc)[UC], bf16x8 (&af)[UC][4][TM]) {
+#pragma unroll
+        for (int u = 0; u < UC; ++u) {
+            const int ch = c0 + NW * u;
+            const bool live = ch < ch_end;
+            q[u] = make_uint4(0u, 0u, 0u, 0u);
+            sc[u] = 0u;
+            if (live) {
+                q[u] = Q[(piece0 + ch) * 64 + lane];
+                sc[u] = S[(piece0 + ch) * 64 + lane];
+            }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int k = 64 * ch + 32 * (lane >> 5) + 8 * ks;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    bf16x8 v;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = bf16_t(0.f);
+                    if (live && a_base[i] >= 0) {
+                        if (AMODE == 0) {
+                            if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + a_base[i] + k);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (k + e < a.K) v[e] = A[a_base[i] + (a.acol ? a.acol[k + e] : k + e)];
+                        }
+                    }
+                    af[u][ks][i] = v;
+                }
+            }
+        }
+    };
+    auto multiply = [&](const uint4 (&q)[UC], const unsigned (&sc)[UC], const bf16x8 (&af)[UC][4][TM]) {
+#pragma unroll
+        for (int u = 0; u < UC; ++u) {
+            bf16x8 bf[4];
+            q4_dequant_block(q[u], sc[u], bf);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks], af[u][ks][i], acc[i], 0, 0, 0);
+        }
+    };
+    {
+        uint4 q0[UC], q1[UC];
+        unsigned sc0[UC], sc1[UC];
+        bf16x8 af0[UC][4][TM], af1[UC][4][TM];
+        constexpr int STEP = NW * UC;
+        int c0 = ch_begin + wave;
+        load_batch(c0, q0, sc0, af0);                    // batches past the end load nothing and multiply zeros
+        for (; c0 < ch_end; c0 += 2 * STEP) {
+            load_batch(c0 + STEP, q1, sc1, af1);
+            multiply(q0, sc0, af0);
+            load_batch(c0 + 2 * STEP, q0, sc0, af0);
+            multiply(q1, sc1, af1);
+        }
+    }
+    split_finish<TM, NW>(a, partial, red, acc, row0, cb, split, nsplit, rows_pad);
+}
+
+template <int TM, int AMODE, int NW>
+__global__ void __launch_bounds__(NW * 64) step_split_q4_kernel(StepArgs a, float* partial, int ksteps_per_split) {
+    __shared__ float red[NW * TM * 1024];
+    split_run_q4<TM, AMODE, NW>(a, partial, ksteps_per_split, red, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z,
+                                gridDim.x * (TM * 32));
 }
 
 // Sums the partial results of the split-K kernel in split order and stores through the tables.

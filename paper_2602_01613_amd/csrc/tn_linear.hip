@@ -67,6 +67,8 @@ struct DevStep {
     void* chain_bbf = nullptr;    // chain2: the next step's packed tensor in the chained layout
     int chain_cfg = 0;            // chain2 instantiation: 0 <3,6,5>, 1 <2,8,2>, 2 <2,5,2>
     int chain_run_c1 = 0;         // chain2: output pieces run along c1 (else along c2)
+    void* q4_codes = nullptr;     // 4-bit stream of the tensor for decode-size launches (codes, then block scales)
+    void* q4_scales = nullptr;
 };
 
 }  // namespace
@@ -128,6 +130,7 @@ struct tn_linear_s {
     std::vector<void*> quant_codes, quant_exps;
     std::vector<int64_t> quant_elems;
     int64_t quant_bytes = 0;
+    int64_t q4_stream_bytes = 0;              // 4-bit streams of the steps whose decode-size launches read them
     std::vector<void*> create_temps;          // device buffers that only live until create returns
     // gradients with respect to the parameter tensors (TN_FLAG_TRAINABLE)
     bool trainable = false;
@@ -173,6 +176,7 @@ void free_handle(tn_linear_s* h) {
     for (auto& s : h->steps) {
         if (s.packed) (void)hipFree(s.packed);
         if (s.chain_bbf) (void)hipFree(s.chain_bbf);
+        if (s.q4_codes) (void)hipFree(s.q4_codes);       // one allocation: the scales follow the codes
     }
     if (h->tables) (void)hipFree(h->tables);
     for (void* v : h->quant_codes)
@@ -273,6 +277,7 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     c.nsplit = std::min(want, max_split);
     for (;;) {
         c.ksteps_per_split = (nks + c.nsplit - 1) / c.nsplit;
+        if (s.q4_codes) c.ksteps_per_split = round_up(c.ksteps_per_split, 4);    // the 4-bit stream comes in pieces of 64 k
         c.nsplit = (nks + c.ksteps_per_split - 1) / c.ksteps_per_split;      // no empty split
         c.partial_bytes = c.nsplit > 1 ? int64_t(c.nsplit) * c.row_tiles * 32 * c.tm * s.Cp * 4 : 0;
         if (c.partial_bytes <= kMaxPartialBytes || c.nsplit == 1) break;
@@ -381,7 +386,17 @@ int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, cons
         float* part = static_cast<float*>(w.partial);
         using split_t = void (*)(StepArgs, float*, int);
         split_t k;
-        if (sc.tm == 1)
+        if (s.q4_codes) {
+            // the launch is a stream of the packed tensor: read its 4-bit form
+            a.B = s.q4_codes;
+            a.Bs = s.q4_scales;
+            if (sc.tm == 1)
+                k = sc.nw == 8 ? (s.amode == 0 ? step_split_q4_kernel<1, 0, 8> : step_split_q4_kernel<1, 1, 8>)
+                               : (s.amode == 0 ? step_split_q4_kernel<1, 0, 4> : step_split_q4_kernel<1, 1, 4>);
+            else
+                k = sc.nw == 8 ? (s.amode == 0 ? step_split_q4_kernel<2, 0, 8> : step_split_q4_kernel<2, 1, 8>)
+                               : (s.amode == 0 ? step_split_q4_kernel<2, 0, 4> : step_split_q4_kernel<2, 1, 4>);
+        } else if (sc.tm == 1)
             k = sc.nw == 8 ? (s.amode == 0 ? step_split_kernel<1, 0, 8> : step_split_kernel<1, 1, 8>)
                            : (s.amode == 0 ? step_split_kernel<1, 0, 4> : step_split_kernel<1, 1, 4>);
         else
@@ -1280,6 +1295,7 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
 constexpr int64_t kFusedDecodeMaxZBytes = 32 * 1024;
 constexpr size_t kFusedDecodeRedBytes = 8 * 1024 * sizeof(float);
 constexpr int kFusedDecodeKPW = 18;          // k-steps of the wide step per wave: K <= 8 * 18 * 16 = 2304
+constexpr int kFusedDecodeQ4KPW = 5;         // 4-bit stream: pieces of 64 k per wave (the same K needs 36 pieces)
 
 bool chain2_split_applies(const tn_linear_s* h, const DevStep& s1, const DevStep& s3, int64_t tokens) {
     if (!s1.fuse_next || s1.chain_cfg == 0 || (h->flags & (TN_FLAG_NO_SPLIT_K | TN_FLAG_NO_DECODE_FUSION))) return false;
@@ -1304,7 +1320,8 @@ Chain2SplitArgs chain2_split_args(const DevStep& s1, const DevStep& s2, const De
     r.c = chain2_args(s1, s2, A, nullptr, tokens);      // the pair's result stays in LDS
     StepArgs& a = r.a;
     a.A = nullptr;                                       // likewise
-    a.B = s3.packed;
+    a.B = s3.q4_codes ? s3.q4_codes : s3.packed;
+    a.Bs = s3.q4_scales;
     a.Out = Out;
     a.arow = nullptr;
     a.acol = nullptr;
@@ -1319,7 +1336,7 @@ Chain2SplitArgs chain2_split_args(const DevStep& s1, const DevStep& s2, const De
     a.C = int32_t(s3.plan.C);
     a.Cp = s3.Cp;
     r.z_bytes = int((tokens * s3.plan.a_tok_stride * 2 + 255) & ~int64_t(255));
-    r.kern = (s1.chain_cfg - 1) * 2 + s1.chain_run_c1;
+    r.kern = (s1.chain_cfg - 1) * 2 + s1.chain_run_c1 + (s3.q4_codes ? 4 : 0);
     r.col_blocks = uint32_t((s3.plan.C + 31) / 32);
     return r;
 }
@@ -1327,10 +1344,13 @@ Chain2SplitArgs chain2_split_args(const DevStep& s1, const DevStep& s2, const De
 // One launch for one layer (p1 == nullptr) or for two layers on the same instantiation (grid.y = 2).
 int launch_chain2_split(const Chain2SplitArgs* p0, const Chain2SplitArgs* p1, hipStream_t st) {
     using k_t = void (*)(Chain2Args, StepArgs, int, Chain2Args, StepArgs, int);
-    static const k_t kerns[4] = {step_chain2_split_kernel<8, 0, kFusedDecodeKPW>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW>,
-                                 step_chain2_split_kernel<5, 0, kFusedDecodeKPW>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW>};
+    static const k_t kerns[8] = {
+        step_chain2_split_kernel<8, 0, kFusedDecodeKPW, 0>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW, 0>,
+        step_chain2_split_kernel<5, 0, kFusedDecodeKPW, 0>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW, 0>,
+        step_chain2_split_kernel<8, 0, kFusedDecodeQ4KPW, 1>, step_chain2_split_kernel<8, 1, kFusedDecodeQ4KPW, 1>,
+        step_chain2_split_kernel<5, 0, kFusedDecodeQ4KPW, 1>, step_chain2_split_kernel<5, 1, kFusedDecodeQ4KPW, 1>};
     if (!p0) {                             // configuration call (create time)
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     int(kFusedDecodeRedBytes + size_t(kFusedDecodeMaxZBytes))) != hipSuccess)
                 return TN_ERR_HIP;
@@ -1342,6 +1362,59 @@ int launch_chain2_split(const Chain2SplitArgs* p0, const Chain2SplitArgs* p1, hi
     hipLaunchKernelGGL(kerns[p0->kern], dim3(blocks, p1 ? 2 : 1), dim3(512), smem, st, p0->c, p0->a, p0->z_bytes, q.c, q.a,
                        q.z_bytes);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+}
+
+// 4-bit streams for the decode-size launches of a quantised layer: a step qualifies when its tensor is one of the
+// caller's (not merged, no traced index pair), its k walks that tensor in memory order (K consecutive elements per
+// column, K a multiple of 32) and every column starts on a block boundary. Such a step's split-K launches then read
+// 0.53 bytes per parameter instead of 2. The bf16 packed tensor stays: larger calls run on it.
+bool q4_streamable(const tn_linear_s* h, const tn::Step& p) {
+    if (p.slot < 0 || p.slot >= h->plan.n_caller_tensors || p.trace_extent != 1 || p.K % 32 || p.kdims.empty()) return false;
+    int64_t run = 1;
+    for (size_t j = p.kdims.size(); j-- > 0;) {
+        if (p.kdims[j].stride != run) return false;
+        run *= p.kdims[j].extent;
+    }
+    for (const tn::GatherDim& d : p.cdims)
+        if (d.stride % 32) return false;
+    return true;
+}
+
+int prepare_q4_stream(tn_linear_s* h, hipStream_t st) {
+    if (!(h->flags & TN_FLAG_QUANT_MXFP4) || (h->flags & (TN_FLAG_NO_Q4_STREAM | TN_FLAG_SCALAR_KERNELS | TN_FLAG_NO_SPLIT_K)) ||
+        h->plan.dtype != TN_DTYPE_BF16)
+        return TN_OK;
+    for (DevStep& s : h->steps) {
+        const tn::Step& p = s.plan;
+        if (s.variant == VAR_SCALAR || !q4_streamable(h, p)) continue;
+        // worth it only where a decode-size launch is a stream of this tensor: the split-K kernel must take one-row calls
+        if (!split_config(s, p.R).use) continue;
+        const int n_chunks = s.Kp / 64, col_blocks = int((p.C + 31) / 32);
+        const int64_t pieces = int64_t(col_blocks) * n_chunks * 64;
+        const int64_t code_bytes = pieces * 16, scale_bytes = (pieces + 255) & ~int64_t(255);
+        if (hipMalloc(&s.q4_codes, size_t(code_bytes + scale_bytes)) != hipSuccess) return TN_ERR_ALLOC;
+        s.q4_scales = static_cast<char*>(s.q4_codes) + code_bytes;
+        h->packed_bytes += code_bytes + scale_bytes;
+        h->q4_stream_bytes += code_bytes + scale_bytes;
+        Q4PackArgs a;
+        memset(&a, 0, sizeof(a));
+        a.codes = static_cast<const unsigned char*>(h->quant_codes[size_t(p.slot)]);
+        a.exps = static_cast<const signed char*>(h->quant_exps[size_t(p.slot)]);
+        a.out_codes = static_cast<uint4*>(s.q4_codes);
+        a.out_scales = static_cast<unsigned char*>(s.q4_scales);
+        a.C = int32_t(p.C);
+        a.K = int32_t(p.K);
+        a.n_chunks = n_chunks;
+        a.col_blocks = col_blocks;
+        a.nc = int32_t(p.cdims.size());
+        for (size_t j = 0; j < p.cdims.size(); ++j) {
+            a.cext[j] = p.cdims[j].extent;
+            a.cstr[j] = p.cdims[j].stride;
+        }
+        hipLaunchKernelGGL(q4_stream_pack_kernel, dim3(uint32_t(std::min<int64_t>((pieces + 255) / 256, 16384))), dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return TN_ERR_HIP;
+    }
+    return TN_OK;
 }
 
 // Kernels that use more than 64 KB of LDS need their limit raised once per device. Done at create
@@ -1894,6 +1967,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
     if (rc == TN_OK) rc = prepare_pair(h, st);
     if (rc == TN_OK) rc = prepare_kron(h, st);
     if (rc == TN_OK) rc = plan_chain2(h, st);
+    if (rc == TN_OK) rc = prepare_q4_stream(h, st);
     if (rc == TN_OK) {
         const int64_t before = h->packed_bytes;
         rc = prepare_lazy(h, desc, st);
@@ -2210,7 +2284,12 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
             for (int n = 0; n < 2; ++n)
                 fa[n] = chain2_split_args(hs[n]->steps[f], hs[n]->steps[f + 1], hs[n]->steps[f + 2],
                                           buffer(n, hs[n]->schedule[li].in), buffer(n, hs[n]->schedule[li + 1].out), tokens);
-            rc = launch_chain2_split(&fa[0], &fa[1], st);
+            if (fa[0].kern == fa[1].kern) {
+                rc = launch_chain2_split(&fa[0], &fa[1], st);
+            } else {                               // e.g. only one of the two streams its 4-bit form
+                rc = launch_chain2_split(&fa[0], nullptr, st);
+                if (rc == TN_OK) rc = launch_chain2_split(&fa[1], nullptr, st);
+            }
             ++li;
         } else if (l.steps == 2 && chain2_small_applies(ha, ha->steps[f], tokens) && chain2_small_applies(hb, hb->steps[f], tokens)) {
             Chain2Args ca[2];
@@ -2372,6 +2451,7 @@ int tn_linear_query(tn_linear_t h, int32_t what, int64_t* value) {
         case TN_QUERY_LAZY_MIN_TOKENS: *value = h->lazy ? h->lazy_min_tokens : 0; return TN_OK;
         case TN_QUERY_LAZY_FLOPS_PER_TOKEN: *value = h->lazy ? h->lazy_plan.flops : 0; return TN_OK;
         case TN_QUERY_QUANT_BYTES: *value = h->quant_bytes; return TN_OK;
+        case TN_QUERY_QUANT_STREAM_BYTES: *value = h->q4_stream_bytes; return TN_OK;
         case TN_QUERY_BACKWARD_CHUNK_TOKENS: *value = h->trainable ? h->bwd_chunk : 0; return TN_OK;
         case TN_QUERY_BACKWARD_WORKSPACE_BYTES: *value = h->trainable ? h->bwd_ws_bytes + h->bwd_partial_bytes : 0; return TN_OK;
         default: break;

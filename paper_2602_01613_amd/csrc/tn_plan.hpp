@@ -498,8 +498,22 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
                 return a < b;
             });
             next = nrows;
-            next.insert(next.end(), nk_rows.begin(), nk_rows.end());
-            next.insert(next.end(), nk_cols.begin(), nk_cols.end());
+            if (p->flags & TN_FLAG_QUANT_MXFP4) {
+                // a 4-bit tensor is streamed in blocks of 32 consecutive elements of the caller's flattening: the
+                // indices the next tensor contracts run in that tensor's own axis order, so that the k of the next
+                // step walks its memory and a block is 32 consecutive k of one column
+                std::vector<int> nk = nk_rows;
+                nk.insert(nk.end(), nk_cols.begin(), nk_cols.end());
+                std::stable_sort(nk.begin(), nk.end(), [&](int a, int b) {
+                    auto pa = std::find(Tn.idx.begin(), Tn.idx.end(), a) - Tn.idx.begin();
+                    auto pb = std::find(Tn.idx.begin(), Tn.idx.end(), b) - Tn.idx.begin();
+                    return pa < pb;
+                });
+                next.insert(next.end(), nk.begin(), nk.end());
+            } else {
+                next.insert(next.end(), nk_rows.begin(), nk_rows.end());
+                next.insert(next.end(), nk_cols.begin(), nk_cols.end());
+            }
         }
         // column order follows the position of the new indices in the next layout
         std::stable_sort(cset.begin(), cset.end(), [&](int a, int b) {

@@ -94,3 +94,83 @@ def test_quantisation_needs_bf16_and_no_gradients():
         plain.quantized_tensor(0)
     assert plain.query(tn.TN_QUERY_QUANT_BYTES) == 0
     plain.close()
+
+
+# Layers whose decode-size calls read the 4-bit form itself: a dense matrix (K whole pieces of 64; K with a half
+# piece at the end; rows and columns ragged against the 32-wide tiles) and Tucker layers whose core has K = S1 * S2
+# a multiple of 32.
+STREAM_CASES = [
+    (tn.TN_FORMAT_DENSE, (200,), (640,), ()),
+    (tn.TN_FORMAT_DENSE, (75,), (416,), ()),
+    (tn.TN_FORMAT_DENSE, (1024,), (5120,), ()),
+    (tn.TN_FORMAT_TUCKER, (16, 24), (16, 40), (8, 16, 8, 16)),
+    (tn.TN_FORMAT_TUCKER, (40, 40), (16, 20), (24, 24, 12, 16)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(STREAM_CASES)))
+def test_decode_size_calls_read_the_4bit_form(case):
+    fmt, om, im, rk = STREAM_CASES[case]
+    spec = wl.TNSpec(fmt, "bf16", tuple(om), tuple(im), tuple(rk))
+    rng = np.random.default_rng(4100 + case)
+    ts = []
+    for shp in spec.tensor_shapes():
+        t = rng.standard_normal(shp) * np.exp2(rng.integers(-4, 4, size=shp))
+        t.reshape(-1)[::13] = 0.0
+        ts.append(wl.round_to_dtype(t, "bf16"))
+    ts[0].reshape(-1)[:64] = 0.0                                      # two all-zero blocks (scale exponent -127)
+    deq = O.mxfp4_dequantized(ts)
+    layer = make_layer(spec, ts, 130, flags=tn.TN_FLAG_QUANT_MXFP4)
+    plain = make_layer(spec, ts, 130, flags=tn.TN_FLAG_QUANT_MXFP4 | tn.TN_FLAG_NO_Q4_STREAM)
+    assert layer.query(tn.TN_QUERY_QUANT_STREAM_BYTES) > 0
+    assert plain.query(tn.TN_QUERY_QUANT_STREAM_BYTES) == 0
+    _check_codes(layer, ts)
+    for tokens in (1, 2, 5, 8, 31, 32, 33, 64, 65, 130):
+        x = wl.round_to_dtype(rng.standard_normal((tokens, spec.N)), "bf16")
+        xd = to_dev(x, "bf16")
+        y = to_host(layer(xd))
+        ref = O.forward(fmt, deq, x, n_out_modes=len(om))
+        err = O.rel_max_err(y, ref)
+        assert err <= TOL["bf16"], (case, tokens, err)
+        # same values, other summation order and kernel: the two paths agree far inside the tolerance
+        assert O.rel_max_err(y, to_host(plain(xd))) <= 1e-2, (case, tokens)
+    layer.close()
+    plain.close()
+
+
+def test_4bit_stream_of_the_tucker_workload():
+    """up_proj with 4-bit tensors: the core (K = 48 * 48) is streamed in its 4-bit form at 1, 3, 8 and 64 tokens."""
+    spec, _ = wl.baseline_spec(2)
+    ts = wl.make_tensors(spec, 2)
+    layer = make_layer(spec, ts, 64, flags=tn.TN_FLAG_QUANT_MXFP4)
+    core_params = int(np.prod(spec.tensor_shapes()[0]))
+    assert layer.query(tn.TN_QUERY_QUANT_STREAM_BYTES) >= core_params * 17 // 32
+    w_q = O.dense_weight(spec.format, O.mxfp4_dequantized(ts), len(spec.out_modes))
+    for tokens in (1, 2, 3, 8, 64):
+        x = wl.make_x(spec, tokens, 2)
+        err = O.rel_max_err(to_host(layer(to_dev(x, "bf16"))), O.apply_linear(w_q, x))
+        assert err <= TOL["bf16"], (tokens, err)
+    layer.close()
+
+
+@pytest.mark.parametrize("flags_b", [tn.TN_FLAG_QUANT_MXFP4, 0])
+def test_two_quantised_layers_in_one_call(flags_b):
+    """tn_linear_forward2 on two up_proj-shaped layers: both with 4-bit tensors (one launch of the 4-bit decode
+    kernel serves both), and one with, one without (each takes its own launch). Results equal tn_linear_forward's."""
+    spec, _ = wl.baseline_spec(2)
+    ta, tb = wl.make_tensors(spec, 2, instance=0), wl.make_tensors(spec, 2, instance=1)
+    la = make_layer(spec, ta, 64, flags=tn.TN_FLAG_QUANT_MXFP4)
+    lb = make_layer(spec, tb, 64, flags=flags_b)
+    wa = O.dense_weight(spec.format, O.mxfp4_dequantized(ta), len(spec.out_modes))
+    wb = O.dense_weight(spec.format, O.mxfp4_dequantized(tb) if flags_b else tb, len(spec.out_modes))
+    for tokens in (1, 2, 5, 40):
+        x = wl.make_x(spec, tokens, 2)
+        xd = to_dev(x, "bf16")
+        ya, yb = tn.forward2(la, lb, xd)
+        torch.cuda.synchronize()
+        for y, w, layer in ((ya, wa, la), (yb, wb, lb)):
+            err = O.rel_max_err(to_host(y), O.apply_linear(w, x))
+            assert err <= TOL["bf16"], (tokens, err)
+            assert torch.equal(y, layer(xd)), tokens
+    la.close()
+    lb.close()
