@@ -560,15 +560,16 @@ struct Chain2Item {
     bf16x8 inf[R1T][K1S], ba[K1S], bb[C2T][KS2];
     int o_lane[C2T];             // offset of the index this lane holds one value of (c2 when RUN_C1; else c1, entry 0 only)
     int o_run[C2T][4];           // offsets of the runs of 4 it holds in its registers (c1 when RUN_C1, entries [0][q]; else c2)
-    int t, ct1;
+    int t, ct1, j0;              // the item covers the c2 tiles j0 .. j0 + C2T - 1
 
-    __device__ __forceinline__ void load(const Chain2Args& c, int token, int tile) {
+    __device__ __forceinline__ void load(const Chain2Args& c, int token, int tile, int first_c2_tile = 0) {
         const bf16_t* In = static_cast<const bf16_t*>(c.In);
         const bf16_t* Ba = static_cast<const bf16_t*>(c.Ba);
         const bf16_t* Bbf = static_cast<const bf16_t*>(c.Bbf);
         const int lane = threadIdx.x & 63, lrow = lane & 31, lhalf = lane >> 5;
         t = token;
         ct1 = tile;
+        j0 = first_c2_tile;
         const bf16_t* in_t = In + int64_t(t) * c.in_tok_stride;
         // straight-line loads from clamped addresses; what lies outside the input is replaced by zeros later
 #pragma unroll
@@ -587,11 +588,11 @@ struct Chain2Item {
         for (int j = 0; j < C2T; ++j)
 #pragma unroll
             for (int sk = 0; sk < KS2; ++sk)
-                bb[j][sk] = *reinterpret_cast<const bf16x8*>(Bbf + (int64_t(j) * KS2 + sk) * 512 + lane * 8);
+                bb[j][sk] = *reinterpret_cast<const bf16x8*>(Bbf + (int64_t(j0 + j) * KS2 + sk) * 512 + lane * 8);
         // output offsets come in aligned runs of 8 along the direction the pieces run (checked by the planner)
         if (RUN_C1) {
 #pragma unroll
-            for (int j = 0; j < C2T; ++j) o_lane[j] = c.off2[min(32 * j + lrow, c.C2 - 1)];
+            for (int j = 0; j < C2T; ++j) o_lane[j] = c.off2[min(32 * (j0 + j) + lrow, c.C2 - 1)];
 #pragma unroll
             for (int q = 0; q < 4; ++q) o_run[0][q] = c.off1[min(32 * ct1 + 8 * q, c.C1 - 1)] + 4 * lhalf;
         } else {
@@ -599,7 +600,7 @@ struct Chain2Item {
 #pragma unroll
             for (int j = 0; j < C2T; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) o_run[j][q] = c.off2[min(32 * j + 8 * q, c.C2 - 1)] + 4 * lhalf;
+                for (int q = 0; q < 4; ++q) o_run[j][q] = c.off2[min(32 * (j0 + j) + 8 * q, c.C2 - 1)] + 4 * lhalf;
         }
     }
 
@@ -631,7 +632,7 @@ struct Chain2Item {
         bf16_t* out_t = out + int64_t(t) * c.out_tok_stride;
 #pragma unroll
         for (int j = 0; j < C2T; ++j) {
-            if (32 * j >= c.C2) continue;                                  // wave-uniform
+            if (32 * (j0 + j) >= c.C2) continue;                           // wave-uniform
             floatx16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -639,12 +640,12 @@ struct Chain2Item {
             for (int sk = 0; sk < KS2; ++sk)
                 acc = RUN_C1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(zb[sk], bb[j][sk], acc, 0, 0, 0)
                              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j][sk], zb[sk], acc, 0, 0, 0);
-            // RUN_C1: lane l holds c2 = 32j + l%32 and, in registers 4q..4q+3, c1 = 32*ct1 + 8q + 4*(l/32) + 0..3
-            // else  : lane l holds c1 = 32*ct1 + l%32 and c2 = 32j + 8q + 4*(l/32) + 0..3
-            const bool lane_ok = RUN_C1 ? 32 * j + lrow < c.C2 : 32 * ct1 + lrow < c.C1;
+            // RUN_C1: lane l holds c2 = 32(j0+j) + l%32 and, in registers 4q..4q+3, c1 = 32*ct1 + 8q + 4*(l/32) + 0..3
+            // else  : lane l holds c1 = 32*ct1 + l%32 and c2 = 32(j0+j) + 8q + 4*(l/32) + 0..3
+            const bool lane_ok = RUN_C1 ? 32 * (j0 + j) + lrow < c.C2 : 32 * ct1 + lrow < c.C1;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const bool run_ok = RUN_C1 ? 32 * ct1 + 8 * q < c.C1 : 32 * j + 8 * q < c.C2;      // runs of 8 are whole
+                const bool run_ok = RUN_C1 ? 32 * ct1 + 8 * q < c.C1 : 32 * (j0 + j) + 8 * q < c.C2;   // runs of 8 are whole
                 if (!lane_ok || !run_ok) continue;
                 const int base = RUN_C1 ? o_lane[j] + o_run[0][q] : o_lane[0] + o_run[j][q];
                 bf16x4 pk;
@@ -667,6 +668,22 @@ __global__ void __launch_bounds__(256) step_chain2_small_kernel(Chain2Args c0, C
     if (item >= c.tokens * c.c1_tiles) return;
     Chain2Item<R1T, K1S, C2T, RUN_C1> it;
     it.load(c, item / c.c1_tiles, item % c.c1_tiles);
+    it.compute(c, static_cast<bf16_t*>(c.Out));
+}
+
+// The same with one wave per (token, c1 tile, c2 tile): five times as many items for the out-factor pair of the
+// up_proj layer (each repeats the first contraction, 18 MFMAs, and requests 30 KB instead of 54), one wave per
+// workgroup so that they spread over as many compute units. A call of a few tokens is one memory round trip and a
+// short MFMA chain either way: what this form cuts is the bytes each CU's memory pipeline delivers in that trip.
+template <int R1T, int K1S, int RUN_C1>
+__global__ void __launch_bounds__(64) step_chain2_fine_kernel(Chain2Args c0, Chain2Args c1) {
+    const Chain2Args& c = blockIdx.y ? c1 : c0;
+    const int c2_tiles = (c.C2 + 31) / 32;
+    const int item = blockIdx.x;
+    if (item >= c.tokens * c.c1_tiles * c2_tiles) return;
+    const int j = item % c2_tiles, rest = item / c2_tiles;
+    Chain2Item<R1T, K1S, 1, RUN_C1> it;
+    it.load(c, rest / c.c1_tiles, rest % c.c1_tiles, j);
     it.compute(c, static_cast<bf16_t*>(c.Out));
 }
 

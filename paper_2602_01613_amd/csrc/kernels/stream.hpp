@@ -375,6 +375,92 @@ __device__ __forceinline__ void split_run_q4(const StepArgs& a, float* partial, 
     split_finish<TM, NW>(a, partial, red, acc, row0, cb, split, nsplit, rows_pad);
 }
 
+// The 4-bit stream for a few rows (decode, verification batches): the rows of A that the workgroup's split needs are
+// copied to LDS once (rows * K-range bf16 values, x_ld elements per row), so that the loop's only vector-memory
+// traffic is the stream itself: a ring of D pieces per wave is requested up front and each slot is requested again
+// as soon as it has been multiplied, while the other operand comes from LDS on its own counter. With A fetched
+// from memory (four 16-byte loads per piece and row tile, behind which the in-order return of loads makes the
+// stream wait) the same launches ran at a third of the bandwidth.
+template <int AMODE, int NW>
+__global__ void __launch_bounds__(NW * 64) step_split_q4_lds_kernel(StepArgs a, float* partial, int ksteps_per_split,
+                                                                    int x_ld) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    float* red = reinterpret_cast<float*>(dyn_smem);                           // NW x 1024
+    bf16_t* xs = reinterpret_cast<bf16_t*>(dyn_smem + NW * 1024 * sizeof(float));      // [rows][x_ld]
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    const uint4* Q = static_cast<const uint4*>(a.B);
+    const unsigned char* S = static_cast<const unsigned char*>(a.Bs);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cb = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
+    const int n_chunks = a.Kp >> 6;
+    const int ch_begin = split * (ksteps_per_split >> 2);
+    const int ch_end = min(n_chunks, ch_begin + (ksteps_per_split >> 2));
+    const int rows = int(a.total_rows);                                        // <= 32: one row tile
+    constexpr int D = 8;
+    uint4 q[D];
+    unsigned sc[D];
+    const int64_t piece0 = int64_t(cb) * n_chunks * 64 + lane;
+    // addresses past the split re-read its last piece (never used)
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+        const int ch = min(ch_begin + wave + NW * u, ch_end - 1);
+        q[u] = Q[piece0 + int64_t(ch) * 64];
+        sc[u] = S[piece0 + int64_t(ch) * 64];
+    }
+    // the rows of A over the split's k range, zero past K
+    {
+        const int k0 = ch_begin * 64, kn = (ch_end - ch_begin) * 64;
+        const int pieces_per_row = kn >> 3;
+        for (int e = tid; e < rows * pieces_per_row; e += NW * 64) {
+            const int g = e / pieces_per_row, k = k0 + 8 * (e - g * pieces_per_row);
+            const uint32_t t = uint32_t(g) / a.R, r = uint32_t(g) - t * a.R;
+            const int64_t base = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+            bf16x8 v;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = bf16_t(0.f);
+            if (AMODE == 0) {
+                if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + base + k);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (k + i < a.K) v[i] = A[base + (a.acol ? a.acol[k + i] : k + i)];
+            }
+            *reinterpret_cast<bf16x8*>(xs + int64_t(g) * x_ld + (k - k0)) = v;
+        }
+    }
+    __syncthreads();
+    floatx16 acc[1];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[0][v] = 0.f;
+    const bool tv = (lane & 31) < rows;
+    const bf16_t* xrow = xs + int64_t(tv ? (lane & 31) : 0) * x_ld + 32 * (lane >> 5);
+    bf16x8 zero;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) zero[i] = bf16_t(0.f);
+    for (int idx0 = 0; ch_begin + wave + NW * idx0 < ch_end; idx0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int ch = ch_begin + wave + NW * (idx0 + u);
+            if (ch < ch_end) {                                                 // wave-uniform
+                bf16x8 w[4];
+                q4_dequant_block(q[u], sc[u], w);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const bf16x8 x = tv ? *reinterpret_cast<const bf16x8*>(xrow + (ch - ch_begin) * 64 + 8 * ks) : zero;
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ks], x, acc[0], 0, 0, 0);
+                }
+            }
+            const int nxt = ch + NW * D;
+            if (nxt < ch_end) {                                                // wave-uniform
+                q[u] = Q[piece0 + int64_t(nxt) * 64];
+                sc[u] = S[piece0 + int64_t(nxt) * 64];
+            }
+        }
+    }
+    split_finish<1, NW>(a, partial, red, acc, 0u, cb, split, nsplit, 32u);
+}
+
 template <int TM, int AMODE, int NW>
 __global__ void __launch_bounds__(NW * 64) step_split_q4_kernel(StepArgs a, float* partial, int ksteps_per_split) {
     __shared__ float red[NW * TM * 1024];

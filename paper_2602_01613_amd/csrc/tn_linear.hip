@@ -254,6 +254,7 @@ struct SplitCfg {
 };
 
 constexpr int64_t kMaxPartialBytes = int64_t(64) << 20;
+constexpr size_t kQ4LdsRowBytes = 120 * 1024;     // rows of A a 4-bit split-K workgroup may keep in LDS
 
 // Decide whether a launch of `rows` rows runs on the split-K kernel: when the tiled kernel would
 // start fewer workgroups than there are compute units and K is long enough to share out.
@@ -275,6 +276,14 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     int want = int(std::max<int64_t>(1, target_wgs / base));
     int max_split = std::max(1, nks / (2 * c.nw));      // at least 2 k-steps per wave
     c.nsplit = std::min(want, max_split);
+    if (s.q4_codes && c.tm == 1 && c.row_tiles == 1) {
+        // 4-bit stream, one row tile: enough splits that the rows' share of A fits in LDS (at least two pieces of 64 k
+        // per wave stay in a split)
+        const int min_ksteps = 8 * c.nw;
+        while (size_t(rows) * size_t(round_up((nks + c.nsplit - 1) / c.nsplit, 4) * 16 + 8) * 2 > kQ4LdsRowBytes &&
+               (nks + c.nsplit) / (c.nsplit + 1) >= min_ksteps)
+            ++c.nsplit;
+    }
     for (;;) {
         c.ksteps_per_split = (nks + c.nsplit - 1) / c.nsplit;
         if (s.q4_codes) c.ksteps_per_split = round_up(c.ksteps_per_split, 4);    // the 4-bit stream comes in pieces of 64 k
@@ -390,7 +399,17 @@ int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, cons
             // the launch is a stream of the packed tensor: read its 4-bit form
             a.B = s.q4_codes;
             a.Bs = s.q4_scales;
-            if (sc.tm == 1)
+            const int x_ld = sc.ksteps_per_split * 16 + 8;
+            const size_t x_bytes = size_t(rows) * size_t(x_ld) * sizeof(bf16_t);
+            if (sc.row_tiles == 1 && sc.tm == 1 && x_bytes <= kQ4LdsRowBytes) {
+                // few rows: their part of A fits in LDS next to the reduction buffer
+                using lds_t = void (*)(StepArgs, float*, int, int);
+                const lds_t kl = sc.nw == 8 ? (s.amode == 0 ? step_split_q4_lds_kernel<0, 8> : step_split_q4_lds_kernel<1, 8>)
+                                            : (s.amode == 0 ? step_split_q4_lds_kernel<0, 4> : step_split_q4_lds_kernel<1, 4>);
+                hipLaunchKernelGGL(kl, sgrid, dim3(uint32_t(sc.nw * 64)), size_t(sc.nw) * 4096 + x_bytes, st, a, part,
+                                   sc.ksteps_per_split, x_ld);
+                k = nullptr;
+            } else if (sc.tm == 1)
                 k = sc.nw == 8 ? (s.amode == 0 ? step_split_q4_kernel<1, 0, 8> : step_split_q4_kernel<1, 1, 8>)
                                : (s.amode == 0 ? step_split_q4_kernel<1, 0, 4> : step_split_q4_kernel<1, 1, 4>);
             else
@@ -402,7 +421,7 @@ int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, cons
         else
             k = sc.nw == 8 ? (s.amode == 0 ? step_split_kernel<2, 0, 8> : step_split_kernel<2, 1, 8>)
                            : (s.amode == 0 ? step_split_kernel<2, 0, 4> : step_split_kernel<2, 1, 4>);
-        hipLaunchKernelGGL(k, sgrid, dim3(uint32_t(sc.nw * 64)), 0, st, a, part, sc.ksteps_per_split);
+        if (k) hipLaunchKernelGGL(k, sgrid, dim3(uint32_t(sc.nw * 64)), 0, st, a, part, sc.ksteps_per_split);
         if (sc.nsplit > 1) {
             int64_t total = rows * s.plan.C;
             uint32_t blocks = uint32_t(std::min<int64_t>((total + 255) / 256, 2048));
@@ -1247,6 +1266,8 @@ bool chain2_small_applies(const tn_linear_s* h, const DevStep& s1, int64_t token
     return tokens * ((s1.plan.C + 31) / 32) <= int64_t(h->num_cus) * 4 && !(h->flags & TN_FLAG_NO_DECODE_FUSION);
 }
 
+constexpr int64_t kChain2FineMaxItems = 64;      // (token, c1 tile) items up to which every c2 tile gets a wave of its own
+
 // One launch for the pair of one layer (p1 == nullptr) or of two layers with the same instantiation.
 int launch_chain2_small(const DevStep& s1, const Chain2Args& p0, const Chain2Args* p1, hipStream_t st) {
     using k_t = void (*)(Chain2Args, Chain2Args);
@@ -1255,6 +1276,17 @@ int launch_chain2_small(const DevStep& s1, const Chain2Args& p0, const Chain2Arg
                                  step_chain2_small_kernel<2, 5, 2, 0>, step_chain2_small_kernel<2, 5, 2, 1>};
     int64_t items = int64_t(p0.tokens) * p0.c1_tiles;
     if (p1) items = std::max(items, int64_t(p1->tokens) * p1->c1_tiles);
+    if (items <= kChain2FineMaxItems) {
+        // few items: one wave per (token, c1 tile, c2 tile)
+        static const k_t fine[6] = {step_chain2_fine_kernel<3, 6, 0>, step_chain2_fine_kernel<3, 6, 1>,
+                                    step_chain2_fine_kernel<2, 8, 0>, step_chain2_fine_kernel<2, 8, 1>,
+                                    step_chain2_fine_kernel<2, 5, 0>, step_chain2_fine_kernel<2, 5, 1>};
+        int64_t fine_items = int64_t(p0.tokens) * p0.c1_tiles * ((p0.C2 + 31) / 32);
+        if (p1) fine_items = std::max(fine_items, int64_t(p1->tokens) * p1->c1_tiles * ((p1->C2 + 31) / 32));
+        hipLaunchKernelGGL(fine[s1.chain_cfg * 2 + s1.chain_run_c1], dim3(uint32_t(fine_items), p1 ? 2 : 1), dim3(64), 0, st, p0,
+                           p1 ? *p1 : p0);
+        return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
+    }
     hipLaunchKernelGGL(small[s1.chain_cfg * 2 + s1.chain_run_c1], dim3(uint32_t((items + 3) / 4), p1 ? 2 : 1), dim3(256), 0, st,
                        p0, p1 ? *p1 : p0);
     return hipGetLastError() == hipSuccess ? TN_OK : TN_ERR_HIP;
@@ -1438,6 +1470,15 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK) rc = launch_chain2_split(nullptr, nullptr, nullptr);
+    if (rc == TN_OK) {
+        using lds_t = void (*)(StepArgs, float*, int, int);
+        const lds_t q4k[4] = {step_split_q4_lds_kernel<0, 8>, step_split_q4_lds_kernel<1, 8>, step_split_q4_lds_kernel<0, 4>,
+                              step_split_q4_lds_kernel<1, 4>};
+        for (lds_t kq : q4k)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kq), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(8 * 4096 + kQ4LdsRowBytes)) != hipSuccess)
+                rc = TN_ERR_HIP;
+    }
     if (rc == TN_OK &&
         (hipFuncSetAttribute(reinterpret_cast<const void*>(&step_pair_kernel<kPairStages, kPairBar>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
