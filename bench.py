@@ -436,6 +436,34 @@ def pair_record(spec, config_id, args, instances=8):
     return out
 
 
+def quant_record(spec, config_id, args):
+    """A layer with 4-bit tensors (TN_FLAG_QUANT_MXFP4) at decode sizes: one-token calls as a captured graph over
+    distinct copies and eight-token calls, reading the 4-bit stream, next to the same quantised layer made to
+    multiply with its bf16 copies (TN_FLAG_NO_Q4_STREAM); both checked against the oracle applied to the
+    dequantised tensors."""
+    import oracle as O
+    import paper_2602_01613_amd as tn
+    out = {"workload": f"{spec.name} with 4-bit tensors (blocks of 32, power-of-two scale, E2M1)"}
+    w_q = None
+    for name, flags in (("stream_4bit", tn.TN_FLAG_QUANT_MXFP4), ("bf16_copies", tn.TN_FLAG_QUANT_MXFP4 | tn.TN_FLAG_NO_Q4_STREAM)):
+        lb = LayerBench(spec, config_id, 64, flags=flags)
+        g = lb.decode_graph(1, args.graph_instances)
+        rec = {"decode_1tok_graph_us_per_layer": g["us_per_layer_call"], "replay_equals_eager": g["replay_equals_eager"],
+               "verify_8tok_us": lb.small_call(8, detail=False)["us_per_call"],
+               "stream_bytes": lb.layer.query(tn.TN_QUERY_QUANT_STREAM_BYTES)}
+        if rec["stream_bytes"]:
+            rec["stream_GBps"] = rec["stream_bytes"] / g["us_per_layer_call"] / 1e3
+        if w_q is None:
+            w_q = O.dense_weight(spec.format, O.mxfp4_dequantized(lb.tensors), len(spec.out_modes))
+        x8 = lb.x[:8].contiguous()
+        y8 = lb.layer.forward(x8).float().cpu().numpy().astype("float64")
+        rec["rel_max_err_vs_oracle_8tok"] = O.rel_max_err(y8, O.apply_linear(w_q, x8.float().cpu().numpy().astype("float64")))
+        out[name] = rec
+        lb.close()
+    out["speedup_1tok"] = out["bf16_copies"]["decode_1tok_graph_us_per_layer"] / out["stream_4bit"]["decode_1tok_graph_us_per_layer"]
+    return out
+
+
 def gradient_record(spec, config_id, tokens, reps=3):
     """tn_linear_param_gradients (gradients of a loss with respect to every parameter tensor, Section 3.4) on a
     trainable copy of the layer: tokens/s of one call (forward with saved intermediates + backward) and the FLOP/s of
@@ -798,6 +826,10 @@ def main() -> int:
             pending_cpu.append((name, sub_keep))
         if time.perf_counter() - t_start <= args.time_budget_s:
             configs["tucker_gate_up_pair"] = pair_record(wl.baseline_spec(2)[0], 2, args)
+        if time.perf_counter() - t_start <= args.time_budget_s:
+            configs["quantised_4bit_decode"] = {
+                "tucker_up_proj": quant_record(wl.baseline_spec(2)[0], 2, args),
+                "dense_q_proj": quant_record(wl.stack_spec(wl.FORMAT_DENSE, 5120, 8192, 0, "dense_q_proj"), 4, args)}
         if time.perf_counter() - t_start <= args.time_budget_s:
             configs["param_gradients"] = {"tt_q_proj": gradient_record(wl.baseline_spec(1)[0], 1, 1024),
                                           "tucker_up_proj": gradient_record(wl.baseline_spec(2)[0], 2, 1024)}
