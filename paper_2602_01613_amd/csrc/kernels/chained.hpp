@@ -687,8 +687,8 @@ __global__ void __launch_bounds__(64) step_chain2_fine_kernel(Chain2Args c0, Cha
     it.compute(c, static_cast<bf16_t*>(c.Out));
 }
 
-// Q4: the wide step's tensor is read in its 4-bit form (see q4_stream_pack_kernel): KPW then counts pieces of 64 k
-// per wave (one 16-byte load of codes and one scale byte per lane and piece) instead of k-steps.
+// KPW: pieces of 64 k per wave. Q4: the wide step's tensor is read in its 4-bit form (see q4_stream_pack_kernel), one
+// 16-byte load of codes and one scale byte per lane and piece instead of four fragment loads.
 template <int K1S, int RUN_C1, int KPW, int Q4>
 __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, StepArgs a0, int z_bytes0, Chain2Args c1,
                                                                 StepArgs a1, int z_bytes1) {
@@ -717,8 +717,10 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, S
     Chain2Item<2, K1S, 2, RUN_C1> item;
     if (has_item) item.load(c, wave / c.c1_tiles, wave % c.c1_tiles);
     __builtin_amdgcn_sched_barrier(0);
-    // ---- 2. the wave's share of the parameter stream: k-steps (pieces of 64 k when Q4) wave, wave + 8, ...
-    bf16x8 bf[Q4 ? 1 : KPW];
+    // ---- 2. the wave's share of the parameter stream: pieces of 64 k (four k-steps) wave, wave + 8, ..., the same
+    //         assignment and order of summation as step_split_lds_kernel, so that a call gives the same bits whether
+    //         it runs fused or as separate launches
+    bf16x8 bf[Q4 ? 1 : KPW][4];
     uint4 qc[Q4 ? KPW : 1];
     unsigned qs[Q4 ? KPW : 1];
     const int n_chunks = nks >> 2;
@@ -734,7 +736,11 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, S
     } else {
         const bf16_t* bp = B + (int64_t(cb) * nks) * 512 + lane * 8;
 #pragma unroll
-        for (int u = 0; u < KPW; ++u) bf[u] = *reinterpret_cast<const bf16x8*>(bp + int64_t(min(wave + NW * u, nks - 1)) * 512);
+        for (int u = 0; u < KPW; ++u) {
+            const int ch = min(wave + NW * u, n_chunks - 1);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bf[u][ks] = *reinterpret_cast<const bf16x8*>(bp + (int64_t(ch) * 4 + ks) * 512);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     // ---- 3. the chained pair for the item, into LDS
@@ -766,13 +772,17 @@ __global__ void __launch_bounds__(512) step_chain2_split_kernel(Chain2Args c0, S
             }
         } else {
 #pragma unroll
-        for (int u = 0; u < KPW; ++u) {
-            const int ks = wave + NW * u;
-            if (ks < nks) {                                                // wave-uniform
-                const bf16x8 x = (tv && 16 * ks + 8 * lhalf < a.K) ? *reinterpret_cast<const bf16x8*>(zrow + 16 * ks) : zero;
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u], x, acc, 0, 0, 0);
+            for (int u = 0; u < KPW; ++u) {
+                const int ch = wave + NW * u;
+                if (ch < n_chunks) {                                           // wave-uniform
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const int k = 64 * ch + 16 * ks;
+                        const bf16x8 x = (tv && k + 8 * lhalf < a.K) ? *reinterpret_cast<const bf16x8*>(zrow + k) : zero;
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[u][ks], x, acc, 0, 0, 0);
+                    }
+                }
             }
-        }
         }
     }
 #pragma unroll

@@ -375,39 +375,47 @@ __device__ __forceinline__ void split_run_q4(const StepArgs& a, float* partial, 
     split_finish<TM, NW>(a, partial, red, acc, row0, cb, split, nsplit, rows_pad);
 }
 
-// The 4-bit stream for a few rows (decode, verification batches): the rows of A that the workgroup's split needs are
-// copied to LDS once (rows * K-range bf16 values, x_ld elements per row), so that the loop's only vector-memory
-// traffic is the stream itself: a ring of D pieces per wave is requested up front and each slot is requested again
-// as soon as it has been multiplied, while the other operand comes from LDS on its own counter. With A fetched
-// from memory (four 16-byte loads per piece and row tile, behind which the in-order return of loads makes the
-// stream wait) the same launches ran at a third of the bandwidth.
-template <int AMODE, int NW>
-__global__ void __launch_bounds__(NW * 64) step_split_q4_lds_kernel(StepArgs a, float* partial, int ksteps_per_split,
-                                                                    int x_ld) {
+// Split-K with the rows of A in LDS, for launches of one row tile (up to 32 * TM rows: decode, verification
+// batches; the host uses TM = 1 only: with two row tiles the splits needed to fit the rows cost more than they save). The rows of A that the workgroup's split needs are copied to LDS once (rows * K-range bf16
+// values, x_ld elements per row; the host raises the number of splits until they fit), so that the loop's only
+// vector-memory traffic is the parameter stream: a ring of D pieces of 64 k per wave is requested up front and each
+// slot is requested again as soon as it has been multiplied, while the other operand comes from LDS on its own
+// counter. With A fetched from memory (one 16-byte gather per k-step and row tile, behind which the in-order return
+// of loads makes the stream wait) the 4-bit launches ran at a third of the bandwidth. Q4: the stream is the 4-bit form (see q4_stream_pack_kernel), else the fragment-major bf16 tensor.
+// The reduction buffer shares the LDS of the rows (they are dead by then).
+template <int TM, int AMODE, int NW, int Q4>
+__global__ void __launch_bounds__(NW * 64) step_split_lds_kernel(StepArgs a, float* partial, int ksteps_per_split,
+                                                                 int x_ld) {
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-    float* red = reinterpret_cast<float*>(dyn_smem);                           // NW x 1024
-    bf16_t* xs = reinterpret_cast<bf16_t*>(dyn_smem + NW * 1024 * sizeof(float));      // [rows][x_ld]
+    float* red = reinterpret_cast<float*>(dyn_smem);                           // NW x TM x 1024, after the loop
+    bf16_t* xs = reinterpret_cast<bf16_t*>(dyn_smem);                          // [rows][x_ld], during the loop
     const bf16_t* A = static_cast<const bf16_t*>(a.A);
-    const uint4* Q = static_cast<const uint4*>(a.B);
-    const unsigned char* S = static_cast<const unsigned char*>(a.Bs);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cb = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
     const int n_chunks = a.Kp >> 6;
     const int ch_begin = split * (ksteps_per_split >> 2);
     const int ch_end = min(n_chunks, ch_begin + (ksteps_per_split >> 2));
-    const int rows = int(a.total_rows);                                        // <= 32: one row tile
-    constexpr int D = 8;
-    uint4 q[D];
-    unsigned sc[D];
-    const int64_t piece0 = int64_t(cb) * n_chunks * 64 + lane;
-    // addresses past the split re-read its last piece (never used)
+    const int rows = int(a.total_rows);                                        // <= 32 * TM: one row tile
+    constexpr int D = Q4 ? 8 : 4;
+    uint4 q[Q4 ? D : 1];
+    unsigned sc[Q4 ? D : 1];
+    bf16x8 bf[Q4 ? 1 : D][4];
+    const uint4* Q = static_cast<const uint4*>(a.B) + int64_t(cb) * n_chunks * 64 + lane;
+    const unsigned char* S = static_cast<const unsigned char*>(a.Bs) + int64_t(cb) * n_chunks * 64 + lane;
+    const bf16_t* Bp = static_cast<const bf16_t*>(a.B) + int64_t(cb) * n_chunks * 2048 + lane * 8;
+    auto request = [&](int u, int ch) {
+        if (Q4) {
+            q[Q4 ? u : 0] = Q[int64_t(ch) * 64];
+            sc[Q4 ? u : 0] = S[int64_t(ch) * 64];
+        } else {
 #pragma unroll
-    for (int u = 0; u < D; ++u) {
-        const int ch = min(ch_begin + wave + NW * u, ch_end - 1);
-        q[u] = Q[piece0 + int64_t(ch) * 64];
-        sc[u] = S[piece0 + int64_t(ch) * 64];
-    }
+            for (int ks = 0; ks < 4; ++ks) bf[Q4 ? 0 : u][ks] = *reinterpret_cast<const bf16x8*>(Bp + (int64_t(ch) * 4 + ks) * 512);
+        }
+    };
+    // pieces past the split re-read its last piece (never used)
+#pragma unroll
+    for (int u = 0; u < D; ++u) request(u, min(ch_begin + wave + NW * u, ch_end - 1));
     // the rows of A over the split's k range, zero past K
     {
         const int k0 = ch_begin * 64, kn = (ch_end - ch_begin) * 64;
@@ -430,11 +438,19 @@ __global__ void __launch_bounds__(NW * 64) step_split_q4_lds_kernel(StepArgs a, 
         }
     }
     __syncthreads();
-    floatx16 acc[1];
+    floatx16 acc[TM];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[0][v] = 0.f;
-    const bool tv = (lane & 31) < rows;
-    const bf16_t* xrow = xs + int64_t(tv ? (lane & 31) : 0) * x_ld + 32 * (lane >> 5);
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    // lane l supplies row 32i + l%32 and, in k-step u of a piece, k = 64*piece + (Q4 ? 32*(l/32) + 8u : 16u + 8*(l/32)) ..
+    bool tv[TM];
+    const bf16_t* xrow[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        tv[i] = 32 * i + (lane & 31) < rows;
+        xrow[i] = xs + int64_t(tv[i] ? 32 * i + (lane & 31) : 0) * x_ld + (Q4 ? 32 : 8) * (lane >> 5);
+    }
     bf16x8 zero;
 #pragma unroll
     for (int i = 0; i < 8; ++i) zero[i] = bf16_t(0.f);
@@ -444,21 +460,27 @@ __global__ void __launch_bounds__(NW * 64) step_split_q4_lds_kernel(StepArgs a, 
             const int ch = ch_begin + wave + NW * (idx0 + u);
             if (ch < ch_end) {                                                 // wave-uniform
                 bf16x8 w[4];
-                q4_dequant_block(q[u], sc[u], w);
+                if (Q4) {
+                    q4_dequant_block(q[Q4 ? u : 0], sc[Q4 ? u : 0], w);
+                } else {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const bf16x8 x = tv ? *reinterpret_cast<const bf16x8*>(xrow + (ch - ch_begin) * 64 + 8 * ks) : zero;
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ks], x, acc[0], 0, 0, 0);
+                    for (int ks = 0; ks < 4; ++ks) w[ks] = bf[Q4 ? 0 : u][ks];
                 }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const bf16x8 x = tv[i] ? *reinterpret_cast<const bf16x8*>(xrow[i] + (ch - ch_begin) * 64 + (Q4 ? 8 : 16) * ks)
+                                               : zero;
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ks], x, acc[i], 0, 0, 0);
+                    }
             }
             const int nxt = ch + NW * D;
-            if (nxt < ch_end) {                                                // wave-uniform
-                q[u] = Q[piece0 + int64_t(nxt) * 64];
-                sc[u] = S[piece0 + int64_t(nxt) * 64];
-            }
+            if (nxt < ch_end) request(u, nxt);                                 // wave-uniform
         }
     }
-    split_finish<1, NW>(a, partial, red, acc, 0u, cb, split, nsplit, 32u);
+    __syncthreads();                                                           // the rows are dead: their LDS becomes red
+    split_finish<TM, NW>(a, partial, red, acc, 0u, cb, split, nsplit, uint32_t(32 * TM));
 }
 
 template <int TM, int AMODE, int NW>

@@ -250,11 +250,17 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
 struct SplitCfg {
     bool use = false;
     int tm = 1, nw = 4, row_tiles = 0, col_blocks = 0, nsplit = 1, ksteps_per_split = 0;
+    bool lds_rows = false;        // one row tile: the kernel that keeps the rows of A in LDS
     int64_t partial_bytes = 0;
 };
 
 constexpr int64_t kMaxPartialBytes = int64_t(64) << 20;
-constexpr size_t kQ4LdsRowBytes = 120 * 1024;     // rows of A a 4-bit split-K workgroup may keep in LDS
+constexpr size_t kSplitLdsRowBytes = 144 * 1024;  // rows of A a split-K workgroup may keep in LDS (the reduction reuses it)
+// Measured (dense 5120->8192 and 25600->5120, us per call, rows in LDS against rows gathered from memory): bf16 stream
+// 1 row 17.5 / 19.3 and 56.3 / 60.0 (captured graph over 16 copies), 8 rows 18.6 / 15.8 (same layer back to back), 64
+// rows (two row tiles, five splits to fit) 62.8 / 31.2; 4-bit stream 1 row 8.6 / 13.0, 8 rows 8.4 / 11.2, 64 rows
+// 56.7 / 26.1. Hence: one row tile only; a bf16 stream up to 4 rows, a 4-bit stream up to 32.
+constexpr int64_t kSplitLdsMaxBf16Rows = 4;
 
 // Decide whether a launch of `rows` rows runs on the split-K kernel: when the tiled kernel would
 // start fewer workgroups than there are compute units and K is long enough to share out.
@@ -276,17 +282,18 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     int want = int(std::max<int64_t>(1, target_wgs / base));
     int max_split = std::max(1, nks / (2 * c.nw));      // at least 2 k-steps per wave
     c.nsplit = std::min(want, max_split);
-    if (s.q4_codes && c.tm == 1 && c.row_tiles == 1) {
-        // 4-bit stream, one row tile: enough splits that the rows' share of A fits in LDS (at least two pieces of 64 k
-        // per wave stay in a split)
+    if (c.row_tiles == 1 && c.tm == 1 && nks % 4 == 0 && (s.q4_codes || rows <= kSplitLdsMaxBf16Rows)) {
+        // the kernel that keeps the rows of A in LDS: enough splits that the rows' share of A fits (at least two
+        // pieces of 64 k per wave stay in a split), and whole pieces of 64 k per split
+        c.lds_rows = true;
         const int min_ksteps = 8 * c.nw;
-        while (size_t(rows) * size_t(round_up((nks + c.nsplit - 1) / c.nsplit, 4) * 16 + 8) * 2 > kQ4LdsRowBytes &&
+        while (size_t(rows) * size_t(round_up((nks + c.nsplit - 1) / c.nsplit, 4) * 16 + 8) * 2 > kSplitLdsRowBytes &&
                (nks + c.nsplit) / (c.nsplit + 1) >= min_ksteps)
             ++c.nsplit;
     }
     for (;;) {
         c.ksteps_per_split = (nks + c.nsplit - 1) / c.nsplit;
-        if (s.q4_codes) c.ksteps_per_split = round_up(c.ksteps_per_split, 4);    // the 4-bit stream comes in pieces of 64 k
+        if (s.q4_codes || c.lds_rows) c.ksteps_per_split = round_up(c.ksteps_per_split, 4);    // pieces of 64 k
         c.nsplit = (nks + c.ksteps_per_split - 1) / c.ksteps_per_split;      // no empty split
         c.partial_bytes = c.nsplit > 1 ? int64_t(c.nsplit) * c.row_tiles * 32 * c.tm * s.Cp * 4 : 0;
         if (c.partial_bytes <= kMaxPartialBytes || c.nsplit == 1) break;
@@ -370,6 +377,18 @@ int launch_pingpong(const tn_linear_s* h, const DevStep& s, const StepArgs& a, i
     return TN_OK;
 }
 
+// Instantiations of the split-K kernel that keeps the rows of A in LDS (one row tile of up to 32 rows): index
+// (8 waves ? 4 : 0) + (gathered A ? 2 : 0) + (4-bit stream ? 1 : 0).
+using split_lds_t = void (*)(StepArgs, float*, int, int);
+constexpr int kSplitLdsKernels = 8;
+const split_lds_t* split_lds_kernels() {
+    static const split_lds_t lds[kSplitLdsKernels] = {
+        step_split_lds_kernel<1, 0, 4, 0>, step_split_lds_kernel<1, 0, 4, 1>, step_split_lds_kernel<1, 1, 4, 0>,
+        step_split_lds_kernel<1, 1, 4, 1>, step_split_lds_kernel<1, 0, 8, 0>, step_split_lds_kernel<1, 0, 8, 1>,
+        step_split_lds_kernel<1, 1, 8, 0>, step_split_lds_kernel<1, 1, 8, 1>};
+    return lds;
+}
+
 int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, const void* A, void* Out, int64_t tokens,
                 hipStream_t st) {
     StepArgs a;
@@ -394,22 +413,22 @@ int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, cons
         dim3 sgrid(uint32_t(sc.row_tiles), uint32_t(sc.col_blocks), uint32_t(sc.nsplit));
         float* part = static_cast<float*>(w.partial);
         using split_t = void (*)(StepArgs, float*, int);
-        split_t k;
-        if (s.q4_codes) {
+        split_t k = nullptr;
+        const int q4 = s.q4_codes ? 1 : 0;
+        if (q4) {
             // the launch is a stream of the packed tensor: read its 4-bit form
             a.B = s.q4_codes;
             a.Bs = s.q4_scales;
-            const int x_ld = sc.ksteps_per_split * 16 + 8;
-            const size_t x_bytes = size_t(rows) * size_t(x_ld) * sizeof(bf16_t);
-            if (sc.row_tiles == 1 && sc.tm == 1 && x_bytes <= kQ4LdsRowBytes) {
-                // few rows: their part of A fits in LDS next to the reduction buffer
-                using lds_t = void (*)(StepArgs, float*, int, int);
-                const lds_t kl = sc.nw == 8 ? (s.amode == 0 ? step_split_q4_lds_kernel<0, 8> : step_split_q4_lds_kernel<1, 8>)
-                                            : (s.amode == 0 ? step_split_q4_lds_kernel<0, 4> : step_split_q4_lds_kernel<1, 4>);
-                hipLaunchKernelGGL(kl, sgrid, dim3(uint32_t(sc.nw * 64)), size_t(sc.nw) * 4096 + x_bytes, st, a, part,
-                                   sc.ksteps_per_split, x_ld);
-                k = nullptr;
-            } else if (sc.tm == 1)
+        }
+        const int x_ld = sc.ksteps_per_split * 16 + 8;
+        const size_t x_bytes = size_t(rows) * size_t(x_ld) * sizeof(bf16_t);
+        if (sc.lds_rows && sc.tm == 1 && sc.row_tiles == 1 && sc.ksteps_per_split % 4 == 0 && x_bytes <= kSplitLdsRowBytes) {
+            // one row tile whose share of A fits in LDS
+            const size_t red_bytes = size_t(sc.nw) * sc.tm * 4096;
+            hipLaunchKernelGGL(split_lds_kernels()[(sc.nw == 8 ? 4 : 0) + (s.amode == 0 ? 0 : 2) + q4], sgrid,
+                               dim3(uint32_t(sc.nw * 64)), std::max(red_bytes, x_bytes), st, a, part, sc.ksteps_per_split, x_ld);
+        } else if (q4) {
+            if (sc.tm == 1)
                 k = sc.nw == 8 ? (s.amode == 0 ? step_split_q4_kernel<1, 0, 8> : step_split_q4_kernel<1, 1, 8>)
                                : (s.amode == 0 ? step_split_q4_kernel<1, 0, 4> : step_split_q4_kernel<1, 1, 4>);
             else
@@ -1326,13 +1345,12 @@ int launch_chain2(const tn_linear_s* h, const DevStep& s1, const DevStep& s2, co
 // register budget and every (token, column tile) item of the pair gets a wave of its own.
 constexpr int64_t kFusedDecodeMaxZBytes = 32 * 1024;
 constexpr size_t kFusedDecodeRedBytes = 8 * 1024 * sizeof(float);
-constexpr int kFusedDecodeKPW = 18;          // k-steps of the wide step per wave: K <= 8 * 18 * 16 = 2304
-constexpr int kFusedDecodeQ4KPW = 5;         // 4-bit stream: pieces of 64 k per wave (the same K needs 36 pieces)
+constexpr int kFusedDecodeKPW = 5;           // pieces of 64 k of the wide step per wave: K <= 8 * 5 * 64 = 2560
 
 bool chain2_split_applies(const tn_linear_s* h, const DevStep& s1, const DevStep& s3, int64_t tokens) {
     if (!s1.fuse_next || s1.chain_cfg == 0 || (h->flags & (TN_FLAG_NO_SPLIT_K | TN_FLAG_NO_DECODE_FUSION))) return false;
     if (s3.fuse_next || s3.variant == VAR_SCALAR || s3.amode != 0 || s3.plan.R != 1) return false;
-    if (tokens * ((s1.plan.C + 31) / 32) > 8 || s3.Kp > 8 * kFusedDecodeKPW * 16) return false;
+    if (tokens * ((s1.plan.C + 31) / 32) > 8 || s3.Kp > 8 * kFusedDecodeKPW * 64) return false;
     if (tokens * s3.plan.a_tok_stride * 2 > kFusedDecodeMaxZBytes) return false;
     const SplitCfg sc = split_config(s3, tokens);
     return sc.use && sc.nsplit == 1 && sc.tm == 1 && sc.nw == 8 && sc.row_tiles == 1;
@@ -1379,8 +1397,8 @@ int launch_chain2_split(const Chain2SplitArgs* p0, const Chain2SplitArgs* p1, hi
     static const k_t kerns[8] = {
         step_chain2_split_kernel<8, 0, kFusedDecodeKPW, 0>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW, 0>,
         step_chain2_split_kernel<5, 0, kFusedDecodeKPW, 0>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW, 0>,
-        step_chain2_split_kernel<8, 0, kFusedDecodeQ4KPW, 1>, step_chain2_split_kernel<8, 1, kFusedDecodeQ4KPW, 1>,
-        step_chain2_split_kernel<5, 0, kFusedDecodeQ4KPW, 1>, step_chain2_split_kernel<5, 1, kFusedDecodeQ4KPW, 1>};
+        step_chain2_split_kernel<8, 0, kFusedDecodeKPW, 1>, step_chain2_split_kernel<8, 1, kFusedDecodeKPW, 1>,
+        step_chain2_split_kernel<5, 0, kFusedDecodeKPW, 1>, step_chain2_split_kernel<5, 1, kFusedDecodeKPW, 1>};
     if (!p0) {                             // configuration call (create time)
         for (int i = 0; i < 8; ++i)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1470,15 +1488,10 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK) rc = launch_chain2_split(nullptr, nullptr, nullptr);
-    if (rc == TN_OK) {
-        using lds_t = void (*)(StepArgs, float*, int, int);
-        const lds_t q4k[4] = {step_split_q4_lds_kernel<0, 8>, step_split_q4_lds_kernel<1, 8>, step_split_q4_lds_kernel<0, 4>,
-                              step_split_q4_lds_kernel<1, 4>};
-        for (lds_t kq : q4k)
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kq), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(8 * 4096 + kQ4LdsRowBytes)) != hipSuccess)
-                rc = TN_ERR_HIP;
-    }
+    for (int i = 0; i < kSplitLdsKernels && rc == TN_OK; ++i)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(split_lds_kernels()[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(kSplitLdsRowBytes)) != hipSuccess)
+            rc = TN_ERR_HIP;
     if (rc == TN_OK &&
         (hipFuncSetAttribute(reinterpret_cast<const void*>(&step_pair_kernel<kPairStages, kPairBar>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, int(kPairSmemBytes)) != hipSuccess ||
