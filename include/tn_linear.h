@@ -110,6 +110,8 @@ extern "C" {
                                        nor chained pairs of few tokens on the kernel that requests its operands up front */
 #define TN_FLAG_NO_Q4_STREAM (1 << 27)   /* a TN_FLAG_QUANT_MXFP4 layer never reads the 4-bit form in its kernels: every call
                                        multiplies with the bf16 copies of the dequantised tensors */
+#define TN_FLAG_NO_SKINNY (1 << 28)      /* never run a launch of 5 to 64 rows on the kernel that keeps the rows in LDS and
+                                       gives a workgroup 256 columns: such launches use the split-K kernel of one column block */
 #define TN_FLAG_VARIANT_SHIFT   8   /* bits 8..15: kernel variant id for the wide bf16 steps (0 = library's choice):
                                        3 = 128x256 and 8 = 256x128 register-prefetch tiles, 9 = short-K store kernel,
                                        12 = 256x256 ping-pong kernel; 20 = the Kronecker-sum kernel for every two-step

@@ -33,6 +33,7 @@ TN_FLAG_NO_DECODE_FUSION = 1 << 24
 TN_FLAG_TRAINABLE = 1 << 25
 TN_FLAG_QUANT_MXFP4 = 1 << 26
 TN_FLAG_NO_Q4_STREAM = 1 << 27
+TN_FLAG_NO_SKINNY = 1 << 28
 TN_QUERY_PARAM_COUNT = 0
 TN_QUERY_PACKED_BYTES = 1
 TN_QUERY_FLOPS_PER_TOKEN = 2

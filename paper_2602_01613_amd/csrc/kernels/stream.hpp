@@ -483,6 +483,142 @@ __global__ void __launch_bounds__(NW * 64) step_split_lds_kernel(StepArgs a, flo
     split_finish<TM, NW>(a, partial, red, acc, 0u, cb, split, nsplit, uint32_t(32 * TM));
 }
 
+// One row tile of up to 64 rows against 256 columns per workgroup ("skinny" launches: small serving batches, 5 to 64
+// rows). The rows of A over the split's k range sit in LDS as in step_split_lds_kernel, but here they are shared by
+// eight column blocks: wave w streams ALL pieces of column block 8 * blockIdx.y + w (ring of D pieces in flight) and
+// owns its 32 columns outright, so there is no reduction across waves, and A is copied once per 256 columns instead
+// of once per 32 (at 64 rows the copies of the one-block kernel moved twice the bytes of the parameter stream).
+// With one split the wave stores through the scatter tables (out_vec4: columns come in aligned runs of four, stored
+// as 8-byte pieces); else fp32 partial sums [split][row][Cp] that step_split_reduce_kernel adds in split order.
+template <int TM, int AMODE, int Q4>
+__global__ void __launch_bounds__(512) step_skinny_kernel(StepArgs a, float* partial, int ksteps_per_split, int x_ld,
+                                                          int out_vec4) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    bf16_t* xs = reinterpret_cast<bf16_t*>(dyn_smem);                          // [rows][x_ld]
+    const bf16_t* A = static_cast<const bf16_t*>(a.A);
+    bf16_t* Out = static_cast<bf16_t*>(a.Out);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cb = blockIdx.y * 8 + wave, split = blockIdx.z, nsplit = gridDim.z;
+    const bool has_cols = cb * 32 < a.C;                                       // wave-uniform
+    const int n_chunks = a.Kp >> 6;
+    const int ch_begin = split * (ksteps_per_split >> 2);
+    const int ch_end = min(n_chunks, ch_begin + (ksteps_per_split >> 2));
+    const int rows = int(a.total_rows);                                        // <= 32 * TM
+    constexpr int D = Q4 ? 8 : 4;
+    uint4 q[Q4 ? D : 1];
+    unsigned sc[Q4 ? D : 1];
+    bf16x8 bf[Q4 ? 1 : D][4];
+    const int cbc = has_cols ? cb : 0;                                         // a wave without columns streams nothing it uses
+    const uint4* Q = static_cast<const uint4*>(a.B) + int64_t(cbc) * n_chunks * 64 + lane;
+    const unsigned char* S = static_cast<const unsigned char*>(a.Bs) + int64_t(cbc) * n_chunks * 64 + lane;
+    const bf16_t* Bp = static_cast<const bf16_t*>(a.B) + int64_t(cbc) * n_chunks * 2048 + lane * 8;
+    auto request = [&](int u, int ch) {
+        if (Q4) {
+            q[Q4 ? u : 0] = Q[int64_t(ch) * 64];
+            sc[Q4 ? u : 0] = S[int64_t(ch) * 64];
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bf[Q4 ? 0 : u][ks] = *reinterpret_cast<const bf16x8*>(Bp + (int64_t(ch) * 4 + ks) * 512);
+        }
+    };
+    if (has_cols) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) request(u, min(ch_begin + u, ch_end - 1));    // pieces past the split: its last one, unused
+    }
+    // the rows of A over the split's k range, zero past K
+    {
+        const int k0 = ch_begin * 64, kn = (ch_end - ch_begin) * 64;
+        const int pieces_per_row = kn >> 3;
+        for (int e = tid; e < rows * pieces_per_row; e += 512) {
+            const int g = e / pieces_per_row, k = k0 + 8 * (e - g * pieces_per_row);
+            const uint32_t t = uint32_t(g) / a.R, r = uint32_t(g) - t * a.R;
+            const int64_t base = int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K);
+            bf16x8 v;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = bf16_t(0.f);
+            if (AMODE == 0) {
+                if (k < a.K) v = *reinterpret_cast<const bf16x8*>(A + base + k);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (k + i < a.K) v[i] = A[base + (a.acol ? a.acol[k + i] : k + i)];
+            }
+            *reinterpret_cast<bf16x8*>(xs + int64_t(g) * x_ld + (k - k0)) = v;
+        }
+    }
+    __syncthreads();
+    if (!has_cols) return;
+    floatx16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    bool tv[TM];
+    const bf16_t* xrow[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        tv[i] = 32 * i + (lane & 31) < rows;
+        xrow[i] = xs + int64_t(tv[i] ? 32 * i + (lane & 31) : 0) * x_ld + (Q4 ? 32 : 8) * (lane >> 5);
+    }
+    bf16x8 zero;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) zero[i] = bf16_t(0.f);
+    for (int c0 = ch_begin; c0 < ch_end; c0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int ch = c0 + u;
+            if (ch < ch_end) {                                                 // wave-uniform
+                bf16x8 w[4];
+                if (Q4) {
+                    q4_dequant_block(q[Q4 ? u : 0], sc[Q4 ? u : 0], w);
+                } else {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) w[ks] = bf[Q4 ? 0 : u][ks];
+                }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const bf16x8 x = tv[i] ? *reinterpret_cast<const bf16x8*>(xrow[i] + (ch - ch_begin) * 64 + (Q4 ? 8 : 16) * ks)
+                                               : zero;
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ks], x, acc[i], 0, 0, 0);
+                    }
+            }
+            if (ch + D < ch_end) request(u, ch + D);                           // wave-uniform
+        }
+    }
+    // lane l, register v of acc[i]: row 32i + l%32, column 32*cb + 8*(v/4) + 4*(l/32) + v%4: registers 4q .. 4q+3 are
+    // four consecutive columns, stored as one piece where the layout allows (always for the partial sums)
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const uint32_t g = uint32_t(32 * i + (lane & 31));
+        if (g >= a.total_rows) continue;
+        const uint32_t t = g / a.R, r = g - t * a.R;
+        const int64_t obase = int64_t(t) * a.c_tok_stride + a.crow[r];
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int c = cb * 32 + 8 * qd + 4 * (lane >> 5);
+            if (c >= a.C) continue;
+            if (nsplit > 1) {                      // Cp is a multiple of 32: the four columns exist in the buffer
+                floatx4 v4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v4[e] = acc[i][4 * qd + e];
+                *reinterpret_cast<floatx4*>(partial + (int64_t(split) * (32 * TM) + g) * a.Cp + c) = v4;
+            } else if (out_vec4 && c + 3 < a.C) {
+                bf16x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk[e] = bf16_t(acc[i][4 * qd + e]);
+                *reinterpret_cast<bf16x4*>(Out + obase + a.ccol[c]) = pk;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < a.C) Out[obase + a.ccol[c + e]] = bf16_t(acc[i][4 * qd + e]);
+            }
+        }
+    }
+}
+
 template <int TM, int AMODE, int NW>
 __global__ void __launch_bounds__(NW * 64) step_split_q4_kernel(StepArgs a, float* partial, int ksteps_per_split) {
     __shared__ float red[NW * TM * 1024];

@@ -69,6 +69,7 @@ struct DevStep {
     int chain_run_c1 = 0;         // chain2: output pieces run along c1 (else along c2)
     void* q4_codes = nullptr;     // 4-bit stream of the tensor for decode-size launches (codes, then block scales)
     void* q4_scales = nullptr;
+    bool no_skinny = false;       // TN_FLAG_NO_SKINNY
 };
 
 }  // namespace
@@ -251,6 +252,7 @@ struct SplitCfg {
     bool use = false;
     int tm = 1, nw = 4, row_tiles = 0, col_blocks = 0, nsplit = 1, ksteps_per_split = 0;
     bool lds_rows = false;        // one row tile: the kernel that keeps the rows of A in LDS
+    bool skinny = false;          // one row tile against 256 columns per workgroup (step_skinny_kernel)
     int64_t partial_bytes = 0;
 };
 
@@ -261,6 +263,10 @@ constexpr size_t kSplitLdsRowBytes = 144 * 1024;  // rows of A a split-K workgro
 // rows (two row tiles, five splits to fit) 62.8 / 31.2; 4-bit stream 1 row 8.6 / 13.0, 8 rows 8.4 / 11.2, 64 rows
 // 56.7 / 26.1. Hence: one row tile only; a bf16 stream up to 4 rows, a 4-bit stream up to 32.
 constexpr int64_t kSplitLdsMaxBf16Rows = 4;
+constexpr int kSkinnyFillWorkgroups = 256;       // compute units the skinny kernel's grid is planned for
+constexpr int64_t kSkinnyLdsPerCu = 160 * 1024;  // LDS of a compute unit: bounds the workgroups it holds at a time
+constexpr int64_t kSplitLdsMaxQ4Rows = 12;
+constexpr int64_t kSkinnyMinRows = 8, kSkinnyMinRowsTimesK = 100000;
 
 // Decide whether a launch of `rows` rows runs on the split-K kernel: when the tiled kernel would
 // start fewer workgroups than there are compute units and K is long enough to share out.
@@ -282,7 +288,13 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     int want = int(std::max<int64_t>(1, target_wgs / base));
     int max_split = std::max(1, nks / (2 * c.nw));      // at least 2 k-steps per wave
     c.nsplit = std::min(want, max_split);
-    if (c.row_tiles == 1 && c.tm == 1 && nks % 4 == 0 && (s.q4_codes || rows <= kSplitLdsMaxBf16Rows)) {
+    const bool rows_fit_as_planned =
+        size_t(rows) * size_t(round_up((nks + c.nsplit - 1) / c.nsplit, 4) * 16 + 8) * 2 <= kSplitLdsRowBytes;
+    const bool skinny_possible = c.row_tiles == 1 && nks % 4 == 0 && c.col_blocks >= 8 && !s.no_skinny;
+    // a 4-bit stream whose rows would need extra splits to fit, or with many rows x K to copy per column block, goes
+    // to the 256-column kernel instead
+    if (c.row_tiles == 1 && c.tm == 1 && nks % 4 == 0 && rows <= (s.q4_codes ? kSplitLdsMaxQ4Rows : kSplitLdsMaxBf16Rows) &&
+        !(s.q4_codes && skinny_possible && (!rows_fit_as_planned || rows * int64_t(s.plan.K) >= kSkinnyMinRowsTimesK))) {
         // the kernel that keeps the rows of A in LDS: enough splits that the rows' share of A fits (at least two
         // pieces of 64 k per wave stay in a split), and whole pieces of 64 k per split
         c.lds_rows = true;
@@ -290,6 +302,46 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
         while (size_t(rows) * size_t(round_up((nks + c.nsplit - 1) / c.nsplit, 4) * 16 + 8) * 2 > kSplitLdsRowBytes &&
                (nks + c.nsplit) / (c.nsplit + 1) >= min_ksteps)
             ++c.nsplit;
+    }
+    if (!c.lds_rows && skinny_possible &&
+        (rows > 32 || s.q4_codes || (rows >= kSkinnyMinRows && rows * int64_t(s.plan.K) >= kSkinnyMinRowsTimesK))) {
+        // up to 64 rows against 256 columns per workgroup (step_skinny_kernel), every wave a column block of its own.
+        // The number of splits (equal, whole pieces of 64 k, the rows' share of A within the LDS budget) is the one
+        // with the least bytes on the critical path: the busiest CU runs ceil(grid / CUs) workgroups, each of which
+        // moves its pieces of the stream and its rows of A (a quarter more when LDS leaves room for only one
+        // workgroup per CU: nothing overlaps its start and end), and every split adds fp32 partial sums that are
+        // written and read back.
+        const int n_chunks = nks / 4, col_tiles = (c.col_blocks + 7) / 8;
+        auto cps_of = [&](int ns) { return (n_chunks + ns - 1) / ns; };
+        auto lds_bytes = [&](int ns) { return int64_t(rows) * (int64_t(cps_of(ns)) * 64 + 8) * 2; };
+        const double stream_bytes_per_k = s.q4_codes ? 256 * 17.0 / 32.0 : 256 * 2.0;
+        int best = 0;
+        double best_cost = 0;
+        for (int ns = 1; ns <= std::max(1, n_chunks / 2); ++ns) {
+            if (ns > 1 && cps_of(ns) == cps_of(ns - 1)) continue;              // same pieces per split: more empty tail
+            if (lds_bytes(ns) > int64_t(kSplitLdsRowBytes)) continue;
+            const int n_real = (n_chunks + cps_of(ns) - 1) / cps_of(ns);
+            const int64_t pb = n_real > 1 ? int64_t(n_real) * 32 * c.tm * s.Cp * 4 : 0;
+            if (pb > kMaxPartialBytes) break;
+            const int per_cu = int(std::max<int64_t>(1, std::min<int64_t>(4, kSkinnyLdsPerCu / std::max<int64_t>(1, lds_bytes(ns)))));
+            const int64_t grid = int64_t(col_tiles) * n_real;
+            const int64_t serial = (grid + kSkinnyFillWorkgroups - 1) / kSkinnyFillWorkgroups;      // workgroups the busiest CU runs
+            const double wg_bytes = cps_of(ns) * 64.0 * (stream_bytes_per_k + 2.0 * double(rows));
+            const double cost = double(serial) * wg_bytes * kSkinnyFillWorkgroups * (per_cu == 1 ? 1.25 : 1.0) + 2.0 * double(pb);
+            if (!best || cost < best_cost) {
+                best = ns;
+                best_cost = cost;
+            }
+        }
+        if (best) {
+            const int cps = cps_of(best);
+            c.skinny = true;
+            c.nsplit = (n_chunks + cps - 1) / cps;
+            c.ksteps_per_split = cps * 4;
+            c.partial_bytes = c.nsplit > 1 ? int64_t(c.nsplit) * 32 * c.tm * s.Cp * 4 : 0;
+            c.use = true;
+            return c;
+        }
     }
     for (;;) {
         c.ksteps_per_split = (nks + c.nsplit - 1) / c.nsplit;
@@ -389,6 +441,16 @@ const split_lds_t* split_lds_kernels() {
     return lds;
 }
 
+// step_skinny_kernel: index (tm - 1) * 4 + (gathered A ? 2 : 0) + (4-bit stream ? 1 : 0).
+constexpr int kSkinnyKernels = 8;
+using skinny_t = void (*)(StepArgs, float*, int, int, int);
+const skinny_t* skinny_kernels() {
+    static const skinny_t k[kSkinnyKernels] = {step_skinny_kernel<1, 0, 0>, step_skinny_kernel<1, 0, 1>, step_skinny_kernel<1, 1, 0>,
+                                                  step_skinny_kernel<1, 1, 1>, step_skinny_kernel<2, 0, 0>, step_skinny_kernel<2, 0, 1>,
+                                                  step_skinny_kernel<2, 1, 0>, step_skinny_kernel<2, 1, 1>};
+    return k;
+}
+
 int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, const void* A, void* Out, int64_t tokens,
                 hipStream_t st) {
     StepArgs a;
@@ -422,7 +484,12 @@ int launch_step(const tn_linear_s* h, const Workspace& w, const DevStep& s, cons
         }
         const int x_ld = sc.ksteps_per_split * 16 + 8;
         const size_t x_bytes = size_t(rows) * size_t(x_ld) * sizeof(bf16_t);
-        if (sc.lds_rows && sc.tm == 1 && sc.row_tiles == 1 && sc.ksteps_per_split % 4 == 0 && x_bytes <= kSplitLdsRowBytes) {
+        if (sc.skinny) {
+            if (x_bytes > kSplitLdsRowBytes) return TN_ERR_UNSUPPORTED;       // split_config sized it to fit
+            const dim3 kgrid(1, uint32_t((sc.col_blocks + 7) / 8), uint32_t(sc.nsplit));
+            hipLaunchKernelGGL(skinny_kernels()[(sc.tm - 1) * 4 + (s.amode == 0 ? 0 : 2) + q4], kgrid, dim3(512), x_bytes, st, a,
+                               part, sc.ksteps_per_split, x_ld, s.plan.c_vec >= 4 ? 1 : 0);
+        } else if (sc.lds_rows && sc.tm == 1 && sc.row_tiles == 1 && sc.ksteps_per_split % 4 == 0 && x_bytes <= kSplitLdsRowBytes) {
             // one row tile whose share of A fits in LDS
             const size_t red_bytes = size_t(sc.nw) * sc.tm * 4096;
             hipLaunchKernelGGL(split_lds_kernels()[(sc.nw == 8 ? 4 : 0) + (s.amode == 0 ? 0 : 2) + q4], sgrid,
@@ -1488,6 +1555,10 @@ int configure_kernels(int device) {
     if (rc == TN_OK) rc = configure_pingpong();
     if (rc == TN_OK) rc = launch_chain2(no_handle, none, none, nullptr, nullptr, 0, nullptr);
     if (rc == TN_OK) rc = launch_chain2_split(nullptr, nullptr, nullptr);
+    for (int i = 0; i < kSkinnyKernels && rc == TN_OK; ++i)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_kernels()[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(kSplitLdsRowBytes)) != hipSuccess)
+            rc = TN_ERR_HIP;
     for (int i = 0; i < kSplitLdsKernels && rc == TN_OK; ++i)
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(split_lds_kernels()[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 int(kSplitLdsRowBytes)) != hipSuccess)
@@ -1949,6 +2020,7 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
         for (size_t i = 0; i < h->steps.size(); ++i) {
             DevStep& s = h->steps[i];
             s.plan = h->plan.steps[i];
+            s.no_skinny = (desc->flags & TN_FLAG_NO_SKINNY) != 0;
             choose_variant(h, &s, desc->flags);
             const tn::Step& p = s.plan;
             tab_off[i] = host_tab.size();

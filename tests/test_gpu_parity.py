@@ -362,6 +362,38 @@ def test_split_k_small_launches(tokens):
         assert np.array_equal(y, run_layer(spec, ts, x))
 
 
+@pytest.mark.parametrize("case", range(6))
+def test_decode_size_kernel_family(case):
+    """Launches of one row tile (1 to 64 rows) choose between the split-K kernel of one column block with A gathered
+    from memory, the same with the rows of A in LDS (up to 4 rows), and the kernel that gives a workgroup 256
+    columns (5 to 64 rows, chosen by rows x K): every row count around the switches, on shapes with ragged column
+    tiles, a K with a half piece of 64 at the end, few and many splits; against the oracle and against the layer with
+    the 256-column kernel switched off."""
+    cases = [
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (1000,), (5120,), ()),           # 32 column blocks (the last ragged), 80 pieces
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (300,), (2464,), ()),            # 10 column blocks, K = 38.5 pieces
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (256,), (25600,), ()),           # one column tile, long K: many splits
+        _spec(tn.TN_FORMAT_DENSE, "bf16", (4096,), (544,), ()),            # short K: one or two splits
+        _spec(tn.TN_FORMAT_TUCKER, "bf16", (40, 48), (32, 40), (24, 32, 16, 24)),      # core 768 x 384 inside a chain
+        _spec(tn.TN_FORMAT_TUCKER, "bf16", (160, 160), (64, 80), (48, 48, 24, 24)),
+    ]
+    spec = cases[case]
+    ts = _rand_layer(spec, 900 + case)
+    layer = make_layer(spec, ts, 64)
+    plain = make_layer(spec, ts, 64, flags=tn.TN_FLAG_NO_SKINNY)
+    w = O.dense_weight(spec.format, ts, len(spec.out_modes))
+    for tokens in (1, 2, 4, 5, 7, 8, 9, 16, 23, 24, 31, 32, 33, 47, 64):
+        x = wl.round_to_dtype(np.random.default_rng(case * 100 + tokens).standard_normal((tokens, spec.N)), "bf16")
+        xd = to_dev(x, "bf16")
+        y = to_host(layer(xd))
+        err = O.rel_max_err(y, O.apply_linear(w, x))
+        assert err <= TOL["bf16"], (case, tokens, err)
+        assert O.rel_max_err(y, to_host(plain(xd))) <= 1e-2, (case, tokens)
+        assert np.array_equal(y, to_host(layer(xd))), (case, tokens)        # fixed-order sums: the same bits again
+    layer.close()
+    plain.close()
+
+
 def test_shared_caller_workspace(dense_w):
     """Several handles keep their intermediates in one caller-owned block (run one after the
     other on one stream); results equal those of handles with their own workspace."""
