@@ -545,7 +545,7 @@ def run_stack(args, verify=True, cpu=True):
     check_classes = {(wl.FORMAT_DENSE, 5120, 1024): None, (wl.FORMAT_TT, 5120, 1024): None,
                      (wl.FORMAT_TUCKER, 5120, 1024): None, (wl.FORMAT_TR, 25600, 5120): None}
     t0 = time.perf_counter()
-    layers, flops, flops_prefill, params, packed = [], [], [], [], []
+    layers, flops, flops_prefill, flops_decode, params, packed = [], [], [], [], [], []
     for n, spec in enumerate(specs):
         ts = draw_on_device(spec, gen)
         layer = tn.TNLinear(spec.format, tn.TN_DTYPE_BF16, spec.out_modes, spec.in_modes, spec.ranks, ts,
@@ -556,6 +556,7 @@ def run_stack(args, verify=True, cpu=True):
         lazy_min = layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS)
         flops_prefill.append(layer.query(tn.TN_QUERY_LAZY_FLOPS_PER_TOKEN) if lazy_min and tokens >= lazy_min
                              else flops[-1])
+        flops_decode.append(layer.query(tn.TN_QUERY_LAZY_FLOPS_PER_TOKEN) if lazy_min and 1 >= lazy_min else flops[-1])
         params.append(spec.n_params)
         packed.append(layer.query(tn.TN_QUERY_PACKED_BYTES))
         key = (spec.format, spec.N, spec.M)
@@ -666,7 +667,7 @@ def run_stack(args, verify=True, cpu=True):
                 "by_format": roof_fmt}
     dec_roof = {k: {"packed_GB": pk_fmt[k] / 1e9, "GBps": pk_fmt[k] / (dec_fmt[k] * 1e-3) / 1e9,
                     "frac_of_hbm_peak": pk_fmt[k] / (dec_fmt[k] * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                    "tflops": sum(f for s, f in zip(specs, flops) if wl.FORMAT_NAMES[s.format] == k) / (dec_fmt[k] * 1e-3) / 1e12}
+                    "tflops": sum(f for s, f in zip(specs, flops_decode) if wl.FORMAT_NAMES[s.format] == k) / (dec_fmt[k] * 1e-3) / 1e12}
                 for k in dec_fmt}
     top = sorted(pre_shape.items(), key=lambda kv: -kv[1][1])[:10]
     result = {

@@ -105,9 +105,10 @@ extern "C" {
                                        TN_QUERY_LAZY_MIN_TOKENS): every call runs the compact steps */
 #define TN_FLAG_SCALAR_GENERATE (1 << 23) /* rebuild the slices of a lazily merged plan with the plain FMA kernel
                                        instead of the MFMA one */
-#define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* never run a chained factor pair and the wide step after it as one launch
-                                       (calls of a few tokens: the in-factor products and the core of a Tucker layer),
-                                       nor chained pairs of few tokens on the kernel that requests its operands up front */
+#define TN_FLAG_NO_DECODE_FUSION (1 << 24) /* none of the forms kept for calls of a few tokens: a chained factor pair and the
+                                       wide step after it as one launch (the in-factor products and the core of a Tucker
+                                       layer), chained pairs on the kernels that request their operands up front, the
+                                       Kronecker-sum kernel with the four waves of a workgroup sharing one token */
 #define TN_FLAG_NO_Q4_STREAM (1 << 27)   /* a TN_FLAG_QUANT_MXFP4 layer never reads the 4-bit form in its kernels: every call
                                        multiplies with the bf16 copies of the dequantised tensors */
 #define TN_FLAG_NO_SKINNY (1 << 28)      /* never run a launch of 5 to 64 rows on the kernel that keeps the rows in LDS and

@@ -23,7 +23,9 @@
 // The slices are the same for every token, so the workgroups of an XCD, which walk rho in step, read
 // them from that XCD's L2; HBM sees X once, Y once and the packed tensors once per XCD.
 // Few tokens: the range of rho is split over workgroups, each writes fp32 partial sums, and a second
-// small kernel adds them in a fixed order.
+// small kernel adds them in a fixed order. One or two tokens: a wave per token would leave three of a CU's four
+// matrix cores idle while one wave works through 16 * AT * O1T MFMAs per value of the bond (six times the time the
+// slices take to arrive), so the four waves share the token (KronArgs::share).
 // Template: AT tiles of 32 values of a, KS0 k-steps of 16 in the first contraction, O2T tiles of 32
 // values of o2, O1T tiles of 32 values of o1 per chunk; smaller shapes run on zero padding (the repacked
 // slices hold zeros there).
@@ -43,6 +45,9 @@ struct KronArgs {
     int32_t n_splits;      // workgroups sharing one (token quad, chunk): each takes rho_per_split values of rho
     int32_t rho_per_split;
     int32_t x_vec8;        // 8 consecutive k of one a are one aligned 16-byte piece of x
+    int32_t share;         // one token (the SHARE instantiation): the four waves of a workgroup share ONE token (the workgroup's index
+                           // counts tokens, not quads): per value of the bond its (o1 tile, a tile) units are dealt
+                           // round-robin to the waves, whose sums are added through LDS in wave order at the end
 };
 
 template <int AT, int KS0, int O2T, int O1T>
@@ -93,7 +98,9 @@ __global__ void __launch_bounds__(256) kron_repack1_kernel(const bf16_t* src, bf
     }
 }
 
-template <int AT, int KS0, int O2T, int O1T>
+// SHARE: the one-token form (KronArgs::share): a compile-time switch, so that the loop of the many-token form stays
+// one straight line of MFMAs and LDS reads (with the test inside it that loop ran 7 % slower).
+template <int AT, int KS0, int O2T, int O1T, int SHARE>
 __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
     using S = KronShape<AT, KS0, O2T, O1T>;
     constexpr int L = S::L, NS = S::NS, NB0 = S::NB0, NB1 = S::NB1, STAGE_BYTES = S::STAGE_BYTES;
@@ -111,7 +118,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
     id /= p.n_splits;
     const int chunk = id % p.n_chunks;
     const int quad = id / p.n_chunks;
-    const int t = quad * 4 + wave;
+    const int t = SHARE ? quad : quad * 4 + wave;
     const int tl = min(t, p.tokens - 1);                 // waves past the end repeat the last token and store nothing
     const int rho_begin = split * p.rho_per_split;
     const int rho_end = min(p.P, rho_begin + p.rho_per_split);
@@ -214,6 +221,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
             for (int ks = 0; ks < KS0; ++ks) h0[ks] = *reinterpret_cast<const bf16x8*>(sb + (o * KS0 + ks) * 1024);
 #pragma unroll
             for (int i = 0; i < AT; ++i) {
+                if (SHARE && ((o * AT + i) & 3) != wave) continue;         // wave-uniform: another wave's unit
                 bf16x8 h1[O2T][2];
 #pragma unroll
                 for (int j = 0; j < O2T; ++j)
@@ -245,6 +253,35 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
             for (int o = 0; o < O1T; ++o) asm volatile("" : "+a"(acc[j][o]));
     }
 
+    if (SHARE) {
+        // the four waves hold sums over disjoint sets of a: add them in wave order in LDS (the stages are dead), then
+        // every wave takes back the tiles it stores (tile j*O1T + o belongs to wave (j*O1T + o) % 4)
+        static_assert(size_t(O2T) * O1T * 4096 <= S::SMEM, "the shared sums fit the stages' LDS");
+        float* red = reinterpret_cast<float*>(dyn_smem);
+        __syncthreads();
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int j = 0; j < O2T; ++j)
+#pragma unroll
+                    for (int o = 0; o < O1T; ++o)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            float* q = red + ((j * O1T + o) * 16 + v) * 64 + lane;
+                            *q = w == 0 ? acc[j][o][v] : *q + acc[j][o][v];
+                        }
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int j = 0; j < O2T; ++j)
+#pragma unroll
+            for (int o = 0; o < O1T; ++o)
+                if (((j * O1T + o) & 3) == wave) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[j][o][v] = red[((j * O1T + o) * 16 + v) * 64 + lane];
+                }
+    }
     // lane l, register v of acc[j][o]: o2 = 32*j + 8*(v/4) + 4*(l/32) + v%4, o1 = 32*O1T*chunk + 32*o + l%32
     if (t >= p.tokens) return;
     int yr[O1T];
@@ -264,7 +301,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
             const int yc = p.ycol[o2];
 #pragma unroll
             for (int o = 0; o < O1T; ++o) {
-                if (yr[o] < 0) continue;
+                if (yr[o] < 0 || (SHARE && ((j * O1T + o) & 3) != wave)) continue;
                 if (p.n_splits > 1) yf[yr[o] + yc] = acc[j][o][v];
                 else yb[yr[o] + yc] = bf16_t(acc[j][o][v]);
             }

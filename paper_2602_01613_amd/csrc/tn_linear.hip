@@ -775,10 +775,13 @@ int kron_entry(const KronArgs* p, uint32_t grid, hipStream_t st, KronTiles* tile
         return TN_OK;
     }
     if (!p)         // configuration call (create time)
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess
+        return (hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 0>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess &&
+                hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess)
                    ? TN_OK : TN_ERR_HIP;
-    hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    if (p->share) hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 1>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    else hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 0>), dim3(grid), dim3(256), S::SMEM, st, *p);
     return TN_OK;
 }
 
@@ -805,13 +808,19 @@ int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, Kro
 struct KronGeom {
     int n_chunks = 1, n_splits = 1, rho_per_split = 1;
     int64_t quads = 1, partial_bytes = 0;
+    bool share = false;       // the four waves of a workgroup share one token (quads then counts tokens)
 };
+
+// measured on seven ring classes with stored half rings (us per call, shared / a wave per token): one token 30/44,
+// 110/214, 146/206, 79/119, 51/65, 31/35, 16/16; two tokens 34/44, 165/195, 214/204, 109/111, 65/63, 41/36, 18/17
+constexpr int64_t kKronShareMaxTokens = 1;
 
 KronGeom kron_geometry(const tn_linear_s* h, const tn::KronDims& d, int64_t tokens, int64_t partial_cap) {
     KronGeom g;
     const int o1_chunk = 32 * tn::kKronConfig[d.cfg][3];
     g.n_chunks = int((d.O1 + o1_chunk - 1) / o1_chunk);
-    g.quads = (tokens + 3) / 4;
+    g.share = tokens <= kKronShareMaxTokens && !(h->flags & TN_FLAG_NO_DECODE_FUSION);
+    g.quads = g.share ? tokens : (tokens + 3) / 4;
     int64_t base = g.quads * g.n_chunks;
     // workgroups a CU holds at a time: one when the three LDS stages take more than half of its 160 KB
     const int* cfg = tn::kKronConfig[d.cfg];
@@ -899,6 +908,7 @@ int launch_kron(const tn_linear_s* h, const Workspace& w, const KronSetup& k, co
     p.n_splits = g.n_splits;
     p.rho_per_split = g.rho_per_split;
     p.x_vec8 = d.x_vec8 ? 1 : 0;
+    p.share = g.share ? 1 : 0;
     const int64_t grid = g.quads * g.n_chunks * g.n_splits;
     int rc = kron_dispatch(d.cfg, &p, uint32_t(grid), st);
     if (rc != TN_OK) return rc;
@@ -1142,8 +1152,12 @@ int launch_kron_lazy(const tn_linear_s* h, const Workspace& w, const void* x, vo
     return launch_kron(h, w, k, x, y, tokens, st);
 }
 
-// Token count from which a lazily merged plan replaces the compact steps.
-constexpr int64_t kLazyMinTokens = 2;
+// Token count from which a lazily merged plan replaces the compact steps: every call. With the one-token form of
+// the Kronecker-sum kernel (four waves share the token) rebuilding the slices and streaming them once is as fast as
+// the compact steps or faster on every ring class of the 64-layer stack (us per one-token call, rebuilt / compact:
+// 25600->5120 r32 49/69, r96 326/527; 5120->25600 r64 246/246; 5120->8192 r96 253/262; 8192->5120 r64 118/130;
+// 5120->1024 r96 97/163, r32 24/46).
+constexpr int64_t kLazyMinTokens = 1;
 
 void fill_gen_dims(GenDims* g, const std::vector<tn::GatherDim>& d) {
     g->n = int32_t(d.size());
@@ -2168,7 +2182,9 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
     }
     // with the chained pair kernel or a lazily merged plan only calls below the token threshold use the buffers
     int64_t ws_tokens = h->pair ? std::min<int64_t>(h->max_tokens, h->pair_min_tokens - 1) : h->max_tokens;
-    if (h->lazy) ws_tokens = std::min<int64_t>(ws_tokens, h->lazy_min_tokens - 1);
+    // (one token's buffers stay: calls that may not use the rebuilt plan - profiled steps, the entry point that
+    // allocates nothing - run the compact steps token by token)
+    if (h->lazy) ws_tokens = std::min<int64_t>(ws_tokens, std::max<int64_t>(1, h->lazy_min_tokens - 1));
     int64_t chunk = ws_tokens;
     if (desc->workspace) {
         // caller-owned block: [partial sums | buffer 0 | buffer 1], 256-byte aligned pieces

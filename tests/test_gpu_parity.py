@@ -263,7 +263,7 @@ def test_stack_rings_prefill_8192(n_in, n_out, r):
     print(f"[ring 8192] x", flush=True)
     x = wl.make_x(spec, tokens, 4, instance=9)
     layer = make_layer(spec, ts, tokens)
-    assert layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 2
+    assert layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 1
     yd = layer(to_dev(x, spec.dtype))
     torch.cuda.synchronize()
     y = to_host(yd[:, torch.from_numpy(rows).cuda()])
@@ -544,16 +544,16 @@ LAZY_CASES = [
 
 @pytest.mark.parametrize("case", range(len(LAZY_CASES)))
 def test_lazily_merged_ring(case):
-    """A default ring layer stores its compact cores; calls of 2 tokens or more rebuild the half-ring
-    slices in the workspace and run the Kronecker-sum kernel. Both regimes against the oracle, the lazy one
-    against the compact steps and against a layer that keeps the merged tensors, and again after a small
-    call has used the same workspace."""
+    """A default ring layer stores its compact cores; every call rebuilds the half-ring slices in the workspace and
+    runs the Kronecker-sum kernel (one-token calls with the four waves of a workgroup sharing the token). Against
+    the oracle, against the compact steps and against a layer that keeps the merged tensors, and again after a
+    small call has used the same workspace."""
     om, im, rk = LAZY_CASES[case]
     spec = _spec(tn.TN_FORMAT_TR, "bf16", om, im, rk)
     ts = wl.make_tensors(spec, 40 + case)
     w = O.dense_weight(spec.format, ts, len(om))
     layer = make_layer(spec, ts, 64)
-    assert layer.query(tn.TN_QUERY_NUM_STEPS) == 4 and layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 2
+    assert layer.query(tn.TN_QUERY_NUM_STEPS) == 4 and layer.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 1
     assert 0 < layer.query(tn.TN_QUERY_LAZY_FLOPS_PER_TOKEN) < layer.query(tn.TN_QUERY_FLOPS_PER_TOKEN)
     compact = make_layer(spec, ts, 64, flags=tn.TN_FLAG_NO_LAZY_MERGE)
     assert compact.query(tn.TN_QUERY_LAZY_MIN_TOKENS) == 0
@@ -572,12 +572,9 @@ def test_lazily_merged_ring(case):
         assert O.rel_max_err(y, ref) <= TOL["bf16"], (case, tokens, O.rel_max_err(y, ref))
         yc = to_host(compact(xd))
         assert O.rel_max_err(yc, ref) <= TOL["bf16"], (case, tokens)
-        if tokens < 2:
-            assert np.array_equal(y, yc)                      # same steps, same bits
-        else:
-            assert O.rel_max_err(y, yc) <= 1e-2
-            assert O.rel_max_err(y, to_host(stored(xd))) <= 1e-2     # rebuilt vs stored slices
-            assert O.rel_max_err(y, to_host(scalar_gen(xd))) <= 1e-2  # the two rebuild kernels: summation order only
+        assert O.rel_max_err(y, yc) <= 1e-2
+        assert O.rel_max_err(y, to_host(stored(xd))) <= 1e-2         # rebuilt vs stored slices
+        assert O.rel_max_err(y, to_host(scalar_gen(xd))) <= 1e-2      # the two rebuild kernels: summation order only
         if tokens == 40:
             if first is None:
                 first = yd.clone()
