@@ -111,6 +111,7 @@ struct tn_linear_s {
     // the same kernel on a plan that exists only for large calls: the layer keeps its compact tensors and
     // steps, and calls of at least lazy_min_tokens tokens rebuild the merged plan's slices in the workspace
     bool lazy = false;
+    bool lazy_slices_kept = false;    // the slices sit in memory only this handle writes (its own workspace): built once, at create
     tn::Plan lazy_plan;
     tn::KronDims lazy_dims;
     int64_t lazy_min_tokens = 0;
@@ -2247,6 +2248,17 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc_in) {
         h->lazy_gen_mfma[w].dst = h->lazy_gen[w].dst;
     }
     h->chunk_tokens = chunk;
+    if (h->lazy && h->owns_workspace) {
+        // the handle's own workspace: nobody else writes the slices, so they are built here once and every call
+        // finds them (a layer that shares a caller's block rebuilds them per call instead)
+        rc = launch_lazy_generate(h, st);
+        if (rc != TN_OK) {
+            (void)hipStreamSynchronize(st);
+            free_handle(h);
+            return rc;
+        }
+        h->lazy_slices_kept = true;
+    }
     {
         std::vector<int> fuse(h->steps.size(), 0);
         for (size_t i = 0; i < h->steps.size(); ++i) fuse[i] = h->steps[i].fuse_next ? 1 : 0;
@@ -2312,7 +2324,8 @@ int forward_in(tn_linear_s* h, const Workspace& w, bool allow_lazy, const void* 
         // both steps in one launch, no intermediate in memory; passes only bound the 32-bit token index
         // (and, for the Kronecker-sum kernel, keep a call's partial sums within their buffer)
         const int64_t pass = use_pair ? int64_t(1) << 24 : int64_t(1) << 20;
-        if (!use_pair && !use_kron) {
+        if (!use_pair && !use_kron && !h->lazy_slices_kept) {
+            // a caller's block is shared with other layers: whatever it held is gone
             int rc = launch_lazy_generate(h, st);          // not part of the profiled launch: a kernel of its own
             if (rc != TN_OK) return rc;
         }
