@@ -142,9 +142,10 @@ extern "C" {
 #define TN_QUERY_LAZY_MIN_TOKENS   12   /* handle only: 0, or the token count from which a call runs on a lazily
                                            merged plan: the plan TN_FLAG_MERGE_HALVES would give (two half rings for
                                            a ring of four cores) is cheaper and fits the Kronecker-sum kernel, so
-                                           such calls rebuild its tensors in the workspace from the caller's
-                                           compact ones (microseconds) and run that one launch; the layer stores
-                                           only the compact tensors, and smaller calls run the compact steps */
+                                           such calls run that one launch on its tensors, rebuilt in the workspace
+                                           from the caller's compact ones (microseconds): per call when the
+                                           workspace is a caller's block shared with other layers, once at create
+                                           when it is the handle's own; 1 since the kernel has a one-token form */
 #define TN_QUERY_LAZY_FLOPS_PER_TOKEN 13 /* handle only: FLOPs per token of that plan (0 if none) */
 #define TN_QUERY_BACKWARD_CHUNK_TOKENS 14 /* handle only: tokens per pass of tn_linear_param_gradients (0: not trainable) */
 #define TN_QUERY_BACKWARD_WORKSPACE_BYTES 15 /* handle only: device memory held for those passes */
@@ -298,8 +299,8 @@ int tn_linear_quantized_tensor(tn_linear_t h, int32_t slot, void* codes, void* e
  *     partial sums of its split launches. More than TN_SCRATCH_BYTES: TN_ERR_SCRATCH, nothing is launched.
  *     Calls that run as one launch with no intermediate in memory (small layers, the chained pair kernel)
  *     need none and are never refused; a layer on the Kronecker-sum kernel takes as many splits as fit.
- *   - Large calls of a lazily merged ring (TN_QUERY_LAZY_MIN_TOKENS) run the compact steps here: the rebuilt
- *     slices belong to the handle's workspace.
+ *   - A lazily merged ring (TN_QUERY_LAZY_MIN_TOKENS) runs its compact steps here: the rebuilt slices belong to
+ *     the handle's workspace.
  *   - Every call on one GPU, from any handle, shares that GPU's array: calls that overlap in time on one GPU
  *     race. Nothing in it needs to start at zero (every element is written before it is read within a call).
  *   - A handle with profiling enabled is refused (TN_ERR_INVALID_ARG): profiling creates events.
