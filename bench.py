@@ -612,6 +612,30 @@ def run_stack(args, verify=True, cpu=True):
         return wall, by_fmt, by_shape
 
     dec_wall, dec_fmt, dec_shape = timed(1, max(1, min(args.steps, 10)))
+    # the same pass as one captured HIP graph (what a serving loop replays per token: no host launch cost between the
+    # 448 forwards); every replay is checked against the eager pass's last output
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for spec, layer in zip(specs, layers):
+            layer.forward(xs[spec.N][:1], out=ys[spec.M][:1])
+    torch.cuda.synchronize()
+    y_eager = {m: y[:1].clone() for m, y in ys.items()}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for spec, layer in zip(specs, layers):
+            layer.forward(xs[spec.N][:1], out=ys[spec.M][:1])
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    reps = max(3, min(args.steps, 10))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dec_graph_wall = (time.perf_counter() - t0) / reps
+    dec_graph_ok = all(bool(torch.equal(y_eager[m], ys[m][:1])) for m in ys)
+    del graph
     pre_wall, pre_fmt, pre_shape = timed(tokens, 0)
 
     # parity of what was just computed: for one matrix per format (the ring at rank 96 on the widest shape, which
@@ -682,7 +706,11 @@ def run_stack(args, verify=True, cpu=True):
                     "top10_classes_ms": {k: {"matrices": v[0], "ms_each": v[1] / v[0]} for k, v in top}},
         "roofline": roofline,
         "decode_1tok": {"ms_per_token_all_matrices": 1e3 * dec_wall, "tokens_per_s": 1.0 / dec_wall,
+                        "graph_ms_per_token_all_matrices": 1e3 * dec_graph_wall, "graph_tokens_per_s": 1.0 / dec_graph_wall,
+                        "graph_replay_equals_eager": dec_graph_ok,
                         "ms_by_format": dec_fmt, "by_format": dec_roof,
+                        "top10_classes_us": {k: {"matrices": v[0], "us_each": 1e3 * v[1] / v[0]}
+                                             for k, v in sorted(dec_shape.items(), key=lambda kv: -kv[1][1])[:10]},
                         "packed_GB": sum(packed) / 1e9, "packed_GBps": sum(packed) / dec_wall / 1e9,
                         "frac_of_hbm_peak": sum(packed) / dec_wall / 1e9 / PEAK_HBM_GBS},
         "parameters": sum(params), "create_seconds": create_s,
