@@ -1435,7 +1435,9 @@ bool chain2_split_applies(const tn_linear_s* h, const DevStep& s1, const DevStep
     if (tokens * ((s1.plan.C + 31) / 32) > 8 || s3.Kp > 8 * kFusedDecodeKPW * 64) return false;
     if (tokens * s3.plan.a_tok_stride * 2 > kFusedDecodeMaxZBytes) return false;
     const SplitCfg sc = split_config(s3, tokens);
-    return sc.use && sc.nsplit == 1 && sc.tm == 1 && sc.nw == 8 && sc.row_tiles == 1;
+    // (however many splits the wide step would take on its own: here a workgroup always walks the whole K, which for a
+    // core this small is a few hundred KB per workgroup at most)
+    return sc.use && sc.tm == 1 && sc.nw == 8 && sc.row_tiles == 1;
 }
 
 struct Chain2SplitArgs {
