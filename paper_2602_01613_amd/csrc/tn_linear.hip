@@ -264,6 +264,7 @@ constexpr size_t kSplitLdsRowBytes = 144 * 1024;  // rows of A a split-K workgro
 // rows (two row tiles, five splits to fit) 62.8 / 31.2; 4-bit stream 1 row 8.6 / 13.0, 8 rows 8.4 / 11.2, 64 rows
 // 56.7 / 26.1. Hence: one row tile only; a bf16 stream up to 4 rows, a 4-bit stream up to 32.
 constexpr int64_t kSplitLdsMaxBf16Rows = 4;
+constexpr int64_t kSplitOneSplitBlocks = 128;
 constexpr int kSkinnyFillWorkgroups = 256;       // compute units the skinny kernel's grid is planned for
 constexpr int64_t kSkinnyLdsPerCu = 160 * 1024;  // LDS of a compute unit: bounds the workgroups it holds at a time
 constexpr int64_t kSplitLdsMaxQ4Rows = 12;
@@ -289,6 +290,7 @@ SplitCfg split_config(const DevStep& s, int64_t rows) {
     int want = int(std::max<int64_t>(1, target_wgs / base));
     int max_split = std::max(1, nks / (2 * c.nw));      // at least 2 k-steps per wave
     c.nsplit = std::min(want, max_split);
+    if (c.row_tiles == 1 && base >= kSplitOneSplitBlocks) c.nsplit = 1;      // enough column blocks: no second pass over partial sums
     const bool rows_fit_as_planned =
         size_t(rows) * size_t(round_up((nks + c.nsplit - 1) / c.nsplit, 4) * 16 + 8) * 2 <= kSplitLdsRowBytes;
     const bool skinny_possible = c.row_tiles == 1 && nks % 4 == 0 && c.col_blocks >= 8 && !s.no_skinny;
