@@ -2431,26 +2431,28 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
     auto buffer = [&](int n, int id) -> void* {
         return id == tn::kBufX ? const_cast<void*>(x) : (id == tn::kBufY ? ys[n] : ws[n].ws[id]);
     };
+    // Each layer takes the launches tn_linear_forward would give it (so that its result has the same bits); where both
+    // take the same decode-size kernel at the same point of the chain, one launch serves both.
+    bool skip[2] = {false, false};                 // the layer's launch at this index ran inside its previous, fused one
     for (size_t li = 0; li < ha->schedule.size(); ++li) {
         const tn::LaunchIO& l = ha->schedule[li];
         const size_t f = size_t(l.first);
         const bool has_next = li + 1 < ha->schedule.size() && ha->schedule[li + 1].steps == 1;
         int rc = TN_OK;
-        if (l.steps == 2 && has_next && chain2_split_applies(ha, ha->steps[f], ha->steps[f + 2], tokens) &&
-            chain2_split_applies(hb, hb->steps[f], hb->steps[f + 2], tokens)) {
-            // pair and wide step of both layers in one launch
-            Chain2SplitArgs fa[2];
-            for (int n = 0; n < 2; ++n)
+        bool fuse[2];
+        Chain2SplitArgs fa[2];
+        for (int n = 0; n < 2; ++n) {
+            fuse[n] = !skip[n] && l.steps == 2 && has_next &&
+                      chain2_split_applies(hs[n], hs[n]->steps[f], hs[n]->steps[f + 2], tokens);
+            if (fuse[n])
                 fa[n] = chain2_split_args(hs[n]->steps[f], hs[n]->steps[f + 1], hs[n]->steps[f + 2],
                                           buffer(n, hs[n]->schedule[li].in), buffer(n, hs[n]->schedule[li + 1].out), tokens);
-            if (fa[0].kern == fa[1].kern) {
-                rc = launch_chain2_split(&fa[0], &fa[1], st);
-            } else {                               // e.g. only one of the two streams its 4-bit form
-                rc = launch_chain2_split(&fa[0], nullptr, st);
-                if (rc == TN_OK) rc = launch_chain2_split(&fa[1], nullptr, st);
-            }
-            ++li;
-        } else if (l.steps == 2 && chain2_small_applies(ha, ha->steps[f], tokens) && chain2_small_applies(hb, hb->steps[f], tokens)) {
+        }
+        if (fuse[0] && fuse[1] && fa[0].kern == fa[1].kern) {
+            rc = launch_chain2_split(&fa[0], &fa[1], st);          // pair and wide step of both layers in one launch
+            skip[0] = skip[1] = true;
+        } else if (!skip[0] && !skip[1] && !fuse[0] && !fuse[1] && l.steps == 2 &&
+                   chain2_small_applies(ha, ha->steps[f], tokens) && chain2_small_applies(hb, hb->steps[f], tokens)) {
             Chain2Args ca[2];
             for (int n = 0; n < 2; ++n)
                 ca[n] = chain2_args(hs[n]->steps[f], hs[n]->steps[f + 1], buffer(n, hs[n]->schedule[li].in),
@@ -2458,6 +2460,15 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
             rc = launch_chain2_small(ha->steps[f], ca[0], &ca[1], st);
         } else {
             for (int n = 0; n < 2 && rc == TN_OK; ++n) {
+                if (skip[n]) {
+                    skip[n] = false;
+                    continue;
+                }
+                if (fuse[n]) {                     // e.g. only this layer qualifies, or only one streams its 4-bit form
+                    rc = launch_chain2_split(&fa[n], nullptr, st);
+                    skip[n] = true;
+                    continue;
+                }
                 const tn::LaunchIO& ln = hs[n]->schedule[li];
                 const DevStep& s = hs[n]->steps[f];
                 rc = ln.steps == 2 ? launch_chain2(hs[n], s, hs[n]->steps[f + 1], buffer(n, ln.in), buffer(n, ln.out), tokens, st)
