@@ -65,3 +65,28 @@ def test_random_layer_against_the_oracle(seed):
         err = np.abs(y - ref[:tokens]).max() / top
         assert err <= TOL["bf16"], (seed, tokens, err)
     layer.close()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_layer_large_calls(seed):
+    """The same draw at token counts that run the tiled, chained and Kronecker-sum kernels over several tiles with
+    ragged ends."""
+    rng = np.random.default_rng(88000 + seed)
+    spec = _draw(rng)
+    flags = int(FLAGS[int(rng.integers(0, len(FLAGS)))])
+    ts = [wl.round_to_dtype(rng.standard_normal(shp) / np.sqrt(max(1.0, 0.5 * (shp[0] + shp[-1]))), "bf16")
+          for shp in spec.tensor_shapes()]
+    print(f"seed {seed}: format {spec.format} out {spec.out_modes} in {spec.in_modes} ranks {spec.ranks} flags {flags}", flush=True)
+    used = O.mxfp4_dequantized(ts) if flags & tn.TN_FLAG_QUANT_MXFP4 else ts
+    w = O.dense_weight(spec.format, used, len(spec.out_modes))
+    if np.abs(w).max() == 0.0:
+        pytest.skip("the drawn layer is the zero matrix")
+    layer = make_layer(spec, ts, 1100, flags=flags)
+    x = wl.round_to_dtype(rng.standard_normal((1100, spec.N)), "bf16")
+    ref = O.apply_linear(w, x)
+    top = np.abs(ref).max()
+    for tokens in (257, 1100):
+        y = to_host(layer(to_dev(x[:tokens], "bf16")))
+        err = np.abs(y - ref[:tokens]).max() / top
+        assert err <= TOL["bf16"], (seed, tokens, err)
+    layer.close()
