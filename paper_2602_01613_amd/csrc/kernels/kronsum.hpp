@@ -45,6 +45,7 @@ struct KronArgs {
     int32_t n_splits;      // workgroups sharing one (token quad, chunk): each takes rho_per_split values of rho
     int32_t rho_per_split;
     int32_t x_vec8;        // 8 consecutive k of one a are one aligned 16-byte piece of x
+    int32_t tpw;           // tokens per wave (the TPW instantiation): 1 or 2
     int32_t share;         // one token (the SHARE instantiation): the four waves of a workgroup share ONE token (the workgroup's index
                            // counts tokens, not quads): per value of the bond its (o1 tile, a tile) units are dealt
                            // round-robin to the waves, whose sums are added through LDS in wave order at the end
@@ -100,8 +101,13 @@ __global__ void __launch_bounds__(256) kron_repack1_kernel(const bf16_t* src, bf
 
 // SHARE: the one-token form (KronArgs::share): a compile-time switch, so that the loop of the many-token form stays
 // one straight line of MFMAs and LDS reads (with the test inside it that loop ran 7 % slower).
-template <int AT, int KS0, int O2T, int O1T, int SHARE>
+// TPW: tokens per wave (1 or 2). With two, a wave reads every slice fragment from LDS once for both tokens and has
+// two independent MFMA chains per unit to interleave: used for the instantiations whose slices are small against their
+// MFMA work per token (fewer than 100 MFMAs per 32 KB of slice), where one token per wave left the matrix cores
+// waiting on LDS, and only for calls with tokens enough to fill the chip in groups of eight.
+template <int AT, int KS0, int O2T, int O1T, int SHARE, int TPW>
 __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
+    static_assert(TPW == 1 || !SHARE, "the shared form is for one token");
     using S = KronShape<AT, KS0, O2T, O1T>;
     constexpr int L = S::L, NS = S::NS, NB0 = S::NB0, NB1 = S::NB1, STAGE_BYTES = S::STAGE_BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
@@ -118,17 +124,18 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
     id /= p.n_splits;
     const int chunk = id % p.n_chunks;
     const int quad = id / p.n_chunks;
-    const int t = SHARE ? quad : quad * 4 + wave;
-    const int tl = min(t, p.tokens - 1);                 // waves past the end repeat the last token and store nothing
+    const int t = SHARE ? quad : (quad * 4 + wave) * TPW;      // the wave's first token (its second is t + 1)
+    // waves past the end repeat the last token and store nothing
     const int rho_begin = split * p.rho_per_split;
     const int rho_end = min(p.P, rho_begin + p.rho_per_split);
     const int n_rho = rho_end - rho_begin;               // >= 1 by construction of the grid
 
     // the token's input as row operands of the first contraction: tile i, k-step ks: lane l holds
     // a = 32*i + l%32, k = 16*ks + 8*(l/32) .. +7
-    bf16x8 xa[AT][KS0];
-    {
-        const bf16_t* xt = X + int64_t(tl) * p.N;
+    bf16x8 xa[TPW][AT][KS0];
+#pragma unroll
+    for (int tp = 0; tp < TPW; ++tp) {
+        const bf16_t* xt = X + int64_t(min(t + tp, p.tokens - 1)) * p.N;
         if (p.x_vec8) {
             // Straight-line code: offsets first (clamped into the tables), then all AT * KS0 loads back to back,
             // values outside the matrix replaced by zeros afterwards. With a branch around every load each one
@@ -157,7 +164,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
 #pragma unroll
                 for (int ks = 0; ks < KS0; ++ks) {
                     const bf16x8 v = *reinterpret_cast<const bf16x8*>(xt + ro[i] + co[ks]);
-                    xa[i][ks] = (va[i] && vk[ks]) ? v : zero;
+                    xa[tp][i][ks] = (va[i] && vk[ks]) ? v : zero;
                 }
         } else {
             // element-wise gather (the k of one a are not contiguous in x); the straight-line form measured slower here
@@ -175,7 +182,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = xt[ro + p.xcol[k + e]];
                     }
-                    xa[i][ks] = v;
+                    xa[tp][i][ks] = v;
                 }
             }
         }
@@ -198,13 +205,15 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
         }
     };
 
-    floatx16 acc[O2T][O1T];
+    floatx16 acc[TPW][O2T][O1T];
 #pragma unroll
-    for (int j = 0; j < O2T; ++j)
+    for (int tp = 0; tp < TPW; ++tp)
 #pragma unroll
-        for (int o = 0; o < O1T; ++o)
+        for (int j = 0; j < O2T; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][o][v] = 0.f;
+            for (int o = 0; o < O1T; ++o)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tp][j][o][v] = 0.f;
 
     issue(rho_begin, 0);
     if (n_rho > 1) issue(rho_begin + 1, 1);
@@ -228,29 +237,40 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
 #pragma unroll
                     for (int s = 0; s < 2; ++s)
                         h1[j][s] = *reinterpret_cast<const bf16x8*>(sb + (NB0 + (j * AT + i) * 2 + s) * 1024);
-                floatx16 d;
+                floatx16 d[TPW];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) d[v] = 0.f;
+                for (int tp = 0; tp < TPW; ++tp)
 #pragma unroll
-                for (int ks = 0; ks < KS0; ++ks) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i][ks], h0[ks], d, 0, 0, 0);
+                    for (int v = 0; v < 16; ++v) d[tp][v] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS0; ++ks)
+#pragma unroll
+                    for (int tp = 0; tp < TPW; ++tp)
+                        d[tp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tp][i][ks], h0[ks], d[tp], 0, 0, 0);
                 // registers 8s .. 8s+7 are the 8 values of a this lane supplies to k-step s
-                bf16x8 zb[2];
+                bf16x8 zb[TPW][2];
 #pragma unroll
-                for (int s = 0; s < 2; ++s)
+                for (int tp = 0; tp < TPW; ++tp)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) zb[s][e] = bf16_t(d[8 * s + e]);
+                    for (int s = 0; s < 2; ++s)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) zb[tp][s][e] = bf16_t(d[tp][8 * s + e]);
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int j = 0; j < O2T; ++j)
-                        acc[j][o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(h1[j][s], zb[s], acc[j][o], 0, 0, 0);
+#pragma unroll
+                        for (int tp = 0; tp < TPW; ++tp)
+                            acc[tp][j][o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(h1[j][s], zb[tp][s], acc[tp][j][o], 0, 0, 0);
             }
         }
         // keep the accumulators in the accumulation registers across the back edge
 #pragma unroll
-        for (int j = 0; j < O2T; ++j)
+        for (int tp = 0; tp < TPW; ++tp)
 #pragma unroll
-            for (int o = 0; o < O1T; ++o) asm volatile("" : "+a"(acc[j][o]));
+            for (int j = 0; j < O2T; ++j)
+#pragma unroll
+                for (int o = 0; o < O1T; ++o) asm volatile("" : "+a"(acc[tp][j][o]));
     }
 
     if (SHARE) {
@@ -268,7 +288,7 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             float* q = red + ((j * O1T + o) * 16 + v) * 64 + lane;
-                            *q = w == 0 ? acc[j][o][v] : *q + acc[j][o][v];
+                            *q = w == 0 ? acc[0][j][o][v] : *q + acc[0][j][o][v];
                         }
             }
             __syncthreads();
@@ -279,33 +299,36 @@ __global__ void __launch_bounds__(256, 1) step_kronsum_kernel(KronArgs p) {
             for (int o = 0; o < O1T; ++o)
                 if (((j * O1T + o) & 3) == wave) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[j][o][v] = red[((j * O1T + o) * 16 + v) * 64 + lane];
+                    for (int v = 0; v < 16; ++v) acc[0][j][o][v] = red[((j * O1T + o) * 16 + v) * 64 + lane];
                 }
     }
     // lane l, register v of acc[j][o]: o2 = 32*j + 8*(v/4) + 4*(l/32) + v%4, o1 = 32*O1T*chunk + 32*o + l%32
-    if (t >= p.tokens) return;
     int yr[O1T];
 #pragma unroll
     for (int o = 0; o < O1T; ++o) {
         const int o1 = 32 * O1T * chunk + 32 * o + (lane & 31);
         yr[o] = o1 < p.O1 ? p.yrow[o1] : -1;
     }
-    bf16_t* yb = static_cast<bf16_t*>(p.Y) + int64_t(t) * p.M;
-    float* yf = static_cast<float*>(p.Y) + (int64_t(split) * p.tokens + t) * p.M;
 #pragma unroll
-    for (int j = 0; j < O2T; ++j)
+    for (int tp = 0; tp < TPW; ++tp) {
+        if (t + tp >= p.tokens) break;
+        bf16_t* yb = static_cast<bf16_t*>(p.Y) + int64_t(t + tp) * p.M;
+        float* yf = static_cast<float*>(p.Y) + (int64_t(split) * p.tokens + t + tp) * p.M;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int o2 = 32 * j + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (o2 >= p.C1) continue;
-            const int yc = p.ycol[o2];
+        for (int j = 0; j < O2T; ++j)
 #pragma unroll
-            for (int o = 0; o < O1T; ++o) {
-                if (yr[o] < 0 || (SHARE && ((j * O1T + o) & 3) != wave)) continue;
-                if (p.n_splits > 1) yf[yr[o] + yc] = acc[j][o][v];
-                else yb[yr[o] + yc] = bf16_t(acc[j][o][v]);
+            for (int v = 0; v < 16; ++v) {
+                const int o2 = 32 * j + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (o2 >= p.C1) continue;
+                const int yc = p.ycol[o2];
+#pragma unroll
+                for (int o = 0; o < O1T; ++o) {
+                    if (yr[o] < 0 || (SHARE && ((j * O1T + o) & 3) != wave)) continue;
+                    if (p.n_splits > 1) yf[yr[o] + yc] = acc[tp][j][o][v];
+                    else yb[yr[o] + yc] = bf16_t(acc[tp][j][o][v]);
+                }
             }
-        }
+    }
 }
 
 // Y[i] = bf16( sum_s partial[s][i] ) for n = tokens * M values (n % 4 == 0). A workgroup owns 64 consecutive

@@ -768,23 +768,40 @@ constexpr int64_t kKronMinTokens = 1;
 struct KronTiles {
     int at = 0, ks0 = 0, o2t = 0, o1t = 0;
     size_t smem = 0;
+    bool two_tokens = false;      // the instantiation with two tokens per wave exists
 };
+
+// Two tokens per wave where the registers allow it: at most 12 accumulation tiles (192 registers) for the two tokens'
+// sums and at most 32 fragments of their inputs (<3,4,4,2> with 16 tiles spills).
+template <int AT, int KS0, int O2T, int O1T>
+constexpr bool kron_two_tokens_fit() { return 2 * O2T * O1T <= 12 && 2 * AT * KS0 <= 32; }
 
 template <int AT, int KS0, int O2T, int O1T>
 int kron_entry(const KronArgs* p, uint32_t grid, hipStream_t st, KronTiles* tiles) {
     using S = KronShape<AT, KS0, O2T, O1T>;
+    constexpr bool two = kron_two_tokens_fit<AT, KS0, O2T, O1T>();
     if (tiles) {
-        *tiles = KronTiles{AT, KS0, O2T, O1T, S::SMEM};
+        *tiles = KronTiles{AT, KS0, O2T, O1T, S::SMEM, two};
         return TN_OK;
     }
-    if (!p)         // configuration call (create time)
-        return (hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 0>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess &&
-                hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess)
-                   ? TN_OK : TN_ERR_HIP;
-    if (p->share) hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 1>), dim3(grid), dim3(256), S::SMEM, st, *p);
-    else hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 0>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    if (!p) {       // configuration call (create time)
+        bool ok = hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 0, 1>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess &&
+                  hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 1, 1>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess;
+        if constexpr (two)
+            ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(step_kronsum_kernel<AT, KS0, O2T, O1T, 0, 2>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, int(S::SMEM)) == hipSuccess;
+        return ok ? TN_OK : TN_ERR_HIP;
+    }
+    if (p->share) {
+        hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 1, 1>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    } else if (p->tpw == 2) {
+        if constexpr (two) hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 0, 2>), dim3(grid), dim3(256), S::SMEM, st, *p);
+        else return TN_ERR_UNSUPPORTED;
+    } else {
+        hipLaunchKernelGGL((step_kronsum_kernel<AT, KS0, O2T, O1T, 0, 1>), dim3(grid), dim3(256), S::SMEM, st, *p);
+    }
     return TN_OK;
 }
 
@@ -812,25 +829,36 @@ struct KronGeom {
     int n_chunks = 1, n_splits = 1, rho_per_split = 1;
     int64_t quads = 1, partial_bytes = 0;
     bool share = false;       // the four waves of a workgroup share one token (quads then counts tokens)
+    int tpw = 1;              // tokens per wave (quads then counts groups of 4 * tpw tokens)
 };
 
 // measured on seven ring classes with stored half rings (us per call, shared / a wave per token): one token 30/44,
 // 110/214, 146/206, 79/119, 51/65, 31/35, 16/16; two tokens 34/44, 165/195, 214/204, 109/111, 65/63, 41/36, 18/17
 constexpr int64_t kKronShareMaxTokens = 1;
+// calls from which a wave takes two tokens, where that instantiation exists (8192->5120 at rank 64, ms per call, two / one:
+// 64 tokens 0.63 / 0.67, 128 1.15 / 1.23, 300 2.46 / 2.74, 8192 58.4 / 65.6)
+constexpr int64_t kKronTwoTokensMin = 64;
 
 KronGeom kron_geometry(const tn_linear_s* h, const tn::KronDims& d, int64_t tokens, int64_t partial_cap) {
     KronGeom g;
     const int o1_chunk = 32 * tn::kKronConfig[d.cfg][3];
     g.n_chunks = int((d.O1 + o1_chunk - 1) / o1_chunk);
     g.share = tokens <= kKronShareMaxTokens && !(h->flags & TN_FLAG_NO_DECODE_FUSION);
-    g.quads = g.share ? tokens : (tokens + 3) / 4;
+    {
+        KronTiles kt;
+        const bool two = kron_dispatch(d.cfg, nullptr, 0, nullptr, &kt) == TN_OK && kt.two_tokens;
+        g.tpw = (two && tokens >= kKronTwoTokensMin) ? 2 : 1;
+    }
+    g.quads = g.share ? tokens : (tokens + 4 * g.tpw - 1) / (4 * g.tpw);
     int64_t base = g.quads * g.n_chunks;
     // workgroups a CU holds at a time: one when the three LDS stages take more than half of its 160 KB
     const int* cfg = tn::kKronConfig[d.cfg];
     const int64_t stage_bytes = 4096 * int64_t((cfg[3] * cfg[1] + cfg[2] * 2 * cfg[0] + 3) / 4);
     // (measured: with several chunks of o1 the two-round split is the faster one at rank 96, so it is kept there)
     const int64_t per_cu = (3 * stage_bytes > 80 * 1024 && g.n_chunks == 1) ? 1 : 2;
-    int64_t want = std::max<int64_t>(1, (per_cu * int64_t(h->num_cus) + base - 1) / base);
+    // as many splits as keep the grid within one round of workgroups (rounding up instead left a second round with a
+    // handful of workgroups: 300 tokens took as long as 512)
+    int64_t want = std::max<int64_t>(1, per_cu * int64_t(h->num_cus) / base);
     if (base >= h->num_cus) want = 1;
     // at least 4 values of the bond per workgroup, partial sums within their buffer
     want = std::min<int64_t>(want, std::max<int64_t>(1, d.P / 4));
@@ -912,6 +940,7 @@ int launch_kron(const tn_linear_s* h, const Workspace& w, const KronSetup& k, co
     p.rho_per_split = g.rho_per_split;
     p.x_vec8 = d.x_vec8 ? 1 : 0;
     p.share = g.share ? 1 : 0;
+    p.tpw = g.tpw;
     const int64_t grid = g.quads * g.n_chunks * g.n_splits;
     int rc = kron_dispatch(d.cfg, &p, uint32_t(grid), st);
     if (rc != TN_OK) return rc;
