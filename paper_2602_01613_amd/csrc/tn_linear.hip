@@ -811,7 +811,7 @@ int kron_entry(const KronArgs* p, uint32_t grid, hipStream_t st, KronTiles* tile
             p, grid, st, tiles);
 
 int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, KronTiles* tiles = nullptr) {
-    static_assert(tn::kKronConfigs == 7, "one case per instantiation");
+    static_assert(tn::kKronConfigs == 8, "one case per instantiation");
     switch (cfg) {
         TN_KRON_CASE(0)
         TN_KRON_CASE(1)
@@ -820,6 +820,7 @@ int kron_dispatch(int cfg, const KronArgs* p, uint32_t grid, hipStream_t st, Kro
         TN_KRON_CASE(4)
         TN_KRON_CASE(5)
         TN_KRON_CASE(6)
+        TN_KRON_CASE(7)
         default: return TN_ERR_INVALID_ARG;
     }
 }

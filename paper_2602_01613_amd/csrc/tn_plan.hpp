@@ -687,9 +687,9 @@ struct KronDims {
     bool x_vec8 = true;
 };
 
-constexpr int kKronConfigs = 7;
+constexpr int kKronConfigs = 8;
 constexpr int kKronConfig[kKronConfigs][4] = {{5, 10, 3, 2}, {3, 4, 5, 2}, {4, 4, 3, 2}, {2, 5, 5, 2},
-                                              {2, 8, 2, 3}, {2, 5, 1, 1}, {3, 4, 4, 2}};
+                                              {2, 8, 2, 3}, {2, 5, 1, 1}, {3, 4, 4, 2}, {2, 5, 5, 1}};
 
 inline bool kron_shape(const Plan& p, KronDims* d) {
     if (p.dtype != TN_DTYPE_BF16 || p.steps.size() != 2) return false;

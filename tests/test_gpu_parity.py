@@ -478,12 +478,14 @@ KRON_FORCE = 20 << tn.TN_FLAG_VARIANT_SHIFT
 KRON_CASES = [
     # (format, out modes, in modes, ranks, flags, instantiation): two-step plans over a shared bond
     (tn.TN_FORMAT_TT, (40, 36), (10, 64), (1, 40, 1), KRON_FORCE, 3),          # plain x, K0 = 64, one chunk of o1
-    (tn.TN_FORMAT_TT, (70, 150), (4, 32), (1, 40, 1), KRON_FORCE, 3),          # 150 values of o1: three chunks, ragged
+    (tn.TN_FORMAT_TT, (70, 150), (4, 32), (1, 40, 1), KRON_FORCE, 7),          # 150 values of o1: five chunks of one tile, ragged
+    (tn.TN_FORMAT_TT, (70, 120), (4, 32), (1, 40, 1), KRON_FORCE, 3),          # 120 values of o1: two chunks of two tiles, ragged
     (tn.TN_FORMAT_TT, (12, 8), (120, 64), (1, 24, 1), KRON_FORCE, 2),          # A = 120: four tiles of a, ragged
     (tn.TN_FORMAT_TR, (4, 6, 5, 8), (2, 5, 7, 8), (3, 4, 2, 5, 3),             # a ring as two half rings, x gathered
      KRON_FORCE | tn.TN_FLAG_MERGE_GROW | tn.TN_FLAG_NO_SMALL_CHAIN, 5),       # in 16-byte pieces, K0 = 56
     (tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, tn.TN_FLAG_MERGE_GROW, 6),   # taken without forcing
     (tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, tn.TN_FLAG_MERGE_GROW, 4),   # x gathered element-wise, 3 tiles of o1
+    (tn.TN_FORMAT_TR, (10, 16, 10, 16), (8, 10, 8, 8), (12,) * 5, tn.TN_FLAG_MERGE_GROW, 7),  # o1 = 160: five chunks, two tokens per wave
 ]
 
 
@@ -536,7 +538,7 @@ def test_kronecker_sum_kernel_caller_workspace(dense_w):
 LAZY_CASES = [
     # rings of four cores whose large calls run on the two-half-ring plan rebuilt in the workspace
     ((8, 10, 8, 8), (10, 16, 10, 16), (32,) * 5),       # the down_proj workload
-    ((10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5),       # three chunks of o1, x gathered element-wise
+    ((10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5),       # five chunks of o1, x gathered element-wise
     ((8, 16, 8, 8), (8, 10, 8, 8), (48,) * 5),          # 2304 values of the shared bond: over a quarter of dense
     ((4, 8, 4, 8), (8, 10, 8, 8), (32,) * 5),           # 32 x 32 outputs per term: the smallest instantiation
 ]

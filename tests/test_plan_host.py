@@ -214,7 +214,7 @@ def test_kronecker_sum_plans():
     assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow) == 1            # <5, 10, 3, 2>
     assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow | tn.TN_FLAG_NO_PAIR_CHAIN) == 0
     assert q(ring.format, ring.out_modes, ring.in_modes, ring.ranks, grow, tn.TN_DTYPE_F32) == 0
-    assert q(ring.format, ring.in_modes[:0] + (10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5, grow) == 4    # <2, 5, 5, 2>
+    assert q(ring.format, ring.in_modes[:0] + (10, 16, 10, 16), (8, 10, 8, 8), (32,) * 5, grow) == 8    # <2, 5, 5, 1>: o1 = 160 is five tiles
     assert q(tn.TN_FORMAT_TR, (8, 16, 8, 8), (8, 10, 8, 8), (16,) * 5, grow) == 7          # <3, 4, 4, 2>
     assert q(tn.TN_FORMAT_TR, (8, 10, 8, 8), (8, 16, 8, 8), (16,) * 5, grow) == 5          # <2, 8, 2, 3>
     train, _ = wl.baseline_spec(1)
