@@ -495,10 +495,11 @@ def gradient_record(spec, config_id, tokens, reps=3):
            "flops_per_token": flops, "tflops": flops * tokens / sec / 1e12,
            "backward_chunk_tokens": layer.query(tn.TN_QUERY_BACKWARD_CHUNK_TOKENS),
            "backward_workspace_MB": layer.query(tn.TN_QUERY_BACKWARD_WORKSPACE_BYTES) / 1e6,
-           "roofline": {"bound": "alu", "achieved": flops * tokens / sec / 1e12, "peak": 157.3, "unit": "TFLOP/s",
-                        "frac": flops * tokens / sec / 1e12 / 157.3,
-                        "kernel": "whole call; its parameter-gradient contractions run on plain fp32 FMA (the forward and "
-                                  "input-gradient steps on the MFMA step kernels), so the fp32 vector peak is the yardstick"}}
+           "roofline": {"bound": "mfma", "achieved": flops * tokens / sec / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": flops * tokens / sec / 1e12 / 2500.0,
+                        "kernel": "whole call: forward and input-gradient steps on the MFMA step kernels, parameter-gradient "
+                                  "contractions on grad_param_mfma_kernel (bf16 tensors of at least 32 x 32; 128 x 128 tiles fed "
+                                  "by element loads, which is what bounds them) or, for skinny tensors, on plain fp32 FMA"}}
     layer.close()
     return out
 

@@ -239,7 +239,8 @@ int tn_linear_create(tn_linear_t* out, const tn_linear_desc* desc);
  * Y = X W^T for `tokens` rows (Section 3.5, the TN matmul).
  *  x  DEVICE [tokens, N] of the handle's dtype, read only
  *  y  DEVICE [tokens, M] of the handle's dtype, fully overwritten
- *  x and y must not overlap each other. Enqueues kernels on `stream`
+ *  x and y must not overlap each other and must be 16-byte aligned (device allocations are; TN_ERR_INVALID_ARG
+ *  otherwise: rows are read and written in 16-byte pieces). Enqueues kernels on `stream`
  *  (hipStream_t) and returns without synchronising or allocating; with
  *  profiling off it makes no other HIP call than kernel launches, so it may be
  *  recorded into a HIP graph (stream capture) from the handle's first call on.
@@ -267,7 +268,7 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
  * loss is back-propagated through every factorised layer). For L = sum_{t,i} dY[t,i] Y[t,i] with Y = X W^T:
  *   grads[s]  DEVICE fp32 array of the shape of desc.tensors[s] (canonical layout), overwritten with dL/d tensors[s];
  *             a NULL entry skips that tensor. The array of pointers is host memory, n_tensors entries.
- *   x  DEVICE [tokens, N], dy DEVICE [tokens, M], of the handle's dtype, read only.
+ *   x  DEVICE [tokens, N], dy DEVICE [tokens, M], of the handle's dtype, read only, 16-byte aligned.
  * The call re-runs the contraction steps keeping every intermediate, then walks them backwards: for each step the
  * gradient of its parameter tensor is the step's own contraction with the token and row indices summed (fp32
  * accumulation, partial sums over row ranges added in a fixed order: bit-reproducible), and the gradient handed to

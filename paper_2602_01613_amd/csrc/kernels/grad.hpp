@@ -29,6 +29,7 @@ struct GradArgs {
     uint32_t total_rows, R;
     int32_t K, C;
     uint32_t rows_per_split;
+    int32_t c_tiles, k_tiles, n_split;      // grad_param_mfma_kernel: a one-dimensional grid of c_tiles * k_tiles * n_split workgroups
 };
 
 template <typename T>
@@ -88,6 +89,121 @@ __global__ void __launch_bounds__(256) grad_param_kernel(GradArgs a) {
             if (k < a.K) out[int64_t(c) * a.K + k] = acc[i][j];
         }
     }
+}
+
+// The same contraction on the matrix cores, for bf16 layers: a workgroup owns a 128 x 128 tile of (c, k), each of
+// its four waves a 64 x 64 quarter (2 x 2 MFMA tiles, fp32 accumulators). The contracted index is the row g, which
+// is the slow index of both operands in memory, while an MFMA lane supplies 8 consecutive values of the contracted
+// index: so the rows go through LDS 32 at a time, stored transposed ([column][g], 16 consecutive g of one column per
+// thread as two 16-byte writes), and a fragment is one 16-byte LDS read. Both operands are read through the forward
+// step's own tables, one element per lane and load, with the lanes of a load along the fast index of a row; the row
+// of a load is the same for the whole wave, so its token and table entry sit in scalar registers. The loads of the
+// next 32 rows are requested before the current ones are multiplied. Partial tiles as in grad_param_kernel.
+__global__ void __launch_bounds__(256) grad_param_mfma_kernel(GradArgs a) {
+    constexpr int BT = 128, BG = 32, PITCH = BG + 8;            // bf16 elements per LDS row: 80 bytes, 16-byte aligned
+    __shared__ __attribute__((aligned(16))) bf16_t sD[BT * PITCH];
+    __shared__ __attribute__((aligned(16))) bf16_t sI[BT * PITCH];
+    const bf16_t* dOut = static_cast<const bf16_t*>(a.dOut);
+    const bf16_t* In = static_cast<const bf16_t*>(a.In);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // workgroup -> (tile, split). With a multiple of 8 splits, all tiles of one split run on one XCD (workgroups are
+    // dealt to the 8 XCDs in turn): the rows of a split then come from memory once, into that XCD's L2, for all of its
+    // tiles, instead of once per XCD.
+    const int tiles = a.c_tiles * a.k_tiles;
+    int tile, split;
+    if ((a.n_split & 7) == 0) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        tile = j % tiles;
+        split = (j / tiles) * 8 + xcd;
+    } else {
+        tile = blockIdx.x % tiles;
+        split = blockIdx.x / tiles;
+    }
+    const int c0 = (tile % a.c_tiles) * BT, k0 = (tile / a.c_tiles) * BT;
+    const uint32_t g_begin = min(a.total_rows, uint32_t(split) * a.rows_per_split);
+    const uint32_t g_end = min(a.total_rows, g_begin + a.rows_per_split);
+    // loads: thread -> column cc of both tiles and the 16 rows 16*half .. 16*half + 15 of a group of 32 (half is
+    // wave-uniform)
+    const int cc = tid & 127;
+    const int half = wave >> 1;
+    const bool vc = c0 + cc < a.C, vk = k0 + cc < a.K;
+    // table entries are offsets inside one token: non-negative, below 2^31 (checked when the plan is built)
+    const uint32_t col_d = vc ? uint32_t(a.ccol[c0 + cc]) : 0u;
+    const uint32_t col_i = vk ? (a.acol ? uint32_t(a.acol[k0 + cc]) : uint32_t(k0 + cc)) : 0u;
+    bf16x8 rd[2], ri[2];
+    auto request = [&](uint32_t g0) {
+        const uint32_t g = g0 + 16u * uint32_t(half);
+        uint32_t t = g / a.R, r = g - t * a.R;                  // wave-uniform
+        // all 16 row offsets first (scalar table reads, one wait), then the 32 loads back to back: with offset and
+        // load of one row next to each other every load waited for its own table entry
+        int64_t od[16], oi[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const bool live = g + uint32_t(j) < g_end;
+            od[j] = live ? int64_t(t) * a.c_tok_stride + a.crow[r] : -1;
+            oi[j] = live ? int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K) : -1;
+            if (++r == a.R) {
+                r = 0;
+                ++t;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            // a wave-uniform row pointer plus a 32-bit lane offset: no vector arithmetic per load
+            rd[j >> 3][j & 7] = (od[j] >= 0 && vc) ? (dOut + od[j])[col_d] : bf16_t(0.f);
+            ri[j >> 3][j & 7] = (oi[j] >= 0 && vk) ? (In + oi[j])[col_i] : bf16_t(0.f);
+        }
+    };
+    auto deposit = [&]() {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            *reinterpret_cast<bf16x8*>(sD + cc * PITCH + 16 * half + 8 * q) = rd[q];
+            *reinterpret_cast<bf16x8*>(sI + cc * PITCH + 16 * half + 8 * q) = ri[q];
+        }
+    };
+    // wave -> quarter (wc, wk); MFMA row operand: c, column operand: k; lane l supplies g = 8*(l/32) .. +7 of a k-step
+    const int wc = wave >> 1, wk = wave & 1;
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    if (g_begin < g_end) request(g_begin);
+    for (uint32_t g0 = g_begin; g0 < g_end; g0 += BG) {
+        deposit();
+        __syncthreads();
+        if (g0 + BG < g_end) request(g0 + BG);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 fd[2], fi[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                fd[i] = *reinterpret_cast<const bf16x8*>(sD + (64 * wc + 32 * i + (lane & 31)) * PITCH + 16 * ks + 8 * (lane >> 5));
+                fi[i] = *reinterpret_cast<const bf16x8*>(sI + (64 * wk + 32 * i + (lane & 31)) * PITCH + 16 * ks + 8 * (lane >> 5));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[i], fi[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();                                        // everyone has read the group before it is overwritten
+    }
+    // lane l, register v of acc[i][j]: c = c0 + 64*wc + 32*i + 8*(v/4) + 4*(l/32) + v%4, k = k0 + 64*wk + 32*j + l%32
+    float* out = a.partial + int64_t(split) * a.C * a.K;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int k = k0 + 64 * wk + 32 * j + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = c0 + 64 * wc + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (c < a.C && k < a.K) out[int64_t(c) * a.K + k] = acc[i][j][v];
+            }
+        }
 }
 
 // grad[position of (c, k) in the caller's tensor] (+)= sum over splits of partial[split][c][k]. The position follows the

@@ -81,6 +81,8 @@ __global__ void __launch_bounds__(256) step_scalar_kernel(StepArgs a) {
 // along whichever direction (columns or rows) is contiguous in the output layout.
 //   AMODE 0: A rows are plain and K % 8 == 0 -> 16-byte global loads
 //   AMODE 1: element-wise gather (tables, or K not a multiple of 8)
+//   AMODE 2 (step_mfma_pipe_kernel only): rows through the tables, the k of a row in aligned contiguous runs of 8
+//            (tn::Step::a_vec): 16-byte loads at arow[r] + acol[k]
 //   CMODE 0: scalar stores; 1: 8 contiguous columns per store; 2: 8 contiguous rows per store
 // ---------------------------------------------------------------------------------------------
 template <int WM, int WN, int TM, int TN, int AMODE>
@@ -301,8 +303,8 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
 
     // A addressing: AMODE 0 -> one pointer, rows 32*j apart; AMODE 1 -> per-row element offsets
     const bf16_t* a_ptr = A + int64_t(row0 + lrow) * a.K + lkc;
-    int64_t a_base[AMODE == 1 ? A_CHUNKS : 1];
-    if (AMODE == 1) {
+    int64_t a_base[AMODE != 0 ? A_CHUNKS : 1];
+    if (AMODE != 0) {
 #pragma unroll
         for (int j = 0; j < A_CHUNKS; ++j) {
             uint32_t g = row0 + lrow + RPP * j;
@@ -330,6 +332,8 @@ step_mfma_pipe_kernel(StepArgs a, int cmode, int nrow_tiles, int ncol_tiles) {
             if (AMODE == 0) {
                 if (row0 + lrow + RPP * j < a.total_rows && k < a.K)
                     v = *reinterpret_cast<const bf16x8*>(a_ptr + int64_t(RPP * j) * a.K + k0);
+            } else if (AMODE == 2) {
+                if (a_base[j] >= 0 && k < a.K) v = *reinterpret_cast<const bf16x8*>(A + a_base[j] + a.acol[k]);
             } else if (a_base[j] >= 0) {
 #pragma unroll
                 for (int q = 0; q < 8; ++q)

@@ -243,7 +243,9 @@ void choose_variant(const tn_linear_s* h, DevStep* s, int flags) {
             default: s->bm = 256; s->bn = 256; break;      // VAR_PINGPONG_256x256
         }
     }
-    s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : 1;
+    // 0: plain rows of 16-byte pieces; 2: gathered rows of 16-byte pieces (the tiled pipeline kernel; every other kernel
+    // reads such a step element by element, like 1); 1: element-wise gather
+    s->amode = (p.a_plain && p.K % 8 == 0) ? 0 : (p.a_vec == 8 ? 2 : 1);
     s->cmode = p.c_vec == 8 ? 1 : (p.r_vec == 8 ? 2 : 0);
     s->Kp = round_up(int(p.K), 64);
     s->Cp = round_up(int(p.C), s->bn);
@@ -374,9 +376,10 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
     int nrow_pad = (nrow + 7) / 8 * 8;
     dim3 grid(uint32_t(nrow_pad) * uint32_t(ncol));
     using kern_t = void (*)(StepArgs, int, int, int);
-    static const kern_t kerns[4] = {
+    static const kern_t kerns[6] = {
         step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 0>, step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 0>,
-        step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 1>, step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 1>};
+        step_mfma_pipe_kernel<WM, WN, TM, TN, 2, STAGES, MINB, 0>, step_mfma_pipe_kernel<WM, WN, TM, TN, 0, STAGES, MINB, 1>,
+        step_mfma_pipe_kernel<WM, WN, TM, TN, 1, STAGES, MINB, 1>, step_mfma_pipe_kernel<WM, WN, TM, TN, 2, STAGES, MINB, 1>};
     if (!s.packed) {                       // configuration call (create time): raise the kernels' LDS limit
         for (kern_t k : kerns)
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -384,7 +387,7 @@ int launch_pipe(const DevStep& s, const StepArgs& a, int64_t rows, hipStream_t s
                 return TN_ERR_HIP;
         return TN_OK;
     }
-    kern_t k = kerns[(s.cmode == 2 ? 2 : 0) + (s.amode == 0 ? 0 : 1)];
+    kern_t k = kerns[(s.cmode == 2 ? 3 : 0) + s.amode];
     hipLaunchKernelGGL(k, grid, dim3(WM * WN * 64), smem, st, a, s.cmode, nrow, ncol);
     return TN_OK;
 }
@@ -1709,15 +1712,23 @@ void launch_pack(const PackArgs& pa, int elt, hipStream_t st) {
 
 // ---- gradients with respect to the parameter tensors (TN_FLAG_TRAINABLE) ----
 constexpr int64_t kMaxGradPartialBytes = int64_t(256) << 20;
+constexpr int64_t kGradMfmaMinExtent = 32;
 
 // Row ranges a gradient launch is split into: enough workgroups to fill the chip, at least 64 rows each, partial
 // tiles within `cap` bytes.
+// bf16 steps whose tensor is at least a quarter of a 128 x 128 tile in both directions run on the matrix cores
+bool grad_on_mfma(const tn_linear_s* h, const tn::Step& p) { return h->elt == 2 && p.C >= kGradMfmaMinExtent && p.K >= kGradMfmaMinExtent; }
+
 int grad_splits(const tn_linear_s* h, const tn::Step& p, int64_t rows, int64_t cap) {
-    const int64_t tiles = ((p.C + 63) / 64) * ((p.K + 63) / 64);
-    int64_t n = std::max<int64_t>(1, (4 * int64_t(h->num_cus) + tiles - 1) / tiles);
+    const int64_t edge = grad_on_mfma(h, p) ? 128 : 64;
+    const int64_t tiles = ((p.C + edge - 1) / edge) * ((p.K + edge - 1) / edge);
+    int64_t n = std::max<int64_t>(1, ((edge == 128 ? 2 : 4) * int64_t(h->num_cus) + tiles - 1) / tiles);
     n = std::min<int64_t>(n, std::max<int64_t>(1, rows / 64));
     n = std::min<int64_t>(n, std::max<int64_t>(1, cap / (p.C * p.K * 4)));
-    return int(std::min<int64_t>(n, 65535));
+    n = std::min<int64_t>(n, 65535);
+    // the matrix-core kernel keeps the tiles of a split on one XCD when the splits come in eights
+    if (edge == 128 && n > 8 && (n + 7) / 8 * 8 * p.C * p.K * 4 <= cap && (n + 7) / 8 * 8 <= std::max<int64_t>(1, rows / 64)) n = (n + 7) / 8 * 8;
+    return int(n);
 }
 
 int prepare_backward(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st) {
@@ -1752,6 +1763,7 @@ int prepare_backward(tn_linear_s* h, const tn_linear_desc* desc, hipStream_t st)
         b.plan.c_tok_stride = f.a_tok_stride;
         b.plan.c_vec = (f.K % 8 == 0) ? 8 : 1;
         b.plan.r_vec = 1;
+        b.plan.a_vec = (f.c_vec == 8 && f.C % 8 == 0) ? 8 : 1;       // dOut's columns in 16-byte runs: gathered as such
         b.plan.kdims = f.cdims;
         b.plan.cdims = f.kdims;
         b.plan.trace_extent = f.trace_extent;
@@ -1829,9 +1841,19 @@ int launch_param_gradient(const tn_linear_s* h, const DevStep& s, const void* dO
     a.K = int32_t(p.K);
     a.C = int32_t(p.C);
     a.rows_per_split = uint32_t((rows + n_split - 1) / n_split);
-    dim3 grid(uint32_t((p.C + 63) / 64), uint32_t((p.K + 63) / 64), uint32_t(n_split));
+    const bool mfma = grad_on_mfma(h, p);
+    const int64_t edge = mfma ? 128 : 64;
+    dim3 grid(uint32_t((p.C + edge - 1) / edge), uint32_t((p.K + edge - 1) / edge), uint32_t(n_split));
     if (grid.y > 65535) return TN_ERR_UNSUPPORTED;
-    if (h->elt == 2)
+    a.c_tiles = int32_t(grid.x);
+    a.k_tiles = int32_t(grid.y);
+    a.n_split = n_split;
+    if (mfma) {
+        const int64_t wgs = int64_t(grid.x) * grid.y * n_split;
+        if (wgs > (int64_t(1) << 30)) return TN_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(grad_param_mfma_kernel, dim3(uint32_t(wgs)), dim3(256), 0, st, a);
+    }
+    else if (h->elt == 2)
         hipLaunchKernelGGL(grad_param_kernel<bf16_t>, grid, dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL(grad_param_kernel<float>, grid, dim3(256), 0, st, a);
@@ -2410,10 +2432,13 @@ int forward_in(tn_linear_s* h, const Workspace& w, bool allow_lazy, const void* 
 
 extern "C" {
 
+// the kernels read and write rows of activations in 16-byte pieces
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 int tn_linear_forward(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
     if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
     if (tokens == 0) return TN_OK;
-    if (!x || !y) return TN_ERR_INVALID_ARG;
+    if (!x || !y || !aligned16(x) || !aligned16(y)) return TN_ERR_INVALID_ARG;
     Workspace w;
     w.ws[0] = h->ws[0];
     w.ws[1] = h->ws[1];
@@ -2427,7 +2452,7 @@ int tn_linear_forward2(tn_linear_t ha, tn_linear_t hb, const void* x, void* ya, 
     if (!ha || !hb || tokens < 0) return TN_ERR_INVALID_ARG;
     if (ha->elt != hb->elt || ha->plan.N != hb->plan.N) return TN_ERR_INVALID_ARG;
     if (tokens == 0) return TN_OK;
-    if (!x || !ya || !yb) return TN_ERR_INVALID_ARG;
+    if (!x || !ya || !yb || !aligned16(x) || !aligned16(ya) || !aligned16(yb)) return TN_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // Launch by launch in step when the two layers have the same launch structure and the call is one pass of
     // the per-step path for both: where a launch of the decode-size kernels serves both layers, it does.
@@ -2514,7 +2539,7 @@ int tn_linear_param_gradients(tn_linear_t h, const void* x, const void* dy, void
                               void* stream) {
     if (!h || tokens < 0 || !grads || !h->trainable) return TN_ERR_INVALID_ARG;
     if (tokens == 0) return TN_OK;
-    if (!x || !dy) return TN_ERR_INVALID_ARG;
+    if (!x || !dy || !aligned16(x) || !aligned16(dy)) return TN_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t n = h->steps.size();
     Workspace w;                                   // the forward workspace serves the split-K partial sums
@@ -2574,7 +2599,7 @@ int tn_linear_quantized_tensor(tn_linear_t h, int32_t slot, void* codes, void* e
 int tn_linear_forward_scratch(tn_linear_t h, const void* x, void* y, int64_t tokens, void* stream) {
     if (!h || tokens < 0) return TN_ERR_INVALID_ARG;
     if (tokens == 0) return TN_OK;
-    if (!x || !y || h->profiling) return TN_ERR_INVALID_ARG;       // profiling creates events, i.e. allocates
+    if (!x || !y || !aligned16(x) || !aligned16(y) || h->profiling) return TN_ERR_INVALID_ARG;       // profiling creates events, i.e. allocates
     void* base = (h->device >= 0 && h->device < 64) ? g_scratch_ptr[h->device] : nullptr;
     if (!base) return TN_ERR_UNSUPPORTED;
     Workspace w;

@@ -57,6 +57,8 @@ struct Step {
     int64_t c_tok_stride = 0;       // elements per token of the step's output
     int c_vec = 1;                  // columns come in aligned contiguous runs of this many (1, 4 or 8)
     int r_vec = 1;                  // rows come in aligned contiguous runs of this many (1 or 8)
+    int a_vec = 1;                  // !a_plain: 8 when the k of one row come in aligned contiguous runs of 8 (acol in runs,
+                                    // arow and a_tok_stride multiples of 8), i.e. a row is gathered in 16-byte pieces
     int64_t flops = 0;              // 2*R*K*C
 };
 
@@ -529,6 +531,8 @@ inline int build_steps(Plan* p, const std::vector<int>& order) {
         if (st.c_vec > 1 && (!all_multiple_of(st.crow, st.c_vec) || st.c_tok_stride % st.c_vec)) st.c_vec = 1;
         st.r_vec = run_length(st.crow, 8) == 8 ? 8 : 1;
         if (st.r_vec > 1 && (!all_multiple_of(st.ccol, 8) || st.c_tok_stride % 8)) st.r_vec = 1;
+        if (!st.a_plain && st.K % 8 == 0 && run_length(st.acol, 8) == 8 && all_multiple_of(st.arow, 8) && st.a_tok_stride % 8 == 0)
+            st.a_vec = 8;
         // packing recipe: B[c][k] = tensor[sum of digit*stride]
         auto dims_of = [&](const std::vector<int>& ids, std::vector<GatherDim>* out) {
             for (int i : ids) {

@@ -205,6 +205,18 @@ def test_errors_through_the_abi():
     with pytest.raises(tn.TNLinearError):
         tn.tn_linear_forward(None, t.data_ptr(), t.data_ptr(), 1, None)
     tn.tn_linear_destroy(None)
+    # activations that are not 16-byte aligned are refused before anything is launched
+    spec = _spec(tn.TN_FORMAT_TT, "bf16", (4, 4), (4, 4), (1, 2, 1))
+    layer = make_layer(spec, _rand_layer(spec, 5), 2)
+    buf = torch.zeros(2 * 16 + 8, device="cuda", dtype=torch.bfloat16)
+    y = torch.zeros(2 * 16, device="cuda", dtype=torch.bfloat16)
+    stream = torch.cuda.current_stream().cuda_stream
+    tn.tn_linear_forward(layer._handle, buf.data_ptr(), y.data_ptr(), 2, stream)
+    for xp, yp in ((buf.data_ptr() + 2, y.data_ptr()), (buf.data_ptr(), y.data_ptr() + 6)):
+        with pytest.raises(tn.TNLinearError):
+            tn.tn_linear_forward(layer._handle, xp, yp, 2, stream)
+    torch.cuda.synchronize()
+    layer.close()
 
 
 def _stack_classes():
