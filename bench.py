@@ -498,8 +498,9 @@ def gradient_record(spec, config_id, tokens, reps=3):
            "roofline": {"bound": "mfma", "achieved": flops * tokens / sec / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                         "frac": flops * tokens / sec / 1e12 / 2500.0,
                         "kernel": "whole call: forward and input-gradient steps on the MFMA step kernels, parameter-gradient "
-                                  "contractions on grad_param_mfma_kernel (bf16 tensors of at least 32 x 32; 128 x 128 tiles fed "
-                                  "by element loads, which is what bounds them) or, for skinny tensors, on plain fp32 FMA"}}
+                                  "contractions on grad_param_mfma_kernel (128 x 128 tiles; both operands transposed through LDS, "
+                                  "loaded in 16-byte pieces where their layout allows) or, for tensors under 8 wide or not bf16, on "
+                                  "plain fp32 FMA"}}
     layer.close()
     return out
 

@@ -30,6 +30,7 @@ struct GradArgs {
     int32_t K, C;
     uint32_t rows_per_split;
     int32_t c_tiles, k_tiles, n_split;      // grad_param_mfma_kernel: a one-dimensional grid of c_tiles * k_tiles * n_split workgroups
+    int32_t d_mode, i_mode;                 // grad_param_mfma_kernel: how dOut and In are loaded (see there)
 };
 
 template <typename T>
@@ -94,17 +95,24 @@ __global__ void __launch_bounds__(256) grad_param_kernel(GradArgs a) {
 // The same contraction on the matrix cores, for bf16 layers: a workgroup owns a 128 x 128 tile of (c, k), each of
 // its four waves a 64 x 64 quarter (2 x 2 MFMA tiles, fp32 accumulators). The contracted index is the row g, which
 // is the slow index of both operands in memory, while an MFMA lane supplies 8 consecutive values of the contracted
-// index: so the rows go through LDS 32 at a time, stored transposed ([column][g], 16 consecutive g of one column per
-// thread as two 16-byte writes), and a fragment is one 16-byte LDS read. Both operands are read through the forward
-// step's own tables, one element per lane and load, with the lanes of a load along the fast index of a row; the row
-// of a load is the same for the whole wave, so its token and table entry sit in scalar registers. The loads of the
-// next 32 rows are requested before the current ones are multiplied. Partial tiles as in grad_param_kernel.
+// index: so the rows go through LDS 32 at a time, stored transposed ([column][g]), and a fragment is one 16-byte LDS
+// read. Waves 0-1 bring the 128 x 32 block of dOut, waves 2-3 that of In, each through the forward step's own tables,
+// in the widest pieces the operand's layout allows (GradArgs::d_mode, i_mode):
+//   1  8 consecutive columns of a row are one aligned 16-byte piece: a thread loads 4 rows x 8 columns, transposes
+//      them in registers and writes 8 pieces of 4 consecutive g;
+//   2  8 consecutive rows of a column are one aligned 16-byte piece (dOut of a step whose output runs along the row
+//      index; R % 8 == 0): such a piece is 8 consecutive g as it stands;
+//   0  neither: one element per lane and load, lanes along the columns of one row (the row of a load is the same
+//      for the whole wave, so its token and table entry sit in scalar registers).
+// The loads of the next 32 rows are requested before the current ones are multiplied. Row ranges start at multiples
+// of 32. Partial tiles as in grad_param_kernel.
 __global__ void __launch_bounds__(256) grad_param_mfma_kernel(GradArgs a) {
-    constexpr int BT = 128, BG = 32, PITCH = BG + 8;            // bf16 elements per LDS row: 80 bytes, 16-byte aligned
-    __shared__ __attribute__((aligned(16))) bf16_t sD[BT * PITCH];
-    __shared__ __attribute__((aligned(16))) bf16_t sI[BT * PITCH];
-    const bf16_t* dOut = static_cast<const bf16_t*>(a.dOut);
-    const bf16_t* In = static_cast<const bf16_t*>(a.In);
+    // LDS row of column x: 32 + 8 bf16 (80 bytes), and every 8 columns 16 bytes more, so that the 8-byte writes of
+    // mode 1 (lanes 8 columns = 640 bytes apart) do not all fall on one bank
+    constexpr int BT = 128, BG = 32, PITCH = BG + 8, LDS_ELEMS = BT * PITCH + (BT / 8) * 8;
+    auto row_of = [](int x) { return x * PITCH + ((x >> 3) << 3); };
+    __shared__ __attribute__((aligned(16))) bf16_t sD[LDS_ELEMS];
+    __shared__ __attribute__((aligned(16))) bf16_t sI[LDS_ELEMS];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // workgroup -> (tile, split). With a multiple of 8 splits, all tiles of one split run on one XCD (workgroups are
@@ -123,43 +131,85 @@ __global__ void __launch_bounds__(256) grad_param_mfma_kernel(GradArgs a) {
     const int c0 = (tile % a.c_tiles) * BT, k0 = (tile / a.c_tiles) * BT;
     const uint32_t g_begin = min(a.total_rows, uint32_t(split) * a.rows_per_split);
     const uint32_t g_end = min(a.total_rows, g_begin + a.rows_per_split);
-    // loads: thread -> column cc of both tiles and the 16 rows 16*half .. 16*half + 15 of a group of 32 (half is
-    // wave-uniform)
-    const int cc = tid & 127;
-    const int half = wave >> 1;
-    const bool vc = c0 + cc < a.C, vk = k0 + cc < a.K;
+
+    // ---- this wave's operand (wave-uniform)
+    const bool is_d = wave < 2;
+    const bf16_t* src = static_cast<const bf16_t*>(is_d ? a.dOut : a.In);
+    const int32_t* rowtab = is_d ? a.crow : a.arow;             // null: plain In, row r at r*K
+    const int32_t* coltab = is_d ? a.ccol : a.acol;             // null: plain In, column k at k
+    const int64_t tok_stride = is_d ? a.c_tok_stride : a.a_tok_stride;
+    const int mode = is_d ? a.d_mode : a.i_mode;
+    const int ext = is_d ? a.C : a.K, x0 = is_d ? c0 : k0;
+    bf16_t* sdst = is_d ? sD : sI;
+    const int u = tid & 127;
+    // modes 0 and 2: thread -> column u; mode 1: thread -> (columns 8*(u%16) .. +7, rows 4*(u/16) .. +3 of the 32)
+    const int col = x0 + (mode == 1 ? 8 * (u & 15) : u);
+    const bool vcol = col < ext;                                // mode 1: ext % 8 == 0, the whole piece is inside
     // table entries are offsets inside one token: non-negative, below 2^31 (checked when the plan is built)
-    const uint32_t col_d = vc ? uint32_t(a.ccol[c0 + cc]) : 0u;
-    const uint32_t col_i = vk ? (a.acol ? uint32_t(a.acol[k0 + cc]) : uint32_t(k0 + cc)) : 0u;
-    bf16x8 rd[2], ri[2];
+    const uint32_t coff = vcol ? (coltab ? uint32_t(coltab[col]) : uint32_t(col)) : 0u;
+    bf16x8 reg[4];
     auto request = [&](uint32_t g0) {
-        const uint32_t g = g0 + 16u * uint32_t(half);
-        uint32_t t = g / a.R, r = g - t * a.R;                  // wave-uniform
-        // all 16 row offsets first (scalar table reads, one wait), then the 32 loads back to back: with offset and
-        // load of one row next to each other every load waited for its own table entry
-        int64_t od[16], oi[16];
+        bf16x8 zero;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const bool live = g + uint32_t(j) < g_end;
-            od[j] = live ? int64_t(t) * a.c_tok_stride + a.crow[r] : -1;
-            oi[j] = live ? int64_t(t) * a.a_tok_stride + (a.arow ? int64_t(a.arow[r]) : int64_t(r) * a.K) : -1;
-            if (++r == a.R) {
-                r = 0;
-                ++t;
+        for (int e = 0; e < 8; ++e) zero[e] = bf16_t(0.f);
+        if (mode == 1) {
+            // per-lane rows: g0 + 4*(u/16) + j
+            uint32_t g = g0 + 4u * uint32_t(u >> 4);
+            uint32_t t = g / a.R, r = g - t * a.R;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                reg[j] = zero;
+                if (g + uint32_t(j) < g_end && vcol) {
+                    const int64_t ro = rowtab ? int64_t(rowtab[r]) : int64_t(r) * a.K;
+                    reg[j] = *reinterpret_cast<const bf16x8*>(src + int64_t(t) * tok_stride + ro + coff);
+                }
+                if (++r == a.R) {
+                    r = 0;
+                    ++t;
+                }
             }
-        }
+        } else if (mode == 2) {
+            // rows g0 + 8q .. +7: one token, one aligned run of the row table (R % 8 == 0, g0 % 8 == 0)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            // a wave-uniform row pointer plus a 32-bit lane offset: no vector arithmetic per load
-            rd[j >> 3][j & 7] = (od[j] >= 0 && vc) ? (dOut + od[j])[col_d] : bf16_t(0.f);
-            ri[j >> 3][j & 7] = (oi[j] >= 0 && vk) ? (In + oi[j])[col_i] : bf16_t(0.f);
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t g = g0 + 8u * uint32_t(q);       // wave-uniform
+                reg[q] = zero;
+                if (g < g_end && vcol) {
+                    const uint32_t t = g / a.R, r = g - t * a.R;
+                    reg[q] = *reinterpret_cast<const bf16x8*>(src + (int64_t(t) * tok_stride + rowtab[r]) + coff);
+                }
+            }
+        } else {
+            uint32_t t = g0 / a.R, r = g0 - t * a.R;            // wave-uniform
+            // all 32 row offsets first (scalar table reads, one wait), then the loads back to back
+            int64_t ro[BG];
+#pragma unroll
+            for (int j = 0; j < BG; ++j) {
+                ro[j] = g0 + uint32_t(j) < g_end ? int64_t(t) * tok_stride + (rowtab ? int64_t(rowtab[r]) : int64_t(r) * a.K) : -1;
+                if (++r == a.R) {
+                    r = 0;
+                    ++t;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < BG; ++j)
+                reg[j >> 3][j & 7] = (ro[j] >= 0 && vcol) ? (src + ro[j])[coff] : bf16_t(0.f);
         }
     };
     auto deposit = [&]() {
+        if (mode == 1) {
+            typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+            const int cl = 8 * (u & 15), gq = 4 * (u >> 4);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            *reinterpret_cast<bf16x8*>(sD + cc * PITCH + 16 * half + 8 * q) = rd[q];
-            *reinterpret_cast<bf16x8*>(sI + cc * PITCH + 16 * half + 8 * q) = ri[q];
+            for (int e = 0; e < 8; ++e) {
+                bf16x4_t v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = reg[j][e];
+                *reinterpret_cast<bf16x4_t*>(sdst + row_of(cl + e) + gq) = v;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) *reinterpret_cast<bf16x8*>(sdst + row_of(u) + 8 * q) = reg[q];
         }
     };
     // wave -> quarter (wc, wk); MFMA row operand: c, column operand: k; lane l supplies g = 8*(l/32) .. +7 of a k-step
@@ -181,8 +231,8 @@ __global__ void __launch_bounds__(256) grad_param_mfma_kernel(GradArgs a) {
             bf16x8 fd[2], fi[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                fd[i] = *reinterpret_cast<const bf16x8*>(sD + (64 * wc + 32 * i + (lane & 31)) * PITCH + 16 * ks + 8 * (lane >> 5));
-                fi[i] = *reinterpret_cast<const bf16x8*>(sI + (64 * wk + 32 * i + (lane & 31)) * PITCH + 16 * ks + 8 * (lane >> 5));
+                fd[i] = *reinterpret_cast<const bf16x8*>(sD + row_of(64 * wc + 32 * i + (lane & 31)) + 16 * ks + 8 * (lane >> 5));
+                fi[i] = *reinterpret_cast<const bf16x8*>(sI + row_of(64 * wk + 32 * i + (lane & 31)) + 16 * ks + 8 * (lane >> 5));
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)

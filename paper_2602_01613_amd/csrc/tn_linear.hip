@@ -1716,8 +1716,29 @@ constexpr int64_t kGradMfmaMinExtent = 32;
 
 // Row ranges a gradient launch is split into: enough workgroups to fill the chip, at least 64 rows each, partial
 // tiles within `cap` bytes.
-// bf16 steps whose tensor is at least a quarter of a 128 x 128 tile in both directions run on the matrix cores
-bool grad_on_mfma(const tn_linear_s* h, const tn::Step& p) { return h->elt == 2 && p.C >= kGradMfmaMinExtent && p.K >= kGradMfmaMinExtent; }
+// How grad_param_mfma_kernel loads dOut (d) and In (i) of a step: 1 = 16-byte pieces along the columns, 2 = 16-byte
+// pieces along the rows (dOut only), 0 = element by element.
+struct GradModes {
+    int d = 0, i = 0;
+};
+
+GradModes grad_modes(const tn::Step& p) {
+    GradModes m;
+    if (p.c_vec == 8 && p.C % 8 == 0) m.d = 1;
+    else if (p.r_vec == 8 && p.R % 8 == 0) m.d = 2;
+    if (p.K % 8 == 0 && p.a_tok_stride % 8 == 0 && (p.a_plain || p.a_vec == 8)) m.i = 1;
+    return m;
+}
+
+// bf16 steps whose tensor is at least a quarter of a 128 x 128 tile in both directions run on the matrix cores, and so
+// do skinny ones (8 to 31 one way, 32 or more the other: the boundary cores of a train) when both operands come in
+// 16-byte pieces: those are bound by reading the long operand once, which the tile kernel does in full lines
+bool grad_on_mfma(const tn_linear_s* h, const tn::Step& p) {
+    if (h->elt != 2) return false;
+    if (p.C >= kGradMfmaMinExtent && p.K >= kGradMfmaMinExtent) return true;
+    const GradModes m = grad_modes(p);
+    return m.d != 0 && m.i != 0 && std::min(p.C, p.K) >= 8 && std::max(p.C, p.K) >= kGradMfmaMinExtent;
+}
 
 int grad_splits(const tn_linear_s* h, const tn::Step& p, int64_t rows, int64_t cap) {
     const int64_t edge = grad_on_mfma(h, p) ? 128 : 64;
@@ -1842,6 +1863,10 @@ int launch_param_gradient(const tn_linear_s* h, const DevStep& s, const void* dO
     a.C = int32_t(p.C);
     a.rows_per_split = uint32_t((rows + n_split - 1) / n_split);
     const bool mfma = grad_on_mfma(h, p);
+    if (mfma) a.rows_per_split = (a.rows_per_split + 31u) & ~31u;        // the tile kernel's row ranges start at multiples of 32
+    const GradModes gm = grad_modes(p);
+    a.d_mode = gm.d;
+    a.i_mode = gm.i;
     const int64_t edge = mfma ? 128 : 64;
     dim3 grid(uint32_t((p.C + edge - 1) / edge), uint32_t((p.K + edge - 1) / edge), uint32_t(n_split));
     if (grid.y > 65535) return TN_ERR_UNSUPPORTED;
