@@ -98,3 +98,22 @@ def test_param_gradients_need_a_trainable_handle():
         layer.param_gradients(x, x)
     assert e.value.status == -1
     layer.close()
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_param_gradients_random_layers(seed):
+    """Seeded random layers (the draw of the random forward test, up to 2048 x 2048) against the oracle: shapes nobody
+    picked by hand, so that the tile kernel meets every way of loading its operands (pieces along the columns, along
+    the rows, single elements), skinny boundary cores and ragged tiles, and the plain kernel the rest."""
+    from test_gpu_random import _draw
+    rng = np.random.default_rng(99000 + seed)
+    while True:
+        spec = _draw(rng)
+        if spec.M <= 2048 and spec.N <= 2048:
+            break
+    ts = [wl.round_to_dtype(rng.standard_normal(shp) / np.sqrt(max(1.0, 0.5 * (shp[0] + shp[-1]))), "bf16")
+          for shp in spec.tensor_shapes()]
+    print(f"seed {seed}: format {spec.format} out {spec.out_modes} in {spec.in_modes} ranks {spec.ranks}", flush=True)
+    for tokens in (3, 70):
+        errs = _check(spec, ts, tokens, 99500 + seed * 3 + tokens)
+        assert max(errs) <= GRAD_TOL["bf16"], (seed, tokens, errs)
