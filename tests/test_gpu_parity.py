@@ -211,6 +211,10 @@ def test_errors_through_the_abi():
     buf = torch.zeros(2 * 16 + 8, device="cuda", dtype=torch.bfloat16)
     y = torch.zeros(2 * 16, device="cuda", dtype=torch.bfloat16)
     stream = torch.cuda.current_stream().cuda_stream
+    y.fill_(7.0)
+    tn.tn_linear_forward(layer._handle, buf.data_ptr(), y.data_ptr(), 0, stream)          # no tokens: nothing is launched
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
     tn.tn_linear_forward(layer._handle, buf.data_ptr(), y.data_ptr(), 2, stream)
     for xp, yp in ((buf.data_ptr() + 2, y.data_ptr()), (buf.data_ptr(), y.data_ptr() + 6)):
         with pytest.raises(tn.TNLinearError):
